@@ -1,0 +1,135 @@
+"""Pins for the oracle's generation loops (CPU only): the paper's invariant that stairs-assisted
+greedy generation returns what the main model alone would generate (abstract, Sec. 1), the
+validation walk of Sec. 3.3 on hand-derived cases, and closed forms for the acceptance counts."""
+import os
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+import synth_inputs as si
+from oracle import stairs_oracle as so
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "stairs_validation_cases.txt")
+
+
+def _cases():
+    out = []
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        parts = [[] if p.strip() == "-" else [int(x) for x in p.split()] for p in line.split("|")]
+        out.append(tuple(parts))
+    return out
+
+
+@pytest.mark.parametrize("prefix,draft,pred,truth", _cases())
+def test_validation_golden(prefix, draft, pred, truth):
+    rows = [prefix + draft[:i] for i in range(len(draft) + 1)]
+    assert so.stairs_validate(rows, pred) == truth
+    n = so.count_accepted(draft, pred)
+    assert prefix + pred[:n + 1] == truth          # the token-level form agrees with the vector walk
+    assert 1 <= len(truth) - len(prefix) <= len(draft) + 1
+
+
+@given(st.lists(st.integers(0, 3), min_size=0, max_size=6), st.data())
+@settings(max_examples=200, deadline=None)
+def test_validation_bruteforce(draft, data):
+    pred = data.draw(st.lists(st.integers(0, 3), min_size=len(draft) + 1, max_size=len(draft) + 1))
+    prefix = [1, 2]
+    rows = [prefix + draft[:i] for i in range(len(draft) + 1)]
+    truth = so.stairs_validate(rows, pred)
+    # brute force: the longest n such that d_1..d_n equal t_0..t_{n-1}
+    n = max(j for j in range(len(draft) + 1) if draft[:j] == pred[:j])
+    assert truth == prefix + pred[:n + 1]
+
+
+def _pair(seed, deep_scale, L=4, Ld=2, d=32, H=2, f=64, V=50):
+    t = si.make_model(seed, L, d, H, f, V, "fp32", deep_from=Ld, deep_scale=deep_scale)
+    return t, si.prefix_draft(t, Ld)
+
+
+@pytest.mark.parametrize("seed,deep_scale", [(7, 0.05), (7, 0.5), (8, 1.0), (9, 0.5)])
+@pytest.mark.parametrize("k", [0, 1, 2, 4, 7])
+def test_literal_stairs_equals_plain_greedy(seed, deep_scale, k):
+    t, d = _pair(seed, deep_scale)
+    T, D = so.OracleModel(t, np.float64), so.OracleModel(d, np.float64)
+    prompt = [3, 1, 4, 1, 5]
+    G = 14
+    want = so.greedy_bruteforce(T, prompt, G)
+    gen = so.stairs_literal(T, D, prompt, G, k)
+    assert gen.tokens == want
+    assert len(gen.tokens) == G
+    for it in gen.iterations:
+        assert 0 <= it.n_accepted <= k
+    assert sum(it.n_accepted + 1 for it in gen.iterations) >= G
+
+
+@given(seed=st.integers(0, 10_000), k=st.integers(0, 5), P=st.integers(1, 6), G=st.integers(1, 10),
+       scale=st.sampled_from([0.05, 0.5, 1.0]))
+@settings(max_examples=25, deadline=None)
+def test_cached_equals_literal_equals_greedy(seed, k, P, G, scale):
+    t, d = _pair(seed, scale, L=3, Ld=1, d=16, H=2, f=32, V=24)
+    T, D = so.OracleModel(t, np.float64), so.OracleModel(d, np.float64)
+    prompt = [int(x) for x in np.random.default_rng(seed).integers(0, 24, P)]
+    lit = so.stairs_literal(T, D, prompt, G, k, keep_logits=True)
+    ca = so.stairs_cached(T, D if k else None, prompt, G, k, keep_logits=True)
+    assert ca.tokens == lit.tokens == so.greedy_bruteforce(T, prompt, G)
+    assert len(ca.iterations) == len(lit.iterations)
+    for a, b in zip(ca.iterations, lit.iterations):
+        assert (a.L, a.draft, a.predicted, a.n_accepted) == (b.L, b.draft, b.predicted, b.n_accepted)
+        assert np.allclose(a.logits, b.logits, atol=1e-12)
+
+
+def test_independent_draft_also_returns_plain_greedy():
+    t = si.make_model(31, 3, 32, 2, 64, 50, "fp32")
+    d = si.make_model(32, 2, 16, 2, 32, 50, "fp32")           # different width, unrelated weights
+    T, D = so.OracleModel(t, np.float64), so.OracleModel(d, np.float64)
+    prompt = [9, 8, 7]
+    want = so.greedy_bruteforce(T, prompt, 12)
+    assert so.stairs_literal(T, D, prompt, 12, 3).tokens == want
+    assert so.stairs_cached(T, D, prompt, 12, 3).tokens == want
+
+
+@pytest.mark.parametrize("k,G", [(1, 9), (3, 12), (3, 13), (4, 5)])
+def test_draft_identical_to_target_accepts_everything(k, G):
+    """Assistant == main model: every iteration keeps k assistant tokens, so the number of
+    main-model iterations is ceil(G / (k+1))."""
+    t, _ = _pair(13, 1.0)
+    T = so.OracleModel(t, np.float64)
+    for fn in (so.stairs_literal, so.stairs_cached):
+        gen = fn(T, T, [2, 7, 1], G, k)
+        assert all(it.n_accepted == k for it in gen.iterations)
+        assert len(gen.iterations) == -(-G // (k + 1))
+        assert gen.tokens == so.greedy_bruteforce(T, [2, 7, 1], G)
+
+
+def test_adversarial_draft_accepts_nothing():
+    """Assistant tokens forced to differ from the main model's prediction: n = 0 every time, so
+    the number of iterations equals G and the output is still plain greedy."""
+    t, d = _pair(14, 0.5)
+    T, D = so.OracleModel(t, np.float64), so.OracleModel(d, np.float64)
+    prompt, G, k = [5, 6], 7, 3
+    want = so.greedy_bruteforce(T, prompt, G)
+    st_ = so.CachedStairs(T, D, prompt, 32)
+    iters = 0
+    while len(st_.seq) - st_.P < G:
+        nxt = want[len(st_.seq) - st_.P]
+        bad = [(nxt + 1) % 50] + [0] * (k - 1)
+        it = st_.verify(bad)
+        assert it.n_accepted == 0 and it.predicted[0] == nxt
+        iters += 1
+    assert iters == G and st_.seq[st_.P:] == want
+
+
+def test_generation_is_truncated_to_G():
+    t, _ = _pair(15, 1.0)
+    T = so.OracleModel(t, np.float64)
+    gen = so.stairs_cached(T, T, [1, 2, 3], 5, 3)             # 2 iterations produce 8, keep 5
+    assert len(gen.tokens) == 5 and len(gen.iterations) == 2
+
+
+def test_top2_margin():
+    assert so.top2_margin(np.array([0.1, 3.0, 2.5, -1.0])) == pytest.approx(0.5)
+    assert so.greedy_token(np.array([1.0, 7.0, 7.0])) == 1     # ties -> lowest index
