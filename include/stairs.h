@@ -1,0 +1,164 @@
+/*
+ * stairs.h -- C ABI of the MI355X (gfx950) library for "stairs" assisted greedy generation.
+ *
+ * The method (paper Sec. 3.3): an assistant ("draft") model greedily generates k tokens; the
+ * current sequence S (length L) is turned into the k+1 "stair" rows S, S+d_1, ..., S+d_1..d_k;
+ * the main ("target") model predicts one more token for every row in one batched iteration;
+ * "stairs" validation keeps the first row's prediction and every following row's prediction as
+ * long as the row equals the running ground truth, i.e. as long as d_i == t_{i-1}.  The output
+ * is the one the target alone would generate greedily (abstract, Sec. 3.1).
+ *
+ * On the GPU the stair batch is one causal forward of the k+1 new rows [S[L-1], d_1..d_k]
+ * against the target's key/value cache: its k+1 output rows are exactly the last-position
+ * logits of the k+1 stair rows.
+ *
+ * Conventions
+ *  - Every function returns 0 (STAIRS_OK) or a negative error code; nothing throws across the
+ *    ABI.  stairs_last_error() gives the text of the last failure of a context.
+ *  - Pointers are HOST pointers unless the argument is documented "host or device".
+ *  - The caller owns every buffer it passes; the library copies what it needs during the call
+ *    and keeps no reference afterwards.  The library owns the context and everything in it.
+ *  - One context serves one sequence at a time and is not thread-safe.
+ *  - All device work is issued on the HIP stream given to stairs_init (NULL = default stream)
+ *    on the device current at that time.  Calls return after their device work has finished
+ *    unless stated otherwise.
+ */
+#ifndef STAIRS_H
+#define STAIRS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define STAIRS_OK          0
+#define STAIRS_EINVAL     (-1)   /* bad argument or unsupported model shape               */
+#define STAIRS_ECAPACITY  (-2)   /* sequence would exceed max_seq                          */
+#define STAIRS_ESTATE     (-3)   /* call order (e.g. verify before prefill / propose)      */
+#define STAIRS_ENOMEM     (-4)   /* host or device allocation failed                       */
+#define STAIRS_EHIP       (-5)   /* a HIP runtime call or kernel launch failed             */
+
+#define STAIRS_DTYPE_FP32  0     /* matrices are float                                     */
+#define STAIRS_DTYPE_BF16  1     /* matrices are bfloat16 bit patterns (uint16_t)          */
+
+#define STAIRS_MAX_ROWS    32    /* most rows one forward takes: k + 1 <= STAIRS_MAX_ROWS  */
+
+/* Shape of one decoder-only pre-RMSNorm transformer (RoPE in the rotate-half pairing
+ * (i, i + head_dim/2), SwiGLU feed-forward, no biases, untied embedding / unembedding).
+ * Supported: head_dim = d_model / n_heads in {64, 128}; bf16 models need d_model and d_ffn
+ * to be multiples of 256 and vocab, 3*d_model, 2*d_ffn multiples of 16; fp32 models need
+ * d_model, d_ffn multiples of 4. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, d_ffn, vocab;
+  int32_t max_seq;        /* most positions the key/value cache must hold                  */
+  float rope_theta;       /* e.g. 10000                                                     */
+  float rms_eps;          /* e.g. 1e-5                                                      */
+  int32_t dtype;          /* STAIRS_DTYPE_*: type of the matrices AND of the KV cache       */
+} stairs_model_cfg;
+
+/* Host pointers to the weights.  Matrices are [out_features, in_features] row-major in
+ * cfg.dtype; norm gains are float[d_model].  The per-layer members point to arrays of
+ * n_layers pointers.  Two models may share tensors (same host address): the library keeps
+ * one device copy per distinct address. */
+typedef struct {
+  const void *tok_emb;          /* [vocab, d_model] */
+  const void *lm_head;          /* [vocab, d_model] */
+  const float *final_norm;      /* [d_model]        */
+  const float *const *attn_norm;
+  const void *const *wq, *const *wk, *const *wv, *const *wo;   /* [d, d]             */
+  const float *const *ffn_norm;
+  const void *const *w_gate, *const *w_up;                     /* [d_ffn, d_model]   */
+  const void *const *w_down;                                   /* [d_model, d_ffn]   */
+} stairs_weights;
+
+typedef struct {
+  int32_t iterations;           /* target iterations (stair batches) run                   */
+  int32_t tokens;               /* tokens produced (= G for stairs_generate)               */
+  int64_t accepted;             /* assistant tokens kept, summed over iterations           */
+  float ms_prefill;             /* prompt ingestion, both models                           */
+  float ms_decode;              /* everything after prefill until the last token           */
+  float ms_draft;               /* part of ms_decode spent in the draft's k-step proposals */
+  float ms_verify;              /* part of ms_decode spent in stair verification + accept  */
+  int32_t accept_hist[STAIRS_MAX_ROWS + 1];   /* accept_hist[n] = iterations that kept n   */
+} stairs_stats;
+
+typedef struct stairs_ctx stairs_ctx;   /* opaque */
+
+const char *stairs_strerror(int code);
+const char *stairs_last_error(const stairs_ctx *ctx);
+
+/* Build a context: upload both models, re-lay the matrices out for the kernels, allocate the
+ * KV caches (max_seq positions each) and workspaces.  dcfg/dw may be NULL (no assistant; only
+ * k = 0 is then legal, which is plain greedy generation of the target -- the paper's
+ * "batch size 1", Sec. 4.3).  k_max: largest draft length that will be used, 0 <= k_max <
+ * STAIRS_MAX_ROWS.  Both models must have the same vocab.  hip_stream: a hipStream_t or NULL.
+ * Errors: EINVAL (shapes, NULLs), ENOMEM, EHIP.  On error *out is NULL. */
+int stairs_init(stairs_ctx **out, const stairs_model_cfg *tcfg, const stairs_weights *tw,
+                const stairs_model_cfg *dcfg, const stairs_weights *dw, int32_t k_max,
+                void *hip_stream);
+
+void stairs_free(stairs_ctx *ctx);
+
+/* Start a new sequence S = prompt[0..P) (Sec. 3.3: the "initial sentence"): both models
+ * ingest prompt[0..P-2] into their KV caches; the last prompt token is the first row of the
+ * first stair batch.  Requires 1 <= P and P + k_max + 1 <= max_seq of both models.
+ * Errors: EINVAL (NULL, P < 1, token id outside [0, vocab)), ECAPACITY. */
+int stairs_prefill(stairs_ctx *ctx, const int32_t *prompt, int32_t P);
+
+/* Sec. 3.3, first step: the assistant greedily generates d_1..d_k after the current S.
+ * draft_out: k ints or NULL.  Must be followed by stairs_verify with the same k before the
+ * next draft_propose.  1 <= k <= k_max.  Errors: EINVAL, ESTATE (no prefill, or a proposal is
+ * already pending, or no draft model), ECAPACITY. */
+int draft_propose(stairs_ctx *ctx, int32_t k, int32_t *draft_out);
+
+/* Sec. 3.3, stair batch + validation: score the k+1 stair rows built from the pending
+ * proposal (k = 0: no proposal needed, one plain greedy step), take the per-row argmax
+ * t_0..t_k (ties -> lowest token id), keep n = max{ n : d_i == t_{i-1}, i <= n } assistant
+ * tokens, append t_0..t_n to S and roll both KV caches back to the accepted length.
+ * target_tok_out: k+1 ints or NULL.  n_accepted_out: 1 int or NULL.  logits_out: host or
+ * device buffer of (k+1)*vocab floats (row i = stair row i's next-token logits) or NULL.
+ * Errors: EINVAL, ESTATE (k > 0 without a pending proposal of the same k), ECAPACITY. */
+int stairs_verify(stairs_ctx *ctx, int32_t k, int32_t *target_tok_out, int32_t *n_accepted_out,
+                  float *logits_out);
+
+/* Same as stairs_verify but the assistant tokens d_1..d_k are given by the caller (tests:
+ * forced acceptance / rejection, replaying another implementation's trace).  Any pending
+ * proposal is discarded; the draft model's cache is brought up to date lazily by its next
+ * proposal.  0 <= k <= k_max.  Token ids outside [0, vocab) -> EINVAL. */
+int stairs_verify_tokens(stairs_ctx *ctx, const int32_t *draft, int32_t k, int32_t *target_tok_out,
+                         int32_t *n_accepted_out, float *logits_out);
+
+/* Whole loop (Sec. 3.3 repeated "until the prompt is fully responded to", Sec. 3.2; here:
+ * until exactly G tokens exist): prefill, then propose / verify until G tokens are produced;
+ * the last iteration is truncated to G.  tokens_out: G ints.  stats: optional.
+ * Requires P + G + k + 1 <= max_seq.  k = 0 is plain greedy generation of the target. */
+int stairs_generate(stairs_ctx *ctx, const int32_t *prompt, int32_t P, int32_t G, int32_t k,
+                    int32_t *tokens_out, stairs_stats *stats);
+
+/* Copy the current sequence (prompt + generated) into out[0..min(cap, len)); *len = length. */
+int stairs_get_tokens(stairs_ctx *ctx, int32_t *out, int32_t cap, int32_t *len);
+
+/* ---- diagnostics (kernel-level tests and roofline measurement) ------------------------ */
+
+/* Y[M, N] = X[M, K] . W[N, K]^T through the same weight re-layout and skinny GEMM kernels the
+ * forward pass uses (bf16: X is split into a bf16 high and low part, fp32 accumulation).
+ * All pointers are host pointers; W is in `dtype`; X, Y are float.  1 <= M <= STAIRS_MAX_ROWS. */
+int stairs_gemm_host(int32_t dtype, const void *W, const float *X, float *Y, int32_t M, int32_t N,
+                     int32_t K, void *hip_stream);
+
+/* Time `reps` back-to-back launches of one kernel of the target's forward at M rows, cycling
+ * through the layers so that the weights come from HBM, bracketed by HIP events on the
+ * context's stream.  which: 0 = gate/up projection GEMM (the largest), 1 = QKV GEMM,
+ * 2 = attention output GEMM, 3 = down projection GEMM, 4 = unembedding GEMM,
+ * 5 = KV-cache attention at context length ctx_len.  *ms_per_launch: mean duration;
+ * *bytes_per_launch: algorithmic bytes (matrix bytes, or K and V bytes of ctx_len positions).
+ * Does not disturb the sequence state, but overwrites workspaces: do not call between
+ * draft_propose and stairs_verify. */
+int stairs_time_kernel(stairs_ctx *ctx, int32_t which, int32_t M, int32_t ctx_len, int32_t reps,
+                       float *ms_per_launch, double *bytes_per_launch);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STAIRS_H */

@@ -317,8 +317,12 @@ class CachedStairs:
                 forward_cached(draft, self.dc, self.seq[:-1], 0, kv_round)
                 self.dc.length = self.P - 1
 
-    def propose(self, k: int) -> List[int]:
-        """k greedy assistant tokens after self.seq."""
+    def propose(self, k: int, forced: Optional[Sequence[int]] = None,
+                logits_out: Optional[list] = None) -> List[int]:
+        """k greedy assistant tokens after self.seq.  ``forced`` (teacher forcing, used by the
+        parity tests): the tokens another implementation chose; they are fed back instead of
+        this oracle's own choices, so that its logits can be compared step by step even after a
+        near-tie was resolved differently.  ``logits_out`` collects each step's logits row."""
         L = len(self.seq)
         d: List[int] = []
         if k == 0:
@@ -327,11 +331,14 @@ class CachedStairs:
         pend = self.seq[self.dc.length:]
         lg = forward_cached(self.draft, self.dc, pend, self.dc.length, self.kv_round)
         self.dc.length = L
-        d.append(greedy_token(lg[-1]))
-        for j in range(1, k):
-            lg = forward_cached(self.draft, self.dc, [d[-1]], L - 1 + j, self.kv_round)
-            self.dc.length = L + j
+        for j in range(k):
+            if j > 0:
+                lg = forward_cached(self.draft, self.dc, [fed], L - 1 + j, self.kv_round)
+                self.dc.length = L + j
+            if logits_out is not None:
+                logits_out.append(lg[-1])
             d.append(greedy_token(lg[-1]))
+            fed = d[-1] if forced is None else int(forced[j])
         return d
 
     def verify(self, d: Sequence[int]) -> Iteration:
@@ -342,11 +349,21 @@ class CachedStairs:
         logits = forward_cached(self.target, self.tc, rows_new, L - 1, self.kv_round)   # [k+1, V]
         t = [greedy_token(logits[i]) for i in range(k + 1)]
         n = count_accepted(d, t)
-        self.seq = self.seq + t[:n + 1]
-        self.tc.length = L + n                    # positions L-1 .. L-1+n stay valid
+        it = Iteration(L, [int(x) for x in d], t, n, logits)
+        self.adopt(L, t[:n + 1])
+        return it
+
+    def adopt(self, L: int, new_tokens: Sequence[int]):
+        """Make ``seq[:L] + new_tokens`` the sequence after an iteration that started at length
+        L.  verify() calls it with its own result; a parity test calls it again with the tokens
+        another implementation accepted (teacher forcing).  new_tokens must be a stair path of
+        the batch just scored (accepted assistant tokens plus one prediction), so the cache rows
+        written for it are the right ones: positions L-1 .. L-2+len(new_tokens) stay valid."""
+        self.seq = self.seq[:L] + [int(x) for x in new_tokens]
+        n = len(new_tokens) - 1
+        self.tc.length = L + n
         if self.dc is not None:
             self.dc.length = min(self.dc.length, L + n)
-        return Iteration(L, [int(x) for x in d], t, n, logits)
 
     def run(self, G: int, k: int, keep_logits: bool = False) -> Generation:
         gen = Generation(tokens=[])

@@ -1,0 +1,296 @@
+"""ctypes binding of include/stairs.h.  Function names mirror the C ABI one to one."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libstairs.so")
+_SOURCES = [os.path.join(_HERE, "csrc", f) for f in ("stairs_kernels.hip", "stairs_api.hip")]
+
+STAIRS_MAX_ROWS = 32
+DTYPE_FP32, DTYPE_BF16 = 0, 1
+
+EXPORTED_SYMBOLS = [
+    "stairs_strerror", "stairs_last_error", "stairs_init", "stairs_free", "stairs_prefill",
+    "draft_propose", "stairs_verify", "stairs_verify_tokens", "stairs_generate",
+    "stairs_get_tokens", "stairs_gemm_host", "stairs_time_kernel",
+]
+
+
+class StairsError(RuntimeError):
+    def __init__(self, code: int, where: str, detail: str = ""):
+        self.code = code
+        super().__init__(f"{where}: error {code} ({stairs_strerror(code)}) {detail}".strip())
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile the HIP sources for gfx950 into libstairs.so next to this file."""
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           *_SOURCES, "-o", LIB_PATH]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    if verbose:
+        print(" ".join(cmd))
+    return LIB_PATH
+
+
+class _ModelCfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
+                ("d_ffn", C.c_int32), ("vocab", C.c_int32), ("max_seq", C.c_int32),
+                ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32)]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
+                ("attn_norm", C.POINTER(C.c_void_p)), ("wq", C.POINTER(C.c_void_p)),
+                ("wk", C.POINTER(C.c_void_p)), ("wv", C.POINTER(C.c_void_p)),
+                ("wo", C.POINTER(C.c_void_p)), ("ffn_norm", C.POINTER(C.c_void_p)),
+                ("w_gate", C.POINTER(C.c_void_p)), ("w_up", C.POINTER(C.c_void_p)),
+                ("w_down", C.POINTER(C.c_void_p))]
+
+
+class StairsStats(C.Structure):
+    _fields_ = [("iterations", C.c_int32), ("tokens", C.c_int32), ("accepted", C.c_int64),
+                ("ms_prefill", C.c_float), ("ms_decode", C.c_float), ("ms_draft", C.c_float),
+                ("ms_verify", C.c_float), ("accept_hist", C.c_int32 * (STAIRS_MAX_ROWS + 1))]
+
+    def as_dict(self) -> dict:
+        return dict(iterations=self.iterations, tokens=self.tokens, accepted=self.accepted,
+                    ms_prefill=self.ms_prefill, ms_decode=self.ms_decode, ms_draft=self.ms_draft,
+                    ms_verify=self.ms_verify, accept_hist=list(self.accept_hist))
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first "
+                          "(python -c 'import __graft_entry__ as g; g.build()')")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i32p, f32p = C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_float)
+    L.stairs_strerror.restype = C.c_char_p
+    L.stairs_strerror.argtypes = [C.c_int]
+    L.stairs_last_error.restype = C.c_char_p
+    L.stairs_last_error.argtypes = [vp]
+    L.stairs_init.argtypes = [C.POINTER(vp), C.POINTER(_ModelCfg), C.POINTER(_Weights),
+                              C.POINTER(_ModelCfg), C.POINTER(_Weights), i32, vp]
+    L.stairs_free.argtypes = [vp]
+    L.stairs_free.restype = None
+    L.stairs_prefill.argtypes = [vp, i32p, i32]
+    L.draft_propose.argtypes = [vp, i32, i32p]
+    L.stairs_verify.argtypes = [vp, i32, i32p, i32p, vp]
+    L.stairs_verify_tokens.argtypes = [vp, i32p, i32, i32p, i32p, vp]
+    L.stairs_generate.argtypes = [vp, i32p, i32, i32, i32, i32p, C.POINTER(StairsStats)]
+    L.stairs_get_tokens.argtypes = [vp, i32p, i32, i32p]
+    L.stairs_gemm_host.argtypes = [i32, vp, f32p, f32p, i32, i32, i32, vp]
+    L.stairs_time_kernel.argtypes = [vp, i32, i32, i32, i32, f32p, C.POINTER(C.c_double)]
+    for name in EXPORTED_SYMBOLS:
+        if name not in ("stairs_strerror", "stairs_last_error", "stairs_free"):
+            getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def stairs_strerror(code: int) -> str:
+    return lib().stairs_strerror(code).decode()
+
+
+def stairs_last_error(ctx) -> str:
+    return lib().stairs_last_error(ctx).decode()
+
+
+def _check(rc: int, where: str, ctx=None):
+    if rc != 0:
+        raise StairsError(rc, where, stairs_last_error(ctx) if ctx else "")
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a: np.ndarray, ty):
+    return a.ctypes.data_as(C.POINTER(ty))
+
+
+def _marshal(model, max_seq: int, keep: list):
+    """model: object with n_layers, d_model, n_heads, d_ffn, vocab, dtype ('fp32'|'bf16'),
+    rope_theta, rms_eps, tok_emb, lm_head, final_norm, layers[list of dict] (numpy arrays)."""
+    want = np.uint16 if model.dtype == "bf16" else np.float32
+
+    def mat(a):
+        if a.dtype != want or not a.flags["C_CONTIGUOUS"]:
+            raise TypeError(f"matrix must be C-contiguous {want.__name__}")
+        keep.append(a)
+        return a.ctypes.data
+
+    def vec(a):
+        if a.dtype != np.float32 or not a.flags["C_CONTIGUOUS"]:
+            raise TypeError("norm gain must be C-contiguous float32")
+        keep.append(a)
+        return a.ctypes.data
+
+    cfg = _ModelCfg(model.n_layers, model.d_model, model.n_heads, model.d_ffn, model.vocab, max_seq,
+                    float(model.rope_theta), float(model.rms_eps),
+                    DTYPE_BF16 if model.dtype == "bf16" else DTYPE_FP32)
+    w = _Weights()
+    w.tok_emb, w.lm_head, w.final_norm = mat(model.tok_emb), mat(model.lm_head), vec(model.final_norm)
+    n = model.n_layers
+    for name in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down"):
+        arr = (C.c_void_p * n)()
+        for l in range(n):
+            t = model.layers[l][name]
+            arr[l] = vec(t) if name.endswith("norm") else mat(t)
+        keep.append(arr)
+        setattr(w, name, C.cast(arr, C.POINTER(C.c_void_p)))
+    return cfg, w
+
+
+def stairs_init(target, draft, k_max: int, max_seq: int, stream: Optional[int] = None):
+    keep: list = []
+    tcfg, tw = _marshal(target, max_seq, keep)
+    ctx = C.c_void_p()
+    if draft is not None:
+        dcfg, dw = _marshal(draft, max_seq, keep)
+        rc = lib().stairs_init(C.byref(ctx), C.byref(tcfg), C.byref(tw), C.byref(dcfg), C.byref(dw), k_max, stream)
+    else:
+        rc = lib().stairs_init(C.byref(ctx), C.byref(tcfg), C.byref(tw), None, None, k_max, stream)
+    _check(rc, "stairs_init")
+    return ctx
+
+
+def stairs_free(ctx):
+    lib().stairs_free(ctx)
+
+
+def stairs_prefill(ctx, prompt: Sequence[int]):
+    p = _i32(prompt)
+    _check(lib().stairs_prefill(ctx, _ptr(p, C.c_int32), len(p)), "stairs_prefill", ctx)
+
+
+def draft_propose(ctx, k: int) -> np.ndarray:
+    out = np.zeros(max(k, 1), np.int32)
+    _check(lib().draft_propose(ctx, k, _ptr(out, C.c_int32)), "draft_propose", ctx)
+    return out[:k]
+
+
+def _logits_arg(logits, k, vocab):
+    """None | True (allocate a host array) | int device pointer."""
+    if logits is None or logits is False:
+        return None, None
+    if logits is True:
+        buf = np.empty((k + 1, vocab), np.float32)
+        return buf, C.c_void_p(buf.ctypes.data)
+    return None, C.c_void_p(int(logits))
+
+
+def stairs_verify(ctx, k: int, vocab: int = 0, logits=None):
+    tgt = np.zeros(k + 1, np.int32)
+    n = C.c_int32(0)
+    buf, lp = _logits_arg(logits, k, vocab)
+    _check(lib().stairs_verify(ctx, k, _ptr(tgt, C.c_int32), C.byref(n), lp), "stairs_verify", ctx)
+    return tgt, n.value, buf
+
+
+def stairs_verify_tokens(ctx, draft: Sequence[int], vocab: int = 0, logits=None):
+    d = _i32(draft)
+    k = len(d)
+    tgt = np.zeros(k + 1, np.int32)
+    n = C.c_int32(0)
+    buf, lp = _logits_arg(logits, k, vocab)
+    dp = _ptr(d, C.c_int32) if k else None
+    _check(lib().stairs_verify_tokens(ctx, dp, k, _ptr(tgt, C.c_int32), C.byref(n), lp),
+           "stairs_verify_tokens", ctx)
+    return tgt, n.value, buf
+
+
+def stairs_generate(ctx, prompt: Sequence[int], G: int, k: int):
+    p = _i32(prompt)
+    out = np.zeros(max(G, 1), np.int32)
+    st = StairsStats()
+    _check(lib().stairs_generate(ctx, _ptr(p, C.c_int32), len(p), G, k, _ptr(out, C.c_int32), C.byref(st)),
+           "stairs_generate", ctx)
+    return out[:G], st
+
+
+def stairs_get_tokens(ctx, cap: int = 1 << 20) -> np.ndarray:
+    n = C.c_int32(0)
+    _check(lib().stairs_get_tokens(ctx, None, 0, C.byref(n)), "stairs_get_tokens", ctx)
+    out = np.zeros(max(1, min(cap, n.value)), np.int32)
+    _check(lib().stairs_get_tokens(ctx, _ptr(out, C.c_int32), len(out), C.byref(n)), "stairs_get_tokens", ctx)
+    return out[:min(cap, n.value)]
+
+
+def stairs_gemm_host(W: np.ndarray, X: np.ndarray, stream: Optional[int] = None) -> np.ndarray:
+    """Y = X . W^T through the library's GEMM path.  W: uint16 (bf16 bits) or float32 [N, K]."""
+    W = np.ascontiguousarray(W)
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    dt = DTYPE_BF16 if W.dtype == np.uint16 else DTYPE_FP32
+    (N, K), M = W.shape, X.shape[0]
+    Y = np.empty((M, N), np.float32)
+    _check(lib().stairs_gemm_host(dt, C.c_void_p(W.ctypes.data), _ptr(X, C.c_float), _ptr(Y, C.c_float), M, N, K,
+                                  stream), "stairs_gemm_host")
+    return Y
+
+
+def stairs_time_kernel(ctx, which: int, M: int, ctx_len: int, reps: int):
+    ms, by = C.c_float(0), C.c_double(0)
+    _check(lib().stairs_time_kernel(ctx, which, M, ctx_len, reps, C.byref(ms), C.byref(by)), "stairs_time_kernel", ctx)
+    return ms.value, by.value
+
+
+class Stairs:
+    """Convenience wrapper owning one context."""
+
+    def __init__(self, target, draft=None, k_max: int = 0, max_seq: int = 1024, stream: Optional[int] = None):
+        self.vocab = target.vocab
+        self.ctx = stairs_init(target, draft, k_max, max_seq, stream)
+
+    def close(self):
+        if self.ctx is not None:
+            stairs_free(self.ctx)
+            self.ctx = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def prefill(self, prompt):
+        stairs_prefill(self.ctx, prompt)
+
+    def propose(self, k):
+        return draft_propose(self.ctx, k)
+
+    def verify(self, k, logits=None):
+        return stairs_verify(self.ctx, k, self.vocab, logits)
+
+    def verify_tokens(self, draft, logits=None):
+        return stairs_verify_tokens(self.ctx, draft, self.vocab, logits)
+
+    def generate(self, prompt, G, k):
+        return stairs_generate(self.ctx, prompt, G, k)
+
+    def tokens(self):
+        return stairs_get_tokens(self.ctx)
+
+    def time_kernel(self, which, M, ctx_len=0, reps=64):
+        return stairs_time_kernel(self.ctx, which, M, ctx_len, reps)

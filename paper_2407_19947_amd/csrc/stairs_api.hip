@@ -1,0 +1,633 @@
+// Host side of the stairs C ABI: context, weight upload and re-layout, the per-forward launch
+// schedule, the propose / verify / accept loop.  All arithmetic of the method runs in the
+// kernels of stairs_kernels.hip; this file only sequences them.
+#include "../../include/stairs.h"
+#include "stairs_kernels.h"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace stairs;
+
+namespace {
+
+struct Layer {
+  const float* attn_norm = nullptr;
+  const float* ffn_norm = nullptr;
+  const void* wqkv = nullptr;   // [3d, d]
+  const void* wo = nullptr;     // [d, d]
+  const void* wgu = nullptr;    // [2f, d]
+  const void* wdown = nullptr;  // [d, f]
+};
+
+struct Model {
+  stairs_model_cfg cfg{};
+  bool bf16 = false;
+  int hd = 0, cap = 0;
+  const void* tok_emb = nullptr;    // row-major, cfg dtype
+  const void* lm_head = nullptr;    // GEMM layout
+  const float* final_norm = nullptr;
+  std::vector<Layer> layers;
+  char* Kc = nullptr;               // [layers][H][cap][hd]
+  char* Vc = nullptr;
+  size_t kv_layer_bytes = 0;
+  int valid = 0;                    // positions 0..valid-1 of the cache hold the current sequence
+  size_t esz() const { return bf16 ? 2 : 4; }
+};
+
+}  // namespace
+
+struct stairs_ctx {
+  hipStream_t st = nullptr;
+  int k_max = 0;
+  bool have_draft = false;
+  Model T, D;
+  std::vector<void*> owned;                       // every device allocation, freed in stairs_free
+  std::map<std::pair<const void*, int>, const void*> dedup;   // (first host ptr, kind) -> device copy
+  // workspaces (sized for the larger of the two models)
+  float *x = nullptr, *ssq = nullptr, *q_rot = nullptr, *attn_out = nullptr, *h = nullptr, *logits = nullptr;
+  float *partial = nullptr, *part_o = nullptr, *part_ml = nullptr;
+  float2* rope_cs = nullptr;
+  int nchunk_cap = 0;
+  int* tokens = nullptr;       // device copy of the sequence, capacity tok_cap
+  int tok_cap = 0;
+  int* tgt_tok = nullptr;      // [kMaxRows]
+  int* state = nullptr;        // [0] = L, [1] = n of last iteration, [2] = constant 0
+  int* h_pinned = nullptr;     // pinned host: [0..1] state, [2..2+kMaxRows) target tokens
+  // host mirror
+  int L = 0, P = 0;
+  bool prefilled = false;
+  int pending_k = -1;          // draft length of the outstanding proposal, -1 = none
+  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  std::string err;
+};
+
+namespace {
+
+#define HIPCHK(c, expr)                                                               \
+  do {                                                                                \
+    hipError_t e_ = (expr);                                                           \
+    if (e_ != hipSuccess) {                                                           \
+      (c)->err = std::string(#expr) + ": " + hipGetErrorString(e_);                   \
+      return STAIRS_EHIP;                                                             \
+    }                                                                                 \
+  } while (0)
+
+int fail(stairs_ctx* c, int code, const char* msg) {
+  if (c) c->err = msg;
+  return code;
+}
+
+template <typename T>
+int dev_alloc(stairs_ctx* c, T** out, size_t count) {
+  void* p = nullptr;
+  hipError_t e = hipMalloc(&p, std::max<size_t>(count, 1) * sizeof(T));
+  if (e != hipSuccess) {
+    c->err = std::string("hipMalloc: ") + hipGetErrorString(e);
+    (void)hipGetLastError();
+    return STAIRS_ENOMEM;
+  }
+  c->owned.push_back(p);
+  *out = static_cast<T*>(p);
+  return STAIRS_OK;
+}
+
+const char* check_cfg(const stairs_model_cfg* m) {
+  if (!m) return "model config is NULL";
+  if (m->n_layers < 1 || m->d_model < 1 || m->n_heads < 1 || m->d_ffn < 1 || m->vocab < 1 || m->max_seq < 2)
+    return "model dimensions must be positive (max_seq >= 2)";
+  if (m->dtype != STAIRS_DTYPE_FP32 && m->dtype != STAIRS_DTYPE_BF16) return "unknown dtype";
+  if (m->d_model % m->n_heads) return "d_model is not a multiple of n_heads";
+  const int hd = m->d_model / m->n_heads;
+  if (hd != 64 && hd != 128) return "head_dim must be 64 or 128";
+  if (m->dtype == STAIRS_DTYPE_BF16) {
+    if (m->d_model % 256 || m->d_ffn % 256) return "bf16 models need d_model and d_ffn to be multiples of 256";
+    if (m->vocab % 16) return "bf16 models need vocab to be a multiple of 16";
+  } else {
+    if (m->d_model % 4 || m->d_ffn % 4 || m->vocab % 4) return "fp32 models need d_model, d_ffn, vocab multiples of 4";
+  }
+  if (!(m->rope_theta > 0.f) || !(m->rms_eps >= 0.f)) return "rope_theta must be > 0 and rms_eps >= 0";
+  return nullptr;
+}
+
+const char* check_weights(const stairs_model_cfg* m, const stairs_weights* w) {
+  if (!w) return "weights are NULL";
+  if (!w->tok_emb || !w->lm_head || !w->final_norm || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo ||
+      !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down)
+    return "a weight pointer is NULL";
+  for (int l = 0; l < m->n_layers; ++l)
+    if (!w->attn_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate[l] ||
+        !w->w_up[l] || !w->w_down[l])
+      return "a per-layer weight pointer is NULL";
+  return nullptr;
+}
+
+// Upload a matrix made of `nparts` row blocks (each [rows_each, K], host, model dtype) as one
+// [nparts*rows_each, K] GEMM operand; bf16 goes through the operand re-layout kernel.
+int upload_matrix(stairs_ctx* c, bool bf16, const void* const* parts, int nparts, int rows_each, int K, int kind,
+                  char* staging, const void** out) {
+  auto key = std::make_pair(parts[0], kind);
+  auto it = c->dedup.find(key);
+  if (it != c->dedup.end()) {
+    *out = it->second;
+    return STAIRS_OK;
+  }
+  const size_t esz = bf16 ? 2 : 4;
+  const size_t part_bytes = (size_t)rows_each * K * esz;
+  char* dst = nullptr;
+  int rc = dev_alloc(c, &dst, part_bytes * nparts);
+  if (rc) return rc;
+  char* raw = bf16 ? staging : dst;
+  for (int p = 0; p < nparts; ++p)
+    HIPCHK(c, hipMemcpyAsync(raw + p * part_bytes, parts[p], part_bytes, hipMemcpyHostToDevice, c->st));
+  if (bf16) {
+    launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(staging), reinterpret_cast<uint4*>(dst), nparts * rows_each, K, c->st);
+    HIPCHK(c, hipGetLastError());
+  }
+  HIPCHK(c, hipStreamSynchronize(c->st));   // staging and the host buffers are reused right away
+  c->dedup[key] = dst;
+  *out = dst;
+  return STAIRS_OK;
+}
+
+int upload_plain(stairs_ctx* c, const void* host, size_t bytes, int kind, const void** out) {
+  auto key = std::make_pair(host, kind);
+  auto it = c->dedup.find(key);
+  if (it != c->dedup.end()) {
+    *out = it->second;
+    return STAIRS_OK;
+  }
+  char* dst = nullptr;
+  int rc = dev_alloc(c, &dst, bytes);
+  if (rc) return rc;
+  HIPCHK(c, hipMemcpyAsync(dst, host, bytes, hipMemcpyHostToDevice, c->st));
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  c->dedup[key] = dst;
+  *out = dst;
+  return STAIRS_OK;
+}
+
+enum { KIND_EMB = 0, KIND_HEAD, KIND_NORM, KIND_QKV, KIND_WO, KIND_GU, KIND_DOWN };
+
+int build_model(stairs_ctx* c, Model* m, const stairs_model_cfg* cfg, const stairs_weights* w, char* staging) {
+  m->cfg = *cfg;
+  m->bf16 = cfg->dtype == STAIRS_DTYPE_BF16;
+  m->hd = cfg->d_model / cfg->n_heads;
+  m->cap = cfg->max_seq;
+  const int d = cfg->d_model, f = cfg->d_ffn, V = cfg->vocab;
+  int rc;
+  if ((rc = upload_plain(c, w->tok_emb, (size_t)V * d * m->esz(), KIND_EMB, &m->tok_emb))) return rc;
+  const void* one[1] = {w->lm_head};
+  if ((rc = upload_matrix(c, m->bf16, one, 1, V, d, KIND_HEAD, staging, &m->lm_head))) return rc;
+  const void* fn = nullptr;
+  if ((rc = upload_plain(c, w->final_norm, (size_t)d * 4, KIND_NORM, &fn))) return rc;
+  m->final_norm = static_cast<const float*>(fn);
+  m->layers.resize(cfg->n_layers);
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    Layer& ly = m->layers[l];
+    const void* p = nullptr;
+    if ((rc = upload_plain(c, w->attn_norm[l], (size_t)d * 4, KIND_NORM, &p))) return rc;
+    ly.attn_norm = static_cast<const float*>(p);
+    if ((rc = upload_plain(c, w->ffn_norm[l], (size_t)d * 4, KIND_NORM, &p))) return rc;
+    ly.ffn_norm = static_cast<const float*>(p);
+    const void* qkv[3] = {w->wq[l], w->wk[l], w->wv[l]};
+    if ((rc = upload_matrix(c, m->bf16, qkv, 3, d, d, KIND_QKV, staging, &ly.wqkv))) return rc;
+    one[0] = w->wo[l];
+    if ((rc = upload_matrix(c, m->bf16, one, 1, d, d, KIND_WO, staging, &ly.wo))) return rc;
+    const void* gu[2] = {w->w_gate[l], w->w_up[l]};
+    if ((rc = upload_matrix(c, m->bf16, gu, 2, f, d, KIND_GU, staging, &ly.wgu))) return rc;
+    one[0] = w->w_down[l];
+    if ((rc = upload_matrix(c, m->bf16, one, 1, d, f, KIND_DOWN, staging, &ly.wdown))) return rc;
+  }
+  m->kv_layer_bytes = (size_t)cfg->n_heads * m->cap * m->hd * m->esz();
+  if ((rc = dev_alloc(c, &m->Kc, m->kv_layer_bytes * cfg->n_layers))) return rc;
+  if ((rc = dev_alloc(c, &m->Vc, m->kv_layer_bytes * cfg->n_layers))) return rc;
+  return STAIRS_OK;
+}
+
+size_t max_matrix_bytes(const stairs_model_cfg* m) {
+  const size_t esz = m->dtype == STAIRS_DTYPE_BF16 ? 2 : 4;
+  const size_t d = m->d_model, f = m->d_ffn, V = m->vocab;
+  return std::max({3 * d * d, 2 * f * d, V * d}) * esz;
+}
+
+size_t max_partial_floats(const stairs_model_cfg* m) {
+  const int b = m->dtype == STAIRS_DTYPE_BF16;
+  const size_t d = m->d_model, f = m->d_ffn, V = m->vocab;
+  const size_t sd = gemm_slices(m->d_model, b), sf = gemm_slices(m->d_ffn, b);
+  return kMaxRows * std::max({sd * 3 * d, sd * 2 * f, sf * d, sd * V});
+}
+
+// One forward of `M` rows at positions pos..pos+M-1 whose token ids are tokens[pos..pos+M-1].
+// pos_host is the host's value of that position (used only to size the attention grid).
+// logits_rows: 0 = no unembedding (prefill), 1 = last row only -> c->logits row 0,
+//              M = every row -> c->logits rows 0..M-1.
+int forward(stairs_ctx* c, Model* m, PosRef pos, int pos_host, int M, int logits_rows) {
+  const stairs_model_cfg& g = m->cfg;
+  const int d = g.d_model, f = g.d_ffn, H = g.n_heads, V = g.vocab;
+  const int b = m->bf16 ? 1 : 0;
+  const int sn = ssq_groups(d);
+  hipStream_t st = c->st;
+  launch_embed(m->tok_emb, b, c->tokens, pos, M, d, c->x, c->ssq, st);
+  launch_rope_table(pos, M, m->hd, g.rope_theta, c->rope_cs, st);
+  const int nchunk = (std::max(pos_host, 0) + M + kAttnChunk - 1) / kAttnChunk;
+  for (int l = 0; l < g.n_layers; ++l) {
+    const Layer& ly = m->layers[l];
+    RowNorm n1{ly.attn_norm, c->ssq, sn, g.rms_eps};
+    int S = launch_gemm_partial(b, ly.wqkv, 3 * d, d, c->x, d, M, n1, c->partial, st);
+    launch_fin_qkv_rope(c->partial, S, M, d, H, c->rope_cs, pos, c->q_rot, m->Kc + l * m->kv_layer_bytes,
+                        m->Vc + l * m->kv_layer_bytes, m->cap, b, st);
+    launch_attention(c->q_rot, m->Kc + l * m->kv_layer_bytes, m->Vc + l * m->kv_layer_bytes, b, m->cap, d, H, M, pos,
+                     nchunk, c->nchunk_cap, c->part_o, c->part_ml, c->attn_out, st);
+    RowNorm none{nullptr, nullptr, 0, 0.f};
+    S = launch_gemm_partial(b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, st);
+    launch_fin_resid(c->partial, S, M, d, c->x, c->ssq, st);
+    RowNorm n2{ly.ffn_norm, c->ssq, sn, g.rms_eps};
+    S = launch_gemm_partial(b, ly.wgu, 2 * f, d, c->x, d, M, n2, c->partial, st);
+    launch_fin_swiglu(c->partial, S, M, f, c->h, st);
+    S = launch_gemm_partial(b, ly.wdown, d, f, c->h, f, M, none, c->partial, st);
+    launch_fin_resid(c->partial, S, M, d, c->x, c->ssq, st);
+  }
+  if (logits_rows > 0) {
+    const int r0 = M - logits_rows;
+    RowNorm nf{m->final_norm, c->ssq + r0 * sn, sn, g.rms_eps};
+    int S = launch_gemm_partial(b, m->lm_head, V, d, c->x + (size_t)r0 * d, d, logits_rows, nf, c->partial, st);
+    launch_fin_plain(c->partial, S, logits_rows, V, c->logits, V, st);
+  }
+  HIPCHK(c, hipGetLastError());
+  return STAIRS_OK;
+}
+
+PosRef abs_pos(const stairs_ctx* c, int p) { return PosRef{c->state + 2, p}; }   // state[2] == 0
+
+// ingest positions [from, to) of the current sequence into a model's cache, no logits
+int ingest(stairs_ctx* c, Model* m, int from, int to) {
+  for (int p = from; p < to; p += kMaxRows) {
+    const int M = std::min(kMaxRows, to - p);
+    int rc = forward(c, m, abs_pos(c, p), p, M, 0);
+    if (rc) return rc;
+  }
+  if (to > m->valid) m->valid = to;
+  return STAIRS_OK;
+}
+
+int do_propose(stairs_ctx* c, int k) {
+  Model* m = &c->D;
+  const int L = c->L;
+  // the draft's cache must hold positions 0..L-3; the 2-row step below covers L-2 and L-1
+  if (m->valid < L - 2) {
+    int rc = ingest(c, m, m->valid, L - 2);
+    if (rc) return rc;
+  }
+  // step 1: rows at L-2, L-1 (row L-2 is recomputed when it is already cached: same values);
+  // its argmax is d_1 -> tokens[L].  Steps 2..k: one row each.
+  int rc = forward(c, m, abs_pos(c, L - 2), L - 2, 2, 1);
+  if (rc) return rc;
+  launch_argmax(c->logits, m->cfg.vocab, m->cfg.vocab, 1, c->tokens, abs_pos(c, L), c->st);
+  for (int j = 1; j < k; ++j) {
+    rc = forward(c, m, abs_pos(c, L - 1 + j), L - 1 + j, 1, 1);
+    if (rc) return rc;
+    launch_argmax(c->logits, m->cfg.vocab, m->cfg.vocab, 1, c->tokens, abs_pos(c, L + j), c->st);
+  }
+  HIPCHK(c, hipGetLastError());
+  m->valid = L + k - 1;      // tokens S, d_1..d_{k-1} are in the cache
+  c->pending_k = k;
+  return STAIRS_OK;
+}
+
+// stair batch + validation for the k draft tokens sitting in tokens[L..L+k)
+int do_verify(stairs_ctx* c, int k, int* n_out) {
+  Model* m = &c->T;
+  const int L = c->L, M = k + 1;
+  int rc = forward(c, m, abs_pos(c, L - 1), L - 1, M, M);
+  if (rc) return rc;
+  launch_argmax(c->logits, m->cfg.vocab, m->cfg.vocab, M, c->tgt_tok, PosRef{nullptr, 0}, c->st);
+  launch_accept(c->tokens, c->tgt_tok, k, c->state, c->st);
+  HIPCHK(c, hipGetLastError());
+  HIPCHK(c, hipMemcpyAsync(c->h_pinned, c->state, 2 * sizeof(int), hipMemcpyDeviceToHost, c->st));
+  HIPCHK(c, hipMemcpyAsync(c->h_pinned + 2, c->tgt_tok, M * sizeof(int), hipMemcpyDeviceToHost, c->st));
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  const int n = c->h_pinned[1];
+  if (c->h_pinned[0] != L + n + 1 || n < 0 || n > k) return fail(c, STAIRS_EHIP, "device state out of sync with host");
+  c->L = L + n + 1;
+  m->valid = L + n;                                   // positions L-1 .. L-1+n stay
+  if (c->have_draft) c->D.valid = std::min(c->D.valid, L + n);
+  c->pending_k = -1;
+  *n_out = n;
+  return STAIRS_OK;
+}
+
+int copy_out(stairs_ctx* c, void* dst, const void* src, size_t bytes) {
+  HIPCHK(c, hipMemcpyAsync(dst, src, bytes, hipMemcpyDefault, c->st));
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  return STAIRS_OK;
+}
+
+int capacity_ok(const stairs_ctx* c, int need) {
+  if (need > c->T.cap) return 0;
+  if (c->have_draft && need > c->D.cap) return 0;
+  return need <= c->tok_cap;
+}
+
+}  // namespace
+
+// =========================================================================================
+extern "C" {
+
+const char* stairs_strerror(int code) {
+  switch (code) {
+    case STAIRS_OK: return "ok";
+    case STAIRS_EINVAL: return "invalid argument";
+    case STAIRS_ECAPACITY: return "sequence exceeds max_seq";
+    case STAIRS_ESTATE: return "call not allowed in this state";
+    case STAIRS_ENOMEM: return "out of memory";
+    case STAIRS_EHIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+const char* stairs_last_error(const stairs_ctx* ctx) { return ctx ? ctx->err.c_str() : "context is NULL"; }
+
+void stairs_free(stairs_ctx* c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->st);
+  for (void* p : c->owned) (void)hipFree(p);
+  if (c->h_pinned) (void)hipHostFree(c->h_pinned);
+  for (auto& e : c->ev)
+    if (e) (void)hipEventDestroy(e);
+  delete c;
+}
+
+int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_weights* tw, const stairs_model_cfg* dcfg,
+                const stairs_weights* dw, int32_t k_max, void* hip_stream) {
+  if (!out) return STAIRS_EINVAL;
+  *out = nullptr;
+  if (check_cfg(tcfg) || check_weights(tcfg, tw)) return STAIRS_EINVAL;
+  const bool have_draft = dcfg != nullptr;
+  if (have_draft && (check_cfg(dcfg) || check_weights(dcfg, dw) || dcfg->vocab != tcfg->vocab)) return STAIRS_EINVAL;
+  if (k_max < 0 || k_max >= STAIRS_MAX_ROWS) return STAIRS_EINVAL;
+  if (!have_draft && k_max != 0) return STAIRS_EINVAL;
+  stairs_ctx* c = new (std::nothrow) stairs_ctx;
+  if (!c) return STAIRS_ENOMEM;
+  c->st = static_cast<hipStream_t>(hip_stream);
+  c->k_max = k_max;
+  c->have_draft = have_draft;
+  int rc = STAIRS_OK;
+  auto bail = [&](int code) {
+    if (code == STAIRS_EHIP || code == STAIRS_ENOMEM) fprintf(stderr, "stairs_init: %s\n", c->err.c_str());
+    stairs_free(c);
+    return code;
+  };
+  if (configure_kernels() != hipSuccess) return bail(STAIRS_EHIP);
+  size_t stage_bytes = max_matrix_bytes(tcfg);
+  if (have_draft) stage_bytes = std::max(stage_bytes, max_matrix_bytes(dcfg));
+  char* staging = nullptr;
+  if (hipMalloc(reinterpret_cast<void**>(&staging), stage_bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return bail(STAIRS_ENOMEM);
+  }
+  rc = build_model(c, &c->T, tcfg, tw, staging);
+  if (!rc && have_draft) rc = build_model(c, &c->D, dcfg, dw, staging);
+  (void)hipFree(staging);
+  if (rc) return bail(rc);
+
+  const int dmax = std::max(tcfg->d_model, have_draft ? dcfg->d_model : 0);
+  const int fmax = std::max(tcfg->d_ffn, have_draft ? dcfg->d_ffn : 0);
+  const int Hmax = std::max(tcfg->n_heads, have_draft ? dcfg->n_heads : 0);
+  const int capmax = std::max(tcfg->max_seq, have_draft ? dcfg->max_seq : 0);
+  size_t pf = max_partial_floats(tcfg);
+  if (have_draft) pf = std::max(pf, max_partial_floats(dcfg));
+  c->nchunk_cap = (capmax + kAttnChunk - 1) / kAttnChunk;
+  c->tok_cap = capmax;
+  if ((rc = dev_alloc(c, &c->x, (size_t)kMaxRows * dmax)) || (rc = dev_alloc(c, &c->ssq, (size_t)kMaxRows * ssq_groups(dmax))) ||
+      (rc = dev_alloc(c, &c->q_rot, (size_t)kMaxRows * dmax)) || (rc = dev_alloc(c, &c->attn_out, (size_t)kMaxRows * dmax)) ||
+      (rc = dev_alloc(c, &c->h, (size_t)kMaxRows * fmax)) || (rc = dev_alloc(c, &c->logits, (size_t)kMaxRows * tcfg->vocab)) ||
+      (rc = dev_alloc(c, &c->partial, pf)) ||
+      (rc = dev_alloc(c, &c->part_o, (size_t)kMaxRows * Hmax * c->nchunk_cap * 128)) ||
+      (rc = dev_alloc(c, &c->part_ml, (size_t)kMaxRows * Hmax * c->nchunk_cap * 2)) ||
+      (rc = dev_alloc(c, &c->rope_cs, (size_t)kMaxRows * 64)) || (rc = dev_alloc(c, &c->tokens, (size_t)c->tok_cap + kMaxRows)) ||
+      (rc = dev_alloc(c, &c->tgt_tok, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->state, 8)))
+    return bail(rc);
+  if (hipMemsetAsync(c->state, 0, 8 * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
+  if (hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), (2 + kMaxRows) * sizeof(int), hipHostMallocDefault) != hipSuccess) {
+    c->h_pinned = nullptr;
+    return bail(STAIRS_ENOMEM);
+  }
+  for (auto& e : c->ev)
+    if (hipEventCreate(&e) != hipSuccess) return bail(STAIRS_EHIP);
+  if (hipStreamSynchronize(c->st) != hipSuccess) return bail(STAIRS_EHIP);
+  *out = c;
+  return STAIRS_OK;
+}
+
+int stairs_prefill(stairs_ctx* c, const int32_t* prompt, int32_t P) {
+  if (!c) return STAIRS_EINVAL;
+  if (!prompt || P < 1) return fail(c, STAIRS_EINVAL, "prompt is NULL or empty");
+  for (int i = 0; i < P; ++i)
+    if (prompt[i] < 0 || prompt[i] >= c->T.cfg.vocab) return fail(c, STAIRS_EINVAL, "prompt token outside the vocabulary");
+  if (!capacity_ok(c, P + c->k_max + 1)) return fail(c, STAIRS_ECAPACITY, "prompt + k_max + 1 exceeds max_seq");
+  c->prefilled = false;
+  c->pending_k = -1;
+  HIPCHK(c, hipMemcpyAsync(c->tokens, prompt, (size_t)P * sizeof(int), hipMemcpyHostToDevice, c->st));
+  const int st3[3] = {P, 0, 0};
+  HIPCHK(c, hipMemcpyAsync(c->state, st3, sizeof(st3), hipMemcpyHostToDevice, c->st));
+  HIPCHK(c, hipStreamSynchronize(c->st));     // st3 is on the stack
+  c->L = c->P = P;
+  c->T.valid = c->D.valid = 0;
+  int rc = ingest(c, &c->T, 0, P - 1);
+  if (!rc && c->have_draft) rc = ingest(c, &c->D, 0, P - 1);
+  if (rc) return rc;
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  c->prefilled = true;
+  return STAIRS_OK;
+}
+
+int draft_propose(stairs_ctx* c, int32_t k, int32_t* draft_out) {
+  if (!c) return STAIRS_EINVAL;
+  if (!c->prefilled) return fail(c, STAIRS_ESTATE, "draft_propose before stairs_prefill");
+  if (!c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
+  if (c->pending_k >= 0) return fail(c, STAIRS_ESTATE, "a proposal is already pending");
+  if (k < 1 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [1, k_max]");
+  if (!capacity_ok(c, c->L + k + 1)) return fail(c, STAIRS_ECAPACITY, "L + k + 1 exceeds max_seq");
+  int rc = do_propose(c, k);
+  if (rc) return rc;
+  if (draft_out) return copy_out(c, draft_out, c->tokens + c->L, (size_t)k * sizeof(int));
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  return STAIRS_OK;
+}
+
+static int verify_common(stairs_ctx* c, int k, int32_t* target_tok_out, int32_t* n_accepted_out, float* logits_out) {
+  int n = 0;
+  int rc = do_verify(c, k, &n);
+  if (rc) return rc;
+  if (target_tok_out) memcpy(target_tok_out, c->h_pinned + 2, (size_t)(k + 1) * sizeof(int));
+  if (n_accepted_out) *n_accepted_out = n;
+  if (logits_out) return copy_out(c, logits_out, c->logits, (size_t)(k + 1) * c->T.cfg.vocab * sizeof(float));
+  return STAIRS_OK;
+}
+
+int stairs_verify(stairs_ctx* c, int32_t k, int32_t* target_tok_out, int32_t* n_accepted_out, float* logits_out) {
+  if (!c) return STAIRS_EINVAL;
+  if (!c->prefilled) return fail(c, STAIRS_ESTATE, "stairs_verify before stairs_prefill");
+  if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
+  if (k > 0 && c->pending_k != k) return fail(c, STAIRS_ESTATE, "no pending proposal of this k");
+  if (k == 0 && c->pending_k > 0) return fail(c, STAIRS_ESTATE, "a proposal of another k is pending");
+  if (!capacity_ok(c, c->L + k + 1)) return fail(c, STAIRS_ECAPACITY, "L + k + 1 exceeds max_seq");
+  return verify_common(c, k, target_tok_out, n_accepted_out, logits_out);
+}
+
+int stairs_verify_tokens(stairs_ctx* c, const int32_t* draft, int32_t k, int32_t* target_tok_out, int32_t* n_accepted_out,
+                         float* logits_out) {
+  if (!c) return STAIRS_EINVAL;
+  if (!c->prefilled) return fail(c, STAIRS_ESTATE, "stairs_verify_tokens before stairs_prefill");
+  if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
+  if (k > 0 && !draft) return fail(c, STAIRS_EINVAL, "draft is NULL");
+  for (int i = 0; i < k; ++i)
+    if (draft[i] < 0 || draft[i] >= c->T.cfg.vocab) return fail(c, STAIRS_EINVAL, "draft token outside the vocabulary");
+  if (!capacity_ok(c, c->L + k + 1)) return fail(c, STAIRS_ECAPACITY, "L + k + 1 exceeds max_seq");
+  if (c->pending_k >= 0 && c->have_draft) c->D.valid = std::min(c->D.valid, c->L - 1);   // drop the proposal's rows
+  c->pending_k = -1;
+  if (k > 0) {
+    HIPCHK(c, hipMemcpyAsync(c->tokens + c->L, draft, (size_t)k * sizeof(int), hipMemcpyHostToDevice, c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    if (c->have_draft) c->D.valid = std::min(c->D.valid, c->L);   // whatever it held beyond S is not these tokens
+  }
+  return verify_common(c, k, target_tok_out, n_accepted_out, logits_out);
+}
+
+int stairs_generate(stairs_ctx* c, const int32_t* prompt, int32_t P, int32_t G, int32_t k, int32_t* tokens_out,
+                    stairs_stats* stats) {
+  if (!c) return STAIRS_EINVAL;
+  if (G < 0 || (G > 0 && !tokens_out)) return fail(c, STAIRS_EINVAL, "G < 0 or tokens_out is NULL");
+  if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
+  if (k > 0 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
+  if (!prompt || P < 1) return fail(c, STAIRS_EINVAL, "prompt is NULL or empty");
+  if (!capacity_ok(c, P + G + k + 1)) return fail(c, STAIRS_ECAPACITY, "P + G + k + 1 exceeds max_seq");
+  stairs_stats s;
+  memset(&s, 0, sizeof(s));
+  HIPCHK(c, hipEventRecord(c->ev[0], c->st));
+  int rc = stairs_prefill(c, prompt, P);
+  if (rc) return rc;
+  HIPCHK(c, hipEventRecord(c->ev[1], c->st));
+  HIPCHK(c, hipEventSynchronize(c->ev[1]));
+  HIPCHK(c, hipEventElapsedTime(&s.ms_prefill, c->ev[0], c->ev[1]));
+  while (c->L - P < G) {
+    HIPCHK(c, hipEventRecord(c->ev[0], c->st));
+    if (k > 0 && (rc = do_propose(c, k))) return rc;
+    HIPCHK(c, hipEventRecord(c->ev[2], c->st));
+    int n = 0;
+    if ((rc = do_verify(c, k, &n))) return rc;
+    HIPCHK(c, hipEventRecord(c->ev[3], c->st));
+    HIPCHK(c, hipEventSynchronize(c->ev[3]));
+    float a = 0.f, b = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&a, c->ev[0], c->ev[2]));
+    HIPCHK(c, hipEventElapsedTime(&b, c->ev[2], c->ev[3]));
+    s.ms_draft += a;
+    s.ms_verify += b;
+    s.iterations += 1;
+    s.accepted += n;
+    s.accept_hist[n] += 1;
+  }
+  HIPCHK(c, hipEventRecord(c->ev[0], c->st));
+  HIPCHK(c, hipEventSynchronize(c->ev[0]));
+  HIPCHK(c, hipEventElapsedTime(&s.ms_decode, c->ev[1], c->ev[0]));
+  s.tokens = G;
+  if (G > 0 && (rc = copy_out(c, tokens_out, c->tokens + P, (size_t)G * sizeof(int)))) return rc;
+  if (stats) *stats = s;
+  return STAIRS_OK;
+}
+
+int stairs_get_tokens(stairs_ctx* c, int32_t* out, int32_t cap, int32_t* len) {
+  if (!c) return STAIRS_EINVAL;
+  if (!c->prefilled) return fail(c, STAIRS_ESTATE, "no sequence yet");
+  if (len) *len = c->L;
+  const int n = std::min(cap, c->L);
+  if (n > 0 && !out) return fail(c, STAIRS_EINVAL, "out is NULL");
+  if (n > 0) return copy_out(c, out, c->tokens, (size_t)n * sizeof(int));
+  return STAIRS_OK;
+}
+
+int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int32_t M, int32_t N, int32_t K, void* hip_stream) {
+  if (!W || !X || !Y || M < 1 || M > kMaxRows || N < 1 || K < 1) return STAIRS_EINVAL;
+  const bool b = dtype == STAIRS_DTYPE_BF16;
+  if (!b && dtype != STAIRS_DTYPE_FP32) return STAIRS_EINVAL;
+  if (b ? (K % 256 || N % 16) : (K % 4 || N % 4)) return STAIRS_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const size_t wbytes = (size_t)N * K * (b ? 2 : 4);
+  const int S = gemm_slices(K, b);
+  char *dW = nullptr, *dWs = nullptr;
+  float *dX = nullptr, *dP = nullptr, *dY = nullptr;
+  int rc = STAIRS_OK;
+  auto ok = [&](hipError_t e) {
+    if (e != hipSuccess && rc == STAIRS_OK) {
+      fprintf(stderr, "stairs_gemm_host: %s\n", hipGetErrorString(e));
+      rc = STAIRS_EHIP;
+    }
+    return e == hipSuccess;
+  };
+  if (ok(hipMalloc((void**)&dW, wbytes)) && ok(hipMalloc((void**)&dX, (size_t)M * K * 4)) &&
+      ok(hipMalloc((void**)&dP, (size_t)S * M * N * 4)) && ok(hipMalloc((void**)&dY, (size_t)M * N * 4)) &&
+      (!b || ok(hipMalloc((void**)&dWs, wbytes)))) {
+    ok(hipMemcpyAsync(dW, W, wbytes, hipMemcpyHostToDevice, st));
+    ok(hipMemcpyAsync(dX, X, (size_t)M * K * 4, hipMemcpyHostToDevice, st));
+    if (b) launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(dW), reinterpret_cast<uint4*>(dWs), N, K, st);
+    RowNorm none{nullptr, nullptr, 0, 0.f};
+    const int S2 = launch_gemm_partial(b, b ? dWs : dW, N, K, dX, K, M, none, dP, st);
+    launch_fin_plain(dP, S2, M, N, dY, N, st);
+    ok(hipGetLastError());
+    ok(hipMemcpyAsync(Y, dY, (size_t)M * N * 4, hipMemcpyDeviceToHost, st));
+    ok(hipStreamSynchronize(st));
+  }
+  (void)hipFree(dW); (void)hipFree(dWs); (void)hipFree(dX); (void)hipFree(dP); (void)hipFree(dY);
+  return rc;
+}
+
+int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len, int32_t reps, float* ms_per_launch,
+                       double* bytes_per_launch) {
+  if (!c) return STAIRS_EINVAL;
+  if (which < 0 || which > 5 || M < 1 || M > kMaxRows || reps < 1 || !ms_per_launch)
+    return fail(c, STAIRS_EINVAL, "bad argument to stairs_time_kernel");
+  if (c->pending_k >= 0) return fail(c, STAIRS_ESTATE, "a proposal is pending");
+  Model* m = &c->T;
+  const stairs_model_cfg& g = m->cfg;
+  const int d = g.d_model, f = g.d_ffn, V = g.vocab, b = m->bf16 ? 1 : 0;
+  const size_t esz = m->esz();
+  if (which == 5 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");
+  RowNorm none{nullptr, nullptr, 0, 0.f};
+  double bytes = 0;
+  for (int pass = 0; pass < 2; ++pass) {          // pass 0 = warm-up of one launch per layer
+    const int n = pass ? reps : g.n_layers;
+    if (pass) HIPCHK(c, hipEventRecord(c->ev[0], c->st));
+    for (int r = 0; r < n; ++r) {
+      const Layer& ly = m->layers[r % g.n_layers];
+      switch (which) {
+        case 0: launch_gemm_partial(b, ly.wgu, 2 * f, d, c->x, d, M, none, c->partial, c->st); bytes = 2.0 * f * d * esz; break;
+        case 1: launch_gemm_partial(b, ly.wqkv, 3 * d, d, c->x, d, M, none, c->partial, c->st); bytes = 3.0 * d * d * esz; break;
+        case 2: launch_gemm_partial(b, ly.wo, d, d, c->x, d, M, none, c->partial, c->st); bytes = 1.0 * d * d * esz; break;
+        case 3: launch_gemm_partial(b, ly.wdown, d, f, c->h, f, M, none, c->partial, c->st); bytes = 1.0 * d * f * esz; break;
+        case 4: launch_gemm_partial(b, m->lm_head, V, d, c->x, d, M, none, c->partial, c->st); bytes = 1.0 * V * d * esz; break;
+        default: {
+          const size_t off = (size_t)(r % g.n_layers) * m->kv_layer_bytes;
+          launch_attention(c->q_rot, m->Kc + off, m->Vc + off, b, m->cap, d, g.n_heads, M, abs_pos(c, ctx_len - M),
+                           (ctx_len + kAttnChunk - 1) / kAttnChunk, c->nchunk_cap, c->part_o, c->part_ml, c->attn_out, c->st);
+          bytes = 2.0 * ctx_len * d * esz;
+        }
+      }
+    }
+    if (pass) HIPCHK(c, hipEventRecord(c->ev[1], c->st));
+    HIPCHK(c, hipGetLastError());
+    HIPCHK(c, hipStreamSynchronize(c->st));
+  }
+  float ms = 0.f;
+  HIPCHK(c, hipEventElapsedTime(&ms, c->ev[0], c->ev[1]));
+  *ms_per_launch = ms / reps;
+  if (bytes_per_launch) *bytes_per_launch = bytes;
+  return STAIRS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+// Launch wrappers of the gfx950 kernels behind the stairs C ABI (see include/stairs.h).
+// Host code only sees these functions; every pointer is a device pointer unless named h_*.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace stairs {
+
+constexpr int kMaxRows = 32;        // rows (new tokens) one forward can take
+constexpr int kAttnChunk = 128;     // keys per attention work-group; boundaries are absolute positions
+constexpr int kSsqGroup = 1024;     // residual columns covered by one sum-of-squares partial
+constexpr int kUnitK = 256;         // k extent of one weight "unit" (8 MFMA k-steps of 32)
+constexpr int kSliceUnits = 2;      // units per split-K slice (512 k)
+
+// Position of row 0 of a forward = *base + offset (base lives in device memory so that the
+// same launch sequence can be replayed without the host knowing the sequence length).
+struct PosRef {
+  const int* base;
+  int offset;
+};
+
+// Row normalisation folded into a GEMM prologue: x[m][k] * gain[k] * rstd[m] with
+// rstd[m] = 1/sqrt(sum_p ssq_part[m*ssq_n + p] / K + eps).  gain == nullptr: no scaling at all.
+struct RowNorm {
+  const float* gain;
+  const float* ssq_part;
+  int ssq_n;
+  float eps;
+};
+
+inline int ssq_groups(int d) { return (d + kSsqGroup - 1) / kSsqGroup; }
+inline int gemm_slices(int K, int dtype_bf16) {
+  if (!dtype_bf16) return 1;
+  int units = K / kUnitK;
+  return (units + kSliceUnits - 1) / kSliceUnits;
+}
+
+// ---- weights --------------------------------------------------------------------------
+// bf16 [N, K] row-major -> MFMA-operand tiles: tile (nt, kt) covers rows nt*16.., k kt*32..,
+// is 1 KiB, stored at index nt*(K/32)+kt; inside it lane l = r + 16*g holds W[nt*16+r][kt*32+g*8..+8].
+void launch_swizzle_bf16(const uint16_t* W, uint4* Wsw, int N, int K, hipStream_t st);
+
+// ---- skinny GEMM: partial[s][m][n] = sum over k-slice s of W[n][k] * xn[m][k] -----------
+// bf16: W is swizzled, split-K slices of 512 k; fp32: W row-major, one slice.
+// partial holds gemm_slices() * M * N floats.  Returns the number of slices.
+int launch_gemm_partial(int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M,
+                        RowNorm nrm, float* partial, hipStream_t st);
+
+// ---- GEMM epilogues (sum the slices in index order, then ...) ---------------------------
+void launch_fin_plain(const float* partial, int S, int M, int N, float* out, int ldo, hipStream_t st);
+// x[m][n] += sum; ssq_part[m][g] = sum over the group's columns of x^2
+void launch_fin_resid(const float* partial, int S, int M, int N, float* x, float* ssq_part, hipStream_t st);
+// h[m][j] = silu(sum[m][j]) * sum[m][f + j]
+void launch_fin_swiglu(const float* partial, int S, int M, int f, float* h, hipStream_t st);
+// columns [0,d) = q, [d,2d) = k, [2d,3d) = v: rotate q and k by the row's position, write q as
+// float, append k and v to the layer's cache ([H][cap][hd], float or bf16) at that position.
+void launch_fin_qkv_rope(const float* partial, int S, int M, int d, int H, const float2* rope_cs,
+                         PosRef pos, float* q_rot, void* Kc, void* Vc, int cap, int kv_bf16,
+                         hipStream_t st);
+
+// ---- small kernels ----------------------------------------------------------------------
+// x[m][:] = emb[tokens[pos+m]][:] (row of zeros if pos+m < 0), plus sum-of-squares partials
+void launch_embed(const void* emb, int emb_bf16, const int* tokens, PosRef pos, int M, int d,
+                  float* x, float* ssq_part, hipStream_t st);
+// cs[m][i] = (cos, sin)((pos+m) * theta^(-2i/hd)), angle formed in double
+void launch_rope_table(PosRef pos, int M, int hd, float theta, float2* cs, hipStream_t st);
+// split-KV attention of M query rows at positions pos..pos+M-1 against keys 0..pos+M-1
+void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv_bf16, int cap, int d,
+                      int H, int M, PosRef pos, int nchunk_launch, int nchunk_cap, float* part_o,
+                      float* part_ml, float* out, hipStream_t st);
+// out[out_pos + r] = argmax_v logits[r][v], ties -> lowest v; out_pos = *pos.base + pos.offset
+void launch_argmax(const float* logits, int ld, int V, int nrows, int* out, PosRef out_pos, hipStream_t st);
+// stairs validation on device: state[0] = L (sequence length). n = longest run with
+// tokens[L+i] == tgt[i]; tokens[L+n] = tgt[n]; state[0] = L+n+1; state[1] = n.
+void launch_accept(int* tokens, const int* tgt, int k, int* state, hipStream_t st);
+
+// opt in to large dynamic LDS for the kernels that need it (once per process/device)
+hipError_t configure_kernels();
+
+}  // namespace stairs

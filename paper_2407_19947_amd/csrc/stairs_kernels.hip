@@ -1,0 +1,645 @@
+// gfx950 kernels of the stairs library.  Written for wave64 / MFMA / LDS of CDNA4 only.
+//
+// Numerics contract shared by all kernels: activations, residual stream, logits and every
+// accumulation are fp32; bf16 appears only as stored weights, stored keys/values and as the
+// MFMA activation operand, which is fed as a bf16 high part plus a bf16 low part (two MFMAs
+// per weight tile) so that the activation keeps ~16 mantissa bits.  Every reduction runs in
+// an order that does not depend on the number of rows M of the launch, so a row of a stair
+// batch gets bit-identical results to the same position computed alone (the property that
+// makes the stair batch return what plain greedy decoding returns, paper abstract / Sec. 3.3).
+#include "stairs_kernels.h"
+
+#include <math.h>
+
+namespace stairs {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// ---------------------------------------------------------------------------------------
+// helpers
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t bf16_bits_rne(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+__device__ __forceinline__ float load_kv(const float* p) { return *p; }
+__device__ __forceinline__ float load_kv(const uint16_t* p) { return bf16_bits_to_float(*p); }
+__device__ __forceinline__ void store_kv(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_kv(uint16_t* p, float v) { *p = (uint16_t)bf16_bits_rne(v); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+  return v;
+}
+// sum over a 256-thread block, fixed order; sm: 4 floats of LDS
+__device__ __forceinline__ float block_sum_256(float v, float* sm) {
+  v = wave_sum(v);
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (sm[0] + sm[1]) + (sm[2] + sm[3]);
+}
+
+__device__ __forceinline__ float row_rstd(const RowNorm& nrm, int m, int K) {
+  float ss = 0.f;
+  for (int p = 0; p < nrm.ssq_n; ++p) ss += nrm.ssq_part[m * nrm.ssq_n + p];
+  return 1.0f / sqrtf(ss / (float)K + nrm.eps);
+}
+
+// ---------------------------------------------------------------------------------------
+// weight re-layout
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_swizzle_bf16(const uint16_t* __restrict__ W, uint4* __restrict__ Wsw,
+                                                      int KT, size_t total, int K) {
+  size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  int lane = (int)(idx & 63);
+  size_t tile = idx >> 6;
+  int nt = (int)(tile / KT), kt = (int)(tile % KT);
+  int r = lane & 15, g = lane >> 4;
+  Wsw[idx] = *reinterpret_cast<const uint4*>(W + ((size_t)nt * 16 + r) * K + kt * 32 + g * 8);
+}
+
+void launch_swizzle_bf16(const uint16_t* W, uint4* Wsw, int N, int K, hipStream_t st) {
+  int KT = K / 32;
+  size_t total = (size_t)(N / 16) * KT * 64;
+  unsigned blocks = (unsigned)((total + 255) / 256);
+  hipLaunchKernelGGL(k_swizzle_bf16, dim3(blocks), dim3(256), 0, st, W, Wsw, KT, total, K);
+}
+
+// ---------------------------------------------------------------------------------------
+// skinny GEMM, bf16 weights, MFMA 16x16x32
+//   work-group = 4 waves; all four work on the same 512-wide k-slice (the X slice is staged once
+//   in LDS as MFMA B fragments, high and low halves) and on 4*NT consecutive 16-row weight tiles.
+//   The weight tile is the MFMA A operand and is loaded straight from HBM in operand order
+//   (1 KiB per wave-load, fully coalesced); the X rows are the B operand.
+// ---------------------------------------------------------------------------------------
+template <int CT, int NT>
+__global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw, int KT, int NTILES,
+                                                   const float* __restrict__ X, int ldx, int M,
+                                                   RowNorm nrm, int K, float* __restrict__ partial, int N) {
+  extern __shared__ uint4 lds[];   // [16 k-steps][CT][hi,lo][64 lanes]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int s = blockIdx.y;
+  const int unit0 = s * kSliceUnits;
+  const int units = min(kSliceUnits, K / kUnitK - unit0);
+  const int kt0 = unit0 * 8;
+  const int tile0 = (blockIdx.x * 4 + wave) * NT;
+
+  uint4 wb[2][8];
+  // first weight unit goes out before anything else: it depends on nothing
+  if (tile0 < NTILES) {
+    const uint4* p = Wsw + ((size_t)tile0 * KT + kt0) * 64 + lane;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) wb[0][i] = p[i * 64];
+  }
+
+  // stage the X slice: fp32 -> (x * rstd * gain) -> bf16 hi + lo, in B-fragment order
+  {
+    const int kgs = units * 32;          // groups of 8 k per row
+    const int k0 = unit0 * kUnitK;
+    for (int w = tid; w < 16 * CT * kgs; w += 256) {
+      const int m = w / kgs, kg = w - m * kgs;
+      float v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = 0.f;
+      if (m < M) {
+        const float4* xp = reinterpret_cast<const float4*>(X + (size_t)m * ldx + k0 + kg * 8);
+        float4 a = xp[0], b = xp[1];
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        if (nrm.gain) {
+          const float r = nrm.ssq_part ? row_rstd(nrm, m, K) : 1.0f;
+          const float4* gp = reinterpret_cast<const float4*>(nrm.gain + k0 + kg * 8);
+          float4 g0 = gp[0], g1 = gp[1];
+          v[0] = v[0] * r * g0.x; v[1] = v[1] * r * g0.y; v[2] = v[2] * r * g0.z; v[3] = v[3] * r * g0.w;
+          v[4] = v[4] * r * g1.x; v[5] = v[5] * r * g1.y; v[6] = v[6] * r * g1.z; v[7] = v[7] * r * g1.w;
+        }
+      }
+      uint32_t hb[8], lb[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        hb[e] = bf16_bits_rne(v[e]);
+        lb[e] = bf16_bits_rne(v[e] - bf16_bits_to_float(hb[e]));
+      }
+      uint4 hi = make_uint4(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16), hb[4] | (hb[5] << 16), hb[6] | (hb[7] << 16));
+      uint4 lo = make_uint4(lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16), lb[4] | (lb[5] << 16), lb[6] | (lb[7] << 16));
+      const int kt = kg >> 2, g = kg & 3, ct = m >> 4, j = m & 15;
+      const int base = ((kt * CT + ct) * 2) * 64 + g * 16 + j;
+      lds[base] = hi;
+      lds[base + 64] = lo;
+    }
+  }
+  __syncthreads();
+
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    f32x4 acc[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const bool tile_ok = (tile0 + t) < NTILES;
+#pragma unroll
+    for (int ku = 0; ku < kSliceUnits; ++ku) {
+      const int u = t * kSliceUnits + ku;
+      // prefetch the next unit into the other buffer
+      if (u + 1 < NT * kSliceUnits) {
+        const int tn = (u + 1) / kSliceUnits, kun = (u + 1) % kSliceUnits;
+        if (kun < units && (tile0 + tn) < NTILES) {
+          const uint4* p = Wsw + ((size_t)(tile0 + tn) * KT + kt0 + kun * 8) * 64 + lane;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) wb[(u + 1) & 1][i] = p[i * 64];
+        }
+      }
+      if (ku < units && tile_ok) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const bf16x8 a = __builtin_bit_cast(bf16x8, wb[u & 1][i]);
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct) {
+            const int base = (((ku * 8 + i) * CT + ct) * 2) * 64 + lane;
+            const bf16x8 bh = __builtin_bit_cast(bf16x8, lds[base]);
+            const bf16x8 bl = __builtin_bit_cast(bf16x8, lds[base + 64]);
+            acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[ct], 0, 0, 0);
+            acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[ct], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if (tile_ok) {
+      const int n = (tile0 + t) * 16 + 4 * (lane >> 4);
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) {
+        const int m = ct * 16 + (lane & 15);
+        if (m < M) {
+          float4 o = make_float4(acc[ct][0], acc[ct][1], acc[ct][2], acc[ct][3]);
+          *reinterpret_cast<float4*>(partial + ((size_t)s * M + m) * N + n) = o;
+        }
+      }
+    }
+  }
+}
+
+// fp32 weights, row-major: one wave per output feature, lanes stride over k.
+template <int MR>
+__global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ W, int N, int K,
+                                                  const float* __restrict__ X, int ldx, int M, RowNorm nrm,
+                                                  float* __restrict__ partial) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = blockIdx.x * 4 + wave;
+  if (n >= N) return;
+  float rs[MR], acc[MR];
+#pragma unroll
+  for (int i = 0; i < MR; ++i) {
+    acc[i] = 0.f;
+    rs[i] = (nrm.gain && nrm.ssq_part && i < M) ? row_rstd(nrm, i, K) : 1.0f;
+  }
+  for (int k = lane * 4; k < K; k += 256) {
+    const float4 w = *reinterpret_cast<const float4*>(W + (size_t)n * K + k);
+    float4 g = make_float4(1.f, 1.f, 1.f, 1.f);
+    if (nrm.gain) g = *reinterpret_cast<const float4*>(nrm.gain + k);
+#pragma unroll
+    for (int i = 0; i < MR; ++i) {
+      if (i < M) {
+        const float4 x = *reinterpret_cast<const float4*>(X + (size_t)i * ldx + k);
+        float a = acc[i];
+        a = fmaf(w.x, x.x * rs[i] * g.x, a);
+        a = fmaf(w.y, x.y * rs[i] * g.y, a);
+        a = fmaf(w.z, x.z * rs[i] * g.z, a);
+        a = fmaf(w.w, x.w * rs[i] * g.w, a);
+        acc[i] = a;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < MR; ++i) {
+    if (i < M) {
+      const float v = wave_sum(acc[i]);
+      if (lane == 0) partial[(size_t)i * N + n] = v;
+    }
+  }
+}
+
+int launch_gemm_partial(int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M,
+                        RowNorm nrm, float* partial, hipStream_t st) {
+  if (!dtype_bf16) {
+    dim3 grid((N + 3) / 4), block(256);
+    const float* Wf = static_cast<const float*>(W);
+    if (M <= 4) hipLaunchKernelGGL(k_gemm_f32<4>, grid, block, 0, st, Wf, N, K, X, ldx, M, nrm, partial);
+    else if (M <= 16) hipLaunchKernelGGL(k_gemm_f32<16>, grid, block, 0, st, Wf, N, K, X, ldx, M, nrm, partial);
+    else hipLaunchKernelGGL(k_gemm_f32<32>, grid, block, 0, st, Wf, N, K, X, ldx, M, nrm, partial);
+    return 1;
+  }
+  const int S = gemm_slices(K, 1);
+  const int NTILES = N / 16, KT = K / 32;
+  const uint4* Wsw = static_cast<const uint4*>(W);
+  // enough work-groups to cover the chip a few times over; otherwise more tiles per wave
+  const int NT = ((size_t)((NTILES + 7) / 8) * S >= 1024) ? 2 : 1;
+  dim3 grid((NTILES + 4 * NT - 1) / (4 * NT), S), block(256);
+  const int CT = (M <= 16) ? 1 : 2;
+  const size_t lds = (size_t)16 * CT * 2 * 64 * sizeof(uint4);
+#define STAIRS_GEMM(ct, nt) \
+  hipLaunchKernelGGL((k_gemm_bf16<ct, nt>), grid, block, lds, st, Wsw, KT, NTILES, X, ldx, M, nrm, K, partial, N)
+  if (CT == 1 && NT == 1) STAIRS_GEMM(1, 1);
+  else if (CT == 1) STAIRS_GEMM(1, 2);
+  else if (NT == 1) STAIRS_GEMM(2, 1);
+  else STAIRS_GEMM(2, 2);
+#undef STAIRS_GEMM
+  return S;
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMM epilogues
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ float4 sum_slices4(const float* partial, int S, int M, int N, int m, int n) {
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int s = 0; s < S; ++s) {
+    const float4 p = *reinterpret_cast<const float4*>(partial + ((size_t)s * M + m) * N + n);
+    a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+  }
+  return a;
+}
+__device__ __forceinline__ float sum_slices1(const float* partial, int S, int M, int N, int m, int n) {
+  float a = 0.f;
+  for (int s = 0; s < S; ++s) a += partial[((size_t)s * M + m) * N + n];
+  return a;
+}
+
+__global__ __launch_bounds__(256) void k_fin_plain(const float* __restrict__ partial, int S, int M, int N,
+                                                   float* __restrict__ out, int ldo) {
+  const int n = (blockIdx.x * 256 + threadIdx.x) * 4, m = blockIdx.y;
+  if (n >= N) return;
+  *reinterpret_cast<float4*>(out + (size_t)m * ldo + n) = sum_slices4(partial, S, M, N, m, n);
+}
+
+__global__ __launch_bounds__(256) void k_fin_resid(const float* __restrict__ partial, int S, int M, int N,
+                                                   float* __restrict__ x, float* __restrict__ ssq_part) {
+  __shared__ float sm[4];
+  const int n = (blockIdx.x * 256 + threadIdx.x) * 4, m = blockIdx.y;
+  float ss = 0.f;
+  if (n < N) {
+    float4 a = sum_slices4(partial, S, M, N, m, n);
+    float4* xp = reinterpret_cast<float4*>(x + (size_t)m * N + n);
+    const float4 r = *xp;
+    a.x += r.x; a.y += r.y; a.z += r.z; a.w += r.w;
+    *xp = a;
+    ss = (a.x * a.x + a.y * a.y) + (a.z * a.z + a.w * a.w);
+  }
+  ss = block_sum_256(ss, sm);
+  if (threadIdx.x == 0) ssq_part[m * gridDim.x + blockIdx.x] = ss;
+}
+
+__global__ __launch_bounds__(256) void k_fin_swiglu(const float* __restrict__ partial, int S, int M, int f,
+                                                    float* __restrict__ h) {
+  const int j = (blockIdx.x * 256 + threadIdx.x) * 4, m = blockIdx.y;
+  if (j >= f) return;
+  const float4 g = sum_slices4(partial, S, M, 2 * f, m, j);
+  const float4 u = sum_slices4(partial, S, M, 2 * f, m, f + j);
+  float4 o;
+  o.x = g.x / (1.0f + expf(-g.x)) * u.x;
+  o.y = g.y / (1.0f + expf(-g.y)) * u.y;
+  o.z = g.z / (1.0f + expf(-g.z)) * u.z;
+  o.w = g.w / (1.0f + expf(-g.w)) * u.w;
+  *reinterpret_cast<float4*>(h + (size_t)m * f + j) = o;
+}
+
+template <typename KV>
+__global__ __launch_bounds__(256) void k_fin_qkv_rope(const float* __restrict__ partial, int S, int M, int d, int H,
+                                                      const float2* __restrict__ rope_cs, PosRef pos,
+                                                      float* __restrict__ q_rot, KV* __restrict__ Kc,
+                                                      KV* __restrict__ Vc, int cap) {
+  const int hd = d / H, half = hd / 2;
+  const int per_row = 3 * H * half;
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int m = blockIdx.y;
+  if (idx >= per_row) return;
+  const int e = idx % half;
+  const int h = (idx / half) % H;
+  const int which = idx / (half * H);
+  const int p = *pos.base + pos.offset + m;
+  if (p < 0) return;
+  const int N = 3 * d;
+  const int col = which * d + h * hd + e;
+  const float a = sum_slices1(partial, S, M, N, m, col);
+  const float b = sum_slices1(partial, S, M, N, m, col + half);
+  if (which == 2) {
+    KV* dst = Vc + ((size_t)h * cap + p) * hd + e;
+    store_kv(dst, a);
+    store_kv(dst + half, b);
+    return;
+  }
+  const float2 cs = rope_cs[m * 64 + e];
+  const float ra = a * cs.x - b * cs.y;
+  const float rb = b * cs.x + a * cs.y;
+  if (which == 0) {
+    q_rot[(size_t)m * d + h * hd + e] = ra;
+    q_rot[(size_t)m * d + h * hd + e + half] = rb;
+  } else {
+    KV* dst = Kc + ((size_t)h * cap + p) * hd + e;
+    store_kv(dst, ra);
+    store_kv(dst + half, rb);
+  }
+}
+
+void launch_fin_plain(const float* partial, int S, int M, int N, float* out, int ldo, hipStream_t st) {
+  hipLaunchKernelGGL(k_fin_plain, dim3((N / 4 + 255) / 256, M), dim3(256), 0, st, partial, S, M, N, out, ldo);
+}
+void launch_fin_resid(const float* partial, int S, int M, int N, float* x, float* ssq_part, hipStream_t st) {
+  hipLaunchKernelGGL(k_fin_resid, dim3(ssq_groups(N), M), dim3(256), 0, st, partial, S, M, N, x, ssq_part);
+}
+void launch_fin_swiglu(const float* partial, int S, int M, int f, float* h, hipStream_t st) {
+  hipLaunchKernelGGL(k_fin_swiglu, dim3((f / 4 + 255) / 256, M), dim3(256), 0, st, partial, S, M, f, h);
+}
+void launch_fin_qkv_rope(const float* partial, int S, int M, int d, int H, const float2* rope_cs, PosRef pos,
+                         float* q_rot, void* Kc, void* Vc, int cap, int kv_bf16, hipStream_t st) {
+  const int per_row = 3 * H * (d / H / 2);
+  dim3 grid((per_row + 255) / 256, M), block(256);
+  if (kv_bf16)
+    hipLaunchKernelGGL(k_fin_qkv_rope<uint16_t>, grid, block, 0, st, partial, S, M, d, H, rope_cs, pos, q_rot,
+                       static_cast<uint16_t*>(Kc), static_cast<uint16_t*>(Vc), cap);
+  else
+    hipLaunchKernelGGL(k_fin_qkv_rope<float>, grid, block, 0, st, partial, S, M, d, H, rope_cs, pos, q_rot,
+                       static_cast<float*>(Kc), static_cast<float*>(Vc), cap);
+}
+
+// ---------------------------------------------------------------------------------------
+// embedding gather, rope table
+// ---------------------------------------------------------------------------------------
+template <typename E>
+__global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const int* __restrict__ tokens, PosRef pos,
+                                               int d, float* __restrict__ x, float* __restrict__ ssq_part) {
+  __shared__ float sm[4];
+  const int c = (blockIdx.x * 256 + threadIdx.x) * 4, m = blockIdx.y;
+  const int p = *pos.base + pos.offset + m;
+  float ss = 0.f;
+  if (c < d) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (p >= 0) {
+      const E* row = emb + (size_t)tokens[p] * d + c;
+      v.x = load_kv(row); v.y = load_kv(row + 1); v.z = load_kv(row + 2); v.w = load_kv(row + 3);
+    }
+    *reinterpret_cast<float4*>(x + (size_t)m * d + c) = v;
+    ss = (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+  }
+  ss = block_sum_256(ss, sm);
+  if (threadIdx.x == 0) ssq_part[m * gridDim.x + blockIdx.x] = ss;
+}
+
+void launch_embed(const void* emb, int emb_bf16, const int* tokens, PosRef pos, int M, int d, float* x,
+                  float* ssq_part, hipStream_t st) {
+  dim3 grid(ssq_groups(d), M), block(256);
+  if (emb_bf16)
+    hipLaunchKernelGGL(k_embed<uint16_t>, grid, block, 0, st, static_cast<const uint16_t*>(emb), tokens, pos, d, x, ssq_part);
+  else
+    hipLaunchKernelGGL(k_embed<float>, grid, block, 0, st, static_cast<const float*>(emb), tokens, pos, d, x, ssq_part);
+}
+
+__global__ void k_rope_table(PosRef pos, int hd, double theta, float2* __restrict__ cs) {
+  const int m = blockIdx.x, i = threadIdx.x;
+  if (i >= hd / 2) return;
+  const double p = (double)(*pos.base + pos.offset + m);
+  const double inv_freq = pow(theta, -2.0 * (double)i / (double)hd);
+  const double ang = p * inv_freq;
+  cs[m * 64 + i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+void launch_rope_table(PosRef pos, int M, int hd, float theta, float2* cs, hipStream_t st) {
+  hipLaunchKernelGGL(k_rope_table, dim3(M), dim3(64), 0, st, pos, hd, (double)theta, cs);
+}
+
+// ---------------------------------------------------------------------------------------
+// KV-cache attention: work-group = (128-key chunk, head, group of up to 16 query rows).
+// The chunk's keys, then its values, are staged in LDS once and used by all the rows.
+// Chunk boundaries are absolute key positions and chunks are combined in index order.
+// ---------------------------------------------------------------------------------------
+template <typename KV, int HD, int MR>
+__global__ __launch_bounds__(128) void k_attn(const float* __restrict__ q, const KV* __restrict__ Kc,
+                                              const KV* __restrict__ Vc, int cap, int d, int H, int M, PosRef pos,
+                                              float scale, int nchunk_cap, float* __restrict__ part_o,
+                                              float* __restrict__ part_ml) {
+  constexpr int EPV = 16 / sizeof(KV);     // elements per 16-byte vector
+  constexpr int ROW = HD + EPV;            // padded LDS row
+  extern __shared__ uint4 smem_u4[];
+  KV* s_kv = reinterpret_cast<KV*>(smem_u4);                                   // [128][ROW]
+  float* s_q = reinterpret_cast<float*>(s_kv + 128 * ROW);                     // [MR][HD]
+  float* s_p = s_q + MR * HD;                                                  // [MR][128]
+  float* s_ml = s_p + MR * 128;                                                // [MR][2]
+
+  const int c = blockIdx.x, h = blockIdx.y, row0 = blockIdx.z * 16;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int pos0 = *pos.base + pos.offset;
+  const int kv_len = pos0 + M;
+  const int key0 = c * kAttnChunk;
+  if (key0 >= kv_len) return;
+  const int nkeys = min(kAttnChunk, kv_len - key0);
+  const int rows = min(MR, M - row0);      // valid query rows of this group
+
+  for (int idx = tid; idx < MR * HD; idx += 128) {
+    const int i = idx / HD, e = idx - i * HD;
+    s_q[idx] = (i < rows) ? q[(size_t)(row0 + i) * d + h * HD + e] : 0.f;
+  }
+  {
+    const uint4* src = reinterpret_cast<const uint4*>(Kc + ((size_t)h * cap + key0) * HD);
+    constexpr int VPR = HD / EPV;
+    for (int idx = tid; idx < nkeys * VPR; idx += 128) {
+      const int r = idx / VPR, cc = idx - r * VPR;
+      *reinterpret_cast<uint4*>(s_kv + r * ROW + cc * EPV) = src[idx];
+    }
+  }
+  __syncthreads();
+
+  float sacc[MR];
+#pragma unroll
+  for (int i = 0; i < MR; ++i) sacc[i] = 0.f;
+  if (tid < nkeys) {
+    const KV* krow = s_kv + tid * ROW;
+    for (int e0 = 0; e0 < HD; e0 += EPV) {
+      float kf[EPV];
+#pragma unroll
+      for (int j = 0; j < EPV; ++j) kf[j] = load_kv(krow + e0 + j);
+#pragma unroll
+      for (int i = 0; i < MR; ++i) {
+        float a = sacc[i];
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) a = fmaf(s_q[i * HD + e0 + j], kf[j], a);
+        sacc[i] = a;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < MR; ++i) {
+    const bool ok = (tid < nkeys) && (i < rows) && (key0 + tid <= pos0 + row0 + i);
+    s_p[i * 128 + tid] = ok ? sacc[i] * scale : -INFINITY;
+  }
+  __syncthreads();   // everybody is done with the keys; scores are in LDS
+
+  {
+    const uint4* src = reinterpret_cast<const uint4*>(Vc + ((size_t)h * cap + key0) * HD);
+    constexpr int VPR = HD / EPV;
+    for (int idx = tid; idx < nkeys * VPR; idx += 128) {
+      const int r = idx / VPR, cc = idx - r * VPR;
+      *reinterpret_cast<uint4*>(s_kv + r * ROW + cc * EPV) = src[idx];
+    }
+  }
+  for (int i = wave; i < MR; i += 2) {
+    const float a = s_p[i * 128 + lane], b = s_p[i * 128 + lane + 64];
+    const float mx = wave_max(fmaxf(a, b));
+    float pa = 0.f, pb = 0.f;
+    if (mx != -INFINITY) {
+      pa = expf(a - mx);
+      pb = expf(b - mx);
+    }
+    const float l = wave_sum(pa + pb);
+    s_p[i * 128 + lane] = pa;
+    s_p[i * 128 + lane + 64] = pb;
+    if (lane == 0) {
+      s_ml[i * 2] = mx;
+      s_ml[i * 2 + 1] = l;
+    }
+  }
+  __syncthreads();
+
+  if (tid < HD) {
+    float o[MR];
+#pragma unroll
+    for (int i = 0; i < MR; ++i) o[i] = 0.f;
+    for (int t = 0; t < nkeys; ++t) {
+      const float v = load_kv(s_kv + t * ROW + tid);
+#pragma unroll
+      for (int i = 0; i < MR; ++i) o[i] = fmaf(s_p[i * 128 + t], v, o[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < MR; ++i)
+      if (i < rows) part_o[(((size_t)(row0 + i) * H + h) * nchunk_cap + c) * HD + tid] = o[i];
+  }
+  if (tid < rows) {
+    float* ml = part_ml + (((size_t)(row0 + tid) * H + h) * nchunk_cap + c) * 2;
+    ml[0] = s_ml[tid * 2];
+    ml[1] = s_ml[tid * 2 + 1];
+  }
+}
+
+template <int HD>
+__global__ void k_attn_combine(const float* __restrict__ part_o, const float* __restrict__ part_ml, int H, PosRef pos,
+                               int nchunk_cap, float* __restrict__ out, int d) {
+  const int h = blockIdx.x, m = blockIdx.y, e = threadIdx.x;
+  const int p = *pos.base + pos.offset + m;
+  float* dst = out + (size_t)m * d + h * HD + e;
+  if (p < 0) {
+    *dst = 0.f;
+    return;
+  }
+  const int nch = p / kAttnChunk + 1;
+  const size_t base = ((size_t)m * H + h) * nchunk_cap;
+  float gmax = -INFINITY;
+  for (int c = 0; c < nch; ++c) gmax = fmaxf(gmax, part_ml[(base + c) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int c = 0; c < nch; ++c) {
+    const float mc = part_ml[(base + c) * 2];
+    if (mc == -INFINITY) continue;
+    const float w = expf(mc - gmax);
+    num = fmaf(w, part_o[(base + c) * HD + e], num);
+    den = fmaf(w, part_ml[(base + c) * 2 + 1], den);
+  }
+  *dst = num / den;
+}
+
+template <typename KV, int HD>
+static void attn_dispatch(const float* q, const void* Kc, const void* Vc, int cap, int d, int H, int M, PosRef pos,
+                          int nchunk_launch, int nchunk_cap, float* part_o, float* part_ml, hipStream_t st) {
+  const float scale = 1.0f / sqrtf((float)HD);
+  const KV* K = static_cast<const KV*>(Kc);
+  const KV* V = static_cast<const KV*>(Vc);
+  dim3 grid(nchunk_launch, H, (M + 15) / 16), block(128);
+  constexpr int EPV = 16 / sizeof(KV);
+#define STAIRS_ATTN(mr)                                                                                   \
+  {                                                                                                       \
+    const size_t lds = (size_t)128 * (HD + EPV) * sizeof(KV) + (size_t)(mr) * (HD + 128 + 2) * sizeof(float); \
+    hipLaunchKernelGGL((k_attn<KV, HD, mr>), grid, block, lds, st, q, K, V, cap, d, H, M, pos, scale,       \
+                       nchunk_cap, part_o, part_ml);                                                      \
+  }
+  if (M <= 2) STAIRS_ATTN(2)
+  else if (M <= 8) STAIRS_ATTN(8)
+  else STAIRS_ATTN(16)
+#undef STAIRS_ATTN
+}
+
+void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv_bf16, int cap, int d, int H, int M,
+                      PosRef pos, int nchunk_launch, int nchunk_cap, float* part_o, float* part_ml, float* out,
+                      hipStream_t st) {
+  const int hd = d / H;
+  if (kv_bf16) {
+    if (hd == 128) attn_dispatch<uint16_t, 128>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
+    else attn_dispatch<uint16_t, 64>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
+  } else {
+    if (hd == 128) attn_dispatch<float, 128>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
+    else attn_dispatch<float, 64>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
+  }
+  if (hd == 128)
+    hipLaunchKernelGGL(k_attn_combine<128>, dim3(H, M), dim3(128), 0, st, part_o, part_ml, H, pos, nchunk_cap, out, d);
+  else
+    hipLaunchKernelGGL(k_attn_combine<64>, dim3(H, M), dim3(64), 0, st, part_o, part_ml, H, pos, nchunk_cap, out, d);
+}
+
+// ---------------------------------------------------------------------------------------
+// per-row vocabulary argmax (ties -> lowest index) and stairs validation
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits, int ld, int V, int* __restrict__ out,
+                                                PosRef out_pos) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const float* row = logits + (size_t)r * ld;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int v = tid * 4; v < V; v += 1024) {
+    const float4 x = *reinterpret_cast<const float4*>(row + v);
+    if (x.x > best || bi == 0x7fffffff) { best = x.x; bi = v; }
+    if (x.y > best) { best = x.y; bi = v + 1; }
+    if (x.z > best) { best = x.z; bi = v + 2; }
+    if (x.w > best) { best = x.w; bi = v + 3; }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const float ov = __shfl_xor(best, off);
+    const int oi = __shfl_xor(bi, off);
+    if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+  }
+  if ((tid & 63) == 0) { sv[tid >> 6] = best; si[tid >> 6] = bi; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
+    const int o = (out_pos.base ? *out_pos.base : 0) + out_pos.offset + r;
+    out[o] = bi;
+  }
+}
+
+void launch_argmax(const float* logits, int ld, int V, int nrows, int* out, PosRef out_pos, hipStream_t st) {
+  hipLaunchKernelGGL(k_argmax, dim3(nrows), dim3(256), 0, st, logits, ld, V, out, out_pos);
+}
+
+__global__ void k_accept(int* __restrict__ tokens, const int* __restrict__ tgt, int k, int* __restrict__ state) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const int L = state[0];
+  int n = 0;
+  while (n < k && tokens[L + n] == tgt[n]) ++n;
+  tokens[L + n] = tgt[n];
+  state[0] = L + n + 1;
+  state[1] = n;
+}
+
+void launch_accept(int* tokens, const int* tgt, int k, int* state, hipStream_t st) {
+  hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, st, tokens, tgt, k, state);
+}
+
+hipError_t configure_kernels() { return hipSuccess; }
+
+}  // namespace stairs

@@ -1,0 +1,57 @@
+"""GPU: the skinny GEMM path against a float64 matrix product on the same inputs."""
+import numpy as np
+import pytest
+
+import paper_2407_19947_amd as pkg
+import synth_inputs as si
+from oracle import stairs_oracle as so
+
+pytestmark = pytest.mark.gpu
+
+
+def _ref(W, X):
+    Wr = so._decode(W, np.float64)
+    return X.astype(np.float64) @ Wr.T
+
+
+# (N, K): tiles that end in the middle of a work-group, odd number of 256-wide k units (ragged
+# last split-K slice), the benchmark shapes of the 125M model, one 7B shape
+BF16_SHAPES = [(16, 256), (48, 768), (2304, 768), (6144, 768), (768, 3072), (32000, 768), (4096, 11008)]
+
+
+@pytest.mark.parametrize("N,K", BF16_SHAPES)
+@pytest.mark.parametrize("M", [1, 2, 5, 16, 17, 32])
+def test_gemm_bf16(N, K, M):
+    print(f"gemm bf16 N={N} K={K} M={M}", flush=True)
+    rng = np.random.default_rng([N, K, M])
+    W = si.bf16_round(rng.standard_normal((N, K), dtype=np.float32) * np.float32(0.02))
+    X = rng.standard_normal((M, K), dtype=np.float32)
+    Y = pkg.stairs_gemm_host(W, X)
+    ref = _ref(W, X)
+    # x is carried as bf16 hi + lo (~16 mantissa bits), products accumulate in fp32
+    tol = 4e-5 * np.sqrt(K) * 0.02 * 4 + 1e-6
+    assert np.max(np.abs(Y - ref)) < tol, np.max(np.abs(Y - ref))
+
+
+@pytest.mark.parametrize("N,K", [(4, 4), (1024, 256), (768, 1024), (1024, 1028)])
+@pytest.mark.parametrize("M", [1, 4, 5, 17, 32])
+def test_gemm_fp32(N, K, M):
+    print(f"gemm fp32 N={N} K={K} M={M}", flush=True)
+    rng = np.random.default_rng([N, K, M, 1])
+    W = rng.standard_normal((N, K), dtype=np.float32) * np.float32(0.02)
+    X = rng.standard_normal((M, K), dtype=np.float32)
+    Y = pkg.stairs_gemm_host(W, X)
+    assert np.max(np.abs(Y - _ref(W, X))) < 2e-6 * np.sqrt(K)
+
+
+def test_gemm_rows_do_not_depend_on_batch():
+    """Row i computed in a batch of M rows is bit-identical to row i computed alone."""
+    rng = np.random.default_rng(5)
+    for dt in ("bf16", "fp32"):
+        W = rng.standard_normal((512, 768), dtype=np.float32) * np.float32(0.02)
+        W = si.bf16_round(W) if dt == "bf16" else W
+        X = rng.standard_normal((17, 768), dtype=np.float32)
+        full = pkg.stairs_gemm_host(W, X)
+        for i in (0, 3, 16):
+            assert np.array_equal(pkg.stairs_gemm_host(W, X[i:i + 1])[0], full[i])
+        assert np.array_equal(pkg.stairs_gemm_host(W, X[:5]), full[:5])

@@ -1,0 +1,154 @@
+"""GPU parity proper: the HIP path through its C ABI against the CPU oracle, element by
+element on per-stair logits and token by token on the generated sequence."""
+import numpy as np
+import pytest
+
+import paper_2407_19947_amd as pkg
+import synth_inputs as si
+from oracle import stairs_oracle as so
+from parity_util import LOGIT_TOL_BF16, run_side_by_side
+
+pytestmark = pytest.mark.gpu
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+def test_cfg1_tiny_fp32_full():
+    """Workload 1 at full size: fp32 pair, P=32, G=64, k=4; oracle in float64."""
+    w = si.WORKLOADS["cfg1_tiny_fp32"]
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    res = run_side_by_side(target, draft, prompt, w["G"], 4, np.float64, 2e-4, log=_log)
+    assert res["token_mismatches"] == 0
+    T = so.OracleModel(target, np.float64)
+    assert res["tokens"] == so.greedy_bruteforce(T, prompt, w["G"])
+    _log(f"cfg1: iterations={res['iterations']} max_logit_err={res['max_logit_err']:.3g} n={res['n_accepted']}")
+
+
+@pytest.mark.parametrize("k", [0, 1, 2, 7, 16])
+def test_cfg1_other_k(k):
+    w = si.WORKLOADS["cfg1_tiny_fp32"]
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    res = run_side_by_side(target, draft, prompt, 40, k, np.float64, 2e-4)
+    assert res["token_mismatches"] == 0
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 33, 130])
+def test_fp32_prompt_lengths(P):
+    """Shortest prompts (nothing to prefill, the draft's two-row step starts before position 0)
+    and prompts that cross prefill-chunk and attention-chunk boundaries."""
+    w = si.scaled_workload("cfg1_tiny_fp32", P=max(P, 1))
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    res = run_side_by_side(target, draft, prompt, 12, 3, np.float64, 2e-4)
+    assert res["token_mismatches"] == 0
+
+
+def test_bf16_small_pair():
+    """bf16 path on a reduced 125M-style pair (d=256, 4 heads of 64, vocab 2048): several GEMM
+    tiles, ragged k slices (d_ffn = 768 -> 3 units), a sequence that crosses an attention chunk."""
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=4, d_model=256, n_heads=4, d_ffn=768, vocab=2048),
+                           draft=dict(kind="prefix", n_layers=1), P=120, G=40)
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    for k in (0, 3, 8):
+        res = run_side_by_side(target, draft, prompt, w["G"], k, np.float64, LOGIT_TOL_BF16, log=_log)
+        _log(f"bf16 small k={k}: err={res['max_logit_err']:.3g} mism={res['token_mismatches']} n={res['n_accepted']}")
+
+
+def test_bf16_head_dim_128_and_independent_draft():
+    w = dict(seed=77, dtype="bf16", target=dict(n_layers=3, d_model=512, n_heads=4, d_ffn=1024, vocab=4096),
+             draft=dict(kind="independent", seed=78, n_layers=2, d_model=256, n_heads=4, d_ffn=512),
+             deep_scale=1.0, P=70, G=24, ks=[4])
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    res = run_side_by_side(target, draft, prompt, w["G"], 4, np.float64, LOGIT_TOL_BF16, log=_log)
+    _log(f"hd128: err={res['max_logit_err']:.3g} n={res['n_accepted']}")
+
+
+@pytest.mark.parametrize("k", [2, 4, 8])
+def test_cfg2_125m_full_shape(k):
+    """Workload 2 at its full model shape and prompt; G shortened to 48 tokens so that the
+    float32 oracle finishes in seconds (the full G runs in the self-consistency test below)."""
+    w = si.WORKLOADS["cfg2_125m"]
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    res = run_side_by_side(target, draft, prompt, 48, k, np.float32, LOGIT_TOL_BF16, log=_log)
+    _log(f"cfg2 k={k}: err={res['max_logit_err']:.3g} mism={res['token_mismatches']} n={res['n_accepted']}")
+
+
+def test_generate_equals_plain_greedy_on_gpu():
+    """The paper's invariant on the device itself: stairs generation with any k returns the
+    tokens of k = 0 (the target alone), bit for bit; workload 2 at full size."""
+    w = si.WORKLOADS["cfg2_125m"]
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    cap = w["P"] + w["G"] + 20
+    with pkg.Stairs(target, draft, k_max=16, max_seq=cap) as s:
+        base, st0 = s.generate(prompt, w["G"], 0)
+        assert st0.iterations == w["G"]
+        for k in (1, 2, 4, 8, 16):
+            toks, st = s.generate(prompt, w["G"], k)
+            _log(f"k={k}: iterations={st.iterations} accepted={st.accepted} decode_ms={st.ms_decode:.1f}")
+            assert np.array_equal(toks, base), f"k={k} differs from plain greedy"
+            assert st.iterations + st.accepted >= w["G"]
+            assert sum(st.accept_hist) == st.iterations
+        again, _ = s.generate(prompt, w["G"], 4)
+        assert np.array_equal(again, base)
+
+
+def test_forced_accept_and_reject_counts():
+    """Closed forms: draft == target keeps every assistant token (iterations = ceil(G/(k+1)));
+    assistant tokens forced to differ keep none (iterations = G)."""
+    w = si.scaled_workload("cfg1_tiny_fp32")
+    target, _ = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    G, k = 30, 4
+    with pkg.Stairs(target, target, k_max=k, max_seq=128) as s:
+        toks, st = s.generate(prompt, G, k)
+        assert st.iterations == -(-G // (k + 1)) and st.accept_hist[k] == st.iterations
+        base, _ = s.generate(prompt, G, 0)
+        assert np.array_equal(toks, base)
+        s.prefill(prompt)
+        for i in range(G):
+            bad = [(int(base[i]) + 1) % w["target"]["vocab"]] + [0] * (k - 1)
+            tgt, n, _ = s.verify_tokens(bad)
+            assert n == 0 and tgt[0] == base[i]
+        assert list(s.tokens()[len(prompt):]) == list(base)
+
+
+def test_error_paths_on_device():
+    w = si.scaled_workload("cfg1_tiny_fp32")
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    with pkg.Stairs(target, draft, k_max=4, max_seq=64) as s:
+        with pytest.raises(pkg.StairsError) as e:
+            s.verify(0)
+        assert e.value.code == -3                              # verify before prefill
+        with pytest.raises(pkg.StairsError) as e:
+            s.prefill(list(prompt) * 2)                        # 64 + k_max + 1 > max_seq
+        assert e.value.code == -2
+        with pytest.raises(pkg.StairsError) as e:
+            s.prefill([5, 99999])
+        assert e.value.code == -1
+        s.prefill(prompt)
+        with pytest.raises(pkg.StairsError) as e:
+            s.verify(3)                                        # no pending proposal
+        assert e.value.code == -3
+        with pytest.raises(pkg.StairsError) as e:
+            s.propose(5)                                       # k > k_max
+        assert e.value.code == -1
+        s.propose(2)
+        with pytest.raises(pkg.StairsError) as e:
+            s.propose(2)                                       # already pending
+        assert e.value.code == -3
+        with pytest.raises(pkg.StairsError) as e:
+            s.verify(3)                                        # pending k differs
+        assert e.value.code == -3
+        s.verify(2)
+        with pytest.raises(pkg.StairsError) as e:
+            s.generate(prompt, 40, 4)                          # P + G + k + 1 > max_seq
+        assert e.value.code == -2
