@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the stairs-assisted greedy generation hot path on one MI355X.
+
+One "step" = one stairs decode of G tokens after an (untimed, separately reported) prefill of
+the workload's prompt: draft k-step proposal, stair verification forward at M = k+1 rows,
+per-row argmax, validation walk, KV rollback, repeated until G tokens exist.  Weights, KV
+caches and the prompt are resident in HBM when the timed region starts.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0           # MI355X published HBM3E peak
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k_gemm_bf16_gateup_cfg4_7b_pmc.txt")
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def measured_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (a line 'traffic_bytes_per_launch: N'), or None."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(w, target, draft, prompt, k, sample_P, sample_G):
+    """The oracle's cached stairs loop, as it stands, on the host cores: same model pair, the
+    first sample_P prompt tokens, sample_G generated tokens; timed after its prefill, like
+    the GPU."""
+    import numpy as np
+    from oracle import stairs_oracle as so
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    T = so.OracleModel(target, np.float32, keep=True)
+    D = so.OracleModel(draft, np.float32, keep=True) if k > 0 else None
+    t0 = time.time()
+    for m in [T] + ([D] if D is not None else []):          # decode the bf16 weights once (data loading)
+        m.tok_emb(), m.lm_head(), m.final_norm()
+        for l in range(m.n_layers):
+            for name in m.inp.layers[l]:
+                m.layer(l, name)
+    t_load = time.time() - t0
+    st = so.CachedStairs(T, D, prompt[:sample_P], sample_P + sample_G + k + 2)
+    t1 = time.time()
+    gen = st.run(sample_G, k)
+    dt = time.time() - t1
+    log(f"[cpu_baseline] weights decoded in {t_load:.1f}s, prefill {t1 - t0 - t_load:.1f}s, "
+        f"{sample_G} tokens in {dt:.2f}s over {len(gen.iterations)} iterations")
+    return {"value": sample_G / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"same model pair and k={k}; first {sample_P} prompt tokens, {sample_G} generated tokens, "
+                      f"decode phase only (after the oracle's own cached prefill); numpy float32",
+            "iterations": len(gen.iterations), "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg4_7b")
+    ap.add_argument("--k", type=int, default=4, help="draft length (stair rows = k+1)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the verify-vs-k sweep and the per-kernel table")
+    ap.add_argument("--cpu-sample", default="64,8", help="prompt tokens, generated tokens of the CPU sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    import paper_2407_19947_amd as pkg
+    import synth_inputs as si
+
+    w = si.WORKLOADS[args.workload]
+    k, P, G = args.k, w["P"], w["G"]
+    t0 = time.time()
+    target, draft = si.make_pair(w, threads=min(16, os.cpu_count() or 8))
+    prompt = si.make_prompt(w)
+    log(f"[bench] {args.workload}: weights drawn in {time.time() - t0:.1f}s "
+        f"(target {target.n_params() / 1e9:.2f}B, draft {draft.n_params() / 1e9:.2f}B params)")
+    k_max = 16
+    t0 = time.time()
+    eng = pkg.Stairs(target, draft, k_max=k_max, max_seq=P + G + k_max + 8)
+    log(f"[bench] context built in {time.time() - t0:.1f}s")
+
+    decode_s, prefill_ms, stats_last, toks0 = [], [], None, None
+    for step in range(args.warmup + args.steps):
+        eng.prefill(prompt)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        toks, st = eng.decode(G, k)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t1
+        if toks0 is None:
+            toks0 = toks.copy()
+        assert np.array_equal(toks, toks0), "generation is not reproducible"
+        if step >= args.warmup:
+            decode_s.append(dt)
+            stats_last = st
+        log(f"[bench] step {step}: decode {dt * 1e3:.1f} ms ({G / dt:.1f} tok/s), iterations {st.iterations}, "
+            f"accepted {st.accepted}, draft {st.ms_draft:.1f} ms, verify {st.ms_verify:.1f} ms")
+    total = sum(decode_s)
+    value = G * len(decode_s) / total
+    # prefill, once, timed through generate()
+    _, stg = eng.generate(prompt, 1, 0)
+    prefill_ms = stg.ms_prefill
+
+    # plain greedy on the same GPU (the paper's "original" comparator), one step
+    eng.prefill(prompt)
+    t1 = time.perf_counter()
+    toks_plain, st_plain = eng.decode(G, 0)
+    plain_s = time.perf_counter() - t1
+    assert np.array_equal(toks_plain, toks0), "stairs output differs from plain greedy"
+
+    # ---- roofline of the dominant kernel: gate/up projection GEMM at M = k+1 rows ----------
+    M = k + 1
+    reps = 4 * target.n_layers
+    ms_gu, bytes_gu = eng.time_kernel(0, M, 0, reps)
+    achieved = bytes_gu / (ms_gu * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "k_gemm_bf16<CT=1,NT=2,ROLE=gate/up>", "achieved": achieved,
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                "traffic": measured_traffic(), "bytes_per_launch": bytes_gu, "ms_per_launch": ms_gu,
+                "launches_timed": reps}
+    copy_bytes = 1 << 30
+    ms_copy = pkg.stairs_copy_probe(copy_bytes, 4)
+    extras = {"copy_probe_GBps": 2 * copy_bytes / (ms_copy * 1e-3) / 1e9}
+
+    if not args.no_sweep:
+        names = {0: "gemm_gate_up", 1: "gemm_qkv", 2: "gemm_wo", 3: "gemm_down", 4: "gemm_lm_head", 5: "attention"}
+        ctx_mid = P + G // 2
+        per_kernel = {}
+        for which, name in names.items():
+            ms, by = eng.time_kernel(which, M, ctx_mid, 2 * target.n_layers)
+            per_kernel[name] = {"ms": ms, "GB/s": by / (ms * 1e-3) / 1e9}
+        extras["per_kernel_at_M"] = per_kernel
+        sweep = {}
+        for kk in range(0, k_max + 1):
+            ms, by = eng.time_kernel(6, kk + 1, ctx_mid, 3)
+            sweep[str(kk)] = {"ms": ms, "GB/s": by / (ms * 1e-3) / 1e9, "frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        extras["verify_vs_k"] = sweep
+        ms, by = eng.time_kernel(7, 1, ctx_mid, 8)
+        extras["draft_step"] = {"ms": ms, "GB/s": by / (ms * 1e-3) / 1e9, "frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    eng.close()
+
+    out = {
+        "metric": "generated tokens/sec (stairs greedy, 7B-class target)" if "7b" in args.workload
+                  else "generated tokens/sec (stairs greedy)",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": len(decode_s), "warmup": args.warmup,
+        "ms_per_step": 1e3 * total / len(decode_s), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "prompt_len": P, "generate": G, "k": k, "stair_rows": k + 1,
+                   "target": w["target"], "draft": w["draft"], "timed_region": "decode phase (prefill excluded)"},
+        "iterations_per_step": stats_last.iterations, "mean_tokens_per_iteration": G / stats_last.iterations,
+        "accept_hist": list(stats_last.accept_hist)[:k + 1],
+        "ms_draft_per_step": stats_last.ms_draft, "ms_verify_per_step": stats_last.ms_verify,
+        "prefill_ms": prefill_ms,
+        "plain_greedy_tokens_per_s": G / plain_s,
+        "time_reduction_vs_plain_greedy_pct": 100.0 * (1.0 - (total / len(decode_s)) / plain_s),
+        "paper_context": "paper reports 9.58-17.24 % inference-time reduction (T5-3B / T5-large + T5-small, MacBook Pro M2 32 GB)",
+        "roofline": roofline,
+    }
+    out.update(extras)
+    if not args.no_cpu_baseline:
+        sp, sg = (int(x) for x in args.cpu_sample.split(","))
+        out["cpu_baseline"] = cpu_baseline(w, target, draft, prompt, k, min(sp, P), sg)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -136,6 +136,12 @@ int stairs_verify_tokens(stairs_ctx *ctx, const int32_t *draft, int32_t k, int32
 int stairs_generate(stairs_ctx *ctx, const int32_t *prompt, int32_t P, int32_t G, int32_t k,
                     int32_t *tokens_out, stairs_stats *stats);
 
+/* The loop of stairs_generate without the prefill: continue the current sequence (after
+ * stairs_prefill, or after an earlier stairs_decode) by exactly G tokens.  stats->ms_prefill
+ * is 0.  Requires L + G + k + 1 <= max_seq.  Errors: EINVAL, ESTATE (no prefill, pending
+ * proposal, k > 0 without a draft model), ECAPACITY. */
+int stairs_decode(stairs_ctx *ctx, int32_t G, int32_t k, int32_t *tokens_out, stairs_stats *stats);
+
 /* Copy the current sequence (prompt + generated) into out[0..min(cap, len)); *len = length. */
 int stairs_get_tokens(stairs_ctx *ctx, int32_t *out, int32_t cap, int32_t *len);
 
@@ -151,12 +157,21 @@ int stairs_gemm_host(int32_t dtype, const void *W, const float *X, float *Y, int
  * through the layers so that the weights come from HBM, bracketed by HIP events on the
  * context's stream.  which: 0 = gate/up projection GEMM (the largest), 1 = QKV GEMM,
  * 2 = attention output GEMM, 3 = down projection GEMM, 4 = unembedding GEMM,
- * 5 = KV-cache attention at context length ctx_len.  *ms_per_launch: mean duration;
- * *bytes_per_launch: algorithmic bytes (matrix bytes, or K and V bytes of ctx_len positions).
- * Does not disturb the sequence state, but overwrites workspaces: do not call between
- * draft_propose and stairs_verify. */
+ * 5 = KV-cache attention at context length ctx_len, 6 = one whole target forward of M rows
+ * ending at position ctx_len-1 with all rows' logits (a stair verification without the
+ * validation step), 7 = one whole draft forward of M rows with the last row's logits.
+ * *ms_per_launch: mean duration; *bytes_per_launch: algorithmic bytes (matrix bytes; K and V
+ * bytes of ctx_len positions; for 6/7 all matrices of the model plus its K and V bytes).
+ * 0..5 do not disturb the sequence state but overwrite workspaces (do not call between
+ * draft_propose and stairs_verify); 6 and 7 also overwrite the cache rows of the M positions
+ * they run at: call stairs_prefill before generating again. */
 int stairs_time_kernel(stairs_ctx *ctx, int32_t which, int32_t M, int32_t ctx_len, int32_t reps,
                        float *ms_per_launch, double *bytes_per_launch);
+
+/* Launch a plain copy kernel (dst[i] = src[i], `bytes` read + `bytes` written, library-owned
+ * buffers) reps+1 times; the reference point that scales a profiler's HBM traffic counters.
+ * bytes: multiple of 16.  *ms_per_launch (optional): mean duration of the last reps launches. */
+int stairs_copy_probe(int64_t bytes, int32_t reps, float *ms_per_launch, void *hip_stream);
 
 #ifdef __cplusplus
 }

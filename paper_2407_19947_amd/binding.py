@@ -17,8 +17,8 @@ DTYPE_FP32, DTYPE_BF16 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "stairs_strerror", "stairs_last_error", "stairs_init", "stairs_free", "stairs_prefill",
-    "draft_propose", "stairs_verify", "stairs_verify_tokens", "stairs_generate",
-    "stairs_get_tokens", "stairs_gemm_host", "stairs_time_kernel",
+    "draft_propose", "stairs_verify", "stairs_verify_tokens", "stairs_generate", "stairs_decode",
+    "stairs_get_tokens", "stairs_gemm_host", "stairs_time_kernel", "stairs_copy_probe",
 ]
 
 
@@ -93,9 +93,11 @@ def lib() -> C.CDLL:
     L.stairs_verify.argtypes = [vp, i32, i32p, i32p, vp]
     L.stairs_verify_tokens.argtypes = [vp, i32p, i32, i32p, i32p, vp]
     L.stairs_generate.argtypes = [vp, i32p, i32, i32, i32, i32p, C.POINTER(StairsStats)]
+    L.stairs_decode.argtypes = [vp, i32, i32, i32p, C.POINTER(StairsStats)]
     L.stairs_get_tokens.argtypes = [vp, i32p, i32, i32p]
     L.stairs_gemm_host.argtypes = [i32, vp, f32p, f32p, i32, i32, i32, vp]
     L.stairs_time_kernel.argtypes = [vp, i32, i32, i32, i32, f32p, C.POINTER(C.c_double)]
+    L.stairs_copy_probe.argtypes = [C.c_int64, i32, f32p, vp]
     for name in EXPORTED_SYMBOLS:
         if name not in ("stairs_strerror", "stairs_last_error", "stairs_free"):
             getattr(L, name).restype = C.c_int
@@ -224,6 +226,13 @@ def stairs_generate(ctx, prompt: Sequence[int], G: int, k: int):
     return out[:G], st
 
 
+def stairs_decode(ctx, G: int, k: int):
+    out = np.zeros(max(G, 1), np.int32)
+    st = StairsStats()
+    _check(lib().stairs_decode(ctx, G, k, _ptr(out, C.c_int32), C.byref(st)), "stairs_decode", ctx)
+    return out[:G], st
+
+
 def stairs_get_tokens(ctx, cap: int = 1 << 20) -> np.ndarray:
     n = C.c_int32(0)
     _check(lib().stairs_get_tokens(ctx, None, 0, C.byref(n)), "stairs_get_tokens", ctx)
@@ -248,6 +257,12 @@ def stairs_time_kernel(ctx, which: int, M: int, ctx_len: int, reps: int):
     ms, by = C.c_float(0), C.c_double(0)
     _check(lib().stairs_time_kernel(ctx, which, M, ctx_len, reps, C.byref(ms), C.byref(by)), "stairs_time_kernel", ctx)
     return ms.value, by.value
+
+
+def stairs_copy_probe(nbytes: int, reps: int = 4, stream: Optional[int] = None) -> float:
+    ms = C.c_float(0)
+    _check(lib().stairs_copy_probe(nbytes, reps, C.byref(ms), stream), "stairs_copy_probe")
+    return ms.value
 
 
 class Stairs:
@@ -288,6 +303,9 @@ class Stairs:
 
     def generate(self, prompt, G, k):
         return stairs_generate(self.ctx, prompt, G, k)
+
+    def decode(self, G, k):
+        return stairs_decode(self.ctx, G, k)
 
     def tokens(self):
         return stairs_get_tokens(self.ctx)

@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <new>
@@ -64,6 +65,7 @@ struct stairs_ctx {
   bool prefilled = false;
   int pending_k = -1;          // draft length of the outstanding proposal, -1 = none
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  bool sync_launches = false;  // env STAIRS_SYNC_LAUNCHES=1: wait after every kernel (for counter-collecting profilers)
   std::string err;
 };
 
@@ -233,34 +235,52 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int pos_host, int M, int logits
   const int b = m->bf16 ? 1 : 0;
   const int sn = ssq_groups(d);
   hipStream_t st = c->st;
+#define SYNCPOINT()                                             \
+  do {                                                          \
+    if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));  \
+  } while (0)
   launch_embed(m->tok_emb, b, c->tokens, pos, M, d, c->x, c->ssq, st);
+  SYNCPOINT();
   launch_rope_table(pos, M, m->hd, g.rope_theta, c->rope_cs, st);
+  SYNCPOINT();
   const int nchunk = (std::max(pos_host, 0) + M + kAttnChunk - 1) / kAttnChunk;
   for (int l = 0; l < g.n_layers; ++l) {
     const Layer& ly = m->layers[l];
     RowNorm n1{ly.attn_norm, c->ssq, sn, g.rms_eps};
-    int S = launch_gemm_partial(b, ly.wqkv, 3 * d, d, c->x, d, M, n1, c->partial, st);
+    int S = launch_gemm_partial(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, n1, c->partial, st);
+    SYNCPOINT();
     launch_fin_qkv_rope(c->partial, S, M, d, H, c->rope_cs, pos, c->q_rot, m->Kc + l * m->kv_layer_bytes,
                         m->Vc + l * m->kv_layer_bytes, m->cap, b, st);
+    SYNCPOINT();
     launch_attention(c->q_rot, m->Kc + l * m->kv_layer_bytes, m->Vc + l * m->kv_layer_bytes, b, m->cap, d, H, M, pos,
                      nchunk, c->nchunk_cap, c->part_o, c->part_ml, c->attn_out, st);
+    SYNCPOINT();
     RowNorm none{nullptr, nullptr, 0, 0.f};
-    S = launch_gemm_partial(b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, st);
+    S = launch_gemm_partial(kRoleWo, b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, st);
+    SYNCPOINT();
     launch_fin_resid(c->partial, S, M, d, c->x, c->ssq, st);
+    SYNCPOINT();
     RowNorm n2{ly.ffn_norm, c->ssq, sn, g.rms_eps};
-    S = launch_gemm_partial(b, ly.wgu, 2 * f, d, c->x, d, M, n2, c->partial, st);
+    S = launch_gemm_partial(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, n2, c->partial, st);
+    SYNCPOINT();
     launch_fin_swiglu(c->partial, S, M, f, c->h, st);
-    S = launch_gemm_partial(b, ly.wdown, d, f, c->h, f, M, none, c->partial, st);
+    SYNCPOINT();
+    S = launch_gemm_partial(kRoleDown, b, ly.wdown, d, f, c->h, f, M, none, c->partial, st);
+    SYNCPOINT();
     launch_fin_resid(c->partial, S, M, d, c->x, c->ssq, st);
+    SYNCPOINT();
   }
   if (logits_rows > 0) {
     const int r0 = M - logits_rows;
     RowNorm nf{m->final_norm, c->ssq + r0 * sn, sn, g.rms_eps};
-    int S = launch_gemm_partial(b, m->lm_head, V, d, c->x + (size_t)r0 * d, d, logits_rows, nf, c->partial, st);
+    int S = launch_gemm_partial(kRoleHead, b, m->lm_head, V, d, c->x + (size_t)r0 * d, d, logits_rows, nf, c->partial, st);
+    SYNCPOINT();
     launch_fin_plain(c->partial, S, logits_rows, V, c->logits, V, st);
+    SYNCPOINT();
   }
   HIPCHK(c, hipGetLastError());
   return STAIRS_OK;
+#undef SYNCPOINT
 }
 
 PosRef abs_pos(const stairs_ctx* c, int p) { return PosRef{c->state + 2, p}; }   // state[2] == 0
@@ -377,6 +397,10 @@ int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_wei
   c->st = static_cast<hipStream_t>(hip_stream);
   c->k_max = k_max;
   c->have_draft = have_draft;
+  {
+    const char* e = getenv("STAIRS_SYNC_LAUNCHES");
+    c->sync_launches = e && e[0] == '1';
+  }
   int rc = STAIRS_OK;
   auto bail = [&](int code) {
     if (code == STAIRS_EHIP || code == STAIRS_ENOMEM) fprintf(stderr, "stairs_init: %s\n", c->err.c_str());
@@ -500,23 +524,20 @@ int stairs_verify_tokens(stairs_ctx* c, const int32_t* draft, int32_t k, int32_t
   return verify_common(c, k, target_tok_out, n_accepted_out, logits_out);
 }
 
-int stairs_generate(stairs_ctx* c, const int32_t* prompt, int32_t P, int32_t G, int32_t k, int32_t* tokens_out,
-                    stairs_stats* stats) {
+int stairs_decode(stairs_ctx* c, int32_t G, int32_t k, int32_t* tokens_out, stairs_stats* stats) {
   if (!c) return STAIRS_EINVAL;
+  if (!c->prefilled) return fail(c, STAIRS_ESTATE, "stairs_decode before stairs_prefill");
+  if (c->pending_k >= 0) return fail(c, STAIRS_ESTATE, "a proposal is pending");
   if (G < 0 || (G > 0 && !tokens_out)) return fail(c, STAIRS_EINVAL, "G < 0 or tokens_out is NULL");
   if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
   if (k > 0 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
-  if (!prompt || P < 1) return fail(c, STAIRS_EINVAL, "prompt is NULL or empty");
-  if (!capacity_ok(c, P + G + k + 1)) return fail(c, STAIRS_ECAPACITY, "P + G + k + 1 exceeds max_seq");
+  if (!capacity_ok(c, c->L + G + k + 1)) return fail(c, STAIRS_ECAPACITY, "L + G + k + 1 exceeds max_seq");
   stairs_stats s;
   memset(&s, 0, sizeof(s));
-  HIPCHK(c, hipEventRecord(c->ev[0], c->st));
-  int rc = stairs_prefill(c, prompt, P);
-  if (rc) return rc;
+  const int L0 = c->L;
+  int rc;
   HIPCHK(c, hipEventRecord(c->ev[1], c->st));
-  HIPCHK(c, hipEventSynchronize(c->ev[1]));
-  HIPCHK(c, hipEventElapsedTime(&s.ms_prefill, c->ev[0], c->ev[1]));
-  while (c->L - P < G) {
+  while (c->L - L0 < G) {
     HIPCHK(c, hipEventRecord(c->ev[0], c->st));
     if (k > 0 && (rc = do_propose(c, k))) return rc;
     HIPCHK(c, hipEventRecord(c->ev[2], c->st));
@@ -537,7 +558,38 @@ int stairs_generate(stairs_ctx* c, const int32_t* prompt, int32_t P, int32_t G, 
   HIPCHK(c, hipEventSynchronize(c->ev[0]));
   HIPCHK(c, hipEventElapsedTime(&s.ms_decode, c->ev[1], c->ev[0]));
   s.tokens = G;
-  if (G > 0 && (rc = copy_out(c, tokens_out, c->tokens + P, (size_t)G * sizeof(int)))) return rc;
+  // the last iteration may have produced more than asked for: the sequence is cut back to
+  // L0 + G (the caches hold a prefix of what they held, which stays valid)
+  if (c->L > L0 + G) {
+    c->L = L0 + G;
+    c->T.valid = std::min(c->T.valid, c->L - 1);
+    if (c->have_draft) c->D.valid = std::min(c->D.valid, c->L - 1);
+    HIPCHK(c, hipMemcpyAsync(c->state, &c->L, sizeof(int), hipMemcpyHostToDevice, c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+  }
+  if (G > 0 && (rc = copy_out(c, tokens_out, c->tokens + L0, (size_t)G * sizeof(int)))) return rc;
+  if (stats) *stats = s;
+  return STAIRS_OK;
+}
+
+int stairs_generate(stairs_ctx* c, const int32_t* prompt, int32_t P, int32_t G, int32_t k, int32_t* tokens_out,
+                    stairs_stats* stats) {
+  if (!c) return STAIRS_EINVAL;
+  if (G < 0 || (G > 0 && !tokens_out)) return fail(c, STAIRS_EINVAL, "G < 0 or tokens_out is NULL");
+  if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
+  if (k > 0 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
+  if (!prompt || P < 1) return fail(c, STAIRS_EINVAL, "prompt is NULL or empty");
+  if (!capacity_ok(c, P + G + k + 1)) return fail(c, STAIRS_ECAPACITY, "P + G + k + 1 exceeds max_seq");
+  float ms_prefill = 0.f;
+  HIPCHK(c, hipEventRecord(c->ev[0], c->st));
+  int rc = stairs_prefill(c, prompt, P);
+  if (rc) return rc;
+  HIPCHK(c, hipEventRecord(c->ev[1], c->st));
+  HIPCHK(c, hipEventSynchronize(c->ev[1]));
+  HIPCHK(c, hipEventElapsedTime(&ms_prefill, c->ev[0], c->ev[1]));
+  stairs_stats s;
+  if ((rc = stairs_decode(c, G, k, tokens_out, &s))) return rc;
+  s.ms_prefill = ms_prefill;
   if (stats) *stats = s;
   return STAIRS_OK;
 }
@@ -577,7 +629,7 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
     ok(hipMemcpyAsync(dX, X, (size_t)M * K * 4, hipMemcpyHostToDevice, st));
     if (b) launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(dW), reinterpret_cast<uint4*>(dWs), N, K, st);
     RowNorm none{nullptr, nullptr, 0, 0.f};
-    const int S2 = launch_gemm_partial(b, b ? dWs : dW, N, K, dX, K, M, none, dP, st);
+    const int S2 = launch_gemm_partial(kRoleHead, b, b ? dWs : dW, N, K, dX, K, M, none, dP, st);
     launch_fin_plain(dP, S2, M, N, dY, N, st);
     ok(hipGetLastError());
     ok(hipMemcpyAsync(Y, dY, (size_t)M * N * 4, hipMemcpyDeviceToHost, st));
@@ -587,30 +639,72 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
   return rc;
 }
 
+int stairs_copy_probe(int64_t bytes, int32_t reps, float* ms_per_launch, void* hip_stream) {
+  if (bytes < 16 || bytes % 16 || reps < 1) return STAIRS_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char *src = nullptr, *dst = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = STAIRS_OK;
+  if (hipMalloc((void**)&src, bytes) != hipSuccess || hipMalloc((void**)&dst, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    rc = STAIRS_ENOMEM;
+  } else if (hipMemsetAsync(src, 1, bytes, st) != hipSuccess || hipEventCreate(&e0) != hipSuccess ||
+             hipEventCreate(&e1) != hipSuccess) {
+    rc = STAIRS_EHIP;
+  } else {
+    launch_copy_probe(src, dst, bytes, st);   // warm-up
+    (void)hipEventRecord(e0, st);
+    for (int r = 0; r < reps; ++r) launch_copy_probe(src, dst, bytes, st);
+    (void)hipEventRecord(e1, st);
+    float ms = 0.f;
+    if (hipGetLastError() != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+        hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+      rc = STAIRS_EHIP;
+    else if (ms_per_launch)
+      *ms_per_launch = ms / reps;
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(src);
+  (void)hipFree(dst);
+  return rc;
+}
+
 int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len, int32_t reps, float* ms_per_launch,
                        double* bytes_per_launch) {
   if (!c) return STAIRS_EINVAL;
-  if (which < 0 || which > 5 || M < 1 || M > kMaxRows || reps < 1 || !ms_per_launch)
+  if (which < 0 || which > 7 || M < 1 || M > kMaxRows || reps < 1 || !ms_per_launch)
     return fail(c, STAIRS_EINVAL, "bad argument to stairs_time_kernel");
   if (c->pending_k >= 0) return fail(c, STAIRS_ESTATE, "a proposal is pending");
-  Model* m = &c->T;
+  if (which == 7 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
+  Model* m = which == 7 ? &c->D : &c->T;
   const stairs_model_cfg& g = m->cfg;
   const int d = g.d_model, f = g.d_ffn, V = g.vocab, b = m->bf16 ? 1 : 0;
   const size_t esz = m->esz();
-  if (which == 5 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");
+  if (which >= 5 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");
   RowNorm none{nullptr, nullptr, 0, 0.f};
   double bytes = 0;
   for (int pass = 0; pass < 2; ++pass) {          // pass 0 = warm-up of one launch per layer
-    const int n = pass ? reps : g.n_layers;
+    const int n = pass ? reps : (which >= 6 ? 1 : g.n_layers);
     if (pass) HIPCHK(c, hipEventRecord(c->ev[0], c->st));
     for (int r = 0; r < n; ++r) {
       const Layer& ly = m->layers[r % g.n_layers];
       switch (which) {
-        case 0: launch_gemm_partial(b, ly.wgu, 2 * f, d, c->x, d, M, none, c->partial, c->st); bytes = 2.0 * f * d * esz; break;
-        case 1: launch_gemm_partial(b, ly.wqkv, 3 * d, d, c->x, d, M, none, c->partial, c->st); bytes = 3.0 * d * d * esz; break;
-        case 2: launch_gemm_partial(b, ly.wo, d, d, c->x, d, M, none, c->partial, c->st); bytes = 1.0 * d * d * esz; break;
-        case 3: launch_gemm_partial(b, ly.wdown, d, f, c->h, f, M, none, c->partial, c->st); bytes = 1.0 * d * f * esz; break;
-        case 4: launch_gemm_partial(b, m->lm_head, V, d, c->x, d, M, none, c->partial, c->st); bytes = 1.0 * V * d * esz; break;
+        case 0: launch_gemm_partial(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, none, c->partial, c->st); bytes = 2.0 * f * d * esz; break;
+        case 1: launch_gemm_partial(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, none, c->partial, c->st); bytes = 3.0 * d * d * esz; break;
+        case 2: launch_gemm_partial(kRoleWo, b, ly.wo, d, d, c->x, d, M, none, c->partial, c->st); bytes = 1.0 * d * d * esz; break;
+        case 3: launch_gemm_partial(kRoleDown, b, ly.wdown, d, f, c->h, f, M, none, c->partial, c->st); bytes = 1.0 * d * f * esz; break;
+        case 4: launch_gemm_partial(kRoleHead, b, m->lm_head, V, d, c->x, d, M, none, c->partial, c->st); bytes = 1.0 * V * d * esz; break;
+        case 6:
+        case 7: {
+          // a whole forward of M rows ending at position ctx_len-1 (all rows' logits for the
+          // target, last row's for the draft); it overwrites those rows of the cache
+          int rc = forward(c, m, abs_pos(c, ctx_len - M), ctx_len - M, M, which == 6 ? M : 1);
+          if (rc) return rc;
+          const double np_ = (double)g.n_layers * (4.0 * d * d + 3.0 * d * f) + (double)V * d;
+          bytes = np_ * esz + 2.0 * g.n_layers * (double)ctx_len * d * esz;
+          break;
+        }
         default: {
           const size_t off = (size_t)(r % g.n_layers) * m->kv_layer_bytes;
           launch_attention(c->q_rot, m->Kc + off, m->Vc + off, b, m->cap, d, g.n_heads, M, abs_pos(c, ctx_len - M),
@@ -618,6 +712,7 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
           bytes = 2.0 * ctx_len * d * esz;
         }
       }
+      if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(c->st));
     }
     if (pass) HIPCHK(c, hipEventRecord(c->ev[1], c->st));
     HIPCHK(c, hipGetLastError());

@@ -41,10 +41,12 @@ inline int gemm_slices(int K, int dtype_bf16) {
 // is 1 KiB, stored at index nt*(K/32)+kt; inside it lane l = r + 16*g holds W[nt*16+r][kt*32+g*8..+8].
 void launch_swizzle_bf16(const uint16_t* W, uint4* Wsw, int N, int K, hipStream_t st);
 
+enum { kRoleQKV = 0, kRoleWo = 1, kRoleGateUp = 2, kRoleDown = 3, kRoleHead = 4 };   // which projection a GEMM launch is
+
 // ---- skinny GEMM: partial[s][m][n] = sum over k-slice s of W[n][k] * xn[m][k] -----------
 // bf16: W is swizzled, split-K slices of 512 k; fp32: W row-major, one slice.
 // partial holds gemm_slices() * M * N floats.  Returns the number of slices.
-int launch_gemm_partial(int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M,
+int launch_gemm_partial(int role, int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M,
                         RowNorm nrm, float* partial, hipStream_t st);
 
 // ---- GEMM epilogues (sum the slices in index order, then ...) ---------------------------
@@ -74,6 +76,9 @@ void launch_argmax(const float* logits, int ld, int V, int nrows, int* out, PosR
 // stairs validation on device: state[0] = L (sequence length). n = longest run with
 // tokens[L+i] == tgt[i]; tokens[L+n] = tgt[n]; state[0] = L+n+1; state[1] = n.
 void launch_accept(int* tokens, const int* tgt, int k, int* state, hipStream_t st);
+
+// dst[0..bytes) = src[0..bytes), bytes a multiple of 16: reads `bytes` and writes `bytes` of HBM
+void launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
 
 // opt in to large dynamic LDS for the kernels that need it (once per process/device)
 hipError_t configure_kernels();

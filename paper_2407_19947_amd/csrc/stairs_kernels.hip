@@ -83,7 +83,9 @@ void launch_swizzle_bf16(const uint16_t* W, uint4* Wsw, int N, int K, hipStream_
 //   The weight tile is the MFMA A operand and is loaded straight from HBM in operand order
 //   (1 KiB per wave-load, fully coalesced); the X rows are the B operand.
 // ---------------------------------------------------------------------------------------
-template <int CT, int NT>
+// ROLE only gives each projection its own kernel symbol, so that a profiler's per-kernel
+// statistics separate the five weight shapes of a layer; the code is the same.
+template <int CT, int NT, int ROLE>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw, int KT, int NTILES,
                                                    const float* __restrict__ X, int ldx, int M,
                                                    RowNorm nrm, int K, float* __restrict__ partial, int N) {
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ W, i
   }
 }
 
-int launch_gemm_partial(int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M,
+int launch_gemm_partial(int role, int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M,
                         RowNorm nrm, float* partial, hipStream_t st) {
   if (!dtype_bf16) {
     dim3 grid((N + 3) / 4), block(256);
@@ -245,12 +247,21 @@ int launch_gemm_partial(int dtype_bf16, const void* W, int N, int K, const float
   dim3 grid((NTILES + 4 * NT - 1) / (4 * NT), S), block(256);
   const int CT = (M <= 16) ? 1 : 2;
   const size_t lds = (size_t)16 * CT * 2 * 64 * sizeof(uint4);
-#define STAIRS_GEMM(ct, nt) \
-  hipLaunchKernelGGL((k_gemm_bf16<ct, nt>), grid, block, lds, st, Wsw, KT, NTILES, X, ldx, M, nrm, K, partial, N)
-  if (CT == 1 && NT == 1) STAIRS_GEMM(1, 1);
-  else if (CT == 1) STAIRS_GEMM(1, 2);
-  else if (NT == 1) STAIRS_GEMM(2, 1);
-  else STAIRS_GEMM(2, 2);
+#define STAIRS_GEMM(ct, nt, role) \
+  hipLaunchKernelGGL((k_gemm_bf16<ct, nt, role>), grid, block, lds, st, Wsw, KT, NTILES, X, ldx, M, nrm, K, partial, N)
+#define STAIRS_GEMM_ROLE(role)             \
+  if (CT == 1 && NT == 1) STAIRS_GEMM(1, 1, role); \
+  else if (CT == 1) STAIRS_GEMM(1, 2, role);       \
+  else if (NT == 1) STAIRS_GEMM(2, 1, role);       \
+  else STAIRS_GEMM(2, 2, role)
+  switch (role) {
+    case kRoleQKV: STAIRS_GEMM_ROLE(kRoleQKV); break;
+    case kRoleWo: STAIRS_GEMM_ROLE(kRoleWo); break;
+    case kRoleGateUp: STAIRS_GEMM_ROLE(kRoleGateUp); break;
+    case kRoleDown: STAIRS_GEMM_ROLE(kRoleDown); break;
+    default: STAIRS_GEMM_ROLE(kRoleHead); break;
+  }
+#undef STAIRS_GEMM_ROLE
 #undef STAIRS_GEMM
   return S;
 }
@@ -638,6 +649,18 @@ __global__ void k_accept(int* __restrict__ tokens, const int* __restrict__ tgt, 
 
 void launch_accept(int* tokens, const int* tgt, int k, int* state, hipStream_t st) {
   hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, st, tokens, tgt, k, state);
+}
+
+// plain streaming copy, the calibration kernel for HBM traffic counters
+__global__ __launch_bounds__(256) void k_copy_probe(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
+void launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st) {
+  const size_t n = bytes / 16;
+  hipLaunchKernelGGL(k_copy_probe, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                     static_cast<const uint4*>(src), static_cast<uint4*>(dst), n);
 }
 
 hipError_t configure_kernels() { return hipSuccess; }
