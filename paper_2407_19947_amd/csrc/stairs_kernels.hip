@@ -30,6 +30,10 @@ __device__ __forceinline__ float load_kv(const float* p) { return *p; }
 __device__ __forceinline__ float load_kv(const uint16_t* p) { return bf16_bits_to_float(*p); }
 __device__ __forceinline__ void store_kv(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_kv(uint16_t* p, float v) { *p = (uint16_t)bf16_bits_rne(v); }
+// keys/values of bf16 models are cached as IEEE half: same bytes as bf16, 8x smaller rounding step
+// (bf16 storage alone moves 1B-class logits by 1.7e-2); saturates at the half range
+__device__ __forceinline__ float load_kv(const _Float16* p) { return (float)*p; }
+__device__ __forceinline__ void store_kv(_Float16* p, float v) { *p = (_Float16)fminf(fmaxf(v, -65504.f), 65504.f); }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -373,8 +377,8 @@ void launch_fin_qkv_rope(const float* partial, int S, int M, int d, int H, const
   const int per_row = 3 * H * (d / H / 2);
   dim3 grid((per_row + 255) / 256, M), block(256);
   if (kv_bf16)
-    hipLaunchKernelGGL(k_fin_qkv_rope<uint16_t>, grid, block, 0, st, partial, S, M, d, H, rope_cs, pos, q_rot,
-                       static_cast<uint16_t*>(Kc), static_cast<uint16_t*>(Vc), cap);
+    hipLaunchKernelGGL(k_fin_qkv_rope<_Float16>, grid, block, 0, st, partial, S, M, d, H, rope_cs, pos, q_rot,
+                       static_cast<_Float16*>(Kc), static_cast<_Float16*>(Vc), cap);
   else
     hipLaunchKernelGGL(k_fin_qkv_rope<float>, grid, block, 0, st, partial, S, M, d, H, rope_cs, pos, q_rot,
                        static_cast<float*>(Kc), static_cast<float*>(Vc), cap);
@@ -587,8 +591,8 @@ void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv
                       hipStream_t st) {
   const int hd = d / H;
   if (kv_bf16) {
-    if (hd == 128) attn_dispatch<uint16_t, 128>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
-    else attn_dispatch<uint16_t, 64>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
+    if (hd == 128) attn_dispatch<_Float16, 128>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
+    else attn_dispatch<_Float16, 64>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
   } else {
     if (hd == 128) attn_dispatch<float, 128>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
     else attn_dispatch<float, 64>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
