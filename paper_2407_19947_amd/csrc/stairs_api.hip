@@ -43,6 +43,9 @@ struct Model {
 
 }  // namespace
 
+constexpr int kGemmCounters = 2048;   // >= column groups of the widest GEMM (N / 64)
+constexpr int kCounters = kGemmCounters + 256;   // + one per attention head
+
 struct stairs_ctx {
   hipStream_t st = nullptr;
   int k_max = 0;
@@ -57,6 +60,7 @@ struct stairs_ctx {
   int nchunk_cap = 0;
   int* tokens = nullptr;       // device copy of the sequence, capacity tok_cap
   int tok_cap = 0;
+  int* counters = nullptr;     // [kCounters] split-K / attention hand-off tickets, zero between launches
   int* tgt_tok = nullptr;      // [kMaxRows]
   int* state = nullptr;        // [0] = L, [1] = n of last iteration, [2] = constant 0
   int* h_pinned = nullptr;     // pinned host: [0..1] state, [2..2+kMaxRows) target tokens
@@ -114,6 +118,9 @@ const char* check_cfg(const stairs_model_cfg* m) {
     if (m->d_model % 4 || m->d_ffn % 4 || m->vocab % 4) return "fp32 models need d_model, d_ffn, vocab multiples of 4";
   }
   if (!(m->rope_theta > 0.f) || !(m->rms_eps >= 0.f)) return "rope_theta must be > 0 and rms_eps >= 0";
+  if (std::max({m->vocab, 3 * m->d_model, 2 * m->d_ffn}) / 64 + 1 > kGemmCounters || m->n_heads > kCounters - kGemmCounters)
+    return "model too wide for the hand-off counters";
+  if (m->max_seq > 60000) return "max_seq above 60000 is not supported (attention merge table lives in LDS)";
   return nullptr;
 }
 
@@ -129,10 +136,13 @@ const char* check_weights(const stairs_model_cfg* m, const stairs_weights* w) {
   return nullptr;
 }
 
+enum { KIND_EMB = 0, KIND_HEAD, KIND_NORM, KIND_QKV, KIND_WO, KIND_GU, KIND_DOWN };
+
 // Upload a matrix made of `nparts` row blocks (each [rows_each, K], host, model dtype) as one
 // [nparts*rows_each, K] GEMM operand; bf16 goes through the operand re-layout kernel.
 int upload_matrix(stairs_ctx* c, bool bf16, const void* const* parts, int nparts, int rows_each, int K, int kind,
                   char* staging, const void** out) {
+  const int interleave_f = (kind == KIND_GU) ? rows_each : 0;   // gate/up tiles alternate (SwiGLU epilogue)
   auto key = std::make_pair(parts[0], kind);
   auto it = c->dedup.find(key);
   if (it != c->dedup.end()) {
@@ -148,7 +158,8 @@ int upload_matrix(stairs_ctx* c, bool bf16, const void* const* parts, int nparts
   for (int p = 0; p < nparts; ++p)
     HIPCHK(c, hipMemcpyAsync(raw + p * part_bytes, parts[p], part_bytes, hipMemcpyHostToDevice, c->st));
   if (bf16) {
-    launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(staging), reinterpret_cast<uint4*>(dst), nparts * rows_each, K, c->st);
+    launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(staging), reinterpret_cast<uint4*>(dst), nparts * rows_each, K,
+                        interleave_f, c->st);
     HIPCHK(c, hipGetLastError());
   }
   HIPCHK(c, hipStreamSynchronize(c->st));   // staging and the host buffers are reused right away
@@ -174,13 +185,11 @@ int upload_plain(stairs_ctx* c, const void* host, size_t bytes, int kind, const 
   return STAIRS_OK;
 }
 
-enum { KIND_EMB = 0, KIND_HEAD, KIND_NORM, KIND_QKV, KIND_WO, KIND_GU, KIND_DOWN };
-
 int build_model(stairs_ctx* c, Model* m, const stairs_model_cfg* cfg, const stairs_weights* w, char* staging) {
   m->cfg = *cfg;
   m->bf16 = cfg->dtype == STAIRS_DTYPE_BF16;
   m->hd = cfg->d_model / cfg->n_heads;
-  m->cap = cfg->max_seq;
+  m->cap = (cfg->max_seq + 31) / 32 * 32;   // whole 32-position value blocks
   const int d = cfg->d_model, f = cfg->d_ffn, V = cfg->vocab;
   int rc;
   if ((rc = upload_plain(c, w->tok_emb, (size_t)V * d * m->esz(), KIND_EMB, &m->tok_emb))) return rc;
@@ -209,6 +218,9 @@ int build_model(stairs_ctx* c, Model* m, const stairs_model_cfg* cfg, const stai
   m->kv_layer_bytes = (size_t)cfg->n_heads * m->cap * m->hd * m->esz();
   if ((rc = dev_alloc(c, &m->Kc, m->kv_layer_bytes * cfg->n_layers))) return rc;
   if ((rc = dev_alloc(c, &m->Vc, m->kv_layer_bytes * cfg->n_layers))) return rc;
+  // positions that were never written are multiplied by probability 0 in the value product: they must be finite
+  HIPCHK(c, hipMemsetAsync(m->Kc, 0, m->kv_layer_bytes * cfg->n_layers, c->st));
+  HIPCHK(c, hipMemsetAsync(m->Vc, 0, m->kv_layer_bytes * cfg->n_layers, c->st));
   return STAIRS_OK;
 }
 
@@ -233,7 +245,7 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int pos_host, int M, int logits
   const stairs_model_cfg& g = m->cfg;
   const int d = g.d_model, f = g.d_ffn, H = g.n_heads, V = g.vocab;
   const int b = m->bf16 ? 1 : 0;
-  const int sn = ssq_groups(d);
+  const int sn = ssq_groups(d, b);
   hipStream_t st = c->st;
 #define SYNCPOINT()                                             \
   do {                                                          \
@@ -244,38 +256,47 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int pos_host, int M, int logits
   launch_rope_table(pos, M, m->hd, g.rope_theta, c->rope_cs, st);
   SYNCPOINT();
   const int nchunk = (std::max(pos_host, 0) + M + kAttnChunk - 1) / kAttnChunk;
+  const RowNorm none{nullptr, nullptr, 0, 0.f};
   for (int l = 0; l < g.n_layers; ++l) {
     const Layer& ly = m->layers[l];
-    RowNorm n1{ly.attn_norm, c->ssq, sn, g.rms_eps};
-    int S = launch_gemm_partial(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, n1, c->partial, st);
+    char* Kl = m->Kc + l * m->kv_layer_bytes;
+    char* Vl = m->Vc + l * m->kv_layer_bytes;
+    GemmEpi e{};
+    e.counters = c->counters;
+    e.rope_cs = c->rope_cs;
+    e.pos = pos;
+    e.Kc = reinterpret_cast<_Float16*>(Kl);
+    e.Vc = reinterpret_cast<_Float16*>(Vl);
+    e.Kc32 = reinterpret_cast<float*>(Kl);
+    e.Vc32 = reinterpret_cast<float*>(Vl);
+    e.cap = m->cap;
+    e.H = H;
+    e.hd = m->hd;
+    e.ssq_out = c->ssq;
+    e.out = c->q_rot;
+    launch_gemm(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, RowNorm{ly.attn_norm, c->ssq, sn, g.rms_eps}, c->partial, e, st);
     SYNCPOINT();
-    launch_fin_qkv_rope(c->partial, S, M, d, H, c->rope_cs, pos, c->q_rot, m->Kc + l * m->kv_layer_bytes,
-                        m->Vc + l * m->kv_layer_bytes, m->cap, b, st);
+    launch_attention(c->q_rot, Kl, Vl, b, m->cap, d, H, M, pos, nchunk, c->nchunk_cap, c->part_o, c->part_ml,
+                     c->counters + kGemmCounters, c->attn_out, st);
     SYNCPOINT();
-    launch_attention(c->q_rot, m->Kc + l * m->kv_layer_bytes, m->Vc + l * m->kv_layer_bytes, b, m->cap, d, H, M, pos,
-                     nchunk, c->nchunk_cap, c->part_o, c->part_ml, c->attn_out, st);
+    e.out = c->x;
+    launch_gemm(kRoleWo, b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, e, st);
     SYNCPOINT();
-    RowNorm none{nullptr, nullptr, 0, 0.f};
-    S = launch_gemm_partial(kRoleWo, b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, st);
+    e.out = c->h;
+    launch_gemm(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, RowNorm{ly.ffn_norm, c->ssq, sn, g.rms_eps}, c->partial, e, st);
     SYNCPOINT();
-    launch_fin_resid(c->partial, S, M, d, c->x, c->ssq, st);
-    SYNCPOINT();
-    RowNorm n2{ly.ffn_norm, c->ssq, sn, g.rms_eps};
-    S = launch_gemm_partial(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, n2, c->partial, st);
-    SYNCPOINT();
-    launch_fin_swiglu(c->partial, S, M, f, c->h, st);
-    SYNCPOINT();
-    S = launch_gemm_partial(kRoleDown, b, ly.wdown, d, f, c->h, f, M, none, c->partial, st);
-    SYNCPOINT();
-    launch_fin_resid(c->partial, S, M, d, c->x, c->ssq, st);
+    e.out = c->x;
+    launch_gemm(kRoleDown, b, ly.wdown, d, f, c->h, f, M, none, c->partial, e, st);
     SYNCPOINT();
   }
   if (logits_rows > 0) {
     const int r0 = M - logits_rows;
-    RowNorm nf{m->final_norm, c->ssq + r0 * sn, sn, g.rms_eps};
-    int S = launch_gemm_partial(kRoleHead, b, m->lm_head, V, d, c->x + (size_t)r0 * d, d, logits_rows, nf, c->partial, st);
-    SYNCPOINT();
-    launch_fin_plain(c->partial, S, logits_rows, V, c->logits, V, st);
+    GemmEpi e{};
+    e.counters = c->counters;
+    e.out = c->logits;
+    e.hd = m->hd;
+    launch_gemm(kRoleHead, b, m->lm_head, V, d, c->x + (size_t)r0 * d, d, logits_rows,
+                RowNorm{m->final_norm, c->ssq + r0 * sn, sn, g.rms_eps}, c->partial, e, st);
     SYNCPOINT();
   }
   HIPCHK(c, hipGetLastError());
@@ -428,16 +449,17 @@ int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_wei
   if (have_draft) pf = std::max(pf, max_partial_floats(dcfg));
   c->nchunk_cap = (capmax + kAttnChunk - 1) / kAttnChunk;
   c->tok_cap = capmax;
-  if ((rc = dev_alloc(c, &c->x, (size_t)kMaxRows * dmax)) || (rc = dev_alloc(c, &c->ssq, (size_t)kMaxRows * ssq_groups(dmax))) ||
+  if ((rc = dev_alloc(c, &c->x, (size_t)kMaxRows * dmax)) || (rc = dev_alloc(c, &c->ssq, (size_t)kMaxRows * ssq_groups(dmax, 1))) ||
       (rc = dev_alloc(c, &c->q_rot, (size_t)kMaxRows * dmax)) || (rc = dev_alloc(c, &c->attn_out, (size_t)kMaxRows * dmax)) ||
       (rc = dev_alloc(c, &c->h, (size_t)kMaxRows * fmax)) || (rc = dev_alloc(c, &c->logits, (size_t)kMaxRows * tcfg->vocab)) ||
       (rc = dev_alloc(c, &c->partial, pf)) ||
       (rc = dev_alloc(c, &c->part_o, (size_t)kMaxRows * Hmax * c->nchunk_cap * 128)) ||
       (rc = dev_alloc(c, &c->part_ml, (size_t)kMaxRows * Hmax * c->nchunk_cap * 2)) ||
       (rc = dev_alloc(c, &c->rope_cs, (size_t)kMaxRows * 64)) || (rc = dev_alloc(c, &c->tokens, (size_t)c->tok_cap + kMaxRows)) ||
-      (rc = dev_alloc(c, &c->tgt_tok, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->state, 8)))
+      (rc = dev_alloc(c, &c->tgt_tok, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->counters, (size_t)kCounters)) || (rc = dev_alloc(c, &c->state, 8)))
     return bail(rc);
   if (hipMemsetAsync(c->state, 0, 8 * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
+  if (hipMemsetAsync(c->counters, 0, kCounters * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
   if (hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), (2 + kMaxRows) * sizeof(int), hipHostMallocDefault) != hipSuccess) {
     c->h_pinned = nullptr;
     return bail(STAIRS_ENOMEM);
@@ -457,6 +479,7 @@ int stairs_prefill(stairs_ctx* c, const int32_t* prompt, int32_t P) {
   if (!capacity_ok(c, P + c->k_max + 1)) return fail(c, STAIRS_ECAPACITY, "prompt + k_max + 1 exceeds max_seq");
   c->prefilled = false;
   c->pending_k = -1;
+  HIPCHK(c, hipMemsetAsync(c->counters, 0, kCounters * sizeof(int), c->st));
   HIPCHK(c, hipMemcpyAsync(c->tokens, prompt, (size_t)P * sizeof(int), hipMemcpyHostToDevice, c->st));
   const int st3[3] = {P, 0, 0};
   HIPCHK(c, hipMemcpyAsync(c->state, st3, sizeof(st3), hipMemcpyHostToDevice, c->st));
@@ -608,12 +631,13 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
   if (!W || !X || !Y || M < 1 || M > kMaxRows || N < 1 || K < 1) return STAIRS_EINVAL;
   const bool b = dtype == STAIRS_DTYPE_BF16;
   if (!b && dtype != STAIRS_DTYPE_FP32) return STAIRS_EINVAL;
-  if (b ? (K % 256 || N % 16) : (K % 4 || N % 4)) return STAIRS_EINVAL;
+  if (b ? (K % 256 || N % 16 || N / 64 + 1 > kGemmCounters) : (K % 4 || N % 4)) return STAIRS_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const size_t wbytes = (size_t)N * K * (b ? 2 : 4);
   const int S = gemm_slices(K, b);
   char *dW = nullptr, *dWs = nullptr;
   float *dX = nullptr, *dP = nullptr, *dY = nullptr;
+  int* dCnt = nullptr;
   int rc = STAIRS_OK;
   auto ok = [&](hipError_t e) {
     if (e != hipSuccess && rc == STAIRS_OK) {
@@ -624,18 +648,22 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
   };
   if (ok(hipMalloc((void**)&dW, wbytes)) && ok(hipMalloc((void**)&dX, (size_t)M * K * 4)) &&
       ok(hipMalloc((void**)&dP, (size_t)S * M * N * 4)) && ok(hipMalloc((void**)&dY, (size_t)M * N * 4)) &&
-      (!b || ok(hipMalloc((void**)&dWs, wbytes)))) {
+      ok(hipMalloc((void**)&dCnt, kGemmCounters * sizeof(int))) && (!b || ok(hipMalloc((void**)&dWs, wbytes)))) {
     ok(hipMemcpyAsync(dW, W, wbytes, hipMemcpyHostToDevice, st));
     ok(hipMemcpyAsync(dX, X, (size_t)M * K * 4, hipMemcpyHostToDevice, st));
-    if (b) launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(dW), reinterpret_cast<uint4*>(dWs), N, K, st);
+    if (b) launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(dW), reinterpret_cast<uint4*>(dWs), N, K, 0, st);
+    ok(hipMemsetAsync(dCnt, 0, kGemmCounters * sizeof(int), st));
     RowNorm none{nullptr, nullptr, 0, 0.f};
-    const int S2 = launch_gemm_partial(kRoleHead, b, b ? dWs : dW, N, K, dX, K, M, none, dP, st);
-    launch_fin_plain(dP, S2, M, N, dY, N, st);
+    GemmEpi e{};
+    e.counters = dCnt;
+    e.out = dY;
+    e.hd = 64;
+    launch_gemm(kRoleHead, b, b ? dWs : dW, N, K, dX, K, M, none, dP, e, st);
     ok(hipGetLastError());
     ok(hipMemcpyAsync(Y, dY, (size_t)M * N * 4, hipMemcpyDeviceToHost, st));
     ok(hipStreamSynchronize(st));
   }
-  (void)hipFree(dW); (void)hipFree(dWs); (void)hipFree(dX); (void)hipFree(dP); (void)hipFree(dY);
+  (void)hipFree(dW); (void)hipFree(dWs); (void)hipFree(dX); (void)hipFree(dP); (void)hipFree(dY); (void)hipFree(dCnt);
   return rc;
 }
 
@@ -684,17 +712,35 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
   if (which >= 5 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");
   RowNorm none{nullptr, nullptr, 0, 0.f};
   double bytes = 0;
+  const PosRef tpos = abs_pos(c, which == 1 ? std::max(ctx_len, M) - M : 0);
+  if (which == 1 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");
+  if (which == 1) launch_rope_table(tpos, M, m->hd, g.rope_theta, c->rope_cs, c->st);
   for (int pass = 0; pass < 2; ++pass) {          // pass 0 = warm-up of one launch per layer
     const int n = pass ? reps : (which >= 6 ? 1 : g.n_layers);
     if (pass) HIPCHK(c, hipEventRecord(c->ev[0], c->st));
     for (int r = 0; r < n; ++r) {
-      const Layer& ly = m->layers[r % g.n_layers];
+      const int l = r % g.n_layers;
+      const Layer& ly = m->layers[l];
+      char* Kl = m->Kc + l * m->kv_layer_bytes;
+      char* Vl = m->Vc + l * m->kv_layer_bytes;
+      GemmEpi e{};
+      e.counters = c->counters;
+      e.rope_cs = c->rope_cs;
+      e.pos = tpos;
+      e.Kc = reinterpret_cast<_Float16*>(Kl);
+      e.Vc = reinterpret_cast<_Float16*>(Vl);
+      e.Kc32 = reinterpret_cast<float*>(Kl);
+      e.Vc32 = reinterpret_cast<float*>(Vl);
+      e.cap = m->cap;
+      e.H = g.n_heads;
+      e.hd = m->hd;
+      e.ssq_out = c->ssq;
       switch (which) {
-        case 0: launch_gemm_partial(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, none, c->partial, c->st); bytes = 2.0 * f * d * esz; break;
-        case 1: launch_gemm_partial(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, none, c->partial, c->st); bytes = 3.0 * d * d * esz; break;
-        case 2: launch_gemm_partial(kRoleWo, b, ly.wo, d, d, c->x, d, M, none, c->partial, c->st); bytes = 1.0 * d * d * esz; break;
-        case 3: launch_gemm_partial(kRoleDown, b, ly.wdown, d, f, c->h, f, M, none, c->partial, c->st); bytes = 1.0 * d * f * esz; break;
-        case 4: launch_gemm_partial(kRoleHead, b, m->lm_head, V, d, c->x, d, M, none, c->partial, c->st); bytes = 1.0 * V * d * esz; break;
+        case 0: e.out = c->h; launch_gemm(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, none, c->partial, e, c->st); bytes = 2.0 * f * d * esz; break;
+        case 1: e.out = c->q_rot; launch_gemm(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, none, c->partial, e, c->st); bytes = 3.0 * d * d * esz; break;
+        case 2: e.out = c->x; launch_gemm(kRoleWo, b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, e, c->st); bytes = 1.0 * d * d * esz; break;
+        case 3: e.out = c->x; launch_gemm(kRoleDown, b, ly.wdown, d, f, c->h, f, M, none, c->partial, e, c->st); bytes = 1.0 * d * f * esz; break;
+        case 4: e.out = c->logits; launch_gemm(kRoleHead, b, m->lm_head, V, d, c->x, d, M, none, c->partial, e, c->st); bytes = 1.0 * V * d * esz; break;
         case 6:
         case 7: {
           // a whole forward of M rows ending at position ctx_len-1 (all rows' logits for the
@@ -708,7 +754,8 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
         default: {
           const size_t off = (size_t)(r % g.n_layers) * m->kv_layer_bytes;
           launch_attention(c->q_rot, m->Kc + off, m->Vc + off, b, m->cap, d, g.n_heads, M, abs_pos(c, ctx_len - M),
-                           (ctx_len + kAttnChunk - 1) / kAttnChunk, c->nchunk_cap, c->part_o, c->part_ml, c->attn_out, c->st);
+                           (ctx_len + kAttnChunk - 1) / kAttnChunk, c->nchunk_cap, c->part_o, c->part_ml,
+                           c->counters + kGemmCounters, c->attn_out, c->st);
           bytes = 2.0 * ctx_len * d * esz;
         }
       }

@@ -9,7 +9,8 @@ namespace stairs {
 
 constexpr int kMaxRows = 32;        // rows (new tokens) one forward can take
 constexpr int kAttnChunk = 128;     // keys per attention work-group; boundaries are absolute positions
-constexpr int kSsqGroup = 1024;     // residual columns covered by one sum-of-squares partial
+constexpr int kSsqGroupF32 = 1024;  // residual columns per sum-of-squares partial, fp32 models
+constexpr int kSsqGroupBf16 = 128;  // ... bf16 models (= column group of the residual-writing GEMMs)
 constexpr int kUnitK = 256;         // k extent of one weight "unit" (8 MFMA k-steps of 32)
 constexpr int kSliceUnits = 2;      // units per split-K slice (512 k)
 
@@ -29,7 +30,10 @@ struct RowNorm {
   float eps;
 };
 
-inline int ssq_groups(int d) { return (d + kSsqGroup - 1) / kSsqGroup; }
+inline int ssq_groups(int d, int bf16) {
+  const int g = bf16 ? kSsqGroupBf16 : kSsqGroupF32;
+  return (d + g - 1) / g;
+}
 inline int gemm_slices(int K, int dtype_bf16) {
   if (!dtype_bf16) return 1;
   int units = K / kUnitK;
@@ -37,29 +41,39 @@ inline int gemm_slices(int K, int dtype_bf16) {
 }
 
 // ---- weights --------------------------------------------------------------------------
-// bf16 [N, K] row-major -> MFMA-operand tiles: tile (nt, kt) covers rows nt*16.., k kt*32..,
-// is 1 KiB, stored at index nt*(K/32)+kt; inside it lane l = r + 16*g holds W[nt*16+r][kt*32+g*8..+8].
-void launch_swizzle_bf16(const uint16_t* W, uint4* Wsw, int N, int K, hipStream_t st);
+// bf16 [N, K] row-major -> MFMA-operand tiles: tile (nt, kt) covers rows nt*16.., k kt*32.., is 1 KiB;
+// inside it lane l = r + 16*g holds W[nt*16+r][kt*32+g*8..+8].  Tiles are stored slice-major:
+// [split-K slice of 16 k-steps][nt][k-step inside the slice], so that one work-group of the GEMM
+// (one slice, 4*NT adjacent row tiles) reads one contiguous run.
+// interleave_f > 0: W = [gate rows; up rows] of f features each; tiles alternate gate / up.
+void launch_swizzle_bf16(const uint16_t* W, uint4* Wsw, int N, int K, int interleave_f, hipStream_t st);
 
 enum { kRoleQKV = 0, kRoleWo = 1, kRoleGateUp = 2, kRoleDown = 3, kRoleHead = 4 };   // which projection a GEMM launch is
 
-// ---- skinny GEMM: partial[s][m][n] = sum over k-slice s of W[n][k] * xn[m][k] -----------
-// bf16: W is swizzled, split-K slices of 512 k; fp32: W row-major, one slice.
-// partial holds gemm_slices() * M * N floats.  Returns the number of slices.
-int launch_gemm_partial(int role, int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M,
-                        RowNorm nrm, float* partial, hipStream_t st);
+// What the GEMM does with its result (by role):
+//   QKV    : columns [0,d) q, [d,2d) k, [2d,3d) v: rotate q and k by the row's position, out = q as
+//            float [M, d], append k and v to the layer's cache at that position
+//   Wo/Down: out = x [M, N] += result; ssq_out[m][g] = sum over column group g of x^2
+//   GateUp : out = h [M, N/2] = silu(gate) * up
+//   Head   : out = logits [M, N]
+struct GemmEpi {
+  int* counters;            // bf16 path: one int per column group, zero between launches
+  float* out;
+  float* ssq_out;
+  const float2* rope_cs;    // [M][64] (cos, sin)
+  PosRef pos;
+  _Float16* Kc;             // bf16 models: half caches of this layer, tiled layout
+  _Float16* Vc;
+  float* Kc32;              // fp32 models: float caches of this layer, [H][cap][hd]
+  float* Vc32;
+  int cap, H, hd;
+};
 
-// ---- GEMM epilogues (sum the slices in index order, then ...) ---------------------------
-void launch_fin_plain(const float* partial, int S, int M, int N, float* out, int ldo, hipStream_t st);
-// x[m][n] += sum; ssq_part[m][g] = sum over the group's columns of x^2
-void launch_fin_resid(const float* partial, int S, int M, int N, float* x, float* ssq_part, hipStream_t st);
-// h[m][j] = silu(sum[m][j]) * sum[m][f + j]
-void launch_fin_swiglu(const float* partial, int S, int M, int f, float* h, hipStream_t st);
-// columns [0,d) = q, [d,2d) = k, [2d,3d) = v: rotate q and k by the row's position, write q as
-// float, append k and v to the layer's cache ([H][cap][hd], float or bf16) at that position.
-void launch_fin_qkv_rope(const float* partial, int S, int M, int d, int H, const float2* rope_cs,
-                         PosRef pos, float* q_rot, void* Kc, void* Vc, int cap, int kv_bf16,
-                         hipStream_t st);
+// ---- skinny GEMM + epilogue ---------------------------------------------------------------
+// bf16: W is swizzled, split-K slices of 512 k, epilogue fused; fp32: W row-major, epilogue in a
+// second kernel.  partial: scratch of gemm_slices() * M * N floats.
+void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M,
+                 RowNorm nrm, float* partial, const GemmEpi& epi, hipStream_t st);
 
 // ---- small kernels ----------------------------------------------------------------------
 // x[m][:] = emb[tokens[pos+m]][:] (row of zeros if pos+m < 0), plus sum-of-squares partials
@@ -68,9 +82,10 @@ void launch_embed(const void* emb, int emb_bf16, const int* tokens, PosRef pos, 
 // cs[m][i] = (cos, sin)((pos+m) * theta^(-2i/hd)), angle formed in double
 void launch_rope_table(PosRef pos, int M, int hd, float theta, float2* cs, hipStream_t st);
 // split-KV attention of M query rows at positions pos..pos+M-1 against keys 0..pos+M-1
-void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv_bf16, int cap, int d,
+// (kv_half: half caches in the tiled layout; else float caches [H][cap][hd]); counters: one int per head
+void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv_half, int cap, int d,
                       int H, int M, PosRef pos, int nchunk_launch, int nchunk_cap, float* part_o,
-                      float* part_ml, float* out, hipStream_t st);
+                      float* part_ml, int* counters, float* out, hipStream_t st);
 // out[out_pos + r] = argmax_v logits[r][v], ties -> lowest v; out_pos = *pos.base + pos.offset
 void launch_argmax(const float* logits, int ld, int V, int nrows, int* out, PosRef out_pos, hipStream_t st);
 // stairs validation on device: state[0] = L (sequence length). n = longest run with

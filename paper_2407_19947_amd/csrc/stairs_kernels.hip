@@ -53,6 +53,36 @@ __device__ __forceinline__ float block_sum_256(float v, float* sm) {
   return (sm[0] + sm[1]) + (sm[2] + sm[3]);
 }
 
+// Data handed from one work-group to another inside a kernel (split-K partial sums, attention chunk
+// partials) is written and read with relaxed device-scope atomic accesses: they write through to / read
+// from the level all XCDs share, so the hand-off needs no cache-wide write-back or invalidate; the
+// writer only waits for its own stores (s_waitcnt) before it takes its ticket.
+__device__ __forceinline__ void st_dev2(float* p, float a, float b) {
+  const unsigned long long v = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(float* p, float a) {
+  __hip_atomic_store(p, a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float* p) {
+  return __hip_atomic_load(const_cast<float*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_dev2(const float* p) {
+  const unsigned long long v = __hip_atomic_load(reinterpret_cast<unsigned long long*>(const_cast<float*>(p)),
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((unsigned)v), __uint_as_float((unsigned)(v >> 32)));
+}
+// all of this work-group's stores have completed; then one thread takes the ticket.  Returns true in
+// every thread of the work-group that arrived last of `expected`.
+__device__ __forceinline__ bool last_arrival(int* counter, int expected, int* s_flag) {
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (threadIdx.x == 0)
+    *s_flag = (__hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1) ? 1 : 0;
+  __syncthreads();
+  return *s_flag != 0;
+}
+
 __device__ __forceinline__ float row_rstd(const RowNorm& nrm, int m, int K) {
   float ss = 0.f;
   for (int p = 0; p < nrm.ssq_n; ++p) ss += nrm.ssq_part[m * nrm.ssq_n + p];
@@ -62,59 +92,211 @@ __device__ __forceinline__ float row_rstd(const RowNorm& nrm, int m, int K) {
 // ---------------------------------------------------------------------------------------
 // weight re-layout
 // ---------------------------------------------------------------------------------------
+// interleave_f > 0: W is [2f, K] = gate rows then up rows; output tile 2t holds gate rows 16t.., tile 2t+1 the up
+// rows 16t.. of the same features, so that a SwiGLU pair lands in the same column group of the GEMM.
 __global__ __launch_bounds__(256) void k_swizzle_bf16(const uint16_t* __restrict__ W, uint4* __restrict__ Wsw,
-                                                      int KT, size_t total, int K) {
+                                                      int KT, int NTILES, size_t total, int K, int interleave_f) {
   size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
-  int lane = (int)(idx & 63);
-  size_t tile = idx >> 6;
-  int nt = (int)(tile / KT), kt = (int)(tile % KT);
-  int r = lane & 15, g = lane >> 4;
-  Wsw[idx] = *reinterpret_cast<const uint4*>(W + ((size_t)nt * 16 + r) * K + kt * 32 + g * 8);
+  // destination order: [k-slice][row tile][k-step inside the slice][lane]
+  const int lane = (int)(idx & 63);
+  const size_t tile_idx = idx >> 6;
+  constexpr int SK = kSliceUnits * 8;                    // k-steps of a full slice
+  const size_t full = (size_t)NTILES * SK;               // tiles per full slice
+  const int s = (int)(tile_idx / full);
+  const size_t rem = tile_idx - (size_t)s * full;
+  const int ks = min(SK, KT - s * SK);                   // k-steps of this slice (the last one may be short)
+  const int nt = (int)(rem / ks), kk = (int)(rem - (size_t)nt * ks);
+  const int kt = s * SK + kk;
+  const int r = lane & 15, g = lane >> 4;
+  size_t row = (size_t)nt * 16 + r;
+  if (interleave_f > 0) row = (size_t)((nt & 1) ? interleave_f : 0) + (size_t)(nt >> 1) * 16 + r;
+  Wsw[idx] = *reinterpret_cast<const uint4*>(W + row * K + kt * 32 + g * 8);
 }
 
-void launch_swizzle_bf16(const uint16_t* W, uint4* Wsw, int N, int K, hipStream_t st) {
+void launch_swizzle_bf16(const uint16_t* W, uint4* Wsw, int N, int K, int interleave_f, hipStream_t st) {
   int KT = K / 32;
   size_t total = (size_t)(N / 16) * KT * 64;
   unsigned blocks = (unsigned)((total + 255) / 256);
-  hipLaunchKernelGGL(k_swizzle_bf16, dim3(blocks), dim3(256), 0, st, W, Wsw, KT, total, K);
+  hipLaunchKernelGGL(k_swizzle_bf16, dim3(blocks), dim3(256), 0, st, W, Wsw, KT, N / 16, total, K, interleave_f);
 }
 
 // ---------------------------------------------------------------------------------------
-// skinny GEMM, bf16 weights, MFMA 16x16x32
+// skinny GEMM, bf16 weights, MFMA 16x16x32, with the projection's epilogue fused in
 //   work-group = 4 waves; all four work on the same 512-wide k-slice (the X slice is staged once
 //   in LDS as MFMA B fragments, high and low halves) and on 4*NT consecutive 16-row weight tiles.
 //   The weight tile is the MFMA A operand and is loaded straight from HBM in operand order
 //   (1 KiB per wave-load, fully coalesced); the X rows are the B operand.
+//   Split-K: every work-group writes its partial sums; the one that arrives last at the column
+//   group's counter adds the slices up in slice order (so the result does not depend on which
+//   one that is) and applies the epilogue of the projection (ROLE).
 // ---------------------------------------------------------------------------------------
-// ROLE only gives each projection its own kernel symbol, so that a profiler's per-kernel
-// statistics separate the five weight shapes of a layer; the code is the same.
+__device__ __forceinline__ size_t k_cache_off(int pos, int e, int hd) {   // element offset inside one head
+  return ((size_t)((pos >> 4) * (hd >> 5) + (e >> 5)) * 64 + (pos & 15) + 16 * ((e & 31) >> 3)) * 8 + (e & 7);
+}
+__device__ __forceinline__ size_t v_cache_off(int pos, int e, int hd) {
+  const int p32 = pos & 31, k16 = p32 & 15;
+  return ((size_t)((pos >> 5) * (hd >> 4) + (e >> 4)) * 64 + (e & 15) + 16 * (k16 >> 2)) * 8 + (k16 & 3) + 4 * (p32 >> 4);
+}
+
+// Sum of the S split-K slices of one element (or 4 adjacent ones), in slice order.  The loads of up to 8
+// slices are issued together (they are full round trips to the memory side), the additions stay ordered.
+__device__ __forceinline__ float slice_sum(const float* partial, int S, size_t stride, size_t off) {
+  float a = 0.f;
+  for (int s0 = 0; s0 < S; s0 += 8) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = ld_dev(partial + (size_t)min(s0 + i, S - 1) * stride + off);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a += (s0 + i < S) ? v[i] : 0.f;
+  }
+  return a;
+}
+__device__ __forceinline__ float4 slice_sum4(const float* partial, int S, size_t stride, size_t off) {
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int s0 = 0; s0 < S; s0 += 8) {
+    float2 p[8], q[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float* src = partial + (size_t)min(s0 + i, S - 1) * stride + off;
+      p[i] = ld_dev2(src);
+      q[i] = ld_dev2(src + 2);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bool ok = s0 + i < S;
+      a.x += ok ? p[i].x : 0.f; a.y += ok ? p[i].y : 0.f; a.z += ok ? q[i].x : 0.f; a.w += ok ? q[i].y : 0.f;
+    }
+  }
+  return a;
+}
+
+// Epilogue of one column group [c0, c0+W) for all M rows, run by the 256 threads of one work-group.
+template <int ROLE, int W>
+__device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M, int N, int c0, const GemmEpi& epi) {
+  const int tid = threadIdx.x;
+  const size_t stride = (size_t)M * N;
+  if (ROLE == kRoleHead) {
+    constexpr int PR = W / 4;
+    for (int idx = tid; idx < M * PR; idx += 256) {
+      const int m = idx / PR, col = c0 + (idx - m * PR) * 4;
+      if (col < N) *reinterpret_cast<float4*>(epi.out + (size_t)m * N + col) = slice_sum4(partial, S, stride, (size_t)m * N + col);
+    }
+  } else if (ROLE == kRoleWo || ROLE == kRoleDown) {
+    constexpr int PR = W / 4;                       // threads per row: a power of two <= 64
+    const int total = M * PR;
+    for (int idx0 = 0; idx0 < total; idx0 += 256) {
+      const int idx = idx0 + tid;
+      const int m = idx / PR, col = c0 + (idx - m * PR) * 4;
+      float ss = 0.f;
+      if (idx < total && col < N) {
+        float4 a = slice_sum4(partial, S, stride, (size_t)m * N + col);
+        float4* xp = reinterpret_cast<float4*>(epi.out + (size_t)m * N + col);
+        const float4 r = *xp;
+        a.x += r.x; a.y += r.y; a.z += r.z; a.w += r.w;
+        *xp = a;
+        ss = (a.x * a.x + a.y * a.y) + (a.z * a.z + a.w * a.w);
+      }
+#pragma unroll
+      for (int off = PR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+      if (idx < total && (idx & (PR - 1)) == 0) epi.ssq_out[m * gridDim.x + blockIdx.x] = ss;
+    }
+  } else if (ROLE == kRoleGateUp) {
+    // weight tiles alternate: even tile = 16 gate rows, odd tile = the 16 up rows of the same features
+    constexpr int PR = W / 8;
+    const int f = N / 2;
+    for (int idx = tid; idx < M * PR; idx += 256) {
+      const int m = idx / PR, r = idx - m * PR;
+      const int q = r >> 2, cc = (r & 3) * 4;
+      const int gcol = c0 + 32 * q + cc;
+      if (gcol < N) {
+        const float4 g = slice_sum4(partial, S, stride, (size_t)m * N + gcol);
+        const float4 u = slice_sum4(partial, S, stride, (size_t)m * N + gcol + 16);
+        float4 o;
+        o.x = g.x / (1.0f + expf(-g.x)) * u.x;
+        o.y = g.y / (1.0f + expf(-g.y)) * u.y;
+        o.z = g.z / (1.0f + expf(-g.z)) * u.z;
+        o.w = g.w / (1.0f + expf(-g.w)) * u.w;
+        *reinterpret_cast<float4*>(epi.out + (size_t)m * f + (c0 >> 1) + 16 * q + cc) = o;
+      }
+    }
+  } else {   // kRoleQKV: rotate q and k, append k and v to the cache
+    const int d = N / 3, hd = epi.hd, half = hd >> 1;
+    constexpr int PR = W / 2;
+    const int part = c0 / d, cp = c0 - part * d;
+    const int pos0 = *epi.pos.base + epi.pos.offset;
+    for (int idx = tid; idx < M * PR; idx += 256) {
+      const int m = idx / PR, r = idx - m * PR;
+      const int hh = r / half, e = r - hh * half;
+      const int p = pos0 + m;
+      if (p < 0) continue;
+      const int colp = cp + hh * hd + e;            // column inside the part
+      const int h = colp / hd;
+      const float a = slice_sum(partial, S, stride, (size_t)m * N + c0 + hh * hd + e);
+      const float b = slice_sum(partial, S, stride, (size_t)m * N + c0 + hh * hd + e + half);
+      if (part == 2) {
+        _Float16* dst = epi.Vc + (size_t)h * epi.cap * hd;
+        store_kv(dst + v_cache_off(p, e, hd), a);
+        store_kv(dst + v_cache_off(p, e + half, hd), b);
+        continue;
+      }
+      const float2 cs = epi.rope_cs[m * 64 + e];
+      const float ra = a * cs.x - b * cs.y;
+      const float rb = b * cs.x + a * cs.y;
+      if (part == 0) {
+        epi.out[(size_t)m * d + colp] = ra;
+        epi.out[(size_t)m * d + colp + half] = rb;
+      } else {
+        _Float16* dst = epi.Kc + (size_t)h * epi.cap * hd;
+        store_kv(dst + k_cache_off(p, e, hd), ra);
+        store_kv(dst + k_cache_off(p, e + half, hd), rb);
+      }
+    }
+  }
+}
+
 template <int CT, int NT, int ROLE>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw, int KT, int NTILES,
                                                    const float* __restrict__ X, int ldx, int M,
-                                                   RowNorm nrm, int K, float* __restrict__ partial, int N) {
+                                                   RowNorm nrm, int K, float* partial, int N, GemmEpi epi) {
   extern __shared__ uint4 lds[];   // [16 k-steps][CT][hi,lo][64 lanes]
+  __shared__ int s_last;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int s = blockIdx.y;
+  const int s = blockIdx.y, S = gridDim.y;
   const int unit0 = s * kSliceUnits;
   const int units = min(kSliceUnits, K / kUnitK - unit0);
-  const int kt0 = unit0 * 8;
-  const int tile0 = (blockIdx.x * 4 + wave) * NT;
+  // weights are stored slice-major: [k-slice][row tile][k-step][lane]; the four waves take adjacent tiles, so
+  // the work-group reads one contiguous run of 64*NT KiB
+  const uint4* Wslice = Wsw + (size_t)s * NTILES * (kSliceUnits * 8) * 64 + lane;
+  const int tile0 = blockIdx.x * 4 * NT + wave;          // this wave's tiles: tile0 + 4 t
 
   uint4 wb[2][8];
   // first weight unit goes out before anything else: it depends on nothing
   if (tile0 < NTILES) {
-    const uint4* p = Wsw + ((size_t)tile0 * KT + kt0) * 64 + lane;
+    const uint4* p = Wslice + (size_t)tile0 * units * 8 * 64;
 #pragma unroll
     for (int i = 0; i < 8; ++i) wb[0][i] = p[i * 64];
+  }
+
+  // 1/rms of the rows: lane l owns row l>>1 (half of the partial sums each), every wave on its own
+  float my_rstd = 1.0f;
+  if (nrm.gain && nrm.ssq_part) {
+    const int m = lane >> 1, n2 = (nrm.ssq_n + 1) >> 1;
+    const int p0 = (lane & 1) * n2, p1 = min(nrm.ssq_n, p0 + n2);
+    float ss = 0.f;
+    if (m < M)
+      for (int p = p0; p < p1; ++p) ss += nrm.ssq_part[m * nrm.ssq_n + p];
+    ss += __shfl_xor(ss, 1);
+    my_rstd = 1.0f / sqrtf(ss / (float)K + nrm.eps);
   }
 
   // stage the X slice: fp32 -> (x * rstd * gain) -> bf16 hi + lo, in B-fragment order
   {
     const int kgs = units * 32;          // groups of 8 k per row
     const int k0 = unit0 * kUnitK;
-    for (int w = tid; w < 16 * CT * kgs; w += 256) {
+    for (int w = tid; w < 16 * CT * kgs; w += 256) {   // trip count is the same for every thread
       const int m = w / kgs, kg = w - m * kgs;
+      const float r = __shfl(my_rstd, 2 * m);
       float v[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = 0.f;
@@ -123,7 +305,6 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
         float4 a = xp[0], b = xp[1];
         v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
         if (nrm.gain) {
-          const float r = nrm.ssq_part ? row_rstd(nrm, m, K) : 1.0f;
           const float4* gp = reinterpret_cast<const float4*>(nrm.gain + k0 + kg * 8);
           float4 g0 = gp[0], g1 = gp[1];
           v[0] = v[0] * r * g0.x; v[1] = v[1] * r * g0.y; v[2] = v[2] * r * g0.z; v[3] = v[3] * r * g0.w;
@@ -151,15 +332,15 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
     f32x4 acc[CT];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const bool tile_ok = (tile0 + t) < NTILES;
+    const bool tile_ok = (tile0 + 4 * t) < NTILES;
 #pragma unroll
     for (int ku = 0; ku < kSliceUnits; ++ku) {
       const int u = t * kSliceUnits + ku;
       // prefetch the next unit into the other buffer
       if (u + 1 < NT * kSliceUnits) {
         const int tn = (u + 1) / kSliceUnits, kun = (u + 1) % kSliceUnits;
-        if (kun < units && (tile0 + tn) < NTILES) {
-          const uint4* p = Wsw + ((size_t)(tile0 + tn) * KT + kt0 + kun * 8) * 64 + lane;
+        if (kun < units && (tile0 + 4 * tn) < NTILES) {
+          const uint4* p = Wslice + ((size_t)(tile0 + 4 * tn) * units + kun) * 8 * 64;
 #pragma unroll
           for (int i = 0; i < 8; ++i) wb[(u + 1) & 1][i] = p[i * 64];
         }
@@ -180,17 +361,23 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
       }
     }
     if (tile_ok) {
-      const int n = (tile0 + t) * 16 + 4 * (lane >> 4);
+      const int n = (tile0 + 4 * t) * 16 + 4 * (lane >> 4);
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct) {
         const int m = ct * 16 + (lane & 15);
         if (m < M) {
-          float4 o = make_float4(acc[ct][0], acc[ct][1], acc[ct][2], acc[ct][3]);
-          *reinterpret_cast<float4*>(partial + ((size_t)s * M + m) * N + n) = o;
+          float* dst = partial + ((size_t)s * M + m) * N + n;
+          st_dev2(dst, acc[ct][0], acc[ct][1]);
+          st_dev2(dst + 2, acc[ct][2], acc[ct][3]);
         }
       }
     }
   }
+
+  // split-K hand-off: the partial sums are out, take a ticket; the last arrival finishes the group
+  if (!last_arrival(&epi.counters[blockIdx.x], S, &s_last)) return;
+  gemm_epilogue<ROLE, 64 * NT>(partial, S, M, N, blockIdx.x * 64 * NT, epi);
+  if (tid == 0) epi.counters[blockIdx.x] = 0;   // ready for the next launch on this stream
 }
 
 // fp32 weights, row-major: one wave per output feature, lanes stride over k.
@@ -233,26 +420,49 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ W, i
   }
 }
 
-int launch_gemm_partial(int role, int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M,
-                        RowNorm nrm, float* partial, hipStream_t st) {
+static int pick_nt(int role, int NTILES, int S, int hd) {
+  if (role == kRoleWo || role == kRoleDown) return 2;      // the sum-of-squares groups are 128 columns wide
+  if (role == kRoleQKV && hd == 128) return 2;              // a head's rotation pairs stay in one column group
+  // enough work-groups to cover the chip a few times over; otherwise more tiles per wave
+  return ((size_t)((NTILES + 7) / 8) * S >= 1024) ? 2 : 1;
+}
+
+// forward declarations of the unfused epilogues (fp32 models)
+void launch_fin_plain(const float* partial, int S, int M, int N, float* out, int ldo, hipStream_t st);
+void launch_fin_resid(const float* partial, int S, int M, int N, float* x, float* ssq_part, hipStream_t st);
+void launch_fin_swiglu(const float* partial, int S, int M, int f, float* h, hipStream_t st);
+void launch_fin_qkv_rope_f32(const float* partial, int S, int M, int d, int H, const float2* rope_cs, PosRef pos,
+                             float* q_rot, float* Kc, float* Vc, int cap, hipStream_t st);
+
+void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M, RowNorm nrm,
+                 float* partial, const GemmEpi& epi, hipStream_t st) {
   if (!dtype_bf16) {
     dim3 grid((N + 3) / 4), block(256);
     const float* Wf = static_cast<const float*>(W);
     if (M <= 4) hipLaunchKernelGGL(k_gemm_f32<4>, grid, block, 0, st, Wf, N, K, X, ldx, M, nrm, partial);
     else if (M <= 16) hipLaunchKernelGGL(k_gemm_f32<16>, grid, block, 0, st, Wf, N, K, X, ldx, M, nrm, partial);
     else hipLaunchKernelGGL(k_gemm_f32<32>, grid, block, 0, st, Wf, N, K, X, ldx, M, nrm, partial);
-    return 1;
+    switch (role) {
+      case kRoleQKV:
+        launch_fin_qkv_rope_f32(partial, 1, M, N / 3, epi.H, epi.rope_cs, epi.pos, epi.out, static_cast<float*>(epi.Kc32),
+                                static_cast<float*>(epi.Vc32), epi.cap, st);
+        break;
+      case kRoleWo:
+      case kRoleDown: launch_fin_resid(partial, 1, M, N, epi.out, epi.ssq_out, st); break;
+      case kRoleGateUp: launch_fin_swiglu(partial, 1, M, N / 2, epi.out, st); break;
+      default: launch_fin_plain(partial, 1, M, N, epi.out, N, st); break;
+    }
+    return;
   }
   const int S = gemm_slices(K, 1);
   const int NTILES = N / 16, KT = K / 32;
   const uint4* Wsw = static_cast<const uint4*>(W);
-  // enough work-groups to cover the chip a few times over; otherwise more tiles per wave
-  const int NT = ((size_t)((NTILES + 7) / 8) * S >= 1024) ? 2 : 1;
+  const int NT = pick_nt(role, NTILES, S, epi.hd);
   dim3 grid((NTILES + 4 * NT - 1) / (4 * NT), S), block(256);
   const int CT = (M <= 16) ? 1 : 2;
   const size_t lds = (size_t)16 * CT * 2 * 64 * sizeof(uint4);
 #define STAIRS_GEMM(ct, nt, role) \
-  hipLaunchKernelGGL((k_gemm_bf16<ct, nt, role>), grid, block, lds, st, Wsw, KT, NTILES, X, ldx, M, nrm, K, partial, N)
+  hipLaunchKernelGGL((k_gemm_bf16<ct, nt, role>), grid, block, lds, st, Wsw, KT, NTILES, X, ldx, M, nrm, K, partial, N, epi)
 #define STAIRS_GEMM_ROLE(role)             \
   if (CT == 1 && NT == 1) STAIRS_GEMM(1, 1, role); \
   else if (CT == 1) STAIRS_GEMM(1, 2, role);       \
@@ -267,7 +477,6 @@ int launch_gemm_partial(int role, int dtype_bf16, const void* W, int N, int K, c
   }
 #undef STAIRS_GEMM_ROLE
 #undef STAIRS_GEMM
-  return S;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -367,29 +576,25 @@ void launch_fin_plain(const float* partial, int S, int M, int N, float* out, int
   hipLaunchKernelGGL(k_fin_plain, dim3((N / 4 + 255) / 256, M), dim3(256), 0, st, partial, S, M, N, out, ldo);
 }
 void launch_fin_resid(const float* partial, int S, int M, int N, float* x, float* ssq_part, hipStream_t st) {
-  hipLaunchKernelGGL(k_fin_resid, dim3(ssq_groups(N), M), dim3(256), 0, st, partial, S, M, N, x, ssq_part);
+  hipLaunchKernelGGL(k_fin_resid, dim3(ssq_groups(N, 0), M), dim3(256), 0, st, partial, S, M, N, x, ssq_part);
 }
 void launch_fin_swiglu(const float* partial, int S, int M, int f, float* h, hipStream_t st) {
   hipLaunchKernelGGL(k_fin_swiglu, dim3((f / 4 + 255) / 256, M), dim3(256), 0, st, partial, S, M, f, h);
 }
-void launch_fin_qkv_rope(const float* partial, int S, int M, int d, int H, const float2* rope_cs, PosRef pos,
-                         float* q_rot, void* Kc, void* Vc, int cap, int kv_bf16, hipStream_t st) {
+void launch_fin_qkv_rope_f32(const float* partial, int S, int M, int d, int H, const float2* rope_cs, PosRef pos,
+                             float* q_rot, float* Kc, float* Vc, int cap, hipStream_t st) {
   const int per_row = 3 * H * (d / H / 2);
   dim3 grid((per_row + 255) / 256, M), block(256);
-  if (kv_bf16)
-    hipLaunchKernelGGL(k_fin_qkv_rope<_Float16>, grid, block, 0, st, partial, S, M, d, H, rope_cs, pos, q_rot,
-                       static_cast<_Float16*>(Kc), static_cast<_Float16*>(Vc), cap);
-  else
-    hipLaunchKernelGGL(k_fin_qkv_rope<float>, grid, block, 0, st, partial, S, M, d, H, rope_cs, pos, q_rot,
-                       static_cast<float*>(Kc), static_cast<float*>(Vc), cap);
+  hipLaunchKernelGGL(k_fin_qkv_rope<float>, grid, block, 0, st, partial, S, M, d, H, rope_cs, pos, q_rot, Kc, Vc, cap);
 }
 
 // ---------------------------------------------------------------------------------------
 // embedding gather, rope table
 // ---------------------------------------------------------------------------------------
-template <typename E>
+// GW = residual columns per sum-of-squares partial: 1024 (one per block) or 128 (one per 32 lanes)
+template <typename E, int GW>
 __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const int* __restrict__ tokens, PosRef pos,
-                                               int d, float* __restrict__ x, float* __restrict__ ssq_part) {
+                                               int d, float* __restrict__ x, float* __restrict__ ssq_part, int ssq_n) {
   __shared__ float sm[4];
   const int c = (blockIdx.x * 256 + threadIdx.x) * 4, m = blockIdx.y;
   const int p = *pos.base + pos.offset + m;
@@ -403,17 +608,24 @@ __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const 
     *reinterpret_cast<float4*>(x + (size_t)m * d + c) = v;
     ss = (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
   }
-  ss = block_sum_256(ss, sm);
-  if (threadIdx.x == 0) ssq_part[m * gridDim.x + blockIdx.x] = ss;
+  if (GW == 1024) {
+    ss = block_sum_256(ss, sm);
+    if (threadIdx.x == 0) ssq_part[m * ssq_n + blockIdx.x] = ss;
+  } else {
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    if ((threadIdx.x & 31) == 0 && c < d) ssq_part[m * ssq_n + c / 128] = ss;
+  }
 }
 
 void launch_embed(const void* emb, int emb_bf16, const int* tokens, PosRef pos, int M, int d, float* x,
                   float* ssq_part, hipStream_t st) {
-  dim3 grid(ssq_groups(d), M), block(256);
+  dim3 grid((d + 1023) / 1024, M), block(256);
+  const int sn = ssq_groups(d, emb_bf16);
   if (emb_bf16)
-    hipLaunchKernelGGL(k_embed<uint16_t>, grid, block, 0, st, static_cast<const uint16_t*>(emb), tokens, pos, d, x, ssq_part);
+    hipLaunchKernelGGL((k_embed<uint16_t, 128>), grid, block, 0, st, static_cast<const uint16_t*>(emb), tokens, pos, d, x, ssq_part, sn);
   else
-    hipLaunchKernelGGL(k_embed<float>, grid, block, 0, st, static_cast<const float*>(emb), tokens, pos, d, x, ssq_part);
+    hipLaunchKernelGGL((k_embed<float, 1024>), grid, block, 0, st, static_cast<const float*>(emb), tokens, pos, d, x, ssq_part, sn);
 }
 
 __global__ void k_rope_table(PosRef pos, int hd, double theta, float2* __restrict__ cs) {
@@ -566,6 +778,210 @@ __global__ void k_attn_combine(const float* __restrict__ part_o, const float* __
   *dst = num / den;
 }
 
+// ---------------------------------------------------------------------------------------
+// KV-cache attention for half-precision caches, MFMA 16x16x32 f16.
+//   Cache layout (per layer, per head): keys in 16-position blocks stored as MFMA A tiles
+//   [16 keys x 32 dims] (k_cache_off), values in 32-position blocks stored as A tiles of V^T
+//   [16 dims x 32 key slots] whose slot order is the one the score tiles come out in (v_cache_off),
+//   so neither K, V nor the probabilities ever pass through LDS for a transpose.
+//   Work-group = (128-key chunk at an absolute position, head); wave w owns keys 32w..32w+31 of the
+//   chunk: scores^T = K . q^T (q as half hi+lo), masked softmax over its 32 keys, out^T = V^T . p^T
+//   (p as half hi+lo).  The four waves are merged in LDS in wave order, the chunks of a head by the
+//   work-group that arrives last at the head's counter, in chunk order.
+// ---------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+
+__device__ __forceinline__ void split_half8(const float* v, f16x8& hi, f16x8& lo) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const _Float16 h = (_Float16)v[e];
+    hi[e] = h;
+    lo[e] = (_Float16)(v[e] - (float)h);
+  }
+}
+
+template <int HD, int CT>
+__global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, const _Float16* __restrict__ Kc,
+                                                  const _Float16* __restrict__ Vc, int cap, int d, int H, int M,
+                                                  PosRef pos, float scale, int nchunk_cap, float* part_o,
+                                                  float* part_ml, int* counters, float* __restrict__ out) {
+  constexpr int KK = HD / 32;   // k-steps of the score MFMA
+  constexpr int ET = HD / 16;   // output-dim tiles of the value MFMA
+  __shared__ float s_o[4][16][HD];
+  __shared__ float s_m[4][16], s_l[4][16];
+  __shared__ int s_last;
+  const int c = blockIdx.x, h = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  const int pos0 = *pos.base + pos.offset;
+  const int kv_len = pos0 + M;
+  const int kb = c * kAttnChunk + wave * 32;          // first key of this wave
+  const bool have_keys = kb < kv_len;
+
+  uint4 kreg[2][KK], vreg[ET];
+  if (have_keys) {
+    const uint4* Kh = reinterpret_cast<const uint4*>(Kc + (size_t)h * cap * HD);
+    const uint4* Vh = reinterpret_cast<const uint4*>(Vc + (size_t)h * cap * HD);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kreg[t][kk] = Kh[((size_t)((kb >> 4) + t) * KK + kk) * 64 + lane];
+#pragma unroll
+    for (int et = 0; et < ET; ++et) vreg[et] = Vh[((size_t)(kb >> 5) * ET + et) * 64 + lane];
+  }
+
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct) {
+    const int qi = ct * 16 + j;                      // this lane's query row
+    f32x4 oacc[ET];
+#pragma unroll
+    for (int et = 0; et < ET; ++et) oacc[et] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mw = -INFINITY, lw = 0.f;
+    if (have_keys) {
+      f16x8 qh[KK], ql[KK];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = 0.f;
+        if (qi < M) {
+          const float4* qp = reinterpret_cast<const float4*>(q + (size_t)qi * d + h * HD + kk * 32 + g * 8);
+          const float4 a = qp[0], b = qp[1];
+          v[0] = a.x * scale; v[1] = a.y * scale; v[2] = a.z * scale; v[3] = a.w * scale;
+          v[4] = b.x * scale; v[5] = b.y * scale; v[6] = b.z * scale; v[7] = b.w * scale;
+        }
+        split_half8(v, qh[kk], ql[kk]);
+      }
+      float sc[8];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        f32x4 sacc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          const f16x8 a = __builtin_bit_cast(f16x8, kreg[t][kk]);
+          sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qh[kk], sacc, 0, 0, 0);
+          sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ql[kk], sacc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int key = kb + t * 16 + g * 4 + v;
+          sc[t * 4 + v] = (qi < M && key <= pos0 + qi) ? sacc[v] : -INFINITY;
+        }
+      }
+      float mx = sc[0];
+#pragma unroll
+      for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sc[i]);
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      float pv[8], sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        pv[i] = (mx == -INFINITY) ? 0.f : expf(sc[i] - mx);
+        sum += pv[i];
+      }
+      sum += __shfl_xor(sum, 16);
+      sum += __shfl_xor(sum, 32);
+      mw = mx;
+      lw = sum;
+      f16x8 ph, pl;
+      split_half8(pv, ph, pl);
+#pragma unroll
+      for (int et = 0; et < ET; ++et) {
+        const f16x8 a = __builtin_bit_cast(f16x8, vreg[et]);
+        oacc[et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ph, oacc[et], 0, 0, 0);
+        oacc[et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pl, oacc[et], 0, 0, 0);
+      }
+    }
+    // merge the four waves (wave order)
+    if (ct > 0) __syncthreads();                     // LDS of the previous query tile has been read
+    if (g == 0) {
+      s_m[wave][j] = mw;
+      s_l[wave][j] = lw;
+    }
+    __syncthreads();
+    float mc = fmaxf(fmaxf(s_m[0][j], s_m[1][j]), fmaxf(s_m[2][j], s_m[3][j]));
+    const float fw = (mw == -INFINITY) ? 0.f : expf(mw - mc);
+#pragma unroll
+    for (int et = 0; et < ET; ++et) {
+      float4 o = make_float4(oacc[et][0] * fw, oacc[et][1] * fw, oacc[et][2] * fw, oacc[et][3] * fw);
+      *reinterpret_cast<float4*>(&s_o[wave][j][et * 16 + g * 4]) = o;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < 16 * HD / 2; idx += 256) {
+      const int jj = idx / (HD / 2), e = (idx - jj * (HD / 2)) * 2;
+      const int m = ct * 16 + jj;
+      if (m < M) {
+        const float o0 = ((s_o[0][jj][e] + s_o[1][jj][e]) + s_o[2][jj][e]) + s_o[3][jj][e];
+        const float o1 = ((s_o[0][jj][e + 1] + s_o[1][jj][e + 1]) + s_o[2][jj][e + 1]) + s_o[3][jj][e + 1];
+        st_dev2(&part_o[(((size_t)m * H + h) * nchunk_cap + c) * HD + e], o0, o1);
+      }
+    }
+    if (tid < 16 && ct * 16 + tid < M) {
+      const float m0 = s_m[0][tid], m1 = s_m[1][tid], m2 = s_m[2][tid], m3 = s_m[3][tid];
+      const float mcc = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+      float lc = 0.f;
+      if (m0 != -INFINITY) lc += expf(m0 - mcc) * s_l[0][tid];
+      if (m1 != -INFINITY) lc += expf(m1 - mcc) * s_l[1][tid];
+      if (m2 != -INFINITY) lc += expf(m2 - mcc) * s_l[2][tid];
+      if (m3 != -INFINITY) lc += expf(m3 - mcc) * s_l[3][tid];
+      float* ml = part_ml + (((size_t)(ct * 16 + tid) * H + h) * nchunk_cap + c) * 2;
+      st_dev2(ml, mcc, lc);
+    }
+  }
+
+  // chunk hand-off: the work-group that arrives last at the head's counter merges the chunks
+  if (!last_arrival(&counters[h], (int)gridDim.x, &s_last)) return;
+  // merge the chunks of this head.  Step A: all (max, sum) pairs of all rows go to LDS in one round trip.
+  // Step B: one thread per (row, 4 adjacent dims) adds its chunks up in chunk order, 20 chunks per round trip.
+  extern __shared__ float s_ml[];                     // [M][nch_max][2], sized by the host
+  const int nch_max = (pos0 + M - 1) / kAttnChunk + 1;
+  for (int idx = tid; idx < M * nch_max; idx += 256) {
+    const int m = idx / nch_max, cc = idx - m * nch_max;
+    const float2 ml = ld_dev2(&part_ml[(((size_t)m * H + h) * nchunk_cap + cc) * 2]);
+    s_ml[idx * 2] = ml.x;
+    s_ml[idx * 2 + 1] = ml.y;
+  }
+  __syncthreads();
+  constexpr int QPR = HD / 4;                         // threads per row
+  for (int idx = tid; idx < M * QPR; idx += 256) {
+    const int m = idx / QPR, e = (idx - m * QPR) * 4;
+    const int p = pos0 + m;
+    float4 res = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (p >= 0) {
+      const int nch = p / kAttnChunk + 1;
+      const float* mlr = s_ml + (size_t)m * nch_max * 2;
+      float gmax = -INFINITY;
+      for (int cc = 0; cc < nch; ++cc) gmax = fmaxf(gmax, mlr[cc * 2]);
+      const float* src = part_o + ((size_t)m * H + h) * nchunk_cap * HD + e;
+      float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+      float den = 0.f;
+      constexpr int CB = 20;
+      for (int c0 = 0; c0 < nch; c0 += CB) {
+        float2 va[CB], vb[CB];
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+          const float* q = src + (size_t)min(c0 + i, nch - 1) * HD;
+          va[i] = ld_dev2(q);
+          vb[i] = ld_dev2(q + 2);
+        }
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+          if (c0 + i < nch) {
+            const float mc = mlr[(c0 + i) * 2];
+            const float w = (mc == -INFINITY) ? 0.f : expf(mc - gmax);
+            num.x = fmaf(w, va[i].x, num.x); num.y = fmaf(w, va[i].y, num.y);
+            num.z = fmaf(w, vb[i].x, num.z); num.w = fmaf(w, vb[i].y, num.w);
+            den = fmaf(w, mlr[(c0 + i) * 2 + 1], den);
+          }
+        }
+      }
+      res = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
+    }
+    *reinterpret_cast<float4*>(out + (size_t)m * d + h * HD + e) = res;
+  }
+  if (tid == 0) counters[h] = 0;
+}
+
 template <typename KV, int HD>
 static void attn_dispatch(const float* q, const void* Kc, const void* Vc, int cap, int d, int H, int M, PosRef pos,
                           int nchunk_launch, int nchunk_cap, float* part_o, float* part_ml, hipStream_t st) {
@@ -586,17 +1002,29 @@ static void attn_dispatch(const float* q, const void* Kc, const void* Vc, int ca
 #undef STAIRS_ATTN
 }
 
-void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv_bf16, int cap, int d, int H, int M,
-                      PosRef pos, int nchunk_launch, int nchunk_cap, float* part_o, float* part_ml, float* out,
-                      hipStream_t st) {
+void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv_half, int cap, int d, int H, int M,
+                      PosRef pos, int nchunk_launch, int nchunk_cap, float* part_o, float* part_ml, int* counters,
+                      float* out, hipStream_t st) {
   const int hd = d / H;
-  if (kv_bf16) {
-    if (hd == 128) attn_dispatch<_Float16, 128>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
-    else attn_dispatch<_Float16, 64>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
-  } else {
-    if (hd == 128) attn_dispatch<float, 128>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
-    else attn_dispatch<float, 64>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
+  if (kv_half) {
+    const float scale = 1.0f / sqrtf((float)hd);
+    const _Float16* K = static_cast<const _Float16*>(Kc);
+    const _Float16* V = static_cast<const _Float16*>(Vc);
+    dim3 grid(nchunk_launch, H), block(256);
+    const size_t lds = (size_t)M * nchunk_launch * 2 * sizeof(float);   // the merge step's (max, sum) table
+#define STAIRS_ATTN16(hdv, ct) \
+  hipLaunchKernelGGL((k_attn_f16<hdv, ct>), grid, block, lds, st, q_rot, K, V, cap, d, H, M, pos, scale, nchunk_cap, \
+                     part_o, part_ml, counters, out)
+    if (hd == 128) {
+      if (M <= 16) STAIRS_ATTN16(128, 1); else STAIRS_ATTN16(128, 2);
+    } else {
+      if (M <= 16) STAIRS_ATTN16(64, 1); else STAIRS_ATTN16(64, 2);
+    }
+#undef STAIRS_ATTN16
+    return;
   }
+  if (hd == 128) attn_dispatch<float, 128>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
+  else attn_dispatch<float, 64>(q_rot, Kc, Vc, cap, d, H, M, pos, nchunk_launch, nchunk_cap, part_o, part_ml, st);
   if (hd == 128)
     hipLaunchKernelGGL(k_attn_combine<128>, dim3(H, M), dim3(128), 0, st, part_o, part_ml, H, pos, nchunk_cap, out, d);
   else
