@@ -68,7 +68,11 @@ struct stairs_ctx {
   int L = 0, P = 0;
   bool prefilled = false;
   int pending_k = -1;          // draft length of the outstanding proposal, -1 = none
-  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t ev[8] = {};       // 0,1: general; 5,6,7: iteration start / after the proposal / after validation
+  struct IterGraph { int half, k, nch; hipGraphExec_t exec; };
+  std::vector<IterGraph> graphs;   // captured iterations, see iteration_graph()
+  bool own_stream = false;
+  bool use_graphs = true;      // env STAIRS_NO_GRAPH=1 turns replay off
   bool sync_launches = false;  // env STAIRS_SYNC_LAUNCHES=1: wait after every kernel (for counter-collecting profilers)
   std::string err;
 };
@@ -238,10 +242,10 @@ size_t max_partial_floats(const stairs_model_cfg* m) {
 }
 
 // One forward of `M` rows at positions pos..pos+M-1 whose token ids are tokens[pos..pos+M-1].
-// pos_host is the host's value of that position (used only to size the attention grid).
+// nchunk = attention chunks to launch: >= ceil((pos + M) / kAttnChunk); extra ones find no keys.
 // logits_rows: 0 = no unembedding (prefill), 1 = last row only -> c->logits row 0,
 //              M = every row -> c->logits rows 0..M-1.
-int forward(stairs_ctx* c, Model* m, PosRef pos, int pos_host, int M, int logits_rows) {
+int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows) {
   const stairs_model_cfg& g = m->cfg;
   const int d = g.d_model, f = g.d_ffn, H = g.n_heads, V = g.vocab;
   const int b = m->bf16 ? 1 : 0;
@@ -255,7 +259,6 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int pos_host, int M, int logits
   SYNCPOINT();
   launch_rope_table(pos, M, m->hd, g.rope_theta, c->rope_cs, st);
   SYNCPOINT();
-  const int nchunk = (std::max(pos_host, 0) + M + kAttnChunk - 1) / kAttnChunk;
   const RowNorm none{nullptr, nullptr, 0, 0.f};
   for (int l = 0; l < g.n_layers; ++l) {
     const Layer& ly = m->layers[l];
@@ -305,61 +308,112 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int pos_host, int M, int logits
 }
 
 PosRef abs_pos(const stairs_ctx* c, int p) { return PosRef{c->state + 2, p}; }   // state[2] == 0
+PosRef rel_pos(const stairs_ctx* c, int off) { return PosRef{c->state, off}; }     // state[0] == L, kept on the device
+int chunks_for(int kv_len) { return (std::max(kv_len, 1) + kAttnChunk - 1) / kAttnChunk; }
 
 // ingest positions [from, to) of the current sequence into a model's cache, no logits
 int ingest(stairs_ctx* c, Model* m, int from, int to) {
   for (int p = from; p < to; p += kMaxRows) {
     const int M = std::min(kMaxRows, to - p);
-    int rc = forward(c, m, abs_pos(c, p), p, M, 0);
+    int rc = forward(c, m, abs_pos(c, p), chunks_for(p + M), M, 0);
     if (rc) return rc;
   }
   if (to > m->valid) m->valid = to;
   return STAIRS_OK;
 }
 
+// Enqueue the draft's k greedy steps.  Positions are taken relative to the device-side sequence
+// length (state[0] == L), so the same launches can be replayed for any L; nch = attention chunks to launch.
+int enqueue_propose(stairs_ctx* c, int k, int nch) {
+  Model* m = &c->D;
+  const int V = m->cfg.vocab;
+  // step 1: rows at L-2, L-1 (row L-2 is recomputed when it is already cached: same values);
+  // its argmax is d_1 -> tokens[L].  Steps 2..k: one row each.
+  int rc = forward(c, m, rel_pos(c, -2), nch, 2, 1);
+  if (rc) return rc;
+  launch_argmax(c->logits, V, V, 1, c->tokens, rel_pos(c, 0), c->st);
+  for (int j = 1; j < k; ++j) {
+    rc = forward(c, m, rel_pos(c, j - 1), nch, 1, 1);
+    if (rc) return rc;
+    launch_argmax(c->logits, V, V, 1, c->tokens, rel_pos(c, j), c->st);
+  }
+  HIPCHK(c, hipGetLastError());
+  return STAIRS_OK;
+}
+
+// Enqueue the stair batch for the k draft tokens sitting in tokens[L..L+k), its per-row argmax and the validation.
+int enqueue_verify(stairs_ctx* c, int k, int nch) {
+  Model* m = &c->T;
+  const int M = k + 1, V = m->cfg.vocab;
+  int rc = forward(c, m, rel_pos(c, -1), nch, M, M);
+  if (rc) return rc;
+  launch_argmax(c->logits, V, V, M, c->tgt_tok, PosRef{nullptr, 0}, c->st);
+  launch_accept(c->tokens, c->tgt_tok, k, c->state, c->st);
+  HIPCHK(c, hipGetLastError());
+  return STAIRS_OK;
+}
+
 int do_propose(stairs_ctx* c, int k) {
   Model* m = &c->D;
   const int L = c->L;
-  // the draft's cache must hold positions 0..L-3; the 2-row step below covers L-2 and L-1
+  // the draft's cache must hold positions 0..L-3; the 2-row first step covers L-2 and L-1
   if (m->valid < L - 2) {
     int rc = ingest(c, m, m->valid, L - 2);
     if (rc) return rc;
   }
-  // step 1: rows at L-2, L-1 (row L-2 is recomputed when it is already cached: same values);
-  // its argmax is d_1 -> tokens[L].  Steps 2..k: one row each.
-  int rc = forward(c, m, abs_pos(c, L - 2), L - 2, 2, 1);
+  int rc = enqueue_propose(c, k, chunks_for(L + k - 1));
   if (rc) return rc;
-  launch_argmax(c->logits, m->cfg.vocab, m->cfg.vocab, 1, c->tokens, abs_pos(c, L), c->st);
-  for (int j = 1; j < k; ++j) {
-    rc = forward(c, m, abs_pos(c, L - 1 + j), L - 1 + j, 1, 1);
-    if (rc) return rc;
-    launch_argmax(c->logits, m->cfg.vocab, m->cfg.vocab, 1, c->tokens, abs_pos(c, L + j), c->st);
-  }
-  HIPCHK(c, hipGetLastError());
   m->valid = L + k - 1;      // tokens S, d_1..d_{k-1} are in the cache
   c->pending_k = k;
   return STAIRS_OK;
 }
 
-// stair batch + validation for the k draft tokens sitting in tokens[L..L+k)
-int do_verify(stairs_ctx* c, int k, int* n_out) {
-  Model* m = &c->T;
+// read back what the validation kernel decided and move the host's mirror of the state
+int finish_verify(stairs_ctx* c, int k, int* n_out) {
   const int L = c->L, M = k + 1;
-  int rc = forward(c, m, abs_pos(c, L - 1), L - 1, M, M);
-  if (rc) return rc;
-  launch_argmax(c->logits, m->cfg.vocab, m->cfg.vocab, M, c->tgt_tok, PosRef{nullptr, 0}, c->st);
-  launch_accept(c->tokens, c->tgt_tok, k, c->state, c->st);
-  HIPCHK(c, hipGetLastError());
   HIPCHK(c, hipMemcpyAsync(c->h_pinned, c->state, 2 * sizeof(int), hipMemcpyDeviceToHost, c->st));
   HIPCHK(c, hipMemcpyAsync(c->h_pinned + 2, c->tgt_tok, M * sizeof(int), hipMemcpyDeviceToHost, c->st));
   HIPCHK(c, hipStreamSynchronize(c->st));
   const int n = c->h_pinned[1];
   if (c->h_pinned[0] != L + n + 1 || n < 0 || n > k) return fail(c, STAIRS_EHIP, "device state out of sync with host");
   c->L = L + n + 1;
-  m->valid = L + n;                                   // positions L-1 .. L-1+n stay
+  c->T.valid = L + n;                                 // positions L-1 .. L-1+n stay
   if (c->have_draft) c->D.valid = std::min(c->D.valid, L + n);
   c->pending_k = -1;
   *n_out = n;
+  return STAIRS_OK;
+}
+
+int do_verify(stairs_ctx* c, int k, int* n_out) {
+  int rc = enqueue_verify(c, k, chunks_for(c->L + k));
+  if (rc) return rc;
+  return finish_verify(c, k, n_out);
+}
+
+// The two halves of an iteration -- (0) the k draft steps, (1) stair batch + argmax + validation -- as HIP
+// graphs that are replayed while their launch shapes stay valid: positions come from the device, only the
+// attention grid (nch chunks, padded to a multiple of 4) bounds the sequence length a graph can serve.
+int iteration_graph(stairs_ctx* c, int half, int k, int nch, hipGraphExec_t* out) {
+  for (auto& g : c->graphs)
+    if (g.half == half && g.k == k && g.nch == nch) {
+      *out = g.exec;
+      return STAIRS_OK;
+    }
+  hipGraph_t graph = nullptr;
+  HIPCHK(c, hipStreamBeginCapture(c->st, hipStreamCaptureModeThreadLocal));
+  const int rc = half == 0 ? enqueue_propose(c, k, nch) : enqueue_verify(c, k, nch);
+  hipError_t e = hipStreamEndCapture(c->st, &graph);
+  if (rc) {
+    if (graph) (void)hipGraphDestroy(graph);
+    return rc;
+  }
+  HIPCHK(c, e);
+  hipGraphExec_t exec = nullptr;
+  e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  HIPCHK(c, e);
+  c->graphs.push_back({half, k, nch, exec});
+  *out = exec;
   return STAIRS_OK;
 }
 
@@ -397,10 +451,12 @@ const char* stairs_last_error(const stairs_ctx* ctx) { return ctx ? ctx->err.c_s
 void stairs_free(stairs_ctx* c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->st);
+  for (auto& g : c->graphs) (void)hipGraphExecDestroy(g.exec);
   for (void* p : c->owned) (void)hipFree(p);
   if (c->h_pinned) (void)hipHostFree(c->h_pinned);
   for (auto& e : c->ev)
     if (e) (void)hipEventDestroy(e);
+  if (c->own_stream) (void)hipStreamDestroy(c->st);
   delete c;
 }
 
@@ -416,11 +472,20 @@ int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_wei
   stairs_ctx* c = new (std::nothrow) stairs_ctx;
   if (!c) return STAIRS_ENOMEM;
   c->st = static_cast<hipStream_t>(hip_stream);
+  if (!c->st) {   // graph capture needs a real stream; default priority
+    if (hipStreamCreateWithFlags(&c->st, hipStreamNonBlocking) != hipSuccess) {
+      delete c;
+      return STAIRS_EHIP;
+    }
+    c->own_stream = true;
+  }
   c->k_max = k_max;
   c->have_draft = have_draft;
   {
     const char* e = getenv("STAIRS_SYNC_LAUNCHES");
     c->sync_launches = e && e[0] == '1';
+    e = getenv("STAIRS_NO_GRAPH");
+    c->use_graphs = !(e && e[0] == '1') && !c->sync_launches;
   }
   int rc = STAIRS_OK;
   auto bail = [&](int code) {
@@ -561,16 +626,28 @@ int stairs_decode(stairs_ctx* c, int32_t G, int32_t k, int32_t* tokens_out, stai
   int rc;
   HIPCHK(c, hipEventRecord(c->ev[1], c->st));
   while (c->L - L0 < G) {
-    HIPCHK(c, hipEventRecord(c->ev[0], c->st));
-    if (k > 0 && (rc = do_propose(c, k))) return rc;
-    HIPCHK(c, hipEventRecord(c->ev[2], c->st));
     int n = 0;
-    if ((rc = do_verify(c, k, &n))) return rc;
-    HIPCHK(c, hipEventRecord(c->ev[3], c->st));
-    HIPCHK(c, hipEventSynchronize(c->ev[3]));
+    if (k > 0 && c->D.valid < c->L - 2 && (rc = ingest(c, &c->D, c->D.valid, c->L - 2))) return rc;
+    HIPCHK(c, hipEventRecord(c->ev[5], c->st));
+    if (c->use_graphs) {
+      const int nch = (chunks_for(c->L + k) + 3) / 4 * 4;
+      hipGraphExec_t gp = nullptr, gv = nullptr;
+      if (k > 0 && (rc = iteration_graph(c, 0, k, nch, &gp))) return rc;
+      if ((rc = iteration_graph(c, 1, k, nch, &gv))) return rc;
+      if (k > 0) HIPCHK(c, hipGraphLaunch(gp, c->st));
+      HIPCHK(c, hipEventRecord(c->ev[6], c->st));
+      HIPCHK(c, hipGraphLaunch(gv, c->st));
+    } else {
+      if (k > 0 && (rc = enqueue_propose(c, k, chunks_for(c->L + k - 1)))) return rc;
+      HIPCHK(c, hipEventRecord(c->ev[6], c->st));
+      if ((rc = enqueue_verify(c, k, chunks_for(c->L + k)))) return rc;
+    }
+    HIPCHK(c, hipEventRecord(c->ev[7], c->st));
+    if (k > 0) c->D.valid = c->L + k - 1;
+    if ((rc = finish_verify(c, k, &n))) return rc;
     float a = 0.f, b = 0.f;
-    HIPCHK(c, hipEventElapsedTime(&a, c->ev[0], c->ev[2]));
-    HIPCHK(c, hipEventElapsedTime(&b, c->ev[2], c->ev[3]));
+    HIPCHK(c, hipEventElapsedTime(&a, c->ev[5], c->ev[6]));
+    HIPCHK(c, hipEventElapsedTime(&b, c->ev[6], c->ev[7]));
     s.ms_draft += a;
     s.ms_verify += b;
     s.iterations += 1;
@@ -745,7 +822,7 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
         case 7: {
           // a whole forward of M rows ending at position ctx_len-1 (all rows' logits for the
           // target, last row's for the draft); it overwrites those rows of the cache
-          int rc = forward(c, m, abs_pos(c, ctx_len - M), ctx_len - M, M, which == 6 ? M : 1);
+          int rc = forward(c, m, abs_pos(c, ctx_len - M), chunks_for(ctx_len), M, which == 6 ? M : 1);
           if (rc) return rc;
           const double np_ = (double)g.n_layers * (4.0 * d * d + 3.0 * d * f) + (double)V * d;
           bytes = np_ * esz + 2.0 * g.n_layers * (double)ctx_len * d * esz;

@@ -152,3 +152,31 @@ def test_error_paths_on_device():
         with pytest.raises(pkg.StairsError) as e:
             s.generate(prompt, 40, 4)                          # P + G + k + 1 > max_seq
         assert e.value.code == -2
+
+
+def test_graph_replay_matches_eager_launches(monkeypatch):
+    """stairs_decode replays one captured HIP graph per iteration; every replay must give what the same
+    launches give when issued one by one (STAIRS_NO_GRAPH=1), across prefills, draft lengths and
+    interleaved step-by-step (eager) calls."""
+    w = si.WORKLOADS["cfg2_125m"]
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    cap = w["P"] + w["G"] + 20
+    monkeypatch.setenv("STAIRS_NO_GRAPH", "1")
+    with pkg.Stairs(target, draft, k_max=8, max_seq=cap) as eager:
+        ref = {k: eager.generate(prompt, w["G"], k) for k in (0, 3, 8)}
+    monkeypatch.delenv("STAIRS_NO_GRAPH")
+    with pkg.Stairs(target, draft, k_max=8, max_seq=cap) as s:
+        for rep in range(2):
+            for k in (3, 0, 8):
+                toks, st = s.generate(prompt, w["G"], k)
+                assert np.array_equal(toks, ref[k][0]), f"graph replay differs from eager launches (k={k})"
+                assert st.iterations == ref[k][1].iterations and st.accepted == ref[k][1].accepted
+                assert list(st.accept_hist) == list(ref[k][1].accept_hist)
+            # eager work between replays: a step-by-step iteration, then a decode that continues from it
+            s.prefill(prompt)
+            d = s.propose(3)
+            tgt, n, _ = s.verify(3)
+            assert list(tgt[:n + 1]) == list(ref[3][0][:n + 1])
+            rest, _ = s.decode(20, 3)
+            assert list(rest) == list(ref[3][0][n + 1:n + 21])
