@@ -278,6 +278,25 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
     for (int i = 0; i < 8; ++i) wb[0][i] = p[i * 64];
   }
 
+  // the X slice: this thread's items are (row m, 8 consecutive k); their loads go out first, the row
+  // statistics are fetched while they fly
+  const int kgs = units * 32;            // groups of 8 k per row
+  const int k0 = unit0 * kUnitK;
+  constexpr int ITEMS = 4 * CT;          // 16*CT rows x 64 groups / 256 threads (a full slice)
+  float4 xa[ITEMS], xb[ITEMS];
+#pragma unroll
+  for (int it = 0; it < ITEMS; ++it) {
+    const int w = tid + 256 * it;
+    const int m = w / kgs, kg = w - m * kgs;
+    xa[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+    xb[it] = xa[it];
+    if (w < 16 * CT * kgs && m < M) {
+      const float4* xp = reinterpret_cast<const float4*>(X + (size_t)m * ldx + k0 + kg * 8);
+      xa[it] = xp[0];
+      xb[it] = xp[1];
+    }
+  }
+
   // 1/rms of the rows: lane l owns row l>>1 (half of the partial sums each), every wave on its own
   float my_rstd = 1.0f;
   if (nrm.gain && nrm.ssq_part) {
@@ -290,26 +309,19 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
     my_rstd = 1.0f / sqrtf(ss / (float)K + nrm.eps);
   }
 
-  // stage the X slice: fp32 -> (x * rstd * gain) -> bf16 hi + lo, in B-fragment order
-  {
-    const int kgs = units * 32;          // groups of 8 k per row
-    const int k0 = unit0 * kUnitK;
-    for (int w = tid; w < 16 * CT * kgs; w += 256) {   // trip count is the same for every thread
-      const int m = w / kgs, kg = w - m * kgs;
-      const float r = __shfl(my_rstd, 2 * m);
-      float v[8];
+  // fp32 -> (x * rstd * gain) -> bf16 hi + lo, stored in B-fragment order
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = 0.f;
-      if (m < M) {
-        const float4* xp = reinterpret_cast<const float4*>(X + (size_t)m * ldx + k0 + kg * 8);
-        float4 a = xp[0], b = xp[1];
-        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-        if (nrm.gain) {
-          const float4* gp = reinterpret_cast<const float4*>(nrm.gain + k0 + kg * 8);
-          float4 g0 = gp[0], g1 = gp[1];
-          v[0] = v[0] * r * g0.x; v[1] = v[1] * r * g0.y; v[2] = v[2] * r * g0.z; v[3] = v[3] * r * g0.w;
-          v[4] = v[4] * r * g1.x; v[5] = v[5] * r * g1.y; v[6] = v[6] * r * g1.z; v[7] = v[7] * r * g1.w;
-        }
+  for (int it = 0; it < ITEMS; ++it) {
+    const int w = tid + 256 * it;                       // w < 16*CT*kgs is uniform per wave
+    const int m = min(w / kgs, 16 * CT - 1), kg = w - (w / kgs) * kgs;
+    const float r = __shfl(my_rstd, 2 * m);
+    if (w < 16 * CT * kgs) {
+      float v[8] = {xa[it].x, xa[it].y, xa[it].z, xa[it].w, xb[it].x, xb[it].y, xb[it].z, xb[it].w};
+      if (nrm.gain && m < M) {
+        const float4* gp = reinterpret_cast<const float4*>(nrm.gain + k0 + kg * 8);
+        float4 g0 = gp[0], g1 = gp[1];
+        v[0] = v[0] * r * g0.x; v[1] = v[1] * r * g0.y; v[2] = v[2] * r * g0.z; v[3] = v[3] * r * g0.w;
+        v[4] = v[4] * r * g1.x; v[5] = v[5] * r * g1.y; v[6] = v[6] * r * g1.z; v[7] = v[7] * r * g1.w;
       }
       uint32_t hb[8], lb[8];
 #pragma unroll
@@ -818,6 +830,20 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
   const int kb = c * kAttnChunk + wave * 32;          // first key of this wave
   const bool have_keys = kb < kv_len;
 
+  // the first query tile's rows are requested before the keys and values: they come from L2 and are
+  // converted while the cache tiles are still on their way
+  float4 qa0[KK], qb0[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    qa0[kk] = make_float4(0.f, 0.f, 0.f, 0.f);
+    qb0[kk] = qa0[kk];
+    if (have_keys && j < M) {
+      const float4* qp = reinterpret_cast<const float4*>(q + (size_t)j * d + h * HD + kk * 32 + g * 8);
+      qa0[kk] = qp[0];
+      qb0[kk] = qp[1];
+    }
+  }
+
   uint4 kreg[2][KK], vreg[ET];
   if (have_keys) {
     const uint4* Kh = reinterpret_cast<const uint4*>(Kc + (size_t)h * cap * HD);
@@ -841,15 +867,18 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
       f16x8 qh[KK], ql[KK];
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        float v[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = 0.f;
-        if (qi < M) {
-          const float4* qp = reinterpret_cast<const float4*>(q + (size_t)qi * d + h * HD + kk * 32 + g * 8);
-          const float4 a = qp[0], b = qp[1];
-          v[0] = a.x * scale; v[1] = a.y * scale; v[2] = a.z * scale; v[3] = a.w * scale;
-          v[4] = b.x * scale; v[5] = b.y * scale; v[6] = b.z * scale; v[7] = b.w * scale;
+        float4 a = qa0[kk], b = qb0[kk];
+        if (ct > 0) {
+          a = make_float4(0.f, 0.f, 0.f, 0.f);
+          b = a;
+          if (qi < M) {
+            const float4* qp = reinterpret_cast<const float4*>(q + (size_t)qi * d + h * HD + kk * 32 + g * 8);
+            a = qp[0];
+            b = qp[1];
+          }
         }
+        const float v[8] = {a.x * scale, a.y * scale, a.z * scale, a.w * scale,
+                            b.x * scale, b.y * scale, b.z * scale, b.w * scale};
         split_half8(v, qh[kk], ql[kk]);
       }
       float sc[8];
