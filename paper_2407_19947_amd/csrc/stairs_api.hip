@@ -71,6 +71,8 @@ struct stairs_ctx {
   hipEvent_t ev[8] = {};       // 0,1: general; 5,6,7: iteration start / after the proposal / after validation
   struct IterGraph { int half, k, nch; hipGraphExec_t exec; };
   std::vector<IterGraph> graphs;   // captured iterations, see iteration_graph()
+  std::vector<hipEvent_t> probe_ev;   // stairs_time_kernel(8): event pairs around one projection inside a forward
+  int probe_role = -1;               // role being timed in situ, -1 = none
   bool own_stream = false;
   bool use_graphs = true;      // env STAIRS_NO_GRAPH=1 turns replay off
   bool sync_launches = false;  // env STAIRS_SYNC_LAUNCHES=1: wait after every kernel (for counter-collecting profilers)
@@ -286,7 +288,9 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     launch_gemm(kRoleWo, b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, e, st);
     SYNCPOINT();
     e.out = c->h;
+    if (c->probe_role == kRoleGateUp) HIPCHK(c, hipEventRecord(c->probe_ev[2 * l], st));
     launch_gemm(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, RowNorm{ly.ffn_norm, c->ssq, sn, g.rms_eps}, c->partial, e, st);
+    if (c->probe_role == kRoleGateUp) HIPCHK(c, hipEventRecord(c->probe_ev[2 * l + 1], st));
     SYNCPOINT();
     e.out = c->x;
     launch_gemm(kRoleDown, b, ly.wdown, d, f, c->h, f, M, none, c->partial, e, st);
@@ -452,6 +456,7 @@ void stairs_free(stairs_ctx* c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->st);
   for (auto& g : c->graphs) (void)hipGraphExecDestroy(g.exec);
+  for (auto& e : c->probe_ev) (void)hipEventDestroy(e);
   for (void* p : c->owned) (void)hipFree(p);
   if (c->h_pinned) (void)hipHostFree(c->h_pinned);
   for (auto& e : c->ev)
@@ -778,7 +783,7 @@ int stairs_copy_probe(int64_t bytes, int32_t reps, float* ms_per_launch, void* h
 int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len, int32_t reps, float* ms_per_launch,
                        double* bytes_per_launch) {
   if (!c) return STAIRS_EINVAL;
-  if (which < 0 || which > 7 || M < 1 || M > kMaxRows || reps < 1 || !ms_per_launch)
+  if (which < 0 || which > 8 || M < 1 || M > kMaxRows || reps < 1 || !ms_per_launch)
     return fail(c, STAIRS_EINVAL, "bad argument to stairs_time_kernel");
   if (c->pending_k >= 0) return fail(c, STAIRS_ESTATE, "a proposal is pending");
   if (which == 7 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
@@ -787,6 +792,32 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
   const int d = g.d_model, f = g.d_ffn, V = g.vocab, b = m->bf16 ? 1 : 0;
   const size_t esz = m->esz();
   if (which >= 5 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");
+  if (which == 8) {
+    // the gate/up projection timed where it really runs: `reps` whole forwards of M rows ending at position
+    // ctx_len-1, an event pair around each layer's gate/up launch, all other kernels untouched in between
+    const int nl = g.n_layers;
+    while ((int)c->probe_ev.size() < 2 * nl) {
+      hipEvent_t e = nullptr;
+      HIPCHK(c, hipEventCreate(&e));
+      c->probe_ev.push_back(e);
+    }
+    double total_ms = 0;
+    for (int r = 0; r <= reps; ++r) {              // r == 0: warm-up
+      c->probe_role = kRoleGateUp;
+      int rc = forward(c, m, abs_pos(c, ctx_len - M), chunks_for(ctx_len), M, M);
+      c->probe_role = -1;
+      if (rc) return rc;
+      HIPCHK(c, hipStreamSynchronize(c->st));
+      for (int l = 0; l < nl && r > 0; ++l) {
+        float ms1 = 0.f;
+        HIPCHK(c, hipEventElapsedTime(&ms1, c->probe_ev[2 * l], c->probe_ev[2 * l + 1]));
+        total_ms += ms1;
+      }
+    }
+    *ms_per_launch = (float)(total_ms / ((double)reps * nl));
+    if (bytes_per_launch) *bytes_per_launch = 2.0 * f * d * esz;
+    return STAIRS_OK;
+  }
   RowNorm none{nullptr, nullptr, 0, 0.f};
   double bytes = 0;
   const PosRef tpos = abs_pos(c, which == 1 ? std::max(ctx_len, M) - M : 0);
