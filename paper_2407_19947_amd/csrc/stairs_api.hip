@@ -253,6 +253,7 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
   const int b = m->bf16 ? 1 : 0;
   const int sn = ssq_groups(d, b);
   hipStream_t st = c->st;
+  if (nchunk < 1 || nchunk > c->nchunk_cap || M < 1 || M > kMaxRows) return fail(c, STAIRS_EINVAL, "forward: launch shape outside the workspaces");
 #define SYNCPOINT()                                             \
   do {                                                          \
     if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));  \
@@ -635,7 +636,7 @@ int stairs_decode(stairs_ctx* c, int32_t G, int32_t k, int32_t* tokens_out, stai
     if (k > 0 && c->D.valid < c->L - 2 && (rc = ingest(c, &c->D, c->D.valid, c->L - 2))) return rc;
     HIPCHK(c, hipEventRecord(c->ev[5], c->st));
     if (c->use_graphs) {
-      const int nch = (chunks_for(c->L + k) + 3) / 4 * 4;
+      const int nch = std::min((chunks_for(c->L + k) + 3) / 4 * 4, c->nchunk_cap);   // never past the partial buffers
       hipGraphExec_t gp = nullptr, gv = nullptr;
       if (k > 0 && (rc = iteration_graph(c, 0, k, nch, &gp))) return rc;
       if ((rc = iteration_graph(c, 1, k, nch, &gv))) return rc;

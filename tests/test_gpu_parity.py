@@ -180,3 +180,23 @@ def test_graph_replay_matches_eager_launches(monkeypatch):
             assert list(tgt[:n + 1]) == list(ref[3][0][:n + 1])
             rest, _ = s.decode(20, 3)
             assert list(rest) == list(ref[3][0][n + 1:n + 21])
+
+
+def test_graph_replay_at_the_end_of_the_cache(monkeypatch):
+    """The replayed attention grid is padded to a multiple of 4 chunks but must never reach past the
+    partial-result buffers (sized for max_seq): sequence that ends in the last chunk the cache has."""
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=4, d_model=256, n_heads=4, d_ffn=768, vocab=2048),
+                           draft=dict(kind="prefix", n_layers=1), P=120, G=200)
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    k = 3
+    cap = w["P"] + w["G"] + k + 2                      # 325 positions = 3 chunks of 128
+    monkeypatch.setenv("STAIRS_NO_GRAPH", "1")
+    with pkg.Stairs(target, draft, k_max=k, max_seq=cap) as eager:
+        ref_t, ref_s = eager.generate(prompt, w["G"], k)
+    monkeypatch.delenv("STAIRS_NO_GRAPH")
+    with pkg.Stairs(target, draft, k_max=k, max_seq=cap) as s:
+        for rep in range(6):
+            toks, st = s.generate(prompt, w["G"], k)
+            assert np.array_equal(toks, ref_t)
+            assert list(st.accept_hist) == list(ref_s.accept_hist)
