@@ -261,6 +261,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
                                                    RowNorm nrm, int K, float* partial, int N, GemmEpi epi) {
   extern __shared__ uint4 lds[];   // [16 k-steps][CT][hi,lo][64 lanes]
   __shared__ int s_last;
+  __shared__ float s_rstd[kMaxRows];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int s = blockIdx.y, S = gridDim.y;
   const int unit0 = s * kSliceUnits;
@@ -297,16 +298,20 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
     }
   }
 
-  // 1/rms of the rows: lane l owns row l>>1 (half of the partial sums each), every wave on its own
-  float my_rstd = 1.0f;
+  // 1/rms of the rows from the sum-of-squares partials: half a wave (32 lanes) per row, one partial per lane
+  // and pass, so all loads of a row are in flight together; wave w takes the row pairs w, w+4, ...
   if (nrm.gain && nrm.ssq_part) {
-    const int m = lane >> 1, n2 = (nrm.ssq_n + 1) >> 1;
-    const int p0 = (lane & 1) * n2, p1 = min(nrm.ssq_n, p0 + n2);
-    float ss = 0.f;
-    if (m < M)
-      for (int p = p0; p < p1; ++p) ss += nrm.ssq_part[m * nrm.ssq_n + p];
-    ss += __shfl_xor(ss, 1);
-    my_rstd = 1.0f / sqrtf(ss / (float)K + nrm.eps);
+    const int half = lane >> 5, pl = lane & 31;
+    for (int r0 = 2 * wave; r0 < M; r0 += 8) {
+      const int m = r0 + half;
+      float ss = 0.f;
+      if (m < M)
+        for (int p = pl; p < nrm.ssq_n; p += 32) ss += nrm.ssq_part[m * nrm.ssq_n + p];
+#pragma unroll
+      for (int off = 16; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+      if (pl == 0 && m < M) s_rstd[m] = 1.0f / sqrtf(ss / (float)K + nrm.eps);
+    }
+    __syncthreads();
   }
 
   // fp32 -> (x * rstd * gain) -> bf16 hi + lo, stored in B-fragment order
@@ -314,8 +319,8 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
   for (int it = 0; it < ITEMS; ++it) {
     const int w = tid + 256 * it;                       // w < 16*CT*kgs is uniform per wave
     const int m = min(w / kgs, 16 * CT - 1), kg = w - (w / kgs) * kgs;
-    const float r = __shfl(my_rstd, 2 * m);
     if (w < 16 * CT * kgs) {
+      const float r = (nrm.gain && nrm.ssq_part && m < M) ? s_rstd[m] : 1.0f;
       float v[8] = {xa[it].x, xa[it].y, xa[it].z, xa[it].w, xb[it].x, xb[it].y, xb[it].z, xb[it].w};
       if (nrm.gain && m < M) {
         const float4* gp = reinterpret_cast<const float4*>(nrm.gain + k0 + kg * 8);
