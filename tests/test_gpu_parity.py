@@ -200,3 +200,53 @@ def test_graph_replay_at_the_end_of_the_cache(monkeypatch):
             toks, st = s.generate(prompt, w["G"], k)
             assert np.array_equal(toks, ref_t)
             assert list(st.accept_hist) == list(ref_s.accept_hist)
+
+
+@pytest.mark.parametrize("P", [127, 128, 129, 256, 257])
+def test_bf16_prompt_lengths_around_chunk_boundaries(P):
+    """Prompt ends just before / on / after an attention chunk boundary (128 keys) and a prefill chunk
+    boundary (32 rows); the first stair batch then straddles it."""
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=3, d_model=256, n_heads=4, d_ffn=512, vocab=2048),
+                           draft=dict(kind="prefix", n_layers=1), P=P, G=8)
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    res = run_side_by_side(target, draft, prompt, 8, 5, np.float64, LOGIT_TOL_BF16)
+    assert res["max_logit_err"] < 2e-3
+
+
+def test_widest_stair_batch_and_exact_capacity():
+    """k = k_max = 31 (32 rows, the most one forward takes) with max_seq sized to the last position used."""
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=2048),
+                           draft=dict(kind="prefix", n_layers=1), P=40, G=70)
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    k = 31
+    res = run_side_by_side(target, draft, prompt, 70, k, np.float64, LOGIT_TOL_BF16)
+    assert res["max_logit_err"] < 2e-3
+    cap = w["P"] + w["G"] + k + 1                            # the documented requirement of stairs_generate
+    with pkg.Stairs(target, draft, k_max=k, max_seq=cap) as s:
+        toks, st = s.generate(prompt, w["G"], k)
+        base, _ = s.generate(prompt, w["G"], 0)
+        assert np.array_equal(toks, base)
+        with pytest.raises(pkg.StairsError) as e:
+            s.generate(prompt, w["G"] + 1, k)                # one position too many
+        assert e.value.code == -2
+
+
+def test_degenerate_requests():
+    """G = 0, a target without any draft model (only k = 0 is legal), generation continued by stairs_decode."""
+    w = si.scaled_workload("cfg1_tiny_fp32")
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    with pkg.Stairs(target, None, k_max=0, max_seq=128) as s:
+        toks, st = s.generate(prompt, 0, 0)
+        assert len(toks) == 0 and st.iterations == 0
+        plain, _ = s.generate(prompt, 20, 0)
+        with pytest.raises(pkg.StairsError) as e:
+            s.generate(prompt, 4, 1)                          # k > k_max
+        assert e.value.code == -1
+    with pkg.Stairs(target, draft, k_max=4, max_seq=128) as s:
+        a, _ = s.generate(prompt, 7, 4)
+        b, _ = s.decode(13, 2)                                # continue the same sequence with another k
+        assert list(a) + list(b) == list(plain)
+        assert list(s.tokens()) == list(prompt) + list(plain)
