@@ -147,8 +147,9 @@ enum { KIND_EMB = 0, KIND_HEAD, KIND_NORM, KIND_QKV, KIND_WO, KIND_GU, KIND_DOWN
 // Upload a matrix made of `nparts` row blocks (each [rows_each, K], host, model dtype) as one
 // [nparts*rows_each, K] GEMM operand; bf16 goes through the operand re-layout kernel.
 int upload_matrix(stairs_ctx* c, bool bf16, const void* const* parts, int nparts, int rows_each, int K, int kind,
-                  char* staging, const void** out) {
-  const int interleave_f = (kind == KIND_GU) ? rows_each : 0;   // gate/up tiles alternate (SwiGLU epilogue)
+                  int hd, char* staging, const void** out) {
+  // gate/up and q/k rows are reordered so that SwiGLU and rotation pairs share a 16-row tile
+  const int perm = (kind == KIND_GU) ? kPermGateUp : (kind == KIND_QKV) ? kPermQKV : kPermNone;
   auto key = std::make_pair(parts[0], kind);
   auto it = c->dedup.find(key);
   if (it != c->dedup.end()) {
@@ -165,7 +166,7 @@ int upload_matrix(stairs_ctx* c, bool bf16, const void* const* parts, int nparts
     HIPCHK(c, hipMemcpyAsync(raw + p * part_bytes, parts[p], part_bytes, hipMemcpyHostToDevice, c->st));
   if (bf16) {
     launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(staging), reinterpret_cast<uint4*>(dst), nparts * rows_each, K,
-                        interleave_f, c->st);
+                        perm, rows_each, hd, c->st);
     HIPCHK(c, hipGetLastError());
   }
   HIPCHK(c, hipStreamSynchronize(c->st));   // staging and the host buffers are reused right away
@@ -200,7 +201,7 @@ int build_model(stairs_ctx* c, Model* m, const stairs_model_cfg* cfg, const stai
   int rc;
   if ((rc = upload_plain(c, w->tok_emb, (size_t)V * d * m->esz(), KIND_EMB, &m->tok_emb))) return rc;
   const void* one[1] = {w->lm_head};
-  if ((rc = upload_matrix(c, m->bf16, one, 1, V, d, KIND_HEAD, staging, &m->lm_head))) return rc;
+  if ((rc = upload_matrix(c, m->bf16, one, 1, V, d, KIND_HEAD, m->hd, staging, &m->lm_head))) return rc;
   const void* fn = nullptr;
   if ((rc = upload_plain(c, w->final_norm, (size_t)d * 4, KIND_NORM, &fn))) return rc;
   m->final_norm = static_cast<const float*>(fn);
@@ -213,13 +214,13 @@ int build_model(stairs_ctx* c, Model* m, const stairs_model_cfg* cfg, const stai
     if ((rc = upload_plain(c, w->ffn_norm[l], (size_t)d * 4, KIND_NORM, &p))) return rc;
     ly.ffn_norm = static_cast<const float*>(p);
     const void* qkv[3] = {w->wq[l], w->wk[l], w->wv[l]};
-    if ((rc = upload_matrix(c, m->bf16, qkv, 3, d, d, KIND_QKV, staging, &ly.wqkv))) return rc;
+    if ((rc = upload_matrix(c, m->bf16, qkv, 3, d, d, KIND_QKV, m->hd, staging, &ly.wqkv))) return rc;
     one[0] = w->wo[l];
-    if ((rc = upload_matrix(c, m->bf16, one, 1, d, d, KIND_WO, staging, &ly.wo))) return rc;
+    if ((rc = upload_matrix(c, m->bf16, one, 1, d, d, KIND_WO, m->hd, staging, &ly.wo))) return rc;
     const void* gu[2] = {w->w_gate[l], w->w_up[l]};
-    if ((rc = upload_matrix(c, m->bf16, gu, 2, f, d, KIND_GU, staging, &ly.wgu))) return rc;
+    if ((rc = upload_matrix(c, m->bf16, gu, 2, f, d, KIND_GU, m->hd, staging, &ly.wgu))) return rc;
     one[0] = w->w_down[l];
-    if ((rc = upload_matrix(c, m->bf16, one, 1, d, f, KIND_DOWN, staging, &ly.wdown))) return rc;
+    if ((rc = upload_matrix(c, m->bf16, one, 1, d, f, KIND_DOWN, m->hd, staging, &ly.wdown))) return rc;
   }
   m->kv_layer_bytes = (size_t)cfg->n_heads * m->cap * m->hd * m->esz();
   if ((rc = dev_alloc(c, &m->Kc, m->kv_layer_bytes * cfg->n_layers))) return rc;
@@ -734,7 +735,7 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
       ok(hipMalloc((void**)&dCnt, kGemmCounters * sizeof(int))) && (!b || ok(hipMalloc((void**)&dWs, wbytes)))) {
     ok(hipMemcpyAsync(dW, W, wbytes, hipMemcpyHostToDevice, st));
     ok(hipMemcpyAsync(dX, X, (size_t)M * K * 4, hipMemcpyHostToDevice, st));
-    if (b) launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(dW), reinterpret_cast<uint4*>(dWs), N, K, 0, st);
+    if (b) launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(dW), reinterpret_cast<uint4*>(dWs), N, K, kPermNone, 0, 0, st);
     ok(hipMemsetAsync(dCnt, 0, kGemmCounters * sizeof(int), st));
     RowNorm none{nullptr, nullptr, 0, 0.f};
     GemmEpi e{};

@@ -13,6 +13,7 @@ constexpr int kSsqGroupF32 = 1024;  // residual columns per sum-of-squares parti
 constexpr int kSsqGroupBf16 = 128;  // ... bf16 models (= column group of the residual-writing GEMMs)
 constexpr int kUnitK = 256;         // k extent of one weight "unit" (8 MFMA k-steps of 32)
 constexpr int kSliceUnits = 2;      // units per split-K slice (512 k)
+constexpr size_t kRowsPathMaxLds = 68 * 1024;   // most LDS the small-M GEMM (whole X block in LDS) may take per work-group
 
 // Position of row 0 of a forward = *base + offset (base lives in device memory so that the
 // same launch sequence can be replayed without the host knowing the sequence length).
@@ -45,8 +46,10 @@ inline int gemm_slices(int K, int dtype_bf16) {
 // inside it lane l = r + 16*g holds W[nt*16+r][kt*32+g*8..+8].  Tiles are stored slice-major:
 // [split-K slice of 16 k-steps][nt][k-step inside the slice], so that one work-group of the GEMM
 // (one slice, 4*NT adjacent row tiles) reads one contiguous run.
-// interleave_f > 0: W = [gate rows; up rows] of f features each; tiles alternate gate / up.
-void launch_swizzle_bf16(const uint16_t* W, uint4* Wsw, int N, int K, int interleave_f, hipStream_t st);
+// perm: order of the rows (= output columns of the GEMM): kPermGateUp (p0 = f) puts the gate and up rows of 8
+// features into one tile, kPermQKV (p0 = d, p1 = head_dim) the two halves of 8 rotation pairs; the epilogues undo it.
+enum { kPermNone = 0, kPermGateUp = 1, kPermQKV = 2 };
+void launch_swizzle_bf16(const uint16_t* W, uint4* Wsw, int N, int K, int perm, int p0, int p1, hipStream_t st);
 
 enum { kRoleQKV = 0, kRoleWo = 1, kRoleGateUp = 2, kRoleDown = 3, kRoleHead = 4 };   // which projection a GEMM launch is
 

@@ -92,10 +92,27 @@ __device__ __forceinline__ float row_rstd(const RowNorm& nrm, int m, int K) {
 // ---------------------------------------------------------------------------------------
 // weight re-layout
 // ---------------------------------------------------------------------------------------
-// interleave_f > 0: W is [2f, K] = gate rows then up rows; output tile 2t holds gate rows 16t.., tile 2t+1 the up
-// rows 16t.. of the same features, so that a SwiGLU pair lands in the same column group of the GEMM.
+// Row order of the re-laid-out matrix.  Output column n' of the GEMM is source row perm(n'):
+//   kPermNone  : identity
+//   kPermGateUp: W = [f gate rows; f up rows]; tile t holds gate rows 8t..8t+7 then up rows 8t..8t+7, so a SwiGLU
+//                pair sits at columns (j, j+8) of one 16-column tile
+//   kPermQKV   : W = [q; k; v] of d rows each, heads of hd rows; inside a q or k head tile t holds dims 8t..8t+7 then
+//                hd/2+8t..hd/2+8t+7, so a rotation pair (e, e+hd/2) sits at columns (j, j+8) of one tile; v unchanged
+__device__ __forceinline__ size_t perm_row(int nprime, int perm, int p0, int p1) {
+  const int r = nprime & 15;
+  if (perm == kPermGateUp) return (size_t)((r >> 3) ? p0 : 0) + (size_t)(nprime >> 4) * 8 + (r & 7);
+  if (perm == kPermQKV) {
+    const int d = p0, hd = p1;
+    const int part = nprime / d, c = nprime - part * d;
+    if (part == 2) return (size_t)nprime;
+    const int h = c / hd, w = c - h * hd;
+    return (size_t)part * d + (size_t)h * hd + (w >> 4) * 8 + (r & 7) + (r >> 3) * (hd >> 1);
+  }
+  return (size_t)nprime;
+}
+
 __global__ __launch_bounds__(256) void k_swizzle_bf16(const uint16_t* __restrict__ W, uint4* __restrict__ Wsw,
-                                                      int KT, int NTILES, size_t total, int K, int interleave_f) {
+                                                      int KT, int NTILES, size_t total, int K, int perm, int p0, int p1) {
   size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
   // destination order: [k-slice][row tile][k-step inside the slice][lane]
@@ -109,16 +126,15 @@ __global__ __launch_bounds__(256) void k_swizzle_bf16(const uint16_t* __restrict
   const int nt = (int)(rem / ks), kk = (int)(rem - (size_t)nt * ks);
   const int kt = s * SK + kk;
   const int r = lane & 15, g = lane >> 4;
-  size_t row = (size_t)nt * 16 + r;
-  if (interleave_f > 0) row = (size_t)((nt & 1) ? interleave_f : 0) + (size_t)(nt >> 1) * 16 + r;
+  const size_t row = perm_row(nt * 16 + r, perm, p0, p1);
   Wsw[idx] = *reinterpret_cast<const uint4*>(W + row * K + kt * 32 + g * 8);
 }
 
-void launch_swizzle_bf16(const uint16_t* W, uint4* Wsw, int N, int K, int interleave_f, hipStream_t st) {
+void launch_swizzle_bf16(const uint16_t* W, uint4* Wsw, int N, int K, int perm, int p0, int p1, hipStream_t st) {
   int KT = K / 32;
   size_t total = (size_t)(N / 16) * KT * 64;
   unsigned blocks = (unsigned)((total + 255) / 256);
-  hipLaunchKernelGGL(k_swizzle_bf16, dim3(blocks), dim3(256), 0, st, W, Wsw, KT, N / 16, total, K, interleave_f);
+  hipLaunchKernelGGL(k_swizzle_bf16, dim3(blocks), dim3(256), 0, st, W, Wsw, KT, N / 16, total, K, perm, p0, p1);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -171,6 +187,41 @@ __device__ __forceinline__ float4 slice_sum4(const float* partial, int S, size_t
   return a;
 }
 
+// The arithmetic of the epilogues lives in these helpers so that every GEMM variant produces the same bits.
+__device__ __forceinline__ float swiglu(float g, float u) {
+#pragma clang fp contract(off)
+  return g / (1.0f + expf(-g)) * u;
+}
+__device__ __forceinline__ float2 rope_rotate(float a, float b, float2 cs) {
+#pragma clang fp contract(off)
+  return make_float2(a * cs.x - b * cs.y, b * cs.x + a * cs.y);
+}
+// Row m, columns col and col+8 of the permuted QKV output (col & 15 < 8): a rotation pair of q or k, or two
+// plain values of v.  pos0 = position of row 0.
+__device__ __forceinline__ void qkv_pair(float a, float b, int m, int col, int d, int pos0, const GemmEpi& epi) {
+  const int p = pos0 + m;
+  if (p < 0) return;
+  const int hd = epi.hd, half = hd >> 1;
+  const int part = col / d, c = col - part * d;
+  const int h = c / hd, w = c - h * hd;
+  if (part == 2) {
+    _Float16* dst = epi.Vc + (size_t)h * epi.cap * hd;
+    store_kv(dst + v_cache_off(p, w, hd), a);
+    store_kv(dst + v_cache_off(p, w + 8, hd), b);
+    return;
+  }
+  const int e = (w >> 4) * 8 + (w & 7);
+  const float2 r = rope_rotate(a, b, epi.rope_cs[m * 64 + e]);
+  if (part == 0) {
+    epi.out[(size_t)m * d + h * hd + e] = r.x;
+    epi.out[(size_t)m * d + h * hd + e + half] = r.y;
+  } else {
+    _Float16* dst = epi.Kc + (size_t)h * epi.cap * hd;
+    store_kv(dst + k_cache_off(p, e, hd), r.x);
+    store_kv(dst + k_cache_off(p, e + half, hd), r.y);
+  }
+}
+
 // Epilogue of one column group [c0, c0+W) for all M rows, run by the 256 threads of one work-group.
 template <int ROLE, int W>
 __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M, int N, int c0, const GemmEpi& epi) {
@@ -202,57 +253,66 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
       if (idx < total && (idx & (PR - 1)) == 0) epi.ssq_out[m * gridDim.x + blockIdx.x] = ss;
     }
   } else if (ROLE == kRoleGateUp) {
-    // weight tiles alternate: even tile = 16 gate rows, odd tile = the 16 up rows of the same features
+    // tile t = 8 gate columns then the 8 up columns of features 8t..8t+7; a thread takes 4 features
     constexpr int PR = W / 8;
     const int f = N / 2;
     for (int idx = tid; idx < M * PR; idx += 256) {
       const int m = idx / PR, r = idx - m * PR;
-      const int q = r >> 2, cc = (r & 3) * 4;
-      const int gcol = c0 + 32 * q + cc;
+      const int gcol = c0 + 16 * (r >> 1) + 4 * (r & 1);
       if (gcol < N) {
         const float4 g = slice_sum4(partial, S, stride, (size_t)m * N + gcol);
-        const float4 u = slice_sum4(partial, S, stride, (size_t)m * N + gcol + 16);
-        float4 o;
-        o.x = g.x / (1.0f + expf(-g.x)) * u.x;
-        o.y = g.y / (1.0f + expf(-g.y)) * u.y;
-        o.z = g.z / (1.0f + expf(-g.z)) * u.z;
-        o.w = g.w / (1.0f + expf(-g.w)) * u.w;
-        *reinterpret_cast<float4*>(epi.out + (size_t)m * f + (c0 >> 1) + 16 * q + cc) = o;
+        const float4 u = slice_sum4(partial, S, stride, (size_t)m * N + gcol + 8);
+        const float4 o = make_float4(swiglu(g.x, u.x), swiglu(g.y, u.y), swiglu(g.z, u.z), swiglu(g.w, u.w));
+        *reinterpret_cast<float4*>(epi.out + (size_t)m * f + (gcol >> 4) * 8 + (gcol & 7)) = o;
       }
     }
   } else {   // kRoleQKV: rotate q and k, append k and v to the cache
-    const int d = N / 3, hd = epi.hd, half = hd >> 1;
     constexpr int PR = W / 2;
-    const int part = c0 / d, cp = c0 - part * d;
     const int pos0 = *epi.pos.base + epi.pos.offset;
     for (int idx = tid; idx < M * PR; idx += 256) {
       const int m = idx / PR, r = idx - m * PR;
-      const int hh = r / half, e = r - hh * half;
-      const int p = pos0 + m;
-      if (p < 0) continue;
-      const int colp = cp + hh * hd + e;            // column inside the part
-      const int h = colp / hd;
-      const float a = slice_sum(partial, S, stride, (size_t)m * N + c0 + hh * hd + e);
-      const float b = slice_sum(partial, S, stride, (size_t)m * N + c0 + hh * hd + e + half);
-      if (part == 2) {
-        _Float16* dst = epi.Vc + (size_t)h * epi.cap * hd;
-        store_kv(dst + v_cache_off(p, e, hd), a);
-        store_kv(dst + v_cache_off(p, e + half, hd), b);
-        continue;
-      }
-      const float2 cs = epi.rope_cs[m * 64 + e];
-      const float ra = a * cs.x - b * cs.y;
-      const float rb = b * cs.x + a * cs.y;
-      if (part == 0) {
-        epi.out[(size_t)m * d + colp] = ra;
-        epi.out[(size_t)m * d + colp + half] = rb;
-      } else {
-        _Float16* dst = epi.Kc + (size_t)h * epi.cap * hd;
-        store_kv(dst + k_cache_off(p, e, hd), ra);
-        store_kv(dst + k_cache_off(p, e + half, hd), rb);
+      const int col = c0 + 16 * (r >> 3) + (r & 7);
+      if (col < N) {
+        const float a = slice_sum(partial, S, stride, (size_t)m * N + col);
+        const float b = slice_sum(partial, S, stride, (size_t)m * N + col + 8);
+        qkv_pair(a, b, m, col, N / 3, pos0, epi);
       }
     }
   }
+}
+
+// 1/rms of the rows from the sum-of-squares partials: half a wave (32 lanes) per row, one partial per lane
+// and pass, so all loads of a row are in flight together; wave w takes the row pairs w, w+4, ...
+__device__ __forceinline__ void rows_rstd(const RowNorm& nrm, int M, int K, float* s_rstd) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int half = lane >> 5, pl = lane & 31;
+  for (int r0 = 2 * wave; r0 < M; r0 += 8) {
+    const int m = r0 + half;
+    float ss = 0.f;
+    if (m < M)
+      for (int p = pl; p < nrm.ssq_n; p += 32) ss += nrm.ssq_part[m * nrm.ssq_n + p];
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    if (pl == 0 && m < M) s_rstd[m] = 1.0f / sqrtf(ss / (float)K + nrm.eps);
+  }
+}
+
+// 8 consecutive x of one row -> (x * rstd * gain) -> bf16 high part and the bf16 of the remainder
+__device__ __forceinline__ void split_bf16x8(const float4& xa, const float4& xb, const float4& g0, const float4& g1,
+                                             float r, bool scale, uint4& hi, uint4& lo) {
+  float v[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+  if (scale) {
+    v[0] = v[0] * r * g0.x; v[1] = v[1] * r * g0.y; v[2] = v[2] * r * g0.z; v[3] = v[3] * r * g0.w;
+    v[4] = v[4] * r * g1.x; v[5] = v[5] * r * g1.y; v[6] = v[6] * r * g1.z; v[7] = v[7] * r * g1.w;
+  }
+  uint32_t hb[8], lb[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    hb[e] = bf16_bits_rne(v[e]);
+    lb[e] = bf16_bits_rne(v[e] - bf16_bits_to_float(hb[e]));
+  }
+  hi = make_uint4(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16), hb[4] | (hb[5] << 16), hb[6] | (hb[7] << 16));
+  lo = make_uint4(lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16), lb[4] | (lb[5] << 16), lb[6] | (lb[7] << 16));
 }
 
 template <int CT, int NT, int ROLE>
@@ -298,19 +358,8 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
     }
   }
 
-  // 1/rms of the rows from the sum-of-squares partials: half a wave (32 lanes) per row, one partial per lane
-  // and pass, so all loads of a row are in flight together; wave w takes the row pairs w, w+4, ...
   if (nrm.gain && nrm.ssq_part) {
-    const int half = lane >> 5, pl = lane & 31;
-    for (int r0 = 2 * wave; r0 < M; r0 += 8) {
-      const int m = r0 + half;
-      float ss = 0.f;
-      if (m < M)
-        for (int p = pl; p < nrm.ssq_n; p += 32) ss += nrm.ssq_part[m * nrm.ssq_n + p];
-#pragma unroll
-      for (int off = 16; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
-      if (pl == 0 && m < M) s_rstd[m] = 1.0f / sqrtf(ss / (float)K + nrm.eps);
-    }
+    rows_rstd(nrm, M, K, s_rstd);
     __syncthreads();
   }
 
@@ -321,21 +370,15 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
     const int m = min(w / kgs, 16 * CT - 1), kg = w - (w / kgs) * kgs;
     if (w < 16 * CT * kgs) {
       const float r = (nrm.gain && nrm.ssq_part && m < M) ? s_rstd[m] : 1.0f;
-      float v[8] = {xa[it].x, xa[it].y, xa[it].z, xa[it].w, xb[it].x, xb[it].y, xb[it].z, xb[it].w};
-      if (nrm.gain && m < M) {
+      float4 g0 = make_float4(1.f, 1.f, 1.f, 1.f), g1 = g0;
+      const bool scale = nrm.gain && m < M;
+      if (scale) {
         const float4* gp = reinterpret_cast<const float4*>(nrm.gain + k0 + kg * 8);
-        float4 g0 = gp[0], g1 = gp[1];
-        v[0] = v[0] * r * g0.x; v[1] = v[1] * r * g0.y; v[2] = v[2] * r * g0.z; v[3] = v[3] * r * g0.w;
-        v[4] = v[4] * r * g1.x; v[5] = v[5] * r * g1.y; v[6] = v[6] * r * g1.z; v[7] = v[7] * r * g1.w;
+        g0 = gp[0];
+        g1 = gp[1];
       }
-      uint32_t hb[8], lb[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        hb[e] = bf16_bits_rne(v[e]);
-        lb[e] = bf16_bits_rne(v[e] - bf16_bits_to_float(hb[e]));
-      }
-      uint4 hi = make_uint4(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16), hb[4] | (hb[5] << 16), hb[6] | (hb[7] << 16));
-      uint4 lo = make_uint4(lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16), lb[4] | (lb[5] << 16), lb[6] | (lb[7] << 16));
+      uint4 hi, lo;
+      split_bf16x8(xa[it], xb[it], g0, g1, r, scale, hi, lo);
       const int kt = kg >> 2, g = kg & 3, ct = m >> 4, j = m & 15;
       const int base = ((kt * CT + ct) * 2) * 64 + g * 16 + j;
       lds[base] = hi;
@@ -395,6 +438,184 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
   if (!last_arrival(&epi.counters[blockIdx.x], S, &s_last)) return;
   gemm_epilogue<ROLE, 64 * NT>(partial, S, M, N, blockIdx.x * 64 * NT, epi);
   if (tid == 0) epi.counters[blockIdx.x] = 0;   // ready for the next launch on this stream
+}
+
+// ---------------------------------------------------------------------------------------
+// The same GEMM for R <= 4 rows when the whole X block fits in LDS (K * R * 4 bytes): one work-group owns ONE
+// 16-row weight tile over the whole k range, its four waves split the 512-wide k chunks between them, the chunk
+// sums meet in LDS and the epilogue follows in the same work-group.  No partial sums in memory and no hand-off
+// between work-groups, so the tail of one work-group overlaps the streaming of the others.  Chunk boundaries,
+// the MFMA order inside a chunk and the order in which the chunk sums are added are those of the split-K
+// kernel: both give the same bits for a row.
+//   LDS: X high parts [K/8][R] uint4, X low parts [K/8][R] uint4, chunk sums float [chunks][R][16]
+// ---------------------------------------------------------------------------------------
+template <int R, int ROLE>
+__global__ __launch_bounds__(256) void k_gemm_bf16_rows(const uint4* __restrict__ Wsw, int NTILES,
+                                                        const float* __restrict__ X, int ldx, RowNorm nrm,
+                                                        int K, int N, GemmEpi epi) {
+  extern __shared__ uint4 lds[];
+  __shared__ float s_rstd[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tile = blockIdx.x;
+  const int KG = K >> 3;                                   // groups of 8 k per row
+  const int units_total = K / kUnitK;
+  const int nchunks = (units_total + kSliceUnits - 1) / kSliceUnits;
+  const int cpw = (nchunks + 3) >> 2;                      // chunks per wave
+  const int c_begin = min(wave * cpw, nchunks), c_end = min(nchunks, c_begin + cpw);
+  const int nu = min(units_total, c_end * kSliceUnits) - c_begin * kSliceUnits;   // this wave's units (<= 0: none)
+  constexpr int GP = 2;                                    // k groups per thread in the first pass: K <= 4096
+
+  // address of unit u of this wave: chunk c_begin + u/2 (= split-K slice), unit u%2 inside it
+  auto unit_ptr = [&](int u) {
+    const int c = c_begin + (u >> 1);
+    const int units_c = min(kSliceUnits, units_total - c * kSliceUnits);
+    return Wsw + (size_t)c * NTILES * (kSliceUnits * 8) * 64 + ((size_t)tile * units_c + (u & 1)) * 8 * 64 + lane;
+  };
+
+  // first pass over the X block: a thread takes all R rows of k group kg (the gain is per k, so it is fetched
+  // once).  These loads (x, gain, row statistics) go out before the weights, so they are not queued behind them.
+  float4 xa[GP][R], xb[GP][R], ga[GP], gb[GP];
+#pragma unroll
+  for (int j = 0; j < GP; ++j) {
+    const int kg = tid + 256 * j;
+    ga[j] = make_float4(1.f, 1.f, 1.f, 1.f);
+    gb[j] = ga[j];
+#pragma unroll
+    for (int m = 0; m < R; ++m) {
+      xa[j][m] = make_float4(0.f, 0.f, 0.f, 0.f);
+      xb[j][m] = xa[j][m];
+    }
+    if (kg < KG) {
+#pragma unroll
+      for (int m = 0; m < R; ++m) {
+        const float4* xp = reinterpret_cast<const float4*>(X + (size_t)m * ldx + kg * 8);
+        xa[j][m] = xp[0];
+        xb[j][m] = xp[1];
+      }
+      if (nrm.gain) {
+        const float4* gp = reinterpret_cast<const float4*>(nrm.gain + kg * 8);
+        ga[j] = gp[0];
+        gb[j] = gp[1];
+      }
+    }
+  }
+  if (nrm.gain && nrm.ssq_part) rows_rstd(nrm, R, K, s_rstd);
+
+  uint4 wb0[8], wb1[8];
+  if (nu > 0) {
+    const uint4* p = unit_ptr(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) wb0[i] = p[i * 64];
+  }
+  if (nu > 1) {
+    const uint4* p = unit_ptr(1);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) wb1[i] = p[i * 64];
+  }
+  __syncthreads();                                         // s_rstd
+
+  uint4* xhi = lds;
+  uint4* xlo = lds + KG * R;
+  float* csum = reinterpret_cast<float*>(lds + 2 * KG * R); // [chunk][R][16]
+  const bool scale = nrm.gain != nullptr;
+#pragma unroll
+  for (int j = 0; j < GP; ++j) {
+    const int kg = tid + 256 * j;
+    if (kg < KG) {
+#pragma unroll
+      for (int m = 0; m < R; ++m) {
+        const float r = (scale && nrm.ssq_part) ? s_rstd[m] : 1.0f;
+        uint4 hi, lo;
+        split_bf16x8(xa[j][m], xb[j][m], ga[j], gb[j], r, scale, hi, lo);
+        xhi[kg * R + m] = hi;
+        xlo[kg * R + m] = lo;
+      }
+    }
+  }
+  // further passes (K > 4096): same thing, loads and conversion back to back
+  for (int kg = 256 * GP + tid; kg < KG; kg += 256) {
+    float4 g0 = make_float4(1.f, 1.f, 1.f, 1.f), g1 = g0;
+    if (scale) {
+      const float4* gp = reinterpret_cast<const float4*>(nrm.gain + kg * 8);
+      g0 = gp[0];
+      g1 = gp[1];
+    }
+#pragma unroll
+    for (int m = 0; m < R; ++m) {
+      const float4* xp = reinterpret_cast<const float4*>(X + (size_t)m * ldx + kg * 8);
+      const float r = (scale && nrm.ssq_part) ? s_rstd[m] : 1.0f;
+      uint4 hi, lo;
+      split_bf16x8(xp[0], xp[1], g0, g1, r, scale, hi, lo);
+      xhi[kg * R + m] = hi;
+      xlo[kg * R + m] = lo;
+    }
+  }
+  __syncthreads();
+
+  // B fragment of lane l at k-step kt: row (l & 15) of X (lanes of rows >= R take row 0; their columns of the
+  // result are never read), k group kt*4 + (l >> 4)
+  const int bofs = (lane >> 4) * R + (((lane & 15) < R) ? (lane & 15) : 0);
+  auto mfma_unit = [&](const uint4 (&wb)[8], int u, f32x4& acc) {
+    const int kt0 = ((c_begin + (u >> 1)) * kSliceUnits + (u & 1)) * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, wb[i]);
+      const int idx = (kt0 + i) * 4 * R + bofs;
+      const bf16x8 bh = __builtin_bit_cast(bf16x8, xhi[idx]);
+      const bf16x8 bl = __builtin_bit_cast(bf16x8, xlo[idx]);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc, 0, 0, 0);
+    }
+  };
+  for (int u = 0; u < nu; u += 2) {                        // one chunk per pass
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    mfma_unit(wb0, u, acc);
+    if (u + 2 < nu) {
+      const uint4* p = unit_ptr(u + 2);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) wb0[i] = p[i * 64];
+    }
+    if (u + 1 < nu) {
+      mfma_unit(wb1, u + 1, acc);
+      if (u + 3 < nu) {
+        const uint4* p = unit_ptr(u + 3);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) wb1[i] = p[i * 64];
+      }
+    }
+    const int m = lane & 15;
+    if (m < R) {
+      float* dst = csum + (((c_begin + (u >> 1)) * R + m) << 4) + 4 * (lane >> 4);
+      dst[0] = acc[0]; dst[1] = acc[1]; dst[2] = acc[2]; dst[3] = acc[3];
+    }
+  }
+  __syncthreads();
+
+  // a thread takes row m, columns j and j+8 of the tile
+  if (tid < R * 8) {
+    const int m = tid >> 3, j = tid & 7;
+    float a = 0.f, b = 0.f;
+    for (int c = 0; c < nchunks; ++c) {
+      a += csum[((c * R + m) << 4) + j];
+      b += csum[((c * R + m) << 4) + j + 8];
+    }
+    const int col = tile * 16 + j;
+    if (ROLE == kRoleHead) {
+      epi.out[(size_t)m * N + col] = a;
+      epi.out[(size_t)m * N + col + 8] = b;
+    } else if (ROLE == kRoleGateUp) {
+      epi.out[(size_t)m * (N >> 1) + tile * 8 + j] = swiglu(a, b);
+    } else {
+      qkv_pair(a, b, m, col, N / 3, *epi.pos.base + epi.pos.offset, epi);
+    }
+  }
+}
+
+// LDS bytes of k_gemm_bf16_rows, or 0 if this shape does not take that path
+static size_t rows_path_lds(int role, int M, int K) {
+  if (M > 4 || !(role == kRoleQKV || role == kRoleGateUp || role == kRoleHead)) return 0;
+  const size_t bytes = (size_t)K * M * 4 + (size_t)gemm_slices(K, 1) * M * 16 * 4;
+  return bytes <= kRowsPathMaxLds ? bytes : 0;
 }
 
 // fp32 weights, row-major: one wave per output feature, lanes stride over k.
@@ -474,6 +695,21 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
   const int S = gemm_slices(K, 1);
   const int NTILES = N / 16, KT = K / 32;
   const uint4* Wsw = static_cast<const uint4*>(W);
+  if (const size_t rl = rows_path_lds(role, M, K)) {
+#define STAIRS_ROWS(r, role) \
+  hipLaunchKernelGGL((k_gemm_bf16_rows<r, role>), dim3(NTILES), dim3(256), rl, st, Wsw, NTILES, X, ldx, nrm, K, N, epi)
+#define STAIRS_ROWS_ROLE(role)           \
+  if (M <= 1) STAIRS_ROWS(1, role);      \
+  else if (M == 2) STAIRS_ROWS(2, role); \
+  else if (M == 3) STAIRS_ROWS(3, role); \
+  else STAIRS_ROWS(4, role)
+    if (role == kRoleQKV) { STAIRS_ROWS_ROLE(kRoleQKV); }
+    else if (role == kRoleGateUp) { STAIRS_ROWS_ROLE(kRoleGateUp); }
+    else { STAIRS_ROWS_ROLE(kRoleHead); }
+#undef STAIRS_ROWS_ROLE
+#undef STAIRS_ROWS
+    return;
+  }
   const int NT = pick_nt(role, NTILES, S, epi.hd);
   dim3 grid((NTILES + 4 * NT - 1) / (4 * NT), S), block(256);
   const int CT = (M <= 16) ? 1 : 2;
@@ -1129,6 +1365,25 @@ void launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st)
                      static_cast<const uint4*>(src), static_cast<uint4*>(dst), n);
 }
 
-hipError_t configure_kernels() { return hipSuccess; }
+hipError_t configure_kernels() {
+  hipError_t e = hipSuccess;
+  auto optin = [&](const void* fn) {
+    const hipError_t r = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRowsPathMaxLds);
+    if (r != hipSuccess) e = r;
+  };
+  optin((const void*)k_gemm_bf16_rows<4, kRoleQKV>);
+  optin((const void*)k_gemm_bf16_rows<4, kRoleGateUp>);
+  optin((const void*)k_gemm_bf16_rows<4, kRoleHead>);
+  optin((const void*)k_gemm_bf16_rows<3, kRoleQKV>);
+  optin((const void*)k_gemm_bf16_rows<3, kRoleGateUp>);
+  optin((const void*)k_gemm_bf16_rows<3, kRoleHead>);
+  optin((const void*)k_gemm_bf16_rows<2, kRoleQKV>);
+  optin((const void*)k_gemm_bf16_rows<2, kRoleGateUp>);
+  optin((const void*)k_gemm_bf16_rows<2, kRoleHead>);
+  optin((const void*)k_gemm_bf16_rows<1, kRoleQKV>);
+  optin((const void*)k_gemm_bf16_rows<1, kRoleGateUp>);
+  optin((const void*)k_gemm_bf16_rows<1, kRoleHead>);
+  return e;
+}
 
 }  // namespace stairs
