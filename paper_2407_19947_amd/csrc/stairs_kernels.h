@@ -10,10 +10,13 @@ namespace stairs {
 constexpr int kMaxRows = 32;        // rows (new tokens) one forward can take
 constexpr int kAttnChunk = 128;     // keys per attention work-group; boundaries are absolute positions
 constexpr int kSsqGroupF32 = 1024;  // residual columns per sum-of-squares partial, fp32 models
-constexpr int kSsqGroupBf16 = 128;  // ... bf16 models (= column group of the residual-writing GEMMs)
+constexpr int kSsqGroupBf16 = 16;   // ... bf16 models (= one weight tile of the residual-writing GEMMs)
 constexpr int kUnitK = 256;         // k extent of one weight "unit" (8 MFMA k-steps of 32)
 constexpr int kSliceUnits = 2;      // units per split-K slice (512 k)
-constexpr size_t kRowsPathMaxLds = 68 * 1024;   // most LDS the small-M GEMM (whole X block in LDS) may take per work-group
+// most LDS the small-M GEMM (whole X block in LDS) may take per work-group: projections with many weight tiles keep
+// two work-groups per CU, the residual-writing ones (one work-group per CU) take most of the CU's LDS
+constexpr size_t kRowsPathMaxLds = 68 * 1024;
+constexpr size_t kRowsPathMaxLdsWide = 150 * 1024;
 
 // Position of row 0 of a forward = *base + offset (base lives in device memory so that the
 // same launch sequence can be replayed without the host knowing the sequence length).

@@ -192,6 +192,11 @@ __device__ __forceinline__ float swiglu(float g, float u) {
 #pragma clang fp contract(off)
   return g / (1.0f + expf(-g)) * u;
 }
+// sum of squares of 4 adjacent residual values; a 16-column tile's partial is ((s0 + s1) + (s2 + s3)) of these
+__device__ __forceinline__ float sumsq4(float x, float y, float z, float w) {
+#pragma clang fp contract(off)
+  return (x * x + y * y) + (z * z + w * w);
+}
 __device__ __forceinline__ float2 rope_rotate(float a, float b, float2 cs) {
 #pragma clang fp contract(off)
   return make_float2(a * cs.x - b * cs.y, b * cs.x + a * cs.y);
@@ -234,7 +239,7 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
       if (col < N) *reinterpret_cast<float4*>(epi.out + (size_t)m * N + col) = slice_sum4(partial, S, stride, (size_t)m * N + col);
     }
   } else if (ROLE == kRoleWo || ROLE == kRoleDown) {
-    constexpr int PR = W / 4;                       // threads per row: a power of two <= 64
+    constexpr int PR = W / 4;                       // threads per row; 4 adjacent threads = one 16-column tile
     const int total = M * PR;
     for (int idx0 = 0; idx0 < total; idx0 += 256) {
       const int idx = idx0 + tid;
@@ -246,11 +251,11 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
         const float4 r = *xp;
         a.x += r.x; a.y += r.y; a.z += r.z; a.w += r.w;
         *xp = a;
-        ss = (a.x * a.x + a.y * a.y) + (a.z * a.z + a.w * a.w);
+        ss = sumsq4(a.x, a.y, a.z, a.w);
       }
-#pragma unroll
-      for (int off = PR / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
-      if (idx < total && (idx & (PR - 1)) == 0) epi.ssq_out[m * gridDim.x + blockIdx.x] = ss;
+      ss += __shfl_xor(ss, 1);
+      ss += __shfl_xor(ss, 2);
+      if (idx < total && col < N && (idx & 3) == 0) epi.ssq_out[m * (N >> 4) + (col >> 4)] = ss;
     }
   } else if (ROLE == kRoleGateUp) {
     // tile t = 8 gate columns then the 8 up columns of features 8t..8t+7; a thread takes 4 features
@@ -289,8 +294,15 @@ __device__ __forceinline__ void rows_rstd(const RowNorm& nrm, int M, int K, floa
   for (int r0 = 2 * wave; r0 < M; r0 += 8) {
     const int m = r0 + half;
     float ss = 0.f;
-    if (m < M)
-      for (int p = pl; p < nrm.ssq_n; p += 32) ss += nrm.ssq_part[m * nrm.ssq_n + p];
+    if (m < M) {
+      for (int p0 = pl; p0 < nrm.ssq_n; p0 += 256) {        // 8 loads in flight, added in index order
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (p0 + 32 * i < nrm.ssq_n) ? nrm.ssq_part[m * nrm.ssq_n + p0 + 32 * i] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ss += v[i];
+      }
+    }
 #pragma unroll
     for (int off = 16; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
     if (pl == 0 && m < M) s_rstd[m] = 1.0f / sqrtf(ss / (float)K + nrm.eps);
@@ -449,10 +461,12 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
 // kernel: both give the same bits for a row.
 //   LDS: X high parts [K/8][R] uint4, X low parts [K/8][R] uint4, chunk sums float [chunks][R][16]
 // ---------------------------------------------------------------------------------------
-template <int R, int ROLE>
-__global__ __launch_bounds__(256) void k_gemm_bf16_rows(const uint4* __restrict__ Wsw, int NTILES,
-                                                        const float* __restrict__ X, int ldx, RowNorm nrm,
-                                                        int K, int N, GemmEpi epi) {
+template <int R, int ROLE, int NW, int GP>
+__global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restrict__ Wsw, int NTILES,
+                                                            const float* __restrict__ X, int ldx, RowNorm nrm,
+                                                            int K, int N, GemmEpi epi) {
+  // NW waves; GP = k groups a thread takes in the first staging pass (covers K <= 8 * 64 * NW * GP)
+  constexpr int NTH = 64 * NW;
   extern __shared__ uint4 lds[];
   __shared__ float s_rstd[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -460,10 +474,9 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_rows(const uint4* __restrict_
   const int KG = K >> 3;                                   // groups of 8 k per row
   const int units_total = K / kUnitK;
   const int nchunks = (units_total + kSliceUnits - 1) / kSliceUnits;
-  const int cpw = (nchunks + 3) >> 2;                      // chunks per wave
+  const int cpw = (nchunks + NW - 1) / NW;                 // chunks per wave
   const int c_begin = min(wave * cpw, nchunks), c_end = min(nchunks, c_begin + cpw);
   const int nu = min(units_total, c_end * kSliceUnits) - c_begin * kSliceUnits;   // this wave's units (<= 0: none)
-  constexpr int GP = 2;                                    // k groups per thread in the first pass: K <= 4096
 
   // address of unit u of this wave: chunk c_begin + u/2 (= split-K slice), unit u%2 inside it
   auto unit_ptr = [&](int u) {
@@ -477,7 +490,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_rows(const uint4* __restrict_
   float4 xa[GP][R], xb[GP][R], ga[GP], gb[GP];
 #pragma unroll
   for (int j = 0; j < GP; ++j) {
-    const int kg = tid + 256 * j;
+    const int kg = tid + NTH * j;
     ga[j] = make_float4(1.f, 1.f, 1.f, 1.f);
     gb[j] = ga[j];
 #pragma unroll
@@ -517,10 +530,11 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_rows(const uint4* __restrict_
   uint4* xhi = lds;
   uint4* xlo = lds + KG * R;
   float* csum = reinterpret_cast<float*>(lds + 2 * KG * R); // [chunk][R][16]
+  float* sq = csum + nchunks * R * 16;                      // [R][16], residual-writing roles only
   const bool scale = nrm.gain != nullptr;
 #pragma unroll
   for (int j = 0; j < GP; ++j) {
-    const int kg = tid + 256 * j;
+    const int kg = tid + NTH * j;
     if (kg < KG) {
 #pragma unroll
       for (int m = 0; m < R; ++m) {
@@ -532,8 +546,8 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_rows(const uint4* __restrict_
       }
     }
   }
-  // further passes (K > 4096): same thing, loads and conversion back to back
-  for (int kg = 256 * GP + tid; kg < KG; kg += 256) {
+  // further passes (longer K): same thing, loads and conversion back to back
+  for (int kg = NTH * GP + tid; kg < KG; kg += NTH) {
     float4 g0 = make_float4(1.f, 1.f, 1.f, 1.f), g1 = g0;
     if (scale) {
       const float4* gp = reinterpret_cast<const float4*>(nrm.gain + kg * 8);
@@ -591,6 +605,27 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_rows(const uint4* __restrict_
   }
   __syncthreads();
 
+  if (ROLE == kRoleWo || ROLE == kRoleDown) {
+    // a thread takes one element of the tile; then one thread per row adds the 16 squares up in the order of
+    // the split-K kernel's epilogue
+    if (tid < R * 16) {
+      const int m = tid >> 4, n = tid & 15;
+      float a = 0.f;
+      for (int c = 0; c < nchunks; ++c) a += csum[((c * R + m) << 4) + n];
+      float* xp = epi.out + (size_t)m * N + tile * 16 + n;
+      a += *xp;
+      *xp = a;
+      sq[tid] = a;
+    }
+    __syncthreads();
+    if (tid < R) {
+      const float* q = sq + tid * 16;
+      const float s0 = sumsq4(q[0], q[1], q[2], q[3]), s1 = sumsq4(q[4], q[5], q[6], q[7]);
+      const float s2 = sumsq4(q[8], q[9], q[10], q[11]), s3 = sumsq4(q[12], q[13], q[14], q[15]);
+      epi.ssq_out[tid * (N >> 4) + tile] = (s0 + s1) + (s2 + s3);
+    }
+    return;
+  }
   // a thread takes row m, columns j and j+8 of the tile
   if (tid < R * 8) {
     const int m = tid >> 3, j = tid & 7;
@@ -611,10 +646,16 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_rows(const uint4* __restrict_
   }
 }
 
-// LDS bytes of k_gemm_bf16_rows, or 0 if this shape does not take that path
-static size_t rows_path_lds(int role, int M, int K) {
-  if (M > 4 || !(role == kRoleQKV || role == kRoleGateUp || role == kRoleHead)) return 0;
-  const size_t bytes = (size_t)K * M * 4 + (size_t)gemm_slices(K, 1) * M * 16 * 4;
+// LDS bytes of k_gemm_bf16_rows, or 0 if this shape does not take that path.  The residual-writing projections
+// have few weight tiles (N = d_model): they run one 8-wave work-group per CU and only when the tiles about
+// cover the chip.
+static size_t rows_path_lds(int role, int M, int N, int K) {
+  if (M > 4) return 0;
+  const size_t bytes = (size_t)K * M * 4 + (size_t)(gemm_slices(K, 1) + 1) * M * 16 * 4;
+  if (role == kRoleWo || role == kRoleDown) {
+    if (N / 16 < 192) return 0;
+    return bytes <= kRowsPathMaxLdsWide ? std::max(bytes, (size_t)81 * 1024) : 0;   // > half a CU's LDS: one per CU
+  }
   return bytes <= kRowsPathMaxLds ? bytes : 0;
 }
 
@@ -695,17 +736,20 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
   const int S = gemm_slices(K, 1);
   const int NTILES = N / 16, KT = K / 32;
   const uint4* Wsw = static_cast<const uint4*>(W);
-  if (const size_t rl = rows_path_lds(role, M, K)) {
-#define STAIRS_ROWS(r, role) \
-  hipLaunchKernelGGL((k_gemm_bf16_rows<r, role>), dim3(NTILES), dim3(256), rl, st, Wsw, NTILES, X, ldx, nrm, K, N, epi)
-#define STAIRS_ROWS_ROLE(role)           \
-  if (M <= 1) STAIRS_ROWS(1, role);      \
-  else if (M == 2) STAIRS_ROWS(2, role); \
-  else if (M == 3) STAIRS_ROWS(3, role); \
-  else STAIRS_ROWS(4, role)
-    if (role == kRoleQKV) { STAIRS_ROWS_ROLE(kRoleQKV); }
-    else if (role == kRoleGateUp) { STAIRS_ROWS_ROLE(kRoleGateUp); }
-    else { STAIRS_ROWS_ROLE(kRoleHead); }
+  if (const size_t rl = rows_path_lds(role, M, N, K)) {
+#define STAIRS_ROWS(r, role, nw, gp)                                                                                  \
+  hipLaunchKernelGGL((k_gemm_bf16_rows<r, role, nw, gp>), dim3(NTILES), dim3(64 * nw), rl, st, Wsw, NTILES, X, ldx, nrm, \
+                     K, N, epi)
+#define STAIRS_ROWS_ROLE(role, nw, gp)           \
+  if (M <= 1) STAIRS_ROWS(1, role, nw, gp);      \
+  else if (M == 2) STAIRS_ROWS(2, role, nw, gp); \
+  else if (M == 3) STAIRS_ROWS(3, role, nw, gp); \
+  else STAIRS_ROWS(4, role, nw, gp)
+    if (role == kRoleQKV) { STAIRS_ROWS_ROLE(kRoleQKV, 4, 2); }
+    else if (role == kRoleGateUp) { STAIRS_ROWS_ROLE(kRoleGateUp, 4, 2); }
+    else if (role == kRoleHead) { STAIRS_ROWS_ROLE(kRoleHead, 4, 2); }
+    else if (role == kRoleWo) { STAIRS_ROWS_ROLE(kRoleWo, 8, 1); }
+    else { STAIRS_ROWS_ROLE(kRoleDown, 8, 3); }
 #undef STAIRS_ROWS_ROLE
 #undef STAIRS_ROWS
     return;
@@ -844,7 +888,7 @@ void launch_fin_qkv_rope_f32(const float* partial, int S, int M, int d, int H, c
 // ---------------------------------------------------------------------------------------
 // embedding gather, rope table
 // ---------------------------------------------------------------------------------------
-// GW = residual columns per sum-of-squares partial: 1024 (one per block) or 128 (one per 32 lanes)
+// GW = residual columns per sum-of-squares partial: 1024 (one per block) or 16 (one per 4 lanes)
 template <typename E, int GW>
 __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const int* __restrict__ tokens, PosRef pos,
                                                int d, float* __restrict__ x, float* __restrict__ ssq_part, int ssq_n) {
@@ -865,9 +909,9 @@ __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const 
     ss = block_sum_256(ss, sm);
     if (threadIdx.x == 0) ssq_part[m * ssq_n + blockIdx.x] = ss;
   } else {
-#pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
-    if ((threadIdx.x & 31) == 0 && c < d) ssq_part[m * ssq_n + c / 128] = ss;
+    ss += __shfl_xor(ss, 1);
+    ss += __shfl_xor(ss, 2);
+    if ((threadIdx.x & 3) == 0 && c < d) ssq_part[m * ssq_n + c / 16] = ss;
   }
 }
 
@@ -876,7 +920,7 @@ void launch_embed(const void* emb, int emb_bf16, const int* tokens, PosRef pos, 
   dim3 grid((d + 1023) / 1024, M), block(256);
   const int sn = ssq_groups(d, emb_bf16);
   if (emb_bf16)
-    hipLaunchKernelGGL((k_embed<uint16_t, 128>), grid, block, 0, st, static_cast<const uint16_t*>(emb), tokens, pos, d, x, ssq_part, sn);
+    hipLaunchKernelGGL((k_embed<uint16_t, 16>), grid, block, 0, st, static_cast<const uint16_t*>(emb), tokens, pos, d, x, ssq_part, sn);
   else
     hipLaunchKernelGGL((k_embed<float, 1024>), grid, block, 0, st, static_cast<const float*>(emb), tokens, pos, d, x, ssq_part, sn);
 }
@@ -1367,22 +1411,21 @@ void launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st)
 
 hipError_t configure_kernels() {
   hipError_t e = hipSuccess;
-  auto optin = [&](const void* fn) {
-    const hipError_t r = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRowsPathMaxLds);
+  auto optin = [&](const void* fn, size_t bytes) {
+    const hipError_t r = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (r != hipSuccess) e = r;
   };
-  optin((const void*)k_gemm_bf16_rows<4, kRoleQKV>);
-  optin((const void*)k_gemm_bf16_rows<4, kRoleGateUp>);
-  optin((const void*)k_gemm_bf16_rows<4, kRoleHead>);
-  optin((const void*)k_gemm_bf16_rows<3, kRoleQKV>);
-  optin((const void*)k_gemm_bf16_rows<3, kRoleGateUp>);
-  optin((const void*)k_gemm_bf16_rows<3, kRoleHead>);
-  optin((const void*)k_gemm_bf16_rows<2, kRoleQKV>);
-  optin((const void*)k_gemm_bf16_rows<2, kRoleGateUp>);
-  optin((const void*)k_gemm_bf16_rows<2, kRoleHead>);
-  optin((const void*)k_gemm_bf16_rows<1, kRoleQKV>);
-  optin((const void*)k_gemm_bf16_rows<1, kRoleGateUp>);
-  optin((const void*)k_gemm_bf16_rows<1, kRoleHead>);
+#define STAIRS_OPTIN(r)                                                                        \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleQKV, 4, 2>, kRowsPathMaxLds);                    \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleGateUp, 4, 2>, kRowsPathMaxLds);                 \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleHead, 4, 2>, kRowsPathMaxLds);                   \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleWo, 8, 1>, kRowsPathMaxLdsWide);                 \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleDown, 8, 3>, kRowsPathMaxLdsWide)
+  STAIRS_OPTIN(1);
+  STAIRS_OPTIN(2);
+  STAIRS_OPTIN(3);
+  STAIRS_OPTIN(4);
+#undef STAIRS_OPTIN
   return e;
 }
 
