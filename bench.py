@@ -154,7 +154,9 @@ def main():
     ms_situ, bytes_gu = eng.time_kernel(8, M, ctx_mid, 4)
     ms_iso, _ = eng.time_kernel(0, M, 0, 4 * target.n_layers)
     achieved = bytes_gu / (ms_situ * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "k_gemm_bf16<1,2,2> (gate/up projection + SwiGLU, M = k+1 rows)",
+    kname = (f"k_gemm_bf16_rows<{M}, gate/up> (whole X block in LDS, one work-group per weight tile)" if M <= 4
+             else f"k_gemm_bf16<{1 if M <= 16 else 2}, 2, gate/up> (split-K with in-kernel hand-off)")
+    roofline = {"bound": "hbm", "kernel": kname + ": gate/up projection + SwiGLU at M = k+1 rows",
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                 "traffic": measured_traffic(), "bytes_per_launch": bytes_gu, "ms_per_launch": ms_situ,
                 "launches_timed": 4 * target.n_layers, "how": "in situ, inside whole verification forwards",
