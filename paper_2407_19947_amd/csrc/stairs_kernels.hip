@@ -1348,20 +1348,32 @@ void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv
 // ---------------------------------------------------------------------------------------
 // per-row vocabulary argmax (ties -> lowest index) and stairs validation
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits, int ld, int V, int* __restrict__ out,
-                                                PosRef out_pos) {
-  __shared__ float sv[4];
-  __shared__ int si[4];
+__global__ __launch_bounds__(1024) void k_argmax(const float* __restrict__ logits, int ld, int V, int* __restrict__ out,
+                                                 PosRef out_pos) {
+  __shared__ float sv[16];
+  __shared__ int si[16];
   const int r = blockIdx.x, tid = threadIdx.x;
   const float* row = logits + (size_t)r * ld;
   float best = -INFINITY;
   int bi = 0x7fffffff;
-  for (int v = tid * 4; v < V; v += 1024) {
-    const float4 x = *reinterpret_cast<const float4*>(row + v);
-    if (x.x > best || bi == 0x7fffffff) { best = x.x; bi = v; }
-    if (x.y > best) { best = x.y; bi = v + 1; }
-    if (x.z > best) { best = x.z; bi = v + 2; }
-    if (x.w > best) { best = x.w; bi = v + 3; }
+  // a thread walks its candidates in ascending index order, 8 loads in flight at a time
+  for (int v0 = tid * 4; v0 < V; v0 += 8 * 4096) {
+    float4 x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int v = v0 + 4096 * i;
+      x[i] = (v < V) ? *reinterpret_cast<const float4*>(row + v) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int v = v0 + 4096 * i;
+      if (v < V) {
+        if (x[i].x > best || bi == 0x7fffffff) { best = x[i].x; bi = v; }
+        if (x[i].y > best) { best = x[i].y; bi = v + 1; }
+        if (x[i].z > best) { best = x[i].z; bi = v + 2; }
+        if (x[i].w > best) { best = x[i].w; bi = v + 3; }
+      }
+    }
   }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
@@ -1372,7 +1384,7 @@ __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits
   if ((tid & 63) == 0) { sv[tid >> 6] = best; si[tid >> 6] = bi; }
   __syncthreads();
   if (tid == 0) {
-    for (int w = 1; w < 4; ++w)
+    for (int w = 1; w < 16; ++w)
       if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
     const int o = (out_pos.base ? *out_pos.base : 0) + out_pos.offset + r;
     out[o] = bi;
@@ -1380,7 +1392,7 @@ __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits
 }
 
 void launch_argmax(const float* logits, int ld, int V, int nrows, int* out, PosRef out_pos, hipStream_t st) {
-  hipLaunchKernelGGL(k_argmax, dim3(nrows), dim3(256), 0, st, logits, ld, V, out, out_pos);
+  hipLaunchKernelGGL(k_argmax, dim3(nrows), dim3(1024), 0, st, logits, ld, V, out, out_pos);
 }
 
 __global__ void k_accept(int* __restrict__ tokens, const int* __restrict__ tgt, int k, int* __restrict__ state) {
