@@ -259,9 +259,7 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
   do {                                                          \
     if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));  \
   } while (0)
-  launch_embed(m->tok_emb, b, c->tokens, pos, M, d, c->x, c->ssq, st);
-  SYNCPOINT();
-  launch_rope_table(pos, M, m->hd, g.rope_theta, c->rope_cs, st);
+  launch_embed(m->tok_emb, b, c->tokens, pos, M, d, c->x, c->ssq, m->hd, g.rope_theta, c->rope_cs, st);
   SYNCPOINT();
   const RowNorm none{nullptr, nullptr, 0, 0.f};
   for (int l = 0; l < g.n_layers; ++l) {

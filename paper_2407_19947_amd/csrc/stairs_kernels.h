@@ -82,9 +82,10 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
                  RowNorm nrm, float* partial, const GemmEpi& epi, hipStream_t st);
 
 // ---- small kernels ----------------------------------------------------------------------
-// x[m][:] = emb[tokens[pos+m]][:] (row of zeros if pos+m < 0), plus sum-of-squares partials
+// x[m][:] = emb[tokens[pos+m]][:] (row of zeros if pos+m < 0), plus sum-of-squares partials; the same launch
+// fills the rotation table cs of the M positions (see launch_rope_table)
 void launch_embed(const void* emb, int emb_bf16, const int* tokens, PosRef pos, int M, int d,
-                  float* x, float* ssq_part, hipStream_t st);
+                  float* x, float* ssq_part, int hd, float theta, float2* cs, hipStream_t st);
 // cs[m][i] = (cos, sin)((pos+m) * theta^(-2i/hd)), angle formed in double
 void launch_rope_table(PosRef pos, int M, int hd, float theta, float2* cs, hipStream_t st);
 // split-KV attention of M query rows at positions pos..pos+M-1 against keys 0..pos+M-1

@@ -889,12 +889,24 @@ void launch_fin_qkv_rope_f32(const float* partial, int S, int M, int d, int H, c
 // embedding gather, rope table
 // ---------------------------------------------------------------------------------------
 // GW = residual columns per sum-of-squares partial: 1024 (one per block) or 16 (one per 4 lanes)
+// The block column after the last embedding column fills the row's rotation table instead:
+// cs[m][i] = (cos, sin)(position * theta^(-2i/hd)), the angle formed in double.
 template <typename E, int GW>
 __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const int* __restrict__ tokens, PosRef pos,
-                                               int d, float* __restrict__ x, float* __restrict__ ssq_part, int ssq_n) {
+                                               int d, float* __restrict__ x, float* __restrict__ ssq_part, int ssq_n,
+                                               int hd, double theta, float2* __restrict__ cs) {
   __shared__ float sm[4];
-  const int c = (blockIdx.x * 256 + threadIdx.x) * 4, m = blockIdx.y;
+  const int m = blockIdx.y;
   const int p = *pos.base + pos.offset + m;
+  if (blockIdx.x == gridDim.x - 1) {
+    const int i = threadIdx.x;
+    if (i < hd / 2) {
+      const double ang = (double)p * pow(theta, -2.0 * (double)i / (double)hd);
+      cs[m * 64 + i] = make_float2((float)cos(ang), (float)sin(ang));
+    }
+    return;
+  }
+  const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
   float ss = 0.f;
   if (c < d) {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -916,13 +928,15 @@ __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const 
 }
 
 void launch_embed(const void* emb, int emb_bf16, const int* tokens, PosRef pos, int M, int d, float* x,
-                  float* ssq_part, hipStream_t st) {
-  dim3 grid((d + 1023) / 1024, M), block(256);
+                  float* ssq_part, int hd, float theta, float2* cs, hipStream_t st) {
+  dim3 grid((d + 1023) / 1024 + 1, M), block(256);
   const int sn = ssq_groups(d, emb_bf16);
   if (emb_bf16)
-    hipLaunchKernelGGL((k_embed<uint16_t, 16>), grid, block, 0, st, static_cast<const uint16_t*>(emb), tokens, pos, d, x, ssq_part, sn);
+    hipLaunchKernelGGL((k_embed<uint16_t, 16>), grid, block, 0, st, static_cast<const uint16_t*>(emb), tokens, pos, d, x,
+                       ssq_part, sn, hd, (double)theta, cs);
   else
-    hipLaunchKernelGGL((k_embed<float, 1024>), grid, block, 0, st, static_cast<const float*>(emb), tokens, pos, d, x, ssq_part, sn);
+    hipLaunchKernelGGL((k_embed<float, 1024>), grid, block, 0, st, static_cast<const float*>(emb), tokens, pos, d, x,
+                       ssq_part, sn, hd, (double)theta, cs);
 }
 
 __global__ void k_rope_table(PosRef pos, int hd, double theta, float2* __restrict__ cs) {
