@@ -72,7 +72,7 @@ struct stairs_ctx {
   struct IterGraph { int half, k, nch; hipGraphExec_t exec; };
   std::vector<IterGraph> graphs;   // captured iterations, see iteration_graph()
   std::vector<hipEvent_t> probe_ev;   // stairs_time_kernel(8): event pairs around one projection inside a forward
-  int probe_role = -1;               // role being timed in situ, -1 = none
+  int probe_role = -1;               // role being timed in situ, -1 = none, kProbeEmptyPair = calibration
   bool own_stream = false;
   bool use_graphs = true;      // env STAIRS_NO_GRAPH=1 turns replay off
   bool sync_launches = false;  // env STAIRS_SYNC_LAUNCHES=1: wait after every kernel (for counter-collecting profilers)
@@ -142,6 +142,7 @@ const char* check_weights(const stairs_model_cfg* m, const stairs_weights* w) {
   return nullptr;
 }
 
+constexpr int kProbeEmptyPair = 100;
 enum { KIND_EMB = 0, KIND_HEAD, KIND_NORM, KIND_QKV, KIND_WO, KIND_GU, KIND_DOWN };
 
 // Upload a matrix made of `nparts` row blocks (each [rows_each, K], host, model dtype) as one
@@ -288,6 +289,10 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     launch_gemm(kRoleWo, b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, e, st);
     SYNCPOINT();
     e.out = c->h;
+    if (c->probe_role == kProbeEmptyPair) {      // calibration: the pair with nothing between its two records
+      HIPCHK(c, hipEventRecord(c->probe_ev[2 * l], st));
+      HIPCHK(c, hipEventRecord(c->probe_ev[2 * l + 1], st));
+    }
     if (c->probe_role == kRoleGateUp) HIPCHK(c, hipEventRecord(c->probe_ev[2 * l], st));
     launch_gemm(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, RowNorm{ly.ffn_norm, c->ssq, sn, g.rms_eps}, c->partial, e, st);
     if (c->probe_role == kRoleGateUp) HIPCHK(c, hipEventRecord(c->probe_ev[2 * l + 1], st));
@@ -783,7 +788,7 @@ int stairs_copy_probe(int64_t bytes, int32_t reps, float* ms_per_launch, void* h
 int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len, int32_t reps, float* ms_per_launch,
                        double* bytes_per_launch) {
   if (!c) return STAIRS_EINVAL;
-  if (which < 0 || which > 8 || M < 1 || M > kMaxRows || reps < 1 || !ms_per_launch)
+  if (which < 0 || which > 9 || M < 1 || M > kMaxRows || reps < 1 || !ms_per_launch)
     return fail(c, STAIRS_EINVAL, "bad argument to stairs_time_kernel");
   if (c->pending_k >= 0) return fail(c, STAIRS_ESTATE, "a proposal is pending");
   if (which == 7 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
@@ -792,7 +797,7 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
   const int d = g.d_model, f = g.d_ffn, V = g.vocab, b = m->bf16 ? 1 : 0;
   const size_t esz = m->esz();
   if (which >= 5 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");
-  if (which == 8) {
+  if (which == 8 || which == 9) {
     // the gate/up projection timed where it really runs: `reps` whole forwards of M rows ending at position
     // ctx_len-1, an event pair around each layer's gate/up launch, all other kernels untouched in between
     const int nl = g.n_layers;
@@ -803,7 +808,7 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
     }
     double total_ms = 0;
     for (int r = 0; r <= reps; ++r) {              // r == 0: warm-up
-      c->probe_role = kRoleGateUp;
+      c->probe_role = which == 8 ? kRoleGateUp : kProbeEmptyPair;   // 9: what an event pair reads with no kernel inside
       int rc = forward(c, m, abs_pos(c, ctx_len - M), chunks_for(ctx_len), M, M);
       c->probe_role = -1;
       if (rc) return rc;
