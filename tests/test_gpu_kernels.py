@@ -20,7 +20,7 @@ BF16_SHAPES = [(16, 256), (48, 768), (2304, 768), (6144, 768), (768, 3072), (320
 
 
 @pytest.mark.parametrize("N,K", BF16_SHAPES)
-@pytest.mark.parametrize("M", [1, 2, 5, 16, 17, 32])
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 16, 17, 32])
 def test_gemm_bf16(N, K, M):
     print(f"gemm bf16 N={N} K={K} M={M}", flush=True)
     rng = np.random.default_rng([N, K, M])
@@ -55,3 +55,19 @@ def test_gemm_rows_do_not_depend_on_batch():
         for i in (0, 3, 16):
             assert np.array_equal(pkg.stairs_gemm_host(W, X[i:i + 1])[0], full[i])
         assert np.array_equal(pkg.stairs_gemm_host(W, X[:5]), full[:5])
+
+
+@pytest.mark.parametrize("K", [256, 768, 4096, 8192])
+def test_both_bf16_gemm_kernels_give_the_same_bits(K):
+    """Up to 4 rows take the kernel that keeps the whole activation block in LDS (when it fits: at K = 8192 only
+    1 and 2 rows do), more rows the split-K kernel: the first m rows of a 16-row and of a 32-row batch must equal
+    the m-row result bit for bit, whichever kernel computed it."""
+    rng = np.random.default_rng([7, K])
+    W = si.bf16_round(rng.standard_normal((272, K), dtype=np.float32) * np.float32(0.02))
+    X = rng.standard_normal((32, K), dtype=np.float32)
+    wide = pkg.stairs_gemm_host(W, X)
+    mid = pkg.stairs_gemm_host(W, X[:16])
+    assert np.array_equal(mid, wide[:16])
+    for m in (1, 2, 3, 4, 5):
+        assert np.array_equal(pkg.stairs_gemm_host(W, X[:m]), wide[:m]), m
+    assert np.array_equal(pkg.stairs_gemm_host(W, X[7:10]), wide[7:10])
