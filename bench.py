@@ -73,13 +73,13 @@ def cpu_baseline(w, target, draft, prompt, k, sample_P, sample_G):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="cfg4_7b")
     ap.add_argument("--k", default="auto", help="draft length (stair rows = k+1); 'auto' = the best of a short sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the verify-vs-k sweep and the per-kernel table")
-    ap.add_argument("--cpu-sample", default="64,8", help="prompt tokens, generated tokens of the CPU sample")
+    ap.add_argument("--cpu-sample", default="64,96", help="prompt tokens, generated tokens of the CPU sample")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -134,6 +134,8 @@ def main():
             f"accepted {st.accepted}, draft {st.ms_draft:.1f} ms, verify {st.ms_verify:.1f} ms")
     total = sum(decode_s)
     value = G * len(decode_s) / total
+    per_step = sorted(G / t for t in decode_s)
+    spread = {"median": per_step[len(per_step) // 2], "min": per_step[0], "max": per_step[-1]}
     # prefill, once, timed through generate()
     _, stg = eng.generate(prompt, 1, 0)
     prefill_ms = stg.ms_prefill
@@ -168,9 +170,13 @@ def main():
                 "net_of_event_overhead_frac": net / HBM_PEAK_GBPS,
                 "isolated_ms_per_launch": ms_iso, "isolated_GBps": bytes_gu / (ms_iso * 1e-3) / 1e9,
                 "isolated_frac": bytes_gu / (ms_iso * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    # second denominator: what a plain copy kernel (1 GiB read + 1 GiB written) streams on this machine
     copy_bytes = 1 << 30
     ms_copy = pkg.stairs_copy_probe(copy_bytes, 4)
-    extras = {"copy_probe_GBps": 2 * copy_bytes / (ms_copy * 1e-3) / 1e9}
+    copy_gbps = 2 * copy_bytes / (ms_copy * 1e-3) / 1e9
+    roofline["measured_stream_GBps"] = copy_gbps
+    roofline["frac_of_measured_stream"] = achieved / copy_gbps
+    extras = {"copy_probe_GBps": copy_gbps}
 
     if not args.no_sweep:
         names = {0: "gemm_gate_up", 1: "gemm_qkv", 2: "gemm_wo", 3: "gemm_down", 4: "gemm_lm_head", 5: "attention"}
@@ -196,6 +202,7 @@ def main():
         "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
         "config": {"workload": args.workload, "prompt_len": P, "generate": G, "k": k, "stair_rows": k + 1,
                    "target": w["target"], "draft": w["draft"], "timed_region": "decode phase (prefill excluded)"},
+        "tokens_per_s_over_steps": spread,
         "iterations_per_step": stats_last.iterations, "mean_tokens_per_iteration": G / stats_last.iterations,
         "accept_hist": list(stats_last.accept_hist)[:k + 1],
         "ms_draft_per_step": stats_last.ms_draft, "ms_verify_per_step": stats_last.ms_verify,
@@ -209,6 +216,7 @@ def main():
     if not args.no_cpu_baseline:
         sp, sg = (int(x) for x in args.cpu_sample.split(","))
         out["cpu_baseline"] = cpu_baseline(w, target, draft, prompt, k, min(sp, P), sg)
+        out["gpu_over_cpu_baseline"] = value / out["cpu_baseline"]["value"]
     print(json.dumps(out), flush=True)
 
 
