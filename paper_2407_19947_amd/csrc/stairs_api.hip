@@ -720,6 +720,7 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
   if (!b && dtype != STAIRS_DTYPE_FP32) return STAIRS_EINVAL;
   if (b ? (K % 256 || N % 16 || N / 64 + 1 > kGemmCounters) : (K % 4 || N % 4)) return STAIRS_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (configure_kernels() != hipSuccess) return STAIRS_EHIP;
   const size_t wbytes = (size_t)N * K * (b ? 2 : 4);
   const int S = gemm_slices(K, b);
   char *dW = nullptr, *dWs = nullptr;
