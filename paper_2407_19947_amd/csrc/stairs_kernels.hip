@@ -498,32 +498,60 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
       xa[j][m] = make_float4(0.f, 0.f, 0.f, 0.f);
       xb[j][m] = xa[j][m];
     }
-    if (kg < KG) {
+    // no condition around the loads (a k group past the end re-reads the last one and is dropped later): the
+    // compiler can then count them exactly and later waits do not have to cover the weight loads as well
+    const int kgc = min(kg, KG - 1);
 #pragma unroll
-      for (int m = 0; m < R; ++m) {
-        const float4* xp = reinterpret_cast<const float4*>(X + (size_t)m * ldx + kg * 8);
-        xa[j][m] = xp[0];
-        xb[j][m] = xp[1];
-      }
-      if (nrm.gain) {
-        const float4* gp = reinterpret_cast<const float4*>(nrm.gain + kg * 8);
-        ga[j] = gp[0];
-        gb[j] = gp[1];
-      }
+    for (int m = 0; m < R; ++m) {
+      const float4* xp = reinterpret_cast<const float4*>(X + (size_t)m * ldx + kgc * 8);
+      xa[j][m] = xp[0];
+      xb[j][m] = xp[1];
+    }
+    if (nrm.gain) {
+      const float4* gp = reinterpret_cast<const float4*>(nrm.gain + kgc * 8);
+      ga[j] = gp[0];
+      gb[j] = gp[1];
     }
   }
-  if (nrm.gain && nrm.ssq_part) rows_rstd(nrm, R, K, s_rstd);
-
-  uint4 wb0[8], wb1[8];
-  if (nu > 0) {
-    const uint4* p = unit_ptr(0);
+  // row statistics: half a wave per row (R <= 4 rows: waves 0 and 1).  The first 256 partials of the row are
+  // requested here, without conditions (indices clamped, values masked later), and added up after the weights
+  // have been requested, in the order rows_rstd uses.
+  const bool has_stats = nrm.gain && nrm.ssq_part;
+  const int st_row = 2 * wave + (lane >> 5), st_pl = lane & 31;
+  float sv[8];
+  if (has_stats) {
+    const float* sp = nrm.ssq_part + (size_t)min(st_row, R - 1) * nrm.ssq_n;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) wb0[i] = p[i * 64];
+    for (int i = 0; i < 8; ++i) sv[i] = sp[min(st_pl + 32 * i, nrm.ssq_n - 1)];
   }
-  if (nu > 1) {
-    const uint4* p = unit_ptr(1);
+
+  // the wave's first two weight units, again without conditions: a wave with fewer units (short K) loads a valid
+  // unit it will not use
+  uint4 wb0[8], wb1[8];
+  {
+    const uint4* p0 = (nu > 0) ? unit_ptr(0) : Wsw + (size_t)tile * min(kSliceUnits, units_total) * 8 * 64 + lane;
+    const uint4* p1 = (nu > 1) ? unit_ptr(1) : p0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) wb1[i] = p[i * 64];
+    for (int i = 0; i < 8; ++i) wb0[i] = p0[i * 64];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) wb1[i] = p1[i * 64];
+  }
+  if (has_stats && wave < 2) {                             // wave-uniform
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ss += (st_pl + 32 * i < nrm.ssq_n) ? sv[i] : 0.f;
+    if (st_row < R) {
+      for (int p0 = st_pl + 256; p0 < nrm.ssq_n; p0 += 256) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (p0 + 32 * i < nrm.ssq_n) ? nrm.ssq_part[st_row * nrm.ssq_n + p0 + 32 * i] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ss += v[i];
+      }
+    }
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    if (st_pl == 0 && st_row < R) s_rstd[st_row] = 1.0f / sqrtf(ss / (float)K + nrm.eps);
   }
   __syncthreads();                                         // s_rstd
 
