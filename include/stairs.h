@@ -142,6 +142,23 @@ int stairs_generate(stairs_ctx *ctx, const int32_t *prompt, int32_t P, int32_t G
  * proposal, k > 0 without a draft model), ECAPACITY. */
 int stairs_decode(stairs_ctx *ctx, int32_t G, int32_t k, int32_t *tokens_out, stairs_stats *stats);
 
+/* Several independent sequences in one context (a batch of stair batches): the k+1 stair rows of B sequences are
+ * scored by ONE forward of B*(k+1) rows, so the weights are streamed once for all of them; every sequence keeps its
+ * own key/value caches, length and acceptance (Sec. 3.3 applied per sequence), and each one's output is what
+ * stairs_generate gives for it alone.  stairs_reserve_batch makes room for up to max_batch sequences (caches and
+ * token arrays grow max_batch-fold; 1 <= max_batch <= STAIRS_MAX_ROWS / 2; bf16 models only) and drops the current
+ * sequence; call it once after stairs_init.  Errors: EINVAL, ENOMEM, EHIP. */
+int stairs_reserve_batch(stairs_ctx *ctx, int32_t max_batch);
+
+/* prompts: B host pointers, prompts[b] has P[b] tokens (lengths may differ).  Generates exactly G tokens for every
+ * sequence with draft length k (a sequence that has its G tokens stops taking part; the loop ends when all have):
+ * tokens_out is [B][G] row-major.  Requires B <= reserved batch, B * (k+1) <= STAIRS_MAX_ROWS, B * 2 <=
+ * STAIRS_MAX_ROWS, P[b] + G + k + 1 <= max_seq.  stats (optional): iterations = batched iterations, tokens = B * G,
+ * accepted / accept_hist summed over sequences.  Afterwards the context holds no current sequence for the
+ * single-sequence calls (stairs_prefill starts one).  Errors: EINVAL, ESTATE (k > 0 without a draft), ECAPACITY, EHIP. */
+int stairs_generate_batch(stairs_ctx *ctx, const int32_t *const *prompts, const int32_t *P, int32_t B, int32_t G,
+                          int32_t k, int32_t *tokens_out, stairs_stats *stats);
+
 /* Copy the current sequence (prompt + generated) into out[0..min(cap, len)); *len = length. */
 int stairs_get_tokens(stairs_ctx *ctx, int32_t *out, int32_t cap, int32_t *len);
 

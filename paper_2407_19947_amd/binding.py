@@ -17,7 +17,7 @@ DTYPE_FP32, DTYPE_BF16 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "stairs_strerror", "stairs_last_error", "stairs_init", "stairs_free", "stairs_prefill",
-    "draft_propose", "stairs_verify", "stairs_verify_tokens", "stairs_generate", "stairs_decode",
+    "draft_propose", "stairs_verify", "stairs_verify_tokens", "stairs_generate", "stairs_decode", "stairs_reserve_batch", "stairs_generate_batch",
     "stairs_get_tokens", "stairs_gemm_host", "stairs_time_kernel", "stairs_copy_probe",
 ]
 
@@ -94,6 +94,8 @@ def lib() -> C.CDLL:
     L.stairs_verify_tokens.argtypes = [vp, i32p, i32, i32p, i32p, vp]
     L.stairs_generate.argtypes = [vp, i32p, i32, i32, i32, i32p, C.POINTER(StairsStats)]
     L.stairs_decode.argtypes = [vp, i32, i32, i32p, C.POINTER(StairsStats)]
+    L.stairs_reserve_batch.argtypes = [vp, i32]
+    L.stairs_generate_batch.argtypes = [vp, C.POINTER(i32p), i32p, i32, i32, i32, i32p, C.POINTER(StairsStats)]
     L.stairs_get_tokens.argtypes = [vp, i32p, i32, i32p]
     L.stairs_gemm_host.argtypes = [i32, vp, f32p, f32p, i32, i32, i32, vp]
     L.stairs_time_kernel.argtypes = [vp, i32, i32, i32, i32, f32p, C.POINTER(C.c_double)]
@@ -226,6 +228,23 @@ def stairs_generate(ctx, prompt: Sequence[int], G: int, k: int):
     return out[:G], st
 
 
+def stairs_reserve_batch(ctx, max_batch: int):
+    _check(lib().stairs_reserve_batch(ctx, max_batch), "stairs_reserve_batch", ctx)
+
+
+def stairs_generate_batch(ctx, prompts: Sequence[Sequence[int]], G: int, k: int):
+    ps = [_i32(p) for p in prompts]
+    B = len(ps)
+    i32p = C.POINTER(C.c_int32)
+    ptrs = (i32p * max(B, 1))(*[_ptr(p, C.c_int32) for p in ps])
+    lens = np.array([len(p) for p in ps], np.int32)
+    out = np.zeros((max(B, 1), max(G, 1)), np.int32)
+    st = StairsStats()
+    _check(lib().stairs_generate_batch(ctx, ptrs, _ptr(lens, C.c_int32), B, G, k, _ptr(out, C.c_int32), C.byref(st)),
+           "stairs_generate_batch", ctx)
+    return out[:B, :G].copy() if G > 0 else np.zeros((B, 0), np.int32), st
+
+
 def stairs_decode(ctx, G: int, k: int):
     out = np.zeros(max(G, 1), np.int32)
     st = StairsStats()
@@ -306,6 +325,12 @@ class Stairs:
 
     def decode(self, G, k):
         return stairs_decode(self.ctx, G, k)
+
+    def reserve_batch(self, max_batch):
+        stairs_reserve_batch(self.ctx, max_batch)
+
+    def generate_batch(self, prompts, G, k):
+        return stairs_generate_batch(self.ctx, prompts, G, k)
 
     def tokens(self):
         return stairs_get_tokens(self.ctx)

@@ -34,7 +34,7 @@ struct Model {
   const void* lm_head = nullptr;    // GEMM layout
   const float* final_norm = nullptr;
   std::vector<Layer> layers;
-  char* Kc = nullptr;               // [layers][H][cap][hd]
+  char* Kc = nullptr;               // [slots][layers][H][cap][hd]
   char* Vc = nullptr;
   size_t kv_layer_bytes = 0;
   int valid = 0;                    // positions 0..valid-1 of the cache hold the current sequence
@@ -44,7 +44,8 @@ struct Model {
 }  // namespace
 
 constexpr int kGemmCounters = 2048;   // >= column groups of the widest GEMM (N / 64)
-constexpr int kCounters = kGemmCounters + 256;   // + one per attention head
+constexpr int kAttnCounters = 1024;                    // one per (sequence slot, attention head)
+constexpr int kCounters = kGemmCounters + kAttnCounters;
 
 struct stairs_ctx {
   hipStream_t st = nullptr;
@@ -58,18 +59,20 @@ struct stairs_ctx {
   float *partial = nullptr, *part_o = nullptr, *part_ml = nullptr;
   float2* rope_cs = nullptr;
   int nchunk_cap = 0;
-  int* tokens = nullptr;       // device copy of the sequence, capacity tok_cap
-  int tok_cap = 0;
+  int* tokens = nullptr;       // device copy of the sequence(s): [n_slots][tok_stride], capacity tok_cap each
+  int tok_cap = 0, tok_stride = 0;
+  int n_slots = 1;             // sequence slots the caches, token arrays and state hold (stairs_reserve_batch)
   int* counters = nullptr;     // [kCounters] split-K / attention hand-off tickets, zero between launches
   int* tgt_tok = nullptr;      // [kMaxRows]
-  int* state = nullptr;        // [0] = L, [1] = n of last iteration, [2] = constant 0
-  int* h_pinned = nullptr;     // pinned host: [0..1] state, [2..2+kMaxRows) target tokens
+  int* state = nullptr;        // per slot kSlotState ints: [0] = L, [1] = n of last iteration, [2] = constant 0, [3] = active
+  int* h_pinned = nullptr;     // pinned host: [0..1] state, [2..2+kMaxRows) target tokens; batch: [n_slots][kSlotState] state
+  int h_pinned_ints = 0;
   // host mirror
   int L = 0, P = 0;
   bool prefilled = false;
   int pending_k = -1;          // draft length of the outstanding proposal, -1 = none
   hipEvent_t ev[8] = {};       // 0,1: general; 5,6,7: iteration start / after the proposal / after validation
-  struct IterGraph { int half, k, nch; hipGraphExec_t exec; };
+  struct IterGraph { int half, k, nch, B; hipGraphExec_t exec; };   // B = 0: the single-sequence path
   std::vector<IterGraph> graphs;   // captured iterations, see iteration_graph()
   std::vector<hipEvent_t> probe_ev;   // stairs_time_kernel(8): event pairs around one projection inside a forward
   int probe_role = -1;               // role being timed in situ, -1 = none, kProbeEmptyPair = calibration
@@ -124,7 +127,7 @@ const char* check_cfg(const stairs_model_cfg* m) {
     if (m->d_model % 4 || m->d_ffn % 4 || m->vocab % 4) return "fp32 models need d_model, d_ffn, vocab multiples of 4";
   }
   if (!(m->rope_theta > 0.f) || !(m->rms_eps >= 0.f)) return "rope_theta must be > 0 and rms_eps >= 0";
-  if (std::max({m->vocab, 3 * m->d_model, 2 * m->d_ffn}) / 64 + 1 > kGemmCounters || m->n_heads > kCounters - kGemmCounters)
+  if (std::max({m->vocab, 3 * m->d_model, 2 * m->d_ffn}) / 64 + 1 > kGemmCounters || m->n_heads > kAttnCounters)
     return "model too wide for the hand-off counters";
   if (m->max_seq > 60000) return "max_seq above 60000 is not supported (attention merge table lives in LDS)";
   return nullptr;
@@ -249,7 +252,9 @@ size_t max_partial_floats(const stairs_model_cfg* m) {
 // nchunk = attention chunks to launch: >= ceil((pos + M) / kAttnChunk); extra ones find no keys.
 // logits_rows: 0 = no unembedding (prefill), 1 = last row only -> c->logits row 0,
 //              M = every row -> c->logits rows 0..M-1.
-int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows) {
+// Several sequences: pos.rps > 0 rows per slot, M = rps * (number of slots), slots 0..M/rps-1; otherwise the
+// rows belong to sequence slot `slot`.
+int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows, int slot = 0) {
   const stairs_model_cfg& g = m->cfg;
   const int d = g.d_model, f = g.d_ffn, H = g.n_heads, V = g.vocab;
   const int b = m->bf16 ? 1 : 0;
@@ -260,13 +265,20 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
   do {                                                          \
     if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));  \
   } while (0)
-  launch_embed(m->tok_emb, b, c->tokens, pos, M, d, c->x, c->ssq, m->hd, g.rope_theta, c->rope_cs, st);
+  const int nslots = pos.rps ? M / pos.rps : 1;
+  const int rows_per_slot = pos.rps ? pos.rps : M;
+  const size_t slot_bytes = (size_t)g.n_layers * m->kv_layer_bytes;
+  const size_t slot_off = pos.rps ? 0 : (size_t)slot * slot_bytes;
+  if (slot < 0 || slot >= c->n_slots || nslots > c->n_slots || nslots * H > kAttnCounters || (pos.rps && (M % pos.rps || !b)))
+    return fail(c, STAIRS_EINVAL, "forward: slots outside what the context holds");
+  launch_embed(m->tok_emb, b, c->tokens + (pos.rps ? 0 : (size_t)slot * c->tok_stride), pos.rps ? c->tok_stride : 0, pos, M, d,
+               c->x, c->ssq, m->hd, g.rope_theta, c->rope_cs, st);
   SYNCPOINT();
   const RowNorm none{nullptr, nullptr, 0, 0.f};
   for (int l = 0; l < g.n_layers; ++l) {
     const Layer& ly = m->layers[l];
-    char* Kl = m->Kc + l * m->kv_layer_bytes;
-    char* Vl = m->Vc + l * m->kv_layer_bytes;
+    char* Kl = m->Kc + slot_off + l * m->kv_layer_bytes;
+    char* Vl = m->Vc + slot_off + l * m->kv_layer_bytes;
     GemmEpi e{};
     e.counters = c->counters;
     e.rope_cs = c->rope_cs;
@@ -278,12 +290,13 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     e.cap = m->cap;
     e.H = H;
     e.hd = m->hd;
+    e.kv_slot_stride = slot_bytes / m->esz();
     e.ssq_out = c->ssq;
     e.out = c->q_rot;
     launch_gemm(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, RowNorm{ly.attn_norm, c->ssq, sn, g.rms_eps}, c->partial, e, st);
     SYNCPOINT();
-    launch_attention(c->q_rot, Kl, Vl, b, m->cap, d, H, M, pos, nchunk, c->nchunk_cap, c->part_o, c->part_ml,
-                     c->counters + kGemmCounters, c->attn_out, st);
+    launch_attention(c->q_rot, Kl, Vl, b, m->cap, d, H, rows_per_slot, pos, nslots, slot_bytes / m->esz(), nchunk,
+                     c->nchunk_cap, c->part_o, c->part_ml, c->counters + kGemmCounters, c->attn_out, st);
     SYNCPOINT();
     e.out = c->x;
     launch_gemm(kRoleWo, b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, e, st);
@@ -340,11 +353,11 @@ int enqueue_propose(stairs_ctx* c, int k, int nch) {
   // its argmax is d_1 -> tokens[L].  Steps 2..k: one row each.
   int rc = forward(c, m, rel_pos(c, -2), nch, 2, 1);
   if (rc) return rc;
-  launch_argmax(c->logits, V, V, 1, c->tokens, rel_pos(c, 0), c->st);
+  launch_argmax(c->logits, V, V, 1, 0, 1, c->tokens, rel_pos(c, 0), 0, c->st);
   for (int j = 1; j < k; ++j) {
     rc = forward(c, m, rel_pos(c, j - 1), nch, 1, 1);
     if (rc) return rc;
-    launch_argmax(c->logits, V, V, 1, c->tokens, rel_pos(c, j), c->st);
+    launch_argmax(c->logits, V, V, 1, 0, 1, c->tokens, rel_pos(c, j), 0, c->st);
   }
   HIPCHK(c, hipGetLastError());
   return STAIRS_OK;
@@ -356,8 +369,36 @@ int enqueue_verify(stairs_ctx* c, int k, int nch) {
   const int M = k + 1, V = m->cfg.vocab;
   int rc = forward(c, m, rel_pos(c, -1), nch, M, M);
   if (rc) return rc;
-  launch_argmax(c->logits, V, V, M, c->tgt_tok, PosRef{nullptr, 0}, c->st);
-  launch_accept(c->tokens, c->tgt_tok, k, c->state, c->st);
+  launch_argmax(c->logits, V, V, M, 0, 1, c->tgt_tok, PosRef{nullptr, 0}, 0, c->st);
+  launch_accept(c->tokens, c->tgt_tok, k, c->state, 1, 0, c->st);
+  HIPCHK(c, hipGetLastError());
+  return STAIRS_OK;
+}
+
+// The same two halves for B sequences at once: every forward holds the rows of all slots (2, then 1, then k+1 per
+// slot), positions, token arrays and caches are looked up per slot on the device.
+int enqueue_propose_batch(stairs_ctx* c, int B, int k, int nch) {
+  Model* m = &c->D;
+  const int V = m->cfg.vocab;
+  int rc = forward(c, m, PosRef{c->state, -2, 2}, nch, 2 * B, 2 * B);
+  if (rc) return rc;
+  launch_argmax(c->logits, V, V, B, 1, 2, c->tokens, PosRef{c->state, 0, 1}, c->tok_stride, c->st);   // each slot's 2nd row
+  for (int j = 1; j < k; ++j) {
+    rc = forward(c, m, PosRef{c->state, j - 1, 1}, nch, B, B);
+    if (rc) return rc;
+    launch_argmax(c->logits, V, V, B, 0, 1, c->tokens, PosRef{c->state, j, 1}, c->tok_stride, c->st);
+  }
+  HIPCHK(c, hipGetLastError());
+  return STAIRS_OK;
+}
+
+int enqueue_verify_batch(stairs_ctx* c, int B, int k, int nch) {
+  Model* m = &c->T;
+  const int M = k + 1, V = m->cfg.vocab;
+  int rc = forward(c, m, PosRef{c->state, -1, M}, nch, B * M, B * M);
+  if (rc) return rc;
+  launch_argmax(c->logits, V, V, B * M, 0, 1, c->tgt_tok, PosRef{nullptr, 0}, 0, c->st);
+  launch_accept(c->tokens, c->tgt_tok, k, c->state, B, c->tok_stride, c->st);
   HIPCHK(c, hipGetLastError());
   return STAIRS_OK;
 }
@@ -402,15 +443,16 @@ int do_verify(stairs_ctx* c, int k, int* n_out) {
 // The two halves of an iteration -- (0) the k draft steps, (1) stair batch + argmax + validation -- as HIP
 // graphs that are replayed while their launch shapes stay valid: positions come from the device, only the
 // attention grid (nch chunks, padded to a multiple of 4) bounds the sequence length a graph can serve.
-int iteration_graph(stairs_ctx* c, int half, int k, int nch, hipGraphExec_t* out) {
+int iteration_graph(stairs_ctx* c, int half, int k, int nch, hipGraphExec_t* out, int B = 0) {
   for (auto& g : c->graphs)
-    if (g.half == half && g.k == k && g.nch == nch) {
+    if (g.half == half && g.k == k && g.nch == nch && g.B == B) {
       *out = g.exec;
       return STAIRS_OK;
     }
   hipGraph_t graph = nullptr;
   HIPCHK(c, hipStreamBeginCapture(c->st, hipStreamCaptureModeThreadLocal));
-  const int rc = half == 0 ? enqueue_propose(c, k, nch) : enqueue_verify(c, k, nch);
+  const int rc = B ? (half == 0 ? enqueue_propose_batch(c, B, k, nch) : enqueue_verify_batch(c, B, k, nch))
+                   : (half == 0 ? enqueue_propose(c, k, nch) : enqueue_verify(c, k, nch));
   hipError_t e = hipStreamEndCapture(c->st, &graph);
   if (rc) {
     if (graph) (void)hipGraphDestroy(graph);
@@ -421,7 +463,7 @@ int iteration_graph(stairs_ctx* c, int half, int k, int nch, hipGraphExec_t* out
   e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
   (void)hipGraphDestroy(graph);
   HIPCHK(c, e);
-  c->graphs.push_back({half, k, nch, exec});
+  c->graphs.push_back({half, k, nch, B, exec});
   *out = exec;
   return STAIRS_OK;
 }
@@ -524,6 +566,7 @@ int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_wei
   if (have_draft) pf = std::max(pf, max_partial_floats(dcfg));
   c->nchunk_cap = (capmax + kAttnChunk - 1) / kAttnChunk;
   c->tok_cap = capmax;
+  c->tok_stride = capmax + kMaxRows;
   if ((rc = dev_alloc(c, &c->x, (size_t)kMaxRows * dmax)) || (rc = dev_alloc(c, &c->ssq, (size_t)kMaxRows * ssq_groups(dmax, 1))) ||
       (rc = dev_alloc(c, &c->q_rot, (size_t)kMaxRows * dmax)) || (rc = dev_alloc(c, &c->attn_out, (size_t)kMaxRows * dmax)) ||
       (rc = dev_alloc(c, &c->h, (size_t)kMaxRows * fmax)) || (rc = dev_alloc(c, &c->logits, (size_t)kMaxRows * tcfg->vocab)) ||
@@ -531,11 +574,12 @@ int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_wei
       (rc = dev_alloc(c, &c->part_o, (size_t)kMaxRows * Hmax * c->nchunk_cap * 128)) ||
       (rc = dev_alloc(c, &c->part_ml, (size_t)kMaxRows * Hmax * c->nchunk_cap * 2)) ||
       (rc = dev_alloc(c, &c->rope_cs, (size_t)kMaxRows * 64)) || (rc = dev_alloc(c, &c->tokens, (size_t)c->tok_cap + kMaxRows)) ||
-      (rc = dev_alloc(c, &c->tgt_tok, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->counters, (size_t)kCounters)) || (rc = dev_alloc(c, &c->state, 8)))
+      (rc = dev_alloc(c, &c->tgt_tok, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->counters, (size_t)kCounters)) || (rc = dev_alloc(c, &c->state, 2 * kSlotState)))
     return bail(rc);
-  if (hipMemsetAsync(c->state, 0, 8 * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
+  if (hipMemsetAsync(c->state, 0, 2 * kSlotState * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
   if (hipMemsetAsync(c->counters, 0, kCounters * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
-  if (hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), (2 + kMaxRows) * sizeof(int), hipHostMallocDefault) != hipSuccess) {
+  c->h_pinned_ints = 2 + kMaxRows;
+  if (hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), c->h_pinned_ints * sizeof(int), hipHostMallocDefault) != hipSuccess) {
     c->h_pinned = nullptr;
     return bail(STAIRS_ENOMEM);
   }
@@ -556,7 +600,7 @@ int stairs_prefill(stairs_ctx* c, const int32_t* prompt, int32_t P) {
   c->pending_k = -1;
   HIPCHK(c, hipMemsetAsync(c->counters, 0, kCounters * sizeof(int), c->st));
   HIPCHK(c, hipMemcpyAsync(c->tokens, prompt, (size_t)P * sizeof(int), hipMemcpyHostToDevice, c->st));
-  const int st3[3] = {P, 0, 0};
+  const int st3[kSlotState] = {P, 0, 0, 1};
   HIPCHK(c, hipMemcpyAsync(c->state, st3, sizeof(st3), hipMemcpyHostToDevice, c->st));
   HIPCHK(c, hipStreamSynchronize(c->st));     // st3 is on the stack
   c->L = c->P = P;
@@ -700,6 +744,177 @@ int stairs_generate(stairs_ctx* c, const int32_t* prompt, int32_t P, int32_t G, 
   stairs_stats s;
   if ((rc = stairs_decode(c, G, k, tokens_out, &s))) return rc;
   s.ms_prefill = ms_prefill;
+  if (stats) *stats = s;
+  return STAIRS_OK;
+}
+
+int stairs_reserve_batch(stairs_ctx* c, int32_t max_batch) {
+  if (!c) return STAIRS_EINVAL;
+  if (max_batch < 1 || max_batch > kMaxRows / 2) return fail(c, STAIRS_EINVAL, "max_batch outside [1, STAIRS_MAX_ROWS / 2]");
+  if (!c->T.bf16 || (c->have_draft && !c->D.bf16)) return fail(c, STAIRS_EINVAL, "several sequences need bf16 models");
+  if (max_batch * std::max(c->T.cfg.n_heads, c->have_draft ? c->D.cfg.n_heads : 0) > kAttnCounters)
+    return fail(c, STAIRS_EINVAL, "max_batch * n_heads exceeds the attention hand-off counters");
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  c->prefilled = false;
+  c->pending_k = -1;
+  if (max_batch <= c->n_slots) return STAIRS_OK;
+  // new, larger arrays; the old ones are released
+  auto release = [&](void* p) {
+    auto it = std::find(c->owned.begin(), c->owned.end(), p);
+    if (it != c->owned.end()) c->owned.erase(it);
+    (void)hipFree(p);
+  };
+  int rc;
+  for (Model* m : {&c->T, &c->D}) {
+    if (m == &c->D && !c->have_draft) continue;
+    const size_t bytes = (size_t)max_batch * m->cfg.n_layers * m->kv_layer_bytes;
+    char *K = nullptr, *V = nullptr;
+    if ((rc = dev_alloc(c, &K, bytes)) || (rc = dev_alloc(c, &V, bytes))) return rc;
+    HIPCHK(c, hipMemsetAsync(K, 0, bytes, c->st));
+    HIPCHK(c, hipMemsetAsync(V, 0, bytes, c->st));
+    release(m->Kc);
+    release(m->Vc);
+    m->Kc = K;
+    m->Vc = V;
+    m->valid = 0;
+  }
+  int *tok = nullptr, *state = nullptr;
+  if ((rc = dev_alloc(c, &tok, (size_t)max_batch * c->tok_stride)) || (rc = dev_alloc(c, &state, (size_t)(max_batch + 1) * kSlotState)))
+    return rc;
+  HIPCHK(c, hipMemsetAsync(tok, 0, (size_t)max_batch * c->tok_stride * sizeof(int), c->st));
+  HIPCHK(c, hipMemsetAsync(state, 0, (size_t)(max_batch + 1) * kSlotState * sizeof(int), c->st));
+  release(c->tokens);
+  release(c->state);
+  c->tokens = tok;
+  c->state = state;
+  int* hp = nullptr;
+  const int ints = std::max(2 + kMaxRows, max_batch * kSlotState);
+  if (hipHostMalloc(reinterpret_cast<void**>(&hp), ints * sizeof(int), hipHostMallocDefault) != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(c, STAIRS_ENOMEM, "hipHostMalloc failed");
+  }
+  (void)hipHostFree(c->h_pinned);
+  c->h_pinned = hp;
+  c->h_pinned_ints = ints;
+  // captured graphs hold the old pointers
+  for (auto& g : c->graphs) (void)hipGraphExecDestroy(g.exec);
+  c->graphs.clear();
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  c->n_slots = max_batch;
+  return STAIRS_OK;
+}
+
+int stairs_generate_batch(stairs_ctx* c, const int32_t* const* prompts, const int32_t* P, int32_t B, int32_t G, int32_t k,
+                          int32_t* tokens_out, stairs_stats* stats) {
+  if (!c) return STAIRS_EINVAL;
+  if (B < 1 || B > c->n_slots) return fail(c, STAIRS_EINVAL, "B outside [1, reserved batch]");
+  if (G < 0 || (G > 0 && !tokens_out)) return fail(c, STAIRS_EINVAL, "G < 0 or tokens_out is NULL");
+  if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
+  if (k > 0 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
+  if (B * (k + 1) > kMaxRows || B * 2 > kMaxRows) return fail(c, STAIRS_EINVAL, "B * (k + 1) exceeds STAIRS_MAX_ROWS");
+  if (!c->T.bf16 || (c->have_draft && !c->D.bf16)) return fail(c, STAIRS_EINVAL, "several sequences need bf16 models");
+  if (!prompts || !P) return fail(c, STAIRS_EINVAL, "prompts or P is NULL");
+  for (int b = 0; b < B; ++b) {
+    if (!prompts[b] || P[b] < 1) return fail(c, STAIRS_EINVAL, "a prompt is NULL or empty");
+    for (int i = 0; i < P[b]; ++i)
+      if (prompts[b][i] < 0 || prompts[b][i] >= c->T.cfg.vocab) return fail(c, STAIRS_EINVAL, "prompt token outside the vocabulary");
+    // a slot that has its G tokens stops, so it never goes past P + G + k
+    if (!capacity_ok(c, P[b] + G + k + 1)) return fail(c, STAIRS_ECAPACITY, "P + G + k + 1 exceeds max_seq");
+  }
+  stairs_stats s;
+  memset(&s, 0, sizeof(s));
+  c->prefilled = false;            // the single-sequence state (slot 0) is overwritten
+  c->pending_k = -1;
+  int rc;
+  HIPCHK(c, hipMemsetAsync(c->counters, 0, kCounters * sizeof(int), c->st));
+  HIPCHK(c, hipEventRecord(c->ev[0], c->st));
+  std::vector<int> L(B), L0(B), hstate((size_t)B * kSlotState);
+  std::vector<char> active(B, 1);
+  for (int b = 0; b < B; ++b) {
+    HIPCHK(c, hipMemcpyAsync(c->tokens + (size_t)b * c->tok_stride, prompts[b], (size_t)P[b] * sizeof(int), hipMemcpyHostToDevice, c->st));
+    L[b] = L0[b] = P[b];
+    hstate[b * kSlotState + 0] = P[b];
+    hstate[b * kSlotState + 1] = 0;
+    hstate[b * kSlotState + 2] = 0;
+    hstate[b * kSlotState + 3] = G > 0 ? 1 : 0;
+    active[b] = G > 0;
+  }
+  HIPCHK(c, hipMemcpyAsync(c->state, hstate.data(), hstate.size() * sizeof(int), hipMemcpyHostToDevice, c->st));
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  // prompt ingestion, one sequence at a time (rows of one slot per forward)
+  for (int b = 0; b < B; ++b)
+    for (Model* m : {&c->T, &c->D}) {
+      if (m == &c->D && !c->have_draft) continue;
+      for (int p = 0; p < P[b] - 1; p += kMaxRows) {
+        const int M = std::min(kMaxRows, P[b] - 1 - p);
+        if ((rc = forward(c, m, abs_pos(c, p), chunks_for(p + M), M, 0, b))) return rc;
+      }
+    }
+  c->T.valid = c->D.valid = 0;     // nothing the single-sequence calls could rely on
+  HIPCHK(c, hipEventRecord(c->ev[1], c->st));
+  int n_active = G > 0 ? B : 0;
+  while (n_active > 0) {
+    int Lmax = 0;
+    for (int b = 0; b < B; ++b)
+      if (active[b]) Lmax = std::max(Lmax, L[b]);
+    HIPCHK(c, hipEventRecord(c->ev[5], c->st));
+    if (c->use_graphs) {
+      const int nch = std::min((chunks_for(Lmax + k) + 3) / 4 * 4, c->nchunk_cap);
+      hipGraphExec_t gp = nullptr, gv = nullptr;
+      if (k > 0 && (rc = iteration_graph(c, 0, k, nch, &gp, B))) return rc;
+      if ((rc = iteration_graph(c, 1, k, nch, &gv, B))) return rc;
+      if (k > 0) HIPCHK(c, hipGraphLaunch(gp, c->st));
+      HIPCHK(c, hipEventRecord(c->ev[6], c->st));
+      HIPCHK(c, hipGraphLaunch(gv, c->st));
+    } else {
+      if (k > 0 && (rc = enqueue_propose_batch(c, B, k, chunks_for(Lmax + k - 1)))) return rc;
+      HIPCHK(c, hipEventRecord(c->ev[6], c->st));
+      if ((rc = enqueue_verify_batch(c, B, k, chunks_for(Lmax + k)))) return rc;
+    }
+    HIPCHK(c, hipEventRecord(c->ev[7], c->st));
+    HIPCHK(c, hipMemcpyAsync(c->h_pinned, c->state, (size_t)B * kSlotState * sizeof(int), hipMemcpyDeviceToHost, c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    bool any_done = false;
+    for (int b = 0; b < B; ++b) {
+      if (!active[b]) continue;
+      const int n = c->h_pinned[b * kSlotState + 1];
+      if (c->h_pinned[b * kSlotState] != L[b] + n + 1 || n < 0 || n > k) return fail(c, STAIRS_EHIP, "device state out of sync with host");
+      L[b] += n + 1;
+      s.accepted += n;
+      s.accept_hist[n] += 1;
+      if (L[b] - L0[b] >= G) {
+        active[b] = 0;
+        --n_active;
+        any_done = true;
+      }
+    }
+    if (any_done) {                                   // finished slots stop: their rows get no position any more
+      for (int b = 0; b < B; ++b) {
+        hstate[b * kSlotState + 0] = L[b];
+        hstate[b * kSlotState + 3] = active[b];
+      }
+      // only the active flags change on the device (L is already there)
+      for (int b = 0; b < B; ++b)
+        if (!active[b])
+          HIPCHK(c, hipMemcpyAsync(c->state + b * kSlotState + 3, &hstate[b * kSlotState + 3], sizeof(int), hipMemcpyHostToDevice, c->st));
+      HIPCHK(c, hipStreamSynchronize(c->st));
+    }
+    float a = 0.f, bms = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&a, c->ev[5], c->ev[6]));
+    HIPCHK(c, hipEventElapsedTime(&bms, c->ev[6], c->ev[7]));
+    s.ms_draft += a;
+    s.ms_verify += bms;
+    s.iterations += 1;
+  }
+  HIPCHK(c, hipEventRecord(c->ev[2], c->st));
+  HIPCHK(c, hipEventSynchronize(c->ev[2]));
+  HIPCHK(c, hipEventElapsedTime(&s.ms_prefill, c->ev[0], c->ev[1]));
+  HIPCHK(c, hipEventElapsedTime(&s.ms_decode, c->ev[1], c->ev[2]));
+  s.tokens = B * G;
+  for (int b = 0; b < B && G > 0; ++b)
+    HIPCHK(c, hipMemcpyAsync(tokens_out + (size_t)b * G, c->tokens + (size_t)b * c->tok_stride + L0[b], (size_t)G * sizeof(int),
+                             hipMemcpyDeviceToHost, c->st));
+  HIPCHK(c, hipStreamSynchronize(c->st));
   if (stats) *stats = s;
   return STAIRS_OK;
 }
@@ -867,7 +1082,7 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
         }
         default: {
           const size_t off = (size_t)(r % g.n_layers) * m->kv_layer_bytes;
-          launch_attention(c->q_rot, m->Kc + off, m->Vc + off, b, m->cap, d, g.n_heads, M, abs_pos(c, ctx_len - M),
+          launch_attention(c->q_rot, m->Kc + off, m->Vc + off, b, m->cap, d, g.n_heads, M, abs_pos(c, ctx_len - M), 1, 0,
                            (ctx_len + kAttnChunk - 1) / kAttnChunk, c->nchunk_cap, c->part_o, c->part_ml,
                            c->counters + kGemmCounters, c->attn_out, c->st);
           bytes = 2.0 * ctx_len * d * esz;

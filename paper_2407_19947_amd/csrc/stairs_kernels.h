@@ -18,12 +18,26 @@ constexpr int kSliceUnits = 2;      // units per split-K slice (512 k)
 constexpr size_t kRowsPathMaxLds = 68 * 1024;
 constexpr size_t kRowsPathMaxLdsWide = 150 * 1024;
 
-// Position of row 0 of a forward = *base + offset (base lives in device memory so that the
-// same launch sequence can be replayed without the host knowing the sequence length).
+// Where the rows of a forward sit.  One sequence (rps == 0): row r is at position *base + offset + r (base lives
+// in device memory so that the same launch sequence can be replayed without the host knowing the sequence length).
+// Several sequences ("slots", rps > 0): the forward holds rps consecutive rows per slot; slot s = r / rps keeps its
+// state in base[s * kSlotState + ...] = {L, n of the last iteration, 0, active}; row r is at position
+// L_s + offset + r % rps, or nowhere (negative) when the slot is not active.
+constexpr int kSlotState = 4;
 struct PosRef {
   const int* base;
   int offset;
+  int rps;
 };
+#ifdef __HIPCC__
+__device__ __forceinline__ int slot_of(const PosRef& p, int r) { return p.rps ? r / p.rps : 0; }
+__device__ __forceinline__ int pos_of(const PosRef& p, int r) {
+  if (!p.rps) return *p.base + p.offset + r;
+  const int s = r / p.rps;
+  const int* st = p.base + s * kSlotState;
+  return st[3] ? st[0] + p.offset + (r - s * p.rps) : -(1 << 24);
+}
+#endif
 
 // Row normalisation folded into a GEMM prologue: x[m][k] * gain[k] * rstd[m] with
 // rstd[m] = 1/sqrt(sum_p ssq_part[m*ssq_n + p] / K + eps).  gain == nullptr: no scaling at all.
@@ -73,6 +87,7 @@ struct GemmEpi {
   float* Kc32;              // fp32 models: float caches of this layer, [H][cap][hd]
   float* Vc32;
   int cap, H, hd;
+  size_t kv_slot_stride;    // elements between the caches of consecutive slots (several sequences), else unused
 };
 
 // ---- skinny GEMM + epilogue ---------------------------------------------------------------
@@ -84,20 +99,26 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
 // ---- small kernels ----------------------------------------------------------------------
 // x[m][:] = emb[tokens[pos+m]][:] (row of zeros if pos+m < 0), plus sum-of-squares partials; the same launch
 // fills the rotation table cs of the M positions (see launch_rope_table)
-void launch_embed(const void* emb, int emb_bf16, const int* tokens, PosRef pos, int M, int d,
+void launch_embed(const void* emb, int emb_bf16, const int* tokens, int tok_slot_stride, PosRef pos, int M, int d,
                   float* x, float* ssq_part, int hd, float theta, float2* cs, hipStream_t st);
 // cs[m][i] = (cos, sin)((pos+m) * theta^(-2i/hd)), angle formed in double
 void launch_rope_table(PosRef pos, int M, int hd, float theta, float2* cs, hipStream_t st);
 // split-KV attention of M query rows at positions pos..pos+M-1 against keys 0..pos+M-1
-// (kv_half: half caches in the tiled layout; else float caches [H][cap][hd]); counters: one int per head
-void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv_half, int cap, int d,
-                      int H, int M, PosRef pos, int nchunk_launch, int nchunk_cap, float* part_o,
+// (kv_half: half caches in the tiled layout; else float caches [H][cap][hd]); counters: one int per (slot, head).
+// Several sequences (pos.rps > 0, half caches only): M = pos.rps rows per slot, nslots slots, caches kv_slot_stride
+// elements apart.
+void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv_half, int cap, int d, int H, int M,
+                      PosRef pos, int nslots, size_t kv_slot_stride, int nchunk_launch, int nchunk_cap, float* part_o,
                       float* part_ml, int* counters, float* out, hipStream_t st);
-// out[out_pos + r] = argmax_v logits[r][v], ties -> lowest v; out_pos = *pos.base + pos.offset
-void launch_argmax(const float* logits, int ld, int V, int nrows, int* out, PosRef out_pos, hipStream_t st);
-// stairs validation on device: state[0] = L (sequence length). n = longest run with
-// tokens[L+i] == tgt[i]; tokens[L+n] = tgt[n]; state[0] = L+n+1; state[1] = n.
-void launch_accept(int* tokens, const int* tgt, int k, int* state, hipStream_t st);
+// out[o(r)] = argmax_v logits[row0 + r * row_stride][v], ties -> lowest v, r < nrows.  One sequence:
+// o(r) = *out_pos.base + out_pos.offset + r (base == nullptr: r).  Several: o(r) = s * out_slot_stride + position of
+// out_pos for row r, nothing written for a slot that is not active.
+void launch_argmax(const float* logits, int ld, int V, int nrows, int row0, int row_stride, int* out, PosRef out_pos,
+                   int out_slot_stride, hipStream_t st);
+// stairs validation on device, one block per slot s (one sequence: nslots = 1, strides unused): state = {L, n, 0,
+// active}.  n = longest run with tokens[L+i] == tgt[i]; tokens[L+n] = tgt[n]; state[0] = L+n+1; state[1] = n.
+// tokens of slot s start at s * tok_slot_stride, its tgt at s * (k+1), its state at s * kSlotState.
+void launch_accept(int* tokens, const int* tgt, int k, int* state, int nslots, int tok_slot_stride, hipStream_t st);
 
 // dst[0..bytes) = src[0..bytes), bytes a multiple of 16: reads `bytes` and writes `bytes` of HBM
 void launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);

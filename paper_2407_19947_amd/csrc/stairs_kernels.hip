@@ -203,14 +203,15 @@ __device__ __forceinline__ float2 rope_rotate(float a, float b, float2 cs) {
 }
 // Row m, columns col and col+8 of the permuted QKV output (col & 15 < 8): a rotation pair of q or k, or two
 // plain values of v.  pos0 = position of row 0.
-__device__ __forceinline__ void qkv_pair(float a, float b, int m, int col, int d, int pos0, const GemmEpi& epi) {
-  const int p = pos0 + m;
+__device__ __forceinline__ void qkv_pair(float a, float b, int m, int col, int d, const GemmEpi& epi) {
+  const int p = pos_of(epi.pos, m);
   if (p < 0) return;
+  const size_t slot_off = (size_t)slot_of(epi.pos, m) * epi.kv_slot_stride;
   const int hd = epi.hd, half = hd >> 1;
   const int part = col / d, c = col - part * d;
   const int h = c / hd, w = c - h * hd;
   if (part == 2) {
-    _Float16* dst = epi.Vc + (size_t)h * epi.cap * hd;
+    _Float16* dst = epi.Vc + slot_off + (size_t)h * epi.cap * hd;
     store_kv(dst + v_cache_off(p, w, hd), a);
     store_kv(dst + v_cache_off(p, w + 8, hd), b);
     return;
@@ -221,7 +222,7 @@ __device__ __forceinline__ void qkv_pair(float a, float b, int m, int col, int d
     epi.out[(size_t)m * d + h * hd + e] = r.x;
     epi.out[(size_t)m * d + h * hd + e + half] = r.y;
   } else {
-    _Float16* dst = epi.Kc + (size_t)h * epi.cap * hd;
+    _Float16* dst = epi.Kc + slot_off + (size_t)h * epi.cap * hd;
     store_kv(dst + k_cache_off(p, e, hd), r.x);
     store_kv(dst + k_cache_off(p, e + half, hd), r.y);
   }
@@ -273,14 +274,13 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
     }
   } else {   // kRoleQKV: rotate q and k, append k and v to the cache
     constexpr int PR = W / 2;
-    const int pos0 = *epi.pos.base + epi.pos.offset;
     for (int idx = tid; idx < M * PR; idx += 256) {
       const int m = idx / PR, r = idx - m * PR;
       const int col = c0 + 16 * (r >> 3) + (r & 7);
       if (col < N) {
         const float a = slice_sum(partial, S, stride, (size_t)m * N + col);
         const float b = slice_sum(partial, S, stride, (size_t)m * N + col + 8);
-        qkv_pair(a, b, m, col, N / 3, pos0, epi);
+        qkv_pair(a, b, m, col, N / 3, epi);
       }
     }
   }
@@ -669,7 +669,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
     } else if (ROLE == kRoleGateUp) {
       epi.out[(size_t)m * (N >> 1) + tile * 8 + j] = swiglu(a, b);
     } else {
-      qkv_pair(a, b, m, col, N / 3, *epi.pos.base + epi.pos.offset, epi);
+      qkv_pair(a, b, m, col, N / 3, epi);
     }
   }
 }
@@ -920,12 +920,14 @@ void launch_fin_qkv_rope_f32(const float* partial, int S, int M, int d, int H, c
 // The block column after the last embedding column fills the row's rotation table instead:
 // cs[m][i] = (cos, sin)(position * theta^(-2i/hd)), the angle formed in double.
 template <typename E, int GW>
-__global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const int* __restrict__ tokens, PosRef pos,
-                                               int d, float* __restrict__ x, float* __restrict__ ssq_part, int ssq_n,
-                                               int hd, double theta, float2* __restrict__ cs) {
+__global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const int* __restrict__ tokens,
+                                               int tok_slot_stride, PosRef pos, int d, float* __restrict__ x,
+                                               float* __restrict__ ssq_part, int ssq_n, int hd, double theta,
+                                               float2* __restrict__ cs) {
   __shared__ float sm[4];
   const int m = blockIdx.y;
-  const int p = *pos.base + pos.offset + m;
+  const int p = pos_of(pos, m);
+  tokens += (size_t)slot_of(pos, m) * tok_slot_stride;
   if (blockIdx.x == gridDim.x - 1) {
     const int i = threadIdx.x;
     if (i < hd / 2) {
@@ -955,16 +957,16 @@ __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const 
   }
 }
 
-void launch_embed(const void* emb, int emb_bf16, const int* tokens, PosRef pos, int M, int d, float* x,
-                  float* ssq_part, int hd, float theta, float2* cs, hipStream_t st) {
+void launch_embed(const void* emb, int emb_bf16, const int* tokens, int tok_slot_stride, PosRef pos, int M, int d,
+                  float* x, float* ssq_part, int hd, float theta, float2* cs, hipStream_t st) {
   dim3 grid((d + 1023) / 1024 + 1, M), block(256);
   const int sn = ssq_groups(d, emb_bf16);
   if (emb_bf16)
-    hipLaunchKernelGGL((k_embed<uint16_t, 16>), grid, block, 0, st, static_cast<const uint16_t*>(emb), tokens, pos, d, x,
-                       ssq_part, sn, hd, (double)theta, cs);
+    hipLaunchKernelGGL((k_embed<uint16_t, 16>), grid, block, 0, st, static_cast<const uint16_t*>(emb), tokens,
+                       tok_slot_stride, pos, d, x, ssq_part, sn, hd, (double)theta, cs);
   else
-    hipLaunchKernelGGL((k_embed<float, 1024>), grid, block, 0, st, static_cast<const float*>(emb), tokens, pos, d, x,
-                       ssq_part, sn, hd, (double)theta, cs);
+    hipLaunchKernelGGL((k_embed<float, 1024>), grid, block, 0, st, static_cast<const float*>(emb), tokens,
+                       tok_slot_stride, pos, d, x, ssq_part, sn, hd, (double)theta, cs);
 }
 
 __global__ void k_rope_table(PosRef pos, int hd, double theta, float2* __restrict__ cs) {
@@ -1142,8 +1144,9 @@ __device__ __forceinline__ void split_half8(const float* v, f16x8& hi, f16x8& lo
 template <int HD, int CT>
 __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, const _Float16* __restrict__ Kc,
                                                   const _Float16* __restrict__ Vc, int cap, int d, int H, int M,
-                                                  PosRef pos, float scale, int nchunk_cap, float* part_o,
-                                                  float* part_ml, int* counters, float* __restrict__ out) {
+                                                  PosRef pos, size_t kv_slot_stride, float scale, int nchunk_cap,
+                                                  float* part_o, float* part_ml, int* counters,
+                                                  float* __restrict__ out) {
   constexpr int KK = HD / 32;   // k-steps of the score MFMA
   constexpr int ET = HD / 16;   // output-dim tiles of the value MFMA
   __shared__ float s_o[4][16][HD];
@@ -1152,7 +1155,17 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
   const int c = blockIdx.x, h = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, g = lane >> 4;
-  const int pos0 = *pos.base + pos.offset;
+  // several sequences: blockIdx.z is the slot; its M = pos.rps rows, caches, partial results and counters follow
+  // those of the slots before it, and everything below sees only this slot
+  const int row0 = blockIdx.z * M;
+  q += (size_t)row0 * d;
+  out += (size_t)row0 * d;
+  part_o += (size_t)row0 * H * nchunk_cap * HD;
+  part_ml += (size_t)row0 * H * nchunk_cap * 2;
+  counters += blockIdx.z * H;
+  Kc += blockIdx.z * kv_slot_stride;
+  Vc += blockIdx.z * kv_slot_stride;
+  const int pos0 = pos_of(pos, row0);
   const int kv_len = pos0 + M;
   const int kb = c * kAttnChunk + wave * 32;          // first key of this wave
   const bool have_keys = kb < kv_len;
@@ -1290,7 +1303,7 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
   // merge the chunks of this head.  Step A: all (max, sum) pairs of all rows go to LDS in one round trip.
   // Step B: one thread per (row, 4 adjacent dims) adds its chunks up in chunk order, 20 chunks per round trip.
   extern __shared__ float s_ml[];                     // [M][nch_max][2], sized by the host
-  const int nch_max = (pos0 + M - 1) / kAttnChunk + 1;
+  const int nch_max = (kv_len > 0) ? (kv_len - 1) / kAttnChunk + 1 : 0;
   for (int idx = tid; idx < M * nch_max; idx += 256) {
     const int m = idx / nch_max, cc = idx - m * nch_max;
     const float2 ml = ld_dev2(&part_ml[(((size_t)m * H + h) * nchunk_cap + cc) * 2]);
@@ -1359,18 +1372,18 @@ static void attn_dispatch(const float* q, const void* Kc, const void* Vc, int ca
 }
 
 void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv_half, int cap, int d, int H, int M,
-                      PosRef pos, int nchunk_launch, int nchunk_cap, float* part_o, float* part_ml, int* counters,
-                      float* out, hipStream_t st) {
+                      PosRef pos, int nslots, size_t kv_slot_stride, int nchunk_launch, int nchunk_cap, float* part_o,
+                      float* part_ml, int* counters, float* out, hipStream_t st) {
   const int hd = d / H;
   if (kv_half) {
     const float scale = 1.0f / sqrtf((float)hd);
     const _Float16* K = static_cast<const _Float16*>(Kc);
     const _Float16* V = static_cast<const _Float16*>(Vc);
-    dim3 grid(nchunk_launch, H), block(256);
+    dim3 grid(nchunk_launch, H, nslots), block(256);
     const size_t lds = (size_t)M * nchunk_launch * 2 * sizeof(float);   // the merge step's (max, sum) table
 #define STAIRS_ATTN16(hdv, ct) \
-  hipLaunchKernelGGL((k_attn_f16<hdv, ct>), grid, block, lds, st, q_rot, K, V, cap, d, H, M, pos, scale, nchunk_cap, \
-                     part_o, part_ml, counters, out)
+  hipLaunchKernelGGL((k_attn_f16<hdv, ct>), grid, block, lds, st, q_rot, K, V, cap, d, H, M, pos, kv_slot_stride, scale, \
+                     nchunk_cap, part_o, part_ml, counters, out)
     if (hd == 128) {
       if (M <= 16) STAIRS_ATTN16(128, 1); else STAIRS_ATTN16(128, 2);
     } else {
@@ -1390,12 +1403,12 @@ void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv
 // ---------------------------------------------------------------------------------------
 // per-row vocabulary argmax (ties -> lowest index) and stairs validation
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_argmax(const float* __restrict__ logits, int ld, int V, int* __restrict__ out,
-                                                 PosRef out_pos) {
+__global__ __launch_bounds__(1024) void k_argmax(const float* __restrict__ logits, int ld, int V, int row0, int row_stride,
+                                                 int* __restrict__ out, PosRef out_pos, int out_slot_stride) {
   __shared__ float sv[16];
   __shared__ int si[16];
   const int r = blockIdx.x, tid = threadIdx.x;
-  const float* row = logits + (size_t)r * ld;
+  const float* row = logits + (size_t)(row0 + r * row_stride) * ld;
   float best = -INFINITY;
   int bi = 0x7fffffff;
   // a thread walks its candidates in ascending index order, 8 loads in flight at a time
@@ -1428,17 +1441,28 @@ __global__ __launch_bounds__(1024) void k_argmax(const float* __restrict__ logit
   if (tid == 0) {
     for (int w = 1; w < 16; ++w)
       if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
-    const int o = (out_pos.base ? *out_pos.base : 0) + out_pos.offset + r;
-    out[o] = bi;
+    if (out_pos.rps) {                     // several sequences: the slot's own token array, only while it is active
+      const int o = pos_of(out_pos, r);
+      if (o >= 0) out[(size_t)slot_of(out_pos, r) * out_slot_stride + o] = bi;
+    } else {
+      out[(out_pos.base ? *out_pos.base : 0) + out_pos.offset + r] = bi;
+    }
   }
 }
 
-void launch_argmax(const float* logits, int ld, int V, int nrows, int* out, PosRef out_pos, hipStream_t st) {
-  hipLaunchKernelGGL(k_argmax, dim3(nrows), dim3(1024), 0, st, logits, ld, V, out, out_pos);
+void launch_argmax(const float* logits, int ld, int V, int nrows, int row0, int row_stride, int* out, PosRef out_pos,
+                   int out_slot_stride, hipStream_t st) {
+  hipLaunchKernelGGL(k_argmax, dim3(nrows), dim3(1024), 0, st, logits, ld, V, row0, row_stride, out, out_pos, out_slot_stride);
 }
 
-__global__ void k_accept(int* __restrict__ tokens, const int* __restrict__ tgt, int k, int* __restrict__ state) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+__global__ void k_accept(int* __restrict__ tokens, const int* __restrict__ tgt, int k, int* __restrict__ state,
+                         int tok_slot_stride) {
+  if (threadIdx.x != 0) return;
+  const int s = blockIdx.x;                 // slot
+  state += s * kSlotState;
+  if (!state[3]) return;                    // the slot is not generating (any more)
+  tokens += (size_t)s * tok_slot_stride;
+  tgt += s * (k + 1);
   const int L = state[0];
   int n = 0;
   while (n < k && tokens[L + n] == tgt[n]) ++n;
@@ -1447,8 +1471,8 @@ __global__ void k_accept(int* __restrict__ tokens, const int* __restrict__ tgt, 
   state[1] = n;
 }
 
-void launch_accept(int* tokens, const int* tgt, int k, int* state, hipStream_t st) {
-  hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, st, tokens, tgt, k, state);
+void launch_accept(int* tokens, const int* tgt, int k, int* state, int nslots, int tok_slot_stride, hipStream_t st) {
+  hipLaunchKernelGGL(k_accept, dim3(nslots), dim3(64), 0, st, tokens, tgt, k, state, tok_slot_stride);
 }
 
 // plain streaming copy, the calibration kernel for HBM traffic counters

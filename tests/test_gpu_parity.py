@@ -6,7 +6,7 @@ import pytest
 import paper_2407_19947_amd as pkg
 import synth_inputs as si
 from oracle import stairs_oracle as so
-from parity_util import LOGIT_TOL_BF16, run_side_by_side
+from parity_util import LOGIT_TOL_BF16, MARGIN_TOL, run_side_by_side
 
 pytestmark = pytest.mark.gpu
 
@@ -250,3 +250,96 @@ def test_degenerate_requests():
         b, _ = s.decode(13, 2)                                # continue the same sequence with another k
         assert list(a) + list(b) == list(plain)
         assert list(s.tokens()) == list(prompt) + list(plain)
+
+
+# ---- several sequences in one context (stairs_generate_batch) ---------------------------------------------
+
+def _batch_pair():
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=3, d_model=256, n_heads=4, d_ffn=512, vocab=2048),
+                           draft=dict(kind="prefix", n_layers=1), P=40, G=48)
+    target, draft = si.make_pair(w)
+    return w, target, draft
+
+
+def _prompts(w, lengths):
+    rng = np.random.default_rng([w["seed"], 77])
+    return [rng.integers(0, w["target"]["vocab"], n).astype(np.int32) for n in lengths]
+
+
+@pytest.mark.parametrize("k", [0, 1, 3, 7])
+def test_batch_of_sequences_equals_each_sequence_alone(k):
+    """Every sequence of a batch gets, bit for bit, the tokens the same context generates for it alone (each stair
+    row's arithmetic does not depend on what else is in the forward), with prompts of different lengths, some
+    ending on a chunk boundary, and sequences that finish at different iterations."""
+    w, target, draft = _batch_pair()
+    lengths = [40, 1, 129, 128][: max(1, min(4, 32 // (k + 1)))]
+    prompts = _prompts(w, lengths)
+    G = 48
+    with pkg.Stairs(target, draft, k_max=7, max_seq=256) as s:
+        alone = [s.generate(p, G, k)[0].copy() for p in prompts]
+        s.reserve_batch(4)
+        toks, st = s.generate_batch(prompts, G, k)
+        assert toks.shape == (len(prompts), G)
+        for b in range(len(prompts)):
+            assert np.array_equal(toks[b], alone[b]), (b, k)
+        assert st.tokens == len(prompts) * G
+        # the single-sequence calls still work afterwards (on slot 0 of the enlarged context)
+        again, _ = s.generate(prompts[0], G, k)
+        assert np.array_equal(again, alone[0])
+        # and graph replay against one-by-one launches
+    import os
+    os.environ["STAIRS_NO_GRAPH"] = "1"
+    try:
+        with pkg.Stairs(target, draft, k_max=7, max_seq=256) as s:
+            s.reserve_batch(4)
+            toks2, _ = s.generate_batch(prompts, G, k)
+    finally:
+        del os.environ["STAIRS_NO_GRAPH"]
+    assert np.array_equal(toks2, toks)
+
+
+def test_batch_against_the_oracle():
+    """The oracle's definition of a batch is the oracle run once per sequence."""
+    w, target, draft = _batch_pair()
+    prompts = _prompts(w, [33, 64, 20])
+    G, k = 24, 3
+    T = so.OracleModel(target, np.float64)
+    with pkg.Stairs(target, draft, k_max=k, max_seq=128) as s:
+        s.reserve_batch(3)
+        toks, st = s.generate_batch(prompts, G, k)
+    for b, p in enumerate(prompts):
+        # every generated token must be an eps-greedy choice under the oracle's logits for the GPU's own prefix
+        seq = np.concatenate([p, toks[b]])
+        logits = so.forward_full(T, seq[:-1])
+        for j in range(G):
+            row = logits[len(p) - 1 + j]
+            assert row[toks[b][j]] >= row.max() - MARGIN_TOL, (b, j)
+    assert st.iterations >= G // (k + 1)
+
+
+def test_batch_limits_and_errors():
+    w, target, draft = _batch_pair()
+    prompts = _prompts(w, [8, 9])
+    with pkg.Stairs(target, draft, k_max=15, max_seq=128) as s:
+        with pytest.raises(pkg.StairsError) as e:
+            s.generate_batch(prompts, 4, 1)                   # nothing reserved beyond one sequence
+        assert e.value.code == -1
+        s.reserve_batch(16)
+        toks, _ = s.generate_batch(_prompts(w, [5] * 16), 6, 1)   # 16 sequences x 2 rows = the widest forward
+        assert toks.shape == (16, 6)
+        with pytest.raises(pkg.StairsError) as e:
+            s.generate_batch(_prompts(w, [5] * 16), 6, 2)     # 16 x 3 rows do not fit
+        assert e.value.code == -1
+        with pytest.raises(pkg.StairsError) as e:
+            s.generate_batch(prompts, 120, 3)                 # capacity
+        assert e.value.code == -2
+        empty, st = s.generate_batch(prompts, 0, 3)
+        assert empty.shape == (2, 0) and st.iterations == 0
+        with pytest.raises(pkg.StairsError):
+            s.reserve_batch(17)
+    fp32 = si.scaled_workload("cfg1_tiny_fp32")
+    t32, d32 = si.make_pair(fp32)
+    with pkg.Stairs(t32, d32, k_max=2, max_seq=64) as s:
+        with pytest.raises(pkg.StairsError) as e:
+            s.reserve_batch(2)                                # fp32 models keep float caches: one sequence only
+        assert e.value.code == -1
