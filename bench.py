@@ -192,6 +192,28 @@ def main():
         extras["verify_vs_k"] = sweep
         ms, by = eng.time_kernel(7, 1, ctx_mid, 8)
         extras["draft_step"] = {"ms": ms, "GB/s": by / (ms * 1e-3) / 1e9, "frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    # ---- several sequences per forward (not the headline: the workload is one sequence) -------------------
+    # B prompts of the workload's length share every weight pass: aggregate tokens/s of stairs_generate_batch,
+    # decode phase, prompt 0 is the workload's prompt and must reproduce its tokens bit for bit
+    if not args.no_sweep and w["dtype"] == "bf16":
+        rngp = np.random.default_rng([w["seed"], 4242])
+        V = w["target"]["vocab"]
+        prompts = [prompt] + [rngp.integers(0, V, P).astype(np.int32) for _ in range(7)]
+        eng.reserve_batch(8)
+        batched = {}
+        for B, kk in ((2, k), (4, k), (8, k), (8, 3), (16, 1)):
+            if B > 8 or B * (kk + 1) > 32:
+                continue
+            toks_b, st_b = eng.generate_batch(prompts[:B], G, kk)
+            assert np.array_equal(toks_b[0], toks0), "a sequence of the batch differs from the same sequence alone"
+            batched[f"B{B}_k{kk}"] = {"sequences": B, "k": kk, "rows_per_forward": B * (kk + 1),
+                                      "tokens_per_s": B * G / (st_b.ms_decode * 1e-3), "iterations": st_b.iterations,
+                                      "ms_verify_per_iteration": st_b.ms_verify / max(1, st_b.iterations),
+                                      "ms_draft_per_iteration": st_b.ms_draft / max(1, st_b.iterations),
+                                      "prefill_ms": st_b.ms_prefill}
+            log(f"[bench] batch B={B} k={kk}: {batched[f'B{B}_k{kk}']['tokens_per_s']:.0f} tok/s aggregate, "
+                f"{st_b.iterations} iterations, verify {batched[f'B{B}_k{kk}']['ms_verify_per_iteration']:.2f} ms/iteration")
+        extras["batched_sequences"] = batched
     eng.close()
 
     out = {

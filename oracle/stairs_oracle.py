@@ -382,6 +382,14 @@ def stairs_cached(target: OracleModel, draft: Optional[OracleModel], prompt: Seq
     return st.run(G, k, keep_logits)
 
 
+def stairs_batch(target: OracleModel, draft: Optional[OracleModel], prompts: Sequence[Sequence[int]], G: int,
+                 k: int) -> list:
+    """Several prompts at once.  Sec. 3.3 treats one sentence; sequences do not interact (Sec. 3.1: the model maps
+    one token sequence to one distribution), so the result for a set of prompts is the result of the method for each
+    of them on its own: a list with one Generation per prompt."""
+    return [stairs_cached(target, draft, p, G, k) for p in prompts]
+
+
 def top2_margin(logits_row: np.ndarray) -> float:
     """Difference between the largest and second-largest logit of one row."""
     part = np.partition(logits_row, -2)

@@ -82,6 +82,18 @@ def test_cached_equals_literal_equals_greedy(seed, k, P, G, scale):
         assert np.allclose(a.logits, b.logits, atol=1e-12)
 
 
+def test_batch_of_prompts_is_each_prompt_on_its_own():
+    """Pin of stairs_batch: for prompts of different lengths every sequence equals brute-force greedy decoding of
+    the target on that prompt alone (nothing leaks between sequences)."""
+    t, d = _pair(11, 0.05, L=3, Ld=1, d=16, H=2, f=32, V=24)
+    T, D = so.OracleModel(t, np.float64), so.OracleModel(d, np.float64)
+    prompts = [[3], [5, 1, 7, 2], [23, 0]]
+    gens = so.stairs_batch(T, D, prompts, 9, 2)
+    assert len(gens) == 3
+    for p, g in zip(prompts, gens):
+        assert g.tokens == so.greedy_bruteforce(T, p, 9)
+
+
 def test_independent_draft_also_returns_plain_greedy():
     t = si.make_model(31, 3, 32, 2, 64, 50, "fp32")
     d = si.make_model(32, 2, 16, 2, 32, 50, "fp32")           # different width, unrelated weights
