@@ -286,21 +286,35 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
   }
 }
 
-// 1/rms of the rows from the sum-of-squares partials: half a wave (32 lanes) per row, one partial per lane
-// and pass, so all loads of a row are in flight together; wave w takes the row pairs w, w+4, ...
+// 1/rms of the rows from the sum-of-squares partials: half a wave (32 lanes) per row; a lane adds partials
+// p = lane, lane + 32, ... in that order, then the 32 lanes are combined by a butterfly.  Wave w takes the row
+// pairs w, w+4, ... (PASSES of them: 8 * PASSES >= M).  The first 256 partials of every pass are requested before any
+// of them is used, so a work-group pays one round trip for all its rows.
+template <int PASSES>
 __device__ __forceinline__ void rows_rstd(const RowNorm& nrm, int M, int K, float* s_rstd) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int half = lane >> 5, pl = lane & 31;
-  for (int r0 = 2 * wave; r0 < M; r0 += 8) {
-    const int m = r0 + half;
+  float v[PASSES][8];
+#pragma unroll
+  for (int ps = 0; ps < PASSES; ++ps) {
+    const int m = min(2 * wave + 8 * ps + half, M - 1);
+    const float* sp = nrm.ssq_part + (size_t)m * nrm.ssq_n;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[ps][i] = sp[min(pl + 32 * i, nrm.ssq_n - 1)];
+  }
+#pragma unroll
+  for (int ps = 0; ps < PASSES; ++ps) {
+    const int m = 2 * wave + 8 * ps + half;
     float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ss += (pl + 32 * i < nrm.ssq_n) ? v[ps][i] : 0.f;
     if (m < M) {
-      for (int p0 = pl; p0 < nrm.ssq_n; p0 += 256) {        // 8 loads in flight, added in index order
-        float v[8];
+      for (int p0 = pl + 256; p0 < nrm.ssq_n; p0 += 256) {   // rows wider than 4096: the rest, 8 loads at a time
+        float u[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = (p0 + 32 * i < nrm.ssq_n) ? nrm.ssq_part[m * nrm.ssq_n + p0 + 32 * i] : 0.f;
+        for (int i = 0; i < 8; ++i) u[i] = (p0 + 32 * i < nrm.ssq_n) ? nrm.ssq_part[m * nrm.ssq_n + p0 + 32 * i] : 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) ss += v[i];
+        for (int i = 0; i < 8; ++i) ss += u[i];
       }
     }
 #pragma unroll
@@ -370,8 +384,15 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
     }
   }
 
+  // the norm gain of this thread's k group (every item of a thread has kg = lane)
+  float4 g0 = make_float4(1.f, 1.f, 1.f, 1.f), g1 = g0;
+  if (nrm.gain) {
+    const float4* gp = reinterpret_cast<const float4*>(nrm.gain + k0 + min(lane, kgs - 1) * 8);
+    g0 = gp[0];
+    g1 = gp[1];
+  }
   if (nrm.gain && nrm.ssq_part) {
-    rows_rstd(nrm, M, K, s_rstd);
+    rows_rstd<2 * CT>(nrm, M, K, s_rstd);
     __syncthreads();
   }
 
@@ -382,13 +403,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
     const int m = min(w / kgs, 16 * CT - 1), kg = w - (w / kgs) * kgs;
     if (w < 16 * CT * kgs) {
       const float r = (nrm.gain && nrm.ssq_part && m < M) ? s_rstd[m] : 1.0f;
-      float4 g0 = make_float4(1.f, 1.f, 1.f, 1.f), g1 = g0;
       const bool scale = nrm.gain && m < M;
-      if (scale) {
-        const float4* gp = reinterpret_cast<const float4*>(nrm.gain + k0 + kg * 8);
-        g0 = gp[0];
-        g1 = gp[1];
-      }
       uint4 hi, lo;
       split_bf16x8(xa[it], xb[it], g0, g1, r, scale, hi, lo);
       const int kt = kg >> 2, g = kg & 3, ct = m >> 4, j = m & 15;
