@@ -58,6 +58,7 @@ struct stairs_ctx {
   float *x = nullptr, *ssq = nullptr, *q_rot = nullptr, *attn_out = nullptr, *h = nullptr, *logits = nullptr;
   float *partial = nullptr, *part_o = nullptr, *part_ml = nullptr;
   float2* rope_cs = nullptr;
+  float* rstd = nullptr;       // [kMaxRows] row statistics formed once per GEMM (forwards of more than 16 rows)
   int nchunk_cap = 0;
   int* tokens = nullptr;       // device copy of the sequence(s): [n_slots][tok_stride], capacity tok_cap each
   int tok_cap = 0, tok_stride = 0;
@@ -274,7 +275,7 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
   launch_embed(m->tok_emb, b, c->tokens + (pos.rps ? 0 : (size_t)slot * c->tok_stride), pos.rps ? c->tok_stride : 0, pos, M, d,
                c->x, c->ssq, m->hd, g.rope_theta, c->rope_cs, st);
   SYNCPOINT();
-  const RowNorm none{nullptr, nullptr, 0, 0.f};
+  const RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
   for (int l = 0; l < g.n_layers; ++l) {
     const Layer& ly = m->layers[l];
     char* Kl = m->Kc + slot_off + l * m->kv_layer_bytes;
@@ -293,7 +294,13 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     e.kv_slot_stride = slot_bytes / m->esz();
     e.ssq_out = c->ssq;
     e.out = c->q_rot;
-    launch_gemm(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, RowNorm{ly.attn_norm, c->ssq, sn, g.rms_eps}, c->partial, e, st);
+    // from 17 rows on the row statistics are formed once per GEMM by a one-work-group kernel
+    RowNorm an{ly.attn_norm, c->ssq, sn, g.rms_eps, nullptr};
+    if (b && M > 16) {
+      launch_rstd(an, M, d, c->rstd, st);
+      an.rstd = c->rstd;
+    }
+    launch_gemm(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, an, c->partial, e, st);
     SYNCPOINT();
     launch_attention(c->q_rot, Kl, Vl, b, m->cap, d, H, rows_per_slot, pos, nslots, slot_bytes / m->esz(), nchunk,
                      c->nchunk_cap, c->part_o, c->part_ml, c->counters + kGemmCounters, c->attn_out, st);
@@ -307,7 +314,12 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
       HIPCHK(c, hipEventRecord(c->probe_ev[2 * l + 1], st));
     }
     if (c->probe_role == kRoleGateUp) HIPCHK(c, hipEventRecord(c->probe_ev[2 * l], st));
-    launch_gemm(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, RowNorm{ly.ffn_norm, c->ssq, sn, g.rms_eps}, c->partial, e, st);
+    RowNorm fn{ly.ffn_norm, c->ssq, sn, g.rms_eps, nullptr};
+    if (b && M > 16) {
+      launch_rstd(fn, M, d, c->rstd, st);
+      fn.rstd = c->rstd;
+    }
+    launch_gemm(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, fn, c->partial, e, st);
     if (c->probe_role == kRoleGateUp) HIPCHK(c, hipEventRecord(c->probe_ev[2 * l + 1], st));
     SYNCPOINT();
     e.out = c->x;
@@ -573,7 +585,7 @@ int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_wei
       (rc = dev_alloc(c, &c->partial, pf)) ||
       (rc = dev_alloc(c, &c->part_o, (size_t)kMaxRows * Hmax * c->nchunk_cap * 128)) ||
       (rc = dev_alloc(c, &c->part_ml, (size_t)kMaxRows * Hmax * c->nchunk_cap * 2)) ||
-      (rc = dev_alloc(c, &c->rope_cs, (size_t)kMaxRows * 64)) || (rc = dev_alloc(c, &c->tokens, (size_t)c->tok_cap + kMaxRows)) ||
+      (rc = dev_alloc(c, &c->rope_cs, (size_t)kMaxRows * 64)) || (rc = dev_alloc(c, &c->rstd, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->tokens, (size_t)c->tok_cap + kMaxRows)) ||
       (rc = dev_alloc(c, &c->tgt_tok, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->counters, (size_t)kCounters)) || (rc = dev_alloc(c, &c->state, 2 * kSlotState)))
     return bail(rc);
   if (hipMemsetAsync(c->state, 0, 2 * kSlotState * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
@@ -956,7 +968,7 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
     ok(hipMemcpyAsync(dX, X, (size_t)M * K * 4, hipMemcpyHostToDevice, st));
     if (b) launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(dW), reinterpret_cast<uint4*>(dWs), N, K, kPermNone, 0, 0, st);
     ok(hipMemsetAsync(dCnt, 0, kGemmCounters * sizeof(int), st));
-    RowNorm none{nullptr, nullptr, 0, 0.f};
+    RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
     GemmEpi e{};
     e.counters = dCnt;
     e.out = dY;
@@ -1039,7 +1051,7 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
     if (bytes_per_launch) *bytes_per_launch = 2.0 * f * d * esz;
     return STAIRS_OK;
   }
-  RowNorm none{nullptr, nullptr, 0, 0.f};
+  RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
   double bytes = 0;
   const PosRef tpos = abs_pos(c, which == 1 ? std::max(ctx_len, M) - M : 0);
   if (which == 1 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");

@@ -46,6 +46,7 @@ struct RowNorm {
   const float* ssq_part;
   int ssq_n;
   float eps;
+  const float* rstd;   // optional: rstd[m] already formed from the partials by launch_rstd (same arithmetic)
 };
 
 inline int ssq_groups(int d, int bf16) {
@@ -95,6 +96,10 @@ struct GemmEpi {
 // second kernel.  partial: scratch of gemm_slices() * M * N floats.
 void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M,
                  RowNorm nrm, float* partial, const GemmEpi& epi, hipStream_t st);
+
+// rstd[m] = 1/sqrt(sum of the row's partials / K + eps) for M rows, once per GEMM instead of once per work-group
+// (bf16 path; pays from 17 rows on, where every work-group would otherwise fetch 32 rows' partials)
+void launch_rstd(RowNorm nrm, int M, int K, float* rstd, hipStream_t st);
 
 // ---- small kernels ----------------------------------------------------------------------
 // x[m][:] = emb[tokens[pos+m]][:] (row of zeros if pos+m < 0), plus sum-of-squares partials; the same launch

@@ -323,6 +323,17 @@ __device__ __forceinline__ void rows_rstd(const RowNorm& nrm, int M, int K, floa
   }
 }
 
+__global__ __launch_bounds__(256) void k_rstd(RowNorm nrm, int M, int K, float* __restrict__ rstd) {
+  __shared__ float s_rstd[kMaxRows];
+  rows_rstd<kMaxRows / 8>(nrm, M, K, s_rstd);
+  __syncthreads();
+  if (threadIdx.x < M) rstd[threadIdx.x] = s_rstd[threadIdx.x];
+}
+
+void launch_rstd(RowNorm nrm, int M, int K, float* rstd, hipStream_t st) {
+  hipLaunchKernelGGL(k_rstd, dim3(1), dim3(256), 0, st, nrm, M, K, rstd);
+}
+
 // 8 consecutive x of one row -> (x * rstd * gain) -> bf16 high part and the bf16 of the remainder
 __device__ __forceinline__ void split_bf16x8(const float4& xa, const float4& xb, const float4& g0, const float4& g1,
                                              float r, bool scale, uint4& hi, uint4& lo) {
@@ -392,7 +403,11 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
     g1 = gp[1];
   }
   if (nrm.gain && nrm.ssq_part) {
-    rows_rstd<2 * CT>(nrm, M, K, s_rstd);
+    if (nrm.rstd) {
+      if (tid < M) s_rstd[tid] = nrm.rstd[tid];
+    } else {
+      rows_rstd<2 * CT>(nrm, M, K, s_rstd);
+    }
     __syncthreads();
   }
 
