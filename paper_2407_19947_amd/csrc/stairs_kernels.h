@@ -13,6 +13,7 @@ constexpr int kSsqGroupF32 = 1024;  // residual columns per sum-of-squares parti
 constexpr int kSsqGroupBf16 = 16;   // ... bf16 models (= one weight tile of the residual-writing GEMMs)
 constexpr int kUnitK = 256;         // k extent of one weight "unit" (8 MFMA k-steps of 32)
 constexpr int kSliceUnits = 2;      // units per split-K slice (512 k)
+constexpr int kSpwRows = 9;         // 9..16 rows: a split-K work-group takes two k chunks (see launch_gemm)
 // most LDS the small-M GEMM (whole X block in LDS) may take per work-group: projections with many weight tiles keep
 // two work-groups per CU, the residual-writing ones (one work-group per CU) take most of the CU's LDS
 constexpr size_t kRowsPathMaxLds = 68 * 1024;

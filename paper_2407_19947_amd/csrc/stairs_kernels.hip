@@ -155,19 +155,29 @@ __device__ __forceinline__ size_t v_cache_off(int pos, int e, int hd) {
   return ((size_t)((pos >> 5) * (hd >> 4) + (e >> 4)) * 64 + (e & 15) + 16 * (k16 >> 2)) * 8 + (k16 & 3) + 4 * (p32 >> 4);
 }
 
-// Sum of the S split-K slices of one element (or 4 adjacent ones), in slice order.  The loads of up to 8
-// slices are issued together (they are full round trips to the memory side), the additions stay ordered.
+// Sum of the split-K partial sums of one element (or 4 adjacent ones).  The order is fixed for every GEMM variant:
+// the 512-wide k chunks are added in pairs, (c0 + c1), (c2 + c3), ..., and the pair sums one after the other.
+// PAIRS = true: the S partials are single chunks (the pairs are formed here); false: they already are pair sums.
+// The loads of up to 8 partials are issued together (they are full round trips to the memory side).
+template <bool PAIRS>
 __device__ __forceinline__ float slice_sum(const float* partial, int S, size_t stride, size_t off) {
   float a = 0.f;
   for (int s0 = 0; s0 < S; s0 += 8) {
     float v[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] = ld_dev(partial + (size_t)min(s0 + i, S - 1) * stride + off);
+    if (PAIRS) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) a += (s0 + i < S) ? v[i] : 0.f;
+      for (int i = 0; i < 8; i += 2)
+        if (s0 + i < S) a += (s0 + i + 1 < S) ? (v[i] + v[i + 1]) : v[i];
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) a += (s0 + i < S) ? v[i] : 0.f;
+    }
   }
   return a;
 }
+template <bool PAIRS>
 __device__ __forceinline__ float4 slice_sum4(const float* partial, int S, size_t stride, size_t off) {
   float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int s0 = 0; s0 < S; s0 += 8) {
@@ -178,10 +188,21 @@ __device__ __forceinline__ float4 slice_sum4(const float* partial, int S, size_t
       p[i] = ld_dev2(src);
       q[i] = ld_dev2(src + 2);
     }
+    if (PAIRS) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const bool ok = s0 + i < S;
-      a.x += ok ? p[i].x : 0.f; a.y += ok ? p[i].y : 0.f; a.z += ok ? q[i].x : 0.f; a.w += ok ? q[i].y : 0.f;
+      for (int i = 0; i < 8; i += 2) {
+        if (s0 + i < S) {
+          const bool two = s0 + i + 1 < S;
+          a.x += two ? (p[i].x + p[i + 1].x) : p[i].x; a.y += two ? (p[i].y + p[i + 1].y) : p[i].y;
+          a.z += two ? (q[i].x + q[i + 1].x) : q[i].x; a.w += two ? (q[i].y + q[i + 1].y) : q[i].y;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const bool ok = s0 + i < S;
+        a.x += ok ? p[i].x : 0.f; a.y += ok ? p[i].y : 0.f; a.z += ok ? q[i].x : 0.f; a.w += ok ? q[i].y : 0.f;
+      }
     }
   }
   return a;
@@ -229,7 +250,7 @@ __device__ __forceinline__ void qkv_pair(float a, float b, int m, int col, int d
 }
 
 // Epilogue of one column group [c0, c0+W) for all M rows, run by the 256 threads of one work-group.
-template <int ROLE, int W>
+template <int ROLE, int W, bool PAIRS>
 __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M, int N, int c0, const GemmEpi& epi) {
   const int tid = threadIdx.x;
   const size_t stride = (size_t)M * N;
@@ -237,7 +258,7 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
     constexpr int PR = W / 4;
     for (int idx = tid; idx < M * PR; idx += 256) {
       const int m = idx / PR, col = c0 + (idx - m * PR) * 4;
-      if (col < N) *reinterpret_cast<float4*>(epi.out + (size_t)m * N + col) = slice_sum4(partial, S, stride, (size_t)m * N + col);
+      if (col < N) *reinterpret_cast<float4*>(epi.out + (size_t)m * N + col) = slice_sum4<PAIRS>(partial, S, stride, (size_t)m * N + col);
     }
   } else if (ROLE == kRoleWo || ROLE == kRoleDown) {
     constexpr int PR = W / 4;                       // threads per row; 4 adjacent threads = one 16-column tile
@@ -247,7 +268,7 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
       const int m = idx / PR, col = c0 + (idx - m * PR) * 4;
       float ss = 0.f;
       if (idx < total && col < N) {
-        float4 a = slice_sum4(partial, S, stride, (size_t)m * N + col);
+        float4 a = slice_sum4<PAIRS>(partial, S, stride, (size_t)m * N + col);
         float4* xp = reinterpret_cast<float4*>(epi.out + (size_t)m * N + col);
         const float4 r = *xp;
         a.x += r.x; a.y += r.y; a.z += r.z; a.w += r.w;
@@ -266,8 +287,8 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
       const int m = idx / PR, r = idx - m * PR;
       const int gcol = c0 + 16 * (r >> 1) + 4 * (r & 1);
       if (gcol < N) {
-        const float4 g = slice_sum4(partial, S, stride, (size_t)m * N + gcol);
-        const float4 u = slice_sum4(partial, S, stride, (size_t)m * N + gcol + 8);
+        const float4 g = slice_sum4<PAIRS>(partial, S, stride, (size_t)m * N + gcol);
+        const float4 u = slice_sum4<PAIRS>(partial, S, stride, (size_t)m * N + gcol + 8);
         const float4 o = make_float4(swiglu(g.x, u.x), swiglu(g.y, u.y), swiglu(g.z, u.z), swiglu(g.w, u.w));
         *reinterpret_cast<float4*>(epi.out + (size_t)m * f + (gcol >> 4) * 8 + (gcol & 7)) = o;
       }
@@ -278,8 +299,8 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
       const int m = idx / PR, r = idx - m * PR;
       const int col = c0 + 16 * (r >> 3) + (r & 7);
       if (col < N) {
-        const float a = slice_sum(partial, S, stride, (size_t)m * N + col);
-        const float b = slice_sum(partial, S, stride, (size_t)m * N + col + 8);
+        const float a = slice_sum<PAIRS>(partial, S, stride, (size_t)m * N + col);
+        const float b = slice_sum<PAIRS>(partial, S, stride, (size_t)m * N + col + 8);
         qkv_pair(a, b, m, col, N / 3, epi);
       }
     }
@@ -352,133 +373,166 @@ __device__ __forceinline__ void split_bf16x8(const float4& xa, const float4& xb,
   lo = make_uint4(lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16), lb[4] | (lb[5] << 16), lb[6] | (lb[7] << 16));
 }
 
-template <int CT, int NT, int ROLE>
+template <int CT, int NT, int ROLE, int SPW>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw, int KT, int NTILES,
                                                    const float* __restrict__ X, int ldx, int M,
                                                    RowNorm nrm, int K, float* partial, int N, GemmEpi epi) {
+  // SPW = k chunks (512 wide) a work-group takes, one after the other through the same LDS buffer: 1, or 2 (then
+  // it writes the sum of its two chunk sums, which halves the partial sums in memory; used for many rows)
   extern __shared__ uint4 lds[];   // [16 k-steps][CT][hi,lo][64 lanes]
   __shared__ int s_last;
   __shared__ float s_rstd[kMaxRows];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int s = blockIdx.y, S = gridDim.y;
-  const int unit0 = s * kSliceUnits;
-  const int units = min(kSliceUnits, K / kUnitK - unit0);
-  // weights are stored slice-major: [k-slice][row tile][k-step][lane]; the four waves take adjacent tiles, so
-  // the work-group reads one contiguous run of 64*NT KiB
-  const uint4* Wslice = Wsw + (size_t)s * NTILES * (kSliceUnits * 8) * 64 + lane;
+  const int sp = blockIdx.y, SG = gridDim.y;               // this work-group's partial slice, number of them
+  const int units_total = K / kUnitK;
+  // weights are stored slice-major: [k chunk][row tile][k-step][lane]; the four waves take adjacent tiles, so
+  // the work-group reads contiguous runs of 64*NT KiB
   const int tile0 = blockIdx.x * 4 * NT + wave;          // this wave's tiles: tile0 + 4 t
+  auto chunk_units = [&](int j) { return max(0, min(kSliceUnits, units_total - (sp * SPW + j) * kSliceUnits)); };
+  // unit u of this wave's sequence: chunk j = u / (2 NT), tile t = (u / 2) % NT, unit ku = u % 2 of the chunk
+  auto unit_ok = [&](int u) {
+    const int j = u / (kSliceUnits * NT), t = (u / kSliceUnits) % NT, ku = u % kSliceUnits;
+    return ku < chunk_units(j) && (tile0 + 4 * t) < NTILES;
+  };
+  auto unit_ptr = [&](int u) {
+    const int j = u / (kSliceUnits * NT), t = (u / kSliceUnits) % NT, ku = u % kSliceUnits;
+    return Wsw + (size_t)(sp * SPW + j) * NTILES * (kSliceUnits * 8) * 64 +
+           ((size_t)(tile0 + 4 * t) * chunk_units(j) + ku) * 8 * 64 + lane;
+  };
 
   uint4 wb[2][8];
   // first weight unit goes out before anything else: it depends on nothing
-  if (tile0 < NTILES) {
-    const uint4* p = Wslice + (size_t)tile0 * units * 8 * 64;
+  if (unit_ok(0)) {
+    const uint4* p = unit_ptr(0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) wb[0][i] = p[i * 64];
   }
 
-  // the X slice: this thread's items are (row m, 8 consecutive k); their loads go out first, the row
-  // statistics are fetched while they fly
-  const int kgs = units * 32;            // groups of 8 k per row
-  const int k0 = unit0 * kUnitK;
-  constexpr int ITEMS = 4 * CT;          // 16*CT rows x 64 groups / 256 threads (a full slice)
-  float4 xa[ITEMS], xb[ITEMS];
+  f32x4 sum[NT][CT];
 #pragma unroll
-  for (int it = 0; it < ITEMS; ++it) {
-    const int w = tid + 256 * it;
-    const int m = w / kgs, kg = w - m * kgs;
-    xa[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-    xb[it] = xa[it];
-    if (w < 16 * CT * kgs && m < M) {
-      const float4* xp = reinterpret_cast<const float4*>(X + (size_t)m * ldx + k0 + kg * 8);
-      xa[it] = xp[0];
-      xb[it] = xp[1];
-    }
-  }
-
-  // the norm gain of this thread's k group (every item of a thread has kg = lane)
-  float4 g0 = make_float4(1.f, 1.f, 1.f, 1.f), g1 = g0;
-  if (nrm.gain) {
-    const float4* gp = reinterpret_cast<const float4*>(nrm.gain + k0 + min(lane, kgs - 1) * 8);
-    g0 = gp[0];
-    g1 = gp[1];
-  }
-  if (nrm.gain && nrm.ssq_part) {
-    if (nrm.rstd) {
-      if (tid < M) s_rstd[tid] = nrm.rstd[tid];
-    } else {
-      rows_rstd<2 * CT>(nrm, M, K, s_rstd);
-    }
-    __syncthreads();
-  }
-
-  // fp32 -> (x * rstd * gain) -> bf16 hi + lo, stored in B-fragment order
+  for (int j = 0; j < SPW; ++j) {
+    const int units = chunk_units(j);
+    const int unit0 = (sp * SPW + j) * kSliceUnits;
+    // the X chunk: this thread's items are (row m, 8 consecutive k)
+    const int kgs = max(units, 1) * 32;    // groups of 8 k per row
+    const int k0 = unit0 * kUnitK;
+    constexpr int ITEMS = 4 * CT;          // 16*CT rows x 64 groups / 256 threads (a full chunk)
+    float4 xa[ITEMS], xb[ITEMS];
+    if (j > 0) __syncthreads();            // the previous chunk's fragments have been read
+    if (units > 0) {
 #pragma unroll
-  for (int it = 0; it < ITEMS; ++it) {
-    const int w = tid + 256 * it;                       // w < 16*CT*kgs is uniform per wave
-    const int m = min(w / kgs, 16 * CT - 1), kg = w - (w / kgs) * kgs;
-    if (w < 16 * CT * kgs) {
-      const float r = (nrm.gain && nrm.ssq_part && m < M) ? s_rstd[m] : 1.0f;
-      const bool scale = nrm.gain && m < M;
-      uint4 hi, lo;
-      split_bf16x8(xa[it], xb[it], g0, g1, r, scale, hi, lo);
-      const int kt = kg >> 2, g = kg & 3, ct = m >> 4, j = m & 15;
-      const int base = ((kt * CT + ct) * 2) * 64 + g * 16 + j;
-      lds[base] = hi;
-      lds[base + 64] = lo;
-    }
-  }
-  __syncthreads();
-
-#pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    f32x4 acc[CT];
-#pragma unroll
-    for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const bool tile_ok = (tile0 + 4 * t) < NTILES;
-#pragma unroll
-    for (int ku = 0; ku < kSliceUnits; ++ku) {
-      const int u = t * kSliceUnits + ku;
-      // prefetch the next unit into the other buffer
-      if (u + 1 < NT * kSliceUnits) {
-        const int tn = (u + 1) / kSliceUnits, kun = (u + 1) % kSliceUnits;
-        if (kun < units && (tile0 + 4 * tn) < NTILES) {
-          const uint4* p = Wslice + ((size_t)(tile0 + 4 * tn) * units + kun) * 8 * 64;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) wb[(u + 1) & 1][i] = p[i * 64];
+      for (int it = 0; it < ITEMS; ++it) {
+        const int w = tid + 256 * it;
+        const int m = w / kgs, kg = w - m * kgs;
+        xa[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+        xb[it] = xa[it];
+        if (w < 16 * CT * kgs && m < M) {
+          const float4* xp = reinterpret_cast<const float4*>(X + (size_t)m * ldx + k0 + kg * 8);
+          xa[it] = xp[0];
+          xb[it] = xp[1];
         }
       }
-      if (ku < units && tile_ok) {
+    }
+    // the norm gain of this thread's k group (every item of a thread has kg = lane)
+    float4 g0 = make_float4(1.f, 1.f, 1.f, 1.f), g1 = g0;
+    if (nrm.gain && units > 0) {
+      const float4* gp = reinterpret_cast<const float4*>(nrm.gain + k0 + min(lane, kgs - 1) * 8);
+      g0 = gp[0];
+      g1 = gp[1];
+    }
+    if (j == 0 && nrm.gain && nrm.ssq_part) {
+      if (nrm.rstd) {
+        if (tid < M) s_rstd[tid] = nrm.rstd[tid];
+      } else {
+        rows_rstd<2 * CT>(nrm, M, K, s_rstd);
+      }
+      __syncthreads();
+    }
+
+    // fp32 -> (x * rstd * gain) -> bf16 hi + lo, stored in B-fragment order
+    if (units > 0) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const bf16x8 a = __builtin_bit_cast(bf16x8, wb[u & 1][i]);
+      for (int it = 0; it < ITEMS; ++it) {
+        const int w = tid + 256 * it;                       // w < 16*CT*kgs is uniform per wave
+        const int m = min(w / kgs, 16 * CT - 1), kg = w - (w / kgs) * kgs;
+        if (w < 16 * CT * kgs) {
+          const float r = (nrm.gain && nrm.ssq_part && m < M) ? s_rstd[m] : 1.0f;
+          const bool scale = nrm.gain && m < M;
+          uint4 hi, lo;
+          split_bf16x8(xa[it], xb[it], g0, g1, r, scale, hi, lo);
+          const int kt = kg >> 2, g = kg & 3, ct = m >> 4, jj = m & 15;
+          const int base = ((kt * CT + ct) * 2) * 64 + g * 16 + jj;
+          lds[base] = hi;
+          lds[base + 64] = lo;
+        }
+      }
+    }
+    __syncthreads();
+
 #pragma unroll
-          for (int ct = 0; ct < CT; ++ct) {
-            const int base = (((ku * 8 + i) * CT + ct) * 2) * 64 + lane;
-            const bf16x8 bh = __builtin_bit_cast(bf16x8, lds[base]);
-            const bf16x8 bl = __builtin_bit_cast(bf16x8, lds[base + 64]);
-            acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[ct], 0, 0, 0);
-            acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[ct], 0, 0, 0);
+    for (int t = 0; t < NT; ++t) {
+      f32x4 acc[CT];
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+      const bool tile_ok = (tile0 + 4 * t) < NTILES;
+#pragma unroll
+      for (int ku = 0; ku < kSliceUnits; ++ku) {
+        const int u = (j * NT + t) * kSliceUnits + ku;
+        // prefetch the next unit into the other buffer (it may belong to the next chunk)
+        if (u + 1 < SPW * NT * kSliceUnits) {
+          if (unit_ok(u + 1)) {
+            const uint4* p = unit_ptr(u + 1);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) wb[(u + 1) & 1][i] = p[i * 64];
+          }
+        }
+        if (ku < units && tile_ok) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, wb[u & 1][i]);
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+              const int base = (((ku * 8 + i) * CT + ct) * 2) * 64 + lane;
+              const bf16x8 bh = __builtin_bit_cast(bf16x8, lds[base]);
+              const bf16x8 bl = __builtin_bit_cast(bf16x8, lds[base + 64]);
+              acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[ct], 0, 0, 0);
+              acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[ct], 0, 0, 0);
+            }
           }
         }
       }
+      // chunk sums of a pair are added once, first + second
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) {
+        if (j == 0) {
+          sum[t][ct] = acc[ct];
+        } else if (units > 0) {
+          sum[t][ct][0] += acc[ct][0]; sum[t][ct][1] += acc[ct][1];
+          sum[t][ct][2] += acc[ct][2]; sum[t][ct][3] += acc[ct][3];
+        }
+      }
     }
-    if (tile_ok) {
+  }
+
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    if ((tile0 + 4 * t) < NTILES) {
       const int n = (tile0 + 4 * t) * 16 + 4 * (lane >> 4);
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct) {
         const int m = ct * 16 + (lane & 15);
         if (m < M) {
-          float* dst = partial + ((size_t)s * M + m) * N + n;
-          st_dev2(dst, acc[ct][0], acc[ct][1]);
-          st_dev2(dst + 2, acc[ct][2], acc[ct][3]);
+          float* dst = partial + ((size_t)sp * M + m) * N + n;
+          st_dev2(dst, sum[t][ct][0], sum[t][ct][1]);
+          st_dev2(dst + 2, sum[t][ct][2], sum[t][ct][3]);
         }
       }
     }
   }
 
   // split-K hand-off: the partial sums are out, take a ticket; the last arrival finishes the group
-  if (!last_arrival(&epi.counters[blockIdx.x], S, &s_last)) return;
-  gemm_epilogue<ROLE, 64 * NT>(partial, S, M, N, blockIdx.x * 64 * NT, epi);
+  if (!last_arrival(&epi.counters[blockIdx.x], SG, &s_last)) return;
+  gemm_epilogue<ROLE, 64 * NT, SPW == 1>(partial, SG, M, N, blockIdx.x * 64 * NT, epi);
   if (tid == 0) epi.counters[blockIdx.x] = 0;   // ready for the next launch on this stream
 }
 
@@ -669,7 +723,8 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
     if (tid < R * 16) {
       const int m = tid >> 4, n = tid & 15;
       float a = 0.f;
-      for (int c = 0; c < nchunks; ++c) a += csum[((c * R + m) << 4) + n];
+      for (int c = 0; c < nchunks; c += 2)      // chunk pairs first, then pair after pair: the order of every GEMM variant
+        a += (c + 1 < nchunks) ? (csum[((c * R + m) << 4) + n] + csum[(((c + 1) * R + m) << 4) + n]) : csum[((c * R + m) << 4) + n];
       float* xp = epi.out + (size_t)m * N + tile * 16 + n;
       a += *xp;
       *xp = a;
@@ -688,9 +743,12 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
   if (tid < R * 8) {
     const int m = tid >> 3, j = tid & 7;
     float a = 0.f, b = 0.f;
-    for (int c = 0; c < nchunks; ++c) {
-      a += csum[((c * R + m) << 4) + j];
-      b += csum[((c * R + m) << 4) + j + 8];
+    for (int c = 0; c < nchunks; c += 2) {
+      const float* p0 = csum + ((c * R + m) << 4);
+      const float* p1 = csum + (((c + 1) * R + m) << 4);
+      const bool two = c + 1 < nchunks;
+      a += two ? (p0[j] + p1[j]) : p0[j];
+      b += two ? (p0[j + 8] + p1[j + 8]) : p0[j + 8];
     }
     const int col = tile * 16 + j;
     if (ROLE == kRoleHead) {
@@ -757,11 +815,10 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ W, i
   }
 }
 
-static int pick_nt(int role, int NTILES, int S, int hd) {
-  if (role == kRoleWo || role == kRoleDown) return 2;      // the sum-of-squares groups are 128 columns wide
-  if (role == kRoleQKV && hd == 128) return 2;              // a head's rotation pairs stay in one column group
-  // enough work-groups to cover the chip a few times over; otherwise more tiles per wave
-  return ((size_t)((NTILES + 7) / 8) * S >= 1024) ? 2 : 1;
+// weight tiles per wave (1 or 2) of the split-K kernel: two when that still leaves enough work-groups to cover
+// the chip a few times over (more tiles per work-group = fewer activation slices staged per weight byte)
+static int pick_nt(int NTILES, int SG, int want_wgs) {
+  return ((size_t)((NTILES + 7) / 8) * SG >= (size_t)want_wgs) ? 2 : 1;
 }
 
 // forward declarations of the unfused epilogues (fp32 models)
@@ -812,17 +869,26 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
 #undef STAIRS_ROWS
     return;
   }
-  const int NT = pick_nt(role, NTILES, S, epi.hd);
-  dim3 grid((NTILES + 4 * NT - 1) / (4 * NT), S), block(256);
+  // 9..16 rows: a work-group takes two k chunks and writes the sum of the pair (half the partial sums in memory;
+  // measured -7 % on a 7B layer at 16 rows).  With two column tiles (17..32 rows) the halved work-group count
+  // or, with one weight tile per wave, the doubled activation staging cost more than the partial sums saved.
   const int CT = (M <= 16) ? 1 : 2;
+  const int SPW = (M >= kSpwRows && CT == 1 && S >= 2) ? 2 : 1;
+  const int SG = (S + SPW - 1) / SPW;
+  int NT;
+  if (SPW == 1) NT = (role == kRoleWo || role == kRoleDown) ? 2 : pick_nt(NTILES, SG, 1024);
+  else NT = pick_nt(NTILES, SG, 640);
+  dim3 grid((NTILES + 4 * NT - 1) / (4 * NT), SG), block(256);
   const size_t lds = (size_t)16 * CT * 2 * 64 * sizeof(uint4);
-#define STAIRS_GEMM(ct, nt, role) \
-  hipLaunchKernelGGL((k_gemm_bf16<ct, nt, role>), grid, block, lds, st, Wsw, KT, NTILES, X, ldx, M, nrm, K, partial, N, epi)
-#define STAIRS_GEMM_ROLE(role)             \
-  if (CT == 1 && NT == 1) STAIRS_GEMM(1, 1, role); \
-  else if (CT == 1) STAIRS_GEMM(1, 2, role);       \
-  else if (NT == 1) STAIRS_GEMM(2, 1, role);       \
-  else STAIRS_GEMM(2, 2, role)
+#define STAIRS_GEMM(ct, nt, role, spw) \
+  hipLaunchKernelGGL((k_gemm_bf16<ct, nt, role, spw>), grid, block, lds, st, Wsw, KT, NTILES, X, ldx, M, nrm, K, partial, N, epi)
+#define STAIRS_GEMM_NT(ct, role, spw)             \
+  if (NT == 1) STAIRS_GEMM(ct, 1, role, spw);     \
+  else STAIRS_GEMM(ct, 2, role, spw)
+#define STAIRS_GEMM_ROLE(role)                                  \
+  if (CT == 1 && SPW == 1) { STAIRS_GEMM_NT(1, role, 1); }      \
+  else if (CT == 1) { STAIRS_GEMM_NT(1, role, 2); }             \
+  else { STAIRS_GEMM_NT(2, role, 1); }
   switch (role) {
     case kRoleQKV: STAIRS_GEMM_ROLE(kRoleQKV); break;
     case kRoleWo: STAIRS_GEMM_ROLE(kRoleWo); break;
@@ -830,6 +896,7 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
     case kRoleDown: STAIRS_GEMM_ROLE(kRoleDown); break;
     default: STAIRS_GEMM_ROLE(kRoleHead); break;
   }
+#undef STAIRS_GEMM_NT
 #undef STAIRS_GEMM_ROLE
 #undef STAIRS_GEMM
 }
