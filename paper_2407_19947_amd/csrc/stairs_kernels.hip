@@ -545,6 +545,21 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
 // kernel: both give the same bits for a row.
 //   LDS: X high parts [K/8][R] uint4, X low parts [K/8][R] uint4, chunk sums float [chunks][R][16]
 // ---------------------------------------------------------------------------------------
+// Sum of one element's chunk sums held in LDS (stride floats apart), in the order of slice_sum<true>: pairs first.
+// 8 chunks are read before any is used.
+__device__ __forceinline__ float lds_chunk_sum(const float* base, int stride, int nchunks) {
+  float a = 0.f;
+  for (int c0 = 0; c0 < nchunks; c0 += 8) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = base[min(c0 + i, nchunks - 1) * stride];
+#pragma unroll
+    for (int i = 0; i < 8; i += 2)
+      if (c0 + i < nchunks) a += (c0 + i + 1 < nchunks) ? (v[i] + v[i + 1]) : v[i];
+  }
+  return a;
+}
+
 template <int R, int ROLE, int NW, int GP>
 __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restrict__ Wsw, int NTILES,
                                                             const float* __restrict__ X, int ldx, RowNorm nrm,
@@ -722,9 +737,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
     // the split-K kernel's epilogue
     if (tid < R * 16) {
       const int m = tid >> 4, n = tid & 15;
-      float a = 0.f;
-      for (int c = 0; c < nchunks; c += 2)      // chunk pairs first, then pair after pair: the order of every GEMM variant
-        a += (c + 1 < nchunks) ? (csum[((c * R + m) << 4) + n] + csum[(((c + 1) * R + m) << 4) + n]) : csum[((c * R + m) << 4) + n];
+      float a = lds_chunk_sum(csum + (m << 4) + n, R * 16, nchunks);
       float* xp = epi.out + (size_t)m * N + tile * 16 + n;
       a += *xp;
       *xp = a;
@@ -742,14 +755,8 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
   // a thread takes row m, columns j and j+8 of the tile
   if (tid < R * 8) {
     const int m = tid >> 3, j = tid & 7;
-    float a = 0.f, b = 0.f;
-    for (int c = 0; c < nchunks; c += 2) {
-      const float* p0 = csum + ((c * R + m) << 4);
-      const float* p1 = csum + (((c + 1) * R + m) << 4);
-      const bool two = c + 1 < nchunks;
-      a += two ? (p0[j] + p1[j]) : p0[j];
-      b += two ? (p0[j + 8] + p1[j + 8]) : p0[j + 8];
-    }
+    const float a = lds_chunk_sum(csum + (m << 4) + j, R * 16, nchunks);
+    const float b = lds_chunk_sum(csum + (m << 4) + j + 8, R * 16, nchunks);
     const int col = tile * 16 + j;
     if (ROLE == kRoleHead) {
       epi.out[(size_t)m * N + col] = a;
