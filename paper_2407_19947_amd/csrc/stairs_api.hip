@@ -4,6 +4,8 @@
 #include "../../include/stairs.h"
 #include "stairs_kernels.h"
 
+#include <rocblas/rocblas.h>
+
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
@@ -24,6 +26,8 @@ struct Layer {
   const void* wo = nullptr;     // [d, d]
   const void* wgu = nullptr;    // [2f, d]
   const void* wdown = nullptr;  // [d, f]
+  // row-major bf16 copies of the same four matrices for the library GEMMs of the block prefill (or nullptr)
+  const uint16_t *wqkv_p = nullptr, *wo_p = nullptr, *wgu_p = nullptr, *wdown_p = nullptr;
 };
 
 struct Model {
@@ -59,6 +63,12 @@ struct stairs_ctx {
   float *partial = nullptr, *part_o = nullptr, *part_ml = nullptr;
   float2* rope_cs = nullptr;
   float* rstd = nullptr;       // [kMaxRows] row statistics formed once per GEMM (forwards of more than 16 rows)
+  // block prefill (bf16 models, env STAIRS_NO_BLOCK_PREFILL=1 turns it off): BLAS handle and [kPfRows, .] workspaces
+  bool block_prefill = false;
+  rocblas_handle blas = nullptr;
+  float *pf_x = nullptr, *pf_y = nullptr, *pf_q = nullptr, *pf_attn = nullptr;
+  uint16_t *pf_hi = nullptr, *pf_lo = nullptr;
+  float2* pf_cs = nullptr;
   int nchunk_cap = 0;
   int* tokens = nullptr;       // device copy of the sequence(s): [n_slots][tok_stride], capacity tok_cap each
   int tok_cap = 0, tok_stride = 0;
@@ -152,13 +162,16 @@ enum { KIND_EMB = 0, KIND_HEAD, KIND_NORM, KIND_QKV, KIND_WO, KIND_GU, KIND_DOWN
 // Upload a matrix made of `nparts` row blocks (each [rows_each, K], host, model dtype) as one
 // [nparts*rows_each, K] GEMM operand; bf16 goes through the operand re-layout kernel.
 int upload_matrix(stairs_ctx* c, bool bf16, const void* const* parts, int nparts, int rows_each, int K, int kind,
-                  int hd, char* staging, const void** out) {
+                  int hd, char* staging, const void** out, const uint16_t** plain_out = nullptr) {
   // gate/up and q/k rows are reordered so that SwiGLU and rotation pairs share a 16-row tile
   const int perm = (kind == KIND_GU) ? kPermGateUp : (kind == KIND_QKV) ? kPermQKV : kPermNone;
   auto key = std::make_pair(parts[0], kind);
+  auto pkey = std::make_pair(parts[0], kind + 100);          // the row-major copy of the same matrix
+  const bool want_plain = plain_out && bf16 && c->block_prefill;
   auto it = c->dedup.find(key);
   if (it != c->dedup.end()) {
     *out = it->second;
+    if (want_plain) *plain_out = static_cast<const uint16_t*>(c->dedup[pkey]);
     return STAIRS_OK;
   }
   const size_t esz = bf16 ? 2 : 4;
@@ -173,6 +186,13 @@ int upload_matrix(stairs_ctx* c, bool bf16, const void* const* parts, int nparts
     launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(staging), reinterpret_cast<uint4*>(dst), nparts * rows_each, K,
                         perm, rows_each, hd, c->st);
     HIPCHK(c, hipGetLastError());
+    if (want_plain) {
+      char* pl = nullptr;
+      if ((rc = dev_alloc(c, &pl, part_bytes * nparts))) return rc;
+      HIPCHK(c, hipMemcpyAsync(pl, staging, part_bytes * nparts, hipMemcpyDeviceToDevice, c->st));
+      c->dedup[pkey] = pl;
+      *plain_out = reinterpret_cast<const uint16_t*>(pl);
+    }
   }
   HIPCHK(c, hipStreamSynchronize(c->st));   // staging and the host buffers are reused right away
   c->dedup[key] = dst;
@@ -219,13 +239,13 @@ int build_model(stairs_ctx* c, Model* m, const stairs_model_cfg* cfg, const stai
     if ((rc = upload_plain(c, w->ffn_norm[l], (size_t)d * 4, KIND_NORM, &p))) return rc;
     ly.ffn_norm = static_cast<const float*>(p);
     const void* qkv[3] = {w->wq[l], w->wk[l], w->wv[l]};
-    if ((rc = upload_matrix(c, m->bf16, qkv, 3, d, d, KIND_QKV, m->hd, staging, &ly.wqkv))) return rc;
+    if ((rc = upload_matrix(c, m->bf16, qkv, 3, d, d, KIND_QKV, m->hd, staging, &ly.wqkv, &ly.wqkv_p))) return rc;
     one[0] = w->wo[l];
-    if ((rc = upload_matrix(c, m->bf16, one, 1, d, d, KIND_WO, m->hd, staging, &ly.wo))) return rc;
+    if ((rc = upload_matrix(c, m->bf16, one, 1, d, d, KIND_WO, m->hd, staging, &ly.wo, &ly.wo_p))) return rc;
     const void* gu[2] = {w->w_gate[l], w->w_up[l]};
-    if ((rc = upload_matrix(c, m->bf16, gu, 2, f, d, KIND_GU, m->hd, staging, &ly.wgu))) return rc;
+    if ((rc = upload_matrix(c, m->bf16, gu, 2, f, d, KIND_GU, m->hd, staging, &ly.wgu, &ly.wgu_p))) return rc;
     one[0] = w->w_down[l];
-    if ((rc = upload_matrix(c, m->bf16, one, 1, d, f, KIND_DOWN, m->hd, staging, &ly.wdown))) return rc;
+    if ((rc = upload_matrix(c, m->bf16, one, 1, d, f, KIND_DOWN, m->hd, staging, &ly.wdown, &ly.wdown_p))) return rc;
   }
   m->kv_layer_bytes = (size_t)cfg->n_heads * m->cap * m->hd * m->esz();
   if ((rc = dev_alloc(c, &m->Kc, m->kv_layer_bytes * cfg->n_layers))) return rc;
@@ -345,14 +365,85 @@ PosRef abs_pos(const stairs_ctx* c, int p) { return PosRef{c->state + 2, p}; }  
 PosRef rel_pos(const stairs_ctx* c, int off) { return PosRef{c->state, off}; }     // state[0] == L, kept on the device
 int chunks_for(int kv_len) { return (std::max(kv_len, 1) + kAttnChunk - 1) / kAttnChunk; }
 
-// ingest positions [from, to) of the current sequence into a model's cache, no logits
-int ingest(stairs_ctx* c, Model* m, int from, int to) {
-  for (int p = from; p < to; p += kMaxRows) {
-    const int M = std::min(kMaxRows, to - p);
-    int rc = forward(c, m, abs_pos(c, p), chunks_for(p + M), M, 0);
-    if (rc) return rc;
+#define BLASCHK(c, expr)                                                      \
+  do {                                                                        \
+    rocblas_status s_ = (expr);                                               \
+    if (s_ != rocblas_status_success) {                                       \
+      (c)->err = std::string(#expr) + ": " + rocblas_status_to_string(s_);    \
+      return STAIRS_EHIP;                                                     \
+    }                                                                         \
+  } while (0)
+
+// Y[R, N] (float, row-major) = X[R, K] . W[N, K]^T with X given as bf16 high + low parts and W row-major bf16:
+// two library GEMMs, the second accumulating onto the first (fp32 accumulation, no atomics: handle default).
+int blas_gemm_hilo(stairs_ctx* c, const uint16_t* W, int N, int K, const uint16_t* hi, const uint16_t* lo, int R, float* Y) {
+  const float one = 1.f, zero = 0.f;
+  BLASCHK(c, rocblas_gemm_ex(c->blas, rocblas_operation_transpose, rocblas_operation_none, N, R, K, &one, W, rocblas_datatype_bf16_r, K,
+                             hi, rocblas_datatype_bf16_r, K, &zero, Y, rocblas_datatype_f32_r, N, Y, rocblas_datatype_f32_r, N,
+                             rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0));
+  BLASCHK(c, rocblas_gemm_ex(c->blas, rocblas_operation_transpose, rocblas_operation_none, N, R, K, &one, W, rocblas_datatype_bf16_r, K,
+                             lo, rocblas_datatype_bf16_r, K, &one, Y, rocblas_datatype_f32_r, N, Y, rocblas_datatype_f32_r, N,
+                             rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0));
+  return STAIRS_OK;
+}
+
+// Positions [from, to) of sequence slot `slot` into a model's cache in blocks of up to kPfRows rows: the four
+// projections of a layer are library GEMMs over the whole block, attention runs the decode kernel on 32 rows at a
+// time (its keys include the block's own rows, appended just before), everything else is element-wise.
+int ingest_blocks(stairs_ctx* c, Model* m, int from, int to, int slot) {
+  const stairs_model_cfg& g = m->cfg;
+  const int d = g.d_model, f = g.d_ffn, H = g.n_heads;
+  hipStream_t st = c->st;
+  const size_t slot_bytes = (size_t)g.n_layers * m->kv_layer_bytes;
+  const int* tokens = c->tokens + (size_t)slot * c->tok_stride;
+  for (int p0 = from; p0 < to; p0 += kPfRows) {
+    const int R = std::min(kPfRows, to - p0);
+    launch_pf_embed(static_cast<const uint16_t*>(m->tok_emb), tokens, p0, R, d, c->pf_x, st);
+    launch_pf_rope_table(p0, R, m->hd, g.rope_theta, c->pf_cs, st);
+    for (int l = 0; l < g.n_layers; ++l) {
+      const Layer& ly = m->layers[l];
+      char* Kl = m->Kc + (size_t)slot * slot_bytes + l * m->kv_layer_bytes;
+      char* Vl = m->Vc + (size_t)slot * slot_bytes + l * m->kv_layer_bytes;
+      int rc;
+      launch_pf_norm_split(c->pf_x, ly.attn_norm, g.rms_eps, R, d, c->pf_hi, c->pf_lo, st);
+      if ((rc = blas_gemm_hilo(c, ly.wqkv_p, 3 * d, d, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
+      launch_pf_rope_kv(c->pf_y, R, d, H, p0, c->pf_cs, c->pf_q, reinterpret_cast<_Float16*>(Kl), reinterpret_cast<_Float16*>(Vl),
+                        m->cap, st);
+      for (int r0 = 0; r0 < R; r0 += kMaxRows) {
+        const int M = std::min(kMaxRows, R - r0);
+        launch_attention(c->pf_q + (size_t)r0 * d, Kl, Vl, 1, m->cap, d, H, M, abs_pos(c, p0 + r0), 1, 0, chunks_for(p0 + r0 + M),
+                         c->nchunk_cap, c->part_o, c->part_ml, c->counters + kGemmCounters, c->pf_attn + (size_t)r0 * d, st);
+      }
+      launch_pf_norm_split(c->pf_attn, nullptr, 0.f, R, d, c->pf_hi, c->pf_lo, st);
+      if ((rc = blas_gemm_hilo(c, ly.wo_p, d, d, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
+      launch_pf_resid(c->pf_x, c->pf_y, (size_t)R * d, st);
+      launch_pf_norm_split(c->pf_x, ly.ffn_norm, g.rms_eps, R, d, c->pf_hi, c->pf_lo, st);
+      if ((rc = blas_gemm_hilo(c, ly.wgu_p, 2 * f, d, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
+      launch_pf_swiglu_split(c->pf_y, R, f, c->pf_hi, c->pf_lo, st);
+      if ((rc = blas_gemm_hilo(c, ly.wdown_p, d, f, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
+      launch_pf_resid(c->pf_x, c->pf_y, (size_t)R * d, st);
+      if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));
+    }
+    HIPCHK(c, hipGetLastError());
   }
-  if (to > m->valid) m->valid = to;
+  return STAIRS_OK;
+}
+
+constexpr int kBlockPrefillMin = 64;   // fewer rows than this go through the decode kernels
+
+// ingest positions [from, to) of sequence slot `slot` into a model's cache, no logits
+int ingest(stairs_ctx* c, Model* m, int from, int to, int slot = 0) {
+  if (c->block_prefill && m->bf16 && to - from >= kBlockPrefillMin && m->layers[0].wqkv_p) {
+    int rc = ingest_blocks(c, m, from, to, slot);
+    if (rc) return rc;
+  } else {
+    for (int p = from; p < to; p += kMaxRows) {
+      const int M = std::min(kMaxRows, to - p);
+      int rc = forward(c, m, abs_pos(c, p), chunks_for(p + M), M, 0, slot);
+      if (rc) return rc;
+    }
+  }
+  if (slot == 0 && to > m->valid) m->valid = to;
   return STAIRS_OK;
 }
 
@@ -516,6 +607,7 @@ void stairs_free(stairs_ctx* c) {
   (void)hipStreamSynchronize(c->st);
   for (auto& g : c->graphs) (void)hipGraphExecDestroy(g.exec);
   for (auto& e : c->probe_ev) (void)hipEventDestroy(e);
+  if (c->blas) (void)rocblas_destroy_handle(c->blas);
   for (void* p : c->owned) (void)hipFree(p);
   if (c->h_pinned) (void)hipHostFree(c->h_pinned);
   for (auto& e : c->ev)
@@ -550,6 +642,8 @@ int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_wei
     c->sync_launches = e && e[0] == '1';
     e = getenv("STAIRS_NO_GRAPH");
     c->use_graphs = !(e && e[0] == '1') && !c->sync_launches;
+    e = getenv("STAIRS_NO_BLOCK_PREFILL");
+    c->block_prefill = tcfg->dtype == STAIRS_DTYPE_BF16 && !(e && e[0] == '1');
   }
   int rc = STAIRS_OK;
   auto bail = [&](int code) {
@@ -588,6 +682,19 @@ int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_wei
       (rc = dev_alloc(c, &c->rope_cs, (size_t)kMaxRows * 64)) || (rc = dev_alloc(c, &c->rstd, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->tokens, (size_t)c->tok_cap + kMaxRows)) ||
       (rc = dev_alloc(c, &c->tgt_tok, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->counters, (size_t)kCounters)) || (rc = dev_alloc(c, &c->state, 2 * kSlotState)))
     return bail(rc);
+  if (c->block_prefill) {
+    const size_t wide = std::max<size_t>(3 * (size_t)dmax, 2 * (size_t)fmax), inner = std::max<size_t>(dmax, fmax);
+    if ((rc = dev_alloc(c, &c->pf_x, (size_t)kPfRows * dmax)) || (rc = dev_alloc(c, &c->pf_y, (size_t)kPfRows * wide)) ||
+        (rc = dev_alloc(c, &c->pf_q, (size_t)kPfRows * dmax)) || (rc = dev_alloc(c, &c->pf_attn, (size_t)kPfRows * dmax)) ||
+        (rc = dev_alloc(c, &c->pf_hi, (size_t)kPfRows * inner)) || (rc = dev_alloc(c, &c->pf_lo, (size_t)kPfRows * inner)) ||
+        (rc = dev_alloc(c, &c->pf_cs, (size_t)kPfRows * 64)))
+      return bail(rc);
+    if (rocblas_create_handle(&c->blas) != rocblas_status_success || rocblas_set_stream(c->blas, c->st) != rocblas_status_success ||
+        rocblas_set_pointer_mode(c->blas, rocblas_pointer_mode_host) != rocblas_status_success) {
+      c->err = "rocBLAS handle could not be created";
+      return bail(STAIRS_EHIP);
+    }
+  }
   if (hipMemsetAsync(c->state, 0, 2 * kSlotState * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
   if (hipMemsetAsync(c->counters, 0, kCounters * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
   c->h_pinned_ints = 2 + kMaxRows;
@@ -857,10 +964,7 @@ int stairs_generate_batch(stairs_ctx* c, const int32_t* const* prompts, const in
   for (int b = 0; b < B; ++b)
     for (Model* m : {&c->T, &c->D}) {
       if (m == &c->D && !c->have_draft) continue;
-      for (int p = 0; p < P[b] - 1; p += kMaxRows) {
-        const int M = std::min(kMaxRows, P[b] - 1 - p);
-        if ((rc = forward(c, m, abs_pos(c, p), chunks_for(p + M), M, 0, b))) return rc;
-      }
+      if ((rc = ingest(c, m, 0, P[b] - 1, b))) return rc;
     }
   c->T.valid = c->D.valid = 0;     // nothing the single-sequence calls could rely on
   HIPCHK(c, hipEventRecord(c->ev[1], c->st));

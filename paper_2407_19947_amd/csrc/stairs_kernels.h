@@ -126,6 +126,26 @@ void launch_argmax(const float* logits, int ld, int V, int nrows, int row0, int 
 // tokens of slot s start at s * tok_slot_stride, its tgt at s * (k+1), its state at s * kSlotState.
 void launch_accept(int* tokens, const int* tgt, int k, int* state, int nslots, int tok_slot_stride, hipStream_t st);
 
+// ---- prompt ingestion in large row blocks (bf16 models) ------------------------------------------------
+// The projections of a block of up to kPfRows prompt rows are plain GEMMs done by the BLAS library on bf16 copies
+// of the activations (high part, then low part accumulated onto it); everything around them is here.
+constexpr int kPfRows = 512;
+// x[r][:] = emb[tokens[p0 + r]][:] as float, r < R
+void launch_pf_embed(const uint16_t* emb, const int* tokens, int p0, int R, int d, float* x, hipStream_t st);
+// one row per work-group: v = x (gain == nullptr) or x * rstd * gain with rstd = 1/sqrt(mean(x^2) + eps);
+// hi = bf16(v), lo = bf16(v - hi); row-major [R, d] outputs
+void launch_pf_norm_split(const float* x, const float* gain, float eps, int R, int d, uint16_t* hi, uint16_t* lo, hipStream_t st);
+// cs[r][i] = (cos, sin)((p0 + r) * theta^(-2i/hd)), angle in double
+void launch_pf_rope_table(int p0, int R, int hd, float theta, float2* cs, hipStream_t st);
+// y = [R, 3d] (q | k | v, natural column order): rotate q and k, q -> q_rot [R, d] float, k and v -> the tiled half
+// caches of one layer at positions p0 .. p0+R-1
+void launch_pf_rope_kv(const float* y, int R, int d, int H, int p0, const float2* cs, float* q_rot, _Float16* Kc,
+                       _Float16* Vc, int cap, hipStream_t st);
+// x[i] += y[i], n a multiple of 4
+void launch_pf_resid(float* x, const float* y, size_t n, hipStream_t st);
+// y = [R, 2f] (gate | up): h = silu(gate) * up, written as bf16 high and low parts [R, f]
+void launch_pf_swiglu_split(const float* y, int R, int f, uint16_t* hi, uint16_t* lo, hipStream_t st);
+
 // dst[0..bytes) = src[0..bytes), bytes a multiple of 16: reads `bytes` and writes `bytes` of HBM
 void launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
 

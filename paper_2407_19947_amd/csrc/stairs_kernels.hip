@@ -1579,6 +1579,129 @@ void launch_accept(int* tokens, const int* tgt, int k, int* state, int nslots, i
   hipLaunchKernelGGL(k_accept, dim3(nslots), dim3(64), 0, st, tokens, tgt, k, state, tok_slot_stride);
 }
 
+// ---------------------------------------------------------------------------------------
+// prompt ingestion in large row blocks: the element-wise work around the library GEMMs
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_pf_embed(const uint16_t* __restrict__ emb, const int* __restrict__ tokens, int p0,
+                                                  int d, float* __restrict__ x) {
+  const int r = blockIdx.y, c = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (c >= d) return;
+  const uint16_t* row = emb + (size_t)tokens[p0 + r] * d + c;
+  *reinterpret_cast<float4*>(x + (size_t)r * d + c) =
+      make_float4(load_kv(row), load_kv(row + 1), load_kv(row + 2), load_kv(row + 3));
+}
+void launch_pf_embed(const uint16_t* emb, const int* tokens, int p0, int R, int d, float* x, hipStream_t st) {
+  hipLaunchKernelGGL(k_pf_embed, dim3((d + 1023) / 1024, R), dim3(256), 0, st, emb, tokens, p0, d, x);
+}
+
+__global__ __launch_bounds__(256) void k_pf_norm_split(const float* __restrict__ x, const float* __restrict__ gain, float eps,
+                                                       int d, uint16_t* __restrict__ hi, uint16_t* __restrict__ lo) {
+  __shared__ float sm[4];
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const float* row = x + (size_t)r * d;
+  float rstd = 1.0f;
+  if (gain) {
+    float ss = 0.f;
+    for (int c = tid * 4; c < d; c += 1024) {
+      const float4 v = *reinterpret_cast<const float4*>(row + c);
+      ss += sumsq4(v.x, v.y, v.z, v.w);
+    }
+    ss = block_sum_256(ss, sm);
+    rstd = 1.0f / sqrtf(ss / (float)d + eps);
+  }
+  for (int c = tid * 4; c < d; c += 1024) {
+    const float4 v = *reinterpret_cast<const float4*>(row + c);
+    float e[4] = {v.x, v.y, v.z, v.w};
+    if (gain) {
+      const float4 g = *reinterpret_cast<const float4*>(gain + c);
+      e[0] = e[0] * rstd * g.x; e[1] = e[1] * rstd * g.y; e[2] = e[2] * rstd * g.z; e[3] = e[3] * rstd * g.w;
+    }
+    uint32_t hb[4], lb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      hb[i] = bf16_bits_rne(e[i]);
+      lb[i] = bf16_bits_rne(e[i] - bf16_bits_to_float(hb[i]));
+    }
+    *reinterpret_cast<uint2*>(hi + (size_t)r * d + c) = make_uint2(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16));
+    *reinterpret_cast<uint2*>(lo + (size_t)r * d + c) = make_uint2(lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16));
+  }
+}
+void launch_pf_norm_split(const float* x, const float* gain, float eps, int R, int d, uint16_t* hi, uint16_t* lo, hipStream_t st) {
+  hipLaunchKernelGGL(k_pf_norm_split, dim3(R), dim3(256), 0, st, x, gain, eps, d, hi, lo);
+}
+
+__global__ void k_pf_rope_table(int p0, int hd, double theta, float2* __restrict__ cs) {
+  const int r = blockIdx.x, i = threadIdx.x;
+  if (i >= hd / 2) return;
+  const double ang = (double)(p0 + r) * pow(theta, -2.0 * (double)i / (double)hd);
+  cs[r * 64 + i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+void launch_pf_rope_table(int p0, int R, int hd, float theta, float2* cs, hipStream_t st) {
+  hipLaunchKernelGGL(k_pf_rope_table, dim3(R), dim3(64), 0, st, p0, hd, (double)theta, cs);
+}
+
+__global__ __launch_bounds__(256) void k_pf_rope_kv(const float* __restrict__ y, int d, int H, int hd, int p0,
+                                                    const float2* __restrict__ cs, float* __restrict__ q_rot,
+                                                    _Float16* __restrict__ Kc, _Float16* __restrict__ Vc, int cap) {
+  // thread = (row r, head h, pair e < hd/2)
+  const int r = blockIdx.y, half = hd >> 1;
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= H * half) return;
+  const int h = idx / half, e = idx - h * half;
+  const int p = p0 + r;
+  const float* yr = y + (size_t)r * 3 * d + h * hd;
+  const float2 c = cs[r * 64 + e];
+  const float2 q = rope_rotate(yr[e], yr[e + half], c);
+  q_rot[(size_t)r * d + h * hd + e] = q.x;
+  q_rot[(size_t)r * d + h * hd + e + half] = q.y;
+  const float2 k = rope_rotate(yr[d + e], yr[d + e + half], c);
+  _Float16* kd = Kc + (size_t)h * cap * hd;
+  store_kv(kd + k_cache_off(p, e, hd), k.x);
+  store_kv(kd + k_cache_off(p, e + half, hd), k.y);
+  _Float16* vd = Vc + (size_t)h * cap * hd;
+  store_kv(vd + v_cache_off(p, e, hd), yr[2 * d + e]);
+  store_kv(vd + v_cache_off(p, e + half, hd), yr[2 * d + e + half]);
+}
+void launch_pf_rope_kv(const float* y, int R, int d, int H, int p0, const float2* cs, float* q_rot, _Float16* Kc,
+                       _Float16* Vc, int cap, hipStream_t st) {
+  const int hd = d / H;
+  hipLaunchKernelGGL(k_pf_rope_kv, dim3((H * hd / 2 + 255) / 256, R), dim3(256), 0, st, y, d, H, hd, p0, cs, q_rot, Kc, Vc, cap);
+}
+
+__global__ __launch_bounds__(256) void k_pf_resid(float4* __restrict__ x, const float4* __restrict__ y, size_t n4) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  float4 a = x[i];
+  const float4 b = y[i];
+  a.x = b.x + a.x; a.y = b.y + a.y; a.z = b.z + a.z; a.w = b.w + a.w;
+  x[i] = a;
+}
+void launch_pf_resid(float* x, const float* y, size_t n, hipStream_t st) {
+  const size_t n4 = n / 4;
+  hipLaunchKernelGGL(k_pf_resid, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, reinterpret_cast<float4*>(x),
+                     reinterpret_cast<const float4*>(y), n4);
+}
+
+__global__ __launch_bounds__(256) void k_pf_swiglu_split(const float* __restrict__ y, int f, uint16_t* __restrict__ hi,
+                                                         uint16_t* __restrict__ lo) {
+  const int r = blockIdx.y, c = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (c >= f) return;
+  const float4 g = *reinterpret_cast<const float4*>(y + (size_t)r * 2 * f + c);
+  const float4 u = *reinterpret_cast<const float4*>(y + (size_t)r * 2 * f + f + c);
+  const float e[4] = {swiglu(g.x, u.x), swiglu(g.y, u.y), swiglu(g.z, u.z), swiglu(g.w, u.w)};
+  uint32_t hb[4], lb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    hb[i] = bf16_bits_rne(e[i]);
+    lb[i] = bf16_bits_rne(e[i] - bf16_bits_to_float(hb[i]));
+  }
+  *reinterpret_cast<uint2*>(hi + (size_t)r * f + c) = make_uint2(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16));
+  *reinterpret_cast<uint2*>(lo + (size_t)r * f + c) = make_uint2(lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16));
+}
+void launch_pf_swiglu_split(const float* y, int R, int f, uint16_t* hi, uint16_t* lo, hipStream_t st) {
+  hipLaunchKernelGGL(k_pf_swiglu_split, dim3((f + 1023) / 1024, R), dim3(256), 0, st, y, f, hi, lo);
+}
+
 // plain streaming copy, the calibration kernel for HBM traffic counters
 __global__ __launch_bounds__(256) void k_copy_probe(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;

@@ -343,3 +343,25 @@ def test_batch_limits_and_errors():
         with pytest.raises(pkg.StairsError) as e:
             s.reserve_batch(2)                                # fp32 models keep float caches: one sequence only
         assert e.value.code == -1
+
+
+def test_block_prefill_against_row_prefill_and_oracle(monkeypatch):
+    """Prompts of 64 rows and more are ingested in blocks with library GEMMs; the first stair batch after either
+    kind of prefill must agree with the oracle, and the two kinds with each other far inside the tolerance."""
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=3, d_model=256, n_heads=4, d_ffn=768, vocab=2048),
+                           draft=dict(kind="prefix", n_layers=1), P=600, G=8)
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)                 # 599 rows: one full block of 512 and a ragged one
+    d_tokens = [3, 1, 4]
+    T = so.OracleModel(target, np.float64)
+    ref = so.forward_full(T, np.concatenate([prompt, d_tokens]))[len(prompt) - 1:]
+    got = {}
+    for mode in ("block", "rows"):
+        if mode == "rows":
+            monkeypatch.setenv("STAIRS_NO_BLOCK_PREFILL", "1")
+        with pkg.Stairs(target, draft, k_max=3, max_seq=640) as s:
+            s.prefill(prompt)
+            _, _, logits = s.verify_tokens(d_tokens, logits=True)
+            got[mode] = logits.copy()
+        assert np.max(np.abs(got[mode] - ref)) < LOGIT_TOL_BF16, mode
+    assert np.max(np.abs(got["block"] - got["rows"])) < 2e-3
