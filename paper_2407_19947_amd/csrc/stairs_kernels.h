@@ -141,6 +141,9 @@ void launch_pf_rope_table(int p0, int R, int hd, float theta, float2* cs, hipStr
 // caches of one layer at positions p0 .. p0+R-1
 void launch_pf_rope_kv(const float* y, int R, int d, int H, int p0, const float2* cs, float* q_rot, _Float16* Kc,
                        _Float16* Vc, int cap, hipStream_t st);
+// state[z] = {p0 + z * rows, 0, 0, 1} for z < n: lets one attention launch treat n consecutive row groups of a block
+// as n "slots" that share one cache (kv_slot_stride 0)
+void launch_pf_slots(int p0, int rows, int n, int* state, hipStream_t st);
 // x[i] += y[i], n a multiple of 4
 void launch_pf_resid(float* x, const float* y, size_t n, hipStream_t st);
 // y = [R, 2f] (gate | up): h = silu(gate) * up, written as bf16 high and low parts [R, f]

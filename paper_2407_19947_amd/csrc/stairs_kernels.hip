@@ -1668,6 +1668,18 @@ void launch_pf_rope_kv(const float* y, int R, int d, int H, int p0, const float2
   hipLaunchKernelGGL(k_pf_rope_kv, dim3((H * hd / 2 + 255) / 256, R), dim3(256), 0, st, y, d, H, hd, p0, cs, q_rot, Kc, Vc, cap);
 }
 
+__global__ void k_pf_slots(int p0, int rows, int n, int* __restrict__ state) {
+  const int z = threadIdx.x;
+  if (z >= n) return;
+  state[z * kSlotState + 0] = p0 + z * rows;
+  state[z * kSlotState + 1] = 0;
+  state[z * kSlotState + 2] = 0;
+  state[z * kSlotState + 3] = 1;
+}
+void launch_pf_slots(int p0, int rows, int n, int* state, hipStream_t st) {
+  hipLaunchKernelGGL(k_pf_slots, dim3(1), dim3(64), 0, st, p0, rows, n, state);
+}
+
 __global__ __launch_bounds__(256) void k_pf_resid(float4* __restrict__ x, const float4* __restrict__ y, size_t n4) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n4) return;
