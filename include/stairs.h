@@ -102,7 +102,9 @@ void stairs_free(stairs_ctx *ctx);
 
 /* Start a new sequence S = prompt[0..P) (Sec. 3.3: the "initial sentence"): both models
  * ingest prompt[0..P-2] into their KV caches; the last prompt token is the first row of the
- * first stair batch.  Requires 1 <= P and P + k_max + 1 <= max_seq of both models.
+ * first stair batch.  Prompts of 64 rows and more are ingested in blocks of up to 512 rows (bf16 models; library
+ * GEMMs on row-major copies of the weights), shorter ones with the decode kernels.  Requires 1 <= P and
+ * P + k_max + 1 <= max_seq of both models.
  * Errors: EINVAL (NULL, P < 1, token id outside [0, vocab)), ECAPACITY. */
 int stairs_prefill(stairs_ctx *ctx, const int32_t *prompt, int32_t P);
 
