@@ -433,7 +433,6 @@ int ingest_blocks(stairs_ctx* c, Model* m, int from, int to, int slot) {
       launch_pf_swiglu_split(c->pf_y, R, f, c->pf_hi, c->pf_lo, st);
       if ((rc = blas_gemm_hilo(c, ly.wdown_p, d, f, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
       launch_pf_resid(c->pf_x, c->pf_y, (size_t)R * d, st);
-      if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));
     }
     HIPCHK(c, hipGetLastError());
   }
@@ -444,7 +443,8 @@ constexpr int kBlockPrefillMin = 64;   // fewer rows than this go through the de
 
 // ingest positions [from, to) of sequence slot `slot` into a model's cache, no logits
 int ingest(stairs_ctx* c, Model* m, int from, int to, int slot = 0) {
-  if (c->block_prefill && m->bf16 && to - from >= kBlockPrefillMin && m->layers[0].wqkv_p) {
+  // (a counter-collecting profiler needs a wait after every launch: then the decode kernels ingest the prompt)
+  if (c->block_prefill && !c->sync_launches && m->bf16 && to - from >= kBlockPrefillMin && m->layers[0].wqkv_p) {
     int rc = ingest_blocks(c, m, from, to, slot);
     if (rc) return rc;
   } else {
