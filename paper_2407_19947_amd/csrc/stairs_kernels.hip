@@ -1245,11 +1245,117 @@ __device__ __forceinline__ void split_half8(const float* v, f16x8& hi, f16x8& lo
   }
 }
 
-template <int HD, int CT>
+// Merge of the chunk partials of one head (one slot): out[m] = sum_c w_c o_c / sum_c w_c l_c with w_c = exp(max_c - max).
+// Step A: all (max, sum) pairs of all rows go to LDS in one round trip, then the row maxima.  Step B, up to kMergeCB
+// chunks: one thread per (row, 4 adjacent dims) adds its chunks up in chunk order, all loads in flight together.
+// More chunks: groups of kMergeCB chunks are summed by different threads in parallel (each as above, from zero) and the
+// group sums added in group order; the grouping depends only on the row's own position.  Dynamic LDS:
+// [M][nch_lds][2] pairs, [kMaxRows] maxima, [rows_per_pass][HD/4][groups][5] group sums.
+constexpr int kMergeCB = 20;
+template <int HD>
+__device__ __forceinline__ void attn_merge(const float* part_o, const float* part_ml, int H, int h, int M, int pos0, int kv_len,
+                                           int nchunk_cap, int nch_lds, int rows_per_pass, float* out, int d, float* s_ml) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nch_max = (kv_len > 0) ? (kv_len - 1) / kAttnChunk + 1 : 0;
+  float* s_gmax = s_ml + (size_t)M * nch_lds * 2;
+  float* grp = s_gmax + kMaxRows;
+  for (int idx = tid; idx < M * nch_max; idx += 256) {
+    const int m = idx / nch_max, cc = idx - m * nch_max;
+    const float2 ml = ld_dev2(&part_ml[(((size_t)m * H + h) * nchunk_cap + cc) * 2]);
+    s_ml[((size_t)m * nch_lds + cc) * 2] = ml.x;
+    s_ml[((size_t)m * nch_lds + cc) * 2 + 1] = ml.y;
+  }
+  __syncthreads();
+  for (int m = wave; m < M; m += 4) {                 // row maxima (max is exact in any order)
+    const int p = pos0 + m;
+    const int nch = p >= 0 ? p / kAttnChunk + 1 : 0;
+    float g = -INFINITY;
+    for (int cc = lane; cc < nch; cc += 64) g = fmaxf(g, s_ml[((size_t)m * nch_lds + cc) * 2]);
+    g = wave_max(g);
+    if (lane == 0) s_gmax[m] = g;
+  }
+  __syncthreads();
+  constexpr int QPR = HD / 4;                         // threads per row
+  constexpr int CB = kMergeCB;
+  const int G = (nch_max + CB - 1) / CB;
+  // sum of the chunks [c0, c1) of row m, dims e..e+3, weighted; all loads of the (at most CB) chunks together
+  auto group_sum = [&](int m, int e, int c0, int c1, float gmax, float4& num, float& den) {
+    const float* mlr = s_ml + (size_t)m * nch_lds * 2;
+    const float* src = part_o + ((size_t)m * H + h) * nchunk_cap * HD + e;
+    float2 va[CB], vb[CB];
+#pragma unroll
+    for (int i = 0; i < CB; ++i) {
+      const float* q = src + (size_t)min(c0 + i, c1 - 1) * HD;
+      va[i] = ld_dev2(q);
+      vb[i] = ld_dev2(q + 2);
+    }
+#pragma unroll
+    for (int i = 0; i < CB; ++i) {
+      if (c0 + i < c1) {
+        const float mc = mlr[(c0 + i) * 2];
+        const float w = (mc == -INFINITY) ? 0.f : expf(mc - gmax);
+        num.x = fmaf(w, va[i].x, num.x); num.y = fmaf(w, va[i].y, num.y);
+        num.z = fmaf(w, vb[i].x, num.z); num.w = fmaf(w, vb[i].y, num.w);
+        den = fmaf(w, mlr[(c0 + i) * 2 + 1], den);
+      }
+    }
+  };
+  if (G <= 1) {
+    for (int idx = tid; idx < M * QPR; idx += 256) {
+      const int m = idx / QPR, e = (idx - m * QPR) * 4;
+      const int p = pos0 + m;
+      float4 res = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (p >= 0) {
+        float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+        float den = 0.f;
+        group_sum(m, e, 0, p / kAttnChunk + 1, s_gmax[m], num, den);
+        res = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
+      }
+      *reinterpret_cast<float4*>(out + (size_t)m * d + h * HD + e) = res;
+    }
+    return;
+  }
+  for (int m0 = 0; m0 < M; m0 += rows_per_pass) {
+    const int rows = min(rows_per_pass, M - m0);
+    for (int idx = tid; idx < rows * QPR * G; idx += 256) {
+      const int g = idx % G, rq = idx / G;
+      const int ml = rq / QPR, e = (rq - ml * QPR) * 4, m = m0 + ml;
+      const int p = pos0 + m;
+      float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+      float den = 0.f;
+      if (p >= 0) {
+        const int nch = p / kAttnChunk + 1;
+        if (g * CB < nch) group_sum(m, e, g * CB, min(nch, (g + 1) * CB), s_gmax[m], num, den);
+      }
+      float* o = grp + (size_t)idx * 5;
+      o[0] = num.x; o[1] = num.y; o[2] = num.z; o[3] = num.w; o[4] = den;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < rows * QPR; idx += 256) {
+      const int ml = idx / QPR, e = (idx - ml * QPR) * 4, m = m0 + ml;
+      const int p = pos0 + m;
+      float4 res = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (p >= 0) {
+        const int ng = (p / kAttnChunk + 1 + CB - 1) / CB;
+        float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+        float den = 0.f;
+        for (int g = 0; g < ng; ++g) {
+          const float* o = grp + ((size_t)idx * G + g) * 5;
+          num.x += o[0]; num.y += o[1]; num.z += o[2]; num.w += o[3]; den += o[4];
+        }
+        res = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
+      }
+      *reinterpret_cast<float4*>(out + (size_t)m * d + h * HD + e) = res;
+    }
+    __syncthreads();
+  }
+}
+
+template <int HD, int CT, bool FUSED>
 __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, const _Float16* __restrict__ Kc,
                                                   const _Float16* __restrict__ Vc, int cap, int d, int H, int M,
                                                   PosRef pos, size_t kv_slot_stride, float scale, int nchunk_cap,
-                                                  float* part_o, float* part_ml, int* counters,
+                                                  int rows_per_pass, float* part_o, float* part_ml, int* counters,
                                                   float* __restrict__ out) {
   constexpr int KK = HD / 32;   // k-steps of the score MFMA
   constexpr int ET = HD / 16;   // output-dim tiles of the value MFMA
@@ -1402,57 +1508,23 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
     }
   }
 
-  // chunk hand-off: the work-group that arrives last at the head's counter merges the chunks
+  // FUSED: the work-group that arrives last at the head's counter merges the chunks; otherwise a second kernel does
+  if (!FUSED) return;
   if (!last_arrival(&counters[h], (int)gridDim.x, &s_last)) return;
-  // merge the chunks of this head.  Step A: all (max, sum) pairs of all rows go to LDS in one round trip.
-  // Step B: one thread per (row, 4 adjacent dims) adds its chunks up in chunk order, 20 chunks per round trip.
-  extern __shared__ float s_ml[];                     // [M][nch_max][2], sized by the host
-  const int nch_max = (kv_len > 0) ? (kv_len - 1) / kAttnChunk + 1 : 0;
-  for (int idx = tid; idx < M * nch_max; idx += 256) {
-    const int m = idx / nch_max, cc = idx - m * nch_max;
-    const float2 ml = ld_dev2(&part_ml[(((size_t)m * H + h) * nchunk_cap + cc) * 2]);
-    s_ml[idx * 2] = ml.x;
-    s_ml[idx * 2 + 1] = ml.y;
-  }
-  __syncthreads();
-  constexpr int QPR = HD / 4;                         // threads per row
-  for (int idx = tid; idx < M * QPR; idx += 256) {
-    const int m = idx / QPR, e = (idx - m * QPR) * 4;
-    const int p = pos0 + m;
-    float4 res = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (p >= 0) {
-      const int nch = p / kAttnChunk + 1;
-      const float* mlr = s_ml + (size_t)m * nch_max * 2;
-      float gmax = -INFINITY;
-      for (int cc = 0; cc < nch; ++cc) gmax = fmaxf(gmax, mlr[cc * 2]);
-      const float* src = part_o + ((size_t)m * H + h) * nchunk_cap * HD + e;
-      float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
-      float den = 0.f;
-      constexpr int CB = 20;
-      for (int c0 = 0; c0 < nch; c0 += CB) {
-        float2 va[CB], vb[CB];
-#pragma unroll
-        for (int i = 0; i < CB; ++i) {
-          const float* q = src + (size_t)min(c0 + i, nch - 1) * HD;
-          va[i] = ld_dev2(q);
-          vb[i] = ld_dev2(q + 2);
-        }
-#pragma unroll
-        for (int i = 0; i < CB; ++i) {
-          if (c0 + i < nch) {
-            const float mc = mlr[(c0 + i) * 2];
-            const float w = (mc == -INFINITY) ? 0.f : expf(mc - gmax);
-            num.x = fmaf(w, va[i].x, num.x); num.y = fmaf(w, va[i].y, num.y);
-            num.z = fmaf(w, vb[i].x, num.z); num.w = fmaf(w, vb[i].y, num.w);
-            den = fmaf(w, mlr[(c0 + i) * 2 + 1], den);
-          }
-        }
-      }
-      res = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
-    }
-    *reinterpret_cast<float4*>(out + (size_t)m * d + h * HD + e) = res;
-  }
+  extern __shared__ float s_ml[];
+  attn_merge<HD>(part_o, part_ml, H, h, M, pos0, kv_len, nchunk_cap, (int)gridDim.x, rows_per_pass, out, d, s_ml);
   if (tid == 0) counters[h] = 0;
+}
+
+// the merge alone (long contexts: the attention work-groups then leave without waiting for their stores)
+template <int HD>
+__global__ __launch_bounds__(256) void k_attn_merge(const float* part_o, const float* part_ml, int d, int H, int M, PosRef pos,
+                                                    int nchunk_cap, int nch_lds, int rows_per_pass, float* __restrict__ out) {
+  extern __shared__ float s_ml[];
+  const int h = blockIdx.x, row0 = blockIdx.y * M;
+  const int pos0 = pos_of(pos, row0);
+  attn_merge<HD>(part_o + (size_t)row0 * H * nchunk_cap * HD, part_ml + (size_t)row0 * H * nchunk_cap * 2, H, h, M, pos0, pos0 + M,
+                 nchunk_cap, nch_lds, rows_per_pass, out + (size_t)row0 * d, d, s_ml);
 }
 
 template <typename KV, int HD>
@@ -1484,14 +1556,27 @@ void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv
     const _Float16* K = static_cast<const _Float16*>(Kc);
     const _Float16* V = static_cast<const _Float16*>(Vc);
     dim3 grid(nchunk_launch, H, nslots), block(256);
-    const size_t lds = (size_t)M * nchunk_launch * 2 * sizeof(float);   // the merge step's (max, sum) table
-#define STAIRS_ATTN16(hdv, ct) \
-  hipLaunchKernelGGL((k_attn_f16<hdv, ct>), grid, block, lds, st, q_rot, K, V, cap, d, H, M, pos, kv_slot_stride, scale, \
-                     nchunk_cap, part_o, part_ml, counters, out)
+    // merge step's LDS: (max, sum) table, row maxima, and for more than kMergeCB chunks the group sums of as many
+    // rows per pass as fit in 48 KiB
+    const int G = (nchunk_launch + kMergeCB - 1) / kMergeCB;
+    const int rpp = G > 1 ? std::max(1, std::min(M, (48 * 1024) / (hd / 4 * G * 5 * 4))) : M;
+    const size_t lds = ((size_t)M * nchunk_launch * 2 + kMaxRows + (G > 1 ? (size_t)rpp * (hd / 4) * G * 5 : 0)) * sizeof(float);
+    // long contexts: attention work-groups only store their partials, a second kernel merges (no wait, no ticket)
+    const bool fused = nchunk_launch <= kAttnFusedMaxChunks;
+#define STAIRS_ATTN16(hdv, ct)                                                                                              \
+  if (fused)                                                                                                                \
+    hipLaunchKernelGGL((k_attn_f16<hdv, ct, true>), grid, block, lds, st, q_rot, K, V, cap, d, H, M, pos, kv_slot_stride,   \
+                       scale, nchunk_cap, rpp, part_o, part_ml, counters, out);                                             \
+  else {                                                                                                                    \
+    hipLaunchKernelGGL((k_attn_f16<hdv, ct, false>), grid, block, 0, st, q_rot, K, V, cap, d, H, M, pos, kv_slot_stride,    \
+                       scale, nchunk_cap, rpp, part_o, part_ml, counters, out);                                             \
+    hipLaunchKernelGGL((k_attn_merge<hdv>), dim3(H, nslots), dim3(256), lds, st, part_o, part_ml, d, H, M, pos, nchunk_cap, \
+                       nchunk_launch, rpp, out);                                                                            \
+  }
     if (hd == 128) {
-      if (M <= 16) STAIRS_ATTN16(128, 1); else STAIRS_ATTN16(128, 2);
+      if (M <= 16) STAIRS_ATTN16(128, 1) else STAIRS_ATTN16(128, 2)
     } else {
-      if (M <= 16) STAIRS_ATTN16(64, 1); else STAIRS_ATTN16(64, 2);
+      if (M <= 16) STAIRS_ATTN16(64, 1) else STAIRS_ATTN16(64, 2)
     }
 #undef STAIRS_ATTN16
     return;
