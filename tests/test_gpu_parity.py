@@ -365,3 +365,22 @@ def test_block_prefill_against_row_prefill_and_oracle(monkeypatch):
             got[mode] = logits.copy()
         assert np.max(np.abs(got[mode] - ref)) < LOGIT_TOL_BF16, mode
     assert np.max(np.abs(got["block"] - got["rows"])) < 2e-3
+
+
+@pytest.mark.parametrize("P", [64, 65, 66, 97, 129, 513, 514, 545, 577])
+def test_block_prefill_row_counts(P, monkeypatch):
+    """Block ingestion at the row counts where its pieces change: the smallest block (P - 1 = 64 rows; one row fewer goes through the decode kernels), whole
+    32-row groups with and without a ragged group, one row past a 512-row block; against the row prefill."""
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=2048),
+                           draft=dict(kind="prefix", n_layers=1), P=P, G=8)
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    got = {}
+    for mode in ("block", "rows"):
+        if mode == "rows":
+            monkeypatch.setenv("STAIRS_NO_BLOCK_PREFILL", "1")
+        with pkg.Stairs(target, draft, k_max=2, max_seq=P + 16) as s:
+            s.prefill(prompt)
+            _, _, logits = s.verify_tokens([5, 6], logits=True)
+            got[mode] = logits.copy()
+    assert np.max(np.abs(got["block"] - got["rows"])) < 2e-3, np.max(np.abs(got["block"] - got["rows"]))
