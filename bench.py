@@ -192,6 +192,18 @@ def main():
         extras["verify_vs_k"] = sweep
         ms, by = eng.time_kernel(7, 1, ctx_mid, 8)
         extras["draft_step"] = {"ms": ms, "GB/s": by / (ms * 1e-3) / 1e9, "frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    # ---- draft length following the acceptance (same output, other iteration count) -----------------------
+    if not args.no_sweep:
+        eng.prefill(prompt)
+        t1 = time.perf_counter()
+        toks_a, st_a = eng.decode_adaptive(G, 2)
+        dt_a = time.perf_counter() - t1
+        assert np.array_equal(toks_a, toks0), "adaptive draft length changed the output"
+        extras["adaptive_draft_length"] = {"k_first": 2, "k_max": k_max, "tokens_per_s": G / dt_a,
+                                           "iterations": st_a.iterations,
+                                           "mean_tokens_per_iteration": G / max(1, st_a.iterations)}
+        log(f"[bench] adaptive draft length: {G / dt_a:.0f} tok/s, {st_a.iterations} iterations")
+
     # ---- several sequences per forward (not the headline: the workload is one sequence) -------------------
     # B prompts of the workload's length share every weight pass: aggregate tokens/s of stairs_generate_batch,
     # decode phase, prompt 0 is the workload's prompt and must reproduce its tokens bit for bit

@@ -144,6 +144,13 @@ int stairs_generate(stairs_ctx *ctx, const int32_t *prompt, int32_t P, int32_t G
  * proposal, k > 0 without a draft model), ECAPACITY. */
 int stairs_decode(stairs_ctx *ctx, int32_t G, int32_t k, int32_t *tokens_out, stairs_stats *stats);
 
+/* stairs_decode with a draft length that follows the acceptance: the first iteration proposes k_first tokens
+ * (1 <= k_first <= k_max); after an iteration that kept all k the next one proposes min(k + 1, k_max), after one that
+ * kept n < k the next one proposes max(1, n + 1).  The output does not depend on the draft lengths (it is the
+ * target's greedy continuation, abstract / Sec. 3.1); only the number of iterations does (the paper picks one best
+ * length per model pair by a sweep, Sec. 4.3).  Requires L + G + k_max + 1 <= max_seq.  Errors as stairs_decode. */
+int stairs_decode_adaptive(stairs_ctx *ctx, int32_t G, int32_t k_first, int32_t *tokens_out, stairs_stats *stats);
+
 /* Several independent sequences in one context (a batch of stair batches): the k+1 stair rows of B sequences are
  * scored by ONE forward of B*(k+1) rows, so the weights are streamed once for all of them; every sequence keeps its
  * own key/value caches, length and acceptance (Sec. 3.3 applied per sequence), and each one's output is what

@@ -376,6 +376,28 @@ class CachedStairs:
         return gen
 
 
+def next_draft_length(k: int, n: int, k_max: int) -> int:
+    """Draft length after an iteration that proposed k tokens and kept n: everything kept -> one more (at most k_max),
+    otherwise one more than was kept (at least 1).  The paper fixes one length per model pair by a sweep (Sec. 4.3);
+    any rule gives the same output (Sec. 3.1), so this one is a choice of this build, stated in the C header too."""
+    return min(k + 1, k_max) if n == k else max(1, n + 1)
+
+
+def stairs_adaptive(target: OracleModel, draft: OracleModel, prompt: Sequence[int], G: int, k_first: int,
+                    k_max: int) -> Generation:
+    """The cached stairs loop with the draft length following next_draft_length."""
+    st = CachedStairs(target, draft, prompt, len(prompt) + G + k_max + 2)
+    gen = Generation(tokens=[])
+    k = k_first
+    while len(st.seq) - st.P < G:
+        it = st.verify(st.propose(k))
+        it.logits = None
+        gen.iterations.append(it)
+        k = next_draft_length(k, it.n_accepted, k_max)
+    gen.tokens = st.seq[st.P:st.P + G]
+    return gen
+
+
 def stairs_cached(target: OracleModel, draft: Optional[OracleModel], prompt: Sequence[int], G: int,
                   k: int, keep_logits: bool = False, kv_round=None) -> Generation:
     st = CachedStairs(target, draft, prompt, len(prompt) + G + k + 2, kv_round)

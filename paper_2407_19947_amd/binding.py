@@ -17,7 +17,7 @@ DTYPE_FP32, DTYPE_BF16 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "stairs_strerror", "stairs_last_error", "stairs_init", "stairs_free", "stairs_prefill",
-    "draft_propose", "stairs_verify", "stairs_verify_tokens", "stairs_generate", "stairs_decode", "stairs_reserve_batch", "stairs_generate_batch",
+    "draft_propose", "stairs_verify", "stairs_verify_tokens", "stairs_generate", "stairs_decode", "stairs_decode_adaptive", "stairs_reserve_batch", "stairs_generate_batch",
     "stairs_get_tokens", "stairs_gemm_host", "stairs_time_kernel", "stairs_copy_probe",
 ]
 
@@ -94,6 +94,7 @@ def lib() -> C.CDLL:
     L.stairs_verify_tokens.argtypes = [vp, i32p, i32, i32p, i32p, vp]
     L.stairs_generate.argtypes = [vp, i32p, i32, i32, i32, i32p, C.POINTER(StairsStats)]
     L.stairs_decode.argtypes = [vp, i32, i32, i32p, C.POINTER(StairsStats)]
+    L.stairs_decode_adaptive.argtypes = [vp, i32, i32, i32p, C.POINTER(StairsStats)]
     L.stairs_reserve_batch.argtypes = [vp, i32]
     L.stairs_generate_batch.argtypes = [vp, C.POINTER(i32p), i32p, i32, i32, i32, i32p, C.POINTER(StairsStats)]
     L.stairs_get_tokens.argtypes = [vp, i32p, i32, i32p]
@@ -228,6 +229,13 @@ def stairs_generate(ctx, prompt: Sequence[int], G: int, k: int):
     return out[:G], st
 
 
+def stairs_decode_adaptive(ctx, G: int, k_first: int):
+    out = np.zeros(max(G, 1), np.int32)
+    st = StairsStats()
+    _check(lib().stairs_decode_adaptive(ctx, G, k_first, _ptr(out, C.c_int32), C.byref(st)), "stairs_decode_adaptive", ctx)
+    return out[:G], st
+
+
 def stairs_reserve_batch(ctx, max_batch: int):
     _check(lib().stairs_reserve_batch(ctx, max_batch), "stairs_reserve_batch", ctx)
 
@@ -325,6 +333,9 @@ class Stairs:
 
     def decode(self, G, k):
         return stairs_decode(self.ctx, G, k)
+
+    def decode_adaptive(self, G, k_first):
+        return stairs_decode_adaptive(self.ctx, G, k_first)
 
     def reserve_batch(self, max_batch):
         stairs_reserve_batch(self.ctx, max_batch)

@@ -803,14 +803,17 @@ int stairs_verify_tokens(stairs_ctx* c, const int32_t* draft, int32_t k, int32_t
   return verify_common(c, k, target_tok_out, n_accepted_out, logits_out);
 }
 
-int stairs_decode(stairs_ctx* c, int32_t G, int32_t k, int32_t* tokens_out, stairs_stats* stats) {
+// The loop of stairs_decode.  adaptive: k is the first draft length and the next one follows from what was accepted
+// (everything: one more, up to k_max; otherwise one more than the accepted count).
+static int decode_loop(stairs_ctx* c, int32_t G, int32_t k, bool adaptive, int32_t* tokens_out, stairs_stats* stats) {
   if (!c) return STAIRS_EINVAL;
   if (!c->prefilled) return fail(c, STAIRS_ESTATE, "stairs_decode before stairs_prefill");
   if (c->pending_k >= 0) return fail(c, STAIRS_ESTATE, "a proposal is pending");
   if (G < 0 || (G > 0 && !tokens_out)) return fail(c, STAIRS_EINVAL, "G < 0 or tokens_out is NULL");
-  if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
+  if (k < 0 || k > c->k_max || (adaptive && k < 1)) return fail(c, STAIRS_EINVAL, adaptive ? "k outside [1, k_max]" : "k outside [0, k_max]");
   if (k > 0 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
-  if (!capacity_ok(c, c->L + G + k + 1)) return fail(c, STAIRS_ECAPACITY, "L + G + k + 1 exceeds max_seq");
+  const int k_cap = adaptive ? c->k_max : k;   // longest draft the loop can reach
+  if (!capacity_ok(c, c->L + G + k_cap + 1)) return fail(c, STAIRS_ECAPACITY, "L + G + k + 1 exceeds max_seq");
   stairs_stats s;
   memset(&s, 0, sizeof(s));
   const int L0 = c->L;
@@ -844,6 +847,7 @@ int stairs_decode(stairs_ctx* c, int32_t G, int32_t k, int32_t* tokens_out, stai
     s.iterations += 1;
     s.accepted += n;
     s.accept_hist[n] += 1;
+    if (adaptive) k = (n == k) ? std::min(k + 1, c->k_max) : std::max(1, n + 1);
   }
   HIPCHK(c, hipEventRecord(c->ev[0], c->st));
   HIPCHK(c, hipEventSynchronize(c->ev[0]));
@@ -861,6 +865,14 @@ int stairs_decode(stairs_ctx* c, int32_t G, int32_t k, int32_t* tokens_out, stai
   if (G > 0 && (rc = copy_out(c, tokens_out, c->tokens + L0, (size_t)G * sizeof(int)))) return rc;
   if (stats) *stats = s;
   return STAIRS_OK;
+}
+
+int stairs_decode(stairs_ctx* c, int32_t G, int32_t k, int32_t* tokens_out, stairs_stats* stats) {
+  return decode_loop(c, G, k, false, tokens_out, stats);
+}
+
+int stairs_decode_adaptive(stairs_ctx* c, int32_t G, int32_t k_first, int32_t* tokens_out, stairs_stats* stats) {
+  return decode_loop(c, G, k_first, true, tokens_out, stats);
 }
 
 int stairs_generate(stairs_ctx* c, const int32_t* prompt, int32_t P, int32_t G, int32_t k, int32_t* tokens_out,

@@ -384,3 +384,34 @@ def test_block_prefill_row_counts(P, monkeypatch):
             _, _, logits = s.verify_tokens([5, 6], logits=True)
             got[mode] = logits.copy()
     assert np.max(np.abs(got["block"] - got["rows"])) < 2e-3, np.max(np.abs(got["block"] - got["rows"]))
+
+
+def test_adaptive_draft_length_on_gpu():
+    """stairs_decode_adaptive: same tokens as plain greedy decoding on the GPU bit for bit, and on the fp32 pair the
+    same iterations and acceptance counts as the oracle's adaptive loop (both follow the rule stated in the header)."""
+    w = si.scaled_workload("cfg1_tiny_fp32")
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    G, k_first, k_max = 60, 2, 6
+    T, D = so.OracleModel(target, np.float64), so.OracleModel(draft, np.float64)
+    want = so.stairs_adaptive(T, D, prompt, G, k_first, k_max)
+    with pkg.Stairs(target, draft, k_max=k_max, max_seq=160) as s:
+        plain, _ = s.generate(prompt, G, 0)
+        s.prefill(prompt)
+        toks, st = s.decode_adaptive(G, k_first)
+        assert np.array_equal(toks, plain)
+        assert list(toks) == want.tokens
+        assert st.iterations == len(want.iterations)
+        assert st.accepted == sum(it.n_accepted for it in want.iterations)
+        with pytest.raises(pkg.StairsError) as e:
+            s.decode_adaptive(4, 0)
+        assert e.value.code == -1
+    w2 = si.scaled_workload("cfg2_125m", target=dict(n_layers=3, d_model=256, n_heads=4, d_ffn=512, vocab=2048),
+                            draft=dict(kind="prefix", n_layers=1), P=70, G=40)
+    t2, d2 = si.make_pair(w2)
+    p2 = si.make_prompt(w2)
+    with pkg.Stairs(t2, d2, k_max=8, max_seq=160) as s:
+        plain, _ = s.generate(p2, 40, 0)
+        s.prefill(p2)
+        toks, st = s.decode_adaptive(40, 3)
+        assert np.array_equal(toks, plain) and st.tokens == 40

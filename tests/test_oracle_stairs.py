@@ -94,6 +94,27 @@ def test_batch_of_prompts_is_each_prompt_on_its_own():
         assert g.tokens == so.greedy_bruteforce(T, p, 9)
 
 
+def test_adaptive_draft_length_rule_and_invariance():
+    """Pins of the adaptive loop: the rule on hand-worked cases; the output is brute-force greedy decoding whatever
+    the lengths were; every iteration's length follows from the one before; with a draft identical to the target all
+    tokens are kept, so the lengths climb 1, 2, 3, ... to k_max."""
+    assert [so.next_draft_length(k, n, 5) for k, n in [(1, 1), (4, 4), (5, 5), (4, 0), (4, 2), (3, 2), (1, 0)]] == \
+        [2, 5, 5, 1, 3, 3, 1]
+    t, d = _pair(21, 0.05, L=3, Ld=1, d=16, H=2, f=32, V=24)
+    T, D = so.OracleModel(t, np.float64), so.OracleModel(d, np.float64)
+    prompt = [4, 9, 2]
+    gen = so.stairs_adaptive(T, D, prompt, 17, 2, 4)
+    assert gen.tokens == so.greedy_bruteforce(T, prompt, 17)
+    ks = [len(it.draft) for it in gen.iterations]
+    assert ks[0] == 2
+    for a, it, b in zip(ks, gen.iterations, ks[1:]):
+        assert b == so.next_draft_length(a, it.n_accepted, 4)
+    same = so.stairs_adaptive(T, T, prompt, 20, 1, 4)
+    assert [len(it.draft) for it in same.iterations][:5] == [1, 2, 3, 4, 4]
+    assert all(it.n_accepted == len(it.draft) for it in same.iterations)
+    assert same.tokens == so.greedy_bruteforce(T, prompt, 20)
+
+
 def test_independent_draft_also_returns_plain_greedy():
     t = si.make_model(31, 3, 32, 2, 64, 50, "fp32")
     d = si.make_model(32, 2, 16, 2, 32, 50, "fp32")           # different width, unrelated weights
