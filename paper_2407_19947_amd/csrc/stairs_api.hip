@@ -403,7 +403,7 @@ int ingest_blocks(stairs_ctx* c, Model* m, int from, int to, int slot) {
     const int R = std::min(kPfRows, to - p0);
     launch_pf_embed(static_cast<const uint16_t*>(m->tok_emb), tokens, p0, R, d, c->pf_x, st);
     launch_pf_rope_table(p0, R, m->hd, g.rope_theta, c->pf_cs, st);
-    if (c->pf_part_o && R >= kMaxRows) launch_pf_slots(p0, kMaxRows, R / kMaxRows, c->pf_state, st);
+    if (c->pf_part_o) launch_pf_slots(p0, kMaxRows, (R + kMaxRows - 1) / kMaxRows, c->pf_state, st);
     for (int l = 0; l < g.n_layers; ++l) {
       const Layer& ly = m->layers[l];
       char* Kl = m->Kc + (size_t)slot * slot_bytes + l * m->kv_layer_bytes;
@@ -413,17 +413,17 @@ int ingest_blocks(stairs_ctx* c, Model* m, int from, int to, int slot) {
       if ((rc = blas_gemm_hilo(c, ly.wqkv_p, 3 * d, d, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
       launch_pf_rope_kv(c->pf_y, R, d, H, p0, c->pf_cs, c->pf_q, reinterpret_cast<_Float16*>(Kl), reinterpret_cast<_Float16*>(Vl),
                         m->cap, st);
-      // the block's full groups of 32 rows in one launch (each group is a "slot" at its own position on the same
-      // cache), a ragged last group on its own
-      const int nfull = c->pf_part_o ? R / kMaxRows : 0;
-      if (nfull > 0)
-        launch_attention(c->pf_q, Kl, Vl, 1, m->cap, d, H, kMaxRows, PosRef{c->pf_state, 0, kMaxRows}, nfull, 0,
-                         chunks_for(p0 + nfull * kMaxRows), c->nchunk_cap, c->pf_part_o, c->pf_part_ml, c->counters + kGemmCounters,
-                         c->pf_attn, st);
-      for (int r0 = nfull * kMaxRows; r0 < R; r0 += kMaxRows) {
-        const int M = std::min(kMaxRows, R - r0);
-        launch_attention(c->pf_q + (size_t)r0 * d, Kl, Vl, 1, m->cap, d, H, M, abs_pos(c, p0 + r0), 1, 0, chunks_for(p0 + r0 + M),
-                         c->nchunk_cap, c->part_o, c->part_ml, c->counters + kGemmCounters, c->pf_attn + (size_t)r0 * d, st);
+      // attention: the cache is read once per 128 rows of the block; without the large partial-result buffers the
+      // decode kernel takes 32 rows per launch
+      if (c->pf_part_o) {
+        launch_attention_block(c->pf_q, Kl, Vl, m->cap, d, H, R, p0, c->nchunk_cap, c->pf_part_o, c->pf_part_ml, c->pf_state,
+                               c->pf_attn, st);
+      } else {
+        for (int r0 = 0; r0 < R; r0 += kMaxRows) {
+          const int M = std::min(kMaxRows, R - r0);
+          launch_attention(c->pf_q + (size_t)r0 * d, Kl, Vl, 1, m->cap, d, H, M, abs_pos(c, p0 + r0), 1, 0, chunks_for(p0 + r0 + M),
+                           c->nchunk_cap, c->part_o, c->part_ml, c->counters + kGemmCounters, c->pf_attn + (size_t)r0 * d, st);
+        }
       }
       launch_pf_norm_split(c->pf_attn, nullptr, 0.f, R, d, c->pf_hi, c->pf_lo, st);
       if ((rc = blas_gemm_hilo(c, ly.wo_p, d, d, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
