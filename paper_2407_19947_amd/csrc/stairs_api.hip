@@ -69,9 +69,6 @@ struct stairs_ctx {
   float *pf_x = nullptr, *pf_y = nullptr, *pf_q = nullptr, *pf_attn = nullptr;
   uint16_t *pf_hi = nullptr, *pf_lo = nullptr;
   float2* pf_cs = nullptr;
-  // attention of a whole block in one launch: partial results for kPfRows rows and one pseudo-slot state per 32 rows
-  float *pf_part_o = nullptr, *pf_part_ml = nullptr;
-  int* pf_state = nullptr;
   int nchunk_cap = 0;
   int* tokens = nullptr;       // device copy of the sequence(s): [n_slots][tok_stride], capacity tok_cap each
   int tok_cap = 0, tok_stride = 0;
@@ -403,7 +400,6 @@ int ingest_blocks(stairs_ctx* c, Model* m, int from, int to, int slot) {
     const int R = std::min(kPfRows, to - p0);
     launch_pf_embed(static_cast<const uint16_t*>(m->tok_emb), tokens, p0, R, d, c->pf_x, st);
     launch_pf_rope_table(p0, R, m->hd, g.rope_theta, c->pf_cs, st);
-    if (c->pf_part_o) launch_pf_slots(p0, kMaxRows, (R + kMaxRows - 1) / kMaxRows, c->pf_state, st);
     for (int l = 0; l < g.n_layers; ++l) {
       const Layer& ly = m->layers[l];
       char* Kl = m->Kc + (size_t)slot * slot_bytes + l * m->kv_layer_bytes;
@@ -413,18 +409,7 @@ int ingest_blocks(stairs_ctx* c, Model* m, int from, int to, int slot) {
       if ((rc = blas_gemm_hilo(c, ly.wqkv_p, 3 * d, d, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
       launch_pf_rope_kv(c->pf_y, R, d, H, p0, c->pf_cs, c->pf_q, reinterpret_cast<_Float16*>(Kl), reinterpret_cast<_Float16*>(Vl),
                         m->cap, st);
-      // attention: the cache is read once per 128 rows of the block; without the large partial-result buffers the
-      // decode kernel takes 32 rows per launch
-      if (c->pf_part_o) {
-        launch_attention_block(c->pf_q, Kl, Vl, m->cap, d, H, R, p0, c->nchunk_cap, c->pf_part_o, c->pf_part_ml, c->pf_state,
-                               c->pf_attn, st);
-      } else {
-        for (int r0 = 0; r0 < R; r0 += kMaxRows) {
-          const int M = std::min(kMaxRows, R - r0);
-          launch_attention(c->pf_q + (size_t)r0 * d, Kl, Vl, 1, m->cap, d, H, M, abs_pos(c, p0 + r0), 1, 0, chunks_for(p0 + r0 + M),
-                           c->nchunk_cap, c->part_o, c->part_ml, c->counters + kGemmCounters, c->pf_attn + (size_t)r0 * d, st);
-        }
-      }
+      launch_attention_flash(c->pf_q, Kl, Vl, m->cap, d, H, R, p0, c->pf_attn, st);
       launch_pf_norm_split(c->pf_attn, nullptr, 0.f, R, d, c->pf_hi, c->pf_lo, st);
       if ((rc = blas_gemm_hilo(c, ly.wo_p, d, d, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
       launch_pf_resid(c->pf_x, c->pf_y, (size_t)R * d, st);
@@ -700,13 +685,6 @@ int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_wei
         (rc = dev_alloc(c, &c->pf_hi, (size_t)kPfRows * inner)) || (rc = dev_alloc(c, &c->pf_lo, (size_t)kPfRows * inner)) ||
         (rc = dev_alloc(c, &c->pf_cs, (size_t)kPfRows * 64)))
       return bail(rc);
-    // whole-block attention needs partial results for kPfRows rows; skipped (32 rows per launch then) if that is large
-    const size_t po = (size_t)kPfRows * Hmax * c->nchunk_cap * 128;
-    if (po * sizeof(float) <= ((size_t)2 << 30) && (kPfRows / kMaxRows) * Hmax <= kAttnCounters) {
-      if ((rc = dev_alloc(c, &c->pf_part_o, po)) || (rc = dev_alloc(c, &c->pf_part_ml, (size_t)kPfRows * Hmax * c->nchunk_cap * 2)) ||
-          (rc = dev_alloc(c, &c->pf_state, (size_t)(kPfRows / kMaxRows) * kSlotState)))
-        return bail(rc);
-    }
     if (rocblas_create_handle(&c->blas) != rocblas_status_success || rocblas_set_stream(c->blas, c->st) != rocblas_status_success ||
         rocblas_set_pointer_mode(c->blas, rocblas_pointer_mode_host) != rocblas_status_success) {
       c->err = "rocBLAS handle could not be created";

@@ -142,14 +142,9 @@ void launch_pf_rope_table(int p0, int R, int hd, float theta, float2* cs, hipStr
 // caches of one layer at positions p0 .. p0+R-1
 void launch_pf_rope_kv(const float* y, int R, int d, int H, int p0, const float2* cs, float* q_rot, _Float16* Kc,
                        _Float16* Vc, int cap, hipStream_t st);
-// state[z] = {p0 + z * rows, 0, 0, 1} for z < n: lets one attention launch treat n consecutive row groups of a block
-// as n "slots" that share one cache (kv_slot_stride 0)
-void launch_pf_slots(int p0, int rows, int n, int* state, hipStream_t st);
 // attention of a prefill block: R consecutive rows at positions p0.. of ONE sequence against its half caches (keys
-// 0 .. own position), q and out [R, d].  part_o / part_ml hold partial results for R rows; group_state are
-// ceil(R / kMaxRows) slot states as written by launch_pf_slots(p0, kMaxRows, ceil(R / kMaxRows), ...).
-void launch_attention_block(const float* q, const void* Kc, const void* Vc, int cap, int d, int H, int R, int p0,
-                            int nchunk_cap, float* part_o, float* part_ml, const int* group_state, float* out,
+// 0 .. own position), q and out [R, d]; running softmax in registers (no partial results, no merge), a wave per 16 rows
+void launch_attention_flash(const float* q, const void* Kc, const void* Vc, int cap, int d, int H, int R, int p0, float* out,
                             hipStream_t st);
 // x[i] += y[i], n a multiple of 4
 void launch_pf_resid(float* x, const float* y, size_t n, hipStream_t st);

@@ -1527,185 +1527,127 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* part_o, const f
                  nchunk_cap, nch_lds, rows_per_pass, out + (size_t)row0 * d, d, s_ml);
 }
 
-// Attention of a prefill block: R consecutive rows at positions p0 .. p0+R-1.  A work-group takes one 128-key chunk
-// of one head (its keys and values stay in registers) and walks over up to kPfAttnRows query rows, 16 at a time, so
-// the cache is read once per kPfAttnRows rows instead of once per 32.  Per-row arithmetic, chunk boundaries and the
-// partial results are those of k_attn_f16; the merge is k_attn_merge.
-constexpr int kPfAttnRows = 128;
+// Attention of a prefill block (R consecutive rows at positions p0 .. p0+R-1 of one sequence) without partial
+// results: a wave owns 16 query rows (a work-group 64) of one head and
+// walks over the keys 0 .. its last row's position, 32 at a time, keeping the running maximum, the running sum and the
+// running output of its rows in registers (rescaled whenever the maximum grows).  Same operands and splits as
+// k_attn_f16 (scores^T = K q^T with q as half high + low, out^T = V^T p^T with p as half high + low); the order of
+// the additions differs from the decode kernels, which only ever see their own results.
 template <int HD>
-__global__ __launch_bounds__(256) void k_attn_pf(const float* __restrict__ q, const _Float16* __restrict__ Kc,
-                                                 const _Float16* __restrict__ Vc, int cap, int d, int H, int R, int p0,
-                                                 float scale, int nchunk_cap, float* __restrict__ part_o,
-                                                 float* __restrict__ part_ml) {
+__global__ __launch_bounds__(256, 2) void k_attn_flash(const float* __restrict__ q, const _Float16* __restrict__ Kc,
+                                                    const _Float16* __restrict__ Vc, int cap, int d, int H, int R, int p0,
+                                                    float scale, float* __restrict__ out) {
   constexpr int KK = HD / 32, ET = HD / 16;
-  __shared__ float s_o[4][16][HD];
-  __shared__ float s_m[4][16], s_l[4][16];
-  const int c = blockIdx.x, h = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int h = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j = lane & 15, g = lane >> 4;
-  const int rb = blockIdx.z * kPfAttnRows;
-  const int nrows = min(kPfAttnRows, R - rb);
-  const int last_pos = p0 + rb + nrows - 1;
-  if (c * kAttnChunk > last_pos) return;              // no row of this bundle sees the chunk
-  const int kb = c * kAttnChunk + wave * 32;          // first key of this wave
-  const bool have_keys = kb <= last_pos;
-  uint4 kreg[2][KK], vreg[ET];
-  if (have_keys) {
-    const uint4* Kh = reinterpret_cast<const uint4*>(Kc + (size_t)h * cap * HD);
-    const uint4* Vh = reinterpret_cast<const uint4*>(Vc + (size_t)h * cap * HD);
+  const int r0 = blockIdx.y * 64 + wave * 16;         // first row of this wave's tile
+  if (r0 >= R) return;                                // no barriers in this kernel: waves are independent
+  const int row = r0 + j;
+  const bool row_ok = row < R;
+  const int p_row = p0 + row;
+  const int tile_last = p0 + min(r0 + 15, R - 1);     // last position of the tile = last key any of its rows sees
+  f16x8 qh[KK], ql[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+    if (row_ok) {
+      const float4* qp = reinterpret_cast<const float4*>(q + (size_t)row * d + h * HD + kk * 32 + g * 8);
+      a = qp[0];
+      b = qp[1];
+    }
+    const float v[8] = {a.x * scale, a.y * scale, a.z * scale, a.w * scale, b.x * scale, b.y * scale, b.z * scale, b.w * scale};
+    split_half8(v, qh[kk], ql[kk]);
+  }
+  const uint4* Kh = reinterpret_cast<const uint4*>(Kc + (size_t)h * cap * HD) + lane;
+  const uint4* Vh = reinterpret_cast<const uint4*>(Vc + (size_t)h * cap * HD) + lane;
+  f32x4 oacc[ET];
+#pragma unroll
+  for (int et = 0; et < ET; ++et) oacc[et] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;
+  // two register sets: the keys and values of the next step are requested before this step's arithmetic
+  uint4 kA[2][KK], vA[ET], kB[2][KK], vB[ET];
+  auto load_kv = [&](int kb, uint4 (&kreg)[2][KK], uint4 (&vreg)[ET]) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) kreg[t][kk] = Kh[((size_t)((kb >> 4) + t) * KK + kk) * 64 + lane];
+      for (int kk = 0; kk < KK; ++kk) kreg[t][kk] = Kh[((size_t)((kb >> 4) + t) * KK + kk) * 64];
 #pragma unroll
-    for (int et = 0; et < ET; ++et) vreg[et] = Vh[((size_t)(kb >> 5) * ET + et) * 64 + lane];
-  }
-#pragma nounroll
-  for (int qt = 0; qt * 16 < nrows; ++qt) {
-    const int tile_last = min(p0 + rb + qt * 16 + 15, last_pos);
-    if (c * kAttnChunk > tile_last) continue;         // uniform: these rows come before the chunk
-    const int row = rb + qt * 16 + j;                 // this lane's query row of the block
-    const bool row_ok = row < rb + nrows;
-    const int p_row = p0 + row;
-    f32x4 oacc[ET];
+    for (int et = 0; et < ET; ++et) vreg[et] = Vh[((size_t)(kb >> 5) * ET + et) * 64];
+  };
+  auto step = [&](int kb, const uint4 (&kreg)[2][KK], const uint4 (&vreg)[ET]) {
+    float sc[8];
 #pragma unroll
-    for (int et = 0; et < ET; ++et) oacc[et] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float mw = -INFINITY, lw = 0.f;
-    if (have_keys && kb <= tile_last) {
-      f16x8 qh[KK], ql[KK];
+    for (int t = 0; t < 2; ++t) {
+      f32x4 sacc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
-        if (row_ok) {
-          const float4* qp = reinterpret_cast<const float4*>(q + (size_t)row * d + h * HD + kk * 32 + g * 8);
-          a = qp[0];
-          b = qp[1];
-        }
-        const float v[8] = {a.x * scale, a.y * scale, a.z * scale, a.w * scale,
-                            b.x * scale, b.y * scale, b.z * scale, b.w * scale};
-        split_half8(v, qh[kk], ql[kk]);
+        const f16x8 a = __builtin_bit_cast(f16x8, kreg[t][kk]);
+        sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qh[kk], sacc, 0, 0, 0);
+        sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ql[kk], sacc, 0, 0, 0);
       }
-      float sc[8];
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        f32x4 sacc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          const f16x8 a = __builtin_bit_cast(f16x8, kreg[t][kk]);
-          sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qh[kk], sacc, 0, 0, 0);
-          sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ql[kk], sacc, 0, 0, 0);
-        }
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int key = kb + t * 16 + g * 4 + v;
-          sc[t * 4 + v] = (row_ok && key <= p_row) ? sacc[v] : -INFINITY;
-        }
-      }
-      float mx = sc[0];
-#pragma unroll
-      for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sc[i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      float pv[8], sum = 0.f;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        pv[i] = (mx == -INFINITY) ? 0.f : expf(sc[i] - mx);
-        sum += pv[i];
-      }
-      sum += __shfl_xor(sum, 16);
-      sum += __shfl_xor(sum, 32);
-      mw = mx;
-      lw = sum;
-      f16x8 ph, pl;
-      split_half8(pv, ph, pl);
-#pragma unroll
-      for (int et = 0; et < ET; ++et) {
-        const f16x8 a = __builtin_bit_cast(f16x8, vreg[et]);
-        oacc[et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ph, oacc[et], 0, 0, 0);
-        oacc[et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pl, oacc[et], 0, 0, 0);
+      for (int v = 0; v < 4; ++v) {
+        const int key = kb + t * 16 + g * 4 + v;
+        sc[t * 4 + v] = (row_ok && key <= p_row) ? sacc[v] : -INFINITY;
       }
     }
-    // merge the four waves (wave order)
-    if (g == 0) {
-      s_m[wave][j] = mw;
-      s_l[wave][j] = lw;
+    float mx = sc[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sc[i]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);   // m_new >= m_run > -inf there
+    float pv[8], sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      pv[i] = (m_new == -INFINITY) ? 0.f : expf(sc[i] - m_new);
+      sum += pv[i];
     }
-    __syncthreads();
-    const float mc = fmaxf(fmaxf(s_m[0][j], s_m[1][j]), fmaxf(s_m[2][j], s_m[3][j]));
-    const float fw = (mw == -INFINITY) ? 0.f : expf(mw - mc);
+    sum += __shfl_xor(sum, 16);
+    sum += __shfl_xor(sum, 32);
+    l_run = l_run * alpha + sum;
+    m_run = m_new;
+    f16x8 ph, pl;
+    split_half8(pv, ph, pl);
 #pragma unroll
     for (int et = 0; et < ET; ++et) {
-      float4 o = make_float4(oacc[et][0] * fw, oacc[et][1] * fw, oacc[et][2] * fw, oacc[et][3] * fw);
-      *reinterpret_cast<float4*>(&s_o[wave][j][et * 16 + g * 4]) = o;
+      oacc[et][0] *= alpha; oacc[et][1] *= alpha; oacc[et][2] *= alpha; oacc[et][3] *= alpha;
+      const f16x8 a = __builtin_bit_cast(f16x8, vreg[et]);
+      oacc[et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ph, oacc[et], 0, 0, 0);
+      oacc[et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pl, oacc[et], 0, 0, 0);
     }
-    __syncthreads();
-    for (int idx = tid; idx < 16 * HD / 2; idx += 256) {
-      const int jj = idx / (HD / 2), e = (idx - jj * (HD / 2)) * 2;
-      const int m = rb + qt * 16 + jj;
-      if (m < rb + nrows) {
-        const float o0 = ((s_o[0][jj][e] + s_o[1][jj][e]) + s_o[2][jj][e]) + s_o[3][jj][e];
-        const float o1 = ((s_o[0][jj][e + 1] + s_o[1][jj][e + 1]) + s_o[2][jj][e + 1]) + s_o[3][jj][e + 1];
-        *reinterpret_cast<float2*>(&part_o[(((size_t)m * H + h) * nchunk_cap + c) * HD + e]) = make_float2(o0, o1);
-      }
-    }
-    if (tid < 16 && rb + qt * 16 + tid < rb + nrows) {
-      const float m0 = s_m[0][tid], m1 = s_m[1][tid], m2 = s_m[2][tid], m3 = s_m[3][tid];
-      const float mcc = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
-      float lc = 0.f;
-      if (m0 != -INFINITY) lc += expf(m0 - mcc) * s_l[0][tid];
-      if (m1 != -INFINITY) lc += expf(m1 - mcc) * s_l[1][tid];
-      if (m2 != -INFINITY) lc += expf(m2 - mcc) * s_l[2][tid];
-      if (m3 != -INFINITY) lc += expf(m3 - mcc) * s_l[3][tid];
-      float* ml = part_ml + (((size_t)(rb + qt * 16 + tid) * H + h) * nchunk_cap + c) * 2;
-      *reinterpret_cast<float2*>(ml) = make_float2(mcc, lc);
-    }
-    __syncthreads();                                  // LDS is free for the next query tile
+  };
+  load_kv(0, kA, vA);
+#pragma nounroll
+  for (int kb = 0; kb <= tile_last; kb += 64) {
+    if (kb + 32 <= tile_last) load_kv(kb + 32, kB, vB);
+    step(kb, kA, vA);
+    if (kb + 32 > tile_last) break;
+    if (kb + 64 <= tile_last) load_kv(kb + 64, kA, vA);
+    step(kb + 32, kB, vB);
+  }
+  if (row_ok) {
+    const float inv = 1.0f / l_run;
+#pragma unroll
+    for (int et = 0; et < ET; ++et)
+      *reinterpret_cast<float4*>(out + (size_t)row * d + h * HD + et * 16 + g * 4) =
+          make_float4(oacc[et][0] * inv, oacc[et][1] * inv, oacc[et][2] * inv, oacc[et][3] * inv);
   }
 }
 
-// LDS floats of the merge step for M rows and nch chunks (see attn_merge), and the rows per pass that go with it
-static size_t merge_lds_bytes(int M, int nch, int hd, int* rpp) {
-  const int G = (nch + kMergeCB - 1) / kMergeCB;
-  *rpp = G > 1 ? std::max(1, std::min(M, (48 * 1024) / (hd / 4 * G * 5 * 4))) : M;
-  return ((size_t)M * nch * 2 + kMaxRows + (G > 1 ? (size_t)*rpp * (hd / 4) * G * 5 : 0)) * sizeof(float);
-}
-
-void launch_attention_block(const float* q, const void* Kc, const void* Vc, int cap, int d, int H, int R, int p0,
-                            int nchunk_cap, float* part_o, float* part_ml, const int* group_state, float* out,
+void launch_attention_flash(const float* q, const void* Kc, const void* Vc, int cap, int d, int H, int R, int p0, float* out,
                             hipStream_t st) {
   const int hd = d / H;
   const float scale = 1.0f / sqrtf((float)hd);
-  const int nch = (p0 + R + kAttnChunk - 1) / kAttnChunk;
   const _Float16* K = static_cast<const _Float16*>(Kc);
   const _Float16* V = static_cast<const _Float16*>(Vc);
-  dim3 grid(nch, H, (R + kPfAttnRows - 1) / kPfAttnRows);
+  dim3 grid(H, (R + 63) / 64);
   if (hd == 128)
-    hipLaunchKernelGGL((k_attn_pf<128>), grid, dim3(256), 0, st, q, K, V, cap, d, H, R, p0, scale, nchunk_cap, part_o, part_ml);
+    hipLaunchKernelGGL((k_attn_flash<128>), grid, dim3(256), 0, st, q, K, V, cap, d, H, R, p0, scale, out);
   else
-    hipLaunchKernelGGL((k_attn_pf<64>), grid, dim3(256), 0, st, q, K, V, cap, d, H, R, p0, scale, nchunk_cap, part_o, part_ml);
-  // merge: the full groups of kMaxRows rows as pseudo-slots of one launch (group_state[z] = {p0 + z*kMaxRows, 0, 0, 1}),
-  // then the ragged rest
-  const int nfull = R / kMaxRows, rem = R - nfull * kMaxRows;
-  int rpp;
-  if (nfull > 0) {
-    const size_t lds = merge_lds_bytes(kMaxRows, nch, hd, &rpp);
-    const PosRef pos{group_state, 0, kMaxRows};
-    if (hd == 128)
-      hipLaunchKernelGGL((k_attn_merge<128>), dim3(H, nfull), dim3(256), lds, st, part_o, part_ml, d, H, kMaxRows, pos, nchunk_cap, nch, rpp, out);
-    else
-      hipLaunchKernelGGL((k_attn_merge<64>), dim3(H, nfull), dim3(256), lds, st, part_o, part_ml, d, H, kMaxRows, pos, nchunk_cap, nch, rpp, out);
-  }
-  if (rem > 0) {
-    const size_t lds = merge_lds_bytes(rem, nch, hd, &rpp);
-    const size_t r0 = (size_t)nfull * kMaxRows;
-    const PosRef pos{group_state + (size_t)nfull * kSlotState, 0, 0};   // its [0] holds the position of row r0
-    const float* po = part_o + r0 * H * nchunk_cap * hd;
-    const float* pm = part_ml + r0 * H * nchunk_cap * 2;
-    if (hd == 128)
-      hipLaunchKernelGGL((k_attn_merge<128>), dim3(H, 1), dim3(256), lds, st, po, pm, d, H, rem, pos, nchunk_cap, nch, rpp, out + r0 * d);
-    else
-      hipLaunchKernelGGL((k_attn_merge<64>), dim3(H, 1), dim3(256), lds, st, po, pm, d, H, rem, pos, nchunk_cap, nch, rpp, out + r0 * d);
-  }
+    hipLaunchKernelGGL((k_attn_flash<64>), grid, dim3(256), 0, st, q, K, V, cap, d, H, R, p0, scale, out);
 }
 
 template <typename KV, int HD>
@@ -1932,18 +1874,6 @@ void launch_pf_rope_kv(const float* y, int R, int d, int H, int p0, const float2
                        _Float16* Vc, int cap, hipStream_t st) {
   const int hd = d / H;
   hipLaunchKernelGGL(k_pf_rope_kv, dim3((H * hd / 2 + 255) / 256, R), dim3(256), 0, st, y, d, H, hd, p0, cs, q_rot, Kc, Vc, cap);
-}
-
-__global__ void k_pf_slots(int p0, int rows, int n, int* __restrict__ state) {
-  const int z = threadIdx.x;
-  if (z >= n) return;
-  state[z * kSlotState + 0] = p0 + z * rows;
-  state[z * kSlotState + 1] = 0;
-  state[z * kSlotState + 2] = 0;
-  state[z * kSlotState + 3] = 1;
-}
-void launch_pf_slots(int p0, int rows, int n, int* state, hipStream_t st) {
-  hipLaunchKernelGGL(k_pf_slots, dim3(1), dim3(64), 0, st, p0, rows, n, state);
 }
 
 __global__ __launch_bounds__(256) void k_pf_resid(float4* __restrict__ x, const float4* __restrict__ y, size_t n4) {
