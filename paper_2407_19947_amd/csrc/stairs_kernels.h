@@ -10,6 +10,7 @@ namespace stairs {
 constexpr int kMaxRows = 32;        // rows (new tokens) one forward can take
 constexpr int kAttnChunk = 128;     // keys per attention work-group; boundaries are absolute positions
 constexpr int kAttnFusedMaxChunks = 24;   // more chunks per head than this: the chunk merge runs as a second kernel
+constexpr size_t kAttnMergeMaxLds = 150 * 1024;   // most dynamic LDS the chunk merge may take
 constexpr int kSsqGroupF32 = 1024;  // residual columns per sum-of-squares partial, fp32 models
 constexpr int kSsqGroupBf16 = 16;   // ... bf16 models (= one weight tile of the residual-writing GEMMs)
 constexpr int kUnitK = 256;         // k extent of one weight "unit" (8 MFMA k-steps of 32)

@@ -1680,10 +1680,13 @@ void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv
     const _Float16* V = static_cast<const _Float16*>(Vc);
     dim3 grid(nchunk_launch, H, nslots), block(256);
     // merge step's LDS: (max, sum) table, row maxima, and for more than kMergeCB chunks the group sums of as many
-    // rows per pass as fit in 48 KiB
+    // rows per pass as fit in 48 KiB, less when the table is large (the whole stays under kAttnMergeMaxLds)
     const int G = (nchunk_launch + kMergeCB - 1) / kMergeCB;
-    const int rpp = G > 1 ? std::max(1, std::min(M, (48 * 1024) / (hd / 4 * G * 5 * 4))) : M;
-    const size_t lds = ((size_t)M * nchunk_launch * 2 + kMaxRows + (G > 1 ? (size_t)rpp * (hd / 4) * G * 5 : 0)) * sizeof(float);
+    const size_t table = ((size_t)M * nchunk_launch * 2 + kMaxRows) * sizeof(float);
+    const size_t per_row = (size_t)(hd / 4) * G * 5 * sizeof(float);
+    const size_t budget = std::min<size_t>(48 * 1024, kAttnMergeMaxLds > table ? kAttnMergeMaxLds - table : 0);
+    const int rpp = G > 1 ? std::max(1, std::min(M, (int)(budget / per_row))) : M;
+    const size_t lds = table + (G > 1 ? (size_t)rpp * per_row : 0);
     // long contexts: attention work-groups only store their partials, a second kernel merges (no wait, no ticket)
     const bool fused = nchunk_launch <= kAttnFusedMaxChunks;
 #define STAIRS_ATTN16(hdv, ct)                                                                                              \
@@ -1939,6 +1942,10 @@ hipError_t configure_kernels() {
   STAIRS_OPTIN(3);
   STAIRS_OPTIN(4);
 #undef STAIRS_OPTIN
+  // the stand-alone attention merge keeps a table of all chunks in LDS: large for long contexts (the fused
+  // merge runs for at most kAttnFusedMaxChunks chunks and stays small)
+  optin((const void*)k_attn_merge<128>, kAttnMergeMaxLds);
+  optin((const void*)k_attn_merge<64>, kAttnMergeMaxLds);
   return e;
 }
 

@@ -6,7 +6,7 @@ import pytest
 import paper_2407_19947_amd as pkg
 import synth_inputs as si
 from oracle import stairs_oracle as so
-from parity_util import LOGIT_TOL_BF16, MARGIN_TOL, run_side_by_side
+from parity_util import LOGIT_TOL_BF16, MARGIN_TOL, eps_greedy_ok as eps_ok, run_side_by_side
 
 pytestmark = pytest.mark.gpu
 
@@ -415,3 +415,40 @@ def test_adaptive_draft_length_on_gpu():
         s.prefill(p2)
         toks, st = s.decode_adaptive(40, 3)
         assert np.array_equal(toks, plain) and st.tokens == 40
+
+
+def test_longest_context_stair_batches(monkeypatch):
+    """max_seq = 60000 (the most the library takes: 469 attention chunks, the stand-alone chunk merge with its
+    largest table).  The 32-row stair batch is compared with the oracle's logits stored by
+    tests/golden/make_long_context_logits.py; batches of 8 rows and 1 row from the same state must give the
+    same bits for the rows they share (a row's result does not depend on how many rows ride along)."""
+    import os
+    g = np.load(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "long_context_logits.npz"))
+    P, max_seq, d, want = int(g["P"]), int(g["max_seq"]), g["draft"], g["logits"]
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=2, d_model=256, n_heads=2, d_ffn=256, vocab=512),
+                           draft=dict(kind="prefix", n_layers=1), P=P, G=1)
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    got = {}
+    for kk in (31, 7, 0):
+        _log(f"longest context: block prefill P={P}, stair batch of {kk + 1} rows")
+        with pkg.Stairs(target, draft, k_max=31, max_seq=max_seq) as s:
+            s.prefill(prompt)
+            tgt, n, lg = s.verify_tokens(d[:kk], logits=True)
+            got[kk] = (tgt.copy(), lg.copy())
+    err = float(np.max(np.abs(got[31][1].astype(np.float64) - want)))
+    _log(f"longest context: max logit error {err:.3g}")
+    assert err <= LOGIT_TOL_BF16
+    for i in range(32):
+        assert eps_ok(want[i], int(got[31][0][i]))
+    assert np.array_equal(got[7][1], got[31][1][:8])
+    assert np.array_equal(got[0][1], got[31][1][:1])
+    # the prompt ingested 32 rows at a time through the decoding kernels instead of by blocks
+    monkeypatch.setenv("STAIRS_NO_BLOCK_PREFILL", "1")
+    _log("longest context: row prefill")
+    with pkg.Stairs(target, draft, k_max=31, max_seq=max_seq) as s:
+        s.prefill(prompt)
+        tgt, n, lg = s.verify_tokens(d, logits=True)
+    err = float(np.max(np.abs(lg.astype(np.float64) - want)))
+    _log(f"longest context, row prefill: max logit error {err:.3g}")
+    assert err <= LOGIT_TOL_BF16
