@@ -164,6 +164,8 @@ def _forward(model: OracleModel, ids: np.ndarray, pos0: int, cache: Optional[KVC
     ``kv_round``: optional function applied to keys and values before they are used/stored (the
     GPU keeps its cache in bfloat16; the parity tests can ask the oracle for the same storage
     rounding to separate that effect from arithmetic error; default: none)."""
+    if hasattr(model, "decoder_forward"):      # the decoder of an encoder-decoder model bound to its source
+        return model.decoder_forward(ids, pos0, cache, kv_round)
     dt = model.dtype
     ids = np.asarray(ids, dtype=np.int64)
     M = ids.shape[0]
