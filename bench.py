@@ -70,6 +70,44 @@ def cpu_baseline(w, target, draft, prompt, k, sample_P, sample_G):
             "iterations": len(gen.iterations), "seconds": dt}
 
 
+def encdec_leg(name):
+    """Stairs with an encoder-decoder pair: source encoded once, G decoder tokens, plain greedy (k = 0) against
+    every k of the workload; decode phase only (encoding reported beside it)."""
+    import numpy as np
+    import paper_2407_19947_amd as pkg
+    import synth_inputs as si
+    w = si.ENCDEC_WORKLOADS[name]
+    target, draft = si.make_encdec_pair(w)
+    src = si.make_source(w)
+    G, ks = w["G"], w["ks"]
+    out = {"source_len": len(src), "generate": G, "target": w["target"], "draft": w["draft"], "k_sweep": {}}
+    with pkg.StairsEncDec(target, draft, k_max=max(ks), max_src=len(src), max_seq=G + max(ks) + 8,
+                          start_token=si.DECODER_START) as eng:
+        eng.generate(src, G, 0)                                   # warm-up (graph capture, first touch)
+        base, st0 = eng.generate(src, G, 0)
+        out["plain_greedy_tokens_per_s"] = G / (st0.ms_decode * 1e-3)
+        out["encode_ms"] = st0.ms_prefill
+        out["greedy_ms_per_token"] = st0.ms_decode / G
+        out["decoder_weight_GBps_at_k0"] = target.decoder_bytes_streamed() / (st0.ms_decode / G * 1e-3) / 1e9
+        best = None
+        for k in ks:
+            eng.generate(src, G, k)
+            toks, st = eng.generate(src, G, k)
+            assert np.array_equal(toks, base), "stairs changed the output of the encoder-decoder pair"
+            tps = G / (st.ms_decode * 1e-3)
+            out["k_sweep"][str(k)] = {"tokens_per_s": tps, "iterations": st.iterations,
+                                      "mean_tokens_per_iteration": G / st.iterations,
+                                      "ms_verify_per_iteration": st.ms_verify / st.iterations,
+                                      "ms_draft_per_iteration": st.ms_draft / st.iterations}
+            if best is None or tps > best[1]:
+                best = (k, tps)
+        out["best_k"], out["tokens_per_s"] = best
+        out["time_reduction_vs_plain_greedy_pct"] = 100.0 * (1.0 - out["plain_greedy_tokens_per_s"] / best[1])
+    log(f"[bench] encoder-decoder {name}: greedy {out['plain_greedy_tokens_per_s']:.0f} tok/s, stairs k={best[0]} "
+        f"{best[1]:.0f} tok/s ({out['time_reduction_vs_plain_greedy_pct']:.1f} % less time), encode {out['encode_ms']:.1f} ms")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -80,6 +118,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the verify-vs-k sweep and the per-kernel table")
     ap.add_argument("--cpu-sample", default="64,96", help="prompt tokens, generated tokens of the CPU sample")
+    ap.add_argument("--encdec", default="t5_large_shape,t5_3b_shape",
+                    help="encoder-decoder workloads of the extra leg (comma separated, empty = none)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -227,6 +267,10 @@ def main():
                 f"{st_b.iterations} iterations, verify {batched[f'B{B}_k{kk}']['ms_verify_per_iteration']:.2f} ms/iteration")
         extras["batched_sequences"] = batched
     eng.close()
+
+    # ---- encoder-decoder pairs in the shapes of the paper's checkpoints (not the headline) -----------------
+    if not args.no_sweep and args.encdec:
+        extras["encoder_decoder"] = {name: encdec_leg(name) for name in args.encdec.split(",") if name}
 
     out = {
         "metric": "generated tokens/sec (stairs greedy, 7B-class target)" if "7b" in args.workload

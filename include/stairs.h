@@ -168,6 +168,61 @@ int stairs_reserve_batch(stairs_ctx *ctx, int32_t max_batch);
 int stairs_generate_batch(stairs_ctx *ctx, const int32_t *const *prompts, const int32_t *P, int32_t B, int32_t G,
                           int32_t k, int32_t *tokens_out, stairs_stats *stats);
 
+/* ---- encoder-decoder models (the model family of the paper's experiments, Sec. 2.3 / 4.2) ------------------
+ * The source text goes through the encoder once; the stair batch of Sec. 3.3 is made of prefixes of the DECODER
+ * sequence, and every stair row reads the same encoder output (its per-layer cross-attention keys and values are
+ * computed once by stairs_encode).  Model: the original T5 layout -- RMS layer norm before every block, attention
+ * scores q.k + bias[bucket(key position - query position)][head] without 1/sqrt(head_dim), one bias table per
+ * stack (two-sided buckets in the encoder, one-sided with the causal mask in the decoder, none in cross-attention),
+ * feed-forward W_out relu(W_in x), no other biases, untied unembedding.  bf16 matrices only.  Supported: head_dim in
+ * {64, 128}; d_model, n_heads * head_dim and d_ffn multiples of 256; vocab a multiple of 16; max_src <= 4096. */
+typedef struct {
+  int32_t n_enc_layers, n_dec_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+  int32_t max_src;            /* most source (encoder) positions                              */
+  int32_t max_seq;            /* most decoder positions (start token included)                */
+  int32_t rel_buckets;        /* rows of the bias tables, e.g. 32 (even)                      */
+  int32_t rel_max_distance;   /* distance from which the last bucket is used, e.g. 128        */
+  float rms_eps;              /* e.g. 1e-6                                                    */
+} stairs_encdec_cfg;
+
+/* Host pointers; matrices are bf16 bit patterns [out_features, in_features] row-major, a = n_heads * head_dim;
+ * gains float[d_model]; bias tables float[rel_buckets][n_heads].  enc_* members point to arrays of n_enc_layers
+ * pointers, dec_* to arrays of n_dec_layers pointers.  Tensors two models share (same host address) are kept once. */
+typedef struct {
+  const void *tok_emb;                       /* [vocab, d_model], encoder and decoder inputs */
+  const void *lm_head;                       /* [vocab, d_model]                             */
+  const float *enc_rel_bias, *dec_rel_bias;
+  const float *enc_final_norm, *dec_final_norm;
+  const float *const *enc_attn_norm, *const *enc_ffn_norm;
+  const void *const *enc_wq, *const *enc_wk, *const *enc_wv;   /* [a, d_model]     */
+  const void *const *enc_wo;                                   /* [d_model, a]     */
+  const void *const *enc_w_in;                                 /* [d_ffn, d_model] */
+  const void *const *enc_w_out;                                /* [d_model, d_ffn] */
+  const float *const *dec_attn_norm, *const *dec_cross_norm, *const *dec_ffn_norm;
+  const void *const *dec_wq, *const *dec_wk, *const *dec_wv, *const *dec_wo;   /* self-attention  */
+  const void *const *dec_cq, *const *dec_ck, *const *dec_cv, *const *dec_co;   /* cross-attention */
+  const void *const *dec_w_in, *const *dec_w_out;
+} stairs_encdec_weights;
+
+/* As stairs_init, for a target (and optional assistant) of the encoder-decoder kind.  start_token: the id every
+ * decoder sequence begins with.  Afterwards stairs_encode starts a sequence; draft_propose, stairs_verify,
+ * stairs_verify_tokens, stairs_decode, stairs_decode_adaptive and stairs_get_tokens then work on the decoder
+ * sequence exactly as for a decoder-only model (its "prompt" is the start token, P = 1).  stairs_prefill, the
+ * several-sequences calls and stairs_time_kernel return EINVAL on such a context. */
+int stairs_encdec_init(stairs_ctx **out, const stairs_encdec_cfg *tcfg, const stairs_encdec_weights *tw,
+                       const stairs_encdec_cfg *dcfg, const stairs_encdec_weights *dw, int32_t k_max,
+                       int32_t start_token, void *hip_stream);
+
+/* Run the encoder of both models over the S source tokens (host pointer), fill every decoder layer's
+ * cross-attention keys and values, and start a new decoder sequence [start_token].  1 <= S <= max_src of both
+ * models.  Errors: EINVAL, ECAPACITY (S > max_src), EHIP. */
+int stairs_encode(stairs_ctx *ctx, const int32_t *src, int32_t S);
+
+/* stairs_encode followed by stairs_decode(G, k): tokens_out[0..G) are the G tokens after the start token;
+ * requires 1 + G + k + 1 <= max_seq.  stats->ms_prefill is the time of stairs_encode. */
+int stairs_encdec_generate(stairs_ctx *ctx, const int32_t *src, int32_t S, int32_t G, int32_t k,
+                           int32_t *tokens_out, stairs_stats *stats);
+
 /* Copy the current sequence (prompt + generated) into out[0..min(cap, len)); *len = length. */
 int stairs_get_tokens(stairs_ctx *ctx, int32_t *out, int32_t cap, int32_t *len);
 

@@ -19,6 +19,7 @@ EXPORTED_SYMBOLS = [
     "stairs_strerror", "stairs_last_error", "stairs_init", "stairs_free", "stairs_prefill",
     "draft_propose", "stairs_verify", "stairs_verify_tokens", "stairs_generate", "stairs_decode", "stairs_decode_adaptive", "stairs_reserve_batch", "stairs_generate_batch",
     "stairs_get_tokens", "stairs_gemm_host", "stairs_time_kernel", "stairs_copy_probe",
+    "stairs_encdec_init", "stairs_encode", "stairs_encdec_generate",
 ]
 
 
@@ -54,6 +55,23 @@ class _Weights(C.Structure):
                 ("wo", C.POINTER(C.c_void_p)), ("ffn_norm", C.POINTER(C.c_void_p)),
                 ("w_gate", C.POINTER(C.c_void_p)), ("w_up", C.POINTER(C.c_void_p)),
                 ("w_down", C.POINTER(C.c_void_p))]
+
+
+_ED_LAYER_FIELDS = ["enc_attn_norm", "enc_ffn_norm", "enc_wq", "enc_wk", "enc_wv", "enc_wo", "enc_w_in", "enc_w_out",
+                    "dec_attn_norm", "dec_cross_norm", "dec_ffn_norm", "dec_wq", "dec_wk", "dec_wv", "dec_wo",
+                    "dec_cq", "dec_ck", "dec_cv", "dec_co", "dec_w_in", "dec_w_out"]
+
+
+class _EncDecCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_enc_layers", "n_dec_layers", "d_model", "n_heads", "head_dim", "d_ffn",
+                                         "vocab", "max_src", "max_seq", "rel_buckets", "rel_max_distance")] + \
+               [("rms_eps", C.c_float)]
+
+
+class _EncDecWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("tok_emb", "lm_head", "enc_rel_bias", "dec_rel_bias", "enc_final_norm",
+                                          "dec_final_norm")] + \
+               [(n, C.POINTER(C.c_void_p)) for n in _ED_LAYER_FIELDS]
 
 
 class StairsStats(C.Structure):
@@ -101,6 +119,10 @@ def lib() -> C.CDLL:
     L.stairs_gemm_host.argtypes = [i32, vp, f32p, f32p, i32, i32, i32, vp]
     L.stairs_time_kernel.argtypes = [vp, i32, i32, i32, i32, f32p, C.POINTER(C.c_double)]
     L.stairs_copy_probe.argtypes = [C.c_int64, i32, f32p, vp]
+    L.stairs_encdec_init.argtypes = [C.POINTER(vp), C.POINTER(_EncDecCfg), C.POINTER(_EncDecWeights),
+                                     C.POINTER(_EncDecCfg), C.POINTER(_EncDecWeights), i32, i32, vp]
+    L.stairs_encode.argtypes = [vp, i32p, i32]
+    L.stairs_encdec_generate.argtypes = [vp, i32p, i32, i32, i32, i32p, C.POINTER(StairsStats)]
     for name in EXPORTED_SYMBOLS:
         if name not in ("stairs_strerror", "stairs_last_error", "stairs_free"):
             getattr(L, name).restype = C.c_int
@@ -292,6 +314,66 @@ def stairs_copy_probe(nbytes: int, reps: int = 4, stream: Optional[int] = None) 
     return ms.value
 
 
+def _marshal_encdec(model, max_src: int, max_seq: int, keep: list):
+    """model: object with the members of synth_inputs.EncDecInputs (numpy arrays; matrices uint16 bf16 bit patterns)."""
+    def mat(a):
+        if a.dtype != np.uint16 or not a.flags["C_CONTIGUOUS"]:
+            raise TypeError("matrix must be C-contiguous uint16 (bfloat16 bit patterns)")
+        keep.append(a)
+        return a.ctypes.data
+
+    def vec(a):
+        if a.dtype != np.float32 or not a.flags["C_CONTIGUOUS"]:
+            raise TypeError("gains and bias tables must be C-contiguous float32")
+        keep.append(a)
+        return a.ctypes.data
+
+    cfg = _EncDecCfg(model.n_enc_layers, model.n_dec_layers, model.d_model, model.n_heads, model.head_dim, model.d_ffn,
+                     model.vocab, max_src, max_seq, model.rel_buckets, model.rel_max_distance, float(model.rms_eps))
+    w = _EncDecWeights()
+    w.tok_emb, w.lm_head = mat(model.tok_emb), mat(model.lm_head)
+    w.enc_rel_bias, w.dec_rel_bias = vec(model.enc_rel_bias), vec(model.dec_rel_bias)
+    w.enc_final_norm, w.dec_final_norm = vec(model.enc_final_norm), vec(model.dec_final_norm)
+    for field in _ED_LAYER_FIELDS:
+        stack, name = field[:3], field[4:]
+        layers = model.enc_layers if stack == "enc" else model.dec_layers
+        arr = (C.c_void_p * len(layers))()
+        for l, ly in enumerate(layers):
+            arr[l] = vec(ly[name]) if name.endswith("norm") else mat(ly[name])
+        keep.append(arr)
+        setattr(w, field, C.cast(arr, C.POINTER(C.c_void_p)))
+    return cfg, w
+
+
+def stairs_encdec_init(target, draft, k_max: int, max_src: int, max_seq: int, start_token: int = 0,
+                       stream: Optional[int] = None):
+    keep: list = []
+    tcfg, tw = _marshal_encdec(target, max_src, max_seq, keep)
+    ctx = C.c_void_p()
+    if draft is not None:
+        dcfg, dw = _marshal_encdec(draft, max_src, max_seq, keep)
+        rc = lib().stairs_encdec_init(C.byref(ctx), C.byref(tcfg), C.byref(tw), C.byref(dcfg), C.byref(dw), k_max,
+                                      start_token, stream)
+    else:
+        rc = lib().stairs_encdec_init(C.byref(ctx), C.byref(tcfg), C.byref(tw), None, None, k_max, start_token, stream)
+    _check(rc, "stairs_encdec_init")
+    return ctx
+
+
+def stairs_encode(ctx, src: Sequence[int]):
+    p = _i32(src)
+    _check(lib().stairs_encode(ctx, _ptr(p, C.c_int32), len(p)), "stairs_encode", ctx)
+
+
+def stairs_encdec_generate(ctx, src: Sequence[int], G: int, k: int):
+    p = _i32(src)
+    out = np.zeros(max(G, 1), np.int32)
+    st = StairsStats()
+    _check(lib().stairs_encdec_generate(ctx, _ptr(p, C.c_int32), len(p), G, k, _ptr(out, C.c_int32), C.byref(st)),
+           "stairs_encdec_generate", ctx)
+    return out[:G], st
+
+
 class Stairs:
     """Convenience wrapper owning one context."""
 
@@ -348,3 +430,18 @@ class Stairs:
 
     def time_kernel(self, which, M, ctx_len=0, reps=64):
         return stairs_time_kernel(self.ctx, which, M, ctx_len, reps)
+
+
+class StairsEncDec(Stairs):
+    """Wrapper owning one encoder-decoder context: encode() starts a sequence, the decoding calls are Stairs'."""
+
+    def __init__(self, target, draft=None, k_max: int = 0, max_src: int = 512, max_seq: int = 1024, start_token: int = 0,
+                 stream: Optional[int] = None):
+        self.vocab = target.vocab
+        self.ctx = stairs_encdec_init(target, draft, k_max, max_src, max_seq, start_token, stream)
+
+    def encode(self, src):
+        stairs_encode(self.ctx, src)
+
+    def generate(self, src, G, k):
+        return stairs_encdec_generate(self.ctx, src, G, k)

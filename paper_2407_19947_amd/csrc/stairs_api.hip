@@ -30,10 +30,33 @@ struct Layer {
   const uint16_t *wqkv_p = nullptr, *wo_p = nullptr, *wgu_p = nullptr, *wdown_p = nullptr;
 };
 
+// One layer of an encoder-decoder stack (decoder layers also hold the cross-attention block)
+struct EdLayer {
+  const float *attn_norm = nullptr, *cross_norm = nullptr, *ffn_norm = nullptr;
+  const void* wqkv = nullptr;    // [3a, d]
+  const void* wo = nullptr;      // [d, a]
+  const void* cqkv = nullptr;    // [3a, d] cross-attention q | k | v: used whole once per source, for its k and v
+  const void* cq = nullptr;      // [a, d] cross-attention query projection alone (every decoder forward)
+  const void* co = nullptr;      // [d, a]
+  const void* w_in = nullptr;    // [f, d]
+  const void* w_out = nullptr;   // [d, f]
+};
+
 struct Model {
   stairs_model_cfg cfg{};
   bool bf16 = false;
   int hd = 0, cap = 0;
+  // encoder-decoder models: cfg describes the decoder (n_layers = decoder layers, rope_theta = 0: no rotation)
+  bool encdec = false;
+  int da = 0;                       // attention width n_heads * head_dim (decoder-only models: d_model)
+  int max_src = 0, cap_src = 0;     // source positions the encoder-side buffers hold
+  std::vector<EdLayer> enc, dec;
+  const float* enc_final_norm = nullptr;
+  float* enc_bias = nullptr;        // [H][2 * max_src - 1]: bias by key position - query position + max_src - 1
+  float* dec_bias = nullptr;        // [H][cap]: bias by key position - query position + cap - 1 (keys before the query)
+  char *Ke = nullptr, *Ve = nullptr;   // encoder self-attention keys/values of the layer being run: [H][cap_src][hd]
+  char *Kx = nullptr, *Vx = nullptr;   // cross-attention keys/values: [decoder layers][H][cap_src][hd]
+  size_t kvx_layer_bytes = 0;
   const void* tok_emb = nullptr;    // row-major, cfg dtype
   const void* lm_head = nullptr;    // GEMM layout
   const float* final_norm = nullptr;
@@ -69,6 +92,11 @@ struct stairs_ctx {
   float *pf_x = nullptr, *pf_y = nullptr, *pf_q = nullptr, *pf_attn = nullptr;
   uint16_t *pf_hi = nullptr, *pf_lo = nullptr;
   float2* pf_cs = nullptr;
+  // encoder-decoder contexts: source tokens and the encoder's activations [max_src, .]
+  bool encdec = false;
+  int start_token = 0, S = 0;   // S = length of the encoded source
+  int* src_tok = nullptr;
+  float *enc_x = nullptr, *enc_ssq = nullptr, *enc_q = nullptr;
   int nchunk_cap = 0;
   int* tokens = nullptr;       // device copy of the sequence(s): [n_slots][tok_stride], capacity tok_cap each
   int tok_cap = 0, tok_stride = 0;
@@ -256,6 +284,144 @@ int build_model(stairs_ctx* c, Model* m, const stairs_model_cfg* cfg, const stai
   return STAIRS_OK;
 }
 
+// ---- encoder-decoder models -----------------------------------------------------------------------------------
+const char* check_encdec_cfg(const stairs_encdec_cfg* m) {
+  if (!m) return "model config is NULL";
+  if (m->n_enc_layers < 1 || m->n_dec_layers < 1 || m->d_model < 1 || m->n_heads < 1 || m->d_ffn < 1 || m->vocab < 1 ||
+      m->max_seq < 2 || m->max_src < 1)
+    return "model dimensions must be positive (max_seq >= 2)";
+  if (m->head_dim != 64 && m->head_dim != 128) return "head_dim must be 64 or 128";
+  const long a = (long)m->n_heads * m->head_dim;
+  if (m->d_model % 256 || m->d_ffn % 256 || a % 256) return "d_model, n_heads * head_dim and d_ffn must be multiples of 256";
+  if (m->vocab % 16) return "vocab must be a multiple of 16";
+  if (!(m->rms_eps >= 0.f)) return "rms_eps must be >= 0";
+  if (m->rel_buckets < 4 || m->rel_buckets % 4 || m->rel_max_distance <= m->rel_buckets / 2)
+    return "rel_buckets must be a multiple of 4 and rel_max_distance above rel_buckets / 2";
+  if (std::max<long>({(long)m->vocab, 3 * a, (long)m->d_ffn}) / 64 + 1 > kGemmCounters || m->n_heads > kAttnCounters)
+    return "model too wide for the hand-off counters";
+  if (m->max_seq > 60000) return "max_seq above 60000 is not supported (attention merge table lives in LDS)";
+  if (m->max_src > 4096) return "max_src above 4096 is not supported";
+  return nullptr;
+}
+
+const char* check_encdec_weights(const stairs_encdec_cfg* m, const stairs_encdec_weights* w) {
+  if (!w) return "weights are NULL";
+  if (!w->tok_emb || !w->lm_head || !w->enc_rel_bias || !w->dec_rel_bias || !w->enc_final_norm || !w->dec_final_norm ||
+      !w->enc_attn_norm || !w->enc_ffn_norm || !w->enc_wq || !w->enc_wk || !w->enc_wv || !w->enc_wo || !w->enc_w_in ||
+      !w->enc_w_out || !w->dec_attn_norm || !w->dec_cross_norm || !w->dec_ffn_norm || !w->dec_wq || !w->dec_wk ||
+      !w->dec_wv || !w->dec_wo || !w->dec_cq || !w->dec_ck || !w->dec_cv || !w->dec_co || !w->dec_w_in || !w->dec_w_out)
+    return "a weight pointer is NULL";
+  for (int l = 0; l < m->n_enc_layers; ++l)
+    if (!w->enc_attn_norm[l] || !w->enc_ffn_norm[l] || !w->enc_wq[l] || !w->enc_wk[l] || !w->enc_wv[l] || !w->enc_wo[l] ||
+        !w->enc_w_in[l] || !w->enc_w_out[l])
+      return "a per-layer weight pointer is NULL";
+  for (int l = 0; l < m->n_dec_layers; ++l)
+    if (!w->dec_attn_norm[l] || !w->dec_cross_norm[l] || !w->dec_ffn_norm[l] || !w->dec_wq[l] || !w->dec_wk[l] ||
+        !w->dec_wv[l] || !w->dec_wo[l] || !w->dec_cq[l] || !w->dec_ck[l] || !w->dec_cv[l] || !w->dec_co[l] ||
+        !w->dec_w_in[l] || !w->dec_w_out[l])
+      return "a per-layer weight pointer is NULL";
+  return nullptr;
+}
+
+// Bucket of a distance n >= 0 when one side of the query has `side` buckets: the distance itself below side / 2,
+// then logarithmically spaced up to max_distance, the last bucket beyond (rule of the original T5).
+int rel_bucket(int n, int side, int max_distance) {
+  const int exact = side / 2;
+  if (n < exact) return n;
+  const double t = std::log((double)n / exact) / std::log((double)max_distance / exact) * (side - exact);
+  return std::min(exact + (int)std::floor(t), side - 1);
+}
+
+// Bias tables by distance: dst[h][i] = table[bucket(rel)][h] with rel = i - zero (key position - query position).
+int upload_bias(stairs_ctx* c, const float* table, int buckets, int max_distance, int H, int len, int zero, bool two_sided,
+                float** out) {
+  std::vector<float> host((size_t)H * len);
+  for (int i = 0; i < len; ++i) {
+    const int rel = i - zero;
+    int b;
+    if (two_sided) b = (rel > 0 ? buckets / 2 : 0) + rel_bucket(std::abs(rel), buckets / 2, max_distance);
+    else b = rel_bucket(std::max(-rel, 0), buckets, max_distance);
+    for (int h = 0; h < H; ++h) host[(size_t)h * len + i] = table[(size_t)b * H + h];
+  }
+  int rc = dev_alloc(c, out, host.size());
+  if (rc) return rc;
+  HIPCHK(c, hipMemcpyAsync(*out, host.data(), host.size() * sizeof(float), hipMemcpyHostToDevice, c->st));
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  return STAIRS_OK;
+}
+
+int build_encdec_model(stairs_ctx* c, Model* m, const stairs_encdec_cfg* cfg, const stairs_encdec_weights* w, char* staging) {
+  m->encdec = true;
+  m->bf16 = true;
+  m->cfg = stairs_model_cfg{cfg->n_dec_layers, cfg->d_model, cfg->n_heads, cfg->d_ffn, cfg->vocab, cfg->max_seq,
+                            0.f /* no rotation */, cfg->rms_eps, STAIRS_DTYPE_BF16};
+  m->hd = cfg->head_dim;
+  m->da = cfg->n_heads * cfg->head_dim;
+  m->cap = (cfg->max_seq + 31) / 32 * 32;
+  m->max_src = cfg->max_src;
+  m->cap_src = (cfg->max_src + 31) / 32 * 32;
+  const int d = cfg->d_model, a = m->da, f = cfg->d_ffn, V = cfg->vocab, H = cfg->n_heads;
+  int rc;
+  if ((rc = upload_plain(c, w->tok_emb, (size_t)V * d * 2, KIND_EMB, &m->tok_emb))) return rc;
+  const void* one[1] = {w->lm_head};
+  if ((rc = upload_matrix(c, true, one, 1, V, d, KIND_HEAD, m->hd, staging, &m->lm_head))) return rc;
+  auto gain = [&](const float* host, const float** out) {
+    const void* p = nullptr;
+    const int r = upload_plain(c, host, (size_t)d * 4, KIND_NORM, &p);
+    *out = static_cast<const float*>(p);
+    return r;
+  };
+  auto plain = [&](const void* host, int N, int K, const void** out) {     // a matrix whose rows keep their order
+    const void* o[1] = {host};
+    return upload_matrix(c, true, o, 1, N, K, KIND_WO, m->hd, staging, out);
+  };
+  if ((rc = gain(w->dec_final_norm, &m->final_norm)) || (rc = gain(w->enc_final_norm, &m->enc_final_norm))) return rc;
+  m->enc.resize(cfg->n_enc_layers);
+  for (int l = 0; l < cfg->n_enc_layers; ++l) {
+    EdLayer& ly = m->enc[l];
+    const void* qkv[3] = {w->enc_wq[l], w->enc_wk[l], w->enc_wv[l]};
+    if ((rc = gain(w->enc_attn_norm[l], &ly.attn_norm)) || (rc = gain(w->enc_ffn_norm[l], &ly.ffn_norm)) ||
+        (rc = upload_matrix(c, true, qkv, 3, a, d, KIND_QKV, m->hd, staging, &ly.wqkv)) ||
+        (rc = plain(w->enc_wo[l], d, a, &ly.wo)) || (rc = plain(w->enc_w_in[l], f, d, &ly.w_in)) ||
+        (rc = plain(w->enc_w_out[l], d, f, &ly.w_out)))
+      return rc;
+  }
+  m->dec.resize(cfg->n_dec_layers);
+  for (int l = 0; l < cfg->n_dec_layers; ++l) {
+    EdLayer& ly = m->dec[l];
+    const void* qkv[3] = {w->dec_wq[l], w->dec_wk[l], w->dec_wv[l]};
+    const void* cqkv[3] = {w->dec_cq[l], w->dec_ck[l], w->dec_cv[l]};
+    if ((rc = gain(w->dec_attn_norm[l], &ly.attn_norm)) || (rc = gain(w->dec_cross_norm[l], &ly.cross_norm)) ||
+        (rc = gain(w->dec_ffn_norm[l], &ly.ffn_norm)) ||
+        (rc = upload_matrix(c, true, qkv, 3, a, d, KIND_QKV, m->hd, staging, &ly.wqkv)) ||
+        (rc = plain(w->dec_wo[l], d, a, &ly.wo)) ||
+        (rc = upload_matrix(c, true, cqkv, 3, a, d, KIND_QKV, m->hd, staging, &ly.cqkv)) ||
+        (rc = plain(w->dec_cq[l], a, d, &ly.cq)) || (rc = plain(w->dec_co[l], d, a, &ly.co)) ||
+        (rc = plain(w->dec_w_in[l], f, d, &ly.w_in)) || (rc = plain(w->dec_w_out[l], d, f, &ly.w_out)))
+      return rc;
+  }
+  if ((rc = upload_bias(c, w->enc_rel_bias, cfg->rel_buckets, cfg->rel_max_distance, H, 2 * m->max_src - 1, m->max_src - 1,
+                        true, &m->enc_bias)) ||
+      (rc = upload_bias(c, w->dec_rel_bias, cfg->rel_buckets, cfg->rel_max_distance, H, m->cap, m->cap - 1, false,
+                        &m->dec_bias)))
+    return rc;
+  m->kv_layer_bytes = (size_t)H * m->cap * m->hd * 2;
+  m->kvx_layer_bytes = (size_t)H * m->cap_src * m->hd * 2;
+  const size_t self_bytes = m->kv_layer_bytes * cfg->n_dec_layers, cross_bytes = m->kvx_layer_bytes * cfg->n_dec_layers;
+  if ((rc = dev_alloc(c, &m->Kc, self_bytes)) || (rc = dev_alloc(c, &m->Vc, self_bytes)) ||
+      (rc = dev_alloc(c, &m->Kx, cross_bytes)) || (rc = dev_alloc(c, &m->Vx, cross_bytes)) ||
+      (rc = dev_alloc(c, &m->Ke, m->kvx_layer_bytes)) || (rc = dev_alloc(c, &m->Ve, m->kvx_layer_bytes)))
+    return rc;
+  // positions never written meet probability 0 in the value product: they must be finite
+  HIPCHK(c, hipMemsetAsync(m->Kc, 0, self_bytes, c->st));
+  HIPCHK(c, hipMemsetAsync(m->Vc, 0, self_bytes, c->st));
+  HIPCHK(c, hipMemsetAsync(m->Kx, 0, cross_bytes, c->st));
+  HIPCHK(c, hipMemsetAsync(m->Vx, 0, cross_bytes, c->st));
+  HIPCHK(c, hipMemsetAsync(m->Ke, 0, m->kvx_layer_bytes, c->st));
+  HIPCHK(c, hipMemsetAsync(m->Ve, 0, m->kvx_layer_bytes, c->st));
+  return STAIRS_OK;
+}
+
 size_t max_matrix_bytes(const stairs_model_cfg* m) {
   const size_t esz = m->dtype == STAIRS_DTYPE_BF16 ? 2 : 4;
   const size_t d = m->d_model, f = m->d_ffn, V = m->vocab;
@@ -275,7 +441,13 @@ size_t max_partial_floats(const stairs_model_cfg* m) {
 //              M = every row -> c->logits rows 0..M-1.
 // Several sequences: pos.rps > 0 rows per slot, M = rps * (number of slots), slots 0..M/rps-1; otherwise the
 // rows belong to sequence slot `slot`.
+int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows);
+
 int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows, int slot = 0) {
+  if (m->encdec) {
+    if (slot != 0 || pos.rps) return fail(c, STAIRS_EINVAL, "forward: encoder-decoder models take one sequence");
+    return forward_ed(c, m, pos, nchunk, M, logits_rows);
+  }
   const stairs_model_cfg& g = m->cfg;
   const int d = g.d_model, f = g.d_ffn, H = g.n_heads, V = g.vocab;
   const int b = m->bf16 ? 1 : 0;
@@ -365,6 +537,170 @@ PosRef abs_pos(const stairs_ctx* c, int p) { return PosRef{c->state + 2, p}; }  
 PosRef rel_pos(const stairs_ctx* c, int off) { return PosRef{c->state, off}; }     // state[0] == L, kept on the device
 int chunks_for(int kv_len) { return (std::max(kv_len, 1) + kAttnChunk - 1) / kAttnChunk; }
 
+// The feed-forward block of an encoder-decoder layer on M rows of x (ssq = their sum-of-squares partials):
+// x += W_out relu(W_in norm(x)); h = workspace [M, f].
+void launch_ed_ffn(stairs_ctx* c, const Model* m, const EdLayer& ly, float* x, float* ssq, int M) {
+  const int d = m->cfg.d_model, f = m->cfg.d_ffn, sn = ssq_groups(d, 1);
+  const RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
+  GemmEpi e{};
+  e.counters = c->counters;
+  e.hd = m->hd;
+  e.out = c->h;
+  e.act = kActRelu;
+  RowNorm fn{ly.ffn_norm, ssq, sn, m->cfg.rms_eps, nullptr};
+  if (M > 16) {
+    launch_rstd(fn, M, d, c->rstd, c->st);
+    fn.rstd = c->rstd;
+  }
+  launch_gemm(kRoleHead, 1, ly.w_in, f, d, x, d, M, fn, c->partial, e, c->st);
+  e.act = kActNone;
+  e.out = x;
+  e.ssq_out = ssq;
+  launch_gemm(kRoleDown, 1, ly.w_out, d, f, c->h, f, M, none, c->partial, e, c->st);
+}
+
+// Decoder forward of an encoder-decoder model: M rows of the decoder sequence at pos.. (see forward()).  Per layer:
+// self-attention over the decoder's cache with the one-sided position bias, cross-attention over the keys and
+// values stairs_encode left for this layer (every row sees all c->S source positions), feed-forward.
+int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows) {
+  const stairs_model_cfg& g = m->cfg;
+  const int d = g.d_model, a = m->da, H = g.n_heads, V = g.vocab;
+  const int sn = ssq_groups(d, 1);
+  hipStream_t st = c->st;
+  const int nch_src = chunks_for(c->S);
+  if (nchunk < 1 || nchunk > c->nchunk_cap || nch_src > c->nchunk_cap || M < 1 || M > kMaxRows || c->S < 1)
+    return fail(c, STAIRS_EINVAL, "forward: launch shape outside the workspaces");
+#define SYNCPOINT()                                             \
+  do {                                                          \
+    if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));  \
+  } while (0)
+  launch_embed(m->tok_emb, 1, c->tokens, 0, pos, M, d, c->x, c->ssq, m->hd, 0.f, c->rope_cs, st);
+  SYNCPOINT();
+  const RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
+  const AttnMode self_mode{1.f, m->dec_bias, m->cap, m->cap - 1, 0};
+  const AttnMode cross_mode{1.f, nullptr, 0, 0, c->S};
+  auto normed = [&](const float* gain) {
+    RowNorm n{gain, c->ssq, sn, g.rms_eps, nullptr};
+    if (M > 16) {
+      launch_rstd(n, M, d, c->rstd, st);
+      n.rstd = c->rstd;
+    }
+    return n;
+  };
+  for (int l = 0; l < g.n_layers; ++l) {
+    const EdLayer& ly = m->dec[l];
+    char* Kl = m->Kc + l * m->kv_layer_bytes;
+    char* Vl = m->Vc + l * m->kv_layer_bytes;
+    GemmEpi e{};
+    e.counters = c->counters;
+    e.rope_cs = c->rope_cs;
+    e.pos = pos;
+    e.Kc = reinterpret_cast<_Float16*>(Kl);
+    e.Vc = reinterpret_cast<_Float16*>(Vl);
+    e.cap = m->cap;
+    e.H = H;
+    e.hd = m->hd;
+    e.ssq_out = c->ssq;
+    e.out = c->q_rot;
+    launch_gemm(kRoleQKV, 1, ly.wqkv, 3 * a, d, c->x, d, M, normed(ly.attn_norm), c->partial, e, st);
+    SYNCPOINT();
+    launch_attention(c->q_rot, Kl, Vl, 1, m->cap, a, H, M, pos, 1, 0, nchunk, c->nchunk_cap, c->part_o, c->part_ml,
+                     c->counters + kGemmCounters, c->attn_out, st, self_mode);
+    SYNCPOINT();
+    e.out = c->x;
+    launch_gemm(kRoleWo, 1, ly.wo, d, a, c->attn_out, a, M, none, c->partial, e, st);
+    SYNCPOINT();
+    e.out = c->q_rot;
+    launch_gemm(kRoleHead, 1, ly.cq, a, d, c->x, d, M, normed(ly.cross_norm), c->partial, e, st);
+    SYNCPOINT();
+    launch_attention(c->q_rot, m->Kx + l * m->kvx_layer_bytes, m->Vx + l * m->kvx_layer_bytes, 1, m->cap_src, a, H, M, pos, 1, 0,
+                     nch_src, c->nchunk_cap, c->part_o, c->part_ml, c->counters + kGemmCounters, c->attn_out, st, cross_mode);
+    SYNCPOINT();
+    e.out = c->x;
+    launch_gemm(kRoleWo, 1, ly.co, d, a, c->attn_out, a, M, none, c->partial, e, st);
+    SYNCPOINT();
+    launch_ed_ffn(c, m, ly, c->x, c->ssq, M);
+    SYNCPOINT();
+  }
+  if (logits_rows > 0) {
+    const int r0 = M - logits_rows;
+    GemmEpi e{};
+    e.counters = c->counters;
+    e.out = c->logits;
+    e.hd = m->hd;
+    launch_gemm(kRoleHead, 1, m->lm_head, V, d, c->x + (size_t)r0 * d, d, logits_rows,
+                RowNorm{m->final_norm, c->ssq + r0 * sn, sn, g.rms_eps}, c->partial, e, st);
+    SYNCPOINT();
+  }
+  HIPCHK(c, hipGetLastError());
+  return STAIRS_OK;
+}
+
+// Encoder of one model over the c->S source tokens in c->src_tok, 32 rows at a time through the decode kernels:
+// per layer first the keys and values of all rows (every row attends to every source position), then attention
+// with the two-sided position bias, output projection and feed-forward block by block.  Afterwards the
+// cross-attention keys and values of every decoder layer are formed from the normalised encoder output.
+int encode_model(stairs_ctx* c, Model* m) {
+  const stairs_model_cfg& g = m->cfg;
+  const int d = g.d_model, a = m->da, H = g.n_heads, S = c->S;
+  const int sn = ssq_groups(d, 1);
+  hipStream_t st = c->st;
+  const int nch = chunks_for(S);
+  if (S < 1 || S > m->max_src || nch > c->nchunk_cap) return fail(c, STAIRS_EINVAL, "encode: source outside the workspaces");
+  const RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
+  const AttnMode mode{1.f, m->enc_bias, 2 * m->max_src - 1, m->max_src - 1, S};
+  auto rows_of = [&](int b) { return std::min(kMaxRows, S - b); };
+  auto epi_for = [&](int b, char* K, char* V, float* out) {
+    GemmEpi e{};
+    e.counters = c->counters;
+    e.rope_cs = c->rope_cs;
+    e.pos = abs_pos(c, b);
+    e.Kc = reinterpret_cast<_Float16*>(K);
+    e.Vc = reinterpret_cast<_Float16*>(V);
+    e.cap = m->cap_src;
+    e.H = H;
+    e.hd = m->hd;
+    e.ssq_out = c->enc_ssq + (size_t)b * sn;
+    e.out = out;
+    return e;
+  };
+  auto normed = [&](const float* gain, int b, int M) {
+    RowNorm n{gain, c->enc_ssq + (size_t)b * sn, sn, g.rms_eps, nullptr};
+    if (M > 16) {
+      launch_rstd(n, M, d, c->rstd, st);
+      n.rstd = c->rstd;
+    }
+    return n;
+  };
+  for (int b = 0; b < S; b += kMaxRows)
+    launch_embed(m->tok_emb, 1, c->src_tok, 0, abs_pos(c, b), rows_of(b), d, c->enc_x + (size_t)b * d, c->enc_ssq + (size_t)b * sn,
+                 m->hd, 0.f, c->rope_cs, st);
+  for (size_t l = 0; l < m->enc.size(); ++l) {
+    const EdLayer& ly = m->enc[l];
+    for (int b = 0; b < S; b += kMaxRows) {
+      const int M = rows_of(b);
+      launch_gemm(kRoleQKV, 1, ly.wqkv, 3 * a, d, c->enc_x + (size_t)b * d, d, M, normed(ly.attn_norm, b, M), c->partial,
+                  epi_for(b, m->Ke, m->Ve, c->enc_q + (size_t)b * a), st);
+    }
+    for (int b = 0; b < S; b += kMaxRows) {
+      const int M = rows_of(b);
+      launch_attention(c->enc_q + (size_t)b * a, m->Ke, m->Ve, 1, m->cap_src, a, H, M, abs_pos(c, b), 1, 0, nch, c->nchunk_cap,
+                       c->part_o, c->part_ml, c->counters + kGemmCounters, c->attn_out, st, mode);
+      launch_gemm(kRoleWo, 1, ly.wo, d, a, c->attn_out, a, M, none, c->partial, epi_for(b, m->Ke, m->Ve, c->enc_x + (size_t)b * d), st);
+      launch_ed_ffn(c, m, ly, c->enc_x + (size_t)b * d, c->enc_ssq + (size_t)b * sn, M);
+    }
+    if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));
+  }
+  for (size_t l = 0; l < m->dec.size(); ++l)
+    for (int b = 0; b < S; b += kMaxRows) {
+      const int M = rows_of(b);
+      launch_gemm(kRoleQKV, 1, m->dec[l].cqkv, 3 * a, d, c->enc_x + (size_t)b * d, d, M, normed(m->enc_final_norm, b, M), c->partial,
+                  epi_for(b, m->Kx + l * m->kvx_layer_bytes, m->Vx + l * m->kvx_layer_bytes, c->enc_q + (size_t)b * a), st);
+    }
+  HIPCHK(c, hipGetLastError());
+  return STAIRS_OK;
+}
+
 #define BLASCHK(c, expr)                                                      \
   do {                                                                        \
     rocblas_status s_ = (expr);                                               \
@@ -429,7 +765,7 @@ constexpr int kBlockPrefillMin = 64;   // fewer rows than this go through the de
 // ingest positions [from, to) of sequence slot `slot` into a model's cache, no logits
 int ingest(stairs_ctx* c, Model* m, int from, int to, int slot = 0) {
   // (a counter-collecting profiler needs a wait after every launch: then the decode kernels ingest the prompt)
-  if (c->block_prefill && !c->sync_launches && m->bf16 && to - from >= kBlockPrefillMin && m->layers[0].wqkv_p) {
+  if (c->block_prefill && !c->sync_launches && m->bf16 && !m->encdec && to - from >= kBlockPrefillMin && m->layers[0].wqkv_p) {
     int rc = ingest_blocks(c, m, from, to, slot);
     if (rc) return rc;
   } else {
@@ -612,6 +948,43 @@ void stairs_free(stairs_ctx* c) {
   delete c;
 }
 
+// Sizes of the workspaces shared by the two models of a context
+struct WsDims {
+  int dmax, amax, fmax, Hmax, capmax, vocab;
+  int srcmax;          // encoder-decoder contexts: most source positions, else 0
+  size_t partial_floats;
+};
+
+// new context on the caller's stream (or one of its own), environment switches read
+static stairs_ctx* new_ctx(void* hip_stream, int k_max, bool have_draft, bool block_prefill_ok, int* rc_out) {
+  stairs_ctx* c = new (std::nothrow) stairs_ctx;
+  if (!c) {
+    *rc_out = STAIRS_ENOMEM;
+    return nullptr;
+  }
+  c->st = static_cast<hipStream_t>(hip_stream);
+  if (!c->st) {   // graph capture needs a real stream; default priority
+    if (hipStreamCreateWithFlags(&c->st, hipStreamNonBlocking) != hipSuccess) {
+      delete c;
+      *rc_out = STAIRS_EHIP;
+      return nullptr;
+    }
+    c->own_stream = true;
+  }
+  c->k_max = k_max;
+  c->have_draft = have_draft;
+  const char* e = getenv("STAIRS_SYNC_LAUNCHES");
+  c->sync_launches = e && e[0] == '1';
+  e = getenv("STAIRS_NO_GRAPH");
+  c->use_graphs = !(e && e[0] == '1') && !c->sync_launches;
+  e = getenv("STAIRS_NO_BLOCK_PREFILL");
+  c->block_prefill = block_prefill_ok && !(e && e[0] == '1');
+  *rc_out = STAIRS_OK;
+  return c;
+}
+
+static int alloc_workspaces(stairs_ctx* c, const WsDims& w);
+
 int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_weights* tw, const stairs_model_cfg* dcfg,
                 const stairs_weights* dw, int32_t k_max, void* hip_stream) {
   if (!out) return STAIRS_EINVAL;
@@ -621,27 +994,9 @@ int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_wei
   if (have_draft && (check_cfg(dcfg) || check_weights(dcfg, dw) || dcfg->vocab != tcfg->vocab)) return STAIRS_EINVAL;
   if (k_max < 0 || k_max >= STAIRS_MAX_ROWS) return STAIRS_EINVAL;
   if (!have_draft && k_max != 0) return STAIRS_EINVAL;
-  stairs_ctx* c = new (std::nothrow) stairs_ctx;
-  if (!c) return STAIRS_ENOMEM;
-  c->st = static_cast<hipStream_t>(hip_stream);
-  if (!c->st) {   // graph capture needs a real stream; default priority
-    if (hipStreamCreateWithFlags(&c->st, hipStreamNonBlocking) != hipSuccess) {
-      delete c;
-      return STAIRS_EHIP;
-    }
-    c->own_stream = true;
-  }
-  c->k_max = k_max;
-  c->have_draft = have_draft;
-  {
-    const char* e = getenv("STAIRS_SYNC_LAUNCHES");
-    c->sync_launches = e && e[0] == '1';
-    e = getenv("STAIRS_NO_GRAPH");
-    c->use_graphs = !(e && e[0] == '1') && !c->sync_launches;
-    e = getenv("STAIRS_NO_BLOCK_PREFILL");
-    c->block_prefill = tcfg->dtype == STAIRS_DTYPE_BF16 && !(e && e[0] == '1');
-  }
   int rc = STAIRS_OK;
+  stairs_ctx* c = new_ctx(hip_stream, k_max, have_draft, tcfg->dtype == STAIRS_DTYPE_BF16, &rc);
+  if (!c) return rc;
   auto bail = [&](int code) {
     if (code == STAIRS_EHIP || code == STAIRS_ENOMEM) fprintf(stderr, "stairs_init: %s\n", c->err.c_str());
     stairs_free(c);
@@ -660,19 +1015,37 @@ int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_wei
   (void)hipFree(staging);
   if (rc) return bail(rc);
 
-  const int dmax = std::max(tcfg->d_model, have_draft ? dcfg->d_model : 0);
-  const int fmax = std::max(tcfg->d_ffn, have_draft ? dcfg->d_ffn : 0);
-  const int Hmax = std::max(tcfg->n_heads, have_draft ? dcfg->n_heads : 0);
-  const int capmax = std::max(tcfg->max_seq, have_draft ? dcfg->max_seq : 0);
-  size_t pf = max_partial_floats(tcfg);
-  if (have_draft) pf = std::max(pf, max_partial_floats(dcfg));
-  c->nchunk_cap = (capmax + kAttnChunk - 1) / kAttnChunk;
+  WsDims w{};
+  w.dmax = w.amax = std::max(tcfg->d_model, have_draft ? dcfg->d_model : 0);
+  w.fmax = std::max(tcfg->d_ffn, have_draft ? dcfg->d_ffn : 0);
+  w.Hmax = std::max(tcfg->n_heads, have_draft ? dcfg->n_heads : 0);
+  w.capmax = std::max(tcfg->max_seq, have_draft ? dcfg->max_seq : 0);
+  w.vocab = tcfg->vocab;
+  w.partial_floats = max_partial_floats(tcfg);
+  if (have_draft) w.partial_floats = std::max(w.partial_floats, max_partial_floats(dcfg));
+  if ((rc = alloc_workspaces(c, w))) return bail(rc);
+  *out = c;
+  return STAIRS_OK;
+}
+
+// workspaces, token array, state, counters, pinned host mirror, events
+static int alloc_workspaces(stairs_ctx* c, const WsDims& w) {
+  int rc;
+  auto bail = [&](int code) { return code; };
+  const int dmax = w.dmax, fmax = w.fmax, Hmax = w.Hmax, capmax = w.capmax;
+  const int wide = std::max(w.dmax, w.amax);
+  c->nchunk_cap = (std::max(capmax, w.srcmax) + kAttnChunk - 1) / kAttnChunk;
   c->tok_cap = capmax;
   c->tok_stride = capmax + kMaxRows;
+  if (w.srcmax > 0 &&
+      ((rc = dev_alloc(c, &c->src_tok, (size_t)w.srcmax + kMaxRows)) || (rc = dev_alloc(c, &c->enc_x, (size_t)w.srcmax * dmax)) ||
+       (rc = dev_alloc(c, &c->enc_ssq, (size_t)w.srcmax * ssq_groups(dmax, 1))) ||
+       (rc = dev_alloc(c, &c->enc_q, (size_t)w.srcmax * w.amax))))
+    return rc;
   if ((rc = dev_alloc(c, &c->x, (size_t)kMaxRows * dmax)) || (rc = dev_alloc(c, &c->ssq, (size_t)kMaxRows * ssq_groups(dmax, 1))) ||
-      (rc = dev_alloc(c, &c->q_rot, (size_t)kMaxRows * dmax)) || (rc = dev_alloc(c, &c->attn_out, (size_t)kMaxRows * dmax)) ||
-      (rc = dev_alloc(c, &c->h, (size_t)kMaxRows * fmax)) || (rc = dev_alloc(c, &c->logits, (size_t)kMaxRows * tcfg->vocab)) ||
-      (rc = dev_alloc(c, &c->partial, pf)) ||
+      (rc = dev_alloc(c, &c->q_rot, (size_t)kMaxRows * wide)) || (rc = dev_alloc(c, &c->attn_out, (size_t)kMaxRows * wide)) ||
+      (rc = dev_alloc(c, &c->h, (size_t)kMaxRows * fmax)) || (rc = dev_alloc(c, &c->logits, (size_t)kMaxRows * w.vocab)) ||
+      (rc = dev_alloc(c, &c->partial, w.partial_floats)) ||
       (rc = dev_alloc(c, &c->part_o, (size_t)kMaxRows * Hmax * c->nchunk_cap * 128)) ||
       (rc = dev_alloc(c, &c->part_ml, (size_t)kMaxRows * Hmax * c->nchunk_cap * 2)) ||
       (rc = dev_alloc(c, &c->rope_cs, (size_t)kMaxRows * 64)) || (rc = dev_alloc(c, &c->rstd, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->tokens, (size_t)c->tok_cap + kMaxRows)) ||
@@ -701,12 +1074,100 @@ int stairs_init(stairs_ctx** out, const stairs_model_cfg* tcfg, const stairs_wei
   for (auto& e : c->ev)
     if (hipEventCreate(&e) != hipSuccess) return bail(STAIRS_EHIP);
   if (hipStreamSynchronize(c->st) != hipSuccess) return bail(STAIRS_EHIP);
+  return STAIRS_OK;
+}
+
+static size_t ed_matrix_bytes(const stairs_encdec_cfg* m) {
+  const size_t d = m->d_model, a = (size_t)m->n_heads * m->head_dim, f = m->d_ffn, V = m->vocab;
+  return std::max({3 * a * d, f * d, V * d}) * 2;
+}
+static size_t ed_partial_floats(const stairs_encdec_cfg* m) {
+  const size_t d = m->d_model, a = (size_t)m->n_heads * m->head_dim, f = m->d_ffn, V = m->vocab;
+  const size_t sd = gemm_slices(m->d_model, 1), sa = gemm_slices((int)a, 1), sf = gemm_slices(m->d_ffn, 1);
+  return kMaxRows * std::max({sd * 3 * a, sd * f, sd * V, sa * d, sf * d});
+}
+
+int stairs_encdec_init(stairs_ctx** out, const stairs_encdec_cfg* tcfg, const stairs_encdec_weights* tw,
+                       const stairs_encdec_cfg* dcfg, const stairs_encdec_weights* dw, int32_t k_max, int32_t start_token,
+                       void* hip_stream) {
+  if (!out) return STAIRS_EINVAL;
+  *out = nullptr;
+  if (check_encdec_cfg(tcfg) || check_encdec_weights(tcfg, tw)) return STAIRS_EINVAL;
+  const bool have_draft = dcfg != nullptr;
+  if (have_draft && (check_encdec_cfg(dcfg) || check_encdec_weights(dcfg, dw) || dcfg->vocab != tcfg->vocab)) return STAIRS_EINVAL;
+  if (k_max < 0 || k_max >= STAIRS_MAX_ROWS || (!have_draft && k_max != 0)) return STAIRS_EINVAL;
+  if (start_token < 0 || start_token >= tcfg->vocab) return STAIRS_EINVAL;
+  int rc = STAIRS_OK;
+  stairs_ctx* c = new_ctx(hip_stream, k_max, have_draft, false, &rc);
+  if (!c) return rc;
+  c->encdec = true;
+  c->start_token = start_token;
+  auto bail = [&](int code) {
+    if (code == STAIRS_EHIP || code == STAIRS_ENOMEM) fprintf(stderr, "stairs_encdec_init: %s\n", c->err.c_str());
+    stairs_free(c);
+    return code;
+  };
+  if (configure_kernels() != hipSuccess) return bail(STAIRS_EHIP);
+  size_t stage_bytes = ed_matrix_bytes(tcfg);
+  if (have_draft) stage_bytes = std::max(stage_bytes, ed_matrix_bytes(dcfg));
+  char* staging = nullptr;
+  if (hipMalloc(reinterpret_cast<void**>(&staging), stage_bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return bail(STAIRS_ENOMEM);
+  }
+  rc = build_encdec_model(c, &c->T, tcfg, tw, staging);
+  if (!rc && have_draft) rc = build_encdec_model(c, &c->D, dcfg, dw, staging);
+  (void)hipFree(staging);
+  if (rc) return bail(rc);
+  WsDims w{};
+  w.dmax = std::max(tcfg->d_model, have_draft ? dcfg->d_model : 0);
+  w.amax = std::max(c->T.da, have_draft ? c->D.da : 0);
+  w.fmax = std::max(tcfg->d_ffn, have_draft ? dcfg->d_ffn : 0);
+  w.Hmax = std::max(tcfg->n_heads, have_draft ? dcfg->n_heads : 0);
+  w.capmax = std::max(tcfg->max_seq, have_draft ? dcfg->max_seq : 0);
+  w.srcmax = std::max(tcfg->max_src, have_draft ? dcfg->max_src : 0);
+  w.vocab = tcfg->vocab;
+  w.partial_floats = ed_partial_floats(tcfg);
+  if (have_draft) w.partial_floats = std::max(w.partial_floats, ed_partial_floats(dcfg));
+  if ((rc = alloc_workspaces(c, w))) return bail(rc);
   *out = c;
+  return STAIRS_OK;
+}
+
+int stairs_encode(stairs_ctx* c, const int32_t* src, int32_t S) {
+  if (!c) return STAIRS_EINVAL;
+  if (!c->encdec) return fail(c, STAIRS_EINVAL, "stairs_encode needs an encoder-decoder context");
+  if (!src || S < 1) return fail(c, STAIRS_EINVAL, "source is NULL or empty");
+  if (S > c->T.max_src || (c->have_draft && S > c->D.max_src)) return fail(c, STAIRS_ECAPACITY, "source exceeds max_src");
+  for (int i = 0; i < S; ++i)
+    if (src[i] < 0 || src[i] >= c->T.cfg.vocab) return fail(c, STAIRS_EINVAL, "source token outside the vocabulary");
+  if (!capacity_ok(c, 1 + c->k_max + 1)) return fail(c, STAIRS_ECAPACITY, "1 + k_max + 1 exceeds max_seq");
+  c->prefilled = false;
+  c->pending_k = -1;
+  // captured iterations hold the previous source length
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  for (auto& g : c->graphs) (void)hipGraphExecDestroy(g.exec);
+  c->graphs.clear();
+  HIPCHK(c, hipMemsetAsync(c->counters, 0, kCounters * sizeof(int), c->st));
+  HIPCHK(c, hipMemcpyAsync(c->src_tok, src, (size_t)S * sizeof(int), hipMemcpyHostToDevice, c->st));
+  const int st4[kSlotState] = {1, 0, 0, 1};
+  HIPCHK(c, hipMemcpyAsync(c->state, st4, sizeof(st4), hipMemcpyHostToDevice, c->st));
+  HIPCHK(c, hipMemcpyAsync(c->tokens, &c->start_token, sizeof(int), hipMemcpyHostToDevice, c->st));
+  HIPCHK(c, hipStreamSynchronize(c->st));     // st4 is on the stack
+  c->S = S;
+  c->L = c->P = 1;
+  c->T.valid = c->D.valid = 0;
+  int rc = encode_model(c, &c->T);
+  if (!rc && c->have_draft) rc = encode_model(c, &c->D);
+  if (rc) return rc;
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  c->prefilled = true;
   return STAIRS_OK;
 }
 
 int stairs_prefill(stairs_ctx* c, const int32_t* prompt, int32_t P) {
   if (!c) return STAIRS_EINVAL;
+  if (c->encdec) return fail(c, STAIRS_EINVAL, "encoder-decoder context: stairs_encode starts a sequence");
   if (!prompt || P < 1) return fail(c, STAIRS_EINVAL, "prompt is NULL or empty");
   for (int i = 0; i < P; ++i)
     if (prompt[i] < 0 || prompt[i] >= c->T.cfg.vocab) return fail(c, STAIRS_EINVAL, "prompt token outside the vocabulary");
@@ -875,8 +1336,31 @@ int stairs_generate(stairs_ctx* c, const int32_t* prompt, int32_t P, int32_t G, 
   return STAIRS_OK;
 }
 
+int stairs_encdec_generate(stairs_ctx* c, const int32_t* src, int32_t S, int32_t G, int32_t k, int32_t* tokens_out,
+                           stairs_stats* stats) {
+  if (!c) return STAIRS_EINVAL;
+  if (!c->encdec) return fail(c, STAIRS_EINVAL, "stairs_encdec_generate needs an encoder-decoder context");
+  if (G < 0 || (G > 0 && !tokens_out)) return fail(c, STAIRS_EINVAL, "G < 0 or tokens_out is NULL");
+  if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
+  if (k > 0 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
+  if (!capacity_ok(c, 1 + G + k + 1)) return fail(c, STAIRS_ECAPACITY, "1 + G + k + 1 exceeds max_seq");
+  float ms_encode = 0.f;
+  HIPCHK(c, hipEventRecord(c->ev[0], c->st));
+  int rc = stairs_encode(c, src, S);
+  if (rc) return rc;
+  HIPCHK(c, hipEventRecord(c->ev[1], c->st));
+  HIPCHK(c, hipEventSynchronize(c->ev[1]));
+  HIPCHK(c, hipEventElapsedTime(&ms_encode, c->ev[0], c->ev[1]));
+  stairs_stats s;
+  if ((rc = stairs_decode(c, G, k, tokens_out, &s))) return rc;
+  s.ms_prefill = ms_encode;
+  if (stats) *stats = s;
+  return STAIRS_OK;
+}
+
 int stairs_reserve_batch(stairs_ctx* c, int32_t max_batch) {
   if (!c) return STAIRS_EINVAL;
+  if (c->encdec) return fail(c, STAIRS_EINVAL, "encoder-decoder contexts take one sequence");
   if (max_batch < 1 || max_batch > kMaxRows / 2) return fail(c, STAIRS_EINVAL, "max_batch outside [1, STAIRS_MAX_ROWS / 2]");
   if (!c->T.bf16 || (c->have_draft && !c->D.bf16)) return fail(c, STAIRS_EINVAL, "several sequences need bf16 models");
   if (max_batch * std::max(c->T.cfg.n_heads, c->have_draft ? c->D.cfg.n_heads : 0) > kAttnCounters)
@@ -934,6 +1418,7 @@ int stairs_reserve_batch(stairs_ctx* c, int32_t max_batch) {
 int stairs_generate_batch(stairs_ctx* c, const int32_t* const* prompts, const int32_t* P, int32_t B, int32_t G, int32_t k,
                           int32_t* tokens_out, stairs_stats* stats) {
   if (!c) return STAIRS_EINVAL;
+  if (c->encdec) return fail(c, STAIRS_EINVAL, "encoder-decoder contexts take one sequence");
   if (B < 1 || B > c->n_slots) return fail(c, STAIRS_EINVAL, "B outside [1, reserved batch]");
   if (G < 0 || (G > 0 && !tokens_out)) return fail(c, STAIRS_EINVAL, "G < 0 or tokens_out is NULL");
   if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
@@ -1130,6 +1615,7 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
   if (!c) return STAIRS_EINVAL;
   if (which < 0 || which > 9 || M < 1 || M > kMaxRows || reps < 1 || !ms_per_launch)
     return fail(c, STAIRS_EINVAL, "bad argument to stairs_time_kernel");
+  if (c->encdec) return fail(c, STAIRS_EINVAL, "stairs_time_kernel takes decoder-only contexts");
   if (c->pending_k >= 0) return fail(c, STAIRS_ESTATE, "a proposal is pending");
   if (which == 7 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
   Model* m = which == 7 ? &c->D : &c->T;

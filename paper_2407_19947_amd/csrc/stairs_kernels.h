@@ -79,7 +79,9 @@ enum { kRoleQKV = 0, kRoleWo = 1, kRoleGateUp = 2, kRoleDown = 3, kRoleHead = 4 
 //            float [M, d], append k and v to the layer's cache at that position
 //   Wo/Down: out = x [M, N] += result; ssq_out[m][g] = sum over column group g of x^2
 //   GateUp : out = h [M, N/2] = silu(gate) * up
-//   Head   : out = logits [M, N]
+//   Head   : out = logits [M, N]; with act == kActRelu out = max(result, 0) (the first matrix of an ungated
+//            feed-forward block)
+enum { kActNone = 0, kActRelu = 1 };
 struct GemmEpi {
   int* counters;            // bf16 path: one int per column group, zero between launches
   float* out;
@@ -92,6 +94,7 @@ struct GemmEpi {
   float* Vc32;
   int cap, H, hd;
   size_t kv_slot_stride;    // elements between the caches of consecutive slots (several sequences), else unused
+  int act;                  // Head role only: kActNone / kActRelu
 };
 
 // ---- skinny GEMM + epilogue ---------------------------------------------------------------
@@ -106,7 +109,7 @@ void launch_rstd(RowNorm nrm, int M, int K, float* rstd, hipStream_t st);
 
 // ---- small kernels ----------------------------------------------------------------------
 // x[m][:] = emb[tokens[pos+m]][:] (row of zeros if pos+m < 0), plus sum-of-squares partials; the same launch
-// fills the rotation table cs of the M positions (see launch_rope_table)
+// fills the rotation table cs of the M positions (see launch_rope_table); theta <= 0: the identity rotation (1, 0)
 void launch_embed(const void* emb, int emb_bf16, const int* tokens, int tok_slot_stride, PosRef pos, int M, int d,
                   float* x, float* ssq_part, int hd, float theta, float2* cs, hipStream_t st);
 // cs[m][i] = (cos, sin)((pos+m) * theta^(-2i/hd)), angle formed in double
@@ -115,9 +118,17 @@ void launch_rope_table(PosRef pos, int M, int hd, float theta, float2* cs, hipSt
 // (kv_half: half caches in the tiled layout; else float caches [H][cap][hd]); counters: one int per (slot, head).
 // Several sequences (pos.rps > 0, half caches only): M = pos.rps rows per slot, nslots slots, caches kv_slot_stride
 // elements apart.
+// am (half caches only): score scale, additive bias by relative position, fixed key set (see AttnMode).
+struct AttnMode {
+  float scale;        // multiplies q; <= 0: 1/sqrt(head_dim)
+  const float* bias;  // nullptr, or [H][bias_ld]: score += bias[h][key position - query position + bias_zero]
+  int bias_ld, bias_zero;
+  int kv_fixed;       // > 0: no causal mask, every row sees the keys 0 .. kv_fixed-1 (nchunk_launch must cover them)
+};
 void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv_half, int cap, int d, int H, int M,
                       PosRef pos, int nslots, size_t kv_slot_stride, int nchunk_launch, int nchunk_cap, float* part_o,
-                      float* part_ml, int* counters, float* out, hipStream_t st);
+                      float* part_ml, int* counters, float* out, hipStream_t st,
+                      const AttnMode& am = AttnMode{0.f, nullptr, 0, 0, 0});
 // out[o(r)] = argmax_v logits[row0 + r * row_stride][v], ties -> lowest v, r < nrows.  One sequence:
 // o(r) = *out_pos.base + out_pos.offset + r (base == nullptr: r).  Several: o(r) = s * out_slot_stride + position of
 // out_pos for row r, nothing written for a slot that is not active.

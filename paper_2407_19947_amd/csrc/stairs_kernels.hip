@@ -258,7 +258,11 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
     constexpr int PR = W / 4;
     for (int idx = tid; idx < M * PR; idx += 256) {
       const int m = idx / PR, col = c0 + (idx - m * PR) * 4;
-      if (col < N) *reinterpret_cast<float4*>(epi.out + (size_t)m * N + col) = slice_sum4<PAIRS>(partial, S, stride, (size_t)m * N + col);
+      if (col < N) {
+        float4 a = slice_sum4<PAIRS>(partial, S, stride, (size_t)m * N + col);
+        if (epi.act == kActRelu) a = make_float4(fmaxf(a.x, 0.f), fmaxf(a.y, 0.f), fmaxf(a.z, 0.f), fmaxf(a.w, 0.f));
+        *reinterpret_cast<float4*>(epi.out + (size_t)m * N + col) = a;
+      }
     }
   } else if (ROLE == kRoleWo || ROLE == kRoleDown) {
     constexpr int PR = W / 4;                       // threads per row; 4 adjacent threads = one 16-column tile
@@ -759,8 +763,9 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
     const float b = lds_chunk_sum(csum + (m << 4) + j + 8, R * 16, nchunks);
     const int col = tile * 16 + j;
     if (ROLE == kRoleHead) {
-      epi.out[(size_t)m * N + col] = a;
-      epi.out[(size_t)m * N + col + 8] = b;
+      const bool relu = epi.act == kActRelu;
+      epi.out[(size_t)m * N + col] = relu ? fmaxf(a, 0.f) : a;
+      epi.out[(size_t)m * N + col + 8] = relu ? fmaxf(b, 0.f) : b;
     } else if (ROLE == kRoleGateUp) {
       epi.out[(size_t)m * (N >> 1) + tile * 8 + j] = swiglu(a, b);
     } else {
@@ -1036,7 +1041,7 @@ __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const 
     const int i = threadIdx.x;
     if (i < hd / 2) {
       const double ang = (double)p * pow(theta, -2.0 * (double)i / (double)hd);
-      cs[m * 64 + i] = make_float2((float)cos(ang), (float)sin(ang));
+      cs[m * 64 + i] = theta > 0.0 ? make_float2((float)cos(ang), (float)sin(ang)) : make_float2(1.f, 0.f);
     }
     return;
   }
@@ -1253,8 +1258,9 @@ __device__ __forceinline__ void split_half8(const float* v, f16x8& hi, f16x8& lo
 // [M][nch_lds][2] pairs, [kMaxRows] maxima, [rows_per_pass][HD/4][groups][5] group sums.
 constexpr int kMergeCB = 20;
 template <int HD>
-__device__ __forceinline__ void attn_merge(const float* part_o, const float* part_ml, int H, int h, int M, int pos0, int kv_len,
-                                           int nchunk_cap, int nch_lds, int rows_per_pass, float* out, int d, float* s_ml) {
+__device__ __forceinline__ void attn_merge(const float* part_o, const float* part_ml, int H, int h, int M, int pos0, int step,
+                                           int kv_len, int nchunk_cap, int nch_lds, int rows_per_pass, float* out, int d,
+                                           float* s_ml) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nch_max = (kv_len > 0) ? (kv_len - 1) / kAttnChunk + 1 : 0;
   float* s_gmax = s_ml + (size_t)M * nch_lds * 2;
@@ -1267,7 +1273,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
   }
   __syncthreads();
   for (int m = wave; m < M; m += 4) {                 // row maxima (max is exact in any order)
-    const int p = pos0 + m;
+    const int p = pos0 + m * step;
     const int nch = p >= 0 ? p / kAttnChunk + 1 : 0;
     float g = -INFINITY;
     for (int cc = lane; cc < nch; cc += 64) g = fmaxf(g, s_ml[((size_t)m * nch_lds + cc) * 2]);
@@ -1303,7 +1309,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
   if (G <= 1) {
     for (int idx = tid; idx < M * QPR; idx += 256) {
       const int m = idx / QPR, e = (idx - m * QPR) * 4;
-      const int p = pos0 + m;
+      const int p = pos0 + m * step;
       float4 res = make_float4(0.f, 0.f, 0.f, 0.f);
       if (p >= 0) {
         float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -1320,7 +1326,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
     for (int idx = tid; idx < rows * QPR * G; idx += 256) {
       const int g = idx % G, rq = idx / G;
       const int ml = rq / QPR, e = (rq - ml * QPR) * 4, m = m0 + ml;
-      const int p = pos0 + m;
+      const int p = pos0 + m * step;
       float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
       float den = 0.f;
       if (p >= 0) {
@@ -1333,7 +1339,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
     __syncthreads();
     for (int idx = tid; idx < rows * QPR; idx += 256) {
       const int ml = idx / QPR, e = (idx - ml * QPR) * 4, m = m0 + ml;
-      const int p = pos0 + m;
+      const int p = pos0 + m * step;
       float4 res = make_float4(0.f, 0.f, 0.f, 0.f);
       if (p >= 0) {
         const int ng = (p / kAttnChunk + 1 + CB - 1) / CB;
@@ -1354,7 +1360,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
 template <int HD, int CT, bool FUSED>
 __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, const _Float16* __restrict__ Kc,
                                                   const _Float16* __restrict__ Vc, int cap, int d, int H, int M,
-                                                  PosRef pos, size_t kv_slot_stride, float scale, int nchunk_cap,
+                                                  PosRef pos, size_t kv_slot_stride, float scale, AttnMode am, int nchunk_cap,
                                                   int rows_per_pass, float* part_o, float* part_ml, int* counters,
                                                   float* __restrict__ out) {
   constexpr int KK = HD / 32;   // k-steps of the score MFMA
@@ -1375,8 +1381,13 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
   counters += blockIdx.z * H;
   Kc += blockIdx.z * kv_slot_stride;
   Vc += blockIdx.z * kv_slot_stride;
-  const int pos0 = pos_of(pos, row0);
-  const int kv_len = pos0 + M;
+  // causal: row i sees the keys 0 .. qpos0 + i; fixed key set (am.kv_fixed > 0): every row sees the keys 0 .. kv_fixed-1
+  const int qpos0 = pos_of(pos, row0);
+  const bool fixed = am.kv_fixed > 0;   // (then also for rows that sit nowhere: their result is unused)
+  const int pos0 = fixed ? am.kv_fixed - 1 : qpos0;   // last key row 0 sees
+  const int step = fixed ? 0 : 1;
+  const int kv_len = pos0 + (fixed ? 1 : M);
+  const float* brow = am.bias ? am.bias + (size_t)h * am.bias_ld + am.bias_zero : nullptr;
   const int kb = c * kAttnChunk + wave * 32;          // first key of this wave
   const bool have_keys = kb < kv_len;
 
@@ -1444,7 +1455,9 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int key = kb + t * 16 + g * 4 + v;
-          sc[t * 4 + v] = (qi < M && key <= pos0 + qi) ? sacc[v] : -INFINITY;
+          const bool seen = qi < M && key <= pos0 + qi * step;
+          const float bv = (brow && seen) ? brow[key - (qpos0 + qi)] : 0.f;   // bias by key position - query position
+          sc[t * 4 + v] = seen ? sacc[v] + bv : -INFINITY;
         }
       }
       float mx = sc[0];
@@ -1512,19 +1525,21 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
   if (!FUSED) return;
   if (!last_arrival(&counters[h], (int)gridDim.x, &s_last)) return;
   extern __shared__ float s_ml[];
-  attn_merge<HD>(part_o, part_ml, H, h, M, pos0, kv_len, nchunk_cap, (int)gridDim.x, rows_per_pass, out, d, s_ml);
+  attn_merge<HD>(part_o, part_ml, H, h, M, pos0, step, kv_len, nchunk_cap, (int)gridDim.x, rows_per_pass, out, d, s_ml);
   if (tid == 0) counters[h] = 0;
 }
 
 // the merge alone (long contexts: the attention work-groups then leave without waiting for their stores)
 template <int HD>
 __global__ __launch_bounds__(256) void k_attn_merge(const float* part_o, const float* part_ml, int d, int H, int M, PosRef pos,
-                                                    int nchunk_cap, int nch_lds, int rows_per_pass, float* __restrict__ out) {
+                                                    int kv_fixed, int nchunk_cap, int nch_lds, int rows_per_pass,
+                                                    float* __restrict__ out) {
   extern __shared__ float s_ml[];
   const int h = blockIdx.x, row0 = blockIdx.y * M;
-  const int pos0 = pos_of(pos, row0);
-  attn_merge<HD>(part_o + (size_t)row0 * H * nchunk_cap * HD, part_ml + (size_t)row0 * H * nchunk_cap * 2, H, h, M, pos0, pos0 + M,
-                 nchunk_cap, nch_lds, rows_per_pass, out + (size_t)row0 * d, d, s_ml);
+  const bool fixed = kv_fixed > 0;
+  const int pos0 = fixed ? kv_fixed - 1 : pos_of(pos, row0);
+  attn_merge<HD>(part_o + (size_t)row0 * H * nchunk_cap * HD, part_ml + (size_t)row0 * H * nchunk_cap * 2, H, h, M, pos0,
+                 fixed ? 0 : 1, pos0 + (fixed ? 1 : M), nchunk_cap, nch_lds, rows_per_pass, out + (size_t)row0 * d, d, s_ml);
 }
 
 // Attention of a prefill block (R consecutive rows at positions p0 .. p0+R-1 of one sequence) without partial
@@ -1672,10 +1687,10 @@ static void attn_dispatch(const float* q, const void* Kc, const void* Vc, int ca
 
 void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv_half, int cap, int d, int H, int M,
                       PosRef pos, int nslots, size_t kv_slot_stride, int nchunk_launch, int nchunk_cap, float* part_o,
-                      float* part_ml, int* counters, float* out, hipStream_t st) {
+                      float* part_ml, int* counters, float* out, hipStream_t st, const AttnMode& am) {
   const int hd = d / H;
   if (kv_half) {
-    const float scale = 1.0f / sqrtf((float)hd);
+    const float scale = am.scale > 0.f ? am.scale : 1.0f / sqrtf((float)hd);
     const _Float16* K = static_cast<const _Float16*>(Kc);
     const _Float16* V = static_cast<const _Float16*>(Vc);
     dim3 grid(nchunk_launch, H, nslots), block(256);
@@ -1692,12 +1707,12 @@ void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv
 #define STAIRS_ATTN16(hdv, ct)                                                                                              \
   if (fused)                                                                                                                \
     hipLaunchKernelGGL((k_attn_f16<hdv, ct, true>), grid, block, lds, st, q_rot, K, V, cap, d, H, M, pos, kv_slot_stride,   \
-                       scale, nchunk_cap, rpp, part_o, part_ml, counters, out);                                             \
+                       scale, am, nchunk_cap, rpp, part_o, part_ml, counters, out);                                         \
   else {                                                                                                                    \
     hipLaunchKernelGGL((k_attn_f16<hdv, ct, false>), grid, block, 0, st, q_rot, K, V, cap, d, H, M, pos, kv_slot_stride,    \
-                       scale, nchunk_cap, rpp, part_o, part_ml, counters, out);                                             \
-    hipLaunchKernelGGL((k_attn_merge<hdv>), dim3(H, nslots), dim3(256), lds, st, part_o, part_ml, d, H, M, pos, nchunk_cap, \
-                       nchunk_launch, rpp, out);                                                                            \
+                       scale, am, nchunk_cap, rpp, part_o, part_ml, counters, out);                                         \
+    hipLaunchKernelGGL((k_attn_merge<hdv>), dim3(H, nslots), dim3(256), lds, st, part_o, part_ml, d, H, M, pos,             \
+                       am.kv_fixed, nchunk_cap, nchunk_launch, rpp, out);                                                   \
   }
     if (hd == 128) {
       if (M <= 16) STAIRS_ATTN16(128, 1) else STAIRS_ATTN16(128, 2)

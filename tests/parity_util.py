@@ -22,11 +22,33 @@ def run_side_by_side(target, draft, prompt, G, k, oracle_dtype, logit_tol, check
     D = so.OracleModel(draft, oracle_dtype, keep=oracle_keep) if k > 0 else None
     cap = len(prompt) + G + k + 2
     orc = so.CachedStairs(T, D, prompt, cap)
-    res = dict(max_logit_err=0.0, max_draft_logit_err=None, n_accepted=[], token_mismatches=0, draft_mismatches=0)
     with pkg.Stairs(target, draft if k > 0 else None, k_max=k, max_seq=cap) as gpu:
         gpu.prefill(prompt)
+        return compare_generation(orc, gpu, len(prompt), G, k, logit_tol, check_draft, max_iters, log)
+
+
+def run_encdec_side_by_side(target, draft, src, G, k, logit_tol, check_draft=True, max_iters=None, log=None,
+                            max_src=None):
+    """The same comparison with an encoder-decoder pair: the oracle's models are bound to the source sequence, the
+    decoder sequence starts with the start token."""
+    import synth_inputs as si
+    from oracle import encdec_oracle as eo
+    T = eo.BoundDecoder(eo.EncDecOracleModel(target), src)
+    D = eo.BoundDecoder(eo.EncDecOracleModel(draft), src) if k > 0 else None
+    cap = 1 + G + k + 2
+    orc = so.CachedStairs(T, D, [si.DECODER_START], cap)
+    with pkg.StairsEncDec(target, draft if k > 0 else None, k_max=k, max_src=max_src or len(src), max_seq=cap,
+                          start_token=si.DECODER_START) as gpu:
+        gpu.encode(src)
+        return compare_generation(orc, gpu, 1, G, k, logit_tol, check_draft, max_iters, log)
+
+
+def compare_generation(orc, gpu, P, G, k, logit_tol, check_draft=True, max_iters=None, log=None):
+    """orc: the oracle's CachedStairs after its prompt; gpu: the library's context after prefill / encode."""
+    res = dict(max_logit_err=0.0, max_draft_logit_err=None, n_accepted=[], token_mismatches=0, draft_mismatches=0)
+    if True:
         iters = 0
-        while len(orc.seq) - len(prompt) < G and (max_iters is None or iters < max_iters):
+        while len(orc.seq) - P < G and (max_iters is None or iters < max_iters):
             L = len(orc.seq)
             d_gpu = [int(x) for x in gpu.propose(k)] if k > 0 else []
             if k > 0 and check_draft:
@@ -57,6 +79,6 @@ def run_side_by_side(target, draft, prompt, G, k, oracle_dtype, logit_tol, check
                 log(f"iter {iters} L={L} n={n} err={err:.3g}")
         seq = gpu.tokens()
         assert list(seq) == orc.seq
-    res["tokens"] = orc.seq[len(prompt):len(prompt) + G]
+    res["tokens"] = orc.seq[P:P + G]
     res["iterations"] = iters
     return res
