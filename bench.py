@@ -120,6 +120,7 @@ def main():
     ap.add_argument("--cpu-sample", default="64,96", help="prompt tokens, generated tokens of the CPU sample")
     ap.add_argument("--encdec", default="t5_large_shape,t5_3b_shape",
                     help="encoder-decoder workloads of the extra leg (comma separated, empty = none)")
+    ap.add_argument("--only-encdec", action="store_true", help="run the encoder-decoder leg alone and print its results")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -129,6 +130,9 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
+    if args.only_encdec:
+        print(json.dumps({"encoder_decoder": {name: encdec_leg(name) for name in args.encdec.split(",") if name}}), flush=True)
+        return
     import paper_2407_19947_amd as pkg
     import synth_inputs as si
 

@@ -20,6 +20,7 @@ constexpr int kSpwRows = 9;         // 9..16 rows: a split-K work-group takes tw
 // two work-groups per CU, the residual-writing ones (one work-group per CU) take most of the CU's LDS
 constexpr size_t kRowsPathMaxLds = 68 * 1024;
 constexpr size_t kRowsPathMaxLdsWide = 150 * 1024;
+constexpr size_t kRowsPathSmallMatrix = 16u << 20;   // residual-writing projections with fewer tiles than CUs: up to this many bytes
 
 // Where the rows of a forward sit.  One sequence (rps == 0): row r is at position *base + offset + r (base lives
 // in device memory so that the same launch sequence can be replayed without the host knowing the sequence length).

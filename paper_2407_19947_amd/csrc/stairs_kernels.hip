@@ -781,7 +781,8 @@ static size_t rows_path_lds(int role, int M, int N, int K) {
   if (M > 4) return 0;
   const size_t bytes = (size_t)K * M * 4 + (size_t)(gemm_slices(K, 1) + 1) * M * 16 * 4;
   if (role == kRoleWo || role == kRoleDown) {
-    if (N / 16 < 192) return 0;
+    // few tiles: only matrices so small that the launch is latency-bound anyway (no partial sums, no hand-off)
+    if (N / 16 < 192) return ((size_t)N * K * 2 <= kRowsPathSmallMatrix && bytes <= kRowsPathMaxLdsWide) ? bytes : 0;
     return bytes <= kRowsPathMaxLdsWide ? std::max(bytes, (size_t)81 * 1024) : 0;   // > half a CU's LDS: one per CU
   }
   return bytes <= kRowsPathMaxLds ? bytes : 0;
