@@ -1391,6 +1391,10 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
   const float* brow = am.bias ? am.bias + (size_t)h * am.bias_ld + am.bias_zero : nullptr;
   const int kb = c * kAttnChunk + wave * 32;          // first key of this wave
   const bool have_keys = kb < kv_len;
+  // all keys in the first chunk: its work-group writes the result itself (what the merge would give for one chunk:
+  // weight exp(0) = 1), the others have nothing to do; no partial results, no ticket
+  const bool single = FUSED && kv_len <= kAttnChunk;
+  if (single && c > 0) return;
 
   // the first query tile's rows are requested before the keys and values: they come from L2 and are
   // converted while the cache tiles are still on their way
@@ -1506,10 +1510,25 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
       if (m < M) {
         const float o0 = ((s_o[0][jj][e] + s_o[1][jj][e]) + s_o[2][jj][e]) + s_o[3][jj][e];
         const float o1 = ((s_o[0][jj][e + 1] + s_o[1][jj][e + 1]) + s_o[2][jj][e + 1]) + s_o[3][jj][e + 1];
-        st_dev2(&part_o[(((size_t)m * H + h) * nchunk_cap + c) * HD + e], o0, o1);
+        if (single) {
+          float2 res = make_float2(0.f, 0.f);
+          if (pos0 + m * step >= 0) {
+            const float m0 = s_m[0][jj], m1 = s_m[1][jj], m2 = s_m[2][jj], m3 = s_m[3][jj];
+            const float mcc = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+            float lc = 0.f;
+            if (m0 != -INFINITY) lc += expf(m0 - mcc) * s_l[0][jj];
+            if (m1 != -INFINITY) lc += expf(m1 - mcc) * s_l[1][jj];
+            if (m2 != -INFINITY) lc += expf(m2 - mcc) * s_l[2][jj];
+            if (m3 != -INFINITY) lc += expf(m3 - mcc) * s_l[3][jj];
+            res = make_float2(o0 / lc, o1 / lc);
+          }
+          *reinterpret_cast<float2*>(out + (size_t)m * d + h * HD + e) = res;
+        } else {
+          st_dev2(&part_o[(((size_t)m * H + h) * nchunk_cap + c) * HD + e], o0, o1);
+        }
       }
     }
-    if (tid < 16 && ct * 16 + tid < M) {
+    if (!single && tid < 16 && ct * 16 + tid < M) {
       const float m0 = s_m[0][tid], m1 = s_m[1][tid], m2 = s_m[2][tid], m3 = s_m[3][tid];
       const float mcc = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
       float lc = 0.f;
@@ -1523,7 +1542,7 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
   }
 
   // FUSED: the work-group that arrives last at the head's counter merges the chunks; otherwise a second kernel does
-  if (!FUSED) return;
+  if (!FUSED || single) return;
   if (!last_arrival(&counters[h], (int)gridDim.x, &s_last)) return;
   extern __shared__ float s_ml[];
   attn_merge<HD>(part_o, part_ml, H, h, M, pos0, step, kv_len, nchunk_cap, (int)gridDim.x, rows_per_pass, out, d, s_ml);
