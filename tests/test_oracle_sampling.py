@@ -1,0 +1,135 @@
+"""Pins of the sampling oracle (CPU only): the counter-based generator's statistics, Gumbel-max draws against the
+softmax, the keep/replace rule against the distribution it must reproduce and its closed-form keep probability, and the
+special cases that reduce to the greedy method."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import sampling_oracle as sa
+from oracle import stairs_oracle as so
+
+KEY = sa.key_from_seed(11)
+
+
+def _chi2_ok(counts, probs, n, sigmas=5.0):
+    """Pearson statistic within `sigmas` standard deviations of its mean (dof = cells - 1)."""
+    exp = probs * n
+    keep = exp > 5
+    stat = float(np.sum((counts[keep] - exp[keep]) ** 2 / exp[keep]))
+    dof = int(keep.sum()) - 1
+    return abs(stat - dof) < sigmas * np.sqrt(2 * dof), (stat, dof)
+
+
+def test_generator_is_deterministic_uniform_and_streams_differ():
+    a = sa.squares32(sa.counters(3, 1, 1000), KEY)
+    assert np.array_equal(a, sa.squares32(sa.counters(3, 1, 1000), KEY))
+    assert a.max() < 2 ** 32
+    for other in (sa.counters(3, 2, 1000), sa.counters(4, 1, 1000)):
+        assert np.mean(sa.squares32(other, KEY) == a) < 0.01
+    assert np.mean(sa.squares32(sa.counters(3, 1, 1000), sa.key_from_seed(12)) == a) < 0.01
+    u = sa.uniform(9, 0, 400000, KEY)
+    assert 0.0 < u.min() and u.max() < 1.0
+    assert abs(u.mean() - 0.5) < 5 * np.sqrt(1 / 12 / len(u))
+    assert abs(u.var() - 1 / 12) < 1e-3
+    ok, info = _chi2_ok(np.bincount((u * 64).astype(int), minlength=64), np.full(64, 1 / 64), len(u))
+    assert ok, info
+    # neighbouring counters are uncorrelated, and so are the same index of neighbouring positions
+    assert abs(np.corrcoef(u[:-1], u[1:])[0, 1]) < 0.01
+    v = np.array([sa.uniform(p, 0, 1, KEY)[0] for p in range(4000)])
+    assert abs(np.corrcoef(v[:-1], v[1:])[0, 1]) < 0.06 and abs(v.mean() - 0.5) < 0.03
+    # every bit of the output is set about half of the time
+    r = sa.squares32(sa.counters(1, 0, 100000), KEY)
+    for b in range(32):
+        assert abs(np.mean((r >> np.uint64(b)) & np.uint64(1)) - 0.5) < 0.01
+
+
+def test_gumbel_max_draws_follow_the_softmax():
+    rng = np.random.default_rng(0)
+    z = rng.standard_normal(12) * 1.5
+    p = np.exp(sa.log_softmax(z))
+    n = 60000
+    counts = np.bincount([sa.draw(z, pos, sa.STREAM_TARGET, KEY) for pos in range(n)], minlength=12)
+    ok, info = _chi2_ok(counts, p, n)
+    assert ok, info
+    assert np.isclose(np.exp(sa.log_softmax(z)).sum(), 1.0)
+
+
+def test_residual_scores_are_the_positive_part():
+    logp = np.log(np.array([0.5, 0.3, 0.2, 0.0 + 1e-300]))
+    logq = np.log(np.array([0.2, 0.3, 0.4, 0.1]))
+    r = sa.residual_scores(logp, logq)
+    assert np.isclose(np.exp(r[0]), 0.3) and np.all(np.isinf(r[1:])) and np.all(r[1:] < 0)
+
+
+@pytest.mark.parametrize("k", [1, 3])
+def test_emitted_tokens_follow_the_main_model(k):
+    """Fixed distributions p_i (main model) and q_j (assistant) over 6 tokens, independent of the prefix: whatever the
+    assistant proposes, the first emitted token must be distributed as p_0, and the first proposal must be kept with
+    probability sum_v min(p_0(v), q_1(v))."""
+    rng = np.random.default_rng(k)
+    V, T = 6, 0.7
+    tl = rng.standard_normal((k + 1, V)) * 1.2
+    dl = rng.standard_normal((k, V)) * 1.2
+    p0 = np.exp(sa.log_softmax(tl[0] / T))
+    q1 = np.exp(sa.log_softmax(dl[0] / T))
+    n_iter = 40000
+    first = np.zeros(V, int)
+    kept_first = 0
+    total_kept = 0
+    for it in range(n_iter):
+        L = 10 + it * (k + 2)                      # fresh positions = fresh random numbers
+        d = [sa.draw(dl[j] / T, L + j, sa.STREAM_DRAFT, KEY) for j in range(k)]
+        n, emitted, us, ratios = sa.validate_sampled(L, d, tl, dl, T, KEY)
+        assert len(emitted) == n + 1 and emitted[:n] == d[:n] and len(us) == min(n + 1, k)
+        first[emitted[0]] += 1
+        kept_first += n >= 1
+        total_kept += n
+    ok, info = _chi2_ok(first, p0, n_iter)
+    assert ok, info
+    want = float(np.minimum(p0, q1).sum())
+    assert abs(kept_first / n_iter - want) < 5 * np.sqrt(want * (1 - want) / n_iter)
+    if k == 3:                                     # expected number kept: sum over j of prod_{i<=j} a_i
+        a = [float(np.minimum(np.exp(sa.log_softmax(tl[j] / T)), np.exp(sa.log_softmax(dl[j] / T))).sum()) for j in range(k)]
+        want_n = a[0] + a[0] * a[1] + a[0] * a[1] * a[2]
+        assert abs(total_kept / n_iter - want_n) < 0.03
+
+
+def _models(G=20):
+    w = si.scaled_workload("cfg1_tiny_fp32", G=G)
+    t, d = si.make_pair(w)
+    return so.OracleModel(t, np.float64), so.OracleModel(d, np.float64), si.make_prompt(w)
+
+
+def test_identical_assistant_keeps_everything():
+    T, D, prompt = _models()
+    toks, its = sa.stairs_sampled(T, T, prompt, 20, 4, 0.3, 5)
+    assert all(it.n_accepted == 4 for it in its)
+    assert all(abs(r - 1.0) < 1e-9 for it in its for r in it.ratios)
+
+
+def test_cold_sampling_is_the_greedy_method():
+    T, D, prompt = _models()
+    want = so.greedy_bruteforce(T, prompt, 20)
+    for k in (0, 2, 5):
+        toks, its = sa.stairs_sampled(T, D, prompt, 20, k, 1e-5, 5)
+        assert toks == want
+    greedy = so.stairs_cached(T, D, prompt, 20, 5)
+    assert [it.n_accepted for it in its] == [it.n_accepted for it in greedy.iterations]
+
+
+def test_draft_length_zero_is_plain_sampling_and_seeds_matter():
+    T, D, prompt = _models()
+    temp = 0.05
+    toks, its = sa.stairs_sampled(T, None, prompt, 12, 0, temp, 5)
+    seq = list(prompt)
+    key = sa.key_from_seed(5)
+    for _ in range(12):
+        z = so.forward_full(T, seq)[-1]
+        seq.append(sa.draw(z / temp, len(seq), sa.STREAM_TARGET, key))
+    assert toks == seq[len(prompt):]
+    other, _ = sa.stairs_sampled(T, None, prompt, 12, 0, temp, 6)
+    assert other != toks
+    # with an assistant the iterations mix kept and replaced tokens at this temperature
+    toks4, its4 = sa.stairs_sampled(T, D, prompt, 40, 4, temp, 5)
+    acc = [it.n_accepted for it in its4]
+    assert 0 < sum(acc) < 4 * len(acc), acc
