@@ -248,6 +248,23 @@ def main():
                                            "mean_tokens_per_iteration": G / max(1, st_a.iterations)}
         log(f"[bench] adaptive draft length: {G / dt_a:.0f} tok/s, {st_a.iterations} iterations")
 
+    # ---- sampling variant: assistant and main model sample at a temperature, keep / replace validation --------
+    if not args.no_sweep:
+        sampled = {}
+        for temp in (0.02, 0.1, 1.0):
+            eng.prefill(prompt)
+            eng.decode_sampled(G, k, temp, 1)                      # graph capture
+            eng.prefill(prompt)
+            toks_s, st_s = eng.decode_sampled(G, k, temp, 1)
+            sampled[f"T{temp}"] = {"temperature": temp, "k": k, "tokens_per_s": G / (st_s.ms_decode * 1e-3),
+                                   "iterations": st_s.iterations, "mean_tokens_per_iteration": G / st_s.iterations,
+                                   "ms_verify_per_iteration": st_s.ms_verify / st_s.iterations,
+                                   "ms_draft_per_iteration": st_s.ms_draft / st_s.iterations,
+                                   "distinct_tokens": int(len(set(toks_s.tolist())))}
+            log(f"[bench] sampled T={temp} k={k}: {sampled[f'T{temp}']['tokens_per_s']:.0f} tok/s, "
+                f"{st_s.iterations} iterations, verify {sampled[f'T{temp}']['ms_verify_per_iteration']:.2f} ms/iteration")
+        extras["sampled"] = sampled
+
     # ---- several sequences per forward (not the headline: the workload is one sequence) -------------------
     # B prompts of the workload's length share every weight pass: aggregate tokens/s of stairs_generate_batch,
     # decode phase, prompt 0 is the workload's prompt and must reproduce its tokens bit for bit

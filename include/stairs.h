@@ -168,6 +168,32 @@ int stairs_reserve_batch(stairs_ctx *ctx, int32_t max_batch);
 int stairs_generate_batch(stairs_ctx *ctx, const int32_t *const *prompts, const int32_t *P, int32_t B, int32_t G,
                           int32_t k, int32_t *tokens_out, stairs_stats *stats);
 
+/* ---- sampling variant (the paper's future work, Sec. 5: sampling instead of greedy choice for the assistant and
+ * the main model, with a temperature; validation by the rejection scheme its related work describes, Sec. 2.2) ----
+ * The assistant DRAWS its k tokens from softmax(logits / temperature); the main model scores the k + 1 stair rows as
+ * in stairs_verify; the walk keeps d_i while u_i < p_{i-1}(d_i) / q_i(d_i) (p, q: main model's and assistant's
+ * probabilities at the temperature, u_i uniform); at the first token not kept one token is drawn from the normalised
+ * positive part of p - q and the walk stops; if all are kept one more token is drawn from p_k.  Each iteration emits
+ * n + 1 tokens distributed as the main model's own sampling.  Random numbers come from a counter-based generator
+ * (Widynski's "squares", key derived from `seed`) indexed by (position of the token being decided, purpose,
+ * vocabulary index), so a run is reproducible and independent of launch shapes; draws are Gumbel-max argmaxes.
+ * One sequence per context (not after stairs_reserve_batch); works on decoder-only and encoder-decoder contexts.
+ * temperature > 0.  Errors as for the greedy calls. */
+int stairs_decode_sampled(stairs_ctx *ctx, int32_t G, int32_t k, float temperature, uint64_t seed,
+                          int32_t *tokens_out, stairs_stats *stats);
+/* stairs_prefill followed by stairs_decode_sampled. */
+int stairs_generate_sampled(stairs_ctx *ctx, const int32_t *prompt, int32_t P, int32_t G, int32_t k,
+                            float temperature, uint64_t seed, int32_t *tokens_out, stairs_stats *stats);
+/* One iteration in two steps (as draft_propose / stairs_verify).  draft_out: k tokens (host, optional);
+ * draft_logits_out: the k logits rows they were drawn from, [k][vocab] float (host, optional). */
+int draft_propose_sampled(stairs_ctx *ctx, int32_t k, float temperature, uint64_t seed, int32_t *draft_out,
+                          float *draft_logits_out);
+/* Needs the pending proposal of draft_propose_sampled with the same k (k = 0: none), temperature and seed.
+ * emitted_out: the n + 1 tokens appended to the sequence (room for k + 1); logits_out: [k+1][vocab] main-model
+ * logits (host, optional). */
+int stairs_verify_sampled(stairs_ctx *ctx, int32_t k, float temperature, uint64_t seed, int32_t *emitted_out,
+                          int32_t *n_accepted_out, float *logits_out);
+
 /* ---- encoder-decoder models (the model family of the paper's experiments, Sec. 2.3 / 4.2) ------------------
  * The source text goes through the encoder once; the stair batch of Sec. 3.3 is made of prefixes of the DECODER
  * sequence, and every stair row reads the same encoder output (its per-layer cross-attention keys and values are

@@ -124,7 +124,10 @@ def validate_sampled(L: int, d: Sequence[int], target_logits: np.ndarray, draft_
         us.append(u)
         ratios.append(ratio)
         if not u < ratio:
-            t = draw(residual_scores(logp, logq), pos, STREAM_TARGET, key)
+            rs = residual_scores(logp, logq)
+            if not np.any(np.isfinite(rs)):     # p == q to the last bit yet not kept (rounding only): p itself
+                rs = logp
+            t = draw(rs, pos, STREAM_TARGET, key)
             return i - 1, [int(x) for x in d[:i - 1]] + [t], us, ratios
     t = draw(target_logits[k] / temperature, L + k, STREAM_TARGET, key)
     return k, [int(x) for x in d] + [t], us, ratios

@@ -20,6 +20,7 @@ EXPORTED_SYMBOLS = [
     "draft_propose", "stairs_verify", "stairs_verify_tokens", "stairs_generate", "stairs_decode", "stairs_decode_adaptive", "stairs_reserve_batch", "stairs_generate_batch",
     "stairs_get_tokens", "stairs_gemm_host", "stairs_time_kernel", "stairs_copy_probe",
     "stairs_encdec_init", "stairs_encode", "stairs_encdec_generate",
+    "stairs_decode_sampled", "stairs_generate_sampled", "draft_propose_sampled", "stairs_verify_sampled",
 ]
 
 
@@ -122,6 +123,10 @@ def lib() -> C.CDLL:
     L.stairs_encdec_init.argtypes = [C.POINTER(vp), C.POINTER(_EncDecCfg), C.POINTER(_EncDecWeights),
                                      C.POINTER(_EncDecCfg), C.POINTER(_EncDecWeights), i32, i32, vp]
     L.stairs_encode.argtypes = [vp, i32p, i32]
+    L.stairs_decode_sampled.argtypes = [vp, i32, i32, C.c_float, C.c_uint64, i32p, C.POINTER(StairsStats)]
+    L.stairs_generate_sampled.argtypes = [vp, i32p, i32, i32, i32, C.c_float, C.c_uint64, i32p, C.POINTER(StairsStats)]
+    L.draft_propose_sampled.argtypes = [vp, i32, C.c_float, C.c_uint64, i32p, f32p]
+    L.stairs_verify_sampled.argtypes = [vp, i32, C.c_float, C.c_uint64, i32p, i32p, f32p]
     L.stairs_encdec_generate.argtypes = [vp, i32p, i32, i32, i32, i32p, C.POINTER(StairsStats)]
     for name in EXPORTED_SYMBOLS:
         if name not in ("stairs_strerror", "stairs_last_error", "stairs_free"):
@@ -374,6 +379,42 @@ def stairs_encdec_generate(ctx, src: Sequence[int], G: int, k: int):
     return out[:G], st
 
 
+def stairs_decode_sampled(ctx, G: int, k: int, temperature: float, seed: int):
+    out = np.zeros(max(G, 1), np.int32)
+    st = StairsStats()
+    _check(lib().stairs_decode_sampled(ctx, G, k, temperature, seed, _ptr(out, C.c_int32), C.byref(st)),
+           "stairs_decode_sampled", ctx)
+    return out[:G], st
+
+
+def stairs_generate_sampled(ctx, prompt: Sequence[int], G: int, k: int, temperature: float, seed: int):
+    p = _i32(prompt)
+    out = np.zeros(max(G, 1), np.int32)
+    st = StairsStats()
+    _check(lib().stairs_generate_sampled(ctx, _ptr(p, C.c_int32), len(p), G, k, temperature, seed, _ptr(out, C.c_int32),
+                                         C.byref(st)), "stairs_generate_sampled", ctx)
+    return out[:G], st
+
+
+def draft_propose_sampled(ctx, k: int, temperature: float, seed: int, vocab: int = 0):
+    """-> (k tokens, their logits rows [k, vocab] or None when vocab == 0)."""
+    out = np.zeros(max(k, 1), np.int32)
+    lg = np.empty((k, vocab), np.float32) if vocab else None
+    _check(lib().draft_propose_sampled(ctx, k, temperature, seed, _ptr(out, C.c_int32),
+                                       _ptr(lg, C.c_float) if vocab else None), "draft_propose_sampled", ctx)
+    return out[:k], lg
+
+
+def stairs_verify_sampled(ctx, k: int, temperature: float, seed: int, vocab: int = 0):
+    """-> (emitted tokens (n + 1), n, main-model logits [k+1, vocab] or None when vocab == 0)."""
+    out = np.zeros(k + 1, np.int32)
+    n = C.c_int32(0)
+    lg = np.empty((k + 1, vocab), np.float32) if vocab else None
+    _check(lib().stairs_verify_sampled(ctx, k, temperature, seed, _ptr(out, C.c_int32), C.byref(n),
+                                       _ptr(lg, C.c_float) if vocab else None), "stairs_verify_sampled", ctx)
+    return out[:n.value + 1], n.value, lg
+
+
 class Stairs:
     """Convenience wrapper owning one context."""
 
@@ -427,6 +468,18 @@ class Stairs:
 
     def tokens(self):
         return stairs_get_tokens(self.ctx)
+
+    def decode_sampled(self, G, k, temperature, seed):
+        return stairs_decode_sampled(self.ctx, G, k, temperature, seed)
+
+    def generate_sampled(self, prompt, G, k, temperature, seed):
+        return stairs_generate_sampled(self.ctx, prompt, G, k, temperature, seed)
+
+    def propose_sampled(self, k, temperature, seed, logits=True):
+        return draft_propose_sampled(self.ctx, k, temperature, seed, self.vocab if logits else 0)
+
+    def verify_sampled(self, k, temperature, seed, logits=True):
+        return stairs_verify_sampled(self.ctx, k, temperature, seed, self.vocab if logits else 0)
 
     def time_kernel(self, which, M, ctx_len=0, reps=64):
         return stairs_time_kernel(self.ctx, which, M, ctx_len, reps)

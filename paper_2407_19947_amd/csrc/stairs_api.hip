@@ -97,6 +97,10 @@ struct stairs_ctx {
   int start_token = 0, S = 0;   // S = length of the encoded source
   int* src_tok = nullptr;
   float *enc_x = nullptr, *enc_ssq = nullptr, *enc_q = nullptr;
+  // sampling variant: parameters on the device, the assistant's logits rows of the pending proposal, log-sum-exps
+  SampleParams* samp = nullptr;
+  float *dlogits = nullptr, *lse = nullptr;
+  bool pending_sampled = false;
   int nchunk_cap = 0;
   int* tokens = nullptr;       // device copy of the sequence(s): [n_slots][tok_stride], capacity tok_cap each
   int tok_cap = 0, tok_stride = 0;
@@ -111,7 +115,7 @@ struct stairs_ctx {
   bool prefilled = false;
   int pending_k = -1;          // draft length of the outstanding proposal, -1 = none
   hipEvent_t ev[8] = {};       // 0,1: general; 5,6,7: iteration start / after the proposal / after validation
-  struct IterGraph { int half, k, nch, B; hipGraphExec_t exec; };   // B = 0: the single-sequence path
+  struct IterGraph { int half, k, nch, B; hipGraphExec_t exec; };   // B = 0: the single-sequence path, -1: its sampled variant
   std::vector<IterGraph> graphs;   // captured iterations, see iteration_graph()
   std::vector<hipEvent_t> probe_ev;   // stairs_time_kernel(8): event pairs around one projection inside a forward
   int probe_role = -1;               // role being timed in situ, -1 = none, kProbeEmptyPair = calibration
@@ -441,12 +445,13 @@ size_t max_partial_floats(const stairs_model_cfg* m) {
 //              M = every row -> c->logits rows 0..M-1.
 // Several sequences: pos.rps > 0 rows per slot, M = rps * (number of slots), slots 0..M/rps-1; otherwise the
 // rows belong to sequence slot `slot`.
-int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows);
+int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows, float* logits_dst);
 
-int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows, int slot = 0) {
+// logits_dst: where the logits rows go (nullptr: c->logits)
+int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows, int slot = 0, float* logits_dst = nullptr) {
   if (m->encdec) {
     if (slot != 0 || pos.rps) return fail(c, STAIRS_EINVAL, "forward: encoder-decoder models take one sequence");
-    return forward_ed(c, m, pos, nchunk, M, logits_rows);
+    return forward_ed(c, m, pos, nchunk, M, logits_rows, logits_dst);
   }
   const stairs_model_cfg& g = m->cfg;
   const int d = g.d_model, f = g.d_ffn, H = g.n_heads, V = g.vocab;
@@ -522,7 +527,7 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     const int r0 = M - logits_rows;
     GemmEpi e{};
     e.counters = c->counters;
-    e.out = c->logits;
+    e.out = logits_dst ? logits_dst : c->logits;
     e.hd = m->hd;
     launch_gemm(kRoleHead, b, m->lm_head, V, d, c->x + (size_t)r0 * d, d, logits_rows,
                 RowNorm{m->final_norm, c->ssq + r0 * sn, sn, g.rms_eps}, c->partial, e, st);
@@ -562,7 +567,7 @@ void launch_ed_ffn(stairs_ctx* c, const Model* m, const EdLayer& ly, float* x, f
 // Decoder forward of an encoder-decoder model: M rows of the decoder sequence at pos.. (see forward()).  Per layer:
 // self-attention over the decoder's cache with the one-sided position bias, cross-attention over the keys and
 // values stairs_encode left for this layer (every row sees all c->S source positions), feed-forward.
-int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows) {
+int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows, float* logits_dst) {
   const stairs_model_cfg& g = m->cfg;
   const int d = g.d_model, a = m->da, H = g.n_heads, V = g.vocab;
   const int sn = ssq_groups(d, 1);
@@ -626,7 +631,7 @@ int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logit
     const int r0 = M - logits_rows;
     GemmEpi e{};
     e.counters = c->counters;
-    e.out = c->logits;
+    e.out = logits_dst ? logits_dst : c->logits;
     e.hd = m->hd;
     launch_gemm(kRoleHead, 1, m->lm_head, V, d, c->x + (size_t)r0 * d, d, logits_rows,
                 RowNorm{m->final_norm, c->ssq + r0 * sn, sn, g.rms_eps}, c->partial, e, st);
@@ -810,6 +815,54 @@ int enqueue_verify(stairs_ctx* c, int k, int nch) {
   return STAIRS_OK;
 }
 
+// The two halves of a SAMPLED iteration: the assistant draws its k tokens one by one (its logits rows stay in
+// c->dlogits for the validation), then the stair batch, the rows' log-sum-exps and the keep / replace walk.
+int enqueue_propose_sampled(stairs_ctx* c, int k, int nch) {
+  Model* m = &c->D;
+  const int V = m->cfg.vocab;
+  int rc = forward(c, m, rel_pos(c, -2), nch, 2, 1, 0, c->dlogits);
+  if (rc) return rc;
+  launch_sample(c->dlogits, V, c->samp, 0, c->tokens, rel_pos(c, 0), c->st);
+  for (int j = 1; j < k; ++j) {
+    rc = forward(c, m, rel_pos(c, j - 1), nch, 1, 1, 0, c->dlogits + (size_t)j * V);
+    if (rc) return rc;
+    launch_sample(c->dlogits + (size_t)j * V, V, c->samp, 0, c->tokens, rel_pos(c, j), c->st);
+  }
+  HIPCHK(c, hipGetLastError());
+  return STAIRS_OK;
+}
+
+int enqueue_verify_sampled(stairs_ctx* c, int k, int nch) {
+  Model* m = &c->T;
+  const int M = k + 1, V = m->cfg.vocab;
+  int rc = forward(c, m, rel_pos(c, -1), nch, M, M);
+  if (rc) return rc;
+  launch_row_lse(c->logits, M, c->dlogits, k, V, V, c->samp, c->lse, c->st);
+  launch_accept_sampled(c->tokens, c->logits, c->dlogits, V, V, k, c->lse, c->samp, c->state, c->tgt_tok, c->st);
+  HIPCHK(c, hipGetLastError());
+  return STAIRS_OK;
+}
+
+// temperature and seed of the sampled calls onto the device (buffers on first use)
+int set_sampling(stairs_ctx* c, float temperature, uint64_t seed) {
+  if (!(temperature > 0.f) || !(temperature < 1e6f)) return fail(c, STAIRS_EINVAL, "temperature must be positive");
+  if (c->n_slots != 1) return fail(c, STAIRS_EINVAL, "sampling takes a context without reserved batch slots");
+  int rc;
+  if (!c->samp) {
+    const size_t V = c->T.cfg.vocab;
+    if ((rc = dev_alloc(c, &c->samp, 1)) || (rc = dev_alloc(c, &c->dlogits, (size_t)kMaxRows * V)) ||
+        (rc = dev_alloc(c, &c->lse, (size_t)2 * kMaxRows)))
+      return rc;
+  }
+  uint64_t z = seed + 0x9E3779B97F4A7C15ull;       // one splitmix64 step, forced odd
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  const SampleParams sp{1.0f / temperature, (z ^ (z >> 31)) | 1ull};
+  HIPCHK(c, hipMemcpyAsync(c->samp, &sp, sizeof(sp), hipMemcpyHostToDevice, c->st));
+  HIPCHK(c, hipStreamSynchronize(c->st));           // sp is on the stack
+  return STAIRS_OK;
+}
+
 // The same two halves for B sequences at once: every forward holds the rows of all slots (2, then 1, then k+1 per
 // slot), positions, token arrays and caches are looked up per slot on the device.
 int enqueue_propose_batch(stairs_ctx* c, int B, int k, int nch) {
@@ -838,7 +891,7 @@ int enqueue_verify_batch(stairs_ctx* c, int B, int k, int nch) {
   return STAIRS_OK;
 }
 
-int do_propose(stairs_ctx* c, int k) {
+int do_propose(stairs_ctx* c, int k, bool sampled = false) {
   Model* m = &c->D;
   const int L = c->L;
   // the draft's cache must hold positions 0..L-3; the 2-row first step covers L-2 and L-1
@@ -846,10 +899,11 @@ int do_propose(stairs_ctx* c, int k) {
     int rc = ingest(c, m, m->valid, L - 2);
     if (rc) return rc;
   }
-  int rc = enqueue_propose(c, k, chunks_for(L + k - 1));
+  int rc = sampled ? enqueue_propose_sampled(c, k, chunks_for(L + k - 1)) : enqueue_propose(c, k, chunks_for(L + k - 1));
   if (rc) return rc;
   m->valid = L + k - 1;      // tokens S, d_1..d_{k-1} are in the cache
   c->pending_k = k;
+  c->pending_sampled = sampled;
   return STAIRS_OK;
 }
 
@@ -869,8 +923,8 @@ int finish_verify(stairs_ctx* c, int k, int* n_out) {
   return STAIRS_OK;
 }
 
-int do_verify(stairs_ctx* c, int k, int* n_out) {
-  int rc = enqueue_verify(c, k, chunks_for(c->L + k));
+int do_verify(stairs_ctx* c, int k, int* n_out, bool sampled = false) {
+  int rc = sampled ? enqueue_verify_sampled(c, k, chunks_for(c->L + k)) : enqueue_verify(c, k, chunks_for(c->L + k));
   if (rc) return rc;
   return finish_verify(c, k, n_out);
 }
@@ -886,8 +940,9 @@ int iteration_graph(stairs_ctx* c, int half, int k, int nch, hipGraphExec_t* out
     }
   hipGraph_t graph = nullptr;
   HIPCHK(c, hipStreamBeginCapture(c->st, hipStreamCaptureModeThreadLocal));
-  const int rc = B ? (half == 0 ? enqueue_propose_batch(c, B, k, nch) : enqueue_verify_batch(c, B, k, nch))
-                   : (half == 0 ? enqueue_propose(c, k, nch) : enqueue_verify(c, k, nch));
+  const int rc = B > 0 ? (half == 0 ? enqueue_propose_batch(c, B, k, nch) : enqueue_verify_batch(c, B, k, nch))
+                 : B < 0 ? (half == 0 ? enqueue_propose_sampled(c, k, nch) : enqueue_verify_sampled(c, k, nch))
+                         : (half == 0 ? enqueue_propose(c, k, nch) : enqueue_verify(c, k, nch));
   hipError_t e = hipStreamEndCapture(c->st, &graph);
   if (rc) {
     if (graph) (void)hipGraphDestroy(graph);
@@ -1244,7 +1299,8 @@ int stairs_verify_tokens(stairs_ctx* c, const int32_t* draft, int32_t k, int32_t
 
 // The loop of stairs_decode.  adaptive: k is the first draft length and the next one follows from what was accepted
 // (everything: one more, up to k_max; otherwise one more than the accepted count).
-static int decode_loop(stairs_ctx* c, int32_t G, int32_t k, bool adaptive, int32_t* tokens_out, stairs_stats* stats) {
+static int decode_loop(stairs_ctx* c, int32_t G, int32_t k, bool adaptive, int32_t* tokens_out, stairs_stats* stats,
+                       bool sampled = false) {
   if (!c) return STAIRS_EINVAL;
   if (!c->prefilled) return fail(c, STAIRS_ESTATE, "stairs_decode before stairs_prefill");
   if (c->pending_k >= 0) return fail(c, STAIRS_ESTATE, "a proposal is pending");
@@ -1265,15 +1321,18 @@ static int decode_loop(stairs_ctx* c, int32_t G, int32_t k, bool adaptive, int32
     if (c->use_graphs) {
       const int nch = std::min((chunks_for(c->L + k) + 3) / 4 * 4, c->nchunk_cap);   // never past the partial buffers
       hipGraphExec_t gp = nullptr, gv = nullptr;
-      if (k > 0 && (rc = iteration_graph(c, 0, k, nch, &gp))) return rc;
-      if ((rc = iteration_graph(c, 1, k, nch, &gv))) return rc;
+      const int gB = sampled ? -1 : 0;
+      if (k > 0 && (rc = iteration_graph(c, 0, k, nch, &gp, gB))) return rc;
+      if ((rc = iteration_graph(c, 1, k, nch, &gv, gB))) return rc;
       if (k > 0) HIPCHK(c, hipGraphLaunch(gp, c->st));
       HIPCHK(c, hipEventRecord(c->ev[6], c->st));
       HIPCHK(c, hipGraphLaunch(gv, c->st));
     } else {
-      if (k > 0 && (rc = enqueue_propose(c, k, chunks_for(c->L + k - 1)))) return rc;
+      if (k > 0 && (rc = sampled ? enqueue_propose_sampled(c, k, chunks_for(c->L + k - 1))
+                                 : enqueue_propose(c, k, chunks_for(c->L + k - 1))))
+        return rc;
       HIPCHK(c, hipEventRecord(c->ev[6], c->st));
-      if ((rc = enqueue_verify(c, k, chunks_for(c->L + k)))) return rc;
+      if ((rc = sampled ? enqueue_verify_sampled(c, k, chunks_for(c->L + k)) : enqueue_verify(c, k, chunks_for(c->L + k)))) return rc;
     }
     HIPCHK(c, hipEventRecord(c->ev[7], c->st));
     if (k > 0) c->D.valid = c->L + k - 1;
@@ -1312,6 +1371,63 @@ int stairs_decode(stairs_ctx* c, int32_t G, int32_t k, int32_t* tokens_out, stai
 
 int stairs_decode_adaptive(stairs_ctx* c, int32_t G, int32_t k_first, int32_t* tokens_out, stairs_stats* stats) {
   return decode_loop(c, G, k_first, true, tokens_out, stats);
+}
+
+int stairs_decode_sampled(stairs_ctx* c, int32_t G, int32_t k, float temperature, uint64_t seed, int32_t* tokens_out,
+                          stairs_stats* stats) {
+  if (!c) return STAIRS_EINVAL;
+  int rc = set_sampling(c, temperature, seed);
+  if (rc) return rc;
+  return decode_loop(c, G, k, false, tokens_out, stats, true);
+}
+
+int draft_propose_sampled(stairs_ctx* c, int32_t k, float temperature, uint64_t seed, int32_t* draft_out, float* draft_logits_out) {
+  if (!c) return STAIRS_EINVAL;
+  if (!c->prefilled) return fail(c, STAIRS_ESTATE, "draft_propose_sampled before a sequence was started");
+  if (!c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
+  if (c->pending_k >= 0) return fail(c, STAIRS_ESTATE, "a proposal is already pending");
+  if (k < 1 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [1, k_max]");
+  if (!capacity_ok(c, c->L + k + 1)) return fail(c, STAIRS_ECAPACITY, "L + k + 1 exceeds max_seq");
+  int rc = set_sampling(c, temperature, seed);
+  if (rc) return rc;
+  if ((rc = do_propose(c, k, true))) return rc;
+  if (draft_logits_out &&
+      (rc = copy_out(c, draft_logits_out, c->dlogits, (size_t)k * c->T.cfg.vocab * sizeof(float))))
+    return rc;
+  if (draft_out) return copy_out(c, draft_out, c->tokens + c->L, (size_t)k * sizeof(int));
+  HIPCHK(c, hipStreamSynchronize(c->st));
+  return STAIRS_OK;
+}
+
+int stairs_verify_sampled(stairs_ctx* c, int32_t k, float temperature, uint64_t seed, int32_t* emitted_out,
+                          int32_t* n_accepted_out, float* logits_out) {
+  if (!c) return STAIRS_EINVAL;
+  if (!c->prefilled) return fail(c, STAIRS_ESTATE, "stairs_verify_sampled before a sequence was started");
+  if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
+  if (k > 0 && (c->pending_k != k || !c->pending_sampled)) return fail(c, STAIRS_ESTATE, "no pending sampled proposal of this k");
+  if (k == 0 && c->pending_k > 0) return fail(c, STAIRS_ESTATE, "a proposal of another k is pending");
+  if (!capacity_ok(c, c->L + k + 1)) return fail(c, STAIRS_ECAPACITY, "L + k + 1 exceeds max_seq");
+  int rc = set_sampling(c, temperature, seed);
+  if (rc) return rc;
+  int n = 0;
+  if ((rc = do_verify(c, k, &n, true))) return rc;
+  if (emitted_out) memcpy(emitted_out, c->h_pinned + 2, (size_t)(n + 1) * sizeof(int));
+  if (n_accepted_out) *n_accepted_out = n;
+  if (logits_out) return copy_out(c, logits_out, c->logits, (size_t)(k + 1) * c->T.cfg.vocab * sizeof(float));
+  return STAIRS_OK;
+}
+
+int stairs_generate_sampled(stairs_ctx* c, const int32_t* prompt, int32_t P, int32_t G, int32_t k, float temperature,
+                            uint64_t seed, int32_t* tokens_out, stairs_stats* stats) {
+  if (!c) return STAIRS_EINVAL;
+  if (G < 0 || (G > 0 && !tokens_out)) return fail(c, STAIRS_EINVAL, "G < 0 or tokens_out is NULL");
+  if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
+  if (k > 0 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
+  if (!prompt || P < 1) return fail(c, STAIRS_EINVAL, "prompt is NULL or empty");
+  if (!capacity_ok(c, P + G + k + 1)) return fail(c, STAIRS_ECAPACITY, "P + G + k + 1 exceeds max_seq");
+  int rc = stairs_prefill(c, prompt, P);
+  if (rc) return rc;
+  return stairs_decode_sampled(c, G, k, temperature, seed, tokens_out, stats);
 }
 
 int stairs_generate(stairs_ctx* c, const int32_t* prompt, int32_t P, int32_t G, int32_t k, int32_t* tokens_out,

@@ -1826,6 +1826,171 @@ void launch_accept(int* tokens, const int* tgt, int k, int* state, int nslots, i
 }
 
 // ---------------------------------------------------------------------------------------
+// sampling variant: counter-based random numbers, Gumbel-max draws, keep / replace walk
+// ---------------------------------------------------------------------------------------
+// "squares" counter-based generator (Widynski 2020): four rounds of squaring, 32-bit output
+__device__ __forceinline__ uint32_t squares32(uint64_t ctr, uint64_t key) {
+  uint64_t x = ctr * key;
+  const uint64_t y = x, z = y + key;
+  x = x * x + y; x = (x >> 32) | (x << 32);
+  x = x * x + z; x = (x >> 32) | (x << 32);
+  x = x * x + y; x = (x >> 32) | (x << 32);
+  return (uint32_t)((x * x + z) >> 32);
+}
+// the draw of (position of the token being decided, stream, vocabulary index) as a uniform in (0, 1)
+__device__ __forceinline__ double sample_uniform(int pos, int stream, int v, uint64_t key) {
+  const uint64_t ctr = ((uint64_t)pos << 34) | ((uint64_t)stream << 32) | (uint32_t)v;
+  return ((double)squares32(ctr, key) + 0.5) * (1.0 / 4294967296.0);
+}
+__device__ __forceinline__ double sample_gumbel(int pos, int stream, int v, uint64_t key) {
+  return -log(-log(sample_uniform(pos, stream, v, key)));
+}
+
+// (max, index) over a 1024-thread block, ties -> lowest index; result valid in thread 0
+__device__ __forceinline__ void block_argmax_1024(double& best, int& bi, double* sv, int* si) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const double ov = __shfl_xor(best, off);
+    const int oi = __shfl_xor(bi, off);
+    if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+  }
+  if ((tid & 63) == 0) { sv[tid >> 6] = best; si[tid >> 6] = bi; }
+  __syncthreads();
+  if (tid == 0)
+    for (int w = 1; w < 16; ++w)
+      if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
+}
+
+// lse[r] = log sum_v exp(rows[r][v] * inv_temp): one 1024-thread block per row; rows 0..n_a-1 from a, the rest from b
+__global__ __launch_bounds__(1024) void k_row_lse(const float* __restrict__ a, int n_a, const float* __restrict__ b, int ld,
+                                                  int V, const SampleParams* __restrict__ sp, float* __restrict__ lse) {
+  __shared__ float red[16];
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const float* row = r < n_a ? a + (size_t)r * ld : b + (size_t)(r - n_a) * ld;
+  const float it = sp->inv_temp;
+  float mx = -INFINITY;
+  for (int v = tid; v < V; v += 1024) mx = fmaxf(mx, row[v] * it);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  if ((tid & 63) == 0) red[tid >> 6] = mx;
+  __syncthreads();
+  mx = red[0];
+  for (int w = 1; w < 16; ++w) mx = fmaxf(mx, red[w]);
+  __syncthreads();
+  float sum = 0.f;
+  for (int v = tid; v < V; v += 1024) sum += expf(row[v] * it - mx);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+  if ((tid & 63) == 0) red[tid >> 6] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    float t = 0.f;
+    for (int w = 0; w < 16; ++w) t += red[w];
+    lse[r] = mx + logf(t);
+  }
+}
+
+// tokens[o] = argmax_v(logits[v] / T + gumbel(o, stream, v)) with o = the position out_pos gives: one categorical draw
+__global__ __launch_bounds__(1024) void k_sample(const float* __restrict__ logits, int V, const SampleParams* __restrict__ sp,
+                                                 int stream, int* __restrict__ tokens, PosRef out_pos) {
+  __shared__ double sv[16];
+  __shared__ int si[16];
+  const int tid = threadIdx.x;
+  const int o = *out_pos.base + out_pos.offset;
+  const float it = sp->inv_temp;
+  const uint64_t key = sp->key;
+  double best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int v = tid; v < V; v += 1024) {
+    const double sc = (double)(logits[v] * it) + sample_gumbel(o, stream, v, key);
+    if (sc > best || bi == 0x7fffffff) { best = sc; bi = v; }
+  }
+  block_argmax_1024(best, bi, sv, si);
+  if (tid == 0) tokens[o] = bi;
+}
+
+// Validation of a sampled stair batch (one sequence).  tokens[L .. L+k) hold the assistant's draws d_1..d_k, dl[j-1]
+// the logits d_j was drawn from, tl[i] the main model's logits of stair row i, lse[0..k] / lse[k+1..2k] their
+// log-sum-exps at the temperature.  d_i is kept while u_i * q_i(d_i) < p_{i-1}(d_i); at the first one that is not,
+// tokens[L+n] is drawn from the positive part of p_n - q_{n+1}; with all kept, tokens[L+k] from p_k.
+// state = {L + n + 1, n}; emitted[0..n] = the n + 1 tokens of this iteration.
+__global__ __launch_bounds__(1024) void k_accept_sampled(int* __restrict__ tokens, const float* __restrict__ tl,
+                                                         const float* __restrict__ dl, int ld, int V, int k,
+                                                         const float* __restrict__ lse, const SampleParams* __restrict__ sp,
+                                                         int* __restrict__ state, int* __restrict__ emitted) {
+  __shared__ double sv[16];
+  __shared__ int si[16];
+  __shared__ int s_n;
+  const int tid = threadIdx.x;
+  const int L = state[0];
+  const float it = sp->inv_temp;
+  const uint64_t key = sp->key;
+  if (tid == 0) {
+    int n = 0;
+    while (n < k) {
+      const int d = tokens[L + n];
+      const float logp = tl[(size_t)n * ld + d] * it - lse[n];
+      const float logq = dl[(size_t)n * ld + d] * it - lse[k + 1 + n];
+      const double u = sample_uniform(L + n, 1, 0, key);
+      if (!(u < (double)expf(logp - logq))) break;
+      ++n;
+    }
+    s_n = n;
+  }
+  __syncthreads();
+  const int n = s_n;
+  const int pos = L + n;
+  const float* trow = tl + (size_t)n * ld;
+  const float* drow = dl + (size_t)n * ld;     // only read when n < k
+  const float lt = lse[n], lq = n < k ? lse[k + 1 + n] : 0.f;
+  __shared__ int s_empty;
+  double best = -INFINITY;
+  int bi = 0x7fffffff;
+  // pass 0: the positive part of p - q (a token was not kept); pass 1: p itself (all kept, or -- possible only in
+  // rounding, when p and q agree to the last bit and a token was still not kept -- an empty positive part)
+  for (int pass = n < k ? 0 : 1; pass < 2; ++pass) {
+    best = -INFINITY;
+    bi = 0x7fffffff;
+    for (int v = tid; v < V; v += 1024) {
+      double sc;
+      if (pass == 0) {
+        const float diff = expf(trow[v] * it - lt) - expf(drow[v] * it - lq);
+        sc = diff > 0.f ? (double)logf(diff) + sample_gumbel(pos, 2, v, key) : -INFINITY;
+      } else {
+        sc = (double)(trow[v] * it) + sample_gumbel(pos, 2, v, key);
+      }
+      if (sc > best || bi == 0x7fffffff) { best = sc; bi = v; }
+    }
+    block_argmax_1024(best, bi, sv, si);
+    if (tid == 0) s_empty = best == -INFINITY;
+    __syncthreads();
+    if (!s_empty) break;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    for (int i = 0; i < n; ++i) emitted[i] = tokens[L + i];
+    emitted[n] = bi;
+    tokens[pos] = bi;
+    state[0] = L + n + 1;
+    state[1] = n;
+  }
+}
+
+void launch_row_lse(const float* a, int n_a, const float* b, int n_b, int ld, int V, const SampleParams* sp, float* lse,
+                    hipStream_t st) {
+  hipLaunchKernelGGL(k_row_lse, dim3(n_a + n_b), dim3(1024), 0, st, a, n_a, b, ld, V, sp, lse);
+}
+void launch_sample(const float* logits, int V, const SampleParams* sp, int stream, int* tokens, PosRef out_pos,
+                   hipStream_t st) {
+  hipLaunchKernelGGL(k_sample, dim3(1), dim3(1024), 0, st, logits, V, sp, stream, tokens, out_pos);
+}
+void launch_accept_sampled(int* tokens, const float* tl, const float* dl, int ld, int V, int k, const float* lse,
+                           const SampleParams* sp, int* state, int* emitted, hipStream_t st) {
+  hipLaunchKernelGGL(k_accept_sampled, dim3(1), dim3(1024), 0, st, tokens, tl, dl, ld, V, k, lse, sp, state, emitted);
+}
+
+// ---------------------------------------------------------------------------------------
 // prompt ingestion in large row blocks: the element-wise work around the library GEMMs
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_pf_embed(const uint16_t* __restrict__ emb, const int* __restrict__ tokens, int p0,
