@@ -41,6 +41,15 @@ def test_source_lengths(S):
     assert res["max_logit_err"] < 5e-3
 
 
+def test_long_source_takes_the_stand_alone_merge():
+    """3300 source positions = 26 attention chunks: above the limit of the fused chunk merge, so the encoder's
+    attention (bias, fixed key set) and the cross-attention run the merge as a kernel of its own."""
+    w, t, d, src = _pair(S=3300)
+    _log("encdec long source S=3300")
+    res = run_encdec_side_by_side(t, d, src, 10, 3, LOGIT_TOL_BF16)
+    assert res["max_logit_err"] < 5e-3
+
+
 def test_wide_attention_and_independent_draft():
     """n_heads * head_dim != d_model (head_dim 128) in the target; a draft with its own weights and shape."""
     w, t, d, src = _pair(target=dict(n_enc_layers=2, n_dec_layers=2, d_model=256, n_heads=4, head_dim=128),
