@@ -4,6 +4,7 @@ GPU's prefix so that one near-tie does not void the rest of the comparison."""
 import numpy as np
 
 import paper_2407_19947_amd as pkg
+from oracle import sampling_oracle as sa
 from oracle import stairs_oracle as so
 
 LOGIT_TOL_BF16 = 2e-2      # spec tolerance: bf16 GPU vs fp32 oracle, absolute, per stair logit
@@ -81,4 +82,77 @@ def compare_generation(orc, gpu, P, G, k, logit_tol, check_draft=True, max_iters
         assert list(seq) == orc.seq
     res["tokens"] = orc.seq[P:P + G]
     res["iterations"] = iters
+    return res
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# sampling variant: floating point decides integers (argmax of perturbed scores, u < p/q), so the oracle is
+# teacher-forced onto the GPU's choices and every choice must be the oracle's own unless the oracle's margin is within
+# what the logit differences measured in that iteration allow
+# ----------------------------------------------------------------------------------------------------------------
+def _draw_ok(scores, pos, stream, key, tok, tol):
+    """tok maximises scores + Gumbel noise of (pos, stream) up to tol (tol may be per token)."""
+    s = np.asarray(scores, dtype=np.float64) + sa.gumbel(pos, stream, len(scores), key)
+    tol = np.broadcast_to(np.asarray(tol, dtype=np.float64), s.shape)
+    best = int(np.argmax(s))
+    return s[tok] + tol[tok] >= s[best] - tol[best], (tok, best, float(s[tok]), float(s[best]))
+
+
+def compare_sampled(orc, gpu, P, G, k, temp, seed, logit_tol):
+    key = orc.key
+    res = dict(n=[], draft_differs=0, decision_differs=0, final_differs=0, max_err=0.0)
+    while len(orc.seq) - P < G:
+        L = len(orc.seq)
+        if k > 0:
+            d_gpu, dl_gpu = gpu.propose_sampled(k, temp, seed)
+            d_gpu = [int(x) for x in d_gpu]
+            d_orc, dl = orc.propose_sampled(k, forced=d_gpu)
+            e_d = float(np.max(np.abs(dl_gpu.astype(np.float64) - dl)))
+            assert e_d <= logit_tol, f"assistant logits differ by {e_d} at L={L}"
+            for j in range(k):
+                ok, info = _draw_ok(dl[j] / temp, L + j, sa.STREAM_DRAFT, key, d_gpu[j], 2 * e_d / temp + 1e-9)
+                assert ok, f"assistant draw {j} at L={L}: {info}"
+                res["draft_differs"] += d_gpu[j] != d_orc[j]
+        else:
+            d_gpu, dl, e_d = [], np.zeros((0, orc.target.V)), 0.0
+        emitted, n, tl_gpu = gpu.verify_sampled(k, temp, seed)
+        emitted = [int(x) for x in emitted]
+        it = orc.verify_sampled(d_gpu, dl)
+        e_t = float(np.max(np.abs(tl_gpu.astype(np.float64) - it.target_logits)))
+        assert e_t <= logit_tol, f"stair logits differ by {e_t} at L={L}"
+        res["max_err"] = max(res["max_err"], e_t, e_d)
+        band = 2 * (e_t + e_d) / temp + 1e-6                 # what log(p/q) can differ by
+        assert emitted[:n] == d_gpu[:n] and len(emitted) == n + 1
+        if n != it.n_accepted:                               # the first decision that differs must be a near-tie
+            i = min(n, it.n_accepted)
+            assert abs(np.log(it.uniforms[i]) - np.log(it.ratios[i])) <= band, \
+                f"keep/replace decision {i} at L={L}: u={it.uniforms[i]} ratio={it.ratios[i]} band={band}"
+            res["decision_differs"] += 1
+        for i in range(min(n, it.n_accepted)):               # decisions both made the same way
+            assert it.uniforms[i] < it.ratios[i] * np.exp(band)
+        # the last emitted token under the oracle's distributions at the GPU's n
+        pos = L + n
+        if n < k:
+            logp = sa.log_softmax(it.target_logits[n] / temp)
+            logq = sa.log_softmax(dl[n] / temp)
+            p, q = np.exp(logp), np.exp(logq)
+            diff = p - q
+            slack = p * (2 * e_t / temp) + q * (2 * e_d / temp) + 1e-12      # what p - q can differ by
+            scores = np.where(diff > 0, np.log(np.maximum(diff, 1e-300)), -np.inf)
+            # a token whose difference is inside the slack may have any score up to log(slack)
+            tol = np.where(diff > slack, np.log1p(slack / np.maximum(diff - slack, 1e-300)) + slack / np.maximum(diff, 1e-300), np.inf)
+            t = emitted[n]
+            if not np.isfinite(tol[t]):
+                assert abs(diff[t]) <= 4 * slack[t], f"replacement token {t} at L={L} has no positive mass"
+            else:
+                ok, info = _draw_ok(scores, pos, sa.STREAM_TARGET, key, t, np.where(np.isfinite(tol), tol, 0.0))
+                assert ok, f"replacement draw at L={L}: {info}"
+        else:
+            ok, info = _draw_ok(it.target_logits[k] / temp, pos, sa.STREAM_TARGET, key, emitted[n], 2 * e_t / temp + 1e-9)
+            assert ok, f"extra-token draw at L={L}: {info}"
+        if n == it.n_accepted:
+            res["final_differs"] += emitted[n] != it.emitted[n]
+        orc.adopt(L, emitted)                                # teacher forcing
+        res["n"].append(n)
+    assert list(gpu.tokens()) == orc.seq
     return res

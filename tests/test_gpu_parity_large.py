@@ -40,6 +40,24 @@ def test_cfg3_1b_full_prompt():
             assert np.array_equal(toks, base)
 
 
+def test_cfg3_1b_sampled():
+    """The sampling variant at the 1B workload's full shape and prompt: draws, keep / replace decisions and emitted
+    tokens against the oracle (float32, teacher-forced), a few iterations."""
+    from oracle import sampling_oracle as sa, stairs_oracle as so
+    from parity_util import compare_sampled
+    w, target, draft = _pair("cfg3_1b")
+    prompt = si.make_prompt(w)
+    k, temp, seed, G = 4, 0.05, 3, 16
+    T, D = so.OracleModel(target, np.float32), so.OracleModel(draft, np.float32)
+    cap = len(prompt) + G + k + 2
+    orc = sa.SampledStairs(T, D, prompt, cap, temp, seed)
+    with pkg.Stairs(target, draft, k_max=k, max_seq=cap) as gpu:
+        gpu.prefill(prompt)
+        res = compare_sampled(orc, gpu, len(prompt), G, k, temp, seed, LOGIT_TOL_BF16)
+    _log(f"cfg3 sampled: kept {res['n']}, err {res['max_err']:.3g}, differing {res['draft_differs']}/{res['final_differs']}/"
+         f"{res['decision_differs']}")
+
+
 @pytest.fixture(scope="module")
 def pair7b():
     return _pair("cfg4_7b")
