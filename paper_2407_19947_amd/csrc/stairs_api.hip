@@ -99,6 +99,7 @@ struct stairs_ctx {
   float *enc_x = nullptr, *enc_ssq = nullptr, *enc_q = nullptr;
   // sampling variant: parameters on the device, the assistant's logits rows of the pending proposal, log-sum-exps
   SampleParams* samp = nullptr;
+  SampleWs* samp_ws = nullptr;
   float *dlogits = nullptr, *lse = nullptr;
   bool pending_sampled = false;
   int nchunk_cap = 0;
@@ -822,11 +823,11 @@ int enqueue_propose_sampled(stairs_ctx* c, int k, int nch) {
   const int V = m->cfg.vocab;
   int rc = forward(c, m, rel_pos(c, -2), nch, 2, 1, 0, c->dlogits);
   if (rc) return rc;
-  launch_sample(c->dlogits, V, c->samp, 0, c->tokens, rel_pos(c, 0), c->st);
+  launch_sample(c->dlogits, V, c->samp, 0, c->tokens, rel_pos(c, 0), c->samp_ws, c->st);
   for (int j = 1; j < k; ++j) {
     rc = forward(c, m, rel_pos(c, j - 1), nch, 1, 1, 0, c->dlogits + (size_t)j * V);
     if (rc) return rc;
-    launch_sample(c->dlogits + (size_t)j * V, V, c->samp, 0, c->tokens, rel_pos(c, j), c->st);
+    launch_sample(c->dlogits + (size_t)j * V, V, c->samp, 0, c->tokens, rel_pos(c, j), c->samp_ws, c->st);
   }
   HIPCHK(c, hipGetLastError());
   return STAIRS_OK;
@@ -838,7 +839,7 @@ int enqueue_verify_sampled(stairs_ctx* c, int k, int nch) {
   int rc = forward(c, m, rel_pos(c, -1), nch, M, M);
   if (rc) return rc;
   launch_row_lse(c->logits, M, c->dlogits, k, V, V, c->samp, c->lse, c->st);
-  launch_accept_sampled(c->tokens, c->logits, c->dlogits, V, V, k, c->lse, c->samp, c->state, c->tgt_tok, c->st);
+  launch_accept_sampled(c->tokens, c->logits, c->dlogits, V, V, k, c->lse, c->samp, c->state, c->tgt_tok, c->samp_ws, c->st);
   HIPCHK(c, hipGetLastError());
   return STAIRS_OK;
 }
@@ -850,9 +851,10 @@ int set_sampling(stairs_ctx* c, float temperature, uint64_t seed) {
   int rc;
   if (!c->samp) {
     const size_t V = c->T.cfg.vocab;
-    if ((rc = dev_alloc(c, &c->samp, 1)) || (rc = dev_alloc(c, &c->dlogits, (size_t)kMaxRows * V)) ||
-        (rc = dev_alloc(c, &c->lse, (size_t)2 * kMaxRows)))
+    if ((rc = dev_alloc(c, &c->samp, 1)) || (rc = dev_alloc(c, &c->samp_ws, 1)) ||
+        (rc = dev_alloc(c, &c->dlogits, (size_t)kMaxRows * V)) || (rc = dev_alloc(c, &c->lse, (size_t)2 * kMaxRows)))
       return rc;
+    HIPCHK(c, hipMemsetAsync(c->samp_ws, 0, sizeof(SampleWs), c->st));
   }
   uint64_t z = seed + 0x9E3779B97F4A7C15ull;       // one splitmix64 step, forced odd
   z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;

@@ -146,16 +146,25 @@ struct SampleParams {
   float inv_temp;      // 1 / temperature
   uint64_t key;        // key of the counter-based generator (from the seed)
 };
+// Scratch of a draw spread over several blocks: one (score, index) per block and the ticket of the last arrival
+// (zero at allocation, zero again after every launch)
+constexpr int kSampleBlocksMax = 512;
+struct SampleWs {
+  int ticket;
+  int pad;
+  unsigned long long score[kSampleBlocksMax];
+  int idx[kSampleBlocksMax];
+};
 // lse[r] = log sum_v exp(row_r[v] * inv_temp) for the n_a rows of a followed by the n_b rows of b (row stride ld)
 void launch_row_lse(const float* a, int n_a, const float* b, int n_b, int ld, int V, const SampleParams* sp, float* lse,
                     hipStream_t st);
 // tokens[o] = one draw from softmax(logits / T) by Gumbel-max with the random numbers of (o, stream), o = out_pos
 void launch_sample(const float* logits, int V, const SampleParams* sp, int stream, int* tokens, PosRef out_pos,
-                   hipStream_t st);
+                   SampleWs* ws, hipStream_t st);
 // keep / replace walk over a sampled stair batch of one sequence (see k_accept_sampled); lse = launch_row_lse over
 // the k+1 rows of tl followed by the k rows of dl
 void launch_accept_sampled(int* tokens, const float* tl, const float* dl, int ld, int V, int k, const float* lse,
-                           const SampleParams* sp, int* state, int* emitted, hipStream_t st);
+                           const SampleParams* sp, int* state, int* emitted, SampleWs* ws, hipStream_t st);
 
 // ---- prompt ingestion in large row blocks (bf16 models) ------------------------------------------------
 // The projections of a block of up to kPfRows prompt rows are plain GEMMs done by the BLAS library on bf16 copies

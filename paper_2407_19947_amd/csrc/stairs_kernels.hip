@@ -1846,8 +1846,8 @@ __device__ __forceinline__ double sample_gumbel(int pos, int stream, int v, uint
   return -log(-log(sample_uniform(pos, stream, v, key)));
 }
 
-// (max, index) over a 1024-thread block, ties -> lowest index; result valid in thread 0
-__device__ __forceinline__ void block_argmax_1024(double& best, int& bi, double* sv, int* si) {
+// (max, index) over a 256-thread block, ties -> lowest index; result valid in thread 0
+__device__ __forceinline__ void block_argmax_256(double& best, int& bi, double* sv, int* si) {
   const int tid = threadIdx.x;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
@@ -1858,8 +1858,32 @@ __device__ __forceinline__ void block_argmax_1024(double& best, int& bi, double*
   if ((tid & 63) == 0) { sv[tid >> 6] = best; si[tid >> 6] = bi; }
   __syncthreads();
   if (tid == 0)
-    for (int w = 1; w < 16; ++w)
+    for (int w = 1; w < 4; ++w)
       if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
+  __syncthreads();
+}
+
+// A draw over the whole vocabulary spread over the blocks of a launch: every block reduces its candidates to one
+// (score, index), stores it, and the block that arrives last at the ticket reduces those.  Returns true (in every
+// thread of that last block) with the winner in best / bi of thread 0; the ticket is zero again afterwards.
+__device__ __forceinline__ bool grid_argmax(double& best, int& bi, SampleWs* ws, double* sv, int* si, int* s_flag) {
+  block_argmax_256(best, bi, sv, si);
+  if (threadIdx.x == 0) {
+    __hip_atomic_store(&ws->score[blockIdx.x], (unsigned long long)__double_as_longlong(best), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&ws->idx[blockIdx.x], bi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (!last_arrival(&ws->ticket, (int)gridDim.x, s_flag)) return false;
+  best = -INFINITY;
+  bi = 0x7fffffff;
+  for (int i = threadIdx.x; i < (int)gridDim.x; i += 256) {
+    const double ov = __longlong_as_double((long long)__hip_atomic_load(&ws->score[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    const int oi = __hip_atomic_load(&ws->idx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+  }
+  block_argmax_256(best, bi, sv, si);
+  if (threadIdx.x == 0) __hip_atomic_store(&ws->ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return true;
 }
 
 // lse[r] = log sum_v exp(rows[r][v] * inv_temp): one 1024-thread block per row; rows 0..n_a-1 from a, the rest from b
@@ -1891,37 +1915,39 @@ __global__ __launch_bounds__(1024) void k_row_lse(const float* __restrict__ a, i
   }
 }
 
-// tokens[o] = argmax_v(logits[v] / T + gumbel(o, stream, v)) with o = the position out_pos gives: one categorical draw
-__global__ __launch_bounds__(1024) void k_sample(const float* __restrict__ logits, int V, const SampleParams* __restrict__ sp,
-                                                 int stream, int* __restrict__ tokens, PosRef out_pos) {
-  __shared__ double sv[16];
-  __shared__ int si[16];
-  const int tid = threadIdx.x;
+// tokens[o] = argmax_v(logits[v] / T + gumbel(o, stream, v)) with o = the position out_pos gives: one categorical
+// draw, one candidate per thread (grid-stride for very large vocabularies)
+__global__ __launch_bounds__(256) void k_sample(const float* __restrict__ logits, int V, const SampleParams* __restrict__ sp,
+                                                int stream, int* __restrict__ tokens, PosRef out_pos, SampleWs* ws) {
+  __shared__ double sv[4];
+  __shared__ int si[4];
+  __shared__ int s_flag;
   const int o = *out_pos.base + out_pos.offset;
   const float it = sp->inv_temp;
   const uint64_t key = sp->key;
   double best = -INFINITY;
   int bi = 0x7fffffff;
-  for (int v = tid; v < V; v += 1024) {
+  for (int v = blockIdx.x * 256 + threadIdx.x; v < V; v += gridDim.x * 256) {
     const double sc = (double)(logits[v] * it) + sample_gumbel(o, stream, v, key);
     if (sc > best || bi == 0x7fffffff) { best = sc; bi = v; }
   }
-  block_argmax_1024(best, bi, sv, si);
-  if (tid == 0) tokens[o] = bi;
+  if (!grid_argmax(best, bi, ws, sv, si, &s_flag)) return;
+  if (threadIdx.x == 0) tokens[o] = bi;
 }
 
 // Validation of a sampled stair batch (one sequence).  tokens[L .. L+k) hold the assistant's draws d_1..d_k, dl[j-1]
 // the logits d_j was drawn from, tl[i] the main model's logits of stair row i, lse[0..k] / lse[k+1..2k] their
 // log-sum-exps at the temperature.  d_i is kept while u_i * q_i(d_i) < p_{i-1}(d_i); at the first one that is not,
 // tokens[L+n] is drawn from the positive part of p_n - q_{n+1}; with all kept, tokens[L+k] from p_k.
-// state = {L + n + 1, n}; emitted[0..n] = the n + 1 tokens of this iteration.
-__global__ __launch_bounds__(1024) void k_accept_sampled(int* __restrict__ tokens, const float* __restrict__ tl,
-                                                         const float* __restrict__ dl, int ld, int V, int k,
-                                                         const float* __restrict__ lse, const SampleParams* __restrict__ sp,
-                                                         int* __restrict__ state, int* __restrict__ emitted) {
-  __shared__ double sv[16];
-  __shared__ int si[16];
-  __shared__ int s_n;
+// state = {L + n + 1, n}; emitted[0..n] = the n + 1 tokens of this iteration.  Every block repeats the (cheap) walk
+// and scores its share of the vocabulary; the block that arrives last picks the winner and writes the results.
+__global__ __launch_bounds__(256) void k_accept_sampled(int* __restrict__ tokens, const float* __restrict__ tl,
+                                                        const float* __restrict__ dl, int ld, int V, int k,
+                                                        const float* __restrict__ lse, const SampleParams* __restrict__ sp,
+                                                        int* __restrict__ state, int* __restrict__ emitted, SampleWs* ws) {
+  __shared__ double sv[4];
+  __shared__ int si[4];
+  __shared__ int s_n, s_flag, s_empty;
   const int tid = threadIdx.x;
   const int L = state[0];
   const float it = sp->inv_temp;
@@ -1944,29 +1970,31 @@ __global__ __launch_bounds__(1024) void k_accept_sampled(int* __restrict__ token
   const float* trow = tl + (size_t)n * ld;
   const float* drow = dl + (size_t)n * ld;     // only read when n < k
   const float lt = lse[n], lq = n < k ? lse[k + 1 + n] : 0.f;
-  __shared__ int s_empty;
   double best = -INFINITY;
   int bi = 0x7fffffff;
-  // pass 0: the positive part of p - q (a token was not kept); pass 1: p itself (all kept, or -- possible only in
-  // rounding, when p and q agree to the last bit and a token was still not kept -- an empty positive part)
-  for (int pass = n < k ? 0 : 1; pass < 2; ++pass) {
+  for (int v = blockIdx.x * 256 + tid; v < V; v += gridDim.x * 256) {
+    double sc;
+    if (n < k) {                               // the positive part of p - q (a token was not kept)
+      const float diff = expf(trow[v] * it - lt) - expf(drow[v] * it - lq);
+      sc = diff > 0.f ? (double)logf(diff) + sample_gumbel(pos, 2, v, key) : -INFINITY;
+    } else {                                   // all kept: p itself
+      sc = (double)(trow[v] * it) + sample_gumbel(pos, 2, v, key);
+    }
+    if (sc > best || bi == 0x7fffffff) { best = sc; bi = v; }
+  }
+  if (!grid_argmax(best, bi, ws, sv, si, &s_flag)) return;
+  if (tid == 0) s_empty = best == -INFINITY;
+  __syncthreads();
+  if (s_empty) {
+    // possible only in rounding (p and q agree to the last bit and a token was still not kept): draw from p, by
+    // this block alone
     best = -INFINITY;
     bi = 0x7fffffff;
-    for (int v = tid; v < V; v += 1024) {
-      double sc;
-      if (pass == 0) {
-        const float diff = expf(trow[v] * it - lt) - expf(drow[v] * it - lq);
-        sc = diff > 0.f ? (double)logf(diff) + sample_gumbel(pos, 2, v, key) : -INFINITY;
-      } else {
-        sc = (double)(trow[v] * it) + sample_gumbel(pos, 2, v, key);
-      }
+    for (int v = tid; v < V; v += 256) {
+      const double sc = (double)(trow[v] * it) + sample_gumbel(pos, 2, v, key);
       if (sc > best || bi == 0x7fffffff) { best = sc; bi = v; }
     }
-    block_argmax_1024(best, bi, sv, si);
-    if (tid == 0) s_empty = best == -INFINITY;
-    __syncthreads();
-    if (!s_empty) break;
-    __syncthreads();
+    block_argmax_256(best, bi, sv, si);
   }
   if (tid == 0) {
     for (int i = 0; i < n; ++i) emitted[i] = tokens[L + i];
@@ -1981,13 +2009,15 @@ void launch_row_lse(const float* a, int n_a, const float* b, int n_b, int ld, in
                     hipStream_t st) {
   hipLaunchKernelGGL(k_row_lse, dim3(n_a + n_b), dim3(1024), 0, st, a, n_a, b, ld, V, sp, lse);
 }
+static int sample_blocks(int V) { return std::min(kSampleBlocksMax, (V + 255) / 256); }
 void launch_sample(const float* logits, int V, const SampleParams* sp, int stream, int* tokens, PosRef out_pos,
-                   hipStream_t st) {
-  hipLaunchKernelGGL(k_sample, dim3(1), dim3(1024), 0, st, logits, V, sp, stream, tokens, out_pos);
+                   SampleWs* ws, hipStream_t st) {
+  hipLaunchKernelGGL(k_sample, dim3(sample_blocks(V)), dim3(256), 0, st, logits, V, sp, stream, tokens, out_pos, ws);
 }
 void launch_accept_sampled(int* tokens, const float* tl, const float* dl, int ld, int V, int k, const float* lse,
-                           const SampleParams* sp, int* state, int* emitted, hipStream_t st) {
-  hipLaunchKernelGGL(k_accept_sampled, dim3(1), dim3(1024), 0, st, tokens, tl, dl, ld, V, k, lse, sp, state, emitted);
+                           const SampleParams* sp, int* state, int* emitted, SampleWs* ws, hipStream_t st) {
+  hipLaunchKernelGGL(k_accept_sampled, dim3(sample_blocks(V)), dim3(256), 0, st, tokens, tl, dl, ld, V, k, lse, sp, state,
+                     emitted, ws);
 }
 
 // ---------------------------------------------------------------------------------------
