@@ -249,6 +249,11 @@ int stairs_encode(stairs_ctx *ctx, const int32_t *src, int32_t S);
 int stairs_encdec_generate(stairs_ctx *ctx, const int32_t *src, int32_t S, int32_t G, int32_t k,
                            int32_t *tokens_out, stairs_stats *stats);
 
+/* The bucket the library's bias tables use for rel = key position - query position (host arithmetic, no GPU needed;
+ * two_sided: the encoder's rule, else the decoder's): lets a caller or a test check the rule against its own.
+ * Returns -1 for table shapes stairs_encdec_init would reject. */
+int32_t stairs_rel_bucket(int32_t rel, int32_t two_sided, int32_t buckets, int32_t max_distance);
+
 /* Copy the current sequence (prompt + generated) into out[0..min(cap, len)); *len = length. */
 int stairs_get_tokens(stairs_ctx *ctx, int32_t *out, int32_t cap, int32_t *len);
 

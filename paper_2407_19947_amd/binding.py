@@ -21,6 +21,7 @@ EXPORTED_SYMBOLS = [
     "stairs_get_tokens", "stairs_gemm_host", "stairs_time_kernel", "stairs_copy_probe",
     "stairs_encdec_init", "stairs_encode", "stairs_encdec_generate",
     "stairs_decode_sampled", "stairs_generate_sampled", "draft_propose_sampled", "stairs_verify_sampled",
+    "stairs_rel_bucket",
 ]
 
 
@@ -123,6 +124,7 @@ def lib() -> C.CDLL:
     L.stairs_encdec_init.argtypes = [C.POINTER(vp), C.POINTER(_EncDecCfg), C.POINTER(_EncDecWeights),
                                      C.POINTER(_EncDecCfg), C.POINTER(_EncDecWeights), i32, i32, vp]
     L.stairs_encode.argtypes = [vp, i32p, i32]
+    L.stairs_rel_bucket.argtypes = [i32, i32, i32, i32]
     L.stairs_decode_sampled.argtypes = [vp, i32, i32, C.c_float, C.c_uint64, i32p, C.POINTER(StairsStats)]
     L.stairs_generate_sampled.argtypes = [vp, i32p, i32, i32, i32, C.c_float, C.c_uint64, i32p, C.POINTER(StairsStats)]
     L.draft_propose_sampled.argtypes = [vp, i32, C.c_float, C.c_uint64, i32p, f32p]
@@ -363,6 +365,10 @@ def stairs_encdec_init(target, draft, k_max: int, max_src: int, max_seq: int, st
         rc = lib().stairs_encdec_init(C.byref(ctx), C.byref(tcfg), C.byref(tw), None, None, k_max, start_token, stream)
     _check(rc, "stairs_encdec_init")
     return ctx
+
+
+def stairs_rel_bucket(rel: int, two_sided: bool, buckets: int, max_distance: int) -> int:
+    return lib().stairs_rel_bucket(rel, 1 if two_sided else 0, buckets, max_distance)
 
 
 def stairs_encode(ctx, src: Sequence[int]):

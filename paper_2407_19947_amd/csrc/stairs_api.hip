@@ -337,15 +337,20 @@ int rel_bucket(int n, int side, int max_distance) {
   return std::min(exact + (int)std::floor(t), side - 1);
 }
 
+// bucket of rel = key position - query position: two-sided (encoder; keys after the query take the upper half of the
+// buckets) or one-sided (decoder; keys after the query count as distance 0)
+int bias_bucket(int rel, bool two_sided, int buckets, int max_distance) {
+  if (two_sided) return (rel > 0 ? buckets / 2 : 0) + rel_bucket(std::abs(rel), buckets / 2, max_distance);
+  return rel_bucket(std::max(-rel, 0), buckets, max_distance);
+}
+
 // Bias tables by distance: dst[h][i] = table[bucket(rel)][h] with rel = i - zero (key position - query position).
 int upload_bias(stairs_ctx* c, const float* table, int buckets, int max_distance, int H, int len, int zero, bool two_sided,
                 float** out) {
   std::vector<float> host((size_t)H * len);
   for (int i = 0; i < len; ++i) {
     const int rel = i - zero;
-    int b;
-    if (two_sided) b = (rel > 0 ? buckets / 2 : 0) + rel_bucket(std::abs(rel), buckets / 2, max_distance);
-    else b = rel_bucket(std::max(-rel, 0), buckets, max_distance);
+    const int b = bias_bucket(rel, two_sided, buckets, max_distance);
     for (int h = 0; h < H; ++h) host[(size_t)h * len + i] = table[(size_t)b * H + h];
   }
   int rc = dev_alloc(c, out, host.size());
@@ -1189,6 +1194,11 @@ int stairs_encdec_init(stairs_ctx** out, const stairs_encdec_cfg* tcfg, const st
   if ((rc = alloc_workspaces(c, w))) return bail(rc);
   *out = c;
   return STAIRS_OK;
+}
+
+int32_t stairs_rel_bucket(int32_t rel, int32_t two_sided, int32_t buckets, int32_t max_distance) {
+  if (buckets < 4 || buckets % 4 || max_distance <= buckets / 2) return -1;
+  return bias_bucket(rel, two_sided != 0, buckets, max_distance);
 }
 
 int stairs_encode(stairs_ctx* c, const int32_t* src, int32_t S) {

@@ -82,3 +82,35 @@ def test_gemm_host_rejects_bad_shapes():
         pkg.stairs_gemm_host(W, X)                      # K % 256 != 0 for bf16
     with pytest.raises(pkg.StairsError):
         pkg.stairs_gemm_host(np.zeros((16, 256), np.uint16), np.zeros((33, 256), np.float32))   # M > 32
+
+
+@pytest.mark.parametrize("buckets,maxd", [(32, 128), (16, 64), (64, 256)])
+def test_host_bucket_rule_equals_the_oracles(buckets, maxd):
+    """The bias tables the library builds on the host use the same buckets as the oracle's own implementation of
+    the rule (itself pinned in test_oracle_encdec.py), for every distance a table can hold."""
+    from oracle import encdec_oracle as eo
+    rel = np.arange(-5000, 5001)
+    for two_sided in (True, False):
+        want = eo.relative_position_bucket(rel, two_sided, buckets, maxd)
+        got = np.array([pkg.stairs_rel_bucket(int(r), two_sided, buckets, maxd) for r in rel])
+        assert np.array_equal(got, want), two_sided
+    assert pkg.stairs_rel_bucket(1, True, 30, 128) == -1 and pkg.stairs_rel_bucket(1, True, 32, 16) == -1
+
+
+def test_encdec_init_rejects_bad_shapes_without_gpu():
+    m = si.make_encdec_model(1, 1, 1, 256, 4, 64, 256, 512)
+    keep = []
+    cfg, w = binding._marshal_encdec(m, 16, 16, keep)
+    ctx = C.c_void_p()
+    L = pkg.lib()
+
+    def init(cfg_, k_max=0, start=0):
+        return L.stairs_encdec_init(C.byref(ctx), C.byref(cfg_), C.byref(w), None, None, k_max, start, None)
+
+    for field, value in (("head_dim", 32), ("d_model", 128), ("d_ffn", 100), ("vocab", 500), ("rel_buckets", 30),
+                         ("rel_max_distance", 8), ("max_src", 5000), ("max_seq", 1), ("n_enc_layers", 0)):
+        bad = binding._EncDecCfg.from_buffer_copy(cfg)
+        setattr(bad, field, value)
+        assert init(bad) == -1 and not ctx.value, field
+    assert init(cfg, k_max=1) == -1                                          # k_max > 0 without a draft
+    assert init(cfg, start=512) == -1                                        # start token outside the vocabulary

@@ -50,6 +50,14 @@ def test_long_source_takes_the_stand_alone_merge():
     assert res["max_logit_err"] < 5e-3
 
 
+def test_long_decoder_sequence_reaches_the_last_bucket():
+    """200 decoder positions: key distances pass 128, where the one-sided rule stays in its last bucket, and the
+    decoder's self-attention crosses a 128-key chunk boundary (two chunks, fused merge with bias)."""
+    w, t, d, src = _pair()
+    res = run_encdec_side_by_side(t, d, src, 200, 4, LOGIT_TOL_BF16)
+    assert res["max_logit_err"] < 5e-3
+
+
 def test_wide_attention_and_independent_draft():
     """n_heads * head_dim != d_model (head_dim 128) in the target; a draft with its own weights and shape."""
     w, t, d, src = _pair(target=dict(n_enc_layers=2, n_dec_layers=2, d_model=256, n_heads=4, head_dim=128),
