@@ -6,7 +6,11 @@ the workload's prompt: draft k-step proposal, stair verification forward at M = 
 per-row argmax, validation walk, KV rollback, repeated until G tokens exist.  Weights, KV
 caches and the prompt are resident in HBM when the timed region starts.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric / value / unit (generated tokens per second of the decode phase at the best draft
+length of a short sweep), the run's shape, "roofline" (the dominant kernel, the gate/up projection, against the HBM
+peak: algorithmic bytes over its mean in-situ duration from HIP-event pairs, plus the isolated figure and the
+measured counter traffic), "cpu_baseline" (the CPU oracle on a bounded sample of the same workload) and the extra
+legs: verification time against k, adaptive draft length, sampling, several sequences, encoder-decoder pairs.
 """
 import argparse
 import json
