@@ -151,3 +151,25 @@ def test_large_shape_pair_against_the_oracle():
         gpu.encode(src)
         res = compare_generation(orc, gpu, 1, 24, 4, LOGIT_TOL_BF16, log=_log)
     _log(f"  max logit err {res['max_logit_err']:.3g}, accepted {res['n_accepted']}")
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_encdec_shape_sweep_against_the_oracle(case):
+    """Seeded sweep over the documented limits: model widths with an odd number of 256-wide weight units, attention
+    widths that differ from d_model, both head sizes, feed-forward widths that are not multiples of 512, source lengths
+    from 1 to a few hundred, draft lengths on every GEMM / attention path."""
+    rng = np.random.default_rng([2025, case])
+    d = int(rng.choice([256, 512, 768]))
+    hd = int(rng.choice([64, 128]))
+    a = int(rng.choice([256, 512, 768]))
+    f = int(rng.choice([256, 768, 1280]))
+    V = int(rng.choice([272, 1008, 2048]))
+    k = [0, 1, 3, 4, 6, 9, 16, 31][case]
+    S = int(rng.integers(1, 400))
+    w = si.scaled_encdec_workload("t5_tiny", seed=7000 + case,
+                                  target=dict(n_enc_layers=2, n_dec_layers=2, d_model=d, n_heads=a // hd, head_dim=hd,
+                                              d_ffn=f, vocab=V), S=400)
+    _log(f"encdec shape sweep {case}: d={d} a={a} hd={hd} f={f} V={V} S={S} k={k}")
+    t, dr = si.make_encdec_pair(w)
+    res = run_encdec_side_by_side(t, dr, si.make_source(w, S), 2 * (k + 1) + 6, k, LOGIT_TOL_BF16)
+    assert res["max_logit_err"] < 5e-3

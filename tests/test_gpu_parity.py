@@ -452,3 +452,26 @@ def test_longest_context_stair_batches(monkeypatch):
     err = float(np.max(np.abs(lg.astype(np.float64) - want)))
     _log(f"longest context, row prefill: max logit error {err:.3g}")
     assert err <= LOGIT_TOL_BF16
+
+
+@pytest.mark.parametrize("case", range(14))
+def test_shape_sweep_against_the_oracle(case):
+    """Seeded sweep over the documented shape limits: widths with an odd number of 256-wide weight units (768, 1280),
+    feed-forward widths that are not multiples of 512, vocabularies that are multiples of 16 but not of 64, both head
+    sizes, prompt lengths from 1 to a few hundred, draft lengths on every GEMM / attention path (<= 4 rows, 5..8,
+    9..16, 17..32 rows)."""
+    rng = np.random.default_rng([2024, case])
+    d = int(rng.choice([256, 512, 768, 1280]))
+    hd = int(rng.choice([64, 128]))
+    f = int(rng.choice([256, 768, 1024, 2816]))
+    V = int(rng.choice([272, 1008, 2048, 4112]))
+    k = int([0, 1, 2, 3, 4, 5, 7, 8, 9, 12, 15, 16, 23, 31][case])
+    P = int(rng.integers(1, 300))
+    G = 2 * (k + 1) + 6
+    w = si.scaled_workload("cfg2_125m", seed=5000 + case,
+                           target=dict(n_layers=2, d_model=d, n_heads=d // hd, d_ffn=f, vocab=V),
+                           draft=dict(kind="prefix", n_layers=1), P=P, G=G)
+    _log(f"shape sweep {case}: d={d} hd={hd} f={f} V={V} P={P} k={k}")
+    target, draft = si.make_pair(w)
+    res = run_side_by_side(target, draft, si.make_prompt(w), G, k, np.float64, LOGIT_TOL_BF16)
+    assert res["max_logit_err"] < 5e-3
