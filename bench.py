@@ -196,26 +196,27 @@ def main():
     assert np.array_equal(toks_plain, toks0), "stairs output differs from plain greedy"
 
     # ---- roofline of the dominant kernel: gate/up projection GEMM at M = k+1 rows ----------
-    # in situ: whole verification forwards at the decode's context length, a HIP-event pair around every layer's
-    # gate/up launch (the event pair costs ~2 us itself, so this is a slight under-estimate of the kernel's rate);
+    # in situ: whole verification forwards at the decode's context length, every layer's gate/up launch recording its
+    # own start and end events (the HIP events of the launch itself: nothing is added to the stream, and the figure
+    # agrees with what rocprofv3 reports for the same launches); also the reading of an event pair recorded around
+    # the launch (which contains the pair's own cost) and of an empty pair;
     # isolated: the same kernel launched back to back, cycling through the layers' matrices
     M = k + 1
     ctx_mid = P + G // 2
-    ms_situ, bytes_gu = eng.time_kernel(8, M, ctx_mid, 4)
+    ms_situ, bytes_gu = eng.time_kernel(10, M, ctx_mid, 4)
+    ms_around, _ = eng.time_kernel(8, M, ctx_mid, 4)
     ms_pair, _ = eng.time_kernel(9, M, ctx_mid, 4)      # what an event pair reads with no kernel inside
     ms_iso, _ = eng.time_kernel(0, M, 0, 4 * target.n_layers)
     achieved = bytes_gu / (ms_situ * 1e-3) / 1e9
-    net = bytes_gu / (max(ms_situ - ms_pair, 1e-6) * 1e-3) / 1e9
     kname = (f"k_gemm_bf16_rows<{M}, gate/up> (whole X block in LDS, one work-group per weight tile)" if M <= 4
              else f"k_gemm_bf16<{1 if M <= 16 else 2}, 2, gate/up> (split-K with in-kernel hand-off)")
     roofline = {"bound": "hbm", "kernel": kname + ": gate/up projection + SwiGLU at M = k+1 rows",
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                 "traffic": measured_traffic(), "bytes_per_launch": bytes_gu, "ms_per_launch": ms_situ,
                 "launches_timed": 4 * target.n_layers,
-                "how": "in situ: HIP-event pair around each layer's launch inside whole verification forwards; "
-                       "achieved/frac use the pair's reading as it is",
-                "event_pair_overhead_ms": ms_pair, "net_of_event_overhead_GBps": net,
-                "net_of_event_overhead_frac": net / HBM_PEAK_GBPS,
+                "how": "in situ: start/end HIP events of each layer's launch inside whole verification forwards",
+                "event_pair_around_launch_ms": ms_around, "empty_event_pair_ms": ms_pair,
+                "event_pair_around_launch_frac": bytes_gu / (ms_around * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                 "isolated_ms_per_launch": ms_iso, "isolated_GBps": bytes_gu / (ms_iso * 1e-3) / 1e9,
                 "isolated_frac": bytes_gu / (ms_iso * 1e-3) / 1e9 / HBM_PEAK_GBPS}
     # second denominator: what a plain copy kernel (1 GiB read + 1 GiB written) streams on this machine

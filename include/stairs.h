@@ -275,11 +275,13 @@ int stairs_gemm_host(int32_t dtype, const void *W, const float *X, float *Y, int
  * 8 = the gate/up projection GEMM in situ: `reps` whole target forwards as in 6, with an event
  * pair around every layer's gate/up launch; the mean over reps * n_layers launches is returned,
  * 9 = the same forwards with each event pair recorded back to back in front of the gate/up launch: what a pair
- * reads with no kernel inside (the overhead contained in 8's figure).
+ * reads with no kernel inside (the overhead contained in 8's figure),
+ * 10 = the same forwards with every layer's gate/up launch recording its own start and end events (the launch's
+ * events, nothing added to the stream): the kernel's duration in situ without the pair's overhead.
  * *ms_per_launch: mean duration; *bytes_per_launch: algorithmic bytes (matrix bytes; K and V
  * bytes of ctx_len positions; for 6/7 all matrices of the model plus its K and V bytes).
  * 0..5 do not disturb the sequence state but overwrite workspaces (do not call between
- * draft_propose and stairs_verify); 6, 7, 8 and 9 also overwrite the cache rows of the M positions
+ * draft_propose and stairs_verify); 6, 7, 8, 9 and 10 also overwrite the cache rows of the M positions
  * they run at: call stairs_prefill before generating again. */
 int stairs_time_kernel(stairs_ctx *ctx, int32_t which, int32_t M, int32_t ctx_len, int32_t reps,
                        float *ms_per_launch, double *bytes_per_launch);

@@ -190,6 +190,7 @@ const char* check_weights(const stairs_model_cfg* m, const stairs_weights* w) {
 }
 
 constexpr int kProbeEmptyPair = 100;
+constexpr int kProbeKernelEvents = 101;   // the gate/up launch records its own start / end events
 enum { KIND_EMB = 0, KIND_HEAD, KIND_NORM, KIND_QKV, KIND_WO, KIND_GU, KIND_DOWN };
 
 // Upload a matrix made of `nparts` row blocks (each [rows_each, K], host, model dtype) as one
@@ -517,6 +518,7 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
       HIPCHK(c, hipEventRecord(c->probe_ev[2 * l + 1], st));
     }
     if (c->probe_role == kRoleGateUp) HIPCHK(c, hipEventRecord(c->probe_ev[2 * l], st));
+    if (c->probe_role == kProbeKernelEvents) set_gemm_launch_events(c->probe_ev[2 * l], c->probe_ev[2 * l + 1]);
     RowNorm fn{ly.ffn_norm, c->ssq, sn, g.rms_eps, nullptr};
     if (b && M > 16) {
       launch_rstd(fn, M, d, c->rstd, st);
@@ -1741,7 +1743,7 @@ int stairs_copy_probe(int64_t bytes, int32_t reps, float* ms_per_launch, void* h
 int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len, int32_t reps, float* ms_per_launch,
                        double* bytes_per_launch) {
   if (!c) return STAIRS_EINVAL;
-  if (which < 0 || which > 9 || M < 1 || M > kMaxRows || reps < 1 || !ms_per_launch)
+  if (which < 0 || which > 10 || M < 1 || M > kMaxRows || reps < 1 || !ms_per_launch)
     return fail(c, STAIRS_EINVAL, "bad argument to stairs_time_kernel");
   if (c->encdec) return fail(c, STAIRS_EINVAL, "stairs_time_kernel takes decoder-only contexts");
   if (c->pending_k >= 0) return fail(c, STAIRS_ESTATE, "a proposal is pending");
@@ -1751,7 +1753,7 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
   const int d = g.d_model, f = g.d_ffn, V = g.vocab, b = m->bf16 ? 1 : 0;
   const size_t esz = m->esz();
   if (which >= 5 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");
-  if (which == 8 || which == 9) {
+  if (which == 8 || which == 9 || which == 10) {
     // the gate/up projection timed where it really runs: `reps` whole forwards of M rows ending at position
     // ctx_len-1, an event pair around each layer's gate/up launch, all other kernels untouched in between
     const int nl = g.n_layers;
@@ -1762,7 +1764,8 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
     }
     double total_ms = 0;
     for (int r = 0; r <= reps; ++r) {              // r == 0: warm-up
-      c->probe_role = which == 8 ? kRoleGateUp : kProbeEmptyPair;   // 9: what an event pair reads with no kernel inside
+      // 9: what an event pair reads with no kernel inside; 10: the launch's own start / end events
+      c->probe_role = which == 8 ? kRoleGateUp : which == 9 ? kProbeEmptyPair : kProbeKernelEvents;
       int rc = forward(c, m, abs_pos(c, ctx_len - M), chunks_for(ctx_len), M, M);
       c->probe_role = -1;
       if (rc) return rc;

@@ -104,6 +104,10 @@ struct GemmEpi {
 void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M,
                  RowNorm nrm, float* partial, const GemmEpi& epi, hipStream_t st);
 
+// The next bf16 launch_gemm records `start` at the beginning and `stop` at the end of its kernel (the events of the
+// launch itself, not records around it in the stream); one launch only.  Measurement aid.
+void set_gemm_launch_events(hipEvent_t start, hipEvent_t stop);
+
 // rstd[m] = 1/sqrt(sum of the row's partials / K + eps) for M rows, once per GEMM instead of once per work-group
 // (bf16 path; pays from 17 rows on, where every work-group would otherwise fetch 32 rows' partials)
 void launch_rstd(RowNorm nrm, int M, int K, float* rstd, hipStream_t st);

@@ -8,6 +8,7 @@
 // batch gets bit-identical results to the same position computed alone (the property that
 // makes the stair batch return what plain greedy decoding returns, paper abstract / Sec. 3.3).
 #include "stairs_kernels.h"
+#include <hip/hip_ext.h>
 
 #include <math.h>
 
@@ -841,6 +842,23 @@ void launch_fin_swiglu(const float* partial, int S, int M, int f, float* h, hipS
 void launch_fin_qkv_rope_f32(const float* partial, int S, int M, int d, int H, const float2* rope_cs, PosRef pos,
                              float* q_rot, float* Kc, float* Vc, int cap, hipStream_t st);
 
+// Events the next bf16 GEMM launch records at the kernel's own start and end (set_gemm_launch_events): lets a
+// measurement take one kernel's duration inside a running forward without event records around it in the stream.
+static hipEvent_t g_gemm_ev_start = nullptr, g_gemm_ev_stop = nullptr;
+void set_gemm_launch_events(hipEvent_t start, hipEvent_t stop) {
+  g_gemm_ev_start = start;
+  g_gemm_ev_stop = stop;
+}
+template <typename F, typename... Args>
+static void launch_gemm_kernel(F kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args) {
+  if (g_gemm_ev_start && g_gemm_ev_stop) {
+    hipExtLaunchKernelGGL(kernel, grid, block, (std::uint32_t)lds, st, g_gemm_ev_start, g_gemm_ev_stop, 0, args...);
+    g_gemm_ev_start = g_gemm_ev_stop = nullptr;
+  } else {
+    hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
+  }
+}
+
 void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M, RowNorm nrm,
                  float* partial, const GemmEpi& epi, hipStream_t st) {
   if (!dtype_bf16) {
@@ -866,7 +884,7 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
   const uint4* Wsw = static_cast<const uint4*>(W);
   if (const size_t rl = rows_path_lds(role, M, N, K)) {
 #define STAIRS_ROWS(r, role, nw, gp)                                                                                  \
-  hipLaunchKernelGGL((k_gemm_bf16_rows<r, role, nw, gp>), dim3(NTILES), dim3(64 * nw), rl, st, Wsw, NTILES, X, ldx, nrm, \
+  launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp>, dim3(NTILES), dim3(64 * nw), rl, st, Wsw, NTILES, X, ldx, nrm, \
                      K, N, epi)
 #define STAIRS_ROWS_ROLE(role, nw, gp)           \
   if (M <= 1) STAIRS_ROWS(1, role, nw, gp);      \
@@ -894,7 +912,7 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
   dim3 grid((NTILES + 4 * NT - 1) / (4 * NT), SG), block(256);
   const size_t lds = (size_t)16 * CT * 2 * 64 * sizeof(uint4);
 #define STAIRS_GEMM(ct, nt, role, spw) \
-  hipLaunchKernelGGL((k_gemm_bf16<ct, nt, role, spw>), grid, block, lds, st, Wsw, KT, NTILES, X, ldx, M, nrm, K, partial, N, epi)
+  launch_gemm_kernel(k_gemm_bf16<ct, nt, role, spw>, grid, block, lds, st, Wsw, KT, NTILES, X, ldx, M, nrm, K, partial, N, epi)
 #define STAIRS_GEMM_NT(ct, role, spw)             \
   if (NT == 1) STAIRS_GEMM(ct, 1, role, spw);     \
   else STAIRS_GEMM(ct, 2, role, spw)
