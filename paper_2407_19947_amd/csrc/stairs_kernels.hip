@@ -844,7 +844,8 @@ void launch_fin_qkv_rope_f32(const float* partial, int S, int M, int d, int H, c
 
 // Events the next bf16 GEMM launch records at the kernel's own start and end (set_gemm_launch_events): lets a
 // measurement take one kernel's duration inside a running forward without event records around it in the stream.
-static hipEvent_t g_gemm_ev_start = nullptr, g_gemm_ev_stop = nullptr;
+// (per thread: a context is used by one thread at a time)
+static thread_local hipEvent_t g_gemm_ev_start = nullptr, g_gemm_ev_stop = nullptr;
 void set_gemm_launch_events(hipEvent_t start, hipEvent_t stop) {
   g_gemm_ev_start = start;
   g_gemm_ev_stop = stop;
