@@ -842,8 +842,9 @@ void launch_fin_swiglu(const float* partial, int S, int M, int f, float* h, hipS
 void launch_fin_qkv_rope_f32(const float* partial, int S, int M, int d, int H, const float2* rope_cs, PosRef pos,
                              float* q_rot, float* Kc, float* Vc, int cap, hipStream_t st);
 
-// Events the next bf16 GEMM launch records at the kernel's own start and end (set_gemm_launch_events): lets a
-// measurement take one kernel's duration inside a running forward without event records around it in the stream.
+// Events the next GEMM launch records at the kernel's own start and end (set_gemm_launch_events): lets a measurement
+// take one kernel's duration inside a running forward without event records around it in the stream.  (fp32 models
+// run two kernels per projection: there the events are recorded around the pair.)
 // (per thread: a context is used by one thread at a time)
 static thread_local hipEvent_t g_gemm_ev_start = nullptr, g_gemm_ev_stop = nullptr;
 void set_gemm_launch_events(hipEvent_t start, hipEvent_t stop) {
@@ -865,6 +866,13 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
   if (!dtype_bf16) {
     dim3 grid((N + 3) / 4), block(256);
     const float* Wf = static_cast<const float*>(W);
+    // two kernels here: requested launch events become records around the pair
+    hipEvent_t ev_stop = nullptr;
+    if (g_gemm_ev_start && g_gemm_ev_stop) {
+      (void)hipEventRecord(g_gemm_ev_start, st);
+      ev_stop = g_gemm_ev_stop;
+      g_gemm_ev_start = g_gemm_ev_stop = nullptr;
+    }
     if (M <= 4) hipLaunchKernelGGL(k_gemm_f32<4>, grid, block, 0, st, Wf, N, K, X, ldx, M, nrm, partial);
     else if (M <= 16) hipLaunchKernelGGL(k_gemm_f32<16>, grid, block, 0, st, Wf, N, K, X, ldx, M, nrm, partial);
     else hipLaunchKernelGGL(k_gemm_f32<32>, grid, block, 0, st, Wf, N, K, X, ldx, M, nrm, partial);
@@ -878,6 +886,7 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
       case kRoleGateUp: launch_fin_swiglu(partial, 1, M, N / 2, epi.out, st); break;
       default: launch_fin_plain(partial, 1, M, N, epi.out, N, st); break;
     }
+    if (ev_stop) (void)hipEventRecord(ev_stop, st);
     return;
   }
   const int S = gemm_slices(K, 1);

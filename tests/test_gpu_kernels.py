@@ -71,3 +71,19 @@ def test_both_bf16_gemm_kernels_give_the_same_bits(K):
     for m in (1, 2, 3, 4, 5):
         assert np.array_equal(pkg.stairs_gemm_host(W, X[:m]), wide[:m]), m
     assert np.array_equal(pkg.stairs_gemm_host(W, X[7:10]), wide[7:10])
+
+
+@pytest.mark.parametrize("name", ["cfg1_tiny_fp32", "cfg2_125m"])
+def test_timing_probes_run_on_both_dtypes(name):
+    """Every mode of stairs_time_kernel returns a positive duration and the bytes it states, on an fp32 and a bf16
+    pair (the benchmark calls them on whatever workload it is given), and leaves the context usable."""
+    w = si.scaled_workload(name, target=dict(n_layers=2), draft=dict(kind="prefix", n_layers=1), P=40, G=8)
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    with pkg.Stairs(target, draft, k_max=4, max_seq=128) as s:
+        base, _ = s.generate(prompt, 8, 2)
+        for which in range(11):
+            ms, by = s.time_kernel(which, 3, 64, 4)
+            assert ms > 0 and (by > 0 or which == 9), which
+        again, _ = s.generate(prompt, 8, 2)
+        assert np.array_equal(base, again)
