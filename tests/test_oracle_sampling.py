@@ -43,6 +43,38 @@ def test_generator_is_deterministic_uniform_and_streams_differ():
         assert abs(np.mean((r >> np.uint64(b)) & np.uint64(1)) - 0.5) < 0.01
 
 
+def test_generator_arithmetic_in_unbounded_integers():
+    """The four squaring rounds redone with Python's unbounded integers reduced mod 2^64 by hand (no fixed-width
+    wrap-around to rely on), for counters of every stream and large positions, and the key derivation likewise."""
+    M = 1 << 64
+
+    def rot32(x):
+        return ((x >> 32) | (x << 32)) % M
+
+    def squares(ctr, key):
+        x = (ctr * key) % M
+        y = x
+        z = (y + key) % M
+        x = rot32((x * x + y) % M)
+        x = rot32((x * x + z) % M)
+        x = rot32((x * x + y) % M)
+        return ((x * x + z) % M) >> 32
+
+    for seed in (0, 1, 11, 2 ** 40 + 7):
+        z = (seed + 0x9E3779B97F4A7C15) % M
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) % M
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) % M
+        key = (z ^ (z >> 31)) | 1
+        assert sa.key_from_seed(seed) == key
+        for pos, stream in ((0, 0), (5, 1), (59999, 2), (123456, 0)):
+            ctrs = sa.counters(pos, stream, 50)
+            got = sa.squares32(ctrs, key)
+            for v in (0, 1, 17, 49):
+                ctr = (pos << 34) | (stream << 32) | v
+                assert int(ctrs[v]) == ctr
+                assert int(got[v]) == squares(ctr, key)
+
+
 def test_gumbel_max_draws_follow_the_softmax():
     rng = np.random.default_rng(0)
     z = rng.standard_normal(12) * 1.5
