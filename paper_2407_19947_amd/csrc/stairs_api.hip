@@ -1213,10 +1213,12 @@ int stairs_encode(stairs_ctx* c, const int32_t* src, int32_t S) {
   if (!capacity_ok(c, 1 + c->k_max + 1)) return fail(c, STAIRS_ECAPACITY, "1 + k_max + 1 exceeds max_seq");
   c->prefilled = false;
   c->pending_k = -1;
-  // captured iterations hold the previous source length
+  // captured iterations hold the source length: they stay valid only for a source of the same length
   HIPCHK(c, hipStreamSynchronize(c->st));
-  for (auto& g : c->graphs) (void)hipGraphExecDestroy(g.exec);
-  c->graphs.clear();
+  if (S != c->S) {
+    for (auto& g : c->graphs) (void)hipGraphExecDestroy(g.exec);
+    c->graphs.clear();
+  }
   HIPCHK(c, hipMemsetAsync(c->counters, 0, kCounters * sizeof(int), c->st));
   HIPCHK(c, hipMemcpyAsync(c->src_tok, src, (size_t)S * sizeof(int), hipMemcpyHostToDevice, c->st));
   const int st4[kSlotState] = {1, 0, 0, 1};

@@ -84,6 +84,12 @@ def test_generate_equals_plain_greedy_and_graph_replay(monkeypatch):
             toks, st = s.generate(src, G, k)
             assert np.array_equal(toks, base), k
             assert st.iterations < G
+        # another source of the same length (captured iterations are reused), checked against a fresh context
+        src2 = src[::-1].copy()
+        same_len, _ = s.generate(src2, G, 3)
+        with pkg.StairsEncDec(t, d, k_max=8, max_src=256, max_seq=G + 16) as s3:
+            fresh2, _ = s3.generate(src2, G, 3)
+        assert np.array_equal(same_len, fresh2) and not np.array_equal(same_len, base)
         # another source of another length on the same context, then the first one again
         other, _ = s.generate(src[:77], G, 3)
         again, _ = s.generate(src, G, 3)

@@ -93,6 +93,11 @@ def test_sampled_errors_and_encoder_decoder_context():
         with pytest.raises(pkg.StairsError) as e:
             s.verify_sampled(2, 0.5, 1, logits=False)
         assert e.value.code == -3
+    with pkg.Stairs(target, draft, k_max=3, max_seq=64) as s:
+        s.reserve_batch(2)                                           # sampling takes one sequence per context
+        with pytest.raises(pkg.StairsError) as e:
+            s.generate_sampled(prompt, 8, 2, 0.5, 1)
+        assert e.value.code == -1
     we = si.scaled_encdec_workload("t5_tiny")
     t, d = si.make_encdec_pair(we)
     src = si.make_source(we)
