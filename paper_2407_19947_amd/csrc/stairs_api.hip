@@ -1128,6 +1128,9 @@ static int alloc_workspaces(stairs_ctx* c, const WsDims& w) {
       return bail(STAIRS_EHIP);
     }
   }
+  // every slot of the token array always holds a valid id: a diagnostic forward may run at positions the current
+  // sequence has not reached, and the embedding gather takes whatever id it finds there
+  if (hipMemsetAsync(c->tokens, 0, ((size_t)c->tok_cap + kMaxRows) * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
   if (hipMemsetAsync(c->state, 0, 2 * kSlotState * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
   if (hipMemsetAsync(c->counters, 0, kCounters * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
   c->h_pinned_ints = 2 + kMaxRows;
