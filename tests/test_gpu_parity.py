@@ -475,3 +475,26 @@ def test_shape_sweep_against_the_oracle(case):
     target, draft = si.make_pair(w)
     res = run_side_by_side(target, draft, si.make_prompt(w), G, k, np.float64, LOGIT_TOL_BF16)
     assert res["max_logit_err"] < 5e-3
+
+
+def test_long_generation_and_two_contexts_interleaved():
+    """700 tokens after a 300-token prompt (the attention grid grows from 3 to 8 chunks, so several captured
+    iterations are made and replayed) on two contexts used in turns: every result equals plain greedy decoding and
+    does not depend on what the other context did in between."""
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=2048),
+                           draft=dict(kind="prefix", n_layers=1), P=300, G=700)
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    other = si.make_prompt(w)[::-1].copy()
+    with pkg.Stairs(target, draft, k_max=5, max_seq=1100) as a, pkg.Stairs(target, draft, k_max=5, max_seq=1100) as b:
+        base, st0 = a.generate(prompt, 700, 0)
+        base_other, _ = b.generate(other, 700, 0)
+        assert st0.iterations == 700 and not np.array_equal(base, base_other)
+        # turn by turn: a decodes 350 tokens, b runs a whole generation, a continues
+        a.prefill(prompt)
+        first, _ = a.decode(350, 3)
+        got_other, _ = b.generate(other, 700, 5)
+        second, st = a.decode(350, 3)
+        assert np.array_equal(np.concatenate([first, second]), base)
+        assert np.array_equal(got_other, base_other)
+        assert st.iterations < 350

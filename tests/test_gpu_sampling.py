@@ -51,6 +51,14 @@ def test_bf16_pair_sampled(k, temp):
     assert res["draft_differs"] + res["final_differs"] + res["decision_differs"] <= 2
 
 
+def test_widest_sampled_stair_batch():
+    """k = 31: 32 stair rows, 31 assistant logits rows, 63 log-sum-exps."""
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=2048),
+                           draft=dict(kind="prefix", n_layers=1), P=24, G=66)
+    res = _run(w, 31, 0.05, 9, 66)
+    assert res["max_err"] < 5e-3 and max(res["n"]) > 0
+
+
 def test_sampled_generation_properties(monkeypatch):
     w = si.scaled_workload("cfg2_125m", target=dict(n_layers=3, d_model=256, n_heads=4, d_ffn=512, vocab=2048),
                            draft=dict(kind="prefix", n_layers=1), P=40, G=64)
