@@ -378,6 +378,13 @@ __device__ __forceinline__ void split_bf16x8(const float4& xa, const float4& xb,
   lo = make_uint4(lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16), lb[4] | (lb[5] << 16), lb[6] | (lb[7] << 16));
 }
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+// streaming load: the line is not kept in the caches on its way (weights are read once per forward)
+__device__ __forceinline__ uint4 ld_nt(const uint4* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 template <int CT, int NT, int ROLE, int SPW>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw, int KT, int NTILES,
                                                    const float* __restrict__ X, int ldx, int M,
@@ -410,7 +417,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
   if (unit_ok(0)) {
     const uint4* p = unit_ptr(0);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) wb[0][i] = p[i * 64];
+    for (int i = 0; i < 8; ++i) wb[0][i] = ld_nt(&p[i * 64]);
   }
 
   f32x4 sum[NT][CT];
@@ -488,7 +495,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
           if (unit_ok(u + 1)) {
             const uint4* p = unit_ptr(u + 1);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) wb[(u + 1) & 1][i] = p[i * 64];
+            for (int i = 0; i < 8; ++i) wb[(u + 1) & 1][i] = ld_nt(&p[i * 64]);
           }
         }
         if (ku < units && tile_ok) {
@@ -636,9 +643,9 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
     const uint4* p0 = (nu > 0) ? unit_ptr(0) : Wsw + (size_t)tile * min(kSliceUnits, units_total) * 8 * 64 + lane;
     const uint4* p1 = (nu > 1) ? unit_ptr(1) : p0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) wb0[i] = p0[i * 64];
+    for (int i = 0; i < 8; ++i) wb0[i] = ld_nt(&p0[i * 64]);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) wb1[i] = p1[i * 64];
+    for (int i = 0; i < 8; ++i) wb1[i] = ld_nt(&p1[i * 64]);
   }
   if (has_stats && wave < 2) {                             // wave-uniform
     float ss = 0.f;
@@ -719,14 +726,14 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
     if (u + 2 < nu) {
       const uint4* p = unit_ptr(u + 2);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) wb0[i] = p[i * 64];
+      for (int i = 0; i < 8; ++i) wb0[i] = ld_nt(&p[i * 64]);
     }
     if (u + 1 < nu) {
       mfma_unit(wb1, u + 1, acc);
       if (u + 3 < nu) {
         const uint4* p = unit_ptr(u + 3);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) wb1[i] = p[i * 64];
+        for (int i = 0; i < 8; ++i) wb1[i] = ld_nt(&p[i * 64]);
       }
     }
     const int m = lane & 15;
