@@ -47,6 +47,8 @@ struct Model {
   bool bf16 = false;
   int hd = 0, cap = 0;
   // encoder-decoder models: cfg describes the decoder (n_layers = decoder layers, rope_theta = 0: no rotation)
+  // matrices of one forward far beyond the 256 MB memory-side cache: read them with the streaming hint
+  bool stream_weights = false;
   bool encdec = false;
   int da = 0;                       // attention width n_heads * head_dim (decoder-only models: d_model)
   int max_src = 0, cap_src = 0;     // source positions the encoder-side buffers hold
@@ -189,6 +191,7 @@ const char* check_weights(const stairs_model_cfg* m, const stairs_weights* w) {
   return nullptr;
 }
 
+constexpr size_t kStreamHintBytes = 512u << 20;   // models streaming more than this per forward use the hint
 constexpr int kProbeEmptyPair = 100;
 constexpr int kProbeKernelEvents = 101;   // the gate/up launch records its own start / end events
 enum { KIND_EMB = 0, KIND_HEAD, KIND_NORM, KIND_QKV, KIND_WO, KIND_GU, KIND_DOWN };
@@ -281,6 +284,7 @@ int build_model(stairs_ctx* c, Model* m, const stairs_model_cfg* cfg, const stai
     one[0] = w->w_down[l];
     if ((rc = upload_matrix(c, m->bf16, one, 1, d, f, KIND_DOWN, m->hd, staging, &ly.wdown, &ly.wdown_p))) return rc;
   }
+  m->stream_weights = m->bf16 && ((size_t)cfg->n_layers * (4 * (size_t)d * d + 3 * (size_t)d * f) + (size_t)V * d) * 2 > kStreamHintBytes;
   m->kv_layer_bytes = (size_t)cfg->n_heads * m->cap * m->hd * m->esz();
   if ((rc = dev_alloc(c, &m->Kc, m->kv_layer_bytes * cfg->n_layers))) return rc;
   if ((rc = dev_alloc(c, &m->Vc, m->kv_layer_bytes * cfg->n_layers))) return rc;
@@ -416,6 +420,7 @@ int build_encdec_model(stairs_ctx* c, Model* m, const stairs_encdec_cfg* cfg, co
       (rc = upload_bias(c, w->dec_rel_bias, cfg->rel_buckets, cfg->rel_max_distance, H, m->cap, m->cap - 1, false,
                         &m->dec_bias)))
     return rc;
+  m->stream_weights = ((size_t)cfg->n_dec_layers * (8 * (size_t)d * a + 2 * (size_t)d * f) + (size_t)V * d) * 2 > kStreamHintBytes;
   m->kv_layer_bytes = (size_t)H * m->cap * m->hd * 2;
   m->kvx_layer_bytes = (size_t)H * m->cap_src * m->hd * 2;
   const size_t self_bytes = m->kv_layer_bytes * cfg->n_dec_layers, cross_bytes = m->kvx_layer_bytes * cfg->n_dec_layers;
@@ -486,6 +491,7 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     char* Vl = m->Vc + slot_off + l * m->kv_layer_bytes;
     GemmEpi e{};
     e.counters = c->counters;
+    e.stream_weights = m->stream_weights;
     e.rope_cs = c->rope_cs;
     e.pos = pos;
     e.Kc = reinterpret_cast<_Float16*>(Kl);
@@ -535,6 +541,7 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     const int r0 = M - logits_rows;
     GemmEpi e{};
     e.counters = c->counters;
+    e.stream_weights = m->stream_weights;
     e.out = logits_dst ? logits_dst : c->logits;
     e.hd = m->hd;
     launch_gemm(kRoleHead, b, m->lm_head, V, d, c->x + (size_t)r0 * d, d, logits_rows,
@@ -557,6 +564,7 @@ void launch_ed_ffn(stairs_ctx* c, const Model* m, const EdLayer& ly, float* x, f
   const RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
   GemmEpi e{};
   e.counters = c->counters;
+  e.stream_weights = m->stream_weights;
   e.hd = m->hd;
   e.out = c->h;
   e.act = kActRelu;
@@ -606,6 +614,7 @@ int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logit
     char* Vl = m->Vc + l * m->kv_layer_bytes;
     GemmEpi e{};
     e.counters = c->counters;
+    e.stream_weights = m->stream_weights;
     e.rope_cs = c->rope_cs;
     e.pos = pos;
     e.Kc = reinterpret_cast<_Float16*>(Kl);
@@ -639,6 +648,7 @@ int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logit
     const int r0 = M - logits_rows;
     GemmEpi e{};
     e.counters = c->counters;
+    e.stream_weights = m->stream_weights;
     e.out = logits_dst ? logits_dst : c->logits;
     e.hd = m->hd;
     launch_gemm(kRoleHead, 1, m->lm_head, V, d, c->x + (size_t)r0 * d, d, logits_rows,
@@ -666,6 +676,7 @@ int encode_model(stairs_ctx* c, Model* m) {
   auto epi_for = [&](int b, char* K, char* V, float* out) {
     GemmEpi e{};
     e.counters = c->counters;
+    e.stream_weights = m->stream_weights;
     e.rope_cs = c->rope_cs;
     e.pos = abs_pos(c, b);
     e.Kc = reinterpret_cast<_Float16*>(K);
@@ -1703,6 +1714,7 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
     RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
     GemmEpi e{};
     e.counters = dCnt;
+    e.stream_weights = wbytes > kStreamHintBytes / 4;   // exercised by the larger test matrices
     e.out = dY;
     e.hd = 64;
     launch_gemm(kRoleHead, b, b ? dWs : dW, N, K, dX, K, M, none, dP, e, st);
@@ -1800,6 +1812,7 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
       char* Vl = m->Vc + l * m->kv_layer_bytes;
       GemmEpi e{};
       e.counters = c->counters;
+      e.stream_weights = m->stream_weights;
       e.rope_cs = c->rope_cs;
       e.pos = tpos;
       e.Kc = reinterpret_cast<_Float16*>(Kl);

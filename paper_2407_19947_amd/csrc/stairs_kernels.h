@@ -96,6 +96,7 @@ struct GemmEpi {
   int cap, H, hd;
   size_t kv_slot_stride;    // elements between the caches of consecutive slots (several sequences), else unused
   int act;                  // Head role only: kActNone / kActRelu
+  int stream_weights;       // bf16: read the weights with the streaming hint (models far larger than the memory-side cache)
 };
 
 // ---- skinny GEMM + epilogue ---------------------------------------------------------------

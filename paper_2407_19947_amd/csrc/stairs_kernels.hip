@@ -379,13 +379,22 @@ __device__ __forceinline__ void split_bf16x8(const float4& xa, const float4& xb,
 }
 
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-// streaming load: the line is not kept in the caches on its way (weights are read once per forward)
+// streaming load: the line is not kept in the caches on its way
 __device__ __forceinline__ uint4 ld_nt(const uint4* p) {
   const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(v.x, v.y, v.z, v.w);
 }
+// One 8 KiB weight unit of a wave (8 loads of 1 KiB).  STREAM (a template argument: a run-time choice between the two
+// load forms cost the whole gain in the kernels' prologues): weights of a model far larger than the
+// 256 MB memory-side cache are read once per forward and gain from the streaming hint (a bare 2 GB read: 6.2 -> 7.05
+// TB/s); a model that about fits that cache is served from it forward after forward and must keep plain loads.
+template <bool STREAM>
+__device__ __forceinline__ void load_unit(const uint4* p, uint4 (&wb)[8]) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) wb[i] = STREAM ? ld_nt(&p[i * 64]) : p[i * 64];
+}
 
-template <int CT, int NT, int ROLE, int SPW>
+template <int CT, int NT, int ROLE, int SPW, bool STREAM>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw, int KT, int NTILES,
                                                    const float* __restrict__ X, int ldx, int M,
                                                    RowNorm nrm, int K, float* partial, int N, GemmEpi epi) {
@@ -416,8 +425,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
   // first weight unit goes out before anything else: it depends on nothing
   if (unit_ok(0)) {
     const uint4* p = unit_ptr(0);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) wb[0][i] = ld_nt(&p[i * 64]);
+    load_unit<STREAM>(p, wb[0]);
   }
 
   f32x4 sum[NT][CT];
@@ -494,8 +502,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
         if (u + 1 < SPW * NT * kSliceUnits) {
           if (unit_ok(u + 1)) {
             const uint4* p = unit_ptr(u + 1);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) wb[(u + 1) & 1][i] = ld_nt(&p[i * 64]);
+            load_unit<STREAM>(p, wb[(u + 1) & 1]);
           }
         }
         if (ku < units && tile_ok) {
@@ -572,7 +579,7 @@ __device__ __forceinline__ float lds_chunk_sum(const float* base, int stride, in
   return a;
 }
 
-template <int R, int ROLE, int NW, int GP>
+template <int R, int ROLE, int NW, int GP, bool STREAM>
 __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restrict__ Wsw, int NTILES,
                                                             const float* __restrict__ X, int ldx, RowNorm nrm,
                                                             int K, int N, GemmEpi epi) {
@@ -642,10 +649,8 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
   {
     const uint4* p0 = (nu > 0) ? unit_ptr(0) : Wsw + (size_t)tile * min(kSliceUnits, units_total) * 8 * 64 + lane;
     const uint4* p1 = (nu > 1) ? unit_ptr(1) : p0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) wb0[i] = ld_nt(&p0[i * 64]);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) wb1[i] = ld_nt(&p1[i * 64]);
+    load_unit<STREAM>(p0, wb0);
+    load_unit<STREAM>(p1, wb1);
   }
   if (has_stats && wave < 2) {                             // wave-uniform
     float ss = 0.f;
@@ -725,15 +730,13 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
     mfma_unit(wb0, u, acc);
     if (u + 2 < nu) {
       const uint4* p = unit_ptr(u + 2);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) wb0[i] = ld_nt(&p[i * 64]);
+      load_unit<STREAM>(p, wb0);
     }
     if (u + 1 < nu) {
       mfma_unit(wb1, u + 1, acc);
       if (u + 3 < nu) {
         const uint4* p = unit_ptr(u + 3);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) wb1[i] = ld_nt(&p[i * 64]);
+        load_unit<STREAM>(p, wb1);
       }
     }
     const int m = lane & 15;
@@ -901,8 +904,14 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
   const uint4* Wsw = static_cast<const uint4*>(W);
   if (const size_t rl = rows_path_lds(role, M, N, K)) {
 #define STAIRS_ROWS(r, role, nw, gp)                                                                                  \
-  launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp>, dim3(NTILES), dim3(64 * nw), rl, st, Wsw, NTILES, X, ldx, nrm, \
-                     K, N, epi)
+  do {                                                                                                                 \
+  if (epi.stream_weights)                                                                                            \
+    launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp, true>, dim3(NTILES), dim3(64 * nw), rl, st, Wsw, NTILES, X,    \
+                       ldx, nrm, K, N, epi);                                                                            \
+  else                                                                                                                 \
+    launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp, false>, dim3(NTILES), dim3(64 * nw), rl, st, Wsw, NTILES, X,   \
+                       ldx, nrm, K, N, epi);                                                                            \
+  } while (0)
 #define STAIRS_ROWS_ROLE(role, nw, gp)           \
   if (M <= 1) STAIRS_ROWS(1, role, nw, gp);      \
   else if (M == 2) STAIRS_ROWS(2, role, nw, gp); \
@@ -929,7 +938,14 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
   dim3 grid((NTILES + 4 * NT - 1) / (4 * NT), SG), block(256);
   const size_t lds = (size_t)16 * CT * 2 * 64 * sizeof(uint4);
 #define STAIRS_GEMM(ct, nt, role, spw) \
-  launch_gemm_kernel(k_gemm_bf16<ct, nt, role, spw>, grid, block, lds, st, Wsw, KT, NTILES, X, ldx, M, nrm, K, partial, N, epi)
+  do {                                                                                                                \
+    if (epi.stream_weights)                                                                                           \
+      launch_gemm_kernel(k_gemm_bf16<ct, nt, role, spw, true>, grid, block, lds, st, Wsw, KT, NTILES, X, ldx, M, nrm, K, \
+                         partial, N, epi);                                                                            \
+    else                                                                                                              \
+      launch_gemm_kernel(k_gemm_bf16<ct, nt, role, spw, false>, grid, block, lds, st, Wsw, KT, NTILES, X, ldx, M, nrm,   \
+                         K, partial, N, epi);                                                                         \
+  } while (0)
 #define STAIRS_GEMM_NT(ct, role, spw)             \
   if (NT == 1) STAIRS_GEMM(ct, 1, role, spw);     \
   else STAIRS_GEMM(ct, 2, role, spw)
@@ -2196,16 +2212,20 @@ hipError_t configure_kernels() {
     const hipError_t r = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (r != hipSuccess) e = r;
   };
-#define STAIRS_OPTIN(r)                                                                        \
-  optin((const void*)k_gemm_bf16_rows<r, kRoleQKV, 4, 2>, kRowsPathMaxLds);                    \
-  optin((const void*)k_gemm_bf16_rows<r, kRoleGateUp, 4, 2>, kRowsPathMaxLds);                 \
-  optin((const void*)k_gemm_bf16_rows<r, kRoleHead, 4, 2>, kRowsPathMaxLds);                   \
-  optin((const void*)k_gemm_bf16_rows<r, kRoleWo, 8, 1>, kRowsPathMaxLdsWide);                 \
-  optin((const void*)k_gemm_bf16_rows<r, kRoleDown, 8, 3>, kRowsPathMaxLdsWide)
+#define STAIRS_OPTIN2(r, st)                                                                       \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleQKV, 4, 2, st>, kRowsPathMaxLds);                    \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleGateUp, 4, 2, st>, kRowsPathMaxLds);                 \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleHead, 4, 2, st>, kRowsPathMaxLds);                   \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleWo, 8, 1, st>, kRowsPathMaxLdsWide);                 \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleDown, 8, 3, st>, kRowsPathMaxLdsWide)
+#define STAIRS_OPTIN(r)    \
+  STAIRS_OPTIN2(r, true);  \
+  STAIRS_OPTIN2(r, false)
   STAIRS_OPTIN(1);
   STAIRS_OPTIN(2);
   STAIRS_OPTIN(3);
   STAIRS_OPTIN(4);
+#undef STAIRS_OPTIN2
 #undef STAIRS_OPTIN
   // the stand-alone attention merge keeps a table of all chunks in LDS: large for long contexts (the fused
   // merge runs for at most kAttnFusedMaxChunks chunks and stays small)
