@@ -251,8 +251,10 @@ __device__ __forceinline__ void qkv_pair(float a, float b, int m, int col, int d
 }
 
 // Epilogue of one column group [c0, c0+W) for all M rows, run by the 256 threads of one work-group.
+// rs: the rows' 1/rms in LDS when the GEMM's input is normalised (the X fragments carry x * gain only), else null.
 template <int ROLE, int W, bool PAIRS>
-__device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M, int N, int c0, const GemmEpi& epi) {
+__device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M, int N, int c0, const GemmEpi& epi,
+                                              const float* rs) {
   const int tid = threadIdx.x;
   const size_t stride = (size_t)M * N;
   if (ROLE == kRoleHead) {
@@ -261,6 +263,7 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
       const int m = idx / PR, col = c0 + (idx - m * PR) * 4;
       if (col < N) {
         float4 a = slice_sum4<PAIRS>(partial, S, stride, (size_t)m * N + col);
+        if (rs) { const float r = rs[m]; a.x *= r; a.y *= r; a.z *= r; a.w *= r; }
         if (epi.act == kActRelu) a = make_float4(fmaxf(a.x, 0.f), fmaxf(a.y, 0.f), fmaxf(a.z, 0.f), fmaxf(a.w, 0.f));
         *reinterpret_cast<float4*>(epi.out + (size_t)m * N + col) = a;
       }
@@ -274,6 +277,7 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
       float ss = 0.f;
       if (idx < total && col < N) {
         float4 a = slice_sum4<PAIRS>(partial, S, stride, (size_t)m * N + col);
+        if (rs) { const float q = rs[m]; a.x *= q; a.y *= q; a.z *= q; a.w *= q; }
         float4* xp = reinterpret_cast<float4*>(epi.out + (size_t)m * N + col);
         const float4 r = *xp;
         a.x += r.x; a.y += r.y; a.z += r.z; a.w += r.w;
@@ -292,8 +296,13 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
       const int m = idx / PR, r = idx - m * PR;
       const int gcol = c0 + 16 * (r >> 1) + 4 * (r & 1);
       if (gcol < N) {
-        const float4 g = slice_sum4<PAIRS>(partial, S, stride, (size_t)m * N + gcol);
-        const float4 u = slice_sum4<PAIRS>(partial, S, stride, (size_t)m * N + gcol + 8);
+        float4 g = slice_sum4<PAIRS>(partial, S, stride, (size_t)m * N + gcol);
+        float4 u = slice_sum4<PAIRS>(partial, S, stride, (size_t)m * N + gcol + 8);
+        if (rs) {
+          const float q = rs[m];
+          g.x *= q; g.y *= q; g.z *= q; g.w *= q;
+          u.x *= q; u.y *= q; u.z *= q; u.w *= q;
+        }
         const float4 o = make_float4(swiglu(g.x, u.x), swiglu(g.y, u.y), swiglu(g.z, u.z), swiglu(g.w, u.w));
         *reinterpret_cast<float4*>(epi.out + (size_t)m * f + (gcol >> 4) * 8 + (gcol & 7)) = o;
       }
@@ -304,8 +313,9 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
       const int m = idx / PR, r = idx - m * PR;
       const int col = c0 + 16 * (r >> 3) + (r & 7);
       if (col < N) {
-        const float a = slice_sum<PAIRS>(partial, S, stride, (size_t)m * N + col);
-        const float b = slice_sum<PAIRS>(partial, S, stride, (size_t)m * N + col + 8);
+        float a = slice_sum<PAIRS>(partial, S, stride, (size_t)m * N + col);
+        float b = slice_sum<PAIRS>(partial, S, stride, (size_t)m * N + col + 8);
+        if (rs) { a *= rs[m]; b *= rs[m]; }
         qkv_pair(a, b, m, col, N / 3, epi);
       }
     }
@@ -360,13 +370,15 @@ void launch_rstd(RowNorm nrm, int M, int K, float* rstd, hipStream_t st) {
   hipLaunchKernelGGL(k_rstd, dim3(1), dim3(256), 0, st, nrm, M, K, rstd);
 }
 
-// 8 consecutive x of one row -> (x * rstd * gain) -> bf16 high part and the bf16 of the remainder
+// 8 consecutive x of one row -> (x * gain) -> bf16 high part and the bf16 of the remainder
 __device__ __forceinline__ void split_bf16x8(const float4& xa, const float4& xb, const float4& g0, const float4& g1,
-                                             float r, bool scale, uint4& hi, uint4& lo) {
+                                             bool scale, uint4& hi, uint4& lo) {
+  // the row's 1/rms is not applied here: it is a scalar per row and multiplies the finished sums in the epilogue, so
+  // the conversion does not wait for the row statistics
   float v[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
   if (scale) {
-    v[0] = v[0] * r * g0.x; v[1] = v[1] * r * g0.y; v[2] = v[2] * r * g0.z; v[3] = v[3] * r * g0.w;
-    v[4] = v[4] * r * g1.x; v[5] = v[5] * r * g1.y; v[6] = v[6] * r * g1.z; v[7] = v[7] * r * g1.w;
+    v[0] = v[0] * g0.x; v[1] = v[1] * g0.y; v[2] = v[2] * g0.z; v[3] = v[3] * g0.w;
+    v[4] = v[4] * g1.x; v[5] = v[5] * g1.y; v[6] = v[6] * g1.z; v[7] = v[7] * g1.w;
   }
   uint32_t hb[8], lb[8];
 #pragma unroll
@@ -466,20 +478,19 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
       } else {
         rows_rstd<2 * CT>(nrm, M, K, s_rstd);
       }
-      __syncthreads();
+      // read by the epilogue only, barriers away
     }
 
-    // fp32 -> (x * rstd * gain) -> bf16 hi + lo, stored in B-fragment order
+    // fp32 -> (x * gain) -> bf16 hi + lo, stored in B-fragment order
     if (units > 0) {
 #pragma unroll
       for (int it = 0; it < ITEMS; ++it) {
         const int w = tid + 256 * it;                       // w < 16*CT*kgs is uniform per wave
         const int m = min(w / kgs, 16 * CT - 1), kg = w - (w / kgs) * kgs;
         if (w < 16 * CT * kgs) {
-          const float r = (nrm.gain && nrm.ssq_part && m < M) ? s_rstd[m] : 1.0f;
           const bool scale = nrm.gain && m < M;
           uint4 hi, lo;
-          split_bf16x8(xa[it], xb[it], g0, g1, r, scale, hi, lo);
+          split_bf16x8(xa[it], xb[it], g0, g1, scale, hi, lo);
           const int kt = kg >> 2, g = kg & 3, ct = m >> 4, jj = m & 15;
           const int base = ((kt * CT + ct) * 2) * 64 + g * 16 + jj;
           lds[base] = hi;
@@ -551,7 +562,8 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
 
   // split-K hand-off: the partial sums are out, take a ticket; the last arrival finishes the group
   if (!last_arrival(&epi.counters[blockIdx.x], SG, &s_last)) return;
-  gemm_epilogue<ROLE, 64 * NT, SPW == 1>(partial, SG, M, N, blockIdx.x * 64 * NT, epi);
+  gemm_epilogue<ROLE, 64 * NT, SPW == 1>(partial, SG, M, N, blockIdx.x * 64 * NT, epi,
+                                         (nrm.gain && nrm.ssq_part) ? s_rstd : nullptr);
   if (tid == 0) epi.counters[blockIdx.x] = 0;   // ready for the next launch on this stream
 }
 
@@ -632,8 +644,8 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
     }
   }
   // row statistics: half a wave per row (R <= 4 rows: waves 0 and 1).  The first 256 partials of the row are
-  // requested here, without conditions (indices clamped, values masked later), and added up after the weights
-  // have been requested, in the order rows_rstd uses.
+  // requested here, without conditions (indices clamped, values masked later), and added up after the conversion of
+  // the X block, in the order rows_rstd uses: the 1/rms multiplies the finished sums in the epilogue.
   const bool has_stats = nrm.gain && nrm.ssq_part;
   const int st_row = 2 * wave + (lane >> 5), st_pl = lane & 31;
   float sv[8];
@@ -652,25 +664,6 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
     load_unit<STREAM>(p0, wb0);
     load_unit<STREAM>(p1, wb1);
   }
-  if (has_stats && wave < 2) {                             // wave-uniform
-    float ss = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) ss += (st_pl + 32 * i < nrm.ssq_n) ? sv[i] : 0.f;
-    if (st_row < R) {
-      for (int p0 = st_pl + 256; p0 < nrm.ssq_n; p0 += 256) {
-        float v[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = (p0 + 32 * i < nrm.ssq_n) ? nrm.ssq_part[st_row * nrm.ssq_n + p0 + 32 * i] : 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) ss += v[i];
-      }
-    }
-#pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
-    if (st_pl == 0 && st_row < R) s_rstd[st_row] = 1.0f / sqrtf(ss / (float)K + nrm.eps);
-  }
-  __syncthreads();                                         // s_rstd
-
   uint4* xhi = lds;
   uint4* xlo = lds + KG * R;
   float* csum = reinterpret_cast<float*>(lds + 2 * KG * R); // [chunk][R][16]
@@ -682,9 +675,8 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
     if (kg < KG) {
 #pragma unroll
       for (int m = 0; m < R; ++m) {
-        const float r = (scale && nrm.ssq_part) ? s_rstd[m] : 1.0f;
         uint4 hi, lo;
-        split_bf16x8(xa[j][m], xb[j][m], ga[j], gb[j], r, scale, hi, lo);
+        split_bf16x8(xa[j][m], xb[j][m], ga[j], gb[j], scale, hi, lo);
         xhi[kg * R + m] = hi;
         xlo[kg * R + m] = lo;
       }
@@ -701,12 +693,28 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
 #pragma unroll
     for (int m = 0; m < R; ++m) {
       const float4* xp = reinterpret_cast<const float4*>(X + (size_t)m * ldx + kg * 8);
-      const float r = (scale && nrm.ssq_part) ? s_rstd[m] : 1.0f;
       uint4 hi, lo;
-      split_bf16x8(xp[0], xp[1], g0, g1, r, scale, hi, lo);
+      split_bf16x8(xp[0], xp[1], g0, g1, scale, hi, lo);
       xhi[kg * R + m] = hi;
       xlo[kg * R + m] = lo;
     }
+  }
+  if (has_stats && wave < 2) {                             // wave-uniform
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ss += (st_pl + 32 * i < nrm.ssq_n) ? sv[i] : 0.f;
+    if (st_row < R) {
+      for (int p0 = st_pl + 256; p0 < nrm.ssq_n; p0 += 256) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (p0 + 32 * i < nrm.ssq_n) ? nrm.ssq_part[st_row * nrm.ssq_n + p0 + 32 * i] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ss += v[i];
+      }
+    }
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    if (st_pl == 0 && st_row < R) s_rstd[st_row] = 1.0f / sqrtf(ss / (float)K + nrm.eps);
   }
   __syncthreads();
 
@@ -753,6 +761,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
     if (tid < R * 16) {
       const int m = tid >> 4, n = tid & 15;
       float a = lds_chunk_sum(csum + (m << 4) + n, R * 16, nchunks);
+      if (has_stats) a *= s_rstd[m];
       float* xp = epi.out + (size_t)m * N + tile * 16 + n;
       a += *xp;
       *xp = a;
@@ -770,8 +779,12 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
   // a thread takes row m, columns j and j+8 of the tile
   if (tid < R * 8) {
     const int m = tid >> 3, j = tid & 7;
-    const float a = lds_chunk_sum(csum + (m << 4) + j, R * 16, nchunks);
-    const float b = lds_chunk_sum(csum + (m << 4) + j + 8, R * 16, nchunks);
+    float a = lds_chunk_sum(csum + (m << 4) + j, R * 16, nchunks);
+    float b = lds_chunk_sum(csum + (m << 4) + j + 8, R * 16, nchunks);
+    if (has_stats) {
+      a *= s_rstd[m];
+      b *= s_rstd[m];
+    }
     const int col = tile * 16 + j;
     if (ROLE == kRoleHead) {
       const bool relu = epi.act == kActRelu;
