@@ -1316,11 +1316,13 @@ __device__ __forceinline__ void split_half8(const float* v, f16x8& hi, f16x8& lo
 }
 
 // Merge of the chunk partials of one head (one slot): out[m] = sum_c w_c o_c / sum_c w_c l_c with w_c = exp(max_c - max).
-// Step A: all (max, sum) pairs of all rows go to LDS in one round trip, then the row maxima.  Step B, up to kMergeCB
-// chunks: one thread per (row, 4 adjacent dims) adds its chunks up in chunk order, all loads in flight together.
+// Step A: all (max, sum) pairs of all rows go to LDS in one round trip, then the row maxima and, in place of the chunk
+// maxima, the weights w_c (one exp per row and chunk; formed per thread they made up most of the merge's time).
+// Step B, up to kMergeCB chunks: one thread per (row, 4 adjacent dims) adds its chunks up in chunk order, all loads in
+// flight together.
 // More chunks: groups of kMergeCB chunks are summed by different threads in parallel (each as above, from zero) and the
 // group sums added in group order; the grouping depends only on the row's own position.  Dynamic LDS:
-// [M][nch_lds][2] pairs, [kMaxRows] maxima, [rows_per_pass][HD/4][groups][5] group sums.
+// [M][nch_lds][2] pairs (weight, sum), [kMaxRows] unused, [rows_per_pass][HD/4][groups][5] group sums.
 constexpr int kMergeCB = 20;
 template <int HD>
 __device__ __forceinline__ void attn_merge(const float* part_o, const float* part_ml, int H, int h, int M, int pos0, int step,
@@ -1328,8 +1330,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
                                            float* s_ml) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nch_max = (kv_len > 0) ? (kv_len - 1) / kAttnChunk + 1 : 0;
-  float* s_gmax = s_ml + (size_t)M * nch_lds * 2;
-  float* grp = s_gmax + kMaxRows;
+  float* grp = s_ml + (size_t)M * nch_lds * 2 + kMaxRows;   // (kMaxRows floats after the table stay unused)
   for (int idx = tid; idx < M * nch_max; idx += 256) {
     const int m = idx / nch_max, cc = idx - m * nch_max;
     const float2 ml = ld_dev2(&part_ml[(((size_t)m * H + h) * nchunk_cap + cc) * 2]);
@@ -1343,14 +1344,19 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
     float g = -INFINITY;
     for (int cc = lane; cc < nch; cc += 64) g = fmaxf(g, s_ml[((size_t)m * nch_lds + cc) * 2]);
     g = wave_max(g);
-    if (lane == 0) s_gmax[m] = g;
+    // the chunk weights, once per (row, chunk) instead of once per thread that uses them: each replaces its chunk's
+    // maximum in the table (the lane that read the slot writes it)
+    for (int cc = lane; cc < nch; cc += 64) {
+      const float mc = s_ml[((size_t)m * nch_lds + cc) * 2];
+      s_ml[((size_t)m * nch_lds + cc) * 2] = (mc == -INFINITY) ? 0.f : expf(mc - g);
+    }
   }
   __syncthreads();
   constexpr int QPR = HD / 4;                         // threads per row
   constexpr int CB = kMergeCB;
   const int G = (nch_max + CB - 1) / CB;
   // sum of the chunks [c0, c1) of row m, dims e..e+3, weighted; all loads of the (at most CB) chunks together
-  auto group_sum = [&](int m, int e, int c0, int c1, float gmax, float4& num, float& den) {
+  auto group_sum = [&](int m, int e, int c0, int c1, float4& num, float& den) {
     const float* mlr = s_ml + (size_t)m * nch_lds * 2;
     const float* src = part_o + ((size_t)m * H + h) * nchunk_cap * HD + e;
     float2 va[CB], vb[CB];
@@ -1363,8 +1369,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
 #pragma unroll
     for (int i = 0; i < CB; ++i) {
       if (c0 + i < c1) {
-        const float mc = mlr[(c0 + i) * 2];
-        const float w = (mc == -INFINITY) ? 0.f : expf(mc - gmax);
+        const float w = mlr[(c0 + i) * 2];
         num.x = fmaf(w, va[i].x, num.x); num.y = fmaf(w, va[i].y, num.y);
         num.z = fmaf(w, vb[i].x, num.z); num.w = fmaf(w, vb[i].y, num.w);
         den = fmaf(w, mlr[(c0 + i) * 2 + 1], den);
@@ -1379,7 +1384,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
       if (p >= 0) {
         float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
         float den = 0.f;
-        group_sum(m, e, 0, p / kAttnChunk + 1, s_gmax[m], num, den);
+        group_sum(m, e, 0, p / kAttnChunk + 1, num, den);
         res = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
       }
       *reinterpret_cast<float4*>(out + (size_t)m * d + h * HD + e) = res;
@@ -1396,7 +1401,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
       float den = 0.f;
       if (p >= 0) {
         const int nch = p / kAttnChunk + 1;
-        if (g * CB < nch) group_sum(m, e, g * CB, min(nch, (g + 1) * CB), s_gmax[m], num, den);
+        if (g * CB < nch) group_sum(m, e, g * CB, min(nch, (g + 1) * CB), num, den);
       }
       float* o = grp + (size_t)idx * 5;
       o[0] = num.x; o[1] = num.y; o[2] = num.z; o[3] = num.w; o[4] = den;
