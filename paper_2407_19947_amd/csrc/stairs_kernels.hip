@@ -1567,13 +1567,16 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
     __syncthreads();
     float mc = fmaxf(fmaxf(s_m[0][j], s_m[1][j]), fmaxf(s_m[2][j], s_m[3][j]));
     const float fw = (mw == -INFINITY) ? 0.f : expf(mw - mc);
+    if (qi < M) {                                    // rows past the last one are never read back
 #pragma unroll
-    for (int et = 0; et < ET; ++et) {
-      float4 o = make_float4(oacc[et][0] * fw, oacc[et][1] * fw, oacc[et][2] * fw, oacc[et][3] * fw);
-      *reinterpret_cast<float4*>(&s_o[wave][j][et * 16 + g * 4]) = o;
+      for (int et = 0; et < ET; ++et) {
+        float4 o = make_float4(oacc[et][0] * fw, oacc[et][1] * fw, oacc[et][2] * fw, oacc[et][3] * fw);
+        *reinterpret_cast<float4*>(&s_o[wave][j][et * 16 + g * 4]) = o;
+      }
     }
     __syncthreads();
-    for (int idx = tid; idx < 16 * HD / 2; idx += 256) {
+    const int rows_here = min(16, M - ct * 16);      // (<= 0 for a second tile no row falls into)
+    for (int idx = tid; idx < rows_here * (HD / 2); idx += 256) {
       const int jj = idx / (HD / 2), e = (idx - jj * (HD / 2)) * 2;
       const int m = ct * 16 + jj;
       if (m < M) {
