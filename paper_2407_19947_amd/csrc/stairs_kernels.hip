@@ -1558,21 +1558,18 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
         oacc[et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pl, oacc[et], 0, 0, 0);
       }
     }
-    // merge the four waves (wave order)
+    // merge the four waves (wave order): every wave leaves its maximum, its sum and its output rows as they are; the
+    // threads that add the four outputs up scale them by exp(max_w - max) on the way (product rounded, then added)
     if (ct > 0) __syncthreads();                     // LDS of the previous query tile has been read
     if (g == 0) {
       s_m[wave][j] = mw;
       s_l[wave][j] = lw;
     }
-    __syncthreads();
-    float mc = fmaxf(fmaxf(s_m[0][j], s_m[1][j]), fmaxf(s_m[2][j], s_m[3][j]));
-    const float fw = (mw == -INFINITY) ? 0.f : expf(mw - mc);
     if (qi < M) {                                    // rows past the last one are never read back
 #pragma unroll
-      for (int et = 0; et < ET; ++et) {
-        float4 o = make_float4(oacc[et][0] * fw, oacc[et][1] * fw, oacc[et][2] * fw, oacc[et][3] * fw);
-        *reinterpret_cast<float4*>(&s_o[wave][j][et * 16 + g * 4]) = o;
-      }
+      for (int et = 0; et < ET; ++et)
+        *reinterpret_cast<float4*>(&s_o[wave][j][et * 16 + g * 4]) =
+            make_float4(oacc[et][0], oacc[et][1], oacc[et][2], oacc[et][3]);
     }
     __syncthreads();
     const int rows_here = min(16, M - ct * 16);      // (<= 0 for a second tile no row falls into)
@@ -1580,18 +1577,22 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
       const int jj = idx / (HD / 2), e = (idx - jj * (HD / 2)) * 2;
       const int m = ct * 16 + jj;
       if (m < M) {
-        const float o0 = ((s_o[0][jj][e] + s_o[1][jj][e]) + s_o[2][jj][e]) + s_o[3][jj][e];
-        const float o1 = ((s_o[0][jj][e + 1] + s_o[1][jj][e + 1]) + s_o[2][jj][e + 1]) + s_o[3][jj][e + 1];
+        const float m0 = s_m[0][jj], m1 = s_m[1][jj], m2 = s_m[2][jj], m3 = s_m[3][jj];
+        const float mcc = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+        const float f0 = (m0 == -INFINITY) ? 0.f : expf(m0 - mcc), f1 = (m1 == -INFINITY) ? 0.f : expf(m1 - mcc);
+        const float f2 = (m2 == -INFINITY) ? 0.f : expf(m2 - mcc), f3 = (m3 == -INFINITY) ? 0.f : expf(m3 - mcc);
+        const float2 a0 = *reinterpret_cast<const float2*>(&s_o[0][jj][e]), a1 = *reinterpret_cast<const float2*>(&s_o[1][jj][e]);
+        const float2 a2 = *reinterpret_cast<const float2*>(&s_o[2][jj][e]), a3 = *reinterpret_cast<const float2*>(&s_o[3][jj][e]);
+        const float o0 = __fadd_rn(__fadd_rn(__fadd_rn(__fmul_rn(a0.x, f0), __fmul_rn(a1.x, f1)), __fmul_rn(a2.x, f2)), __fmul_rn(a3.x, f3));
+        const float o1 = __fadd_rn(__fadd_rn(__fadd_rn(__fmul_rn(a0.y, f0), __fmul_rn(a1.y, f1)), __fmul_rn(a2.y, f2)), __fmul_rn(a3.y, f3));
         if (single) {
           float2 res = make_float2(0.f, 0.f);
           if (pos0 + m * step >= 0) {
-            const float m0 = s_m[0][jj], m1 = s_m[1][jj], m2 = s_m[2][jj], m3 = s_m[3][jj];
-            const float mcc = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
             float lc = 0.f;
-            if (m0 != -INFINITY) lc += expf(m0 - mcc) * s_l[0][jj];
-            if (m1 != -INFINITY) lc += expf(m1 - mcc) * s_l[1][jj];
-            if (m2 != -INFINITY) lc += expf(m2 - mcc) * s_l[2][jj];
-            if (m3 != -INFINITY) lc += expf(m3 - mcc) * s_l[3][jj];
+            if (m0 != -INFINITY) lc += f0 * s_l[0][jj];
+            if (m1 != -INFINITY) lc += f1 * s_l[1][jj];
+            if (m2 != -INFINITY) lc += f2 * s_l[2][jj];
+            if (m3 != -INFINITY) lc += f3 * s_l[3][jj];
             res = make_float2(o0 / lc, o1 / lc);
           }
           *reinterpret_cast<float2*>(out + (size_t)m * d + h * HD + e) = res;
