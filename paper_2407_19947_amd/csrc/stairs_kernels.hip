@@ -26,6 +26,19 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float x) {
   return u >> 16;
 }
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+// Two floats -> a packed pair of bf16 (a in the low half), round to nearest even, by the conversion instruction of
+// gfx950 (one instruction for the pair; same bits as bf16_bits_rne for every value that is not a NaN), and the split
+// of the pair into that high part and the bf16 of the remainders.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_pack2_rne(float a, float b) {
+  const f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+__device__ __forceinline__ void bf16_split2(float a, float b, uint32_t& hi, uint32_t& lo) {
+  hi = bf16_pack2_rne(a, b);
+  lo = bf16_pack2_rne(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
+}
 
 __device__ __forceinline__ float load_kv(const float* p) { return *p; }
 __device__ __forceinline__ float load_kv(const uint16_t* p) { return bf16_bits_to_float(*p); }
@@ -380,14 +393,10 @@ __device__ __forceinline__ void split_bf16x8(const float4& xa, const float4& xb,
     v[0] = v[0] * g0.x; v[1] = v[1] * g0.y; v[2] = v[2] * g0.z; v[3] = v[3] * g0.w;
     v[4] = v[4] * g1.x; v[5] = v[5] * g1.y; v[6] = v[6] * g1.z; v[7] = v[7] * g1.w;
   }
-  uint32_t hb[8], lb[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    hb[e] = bf16_bits_rne(v[e]);
-    lb[e] = bf16_bits_rne(v[e] - bf16_bits_to_float(hb[e]));
-  }
-  hi = make_uint4(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16), hb[4] | (hb[5] << 16), hb[6] | (hb[7] << 16));
-  lo = make_uint4(lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16), lb[4] | (lb[5] << 16), lb[6] | (lb[7] << 16));
+  bf16_split2(v[0], v[1], hi.x, lo.x);
+  bf16_split2(v[2], v[3], hi.y, lo.y);
+  bf16_split2(v[4], v[5], hi.z, lo.z);
+  bf16_split2(v[6], v[7], hi.w, lo.w);
 }
 
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
@@ -2130,14 +2139,11 @@ __global__ __launch_bounds__(256) void k_pf_norm_split(const float* __restrict__
       const float4 g = *reinterpret_cast<const float4*>(gain + c);
       e[0] = e[0] * rstd * g.x; e[1] = e[1] * rstd * g.y; e[2] = e[2] * rstd * g.z; e[3] = e[3] * rstd * g.w;
     }
-    uint32_t hb[4], lb[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      hb[i] = bf16_bits_rne(e[i]);
-      lb[i] = bf16_bits_rne(e[i] - bf16_bits_to_float(hb[i]));
-    }
-    *reinterpret_cast<uint2*>(hi + (size_t)r * d + c) = make_uint2(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16));
-    *reinterpret_cast<uint2*>(lo + (size_t)r * d + c) = make_uint2(lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16));
+    uint2 h2, l2;
+    bf16_split2(e[0], e[1], h2.x, l2.x);
+    bf16_split2(e[2], e[3], h2.y, l2.y);
+    *reinterpret_cast<uint2*>(hi + (size_t)r * d + c) = h2;
+    *reinterpret_cast<uint2*>(lo + (size_t)r * d + c) = l2;
   }
 }
 void launch_pf_norm_split(const float* x, const float* gain, float eps, int R, int d, uint16_t* hi, uint16_t* lo, hipStream_t st) {
@@ -2203,14 +2209,11 @@ __global__ __launch_bounds__(256) void k_pf_swiglu_split(const float* __restrict
   const float4 g = *reinterpret_cast<const float4*>(y + (size_t)r * 2 * f + c);
   const float4 u = *reinterpret_cast<const float4*>(y + (size_t)r * 2 * f + f + c);
   const float e[4] = {swiglu(g.x, u.x), swiglu(g.y, u.y), swiglu(g.z, u.z), swiglu(g.w, u.w)};
-  uint32_t hb[4], lb[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    hb[i] = bf16_bits_rne(e[i]);
-    lb[i] = bf16_bits_rne(e[i] - bf16_bits_to_float(hb[i]));
-  }
-  *reinterpret_cast<uint2*>(hi + (size_t)r * f + c) = make_uint2(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16));
-  *reinterpret_cast<uint2*>(lo + (size_t)r * f + c) = make_uint2(lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16));
+  uint2 h2, l2;
+  bf16_split2(e[0], e[1], h2.x, l2.x);
+  bf16_split2(e[2], e[3], h2.y, l2.y);
+  *reinterpret_cast<uint2*>(hi + (size_t)r * f + c) = h2;
+  *reinterpret_cast<uint2*>(lo + (size_t)r * f + c) = l2;
 }
 void launch_pf_swiglu_split(const float* y, int R, int f, uint16_t* hi, uint16_t* lo, hipStream_t st) {
   hipLaunchKernelGGL(k_pf_swiglu_split, dim3((f + 1023) / 1024, R), dim3(256), 0, st, y, f, hi, lo);
