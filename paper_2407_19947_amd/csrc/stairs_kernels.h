@@ -43,8 +43,9 @@ __device__ __forceinline__ int pos_of(const PosRef& p, int r) {
 }
 #endif
 
-// Row normalisation folded into a GEMM prologue: x[m][k] * gain[k] * rstd[m] with
+// Row normalisation folded into a GEMM: the input is x[m][k] * gain[k] * rstd[m] with
 // rstd[m] = 1/sqrt(sum_p ssq_part[m*ssq_n + p] / K + eps).  gain == nullptr: no scaling at all.
+// (bf16 kernels: the gain goes into the activation fragments, rstd[m] multiplies the row's finished sums.)
 struct RowNorm {
   const float* gain;
   const float* ssq_part;
