@@ -73,6 +73,27 @@ def test_both_bf16_gemm_kernels_give_the_same_bits(K):
     assert np.array_equal(pkg.stairs_gemm_host(W, X[7:10]), wide[7:10])
 
 
+@pytest.mark.parametrize("M", [1, 3, 5, 17])
+def test_activation_split_keeps_sixteen_bits(M):
+    """The bf16 kernels carry an activation as a bf16 high part plus the bf16 of the remainder.  Against an identity
+    matrix the product returns that pair's sum: exact for values of at most 16 significant bits (ties of the first
+    rounding, both signs, a subnormal and a large value among them), within 2^-17 relative otherwise.  A dropped low
+    part or a rounding that is not to nearest shows as an error of 2^-9."""
+    print(f"activation split M={M}", flush=True)
+    K = 256
+    W = si.bf16_round(np.eye(K, dtype=np.float32))
+    rng = np.random.default_rng([11, M])
+    X = rng.standard_normal((M, K), dtype=np.float32) * np.float32(3.0)
+    exact = X.copy()
+    exact.view(np.uint32)[...] &= np.uint32(0xFFFFFF00)          # 16 significant bits
+    special = np.array([1 + 2.0 ** -8, -(1 + 2.0 ** -8), 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -7 + 2.0 ** -15, 2.0 ** -130,
+                        -3.0 * 2.0 ** 100, 0.0, 255.5], np.float32)
+    exact[0, :special.size] = special
+    assert np.array_equal(pkg.stairs_gemm_host(W, exact), exact)
+    Y = pkg.stairs_gemm_host(W, X)
+    assert np.all(np.abs(Y.astype(np.float64) - X) <= np.abs(X).astype(np.float64) * 2.0 ** -17)
+
+
 @pytest.mark.parametrize("name", ["cfg1_tiny_fp32", "cfg2_125m"])
 def test_timing_probes_run_on_both_dtypes(name):
     """Every mode of stairs_time_kernel returns a positive duration and the bytes it states, on an fp32 and a bf16
