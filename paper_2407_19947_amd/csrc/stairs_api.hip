@@ -87,7 +87,6 @@ struct stairs_ctx {
   float *x = nullptr, *ssq = nullptr, *q_rot = nullptr, *attn_out = nullptr, *h = nullptr, *logits = nullptr;
   float *partial = nullptr, *part_o = nullptr, *part_ml = nullptr;
   float2* rope_cs = nullptr;
-  float* rstd = nullptr;       // [kMaxRows] row statistics formed once per GEMM (forwards of more than 16 rows)
   // block prefill (bf16 models, env STAIRS_NO_BLOCK_PREFILL=1 turns it off): BLAS handle and [kPfRows, .] workspaces
   bool block_prefill = false;
   rocblas_handle blas = nullptr;
@@ -484,7 +483,7 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
   launch_embed(m->tok_emb, b, c->tokens + (pos.rps ? 0 : (size_t)slot * c->tok_stride), pos.rps ? c->tok_stride : 0, pos, M, d,
                c->x, c->ssq, m->hd, g.rope_theta, c->rope_cs, st);
   SYNCPOINT();
-  const RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
+  const RowNorm none{nullptr, nullptr, 0, 0.f};
   for (int l = 0; l < g.n_layers; ++l) {
     const Layer& ly = m->layers[l];
     char* Kl = m->Kc + slot_off + l * m->kv_layer_bytes;
@@ -504,12 +503,7 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     e.kv_slot_stride = slot_bytes / m->esz();
     e.ssq_out = c->ssq;
     e.out = c->q_rot;
-    // from 17 rows on the row statistics are formed once per GEMM by a one-work-group kernel
-    RowNorm an{ly.attn_norm, c->ssq, sn, g.rms_eps, nullptr};
-    if (b && M > 16) {
-      launch_rstd(an, M, d, c->rstd, st);
-      an.rstd = c->rstd;
-    }
+    RowNorm an{ly.attn_norm, c->ssq, sn, g.rms_eps};
     launch_gemm(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, an, c->partial, e, st);
     SYNCPOINT();
     launch_attention(c->q_rot, Kl, Vl, b, m->cap, d, H, rows_per_slot, pos, nslots, slot_bytes / m->esz(), nchunk,
@@ -525,11 +519,7 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     }
     if (c->probe_role == kRoleGateUp) HIPCHK(c, hipEventRecord(c->probe_ev[2 * l], st));
     if (c->probe_role == kProbeKernelEvents) set_gemm_launch_events(c->probe_ev[2 * l], c->probe_ev[2 * l + 1]);
-    RowNorm fn{ly.ffn_norm, c->ssq, sn, g.rms_eps, nullptr};
-    if (b && M > 16) {
-      launch_rstd(fn, M, d, c->rstd, st);
-      fn.rstd = c->rstd;
-    }
+    RowNorm fn{ly.ffn_norm, c->ssq, sn, g.rms_eps};
     launch_gemm(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, fn, c->partial, e, st);
     if (c->probe_role == kRoleGateUp) HIPCHK(c, hipEventRecord(c->probe_ev[2 * l + 1], st));
     SYNCPOINT();
@@ -561,18 +551,14 @@ int chunks_for(int kv_len) { return (std::max(kv_len, 1) + kAttnChunk - 1) / kAt
 // x += W_out relu(W_in norm(x)); h = workspace [M, f].
 void launch_ed_ffn(stairs_ctx* c, const Model* m, const EdLayer& ly, float* x, float* ssq, int M) {
   const int d = m->cfg.d_model, f = m->cfg.d_ffn, sn = ssq_groups(d, 1);
-  const RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
+  const RowNorm none{nullptr, nullptr, 0, 0.f};
   GemmEpi e{};
   e.counters = c->counters;
   e.stream_weights = m->stream_weights;
   e.hd = m->hd;
   e.out = c->h;
   e.act = kActRelu;
-  RowNorm fn{ly.ffn_norm, ssq, sn, m->cfg.rms_eps, nullptr};
-  if (M > 16) {
-    launch_rstd(fn, M, d, c->rstd, c->st);
-    fn.rstd = c->rstd;
-  }
+  RowNorm fn{ly.ffn_norm, ssq, sn, m->cfg.rms_eps};
   launch_gemm(kRoleHead, 1, ly.w_in, f, d, x, d, M, fn, c->partial, e, c->st);
   e.act = kActNone;
   e.out = x;
@@ -597,15 +583,11 @@ int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logit
   } while (0)
   launch_embed(m->tok_emb, 1, c->tokens, 0, pos, M, d, c->x, c->ssq, m->hd, 0.f, c->rope_cs, st);
   SYNCPOINT();
-  const RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
+  const RowNorm none{nullptr, nullptr, 0, 0.f};
   const AttnMode self_mode{1.f, m->dec_bias, m->cap, m->cap - 1, 0};
   const AttnMode cross_mode{1.f, nullptr, 0, 0, c->S};
   auto normed = [&](const float* gain) {
-    RowNorm n{gain, c->ssq, sn, g.rms_eps, nullptr};
-    if (M > 16) {
-      launch_rstd(n, M, d, c->rstd, st);
-      n.rstd = c->rstd;
-    }
+    RowNorm n{gain, c->ssq, sn, g.rms_eps};
     return n;
   };
   for (int l = 0; l < g.n_layers; ++l) {
@@ -670,7 +652,7 @@ int encode_model(stairs_ctx* c, Model* m) {
   hipStream_t st = c->st;
   const int nch = chunks_for(S);
   if (S < 1 || S > m->max_src || nch > c->nchunk_cap) return fail(c, STAIRS_EINVAL, "encode: source outside the workspaces");
-  const RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
+  const RowNorm none{nullptr, nullptr, 0, 0.f};
   const AttnMode mode{1.f, m->enc_bias, 2 * m->max_src - 1, m->max_src - 1, S};
   auto rows_of = [&](int b) { return std::min(kMaxRows, S - b); };
   auto epi_for = [&](int b, char* K, char* V, float* out) {
@@ -689,11 +671,7 @@ int encode_model(stairs_ctx* c, Model* m) {
     return e;
   };
   auto normed = [&](const float* gain, int b, int M) {
-    RowNorm n{gain, c->enc_ssq + (size_t)b * sn, sn, g.rms_eps, nullptr};
-    if (M > 16) {
-      launch_rstd(n, M, d, c->rstd, st);
-      n.rstd = c->rstd;
-    }
+    RowNorm n{gain, c->enc_ssq + (size_t)b * sn, sn, g.rms_eps};
     return n;
   };
   for (int b = 0; b < S; b += kMaxRows)
@@ -1123,7 +1101,7 @@ static int alloc_workspaces(stairs_ctx* c, const WsDims& w) {
       (rc = dev_alloc(c, &c->partial, w.partial_floats)) ||
       (rc = dev_alloc(c, &c->part_o, (size_t)kMaxRows * Hmax * c->nchunk_cap * 128)) ||
       (rc = dev_alloc(c, &c->part_ml, (size_t)kMaxRows * Hmax * c->nchunk_cap * 2)) ||
-      (rc = dev_alloc(c, &c->rope_cs, (size_t)kMaxRows * 64)) || (rc = dev_alloc(c, &c->rstd, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->tokens, (size_t)c->tok_cap + kMaxRows)) ||
+      (rc = dev_alloc(c, &c->rope_cs, (size_t)kMaxRows * 64)) || (rc = dev_alloc(c, &c->tokens, (size_t)c->tok_cap + kMaxRows)) ||
       (rc = dev_alloc(c, &c->tgt_tok, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->counters, (size_t)kCounters)) || (rc = dev_alloc(c, &c->state, 2 * kSlotState)))
     return bail(rc);
   if (c->block_prefill) {
@@ -1711,7 +1689,7 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
     ok(hipMemcpyAsync(dX, X, (size_t)M * K * 4, hipMemcpyHostToDevice, st));
     if (b) launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(dW), reinterpret_cast<uint4*>(dWs), N, K, kPermNone, 0, 0, st);
     ok(hipMemsetAsync(dCnt, 0, kGemmCounters * sizeof(int), st));
-    RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
+    RowNorm none{nullptr, nullptr, 0, 0.f};
     GemmEpi e{};
     e.counters = dCnt;
     e.stream_weights = wbytes > kStreamHintBytes / 4;   // exercised by the larger test matrices
@@ -1797,7 +1775,7 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
     if (bytes_per_launch) *bytes_per_launch = 2.0 * f * d * esz;
     return STAIRS_OK;
   }
-  RowNorm none{nullptr, nullptr, 0, 0.f, nullptr};
+  RowNorm none{nullptr, nullptr, 0, 0.f};
   double bytes = 0;
   const PosRef tpos = abs_pos(c, which == 1 ? std::max(ctx_len, M) - M : 0);
   if (which == 1 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");

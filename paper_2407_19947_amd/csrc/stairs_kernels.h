@@ -45,13 +45,13 @@ __device__ __forceinline__ int pos_of(const PosRef& p, int r) {
 
 // Row normalisation folded into a GEMM: the input is x[m][k] * gain[k] * rstd[m] with
 // rstd[m] = 1/sqrt(sum_p ssq_part[m*ssq_n + p] / K + eps).  gain == nullptr: no scaling at all.
-// (bf16 kernels: the gain goes into the activation fragments, rstd[m] multiplies the row's finished sums.)
+// (bf16 kernels: the gain goes into the activation fragments, rstd[m] multiplies the row's finished sums; the
+// split-K kernel forms it in the work-group that finishes a column group, the small-M kernel in every work-group.)
 struct RowNorm {
   const float* gain;
   const float* ssq_part;
   int ssq_n;
   float eps;
-  const float* rstd;   // optional: rstd[m] already formed from the partials by launch_rstd (same arithmetic)
 };
 
 inline int ssq_groups(int d, int bf16) {
@@ -109,10 +109,6 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
 // The next bf16 launch_gemm records `start` at the beginning and `stop` at the end of its kernel (the events of the
 // launch itself, not records around it in the stream); one launch only.  Measurement aid.
 void set_gemm_launch_events(hipEvent_t start, hipEvent_t stop);
-
-// rstd[m] = 1/sqrt(sum of the row's partials / K + eps) for M rows, once per GEMM instead of once per work-group
-// (bf16 path; pays from 17 rows on, where every work-group would otherwise fetch 32 rows' partials)
-void launch_rstd(RowNorm nrm, int M, int K, float* rstd, hipStream_t st);
 
 // ---- small kernels ----------------------------------------------------------------------
 // x[m][:] = emb[tokens[pos+m]][:] (row of zeros if pos+m < 0), plus sum-of-squares partials; the same launch

@@ -372,17 +372,6 @@ __device__ __forceinline__ void rows_rstd(const RowNorm& nrm, int M, int K, floa
   }
 }
 
-__global__ __launch_bounds__(256) void k_rstd(RowNorm nrm, int M, int K, float* __restrict__ rstd) {
-  __shared__ float s_rstd[kMaxRows];
-  rows_rstd<kMaxRows / 8>(nrm, M, K, s_rstd);
-  __syncthreads();
-  if (threadIdx.x < M) rstd[threadIdx.x] = s_rstd[threadIdx.x];
-}
-
-void launch_rstd(RowNorm nrm, int M, int K, float* rstd, hipStream_t st) {
-  hipLaunchKernelGGL(k_rstd, dim3(1), dim3(256), 0, st, nrm, M, K, rstd);
-}
-
 // 8 consecutive x of one row -> (x * gain) -> bf16 high part and the bf16 of the remainder
 __device__ __forceinline__ void split_bf16x8(const float4& xa, const float4& xb, const float4& g0, const float4& g1,
                                              bool scale, uint4& hi, uint4& lo) {
@@ -481,14 +470,6 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
       g0 = gp[0];
       g1 = gp[1];
     }
-    if (j == 0 && nrm.gain && nrm.ssq_part) {
-      if (nrm.rstd) {
-        if (tid < M) s_rstd[tid] = nrm.rstd[tid];
-      } else {
-        rows_rstd<2 * CT>(nrm, M, K, s_rstd);
-      }
-      // read by the epilogue only, barriers away
-    }
 
     // fp32 -> (x * gain) -> bf16 hi + lo, stored in B-fragment order
     if (units > 0) {
@@ -571,8 +552,13 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint4* __restrict__ Wsw
 
   // split-K hand-off: the partial sums are out, take a ticket; the last arrival finishes the group
   if (!last_arrival(&epi.counters[blockIdx.x], SG, &s_last)) return;
-  gemm_epilogue<ROLE, 64 * NT, SPW == 1>(partial, SG, M, N, blockIdx.x * 64 * NT, epi,
-                                         (nrm.gain && nrm.ssq_part) ? s_rstd : nullptr);
+  // the rows' 1/rms is needed here only: the work-group that finishes a column group forms it
+  const bool normed = nrm.gain && nrm.ssq_part;
+  if (normed) {
+    rows_rstd<2 * CT>(nrm, M, K, s_rstd);
+    __syncthreads();
+  }
+  gemm_epilogue<ROLE, 64 * NT, SPW == 1>(partial, SG, M, N, blockIdx.x * 64 * NT, epi, normed ? s_rstd : nullptr);
   if (tid == 0) epi.counters[blockIdx.x] = 0;   // ready for the next launch on this stream
 }
 
