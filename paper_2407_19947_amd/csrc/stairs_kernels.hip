@@ -1580,32 +1580,24 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
         const float2 a2 = *reinterpret_cast<const float2*>(&s_o[2][jj][e]), a3 = *reinterpret_cast<const float2*>(&s_o[3][jj][e]);
         const float o0 = __fadd_rn(__fadd_rn(__fadd_rn(__fmul_rn(a0.x, f0), __fmul_rn(a1.x, f1)), __fmul_rn(a2.x, f2)), __fmul_rn(a3.x, f3));
         const float o1 = __fadd_rn(__fadd_rn(__fadd_rn(__fmul_rn(a0.y, f0), __fmul_rn(a1.y, f1)), __fmul_rn(a2.y, f2)), __fmul_rn(a3.y, f3));
+        // the chunk's sum of exponentials (a wave without keys has weight 0 and sum 0: it adds nothing); no branch
+        // around the LDS reads
+        const float l0 = s_l[0][jj], l1 = s_l[1][jj], l2 = s_l[2][jj], l3 = s_l[3][jj];
+        float lc = 0.f;
+        lc += f0 * l0;
+        lc += f1 * l1;
+        lc += f2 * l2;
+        lc += f3 * l3;
         if (single) {
           float2 res = make_float2(0.f, 0.f);
-          if (pos0 + m * step >= 0) {
-            float lc = 0.f;
-            if (m0 != -INFINITY) lc += f0 * s_l[0][jj];
-            if (m1 != -INFINITY) lc += f1 * s_l[1][jj];
-            if (m2 != -INFINITY) lc += f2 * s_l[2][jj];
-            if (m3 != -INFINITY) lc += f3 * s_l[3][jj];
-            res = make_float2(o0 / lc, o1 / lc);
-          }
+          if (pos0 + m * step >= 0) res = make_float2(o0 / lc, o1 / lc);
           *reinterpret_cast<float2*>(out + (size_t)m * d + h * HD + e) = res;
         } else {
           st_dev2(&part_o[(((size_t)m * H + h) * nchunk_cap + c) * HD + e], o0, o1);
+          // the thread with the row's first dims also leaves the chunk's (max, sum) pair
+          if (e == 0) st_dev2(part_ml + (((size_t)m * H + h) * nchunk_cap + c) * 2, mcc, lc);
         }
       }
-    }
-    if (!single && tid < 16 && ct * 16 + tid < M) {
-      const float m0 = s_m[0][tid], m1 = s_m[1][tid], m2 = s_m[2][tid], m3 = s_m[3][tid];
-      const float mcc = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
-      float lc = 0.f;
-      if (m0 != -INFINITY) lc += expf(m0 - mcc) * s_l[0][tid];
-      if (m1 != -INFINITY) lc += expf(m1 - mcc) * s_l[1][tid];
-      if (m2 != -INFINITY) lc += expf(m2 - mcc) * s_l[2][tid];
-      if (m3 != -INFINITY) lc += expf(m3 - mcc) * s_l[3][tid];
-      float* ml = part_ml + (((size_t)(ct * 16 + tid) * H + h) * nchunk_cap + c) * 2;
-      st_dev2(ml, mcc, lc);
     }
   }
 
