@@ -100,9 +100,9 @@ int stairs_init(stairs_ctx **out, const stairs_model_cfg *tcfg, const stairs_wei
 
 void stairs_free(stairs_ctx *ctx);
 
-/* Start a new sequence S = prompt[0..P) (Sec. 3.3: the "initial sentence"): both models
- * ingest prompt[0..P-2] into their KV caches; the last prompt token is the first row of the
- * first stair batch.  Prompts of 64 rows and more are ingested in blocks of up to 512 rows (bf16 models; library
+/* Start a new sequence S = prompt[0..P) (the text both models start from, Sec. 3.3 first
+ * paragraph): both models ingest prompt[0..P-2] into their KV caches; the last prompt token is
+ * the first row of the first stair batch.  Prompts of 64 rows and more are ingested in blocks of up to 512 rows (bf16 models; library
  * GEMMs on row-major copies of the weights), shorter ones with the decode kernels.  Requires 1 <= P and
  * P + k_max + 1 <= max_seq of both models.
  * Errors: EINVAL (NULL, P < 1, token id outside [0, vocab)), ECAPACITY. */
@@ -131,9 +131,9 @@ int stairs_verify(stairs_ctx *ctx, int32_t k, int32_t *target_tok_out, int32_t *
 int stairs_verify_tokens(stairs_ctx *ctx, const int32_t *draft, int32_t k, int32_t *target_tok_out,
                          int32_t *n_accepted_out, float *logits_out);
 
-/* Whole loop (Sec. 3.3 repeated "until the prompt is fully responded to", Sec. 3.2; here:
- * until exactly G tokens exist): prefill, then propose / verify until G tokens are produced;
- * the last iteration is truncated to G.  tokens_out: G ints.  stats: optional.
+/* Whole loop (the iteration of Sec. 3.3 repeated until the answer is complete, Sec. 3.2; the
+ * synthetic models have no end token, so here: until exactly G tokens exist): prefill, then
+ * propose / verify until G tokens are produced; the last iteration is truncated to G.  tokens_out: G ints.  stats: optional.
  * Requires P + G + k + 1 <= max_seq.  k = 0 is plain greedy generation of the target. */
 int stairs_generate(stairs_ctx *ctx, const int32_t *prompt, int32_t P, int32_t G, int32_t k,
                     int32_t *tokens_out, stairs_stats *stats);
@@ -194,7 +194,7 @@ int draft_propose_sampled(stairs_ctx *ctx, int32_t k, float temperature, uint64_
 int stairs_verify_sampled(stairs_ctx *ctx, int32_t k, float temperature, uint64_t seed, int32_t *emitted_out,
                           int32_t *n_accepted_out, float *logits_out);
 
-/* ---- encoder-decoder models (the model family of the paper's experiments, Sec. 2.3 / 4.2) ------------------
+/* ---- encoder-decoder models (the model family of the paper's experiments, Sec. 2.3 / 4.3 / 4.4) -----------
  * The source text goes through the encoder once; the stair batch of Sec. 3.3 is made of prefixes of the DECODER
  * sequence, and every stair row reads the same encoder output (its per-layer cross-attention keys and values are
  * computed once by stairs_encode).  Model: the original T5 layout -- RMS layer norm before every block, attention
@@ -280,9 +280,10 @@ int stairs_gemm_host(int32_t dtype, const void *W, const float *X, float *Y, int
  * events, nothing added to the stream): the kernel's duration in situ without the pair's overhead.
  * *ms_per_launch: mean duration; *bytes_per_launch: algorithmic bytes (matrix bytes; K and V
  * bytes of ctx_len positions; for 6/7 all matrices of the model plus its K and V bytes).
- * 0..5 do not disturb the sequence state but overwrite workspaces (do not call between
- * draft_propose and stairs_verify); 6, 7, 8, 9 and 10 also overwrite the cache rows of the M positions
- * they run at: call stairs_prefill before generating again. */
+ * 0, 2, 3, 4 and 5 do not disturb the sequence state but overwrite workspaces (not allowed between
+ * draft_propose and stairs_verify: ESTATE); 1 (its epilogue appends keys and values at positions
+ * ctx_len-M .. ctx_len-1; M <= ctx_len <= max_seq) and 6..10 overwrite cache rows: they END the current
+ * sequence, and the generation calls return ESTATE until stairs_prefill starts a new one. */
 int stairs_time_kernel(stairs_ctx *ctx, int32_t which, int32_t M, int32_t ctx_len, int32_t reps,
                        float *ms_per_launch, double *bytes_per_launch);
 

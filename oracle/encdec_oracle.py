@@ -3,7 +3,7 @@
 Only the tests, the smoke check and the benchmark's cpu_baseline leg may import this file.  It shares no code with
 the HIP library and never imports it; the library never imports it.
 
-The paper's experiments run encoder-decoder checkpoints (Sec. 2.3, Sec. 4.2): the source text goes through the
+The paper's experiments run encoder-decoder checkpoints (Sec. 2.3, Sec. 4.3, Sec. 4.4): the source text goes through the
 encoder once, and the stair batch of Sec. 3.3 is made of prefixes of the DECODER sequence; every stair row reads the
 same encoder output.  The paper gives no model arithmetic; the model here follows the published description of the
 original T5 (Raffel et al., 2020, Sec. 2.1) in this oracle's own code:

@@ -480,8 +480,8 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
   const size_t slot_off = pos.rps ? 0 : (size_t)slot * slot_bytes;
   if (slot < 0 || slot >= c->n_slots || nslots > c->n_slots || nslots * H > kAttnCounters || (pos.rps && (M % pos.rps || !b)))
     return fail(c, STAIRS_EINVAL, "forward: slots outside what the context holds");
-  launch_embed(m->tok_emb, b, c->tokens + (pos.rps ? 0 : (size_t)slot * c->tok_stride), pos.rps ? c->tok_stride : 0, pos, M, d,
-               c->x, c->ssq, m->hd, g.rope_theta, c->rope_cs, st);
+  launch_embed(m->tok_emb, b, c->tokens + (pos.rps ? 0 : (size_t)slot * c->tok_stride), pos.rps ? c->tok_stride : 0,
+               c->tok_stride, V, pos, M, d, c->x, c->ssq, m->hd, g.rope_theta, c->rope_cs, st);
   SYNCPOINT();
   const RowNorm none{nullptr, nullptr, 0, 0.f};
   for (int l = 0; l < g.n_layers; ++l) {
@@ -581,7 +581,7 @@ int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logit
   do {                                                          \
     if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));  \
   } while (0)
-  launch_embed(m->tok_emb, 1, c->tokens, 0, pos, M, d, c->x, c->ssq, m->hd, 0.f, c->rope_cs, st);
+  launch_embed(m->tok_emb, 1, c->tokens, 0, c->tok_stride, V, pos, M, d, c->x, c->ssq, m->hd, 0.f, c->rope_cs, st);
   SYNCPOINT();
   const RowNorm none{nullptr, nullptr, 0, 0.f};
   const AttnMode self_mode{1.f, m->dec_bias, m->cap, m->cap - 1, 0};
@@ -675,8 +675,8 @@ int encode_model(stairs_ctx* c, Model* m) {
     return n;
   };
   for (int b = 0; b < S; b += kMaxRows)
-    launch_embed(m->tok_emb, 1, c->src_tok, 0, abs_pos(c, b), rows_of(b), d, c->enc_x + (size_t)b * d, c->enc_ssq + (size_t)b * sn,
-                 m->hd, 0.f, c->rope_cs, st);
+    launch_embed(m->tok_emb, 1, c->src_tok, 0, S, g.vocab, abs_pos(c, b), rows_of(b), d, c->enc_x + (size_t)b * d,
+                 c->enc_ssq + (size_t)b * sn, m->hd, 0.f, c->rope_cs, st);
   for (size_t l = 0; l < m->enc.size(); ++l) {
     const EdLayer& ly = m->enc[l];
     for (int b = 0; b < S; b += kMaxRows) {
@@ -736,7 +736,7 @@ int ingest_blocks(stairs_ctx* c, Model* m, int from, int to, int slot) {
   const int* tokens = c->tokens + (size_t)slot * c->tok_stride;
   for (int p0 = from; p0 < to; p0 += kPfRows) {
     const int R = std::min(kPfRows, to - p0);
-    launch_pf_embed(static_cast<const uint16_t*>(m->tok_emb), tokens, p0, R, d, c->pf_x, st);
+    launch_pf_embed(static_cast<const uint16_t*>(m->tok_emb), tokens, p0, c->tok_stride, g.vocab, R, d, c->pf_x, st);
     launch_pf_rope_table(p0, R, m->hd, g.rope_theta, c->pf_cs, st);
     for (int l = 0; l < g.n_layers; ++l) {
       const Layer& ly = m->layers[l];
@@ -1493,6 +1493,10 @@ int stairs_reserve_batch(stairs_ctx* c, int32_t max_batch) {
   c->prefilled = false;
   c->pending_k = -1;
   if (max_batch <= c->n_slots) return STAIRS_OK;
+  // captured graphs hold the old pointers: they go first, so that no failure below can leave one that replays
+  // launches on released memory
+  for (auto& g : c->graphs) (void)hipGraphExecDestroy(g.exec);
+  c->graphs.clear();
   // new, larger arrays; the old ones are released
   auto release = [&](void* p) {
     auto it = std::find(c->owned.begin(), c->owned.end(), p);
@@ -1531,9 +1535,6 @@ int stairs_reserve_batch(stairs_ctx* c, int32_t max_batch) {
   (void)hipHostFree(c->h_pinned);
   c->h_pinned = hp;
   c->h_pinned_ints = ints;
-  // captured graphs hold the old pointers
-  for (auto& g : c->graphs) (void)hipGraphExecDestroy(g.exec);
-  c->graphs.clear();
   HIPCHK(c, hipStreamSynchronize(c->st));
   c->n_slots = max_batch;
   return STAIRS_OK;
@@ -1748,6 +1749,13 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
   const int d = g.d_model, f = g.d_ffn, V = g.vocab, b = m->bf16 ? 1 : 0;
   const size_t esz = m->esz();
   if (which >= 5 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");
+  if (which == 1 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");
+  // the QKV projection appends keys and values, the whole forwards do too: the caches no longer hold the current
+  // sequence afterwards, so it ends here (the generation calls then ask for stairs_prefill instead of using them)
+  if (which == 1 || which >= 6) {
+    c->prefilled = false;
+    c->T.valid = c->D.valid = 0;
+  }
   if (which == 8 || which == 9 || which == 10) {
     // the gate/up projection timed where it really runs: `reps` whole forwards of M rows ending at position
     // ctx_len-1, an event pair around each layer's gate/up launch, all other kernels untouched in between
@@ -1777,8 +1785,7 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
   }
   RowNorm none{nullptr, nullptr, 0, 0.f};
   double bytes = 0;
-  const PosRef tpos = abs_pos(c, which == 1 ? std::max(ctx_len, M) - M : 0);
-  if (which == 1 && (ctx_len < M || ctx_len > m->cap)) return fail(c, STAIRS_EINVAL, "ctx_len outside [M, max_seq]");
+  const PosRef tpos = abs_pos(c, which == 1 ? ctx_len - M : 0);
   if (which == 1) launch_rope_table(tpos, M, m->hd, g.rope_theta, c->rope_cs, c->st);
   for (int pass = 0; pass < 2; ++pass) {          // pass 0 = warm-up of one launch per layer
     const int n = pass ? reps : (which >= 6 ? 1 : g.n_layers);

@@ -111,10 +111,11 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
 void set_gemm_launch_events(hipEvent_t start, hipEvent_t stop);
 
 // ---- small kernels ----------------------------------------------------------------------
-// x[m][:] = emb[tokens[pos+m]][:] (row of zeros if pos+m < 0), plus sum-of-squares partials; the same launch
-// fills the rotation table cs of the M positions (see launch_rope_table); theta <= 0: the identity rotation (1, 0)
-void launch_embed(const void* emb, int emb_bf16, const int* tokens, int tok_slot_stride, PosRef pos, int M, int d,
-                  float* x, float* ssq_part, int hd, float theta, float2* cs, hipStream_t st);
+// x[m][:] = emb[tokens[pos+m]][:] (row of zeros if pos+m lies outside [0, tok_cap) or the id found there outside
+// [0, vocab)), plus sum-of-squares partials; the same launch fills the rotation table cs of the M positions (see
+// launch_rope_table); theta <= 0: the identity rotation (1, 0).  tok_cap = ints one sequence's token array holds.
+void launch_embed(const void* emb, int emb_bf16, const int* tokens, int tok_slot_stride, int tok_cap, int vocab, PosRef pos,
+                  int M, int d, float* x, float* ssq_part, int hd, float theta, float2* cs, hipStream_t st);
 // cs[m][i] = (cos, sin)((pos+m) * theta^(-2i/hd)), angle formed in double
 void launch_rope_table(PosRef pos, int M, int hd, float theta, float2* cs, hipStream_t st);
 // split-KV attention of M query rows at positions pos..pos+M-1 against keys 0..pos+M-1
@@ -172,8 +173,9 @@ void launch_accept_sampled(int* tokens, const float* tl, const float* dl, int ld
 // The projections of a block of up to kPfRows prompt rows are plain GEMMs done by the BLAS library on bf16 copies
 // of the activations (high part, then low part accumulated onto it); everything around them is here.
 constexpr int kPfRows = 512;
-// x[r][:] = emb[tokens[p0 + r]][:] as float, r < R
-void launch_pf_embed(const uint16_t* emb, const int* tokens, int p0, int R, int d, float* x, hipStream_t st);
+// x[r][:] = emb[tokens[p0 + r]][:] as float, r < R (zeros for a position outside [0, tok_cap) or an id outside [0, vocab))
+void launch_pf_embed(const uint16_t* emb, const int* tokens, int p0, int tok_cap, int vocab, int R, int d, float* x,
+                     hipStream_t st);
 // one row per work-group: v = x (gain == nullptr) or x * rstd * gain with rstd = 1/sqrt(mean(x^2) + eps);
 // hi = bf16(v), lo = bf16(v - hi); row-major [R, d] outputs
 void launch_pf_norm_split(const float* x, const float* gain, float eps, int R, int d, uint16_t* hi, uint16_t* lo, hipStream_t st);

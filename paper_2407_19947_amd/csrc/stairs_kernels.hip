@@ -89,11 +89,20 @@ __device__ __forceinline__ float2 ld_dev2(const float* p) {
 // all of this work-group's stores have completed; then one thread takes the ticket.  Returns true in
 // every thread of the work-group that arrived last of `expected`.
 __device__ __forceinline__ bool last_arrival(int* counter, int expected, int* s_flag) {
+  // The hand-off rests on two things the memory model does not promise for relaxed accesses: (1) a device-scope
+  // write-through store is acknowledged only once it sits at the level all XCDs share, so "vmcnt == 0" means the
+  // partial results are visible there; (2) the last arrival's loads of the others' results are issued after its
+  // ticket.  (1) is the hardware's behaviour for sc1 stores; for (2) the signal fences keep the compiler from moving
+  // memory accesses across the ticket in either direction (they emit no instruction).  Should either stop holding,
+  // the fix is a release fence before and an acquire fence after the ticket (__atomic_thread_fence at agent scope):
+  // correct by the model, at the price of an L2 write-back / invalidate per work-group.
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   if (threadIdx.x == 0)
     *s_flag = (__hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1) ? 1 : 0;
   __syncthreads();
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
   return *s_flag != 0;
 }
 
@@ -1088,11 +1097,13 @@ void launch_fin_qkv_rope_f32(const float* partial, int S, int M, int d, int H, c
 // GW = residual columns per sum-of-squares partial: 1024 (one per block) or 16 (one per 4 lanes)
 // The block column after the last embedding column fills the row's rotation table instead:
 // cs[m][i] = (cos, sin)(position * theta^(-2i/hd)), the angle formed in double.
+// A row whose position lies outside [0, tok_cap) or whose token id lies outside [0, vocab) becomes a row of zeros:
+// the gather never leaves the token array or the embedding table, whatever the array holds.
 template <typename E, int GW>
 __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const int* __restrict__ tokens,
-                                               int tok_slot_stride, PosRef pos, int d, float* __restrict__ x,
-                                               float* __restrict__ ssq_part, int ssq_n, int hd, double theta,
-                                               float2* __restrict__ cs) {
+                                               int tok_slot_stride, int tok_cap, int vocab, PosRef pos, int d,
+                                               float* __restrict__ x, float* __restrict__ ssq_part, int ssq_n, int hd,
+                                               double theta, float2* __restrict__ cs) {
   __shared__ float sm[4];
   const int m = blockIdx.y;
   const int p = pos_of(pos, m);
@@ -1109,8 +1120,9 @@ __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const 
   float ss = 0.f;
   if (c < d) {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (p >= 0) {
-      const E* row = emb + (size_t)tokens[p] * d + c;
+    const int id = (p >= 0 && p < tok_cap) ? tokens[p] : -1;
+    if (id >= 0 && id < vocab) {
+      const E* row = emb + (size_t)id * d + c;
       v.x = load_kv(row); v.y = load_kv(row + 1); v.z = load_kv(row + 2); v.w = load_kv(row + 3);
     }
     *reinterpret_cast<float4*>(x + (size_t)m * d + c) = v;
@@ -1126,16 +1138,16 @@ __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const 
   }
 }
 
-void launch_embed(const void* emb, int emb_bf16, const int* tokens, int tok_slot_stride, PosRef pos, int M, int d,
-                  float* x, float* ssq_part, int hd, float theta, float2* cs, hipStream_t st) {
+void launch_embed(const void* emb, int emb_bf16, const int* tokens, int tok_slot_stride, int tok_cap, int vocab, PosRef pos,
+                  int M, int d, float* x, float* ssq_part, int hd, float theta, float2* cs, hipStream_t st) {
   dim3 grid((d + 1023) / 1024 + 1, M), block(256);
   const int sn = ssq_groups(d, emb_bf16);
   if (emb_bf16)
     hipLaunchKernelGGL((k_embed<uint16_t, 16>), grid, block, 0, st, static_cast<const uint16_t*>(emb), tokens,
-                       tok_slot_stride, pos, d, x, ssq_part, sn, hd, (double)theta, cs);
+                       tok_slot_stride, tok_cap, vocab, pos, d, x, ssq_part, sn, hd, (double)theta, cs);
   else
     hipLaunchKernelGGL((k_embed<float, 1024>), grid, block, 0, st, static_cast<const float*>(emb), tokens,
-                       tok_slot_stride, pos, d, x, ssq_part, sn, hd, (double)theta, cs);
+                       tok_slot_stride, tok_cap, vocab, pos, d, x, ssq_part, sn, hd, (double)theta, cs);
 }
 
 __global__ void k_rope_table(PosRef pos, int hd, double theta, float2* __restrict__ cs) {
@@ -2084,15 +2096,21 @@ void launch_accept_sampled(int* tokens, const float* tl, const float* dl, int ld
 // prompt ingestion in large row blocks: the element-wise work around the library GEMMs
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_pf_embed(const uint16_t* __restrict__ emb, const int* __restrict__ tokens, int p0,
-                                                  int d, float* __restrict__ x) {
+                                                  int tok_cap, int vocab, int d, float* __restrict__ x) {
   const int r = blockIdx.y, c = (blockIdx.x * 256 + threadIdx.x) * 4;
   if (c >= d) return;
-  const uint16_t* row = emb + (size_t)tokens[p0 + r] * d + c;
-  *reinterpret_cast<float4*>(x + (size_t)r * d + c) =
-      make_float4(load_kv(row), load_kv(row + 1), load_kv(row + 2), load_kv(row + 3));
+  const int p = p0 + r;
+  const int id = (p >= 0 && p < tok_cap) ? tokens[p] : -1;     // as k_embed: never outside the array or the table
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (id >= 0 && id < vocab) {
+    const uint16_t* row = emb + (size_t)id * d + c;
+    v = make_float4(load_kv(row), load_kv(row + 1), load_kv(row + 2), load_kv(row + 3));
+  }
+  *reinterpret_cast<float4*>(x + (size_t)r * d + c) = v;
 }
-void launch_pf_embed(const uint16_t* emb, const int* tokens, int p0, int R, int d, float* x, hipStream_t st) {
-  hipLaunchKernelGGL(k_pf_embed, dim3((d + 1023) / 1024, R), dim3(256), 0, st, emb, tokens, p0, d, x);
+void launch_pf_embed(const uint16_t* emb, const int* tokens, int p0, int tok_cap, int vocab, int R, int d, float* x,
+                     hipStream_t st) {
+  hipLaunchKernelGGL(k_pf_embed, dim3((d + 1023) / 1024, R), dim3(256), 0, st, emb, tokens, p0, tok_cap, vocab, d, x);
 }
 
 __global__ __launch_bounds__(256) void k_pf_norm_split(const float* __restrict__ x, const float* __restrict__ gain, float eps,

@@ -193,7 +193,7 @@ def make_prompt(workload, P: Optional[int] = None) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------------------
-# Encoder-decoder models (the model family of the paper's experiments, Sec. 2.3 / Sec. 4.2: T5)
+# Encoder-decoder models (the model family of the paper's experiments, Sec. 2.3, Sec. 4.3, Sec. 4.4: T5)
 # ----------------------------------------------------------------------------------------
 REL_BUCKETS = 32
 REL_MAX_DISTANCE = 128

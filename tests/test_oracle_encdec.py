@@ -191,3 +191,120 @@ def test_independent_draft_and_wide_attention():
     T = eo.BoundDecoder(eo.EncDecOracleModel(t), src)
     D = eo.BoundDecoder(eo.EncDecOracleModel(d), src)
     assert so.stairs_cached(T, D, [0], 12, 3).tokens == so.greedy_bruteforce(T, [0], 12)
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# the composition of the blocks (which norm feeds which projection, where the residuals are added, the encoder's final
+# norm in front of the cross-attention keys and values): the whole model again out of PyTorch library routines, with a
+# different gain vector on every norm so that a misplaced or missing one changes the result
+# ----------------------------------------------------------------------------------------------------------------
+def _with_distinct_gains(t, seed=11):
+    rng = np.random.default_rng(seed)
+    c = _clone(t)
+    gain = lambda: (1.0 + 0.5 * rng.standard_normal(t.d_model)).astype(np.float32)     # noqa: E731
+    for l in c.enc_layers:
+        l["attn_norm"], l["ffn_norm"] = gain(), gain()
+    for l in c.dec_layers:
+        l["attn_norm"], l["cross_norm"], l["ffn_norm"] = gain(), gain(), gain()
+    c.enc_final_norm, c.dec_final_norm = gain(), gain()
+    return c
+
+
+def _torch_encdec_logits(t, src, ids):
+    """Encoder-decoder forward of the original T5 layout out of torch.nn.functional routines (float64)."""
+    F = torch.nn.functional
+    f64 = lambda a: torch.from_numpy(so._decode(np.asarray(a), np.float64).copy())     # noqa: E731
+    H, hd, d = t.n_heads, t.head_dim, t.d_model
+
+    def norm(x, g):
+        return F.rms_norm(x, (d,), weight=f64(g), eps=t.rms_eps)
+
+    def heads(x):                                   # [T, H*hd] -> [H, T, hd]
+        return x.reshape(x.shape[0], H, hd).transpose(0, 1)
+
+    def attn(xq, xkv, lw, names, mask):
+        q, k, v = (heads(F.linear(x, f64(lw[n]))) for x, n in zip((xq, xkv, xkv), names[:3]))
+        a = F.scaled_dot_product_attention(q, k, v, attn_mask=mask, scale=1.0)
+        return F.linear(a.transpose(0, 1).reshape(xq.shape[0], H * hd), f64(lw[names[3]]))
+
+    def ffn(x, lw):
+        return F.linear(F.relu(F.linear(norm(x, lw["ffn_norm"]), f64(lw["w_in"]))), f64(lw["w_out"]))
+
+    S, M = len(src), len(ids)
+    emb = f64(t.tok_emb)
+    pos_s, pos_m = np.arange(S), np.arange(M)
+    enc_mask = torch.from_numpy(eo.position_bias(t.enc_rel_bias.astype(np.float64), pos_s, pos_s, True, t.rel_max_distance))
+    x = emb[torch.as_tensor(np.asarray(src, dtype=np.int64))]
+    for lw in t.enc_layers:
+        h = norm(x, lw["attn_norm"])
+        x = x + attn(h, h, lw, ("wq", "wk", "wv", "wo"), enc_mask)
+        x = x + ffn(x, lw)
+    memory = norm(x, t.enc_final_norm)
+    dec_bias = eo.position_bias(t.dec_rel_bias.astype(np.float64), pos_m, pos_m, False, t.rel_max_distance)
+    causal = np.where(pos_m[None, :] > pos_m[:, None], -np.inf, 0.0)
+    dec_mask = torch.from_numpy(dec_bias + causal[None])
+    y = emb[torch.as_tensor(np.asarray(ids, dtype=np.int64))]
+    for lw in t.dec_layers:
+        h = norm(y, lw["attn_norm"])
+        y = y + attn(h, h, lw, ("wq", "wk", "wv", "wo"), dec_mask)
+        y = y + attn(norm(y, lw["cross_norm"]), memory, lw, ("cq", "ck", "cv", "co"), None)
+        y = y + ffn(y, lw)
+    return F.linear(norm(y, t.dec_final_norm), f64(t.lm_head)).numpy()
+
+
+def test_whole_model_against_a_library_composition_with_distinct_gains():
+    w, t, d, src = _tiny()
+    tt = _with_distinct_gains(t)
+    ids = [0] + list(np.random.default_rng(8).integers(1, t.vocab, 9))
+    got = so.forward_full(eo.BoundDecoder(eo.EncDecOracleModel(tt), src), ids)
+    want = _torch_encdec_logits(tt, src, ids)
+    assert np.allclose(got, want, atol=1e-9), float(np.max(np.abs(got - want)))
+    # the check has teeth: every one of the gain vectors moves the logits
+    for stack, name in (("enc", "attn_norm"), ("enc", "ffn_norm"), ("dec", "attn_norm"), ("dec", "cross_norm"),
+                        ("dec", "ffn_norm"), (None, "enc_final_norm"), (None, "dec_final_norm")):
+        t2 = _clone(tt)
+        if stack is None:
+            setattr(t2, name, np.ones(t.d_model, np.float32))
+        else:
+            (t2.enc_layers if stack == "enc" else t2.dec_layers)[0][name] = np.ones(t.d_model, np.float32)
+        other = so.forward_full(eo.BoundDecoder(eo.EncDecOracleModel(t2), src), ids)
+        assert np.max(np.abs(other - want)) > 1e-6, (stack, name)
+
+
+def test_cross_attention_block_written_out_with_loops():
+    """One decoder layer, one head, decoder matrices that switch self-attention and feed-forward off (zero output
+    projections): logits = unembedding of norm(x + W_co sum_s softmax_s(q . k_s) v_s) with q from the cross norm of the
+    embedding and k_s, v_s from the encoder output, written out element by element."""
+    w = si.scaled_encdec_workload("t5_tiny", target=dict(n_enc_layers=1, n_dec_layers=1, d_model=256, n_heads=1, head_dim=64,
+                                                       d_ffn=256, vocab=64))
+    t, _ = si.make_encdec_pair(w)
+    tt = _with_distinct_gains(t, seed=3)
+    lw = tt.dec_layers[0]
+    lw["wo"] = np.zeros_like(lw["wo"])
+    lw["w_out"] = np.zeros_like(lw["w_out"])
+    src = si.make_source(w)[:5]
+    m = eo.EncDecOracleModel(tt)
+    ids = [0, 9]
+    got = so.forward_full(eo.BoundDecoder(m, src), ids)
+    enc = m.encode(src)                                   # [S, d]; the encoder stack is pinned by the test above
+    dec = lambda a: so._decode(np.asarray(a), np.float64)  # noqa: E731
+    emb, cq, ck, cv, co, head = (dec(a) for a in (tt.tok_emb, lw["cq"], lw["ck"], lw["cv"], lw["co"], tt.lm_head))
+    d_model, hd = t.d_model, t.head_dim
+    for row, tok in enumerate(ids):
+        x = emb[tok]
+        ms = sum(float(v) ** 2 for v in x) / d_model
+        h = [float(x[i]) / np.sqrt(ms + tt.rms_eps) * float(lw["cross_norm"][i]) for i in range(d_model)]
+        q = [sum(cq[e, i] * h[i] for i in range(d_model)) for e in range(hd)]
+        scores, vals = [], []
+        for s in range(len(src)):
+            k_s = [sum(ck[e, i] * enc[s, i] for i in range(d_model)) for e in range(hd)]
+            vals.append([sum(cv[e, i] * enc[s, i] for i in range(d_model)) for e in range(hd)])
+            scores.append(sum(q[e] * k_s[e] for e in range(hd)))
+        mx = max(scores)
+        wts = [np.exp(s - mx) for s in scores]
+        a = [sum(wts[s] * vals[s][e] for s in range(len(src))) / sum(wts) for e in range(hd)]
+        y = [float(x[i]) + sum(co[i, e] * a[e] for e in range(hd)) for i in range(d_model)]
+        ms = sum(v * v for v in y) / d_model
+        z = [y[i] / np.sqrt(ms + tt.rms_eps) * float(tt.dec_final_norm[i]) for i in range(d_model)]
+        want = [sum(head[v, i] * z[i] for i in range(d_model)) for v in range(t.vocab)]
+        assert np.allclose(got[row], want, atol=1e-9)

@@ -165,3 +165,39 @@ def test_draft_length_zero_is_plain_sampling_and_seeds_matter():
     toks4, its4 = sa.stairs_sampled(T, D, prompt, 40, 4, temp, 5)
     acc = [it.n_accepted for it in its4]
     assert 0 < sum(acc) < 4 * len(acc), acc
+
+
+def test_fallback_when_nothing_is_left_of_p_minus_q(monkeypatch):
+    """A token that is not kept while p - q has no positive entry.  In exact arithmetic this has probability zero (not
+    kept means p(d) < q(d), and two distributions cannot differ downwards only); the scheme the paper points to (Sec. 2.2,
+    Sec. 5) therefore says nothing about it, and in float64 no honest input reaches it (p == q gives a ratio of
+    exactly 1 > u).  The reading: the replacement is drawn from p itself, which is the right distribution when p == q.
+    The walk is driven there by substituting a keep/replace uniform of 1."""
+    rng = np.random.default_rng(4)
+    V, k, L, temp, key = 50, 3, 11, 0.7, sa.key_from_seed(9)
+    logits = rng.standard_normal((k + 1, V))
+    d = [int(x) for x in rng.integers(0, V, k)]
+    real_uniform = sa.uniform
+
+    def fake_uniform(pos, stream, n, key_):
+        if stream == sa.STREAM_ACCEPT and pos == L + 1:      # the second proposal is refused whatever its ratio is
+            return np.ones(n)
+        return real_uniform(pos, stream, n, key_)
+
+    monkeypatch.setattr(sa, "uniform", fake_uniform)
+    n, emitted, us, ratios = sa.validate_sampled(L, d, logits, logits[:k], temp, key)     # assistant == main model
+    assert n == 1 and emitted[:1] == d[:1] and len(emitted) == 2
+    assert ratios == [1.0, 1.0] and us[1] == 1.0
+    logp = sa.log_softmax(logits[1] / temp)
+    assert not np.any(np.isfinite(sa.residual_scores(logp, logp)))
+    assert emitted[1] == sa.draw(logp, L + 1, sa.STREAM_TARGET, key)                    # a draw from p at that position
+    # and such draws follow p: over many positions the emitted token's frequencies match (chi-square, 30 cells)
+    p = np.exp(sa.log_softmax(logits[0][:30] / temp))
+    counts = np.zeros(30)
+    N = 6000
+    for pos in range(N):
+        monkeypatch.setattr(sa, "uniform", lambda ps, st, n_, k_: np.ones(n_) if st == sa.STREAM_ACCEPT else real_uniform(ps, st, n_, k_))
+        _, em, _, _ = sa.validate_sampled(pos, [d[0] % 30], logits[:2, :30], logits[:1, :30], temp, key)
+        counts[em[0]] += 1
+    chi2 = float(np.sum((counts - N * p) ** 2 / (N * p)))
+    assert chi2 < 70.0, chi2                                                              # 29 degrees of freedom

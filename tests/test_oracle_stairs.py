@@ -166,3 +166,81 @@ def test_generation_is_truncated_to_G():
 def test_top2_margin():
     assert so.top2_margin(np.array([0.1, 3.0, 2.5, -1.0])) == pytest.approx(0.5)
     assert so.greedy_token(np.array([1.0, 7.0, 7.0])) == 1     # ties -> lowest index
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# the teacher-forcing hooks the GPU parity tests lean on: CachedStairs.propose(forced=) and .adopt
+# ----------------------------------------------------------------------------------------------------------------
+def _hook_models():
+    w = si.scaled_workload("cfg1_tiny_fp32", target=dict(n_layers=3, d_model=64, n_heads=2, d_ffn=128, vocab=96),
+                           draft=dict(kind="prefix", n_layers=1), deep_scale=0.3, P=7, G=20)
+    target, draft = si.make_pair(w)
+    return so.OracleModel(target, np.float64), so.OracleModel(draft, np.float64), [int(x) for x in si.make_prompt(w)]
+
+
+def test_forcing_the_oracles_own_choices_changes_nothing():
+    T, D, prompt = _hook_models()
+    k, G = 3, 18
+    free = so.CachedStairs(T, D, prompt, len(prompt) + G + k + 2).run(G, k, keep_logits=True)
+    st = so.CachedStairs(T, D, prompt, len(prompt) + G + k + 2)
+    for it in free.iterations:
+        L = len(st.seq)
+        assert L == it.L
+        d = st.propose(k, forced=it.draft)
+        assert d == it.draft
+        got = st.verify(d)
+        assert got.predicted == it.predicted and got.n_accepted == it.n_accepted
+        assert np.array_equal(got.logits, it.logits)
+        st.adopt(L, it.predicted[:it.n_accepted + 1])          # adopting its own result again is the identity
+    assert st.seq[len(prompt):len(prompt) + G] == free.tokens
+
+
+def test_forced_tokens_are_what_the_assistant_is_fed():
+    """With forced tokens f_1..f_k the j-th logits row is the assistant's distribution after seq + f_1..f_{j-1}
+    (a plain full forward), whatever the oracle itself would have chosen."""
+    T, D, prompt = _hook_models()
+    k = 4
+    st = so.CachedStairs(T, D, prompt, len(prompt) + 3 * (k + 1) + 2)
+    rng = np.random.default_rng(0)
+    seq = list(prompt)
+    for _ in range(2):
+        L = len(st.seq)
+        forced = [int(x) for x in rng.integers(0, T.V, k)]
+        rows = []
+        own = st.propose(k, forced=forced, logits_out=rows)
+        assert len(rows) == k
+        for j in range(k):
+            want = so.forward_full(D, st.seq + forced[:j])[-1]
+            assert np.allclose(rows[j], want, atol=1e-10)
+            assert own[j] == int(np.argmax(want))
+        # the main model scores the forced tokens; the test adopts a SHORTER stair path than the oracle's own walk
+        it = st.verify(forced)
+        want = so.forward_full(T, st.seq[:L] + forced)[L - 1:]
+        assert np.allclose(it.logits, want, atol=1e-10)
+        st.adopt(L, it.predicted[:1])
+        seq = seq + it.predicted[:1]
+        assert st.seq == seq
+        assert st.tc.length == L and st.dc.length <= L
+
+
+def test_adopting_another_path_keeps_the_caches_consistent():
+    """After adopt() onto tokens another implementation accepted (here: fewer than the oracle's own walk kept), the next
+    stair batch's logits are those of a full forward over the adopted sequence: the cache rows beyond it are dead."""
+    T, D, prompt = _hook_models()
+    k = 3
+    st = so.CachedStairs(T, T, prompt, len(prompt) + 40)           # assistant == main model: everything is accepted
+    seq = list(prompt)
+    for cut in (0, 2, 1, 3):
+        L = len(st.seq)
+        d = st.propose(k)
+        it = st.verify(d)
+        assert it.n_accepted == k
+        st.adopt(L, it.predicted[:cut + 1])                         # keep only `cut` assistant tokens
+        seq = seq + it.predicted[:cut + 1]
+        assert st.seq == seq
+        d2 = st.propose(k)
+        full = so.forward_full(T, seq + d2)
+        assert d2 == [int(np.argmax(full[len(seq) - 1 + j])) for j in range(k)]   # the assistant's cache is consistent too
+        it2 = st.verify(d2)
+        assert np.allclose(it2.logits, full[len(seq) - 1:], atol=1e-10)
+        seq = st.seq
