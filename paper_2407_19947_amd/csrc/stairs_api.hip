@@ -87,6 +87,8 @@ struct stairs_ctx {
   float *x = nullptr, *ssq = nullptr, *q_rot = nullptr, *attn_out = nullptr, *h = nullptr, *logits = nullptr;
   float *partial = nullptr, *part_o = nullptr, *part_ml = nullptr;
   float2* rope_cs = nullptr;
+  // activation fragments of x, attn_out and h for forwards of more than 4 rows (bf16 models), see frag_bytes()
+  uint4 *xf = nullptr, *af = nullptr, *hf = nullptr;
   // block prefill (bf16 models, env STAIRS_NO_BLOCK_PREFILL=1 turns it off): BLAS handle and [kPfRows, .] workspaces
   bool block_prefill = false;
   rocblas_handle blas = nullptr;
@@ -480,10 +482,15 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
   const size_t slot_off = pos.rps ? 0 : (size_t)slot * slot_bytes;
   if (slot < 0 || slot >= c->n_slots || nslots > c->n_slots || nslots * H > kAttnCounters || (pos.rps && (M % pos.rps || !b)))
     return fail(c, STAIRS_EINVAL, "forward: slots outside what the context holds");
+  // more than 4 rows (bf16): every producer of an activation also leaves its MFMA operand fragments, with the gain of
+  // the norm in front of the next projection folded in, and the projections take the hand-off-free kernel
+  const bool fr = b && M > 4;
   launch_embed(m->tok_emb, b, c->tokens + (pos.rps ? 0 : (size_t)slot * c->tok_stride), pos.rps ? c->tok_stride : 0,
-               c->tok_stride, V, pos, M, d, c->x, c->ssq, m->hd, g.rope_theta, c->rope_cs, st);
+               c->tok_stride, V, pos, M, d, c->x, c->ssq, m->hd, g.rope_theta, c->rope_cs, st, fr ? c->xf : nullptr,
+               m->layers[0].attn_norm);
   SYNCPOINT();
   const RowNorm none{nullptr, nullptr, 0, 0.f};
+  AttnMode amode{0.f, nullptr, 0, 0, 0, fr ? c->af : nullptr};
   for (int l = 0; l < g.n_layers; ++l) {
     const Layer& ly = m->layers[l];
     char* Kl = m->Kc + slot_off + l * m->kv_layer_bytes;
@@ -504,15 +511,19 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     e.ssq_out = c->ssq;
     e.out = c->q_rot;
     RowNorm an{ly.attn_norm, c->ssq, sn, g.rms_eps};
-    launch_gemm(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, an, c->partial, e, st);
+    launch_gemm(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, an, c->partial, e, st, fr ? c->xf : nullptr);
     SYNCPOINT();
     launch_attention(c->q_rot, Kl, Vl, b, m->cap, d, H, rows_per_slot, pos, nslots, slot_bytes / m->esz(), nchunk,
-                     c->nchunk_cap, c->part_o, c->part_ml, c->counters + kGemmCounters, c->attn_out, st);
+                     c->nchunk_cap, c->part_o, c->part_ml, c->counters + kGemmCounters, c->attn_out, st, amode);
     SYNCPOINT();
     e.out = c->x;
-    launch_gemm(kRoleWo, b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, e, st);
+    e.frag_out = fr ? c->xf : nullptr;             // x after the attention block, for the gate/up projection
+    e.frag_gain = ly.ffn_norm;
+    launch_gemm(kRoleWo, b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, e, st, fr ? c->af : nullptr);
     SYNCPOINT();
     e.out = c->h;
+    e.frag_out = fr ? c->hf : nullptr;             // the SwiGLU output, for the down projection
+    e.frag_gain = nullptr;
     if (c->probe_role == kProbeEmptyPair) {      // calibration: the pair with nothing between its two records
       HIPCHK(c, hipEventRecord(c->probe_ev[2 * l], st));
       HIPCHK(c, hipEventRecord(c->probe_ev[2 * l + 1], st));
@@ -520,11 +531,13 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     if (c->probe_role == kRoleGateUp) HIPCHK(c, hipEventRecord(c->probe_ev[2 * l], st));
     if (c->probe_role == kProbeKernelEvents) set_gemm_launch_events(c->probe_ev[2 * l], c->probe_ev[2 * l + 1]);
     RowNorm fn{ly.ffn_norm, c->ssq, sn, g.rms_eps};
-    launch_gemm(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, fn, c->partial, e, st);
+    launch_gemm(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, fn, c->partial, e, st, fr ? c->xf : nullptr);
     if (c->probe_role == kRoleGateUp) HIPCHK(c, hipEventRecord(c->probe_ev[2 * l + 1], st));
     SYNCPOINT();
     e.out = c->x;
-    launch_gemm(kRoleDown, b, ly.wdown, d, f, c->h, f, M, none, c->partial, e, st);
+    e.frag_out = fr ? c->xf : nullptr;             // x after the layer, for the next layer's QKV or the unembedding
+    e.frag_gain = l + 1 < g.n_layers ? m->layers[l + 1].attn_norm : m->final_norm;
+    launch_gemm(kRoleDown, b, ly.wdown, d, f, c->h, f, M, none, c->partial, e, st, fr ? c->hf : nullptr);
     SYNCPOINT();
   }
   if (logits_rows > 0) {
@@ -534,8 +547,9 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     e.stream_weights = m->stream_weights;
     e.out = logits_dst ? logits_dst : c->logits;
     e.hd = m->hd;
+    // (the fragments hold all M rows: usable when the unembedding takes them all)
     launch_gemm(kRoleHead, b, m->lm_head, V, d, c->x + (size_t)r0 * d, d, logits_rows,
-                RowNorm{m->final_norm, c->ssq + r0 * sn, sn, g.rms_eps}, c->partial, e, st);
+                RowNorm{m->final_norm, c->ssq + r0 * sn, sn, g.rms_eps}, c->partial, e, st, (fr && r0 == 0) ? c->xf : nullptr);
     SYNCPOINT();
   }
   HIPCHK(c, hipGetLastError());
@@ -1099,6 +1113,8 @@ static int alloc_workspaces(stairs_ctx* c, const WsDims& w) {
       (rc = dev_alloc(c, &c->q_rot, (size_t)kMaxRows * wide)) || (rc = dev_alloc(c, &c->attn_out, (size_t)kMaxRows * wide)) ||
       (rc = dev_alloc(c, &c->h, (size_t)kMaxRows * fmax)) || (rc = dev_alloc(c, &c->logits, (size_t)kMaxRows * w.vocab)) ||
       (rc = dev_alloc(c, &c->partial, w.partial_floats)) ||
+      (rc = dev_alloc(c, &c->xf, frag_bytes(dmax) / sizeof(uint4))) || (rc = dev_alloc(c, &c->af, frag_bytes(wide) / sizeof(uint4))) ||
+      (rc = dev_alloc(c, &c->hf, frag_bytes(fmax) / sizeof(uint4))) ||
       (rc = dev_alloc(c, &c->part_o, (size_t)kMaxRows * Hmax * c->nchunk_cap * 128)) ||
       (rc = dev_alloc(c, &c->part_ml, (size_t)kMaxRows * Hmax * c->nchunk_cap * 2)) ||
       (rc = dev_alloc(c, &c->rope_cs, (size_t)kMaxRows * 64)) || (rc = dev_alloc(c, &c->tokens, (size_t)c->tok_cap + kMaxRows)) ||
@@ -1675,6 +1691,8 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
   char *dW = nullptr, *dWs = nullptr;
   float *dX = nullptr, *dP = nullptr, *dY = nullptr;
   int* dCnt = nullptr;
+  uint4* dF = nullptr;                       // activation fragments (bf16, more than 4 rows)
+  const bool fr = b && M > 4;
   int rc = STAIRS_OK;
   auto ok = [&](hipError_t e) {
     if (e != hipSuccess && rc == STAIRS_OK) {
@@ -1685,7 +1703,8 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
   };
   if (ok(hipMalloc((void**)&dW, wbytes)) && ok(hipMalloc((void**)&dX, (size_t)M * K * 4)) &&
       ok(hipMalloc((void**)&dP, (size_t)S * M * N * 4)) && ok(hipMalloc((void**)&dY, (size_t)M * N * 4)) &&
-      ok(hipMalloc((void**)&dCnt, kGemmCounters * sizeof(int))) && (!b || ok(hipMalloc((void**)&dWs, wbytes)))) {
+      ok(hipMalloc((void**)&dCnt, kGemmCounters * sizeof(int))) && (!b || ok(hipMalloc((void**)&dWs, wbytes))) &&
+      (!fr || ok(hipMalloc((void**)&dF, frag_bytes(K))))) {
     ok(hipMemcpyAsync(dW, W, wbytes, hipMemcpyHostToDevice, st));
     ok(hipMemcpyAsync(dX, X, (size_t)M * K * 4, hipMemcpyHostToDevice, st));
     if (b) launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(dW), reinterpret_cast<uint4*>(dWs), N, K, kPermNone, 0, 0, st);
@@ -1696,12 +1715,14 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
     e.stream_weights = wbytes > kStreamHintBytes / 4;   // exercised by the larger test matrices
     e.out = dY;
     e.hd = 64;
-    launch_gemm(kRoleHead, b, b ? dWs : dW, N, K, dX, K, M, none, dP, e, st);
+    if (fr) launch_split_frag(dX, K, M, K, nullptr, dF, st);
+    launch_gemm(kRoleHead, b, b ? dWs : dW, N, K, dX, K, M, none, dP, e, st, dF);
     ok(hipGetLastError());
     ok(hipMemcpyAsync(Y, dY, (size_t)M * N * 4, hipMemcpyDeviceToHost, st));
     ok(hipStreamSynchronize(st));
   }
   (void)hipFree(dW); (void)hipFree(dWs); (void)hipFree(dX); (void)hipFree(dP); (void)hipFree(dY); (void)hipFree(dCnt);
+  (void)hipFree(dF);
   return rc;
 }
 
@@ -1787,6 +1808,14 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
   double bytes = 0;
   const PosRef tpos = abs_pos(c, which == 1 ? ctx_len - M : 0);
   if (which == 1) launch_rope_table(tpos, M, m->hd, g.rope_theta, c->rope_cs, c->st);
+  // more than 4 rows: the projections read activation fragments, as inside a forward (whatever the workspaces hold)
+  const bool fr = b && M > 4 && which <= 4;
+  if (fr) {
+    launch_split_frag(c->x, d, M, d, nullptr, c->xf, c->st);
+    launch_split_frag(c->attn_out, d, M, d, nullptr, c->af, c->st);
+    launch_split_frag(c->h, f, M, f, nullptr, c->hf, c->st);
+  }
+  const uint4 *xf = fr ? c->xf : nullptr, *af = fr ? c->af : nullptr, *hf = fr ? c->hf : nullptr;
   for (int pass = 0; pass < 2; ++pass) {          // pass 0 = warm-up of one launch per layer
     const int n = pass ? reps : (which >= 6 ? 1 : g.n_layers);
     if (pass) HIPCHK(c, hipEventRecord(c->ev[0], c->st));
@@ -1809,11 +1838,11 @@ int stairs_time_kernel(stairs_ctx* c, int32_t which, int32_t M, int32_t ctx_len,
       e.hd = m->hd;
       e.ssq_out = c->ssq;
       switch (which) {
-        case 0: e.out = c->h; launch_gemm(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, none, c->partial, e, c->st); bytes = 2.0 * f * d * esz; break;
-        case 1: e.out = c->q_rot; launch_gemm(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, none, c->partial, e, c->st); bytes = 3.0 * d * d * esz; break;
-        case 2: e.out = c->x; launch_gemm(kRoleWo, b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, e, c->st); bytes = 1.0 * d * d * esz; break;
-        case 3: e.out = c->x; launch_gemm(kRoleDown, b, ly.wdown, d, f, c->h, f, M, none, c->partial, e, c->st); bytes = 1.0 * d * f * esz; break;
-        case 4: e.out = c->logits; launch_gemm(kRoleHead, b, m->lm_head, V, d, c->x, d, M, none, c->partial, e, c->st); bytes = 1.0 * V * d * esz; break;
+        case 0: e.out = c->h; launch_gemm(kRoleGateUp, b, ly.wgu, 2 * f, d, c->x, d, M, none, c->partial, e, c->st, xf); bytes = 2.0 * f * d * esz; break;
+        case 1: e.out = c->q_rot; launch_gemm(kRoleQKV, b, ly.wqkv, 3 * d, d, c->x, d, M, none, c->partial, e, c->st, xf); bytes = 3.0 * d * d * esz; break;
+        case 2: e.out = c->x; launch_gemm(kRoleWo, b, ly.wo, d, d, c->attn_out, d, M, none, c->partial, e, c->st, af); bytes = 1.0 * d * d * esz; break;
+        case 3: e.out = c->x; launch_gemm(kRoleDown, b, ly.wdown, d, f, c->h, f, M, none, c->partial, e, c->st, hf); bytes = 1.0 * d * f * esz; break;
+        case 4: e.out = c->logits; launch_gemm(kRoleHead, b, m->lm_head, V, d, c->x, d, M, none, c->partial, e, c->st, xf); bytes = 1.0 * V * d * esz; break;
         case 6:
         case 7: {
           // a whole forward of M rows ending at position ctx_len-1 (all rows' logits for the

@@ -20,6 +20,8 @@ constexpr int kSpwRows = 9;         // 9..16 rows: a split-K work-group takes tw
 // two work-groups per CU, the residual-writing ones (one work-group per CU) take most of the CU's LDS
 constexpr size_t kRowsPathMaxLds = 68 * 1024;
 constexpr size_t kRowsPathMaxLdsWide = 150 * 1024;
+constexpr size_t kWideMaxLds = 150 * 1024;      // chunk sums of k_gemm_bf16_wide: chunks * rows * 16 NT * 4 bytes
+constexpr int kWideDepth8 = 2, kWideDepth4 = 3, kWideDepth2 = 5, kWideDepth1 = 8;   // k-steps in flight per wave at 4 / 2 / 1 tiles per wave
 constexpr size_t kRowsPathSmallMatrix = 16u << 20;   // residual-writing projections with fewer tiles than CUs: up to this many bytes
 
 // Where the rows of a forward sit.  One sequence (rps == 0): row r is at position *base + offset + r (base lives
@@ -96,6 +98,10 @@ struct GemmEpi {
   float* Vc32;
   int cap, H, hd;
   size_t kv_slot_stride;    // elements between the caches of consecutive slots (several sequences), else unused
+  // k_gemm_bf16_wide, residual-writing and gate/up roles: where the fragments of the result go for the next
+  // projection (see frag_bytes), with frag_gain[k] folded in; nullptr: none
+  uint4* frag_out;
+  const float* frag_gain;
   int act;                  // Head role only: kActNone / kActRelu
   int stream_weights;       // bf16: read the weights with the streaming hint (models far larger than the memory-side cache)
 };
@@ -103,8 +109,18 @@ struct GemmEpi {
 // ---- skinny GEMM + epilogue ---------------------------------------------------------------
 // bf16: W is swizzled, split-K slices of 512 k, epilogue fused; fp32: W row-major, epilogue in a
 // second kernel.  partial: scratch of gemm_slices() * M * N floats.
+// xfrag (bf16, M > 4): the fragments of X with nrm.gain folded in, left by X's producer or by launch_split_frag; with
+// them the launch takes the hand-off-free kernel k_gemm_bf16_wide (no partial sums), without them the split-K kernel.
 void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M,
-                 RowNorm nrm, float* partial, const GemmEpi& epi, hipStream_t st);
+                 RowNorm nrm, float* partial, const GemmEpi& epi, hipStream_t st, const uint4* xfrag = nullptr);
+
+// Activation fragments of a [M <= 32, K] block: K / 32 k-steps x 2 column tiles x (high, low) x 1 KiB
+// (+ kFragChunkPad uint4 after every 16 k-steps: the k chunks the waves of a work-group read at the same time then do
+// not sit a power of two apart)
+constexpr int kFragChunkPad = 272;
+inline size_t frag_bytes(int K) { return ((size_t)(K / 32) * 256 + (size_t)(K / 512 + 1) * kFragChunkPad) * 16; }
+// frag = fragments of x [M, K] (row stride ldx) times gain (nullptr: none)
+void launch_split_frag(const float* X, int ldx, int M, int K, const float* gain, uint4* frag, hipStream_t st);
 
 // The next bf16 launch_gemm records `start` at the beginning and `stop` at the end of its kernel (the events of the
 // launch itself, not records around it in the stream); one launch only.  Measurement aid.
@@ -115,7 +131,8 @@ void set_gemm_launch_events(hipEvent_t start, hipEvent_t stop);
 // [0, vocab)), plus sum-of-squares partials; the same launch fills the rotation table cs of the M positions (see
 // launch_rope_table); theta <= 0: the identity rotation (1, 0).  tok_cap = ints one sequence's token array holds.
 void launch_embed(const void* emb, int emb_bf16, const int* tokens, int tok_slot_stride, int tok_cap, int vocab, PosRef pos,
-                  int M, int d, float* x, float* ssq_part, int hd, float theta, float2* cs, hipStream_t st);
+                  int M, int d, float* x, float* ssq_part, int hd, float theta, float2* cs, hipStream_t st,
+                  uint4* frag = nullptr, const float* frag_gain = nullptr);   // bf16: also the fragments of x * frag_gain
 // cs[m][i] = (cos, sin)((pos+m) * theta^(-2i/hd)), angle formed in double
 void launch_rope_table(PosRef pos, int M, int hd, float theta, float2* cs, hipStream_t st);
 // split-KV attention of M query rows at positions pos..pos+M-1 against keys 0..pos+M-1
@@ -128,11 +145,12 @@ struct AttnMode {
   const float* bias;  // nullptr, or [H][bias_ld]: score += bias[h][key position - query position + bias_zero]
   int bias_ld, bias_zero;
   int kv_fixed;       // > 0: no causal mask, every row sees the keys 0 .. kv_fixed-1 (nchunk_launch must cover them)
+  uint4* frag_out;    // half caches: also leave the output's activation fragments here (nullptr: none)
 };
 void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv_half, int cap, int d, int H, int M,
                       PosRef pos, int nslots, size_t kv_slot_stride, int nchunk_launch, int nchunk_cap, float* part_o,
                       float* part_ml, int* counters, float* out, hipStream_t st,
-                      const AttnMode& am = AttnMode{0.f, nullptr, 0, 0, 0});
+                      const AttnMode& am = AttnMode{0.f, nullptr, 0, 0, 0, nullptr});
 // out[o(r)] = argmax_v logits[row0 + r * row_stride][v], ties -> lowest v, r < nrows.  One sequence:
 // o(r) = *out_pos.base + out_pos.offset + r (base == nullptr: r).  Several: o(r) = s * out_slot_stride + position of
 // out_pos for row r, nothing written for a slot that is not active.

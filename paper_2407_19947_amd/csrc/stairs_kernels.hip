@@ -11,6 +11,11 @@
 #include <hip/hip_ext.h>
 
 #include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+#include <algorithm>
+#include <vector>
 
 namespace stairs {
 
@@ -38,6 +43,37 @@ __device__ __forceinline__ uint32_t bf16_pack2_rne(float a, float b) {
 __device__ __forceinline__ void bf16_split2(float a, float b, uint32_t& hi, uint32_t& lo) {
   hi = bf16_pack2_rne(a, b);
   lo = bf16_pack2_rne(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
+}
+
+// Activation fragments: the MFMA B operand of a forward with more than 4 rows is formed ONCE by whoever produces the
+// activation (embedding gather, attention, the previous projection's epilogue) and kept beside the fp32 values as
+// [k-step of 32][column tile of 16 rows (2)][high, low][lane] x 16 bytes: lane r + 16 g of k-step kt holds
+// x[16 ct + r][32 kt + 8 g .. + 8] * gain as bf16 (high part) and the bf16 of the remainders (low part), the very
+// values split_bf16x8 gives.  A consumer wave loads a fragment as one coalesced 1 KiB read.
+__device__ __forceinline__ size_t frag_off(int m, int k) {        // in units of 8 bytes: 4 consecutive k of row m, high part
+  return ((((size_t)(k >> 5) * 2 + (m >> 4)) * 2) * 64 + (size_t)(k >> 9) * kFragChunkPad + (m & 15) + 16 * ((k & 31) >> 3)) * 2 +
+         ((k & 7) >> 2);
+}
+// row m, columns k .. k+3 (k a multiple of 4); g = the gain of those columns or nullptr
+__device__ __forceinline__ void store_frag4(uint4* frag, int m, int k, float4 v, const float* gain) {
+  if (gain) {
+    const float4 g = *reinterpret_cast<const float4*>(gain + k);
+    v.x = v.x * g.x; v.y = v.y * g.y; v.z = v.z * g.z; v.w = v.w * g.w;
+  }
+  uint2 hi, lo;
+  bf16_split2(v.x, v.y, hi.x, lo.x);
+  bf16_split2(v.z, v.w, hi.y, lo.y);
+  uint2* dst = reinterpret_cast<uint2*>(frag) + frag_off(m, k);
+  dst[0] = hi;
+  dst[128] = lo;                                               // the low fragment follows 64 lanes x 16 bytes later
+}
+// row m, columns k, k+1 (k even)
+__device__ __forceinline__ void store_frag2(uint4* frag, int m, int k, float a, float b) {
+  uint32_t hi, lo;
+  bf16_split2(a, b, hi, lo);
+  uint32_t* dst = reinterpret_cast<uint32_t*>(reinterpret_cast<uint2*>(frag) + frag_off(m, k & ~3)) + ((k & 3) >> 1);
+  dst[0] = hi;
+  dst[256] = lo;
 }
 
 __device__ __forceinline__ float load_kv(const float* p) { return *p; }
@@ -305,6 +341,7 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
         a.x += r.x; a.y += r.y; a.z += r.z; a.w += r.w;
         *xp = a;
         ss = sumsq4(a.x, a.y, a.z, a.w);
+        if (epi.frag_out) store_frag4(epi.frag_out, m, col, a, epi.frag_gain);
       }
       ss += __shfl_xor(ss, 1);
       ss += __shfl_xor(ss, 2);
@@ -327,6 +364,7 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
         }
         const float4 o = make_float4(swiglu(g.x, u.x), swiglu(g.y, u.y), swiglu(g.z, u.z), swiglu(g.w, u.w));
         *reinterpret_cast<float4*>(epi.out + (size_t)m * f + (gcol >> 4) * 8 + (gcol & 7)) = o;
+        if (epi.frag_out) store_frag4(epi.frag_out, m, (gcol >> 4) * 8 + (gcol & 7), o, nullptr);
       }
     }
   } else {   // kRoleQKV: rotate q and k, append k and v to the cache
@@ -802,6 +840,266 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// The hand-off-free GEMM for more than 4 rows (M <= 32): a work-group owns NT adjacent 16-row weight tiles over the
+// WHOLE k range, its waves split the 512-wide k chunks between them, and a wave feeds every k-step's weight tiles
+// with the activation fragments their producer left in memory (see frag_off): per k-step NT coalesced 1 KiB reads of
+// weights (HBM) and 2 CT of fragments (L2), no conversion, nothing staged in LDS, no barrier before the first MFMA.
+// A fragment is shared by the wave's NT tiles.  The chunk sums meet in LDS as in k_gemm_bf16_rows and the epilogue
+// runs in the same work-group: no partial sums in memory, no ticket.  Chunk boundaries, the MFMA order inside a chunk
+// and the order of the chunk sums are those of the other two kernels: all three give the same bits for a row.
+//   CT = 16-row column tiles (rows of x) per MFMA pass: 1 (M <= 16) or 2; DEPTH = k-steps whose loads are in flight
+//   LDS: chunk sums float [chunks][M][NT * 16]
+// The epilogue can leave the fragments of ITS result for the next projection (epi.frag_out, with epi.frag_gain
+// folded in): residual stream and SwiGLU output.
+// ---------------------------------------------------------------------------------------
+// 1/rms of the rows for a work-group of any size: half a wave per row, the additions in the order of rows_rstd
+__device__ __forceinline__ void rows_rstd_any(const RowNorm& nrm, int M, int K, float* s_rstd) {
+  const int pl = threadIdx.x & 31, hw = threadIdx.x >> 5, nhw = blockDim.x >> 5;
+  for (int m = hw; m < M; m += nhw) {
+    const float* sp = nrm.ssq_part + (size_t)m * nrm.ssq_n;
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = sp[min(pl + 32 * i, nrm.ssq_n - 1)];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ss += (pl + 32 * i < nrm.ssq_n) ? v[i] : 0.f;
+    for (int p0 = pl + 256; p0 < nrm.ssq_n; p0 += 256) {
+      float u[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) u[i] = (p0 + 32 * i < nrm.ssq_n) ? sp[p0 + 32 * i] : 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ss += u[i];
+    }
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    if (pl == 0) s_rstd[m] = 1.0f / sqrtf(ss / (float)K + nrm.eps);
+  }
+}
+
+// The epilogue of gemm_epilogue with the chunk sums in LDS ([chunk][M][W] floats) instead of partial sums in memory;
+// run by all threads of the work-group.  The additions are those of slice_sum<true>: chunk pairs first.
+template <int ROLE, int W>
+__device__ __forceinline__ void gemm_epilogue_lds(const float* csum, int nchunks, int M, int N, int c0, const GemmEpi& epi,
+                                                  const float* rs) {
+  const int tid = threadIdx.x, nth = blockDim.x;
+  const int cstride = M * W;
+  auto sum4 = [&](int m, int lc) {
+    const float* src = csum + m * W + lc;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c = 0; c < nchunks; c += 2) {
+      const float4 p = *reinterpret_cast<const float4*>(src + c * cstride);
+      if (c + 1 < nchunks) {
+        const float4 q = *reinterpret_cast<const float4*>(src + (c + 1) * cstride);
+        a.x += p.x + q.x; a.y += p.y + q.y; a.z += p.z + q.z; a.w += p.w + q.w;
+      } else {
+        a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+      }
+    }
+    return a;
+  };
+  auto sum1 = [&](int m, int lc) {
+    const float* src = csum + m * W + lc;
+    float a = 0.f;
+    for (int c = 0; c < nchunks; c += 2) a += (c + 1 < nchunks) ? (src[c * cstride] + src[(c + 1) * cstride]) : src[c * cstride];
+    return a;
+  };
+  if (ROLE == kRoleHead) {
+    constexpr int PR = W / 4;
+    for (int idx = tid; idx < M * PR; idx += nth) {
+      const int m = idx / PR, lc = (idx - m * PR) * 4, col = c0 + lc;
+      if (col < N) {
+        float4 a = sum4(m, lc);
+        if (rs) { const float r = rs[m]; a.x *= r; a.y *= r; a.z *= r; a.w *= r; }
+        if (epi.act == kActRelu) a = make_float4(fmaxf(a.x, 0.f), fmaxf(a.y, 0.f), fmaxf(a.z, 0.f), fmaxf(a.w, 0.f));
+        *reinterpret_cast<float4*>(epi.out + (size_t)m * N + col) = a;
+      }
+    }
+  } else if (ROLE == kRoleWo || ROLE == kRoleDown) {
+    constexpr int PR = W / 4;                       // 4 adjacent threads = one 16-column tile
+    const int total = M * PR;
+    for (int idx0 = 0; idx0 < total; idx0 += nth) {
+      const int idx = idx0 + tid;
+      const int m = idx / PR, lc = (idx - m * PR) * 4, col = c0 + lc;
+      float ss = 0.f;
+      if (idx < total && col < N) {
+        float4 a = sum4(m, lc);
+        if (rs) { const float q = rs[m]; a.x *= q; a.y *= q; a.z *= q; a.w *= q; }
+        float4* xp = reinterpret_cast<float4*>(epi.out + (size_t)m * N + col);
+        const float4 r = *xp;
+        a.x += r.x; a.y += r.y; a.z += r.z; a.w += r.w;
+        *xp = a;
+        ss = sumsq4(a.x, a.y, a.z, a.w);
+        if (epi.frag_out) store_frag4(epi.frag_out, m, col, a, epi.frag_gain);
+      }
+      ss += __shfl_xor(ss, 1);
+      ss += __shfl_xor(ss, 2);
+      if (idx < total && col < N && (idx & 3) == 0) epi.ssq_out[m * (N >> 4) + (col >> 4)] = ss;
+    }
+  } else if (ROLE == kRoleGateUp) {
+    constexpr int PR = W / 8;
+    const int f = N / 2;
+    for (int idx = tid; idx < M * PR; idx += nth) {
+      const int m = idx / PR, r = idx - m * PR;
+      const int lc = 16 * (r >> 1) + 4 * (r & 1), gcol = c0 + lc;
+      if (gcol < N) {
+        float4 g = sum4(m, lc);
+        float4 u = sum4(m, lc + 8);
+        if (rs) {
+          const float q = rs[m];
+          g.x *= q; g.y *= q; g.z *= q; g.w *= q;
+          u.x *= q; u.y *= q; u.z *= q; u.w *= q;
+        }
+        const float4 o = make_float4(swiglu(g.x, u.x), swiglu(g.y, u.y), swiglu(g.z, u.z), swiglu(g.w, u.w));
+        *reinterpret_cast<float4*>(epi.out + (size_t)m * f + (gcol >> 4) * 8 + (gcol & 7)) = o;
+        if (epi.frag_out) store_frag4(epi.frag_out, m, (gcol >> 4) * 8 + (gcol & 7), o, nullptr);
+      }
+    }
+  } else {   // kRoleQKV
+    constexpr int PR = W / 2;
+    for (int idx = tid; idx < M * PR; idx += nth) {
+      const int m = idx / PR, r = idx - m * PR;
+      const int lc = 16 * (r >> 3) + (r & 7), col = c0 + lc;
+      if (col < N) {
+        float a = sum1(m, lc);
+        float b = sum1(m, lc + 8);
+        if (rs) { a *= rs[m]; b *= rs[m]; }
+        qkv_pair(a, b, m, col, N / 3, epi);
+      }
+    }
+  }
+}
+
+template <int CT, int NT, int DEPTH, bool STREAM>
+__global__ __launch_bounds__(512) void k_gemm_bf16_wide(const uint4* __restrict__ Wsw, int NTILES,
+                                                        const uint4* __restrict__ XF, int M, RowNorm nrm, int K, int N,
+                                                        int role, GemmEpi epi) {
+  constexpr int RING = DEPTH + 1;
+  constexpr int W = NT * 16;
+  extern __shared__ float csum[];                          // [chunk][M][W]
+  __shared__ float s_rstd[kMaxRows];
+  const int tid = threadIdx.x, lane = tid & 63, NW = blockDim.x >> 6;
+  // (the wave index as a scalar: everything derived from it -- chunk, k-step, addresses -- is then scalar arithmetic)
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j = lane & 15, g = lane >> 4;
+  const int tile0 = blockIdx.x * NT;
+  const int units_total = K / kUnitK;
+  const int nchunks = (units_total + kSliceUnits - 1) / kSliceUnits;
+  const int cpw = (nchunks + NW - 1) / NW;                 // chunks per wave
+  const int c_begin = min(wave * cpw, nchunks), c_end = min(nchunks, c_begin + cpw);
+  const int s_begin = c_begin * 16, s_end = min(K >> 5, c_end * 16);   // this wave's k-steps (32 k each)
+  const bool has_stats = nrm.gain && nrm.ssq_part;
+
+  struct Stage {
+    uint4 a[NT], bh[CT], bl[CT];
+  };
+  // what a k-step needs, requested without conditions (tiles past the end re-read the last one and are dropped
+  // later), so that the outstanding loads can be counted exactly
+  int tile_c[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) tile_c[t] = min(tile0 + t, NTILES - 1);
+  auto load_stage = [&](Stage& st, int s) {
+    const int c = s >> 4, kk = s & 15;
+    const int ksteps_c = min(kSliceUnits, units_total - c * kSliceUnits) * 8;
+    const uint4* wbase = Wsw + (size_t)c * NTILES * (kSliceUnits * 8) * 64 + (size_t)kk * 64 + lane;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const uint4* p = wbase + (size_t)tile_c[t] * ksteps_c * 64;
+      st.a[t] = STREAM ? ld_nt(p) : *p;
+    }
+    const uint4* xb = XF + (size_t)s * 4 * 64 + (size_t)c * kFragChunkPad + lane;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+      st.bh[ct] = xb[(ct * 2) * 64];
+      st.bl[ct] = xb[(ct * 2 + 1) * 64];
+    }
+  };
+
+  f32x4 acc[NT][CT];
+  auto compute_stage = [&](const Stage& st, int s) {
+    if ((s & 15) == 0) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, st.a[t]);
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) {
+        acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, st.bh[ct]), acc[t][ct], 0, 0, 0);
+        acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, st.bl[ct]), acc[t][ct], 0, 0, 0);
+      }
+    }
+    if ((s & 15) == 15 || s == s_end - 1) {                // the chunk is complete (the last one may be short)
+      float* dst = csum + (size_t)(s >> 4) * M * W;
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) {
+        const int m = ct * 16 + j;
+        if (m < M) {
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            *reinterpret_cast<float4*>(dst + m * W + t * 16 + 4 * g) =
+                make_float4(acc[t][ct][0], acc[t][ct][1], acc[t][ct][2], acc[t][ct][3]);
+        }
+      }
+    }
+  };
+
+  Stage st[RING];
+  const bool work = s_begin < s_end;                       // (a wave without k chunks only helps in the epilogue)
+  if (work) {
+#pragma unroll
+    for (int i = 0; i < DEPTH; ++i) load_stage(st[i], min(s_begin + i, s_end - 1));
+  }
+  // the rows' 1/rms, needed by the epilogue only: its loads go out behind the first weight requests and come back
+  // (from L2) long before those
+  if (has_stats) rows_rstd_any(nrm, M, K, s_rstd);
+  if (work) {
+    // whole turns of the ring without a condition around a request (a branch would make the compiler assume the
+    // fewest outstanding loads at every join and wait for nearly all of them); the last DEPTH or fewer k-steps have
+    // been requested by then
+    int s = s_begin;
+    for (; s + RING <= s_end; s += RING) {
+#pragma unroll
+      for (int i = 0; i < RING; ++i) {
+        load_stage(st[(i + DEPTH) % RING], min(s + i + DEPTH, s_end - 1));
+        __builtin_amdgcn_sched_barrier(0);         // the requests stay in front of the arithmetic they overlap with
+        compute_stage(st[i], s + i);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < DEPTH; ++i)
+      if (s + i < s_end) compute_stage(st[i], s + i);
+  }
+  __syncthreads();
+
+  const float* rs = has_stats ? s_rstd : nullptr;
+  const int c0 = tile0 * 16;
+  switch (role) {
+    case kRoleQKV: gemm_epilogue_lds<kRoleQKV, W>(csum, nchunks, M, N, c0, epi, rs); break;
+    case kRoleWo:
+    case kRoleDown: gemm_epilogue_lds<kRoleWo, W>(csum, nchunks, M, N, c0, epi, rs); break;
+    case kRoleGateUp: gemm_epilogue_lds<kRoleGateUp, W>(csum, nchunks, M, N, c0, epi, rs); break;
+    default: gemm_epilogue_lds<kRoleHead, W>(csum, nchunks, M, N, c0, epi, rs); break;
+  }
+}
+
+// x [M, K] (row stride ldx) -> its fragments, gain folded in (nullptr: none): for activations whose producer does not
+// leave them itself.  One thread per (row, 4 consecutive k).
+__global__ __launch_bounds__(256) void k_split_frag(const float* __restrict__ X, int ldx, int M, int K,
+                                                    const float* __restrict__ gain, uint4* __restrict__ frag) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int k4 = K >> 2;
+  if (idx >= M * k4) return;
+  const int m = idx / k4, k = (idx - m * k4) * 4;
+  store_frag4(frag, m, k, *reinterpret_cast<const float4*>(X + (size_t)m * ldx + k), gain);
+}
+void launch_split_frag(const float* X, int ldx, int M, int K, const float* gain, uint4* frag, hipStream_t st) {
+  hipLaunchKernelGGL(k_split_frag, dim3((M * (K / 4) + 255) / 256), dim3(256), 0, st, X, ldx, M, K, gain, frag);
+}
+
 // LDS bytes of k_gemm_bf16_rows, or 0 if this shape does not take that path.  The residual-writing projections
 // have few weight tiles (N = d_model): they run one 8-wave work-group per CU and only when the tiles about
 // cover the chip.
@@ -814,6 +1112,41 @@ static size_t rows_path_lds(int role, int M, int N, int K) {
     return bytes <= kRowsPathMaxLdsWide ? std::max(bytes, (size_t)81 * 1024) : 0;   // > half a CU's LDS: one per CU
   }
   return bytes <= kRowsPathMaxLds ? bytes : 0;
+}
+
+// Launch shape of k_gemm_bf16_wide: NT weight tiles per wave and NW waves that split the k chunks; nt == 0: the
+// split-K kernel instead.  Measured on 7B-class projections (isolated launches, 8 / 17 rows, microseconds; split-K
+// in brackets): gate/up 1376 tiles 8/4 33 / 46 (37 / 48), unembedding 2000 tiles 8/4 41 / 55 (48 / 63), QKV 768 tiles
+// 4/4 21 / 30 (23 / 33), attention-out 256 tiles 1/8 10.4 / 24 (11.4 / 15.4), down 256 tiles and 22 chunks 1/4 23 /
+// 38 (21 / 34).  More tiles per wave means fewer fragment reads per weight byte (2 CT / NT), which is what the
+// launches with many tiles are bound by beyond the weight stream; with few tiles (N = d_model) there are too few
+// work-groups for that and split-K's extra parallelism wins once the fragments double (more than 16 rows) or k is long.
+struct WideCfg { int nt, nw; };
+static WideCfg wide_cfg(int role, int M, int NTILES, int K) {
+  // STAIRS_WIDE_CFG="nt/nw,nt/nw,nt/nw,nt/nw,nt/nw" (QKV, out, gate-up, down, head; nt = 0: split-K) overrides the
+  // choice: tuning aid
+  static const std::vector<WideCfg> forced = [] {
+    std::vector<WideCfg> v;
+    if (const char* e = getenv("STAIRS_WIDE_CFG")) {
+      int nt = 0, nw = 0, n = 0;
+      while (sscanf(e, "%d/%d%n", &nt, &nw, &n) == 2) {
+        v.push_back({nt, nw});
+        e += n;
+        if (*e == ',') ++e;
+      }
+    }
+    return v;
+  }();
+  const int nchunks = gemm_slices(K, 1);
+  WideCfg c{0, 0};
+  if (NTILES >= 1024) c = {8, std::min(4, nchunks)};
+  else if (NTILES >= 512) c = {4, std::min(4, nchunks)};
+  else if (NTILES >= 192 && M <= 16 && nchunks <= 8) c = {1, std::min(8, nchunks)};
+  if ((int)forced.size() == 5) {
+    const WideCfg f = forced[role];
+    if ((f.nt == 0 || f.nt == 1 || f.nt == 2 || f.nt == 4 || f.nt == 8) && f.nw >= 1 && f.nw <= 8) c = f;
+  }
+  return c;
 }
 
 // fp32 weights, row-major: one wave per output feature, lanes stride over k.
@@ -889,7 +1222,7 @@ static void launch_gemm_kernel(F kernel, dim3 grid, dim3 block, size_t lds, hipS
 }
 
 void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M, RowNorm nrm,
-                 float* partial, const GemmEpi& epi, hipStream_t st) {
+                 float* partial, const GemmEpi& epi, hipStream_t st, const uint4* xfrag) {
   if (!dtype_bf16) {
     dim3 grid((N + 3) / 4), block(256);
     const float* Wf = static_cast<const float*>(W);
@@ -941,6 +1274,35 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
     else { STAIRS_ROWS_ROLE(kRoleDown, 8, 3); }
 #undef STAIRS_ROWS_ROLE
 #undef STAIRS_ROWS
+    return;
+  }
+  // more than 4 rows with the activation fragments at hand: the hand-off-free kernel
+  WideCfg wc = wide_cfg(role, M, NTILES, K);
+  const int nchunks = gemm_slices(K, 1);
+  auto wide_lds = [&](int nt) { return (size_t)nchunks * M * nt * 16 * sizeof(float); };
+  while (wc.nt > 1 && wide_lds(wc.nt) > kWideMaxLds) wc.nt /= 2;      // very long k: fewer tiles per work-group
+  if (xfrag && wc.nt > 0 && wide_lds(wc.nt) <= kWideMaxLds) {
+    const int CT = (M <= 16) ? 1 : 2;
+    dim3 grid((NTILES + wc.nt - 1) / wc.nt), block(64 * wc.nw);
+    const size_t lds = wide_lds(wc.nt);
+#define STAIRS_WIDE(ct, nt, dp)                                                                                          \
+  do {                                                                                                                   \
+    if (epi.stream_weights)                                                                                              \
+      launch_gemm_kernel(k_gemm_bf16_wide<ct, nt, dp, true>, grid, block, lds, st, Wsw, NTILES, xfrag, M, nrm, K, N,     \
+                         role, epi);                                                                                     \
+    else                                                                                                                 \
+      launch_gemm_kernel(k_gemm_bf16_wide<ct, nt, dp, false>, grid, block, lds, st, Wsw, NTILES, xfrag, M, nrm, K, N,    \
+                         role, epi);                                                                                     \
+  } while (0)
+#define STAIRS_WIDE_CT(nt, dp)       \
+  if (CT == 1) STAIRS_WIDE(1, nt, dp); \
+  else STAIRS_WIDE(2, nt, dp)
+    if (wc.nt == 8) { STAIRS_WIDE_CT(8, kWideDepth8); }
+    else if (wc.nt == 4) { STAIRS_WIDE_CT(4, kWideDepth4); }
+    else if (wc.nt == 2) { STAIRS_WIDE_CT(2, kWideDepth2); }
+    else { STAIRS_WIDE_CT(1, kWideDepth1); }
+#undef STAIRS_WIDE_CT
+#undef STAIRS_WIDE
     return;
   }
   // 9..16 rows: a work-group takes two k chunks and writes the sum of the pair (half the partial sums in memory;
@@ -1103,7 +1465,8 @@ template <typename E, int GW>
 __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const int* __restrict__ tokens,
                                                int tok_slot_stride, int tok_cap, int vocab, PosRef pos, int d,
                                                float* __restrict__ x, float* __restrict__ ssq_part, int ssq_n, int hd,
-                                               double theta, float2* __restrict__ cs) {
+                                               double theta, float2* __restrict__ cs, uint4* frag,
+                                               const float* __restrict__ frag_gain) {
   __shared__ float sm[4];
   const int m = blockIdx.y;
   const int p = pos_of(pos, m);
@@ -1127,6 +1490,7 @@ __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const 
     }
     *reinterpret_cast<float4*>(x + (size_t)m * d + c) = v;
     ss = (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+    if (frag) store_frag4(frag, m, c, v, frag_gain);
   }
   if (GW == 1024) {
     ss = block_sum_256(ss, sm);
@@ -1139,15 +1503,16 @@ __global__ __launch_bounds__(256) void k_embed(const E* __restrict__ emb, const 
 }
 
 void launch_embed(const void* emb, int emb_bf16, const int* tokens, int tok_slot_stride, int tok_cap, int vocab, PosRef pos,
-                  int M, int d, float* x, float* ssq_part, int hd, float theta, float2* cs, hipStream_t st) {
+                  int M, int d, float* x, float* ssq_part, int hd, float theta, float2* cs, hipStream_t st, uint4* frag,
+                  const float* frag_gain) {
   dim3 grid((d + 1023) / 1024 + 1, M), block(256);
   const int sn = ssq_groups(d, emb_bf16);
   if (emb_bf16)
     hipLaunchKernelGGL((k_embed<uint16_t, 16>), grid, block, 0, st, static_cast<const uint16_t*>(emb), tokens,
-                       tok_slot_stride, tok_cap, vocab, pos, d, x, ssq_part, sn, hd, (double)theta, cs);
+                       tok_slot_stride, tok_cap, vocab, pos, d, x, ssq_part, sn, hd, (double)theta, cs, frag, frag_gain);
   else
     hipLaunchKernelGGL((k_embed<float, 1024>), grid, block, 0, st, static_cast<const float*>(emb), tokens,
-                       tok_slot_stride, tok_cap, vocab, pos, d, x, ssq_part, sn, hd, (double)theta, cs);
+                       tok_slot_stride, tok_cap, vocab, pos, d, x, ssq_part, sn, hd, (double)theta, cs, nullptr, nullptr);
 }
 
 __global__ void k_rope_table(PosRef pos, int hd, double theta, float2* __restrict__ cs) {
@@ -1334,7 +1699,7 @@ constexpr int kMergeCB = 20;
 template <int HD>
 __device__ __forceinline__ void attn_merge(const float* part_o, const float* part_ml, int H, int h, int M, int pos0, int step,
                                            int kv_len, int nchunk_cap, int nch_lds, int rows_per_pass, float* out, int d,
-                                           float* s_ml) {
+                                           float* s_ml, uint4* frag, int frag_row0) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nch_max = (kv_len > 0) ? (kv_len - 1) / kAttnChunk + 1 : 0;
   float* grp = s_ml + (size_t)M * nch_lds * 2 + kMaxRows;   // (kMaxRows floats after the table stay unused)
@@ -1395,6 +1760,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
         res = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
       }
       *reinterpret_cast<float4*>(out + (size_t)m * d + h * HD + e) = res;
+      if (frag) store_frag4(frag, frag_row0 + m, h * HD + e, res, nullptr);
     }
     return;
   }
@@ -1429,6 +1795,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
         res = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
       }
       *reinterpret_cast<float4*>(out + (size_t)m * d + h * HD + e) = res;
+      if (frag) store_frag4(frag, frag_row0 + m, h * HD + e, res, nullptr);
     }
     __syncthreads();
   }
@@ -1604,6 +1971,7 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
           float2 res = make_float2(0.f, 0.f);
           if (pos0 + m * step >= 0) res = make_float2(o0 / lc, o1 / lc);
           *reinterpret_cast<float2*>(out + (size_t)m * d + h * HD + e) = res;
+          if (am.frag_out) store_frag2(am.frag_out, row0 + m, h * HD + e, res.x, res.y);
         } else {
           st_dev2(&part_o[(((size_t)m * H + h) * nchunk_cap + c) * HD + e], o0, o1);
           // the thread with the row's first dims also leaves the chunk's (max, sum) pair
@@ -1617,7 +1985,8 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
   if (!FUSED || single) return;
   if (!last_arrival(&counters[h], (int)gridDim.x, &s_last)) return;
   extern __shared__ float s_ml[];
-  attn_merge<HD>(part_o, part_ml, H, h, M, pos0, step, kv_len, nchunk_cap, (int)gridDim.x, rows_per_pass, out, d, s_ml);
+  attn_merge<HD>(part_o, part_ml, H, h, M, pos0, step, kv_len, nchunk_cap, (int)gridDim.x, rows_per_pass, out, d, s_ml,
+                 am.frag_out, row0);
   if (tid == 0) counters[h] = 0;
 }
 
@@ -1625,13 +1994,14 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
 template <int HD>
 __global__ __launch_bounds__(256) void k_attn_merge(const float* part_o, const float* part_ml, int d, int H, int M, PosRef pos,
                                                     int kv_fixed, int nchunk_cap, int nch_lds, int rows_per_pass,
-                                                    float* __restrict__ out) {
+                                                    float* __restrict__ out, uint4* frag) {
   extern __shared__ float s_ml[];
   const int h = blockIdx.x, row0 = blockIdx.y * M;
   const bool fixed = kv_fixed > 0;
   const int pos0 = fixed ? kv_fixed - 1 : pos_of(pos, row0);
   attn_merge<HD>(part_o + (size_t)row0 * H * nchunk_cap * HD, part_ml + (size_t)row0 * H * nchunk_cap * 2, H, h, M, pos0,
-                 fixed ? 0 : 1, pos0 + (fixed ? 1 : M), nchunk_cap, nch_lds, rows_per_pass, out + (size_t)row0 * d, d, s_ml);
+                 fixed ? 0 : 1, pos0 + (fixed ? 1 : M), nchunk_cap, nch_lds, rows_per_pass, out + (size_t)row0 * d, d, s_ml,
+                 frag, row0);
 }
 
 // Attention of a prefill block (R consecutive rows at positions p0 .. p0+R-1 of one sequence) without partial
@@ -1804,7 +2174,7 @@ void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv
     hipLaunchKernelGGL((k_attn_f16<hdv, ct, false>), grid, block, 0, st, q_rot, K, V, cap, d, H, M, pos, kv_slot_stride,    \
                        scale, am, nchunk_cap, rpp, part_o, part_ml, counters, out);                                         \
     hipLaunchKernelGGL((k_attn_merge<hdv>), dim3(H, nslots), dim3(256), lds, st, part_o, part_ml, d, H, M, pos,             \
-                       am.kv_fixed, nchunk_cap, nchunk_launch, rpp, out);                                                   \
+                       am.kv_fixed, nchunk_cap, nchunk_launch, rpp, out, am.frag_out);                                      \
   }
     if (hd == 128) {
       if (M <= 16) STAIRS_ATTN16(128, 1) else STAIRS_ATTN16(128, 2)
@@ -2248,6 +2618,14 @@ hipError_t configure_kernels() {
   STAIRS_OPTIN(4);
 #undef STAIRS_OPTIN2
 #undef STAIRS_OPTIN
+#define STAIRS_OPTIN_WIDE(ct, nt, dp)                                            \
+  optin((const void*)k_gemm_bf16_wide<ct, nt, dp, true>, kWideMaxLds);            \
+  optin((const void*)k_gemm_bf16_wide<ct, nt, dp, false>, kWideMaxLds)
+  STAIRS_OPTIN_WIDE(1, 8, kWideDepth8); STAIRS_OPTIN_WIDE(2, 8, kWideDepth8);
+  STAIRS_OPTIN_WIDE(1, 4, kWideDepth4); STAIRS_OPTIN_WIDE(2, 4, kWideDepth4);
+  STAIRS_OPTIN_WIDE(1, 2, kWideDepth2); STAIRS_OPTIN_WIDE(2, 2, kWideDepth2);
+  STAIRS_OPTIN_WIDE(1, 1, kWideDepth1); STAIRS_OPTIN_WIDE(2, 1, kWideDepth1);
+#undef STAIRS_OPTIN_WIDE
   // the stand-alone attention merge keeps a table of all chunks in LDS: large for long contexts (the fused
   // merge runs for at most kAttnFusedMaxChunks chunks and stays small)
   optin((const void*)k_attn_merge<128>, kAttnMergeMaxLds);
