@@ -265,6 +265,22 @@ int stairs_get_tokens(stairs_ctx *ctx, int32_t *out, int32_t cap, int32_t *len);
 int stairs_gemm_host(int32_t dtype, const void *W, const float *X, float *Y, int32_t M, int32_t N,
                      int32_t K, void *hip_stream);
 
+/* stairs_gemm_host for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same kernels, but W [N, K] (row-major, `dtype`), X [M, K] and Y [M, N]
+ * (float) are DEVICE pointers the caller owns, and everything stairs_gemm_host allocates per call (hand-off counters,
+ * partial sums, the re-laid-out bf16 weights, the activation fragments) lives in a fixed device array inside the
+ * library (about 9.3 MiB per GPU the call is used on, held until the process ends).  The call allocates nothing,
+ * frees nothing and does not wait: the work is enqueued on hip_stream (a hipStream_t or NULL) and Y is valid once
+ * that stream has reached the end of it.  Limits (ECAPACITY beyond them): K <= STAIRS_GEMM_DEVICE_MAX_K; bf16:
+ * N * K * 2 <= STAIRS_GEMM_DEVICE_MAX_WEIGHT; ceil(K / 512) * M * N * 4 (bf16) or M * N * 4 (fp32) <=
+ * STAIRS_GEMM_DEVICE_MAX_PARTIAL; shape rules as stairs_gemm_host (EINVAL).  All calls on one GPU share the one
+ * array: calls that overlap on a GPU (two streams, two threads) race; issue them on one stream or order them. */
+#define STAIRS_GEMM_DEVICE_MAX_K        8192
+#define STAIRS_GEMM_DEVICE_MAX_WEIGHT   (4u << 20)
+#define STAIRS_GEMM_DEVICE_MAX_PARTIAL  (4u << 20)
+int stairs_gemm_device(int32_t dtype, const void *W, const float *X, float *Y, int32_t M, int32_t N,
+                       int32_t K, void *hip_stream);
+
 /* Time `reps` back-to-back launches of one kernel of the target's forward at M rows, cycling
  * through the layers so that the weights come from HBM, bracketed by HIP events on the
  * context's stream.  which: 0 = gate/up projection GEMM (the largest), 1 = QKV GEMM,

@@ -18,7 +18,7 @@ DTYPE_FP32, DTYPE_BF16 = 0, 1
 EXPORTED_SYMBOLS = [
     "stairs_strerror", "stairs_last_error", "stairs_init", "stairs_free", "stairs_prefill",
     "draft_propose", "stairs_verify", "stairs_verify_tokens", "stairs_generate", "stairs_decode", "stairs_decode_adaptive", "stairs_reserve_batch", "stairs_generate_batch",
-    "stairs_get_tokens", "stairs_gemm_host", "stairs_time_kernel", "stairs_copy_probe",
+    "stairs_get_tokens", "stairs_gemm_host", "stairs_gemm_device", "stairs_time_kernel", "stairs_copy_probe",
     "stairs_encdec_init", "stairs_encode", "stairs_encdec_generate",
     "stairs_decode_sampled", "stairs_generate_sampled", "draft_propose_sampled", "stairs_verify_sampled",
     "stairs_rel_bucket",
@@ -119,6 +119,7 @@ def lib() -> C.CDLL:
     L.stairs_generate_batch.argtypes = [vp, C.POINTER(i32p), i32p, i32, i32, i32, i32p, C.POINTER(StairsStats)]
     L.stairs_get_tokens.argtypes = [vp, i32p, i32, i32p]
     L.stairs_gemm_host.argtypes = [i32, vp, f32p, f32p, i32, i32, i32, vp]
+    L.stairs_gemm_device.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp]
     L.stairs_time_kernel.argtypes = [vp, i32, i32, i32, i32, f32p, C.POINTER(C.c_double)]
     L.stairs_copy_probe.argtypes = [C.c_int64, i32, f32p, vp]
     L.stairs_encdec_init.argtypes = [C.POINTER(vp), C.POINTER(_EncDecCfg), C.POINTER(_EncDecWeights),
@@ -307,6 +308,14 @@ def stairs_gemm_host(W: np.ndarray, X: np.ndarray, stream: Optional[int] = None)
     _check(lib().stairs_gemm_host(dt, C.c_void_p(W.ctypes.data), _ptr(X, C.c_float), _ptr(Y, C.c_float), M, N, K,
                                   stream), "stairs_gemm_host")
     return Y
+
+
+def stairs_gemm_device(dtype: int, W_dev: int, X_dev: int, Y_dev: int, M: int, N: int, K: int,
+                       stream: Optional[int] = None) -> None:
+    """stairs_gemm_host on DEVICE addresses (ints) the caller owns, without any allocation inside the library; the
+    work is enqueued on `stream` and not waited for."""
+    _check(lib().stairs_gemm_device(dtype, C.c_void_p(W_dev), C.c_void_p(X_dev), C.c_void_p(Y_dev), M, N, K, stream),
+           "stairs_gemm_device")
 
 
 def stairs_time_kernel(ctx, which: int, M: int, ctx_len: int, reps: int):

@@ -1726,6 +1726,78 @@ int stairs_gemm_host(int32_t dtype, const void* W, const float* X, float* Y, int
   return rc;
 }
 
+// ---- stairs_gemm_device: stairs_gemm_host for callers that cannot allocate ---------------------------------------
+// Everything stairs_gemm_host allocates per call lives in one file-scope device array instead; every GPU the library
+// runs on holds its own copy at its own address until the process ends.  Layout (bytes): hand-off counters, split-K /
+// fp32 partial sums, the re-laid-out bf16 weights, the activation fragments.
+constexpr size_t kNaCounterBytes = (size_t)kGemmCounters * sizeof(int);
+constexpr size_t kNaPartialBytes = (size_t)STAIRS_GEMM_DEVICE_MAX_PARTIAL;
+constexpr size_t kNaWeightBytes = (size_t)STAIRS_GEMM_DEVICE_MAX_WEIGHT;
+constexpr size_t kNaFragBytes = ((size_t)(STAIRS_GEMM_DEVICE_MAX_K / 32) * 256 + (size_t)(STAIRS_GEMM_DEVICE_MAX_K / 512 + 1) * kFragChunkPad) * 16;
+constexpr size_t kNaPartialOff = kNaCounterBytes;
+constexpr size_t kNaWeightOff = kNaPartialOff + kNaPartialBytes;
+constexpr size_t kNaFragOff = kNaWeightOff + kNaWeightBytes;
+constexpr size_t kNaScratchBytes = kNaFragOff + kNaFragBytes;
+static_assert(kNaPartialOff % 256 == 0 && kNaWeightOff % 256 == 0 && kNaFragOff % 256 == 0, "scratch regions stay 256-byte aligned");
+static __device__ __align__(256) unsigned char scratch[kNaScratchBytes];
+
+// `scratch` is a host-side stand-in in host code, not a device address: the address on the current device is looked
+// up once per device and kept; everything below passes that pointer.
+constexpr int kNaMaxDevices = 64;
+static unsigned char* g_scratch_ptr[kNaMaxDevices] = {};
+
+static __global__ __launch_bounds__(256) void k_fill_zero(int* p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+int stairs_gemm_device(int32_t dtype, const void* W, const float* X, float* Y, int32_t M, int32_t N, int32_t K, void* hip_stream) {
+  if (!W || !X || !Y || M < 1 || M > kMaxRows || N < 1 || K < 1) return STAIRS_EINVAL;
+  const bool b = dtype == STAIRS_DTYPE_BF16;
+  if (!b && dtype != STAIRS_DTYPE_FP32) return STAIRS_EINVAL;
+  if (b ? (K % 256 || N % 16 || N / 64 + 1 > kGemmCounters) : (K % 4 || N % 4)) return STAIRS_EINVAL;
+  // limits of the fixed scratch array
+  const size_t S = gemm_slices(K, b);
+  if (K > STAIRS_GEMM_DEVICE_MAX_K || S * M * N * sizeof(float) > kNaPartialBytes || (b && (size_t)N * K * 2 > kNaWeightBytes)) {
+    fprintf(stderr, "stairs_gemm_device: shape M=%d N=%d K=%d exceeds the fixed scratch (K <= %d, slices*M*N*4 <= %zu, bf16 N*K*2 <= %zu)\n",
+            M, N, K, STAIRS_GEMM_DEVICE_MAX_K, kNaPartialBytes, kNaWeightBytes);
+    return STAIRS_ECAPACITY;
+  }
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kNaMaxDevices) return STAIRS_EHIP;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      fprintf(stderr, "stairs_gemm_device: hipGetSymbolAddress: %s\n", hipGetErrorString(e));
+      return STAIRS_EHIP;
+    }
+    if (configure_kernels() != hipSuccess) return STAIRS_EHIP;      // (function attributes: no allocation)
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+  }
+  unsigned char* base = g_scratch_ptr[dev];
+  int* cnt = reinterpret_cast<int*>(base);
+  float* partial = reinterpret_cast<float*>(base + kNaPartialOff);
+  uint4* wsw = reinterpret_cast<uint4*>(base + kNaWeightOff);
+  uint4* frag = reinterpret_cast<uint4*>(base + kNaFragOff);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // the array keeps the last call's contents: the counters must start at zero (a fill kernel, not a memset node, so
+  // that a caller may capture the call)
+  hipLaunchKernelGGL(k_fill_zero, dim3((kGemmCounters + 255) / 256), dim3(256), 0, st, cnt, kGemmCounters);
+  if (b) launch_swizzle_bf16(static_cast<const uint16_t*>(W), wsw, N, K, kPermNone, 0, 0, st);
+  const bool fr = b && M > 4;
+  if (fr) launch_split_frag(X, K, M, K, nullptr, frag, st);
+  RowNorm none{nullptr, nullptr, 0, 0.f};
+  GemmEpi e{};
+  e.counters = cnt;
+  e.stream_weights = (size_t)N * K * (b ? 2 : 4) > kStreamHintBytes / 4;
+  e.out = Y;
+  e.hd = 64;
+  launch_gemm(kRoleHead, b, b ? static_cast<const void*>(wsw) : W, N, K, X, K, M, none, partial, e, st, fr ? frag : nullptr);
+  if (hipGetLastError() != hipSuccess) return STAIRS_EHIP;
+  return STAIRS_OK;
+}
+
 int stairs_copy_probe(int64_t bytes, int32_t reps, float* ms_per_launch, void* hip_stream) {
   if (bytes < 16 || bytes % 16 || reps < 1) return STAIRS_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
