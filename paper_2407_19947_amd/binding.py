@@ -35,7 +35,7 @@ def build_library(verbose: bool = False) -> str:
     """Compile the HIP sources for gfx950 into libstairs.so next to this file."""
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           *_SOURCES, "-o", LIB_PATH, "-L/opt/rocm/lib", "-lrocblas", "-Wl,-rpath,/opt/rocm/lib"]
+           *_SOURCES, "-o", LIB_PATH]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)

@@ -4,8 +4,6 @@
 #include "../../include/stairs.h"
 #include "stairs_kernels.h"
 
-#include <rocblas/rocblas.h>
-
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
@@ -26,8 +24,6 @@ struct Layer {
   const void* wo = nullptr;     // [d, d]
   const void* wgu = nullptr;    // [2f, d]
   const void* wdown = nullptr;  // [d, f]
-  // row-major bf16 copies of the same four matrices for the library GEMMs of the block prefill (or nullptr)
-  const uint16_t *wqkv_p = nullptr, *wo_p = nullptr, *wgu_p = nullptr, *wdown_p = nullptr;
 };
 
 // One layer of an encoder-decoder stack (decoder layers also hold the cross-attention block)
@@ -89,11 +85,10 @@ struct stairs_ctx {
   float2* rope_cs = nullptr;
   // activation fragments of x, attn_out and h for forwards of more than 4 rows (bf16 models), see frag_bytes()
   uint4 *xf = nullptr, *af = nullptr, *hf = nullptr;
-  // block prefill (bf16 models, env STAIRS_NO_BLOCK_PREFILL=1 turns it off): BLAS handle and [kPfRows, .] workspaces
+  // block prefill (bf16 models, env STAIRS_NO_BLOCK_PREFILL=1 turns it off): [kPfRows, .] workspaces
   bool block_prefill = false;
-  rocblas_handle blas = nullptr;
   float *pf_x = nullptr, *pf_y = nullptr, *pf_q = nullptr, *pf_attn = nullptr;
-  uint16_t *pf_hi = nullptr, *pf_lo = nullptr;
+  uint4* pf_frag = nullptr;    // block fragments of the activation in front of the current projection
   float2* pf_cs = nullptr;
   // encoder-decoder contexts: source tokens and the encoder's activations [max_src, .]
   bool encdec = false;
@@ -200,16 +195,13 @@ enum { KIND_EMB = 0, KIND_HEAD, KIND_NORM, KIND_QKV, KIND_WO, KIND_GU, KIND_DOWN
 // Upload a matrix made of `nparts` row blocks (each [rows_each, K], host, model dtype) as one
 // [nparts*rows_each, K] GEMM operand; bf16 goes through the operand re-layout kernel.
 int upload_matrix(stairs_ctx* c, bool bf16, const void* const* parts, int nparts, int rows_each, int K, int kind,
-                  int hd, char* staging, const void** out, const uint16_t** plain_out = nullptr) {
+                  int hd, char* staging, const void** out) {
   // gate/up and q/k rows are reordered so that SwiGLU and rotation pairs share a 16-row tile
   const int perm = (kind == KIND_GU) ? kPermGateUp : (kind == KIND_QKV) ? kPermQKV : kPermNone;
   auto key = std::make_pair(parts[0], kind);
-  auto pkey = std::make_pair(parts[0], kind + 100);          // the row-major copy of the same matrix
-  const bool want_plain = plain_out && bf16 && c->block_prefill;
   auto it = c->dedup.find(key);
   if (it != c->dedup.end()) {
     *out = it->second;
-    if (want_plain) *plain_out = static_cast<const uint16_t*>(c->dedup[pkey]);
     return STAIRS_OK;
   }
   const size_t esz = bf16 ? 2 : 4;
@@ -224,13 +216,6 @@ int upload_matrix(stairs_ctx* c, bool bf16, const void* const* parts, int nparts
     launch_swizzle_bf16(reinterpret_cast<const uint16_t*>(staging), reinterpret_cast<uint4*>(dst), nparts * rows_each, K,
                         perm, rows_each, hd, c->st);
     HIPCHK(c, hipGetLastError());
-    if (want_plain) {
-      char* pl = nullptr;
-      if ((rc = dev_alloc(c, &pl, part_bytes * nparts))) return rc;
-      HIPCHK(c, hipMemcpyAsync(pl, staging, part_bytes * nparts, hipMemcpyDeviceToDevice, c->st));
-      c->dedup[pkey] = pl;
-      *plain_out = reinterpret_cast<const uint16_t*>(pl);
-    }
   }
   HIPCHK(c, hipStreamSynchronize(c->st));   // staging and the host buffers are reused right away
   c->dedup[key] = dst;
@@ -277,13 +262,13 @@ int build_model(stairs_ctx* c, Model* m, const stairs_model_cfg* cfg, const stai
     if ((rc = upload_plain(c, w->ffn_norm[l], (size_t)d * 4, KIND_NORM, &p))) return rc;
     ly.ffn_norm = static_cast<const float*>(p);
     const void* qkv[3] = {w->wq[l], w->wk[l], w->wv[l]};
-    if ((rc = upload_matrix(c, m->bf16, qkv, 3, d, d, KIND_QKV, m->hd, staging, &ly.wqkv, &ly.wqkv_p))) return rc;
+    if ((rc = upload_matrix(c, m->bf16, qkv, 3, d, d, KIND_QKV, m->hd, staging, &ly.wqkv))) return rc;
     one[0] = w->wo[l];
-    if ((rc = upload_matrix(c, m->bf16, one, 1, d, d, KIND_WO, m->hd, staging, &ly.wo, &ly.wo_p))) return rc;
+    if ((rc = upload_matrix(c, m->bf16, one, 1, d, d, KIND_WO, m->hd, staging, &ly.wo))) return rc;
     const void* gu[2] = {w->w_gate[l], w->w_up[l]};
-    if ((rc = upload_matrix(c, m->bf16, gu, 2, f, d, KIND_GU, m->hd, staging, &ly.wgu, &ly.wgu_p))) return rc;
+    if ((rc = upload_matrix(c, m->bf16, gu, 2, f, d, KIND_GU, m->hd, staging, &ly.wgu))) return rc;
     one[0] = w->w_down[l];
-    if ((rc = upload_matrix(c, m->bf16, one, 1, d, f, KIND_DOWN, m->hd, staging, &ly.wdown, &ly.wdown_p))) return rc;
+    if ((rc = upload_matrix(c, m->bf16, one, 1, d, f, KIND_DOWN, m->hd, staging, &ly.wdown))) return rc;
   }
   m->stream_weights = m->bf16 && ((size_t)cfg->n_layers * (4 * (size_t)d * d + 3 * (size_t)d * f) + (size_t)V * d) * 2 > kStreamHintBytes;
   m->kv_layer_bytes = (size_t)cfg->n_heads * m->cap * m->hd * m->esz();
@@ -717,31 +702,9 @@ int encode_model(stairs_ctx* c, Model* m) {
   return STAIRS_OK;
 }
 
-#define BLASCHK(c, expr)                                                      \
-  do {                                                                        \
-    rocblas_status s_ = (expr);                                               \
-    if (s_ != rocblas_status_success) {                                       \
-      (c)->err = std::string(#expr) + ": " + rocblas_status_to_string(s_);    \
-      return STAIRS_EHIP;                                                     \
-    }                                                                         \
-  } while (0)
-
-// Y[R, N] (float, row-major) = X[R, K] . W[N, K]^T with X given as bf16 high + low parts and W row-major bf16:
-// two library GEMMs, the second accumulating onto the first (fp32 accumulation, no atomics: handle default).
-int blas_gemm_hilo(stairs_ctx* c, const uint16_t* W, int N, int K, const uint16_t* hi, const uint16_t* lo, int R, float* Y) {
-  const float one = 1.f, zero = 0.f;
-  BLASCHK(c, rocblas_gemm_ex(c->blas, rocblas_operation_transpose, rocblas_operation_none, N, R, K, &one, W, rocblas_datatype_bf16_r, K,
-                             hi, rocblas_datatype_bf16_r, K, &zero, Y, rocblas_datatype_f32_r, N, Y, rocblas_datatype_f32_r, N,
-                             rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0));
-  BLASCHK(c, rocblas_gemm_ex(c->blas, rocblas_operation_transpose, rocblas_operation_none, N, R, K, &one, W, rocblas_datatype_bf16_r, K,
-                             lo, rocblas_datatype_bf16_r, K, &one, Y, rocblas_datatype_f32_r, N, Y, rocblas_datatype_f32_r, N,
-                             rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0));
-  return STAIRS_OK;
-}
-
 // Positions [from, to) of sequence slot `slot` into a model's cache in blocks of up to kPfRows rows: the four
-// projections of a layer are library GEMMs over the whole block, attention runs the decode kernel on 32 rows at a
-// time (its keys include the block's own rows, appended just before), everything else is element-wise.
+// projections of a layer run on the MFMA-bound block GEMM over the whole block (the residual additions inside it),
+// attention on k_attn_flash (its keys include the block's own rows, appended just before), the rest is element-wise.
 int ingest_blocks(stairs_ctx* c, Model* m, int from, int to, int slot) {
   const stairs_model_cfg& g = m->cfg;
   const int d = g.d_model, f = g.d_ffn, H = g.n_heads;
@@ -756,20 +719,17 @@ int ingest_blocks(stairs_ctx* c, Model* m, int from, int to, int slot) {
       const Layer& ly = m->layers[l];
       char* Kl = m->Kc + (size_t)slot * slot_bytes + l * m->kv_layer_bytes;
       char* Vl = m->Vc + (size_t)slot * slot_bytes + l * m->kv_layer_bytes;
-      int rc;
-      launch_pf_norm_split(c->pf_x, ly.attn_norm, g.rms_eps, R, d, c->pf_hi, c->pf_lo, st);
-      if ((rc = blas_gemm_hilo(c, ly.wqkv_p, 3 * d, d, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
+      launch_pf_norm_split(c->pf_x, ly.attn_norm, g.rms_eps, R, d, c->pf_frag, st);
+      launch_gemm_block(ly.wqkv, 3 * d, d, c->pf_frag, R, c->pf_y, 3 * d, kPermQKV, d, m->hd, 0, st);
       launch_pf_rope_kv(c->pf_y, R, d, H, p0, c->pf_cs, c->pf_q, reinterpret_cast<_Float16*>(Kl), reinterpret_cast<_Float16*>(Vl),
                         m->cap, st);
       launch_attention_flash(c->pf_q, Kl, Vl, m->cap, d, H, R, p0, c->pf_attn, st);
-      launch_pf_norm_split(c->pf_attn, nullptr, 0.f, R, d, c->pf_hi, c->pf_lo, st);
-      if ((rc = blas_gemm_hilo(c, ly.wo_p, d, d, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
-      launch_pf_resid(c->pf_x, c->pf_y, (size_t)R * d, st);
-      launch_pf_norm_split(c->pf_x, ly.ffn_norm, g.rms_eps, R, d, c->pf_hi, c->pf_lo, st);
-      if ((rc = blas_gemm_hilo(c, ly.wgu_p, 2 * f, d, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
-      launch_pf_swiglu_split(c->pf_y, R, f, c->pf_hi, c->pf_lo, st);
-      if ((rc = blas_gemm_hilo(c, ly.wdown_p, d, f, c->pf_hi, c->pf_lo, R, c->pf_y))) return rc;
-      launch_pf_resid(c->pf_x, c->pf_y, (size_t)R * d, st);
+      launch_pf_norm_split(c->pf_attn, nullptr, 0.f, R, d, c->pf_frag, st);
+      launch_gemm_block(ly.wo, d, d, c->pf_frag, R, c->pf_x, d, kPermNone, 0, 0, 1, st);
+      launch_pf_norm_split(c->pf_x, ly.ffn_norm, g.rms_eps, R, d, c->pf_frag, st);
+      launch_gemm_block(ly.wgu, 2 * f, d, c->pf_frag, R, c->pf_y, 2 * f, kPermGateUp, f, 0, 0, st);
+      launch_pf_swiglu_split(c->pf_y, R, f, c->pf_frag, st);
+      launch_gemm_block(ly.wdown, d, f, c->pf_frag, R, c->pf_x, d, kPermNone, 0, 0, 1, st);
     }
     HIPCHK(c, hipGetLastError());
   }
@@ -781,7 +741,7 @@ constexpr int kBlockPrefillMin = 64;   // fewer rows than this go through the de
 // ingest positions [from, to) of sequence slot `slot` into a model's cache, no logits
 int ingest(stairs_ctx* c, Model* m, int from, int to, int slot = 0) {
   // (a counter-collecting profiler needs a wait after every launch: then the decode kernels ingest the prompt)
-  if (c->block_prefill && !c->sync_launches && m->bf16 && !m->encdec && to - from >= kBlockPrefillMin && m->layers[0].wqkv_p) {
+  if (c->block_prefill && !c->sync_launches && m->bf16 && !m->encdec && to - from >= kBlockPrefillMin) {
     int rc = ingest_blocks(c, m, from, to, slot);
     if (rc) return rc;
   } else {
@@ -1006,7 +966,6 @@ void stairs_free(stairs_ctx* c) {
   (void)hipStreamSynchronize(c->st);
   for (auto& g : c->graphs) (void)hipGraphExecDestroy(g.exec);
   for (auto& e : c->probe_ev) (void)hipEventDestroy(e);
-  if (c->blas) (void)rocblas_destroy_handle(c->blas);
   for (void* p : c->owned) (void)hipFree(p);
   if (c->h_pinned) (void)hipHostFree(c->h_pinned);
   for (auto& e : c->ev)
@@ -1121,17 +1080,16 @@ static int alloc_workspaces(stairs_ctx* c, const WsDims& w) {
       (rc = dev_alloc(c, &c->tgt_tok, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->counters, (size_t)kCounters)) || (rc = dev_alloc(c, &c->state, 2 * kSlotState)))
     return bail(rc);
   if (c->block_prefill) {
+    // rows per block: what the longest sequence needs, at most kPfRows
+    const int rows = std::min(kPfRows, (capmax + kBlkRows - 1) / kBlkRows * kBlkRows);
     const size_t wide = std::max<size_t>(3 * (size_t)dmax, 2 * (size_t)fmax), inner = std::max<size_t>(dmax, fmax);
-    if ((rc = dev_alloc(c, &c->pf_x, (size_t)kPfRows * dmax)) || (rc = dev_alloc(c, &c->pf_y, (size_t)kPfRows * wide)) ||
-        (rc = dev_alloc(c, &c->pf_q, (size_t)kPfRows * dmax)) || (rc = dev_alloc(c, &c->pf_attn, (size_t)kPfRows * dmax)) ||
-        (rc = dev_alloc(c, &c->pf_hi, (size_t)kPfRows * inner)) || (rc = dev_alloc(c, &c->pf_lo, (size_t)kPfRows * inner)) ||
-        (rc = dev_alloc(c, &c->pf_cs, (size_t)kPfRows * 64)))
+    if ((rc = dev_alloc(c, &c->pf_x, (size_t)rows * dmax)) || (rc = dev_alloc(c, &c->pf_y, (size_t)rows * wide)) ||
+        (rc = dev_alloc(c, &c->pf_q, (size_t)rows * dmax)) || (rc = dev_alloc(c, &c->pf_attn, (size_t)rows * dmax)) ||
+        (rc = dev_alloc(c, &c->pf_frag, pf_frag_bytes(rows, (int)inner) / sizeof(uint4))) ||
+        (rc = dev_alloc(c, &c->pf_cs, (size_t)rows * 64)))
       return bail(rc);
-    if (rocblas_create_handle(&c->blas) != rocblas_status_success || rocblas_set_stream(c->blas, c->st) != rocblas_status_success ||
-        rocblas_set_pointer_mode(c->blas, rocblas_pointer_mode_host) != rocblas_status_success) {
-      c->err = "rocBLAS handle could not be created";
-      return bail(STAIRS_EHIP);
-    }
+    // rows of a block past its last one are read by the GEMM (and their results dropped): they must hold numbers
+    if (hipMemsetAsync(c->pf_frag, 0, pf_frag_bytes(rows, (int)inner), c->st) != hipSuccess) return bail(STAIRS_EHIP);
   }
   // every slot of the token array always holds a valid id: a diagnostic forward may run at positions the current
   // sequence has not reached, and the embedding gather takes whatever id it finds there

@@ -188,15 +188,24 @@ void launch_accept_sampled(int* tokens, const float* tl, const float* dl, int ld
                            const SampleParams* sp, int* state, int* emitted, SampleWs* ws, hipStream_t st);
 
 // ---- prompt ingestion in large row blocks (bf16 models) ------------------------------------------------
-// The projections of a block of up to kPfRows prompt rows are plain GEMMs done by the BLAS library on bf16 copies
-// of the activations (high part, then low part accumulated onto it); everything around them is here.
-constexpr int kPfRows = 512;
+// The projections of a block of up to kPfRows prompt rows run on the MFMA-bound kernel k_gemm_bf16_block: the weights
+// in the decode kernels' layout, the activations as fragments (bf16 high + low parts in operand order) written by
+// the element-wise kernel in front of each projection.
+constexpr int kPfRows = 2048;
+constexpr int kBlkRows = 128;       // rows of one GEMM work-group; fragment buffers are laid out for whole groups
+inline int pf_col_tiles(int R) { return (R + kBlkRows - 1) / kBlkRows * (kBlkRows / 16); }
+// bytes of the fragments of a [R, K] activation block
+inline size_t pf_frag_bytes(int R, int K) { return (size_t)(K / 32) * pf_col_tiles(R) * 2 * 1024; }
+// Y[R, N] = (accumulate ? Y : 0) + X . W^T; W [N, K] in the operand-tile layout with row permutation (perm, p0, p1)
+// as given to launch_swizzle_bf16 (Y's columns are in natural order), xfrag the fragments of X [R, K]
+void launch_gemm_block(const void* W, int N, int K, const uint4* xfrag, int R, float* Y, int ldy, int perm, int p0, int p1,
+                       int accumulate, hipStream_t st);
 // x[r][:] = emb[tokens[p0 + r]][:] as float, r < R (zeros for a position outside [0, tok_cap) or an id outside [0, vocab))
 void launch_pf_embed(const uint16_t* emb, const int* tokens, int p0, int tok_cap, int vocab, int R, int d, float* x,
                      hipStream_t st);
 // one row per work-group: v = x (gain == nullptr) or x * rstd * gain with rstd = 1/sqrt(mean(x^2) + eps);
-// hi = bf16(v), lo = bf16(v - hi); row-major [R, d] outputs
-void launch_pf_norm_split(const float* x, const float* gain, float eps, int R, int d, uint16_t* hi, uint16_t* lo, hipStream_t st);
+// frag = the block fragments of v (bf16(v) and bf16(v - bf16(v)))
+void launch_pf_norm_split(const float* x, const float* gain, float eps, int R, int d, uint4* frag, hipStream_t st);
 // cs[r][i] = (cos, sin)((p0 + r) * theta^(-2i/hd)), angle in double
 void launch_pf_rope_table(int p0, int R, int hd, float theta, float2* cs, hipStream_t st);
 // y = [R, 3d] (q | k | v, natural column order): rotate q and k, q -> q_rot [R, d] float, k and v -> the tiled half
@@ -207,10 +216,8 @@ void launch_pf_rope_kv(const float* y, int R, int d, int H, int p0, const float2
 // 0 .. own position), q and out [R, d]; running softmax in registers (no partial results, no merge), a wave per 16 rows
 void launch_attention_flash(const float* q, const void* Kc, const void* Vc, int cap, int d, int H, int R, int p0, float* out,
                             hipStream_t st);
-// x[i] += y[i], n a multiple of 4
-void launch_pf_resid(float* x, const float* y, size_t n, hipStream_t st);
-// y = [R, 2f] (gate | up): h = silu(gate) * up, written as bf16 high and low parts [R, f]
-void launch_pf_swiglu_split(const float* y, int R, int f, uint16_t* hi, uint16_t* lo, hipStream_t st);
+// y = [R, 2f] (gate | up): h = silu(gate) * up, written as block fragments of [R, f]
+void launch_pf_swiglu_split(const float* y, int R, int f, uint4* frag, hipStream_t st);
 
 // dst[0..bytes) = src[0..bytes), bytes a multiple of 16: reads `bytes` and writes `bytes` of HBM
 void launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);

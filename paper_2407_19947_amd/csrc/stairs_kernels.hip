@@ -2463,8 +2463,150 @@ void launch_accept_sampled(int* tokens, const float* tl, const float* dl, int ld
 }
 
 // ---------------------------------------------------------------------------------------
-// prompt ingestion in large row blocks: the element-wise work around the library GEMMs
+// prompt ingestion in large row blocks: an MFMA-bound GEMM and the element-wise work around it
 // ---------------------------------------------------------------------------------------
+// Activations of a row block as MFMA B-operand fragments, written once by their producer: [k-step of 32][column tile
+// of 16 rows][high, low][lane] x 16 bytes (lane r + 16 g: x[16 ct + r][32 kt + 8 g .. + 8] as bf16 high part / bf16 of
+// the remainders).  RT = column tiles the buffer is laid out for (rows rounded up to a multiple of kBlkRows).
+__device__ __forceinline__ void pf_store_frag4(uint4* frag, int RT, int r, int k, const float (&v)[4]) {
+  uint2 hi, lo;
+  bf16_split2(v[0], v[1], hi.x, lo.x);
+  bf16_split2(v[2], v[3], hi.y, lo.y);
+  const size_t u4 = (((size_t)(k >> 5) * RT + (r >> 4)) * 2) * 64 + (r & 15) + 16 * ((k & 31) >> 3);
+  uint2* dst = reinterpret_cast<uint2*>(frag) + u4 * 2 + ((k & 7) >> 2);
+  dst[0] = hi;
+  dst[128] = lo;
+}
+
+// Y[R, N] (+)= X[R, K] . W[N, K]^T for row blocks of up to thousands of rows: the MFMA-bound regime.
+//   W: the operand-tile layout of the decode kernels (read as the MFMA A operand straight from memory, 1 KiB per load);
+//   X: block fragments (above), staged through LDS two k-steps at a time, double-buffered, shared by the 4 waves.
+//   Work-group = 256 output features (16 weight tiles, 4 per wave) x 128 rows (8 column tiles): a wave's k-step is
+//   4 KiB of weights from memory, 16 KiB of fragments from LDS and 64 MFMAs (high and low part of x), fp32 accumulators
+//   [4][8] tiles.  Output columns are stored in natural order (the row permutation of the weight layout is undone:
+//   4 consecutive permuted rows are 4 consecutive features).  accumulate: Y += (the residual connections).
+//   One order of additions per output (k ascending, high before low): results do not depend on R or on the grid.
+constexpr int kBlkKs = 2;                              // k-steps per LDS stage
+constexpr int kBlkStageU4 = kBlkKs * (kBlkRows / 16) * 2 * 64;   // uint4 per stage: 2048 (32 KiB)
+__global__ __launch_bounds__(256, 2) void k_gemm_bf16_block(const uint4* __restrict__ Wsw, int NTILES, int K,
+                                                            const uint4* __restrict__ XF, int RT, int R,
+                                                            float* __restrict__ Y, int ldy, int perm, int p0, int p1,
+                                                            int accumulate) {
+  constexpr int NT = 4, CT = kBlkRows / 16;
+  extern __shared__ uint4 lds[];                       // [2][kBlkStageU4]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j = lane & 15, g = lane >> 4;
+  const int tile0 = (blockIdx.x * 4 + wave) * NT;
+  const int ct0 = blockIdx.y * CT;
+  const int units_total = K / kUnitK;
+  const int nstages = (K >> 5) / kBlkKs;               // K is a multiple of 256: whole stages
+  int tile_c[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) tile_c[t] = min(tile0 + t, NTILES - 1);
+
+  auto load_a = [&](uint4 (&a)[kBlkKs][NT], int stage) {
+#pragma unroll
+    for (int ks = 0; ks < kBlkKs; ++ks) {
+      const int s = stage * kBlkKs + ks, c = s >> 4, kk = s & 15;
+      const int ksteps_c = min(kSliceUnits, units_total - c * kSliceUnits) * 8;
+      const uint4* wbase = Wsw + (size_t)c * NTILES * (kSliceUnits * 8) * 64 + (size_t)kk * 64 + lane;
+#pragma unroll
+      for (int t = 0; t < NT; ++t) a[ks][t] = wbase[(size_t)tile_c[t] * ksteps_c * 64];
+    }
+  };
+  // the stage's fragments: per k-step the work-group's 8 column tiles x (high, low) are 1024 consecutive uint4
+  auto load_b = [&](uint4 (&b)[kBlkKs * 4], int stage) {
+#pragma unroll
+    for (int ks = 0; ks < kBlkKs; ++ks) {
+      const uint4* src = XF + ((size_t)(stage * kBlkKs + ks) * RT + ct0) * 2 * 64 + tid;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) b[ks * 4 + i] = src[i * 256];
+    }
+  };
+  auto store_b = [&](const uint4 (&b)[kBlkKs * 4], int buf) {
+    uint4* dst = lds + buf * kBlkStageU4 + tid;
+#pragma unroll
+    for (int ks = 0; ks < kBlkKs; ++ks)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) dst[ks * 1024 + i * 256] = b[ks * 4 + i];
+  };
+
+  f32x4 acc[NT][CT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  uint4 a0[kBlkKs][NT], a1[kBlkKs][NT], breg[kBlkKs * 4];
+  load_b(breg, 0);
+  load_a(a0, 0);
+  store_b(breg, 0);
+  __syncthreads();
+  auto compute = [&](const uint4 (&a)[kBlkKs][NT], int buf) {
+    const uint4* src = lds + buf * kBlkStageU4 + lane;
+#pragma unroll
+    for (int ks = 0; ks < kBlkKs; ++ks) {
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) {
+        const bf16x8 bh = __builtin_bit_cast(bf16x8, src[ks * 1024 + (ct * 2) * 64]);
+        const bf16x8 bl = __builtin_bit_cast(bf16x8, src[ks * 1024 + (ct * 2 + 1) * 64]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const bf16x8 av = __builtin_bit_cast(bf16x8, a[ks][t]);
+          acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh, acc[t][ct], 0, 0, 0);
+          acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl, acc[t][ct], 0, 0, 0);
+        }
+      }
+    }
+  };
+  // two stages per turn so that the weight registers alternate without copies; requests of the next stage go out
+  // before the arithmetic of the current one (unconditionally: past the end the last stage is read again)
+  for (int st = 0; st < nstages; st += 2) {
+    load_b(breg, min(st + 1, nstages - 1));
+    load_a(a1, min(st + 1, nstages - 1));
+    __builtin_amdgcn_sched_barrier(0);
+    compute(a0, 0);
+    store_b(breg, 1);
+    __syncthreads();
+    if (st + 1 >= nstages) break;
+    load_b(breg, min(st + 2, nstages - 1));
+    load_a(a0, min(st + 2, nstages - 1));
+    __builtin_amdgcn_sched_barrier(0);
+    compute(a1, 1);
+    store_b(breg, 0);
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    if (tile0 + t < NTILES) {
+      const size_t col = perm_row((tile0 + t) * 16 + 4 * g, perm, p0, p1);
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) {
+        const int row = (ct0 + ct) * 16 + j;
+        if (row < R) {
+          float4* dst = reinterpret_cast<float4*>(Y + (size_t)row * ldy + col);
+          float4 v = make_float4(acc[t][ct][0], acc[t][ct][1], acc[t][ct][2], acc[t][ct][3]);
+          if (accumulate) {
+            const float4 o = *dst;
+            v.x = v.x + o.x; v.y = v.y + o.y; v.z = v.z + o.z; v.w = v.w + o.w;
+          }
+          *dst = v;
+        }
+      }
+    }
+  }
+}
+
+void launch_gemm_block(const void* W, int N, int K, const uint4* xfrag, int R, float* Y, int ldy, int perm, int p0, int p1,
+                       int accumulate, hipStream_t st) {
+  const int NTILES = N / 16;
+  dim3 grid((NTILES + 15) / 16, (R + kBlkRows - 1) / kBlkRows), block(256);
+  hipLaunchKernelGGL(k_gemm_bf16_block, grid, block, 2 * kBlkStageU4 * sizeof(uint4), st, static_cast<const uint4*>(W), NTILES,
+                     K, xfrag, pf_col_tiles(R), R, Y, ldy, perm, p0, p1, accumulate);
+}
+
 __global__ __launch_bounds__(256) void k_pf_embed(const uint16_t* __restrict__ emb, const int* __restrict__ tokens, int p0,
                                                   int tok_cap, int vocab, int d, float* __restrict__ x) {
   const int r = blockIdx.y, c = (blockIdx.x * 256 + threadIdx.x) * 4;
@@ -2484,7 +2626,7 @@ void launch_pf_embed(const uint16_t* emb, const int* tokens, int p0, int tok_cap
 }
 
 __global__ __launch_bounds__(256) void k_pf_norm_split(const float* __restrict__ x, const float* __restrict__ gain, float eps,
-                                                       int d, uint16_t* __restrict__ hi, uint16_t* __restrict__ lo) {
+                                                       int d, uint4* __restrict__ frag, int RT) {
   __shared__ float sm[4];
   const int r = blockIdx.x, tid = threadIdx.x;
   const float* row = x + (size_t)r * d;
@@ -2505,15 +2647,11 @@ __global__ __launch_bounds__(256) void k_pf_norm_split(const float* __restrict__
       const float4 g = *reinterpret_cast<const float4*>(gain + c);
       e[0] = e[0] * rstd * g.x; e[1] = e[1] * rstd * g.y; e[2] = e[2] * rstd * g.z; e[3] = e[3] * rstd * g.w;
     }
-    uint2 h2, l2;
-    bf16_split2(e[0], e[1], h2.x, l2.x);
-    bf16_split2(e[2], e[3], h2.y, l2.y);
-    *reinterpret_cast<uint2*>(hi + (size_t)r * d + c) = h2;
-    *reinterpret_cast<uint2*>(lo + (size_t)r * d + c) = l2;
+    pf_store_frag4(frag, RT, r, c, e);
   }
 }
-void launch_pf_norm_split(const float* x, const float* gain, float eps, int R, int d, uint16_t* hi, uint16_t* lo, hipStream_t st) {
-  hipLaunchKernelGGL(k_pf_norm_split, dim3(R), dim3(256), 0, st, x, gain, eps, d, hi, lo);
+void launch_pf_norm_split(const float* x, const float* gain, float eps, int R, int d, uint4* frag, hipStream_t st) {
+  hipLaunchKernelGGL(k_pf_norm_split, dim3(R), dim3(256), 0, st, x, gain, eps, d, frag, pf_col_tiles(R));
 }
 
 __global__ void k_pf_rope_table(int p0, int hd, double theta, float2* __restrict__ cs) {
@@ -2554,35 +2692,16 @@ void launch_pf_rope_kv(const float* y, int R, int d, int H, int p0, const float2
   hipLaunchKernelGGL(k_pf_rope_kv, dim3((H * hd / 2 + 255) / 256, R), dim3(256), 0, st, y, d, H, hd, p0, cs, q_rot, Kc, Vc, cap);
 }
 
-__global__ __launch_bounds__(256) void k_pf_resid(float4* __restrict__ x, const float4* __restrict__ y, size_t n4) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n4) return;
-  float4 a = x[i];
-  const float4 b = y[i];
-  a.x = b.x + a.x; a.y = b.y + a.y; a.z = b.z + a.z; a.w = b.w + a.w;
-  x[i] = a;
-}
-void launch_pf_resid(float* x, const float* y, size_t n, hipStream_t st) {
-  const size_t n4 = n / 4;
-  hipLaunchKernelGGL(k_pf_resid, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, reinterpret_cast<float4*>(x),
-                     reinterpret_cast<const float4*>(y), n4);
-}
-
-__global__ __launch_bounds__(256) void k_pf_swiglu_split(const float* __restrict__ y, int f, uint16_t* __restrict__ hi,
-                                                         uint16_t* __restrict__ lo) {
+__global__ __launch_bounds__(256) void k_pf_swiglu_split(const float* __restrict__ y, int f, uint4* __restrict__ frag, int RT) {
   const int r = blockIdx.y, c = (blockIdx.x * 256 + threadIdx.x) * 4;
   if (c >= f) return;
   const float4 g = *reinterpret_cast<const float4*>(y + (size_t)r * 2 * f + c);
   const float4 u = *reinterpret_cast<const float4*>(y + (size_t)r * 2 * f + f + c);
   const float e[4] = {swiglu(g.x, u.x), swiglu(g.y, u.y), swiglu(g.z, u.z), swiglu(g.w, u.w)};
-  uint2 h2, l2;
-  bf16_split2(e[0], e[1], h2.x, l2.x);
-  bf16_split2(e[2], e[3], h2.y, l2.y);
-  *reinterpret_cast<uint2*>(hi + (size_t)r * f + c) = h2;
-  *reinterpret_cast<uint2*>(lo + (size_t)r * f + c) = l2;
+  pf_store_frag4(frag, RT, r, c, e);
 }
-void launch_pf_swiglu_split(const float* y, int R, int f, uint16_t* hi, uint16_t* lo, hipStream_t st) {
-  hipLaunchKernelGGL(k_pf_swiglu_split, dim3((f + 1023) / 1024, R), dim3(256), 0, st, y, f, hi, lo);
+void launch_pf_swiglu_split(const float* y, int R, int f, uint4* frag, hipStream_t st) {
+  hipLaunchKernelGGL(k_pf_swiglu_split, dim3((f + 1023) / 1024, R), dim3(256), 0, st, y, f, frag, pf_col_tiles(R));
 }
 
 // plain streaming copy, the calibration kernel for HBM traffic counters
@@ -2626,6 +2745,7 @@ hipError_t configure_kernels() {
   STAIRS_OPTIN_WIDE(1, 2, kWideDepth2); STAIRS_OPTIN_WIDE(2, 2, kWideDepth2);
   STAIRS_OPTIN_WIDE(1, 1, kWideDepth1); STAIRS_OPTIN_WIDE(2, 1, kWideDepth1);
 #undef STAIRS_OPTIN_WIDE
+  optin((const void*)k_gemm_bf16_block, 2 * kBlkStageU4 * sizeof(uint4));
   // the stand-alone attention merge keeps a table of all chunks in LDS: large for long contexts (the fused
   // merge runs for at most kAttnFusedMaxChunks chunks and stays small)
   optin((const void*)k_attn_merge<128>, kAttnMergeMaxLds);
