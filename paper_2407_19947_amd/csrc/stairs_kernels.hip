@@ -2488,7 +2488,7 @@ __device__ __forceinline__ void pf_store_frag4(uint4* frag, int RT, int r, int k
 //   One order of additions per output (k ascending, high before low): results do not depend on R or on the grid.
 constexpr int kBlkKs = 2;                              // k-steps per LDS stage
 constexpr int kBlkStageU4 = kBlkKs * (kBlkRows / 16) * 2 * 64;   // uint4 per stage: 2048 (32 KiB)
-__global__ __launch_bounds__(256, 2) void k_gemm_bf16_block(const uint4* __restrict__ Wsw, int NTILES, int K,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_bf16_block(const uint4* __restrict__ Wsw, int NTILES, int K,
                                                             const uint4* __restrict__ XF, int RT, int R,
                                                             float* __restrict__ Y, int ldy, int perm, int p0, int p1,
                                                             int accumulate) {
@@ -2538,30 +2538,41 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_block(const uint4* __restr
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  uint4 a0[kBlkKs][NT], a1[kBlkKs][NT], breg[kBlkKs * 4];
-  load_b(breg, 0);
-  load_a(a0, 0);
-  store_b(breg, 0);
-  __syncthreads();
+  // the fragments of the next column tile are read from LDS before the MFMAs of the current one are issued, so the
+  // wave (alone on its SIMD) does not sit through the LDS latency 8 times per k-step
   auto compute = [&](const uint4 (&a)[kBlkKs][NT], int buf) {
     const uint4* src = lds + buf * kBlkStageU4 + lane;
+    uint4 bh = src[0], bl = src[64];
 #pragma unroll
     for (int ks = 0; ks < kBlkKs; ++ks) {
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct) {
-        const bf16x8 bh = __builtin_bit_cast(bf16x8, src[ks * 1024 + (ct * 2) * 64]);
-        const bf16x8 bl = __builtin_bit_cast(bf16x8, src[ks * 1024 + (ct * 2 + 1) * 64]);
+        const int nxt = ks * CT + ct + 1;                                  // (the last one reads the first again)
+        const int nks = nxt < kBlkKs * CT ? nxt / CT : 0, nct = nxt < kBlkKs * CT ? nxt % CT : 0;
+        const uint4 nh = src[nks * 1024 + (nct * 2) * 64], nl = src[nks * 1024 + (nct * 2 + 1) * 64];
+        const bf16x8 vh = __builtin_bit_cast(bf16x8, bh), vl = __builtin_bit_cast(bf16x8, bl);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
           const bf16x8 av = __builtin_bit_cast(bf16x8, a[ks][t]);
-          acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh, acc[t][ct], 0, 0, 0);
-          acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl, acc[t][ct], 0, 0, 0);
+          acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, vh, acc[t][ct], 0, 0, 0);
         }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const bf16x8 av = __builtin_bit_cast(bf16x8, a[ks][t]);
+          acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, vl, acc[t][ct], 0, 0, 0);
+        }
+        bh = nh;
+        bl = nl;
       }
     }
   };
   // two stages per turn so that the weight registers alternate without copies; requests of the next stage go out
   // before the arithmetic of the current one (unconditionally: past the end the last stage is read again)
+  uint4 a0[kBlkKs][NT], a1[kBlkKs][NT], breg[kBlkKs * 4];
+  load_b(breg, 0);
+  load_a(a0, 0);
+  store_b(breg, 0);
+  __syncthreads();
   for (int st = 0; st < nstages; st += 2) {
     load_b(breg, min(st + 1, nstages - 1));
     load_a(a1, min(st + 1, nstages - 1));
