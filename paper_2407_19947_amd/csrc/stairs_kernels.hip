@@ -2481,24 +2481,26 @@ __device__ __forceinline__ void pf_store_frag4(uint4* frag, int RT, int r, int k
 // Y[R, N] (+)= X[R, K] . W[N, K]^T for row blocks of up to thousands of rows: the MFMA-bound regime.
 //   W: the operand-tile layout of the decode kernels (read as the MFMA A operand straight from memory, 1 KiB per load);
 //   X: block fragments (above), staged through LDS two k-steps at a time, double-buffered, shared by the 4 waves.
-//   Work-group = 256 output features (16 weight tiles, 4 per wave) x 128 rows (8 column tiles): a wave's k-step is
-//   4 KiB of weights from memory, 16 KiB of fragments from LDS and 64 MFMAs (high and low part of x), fp32 accumulators
-//   [4][8] tiles.  Output columns are stored in natural order (the row permutation of the weight layout is undone:
+//   Work-group = 256 output features (16 weight tiles) x 128 rows (8 column tiles) on 8 waves, each 4 weight tiles x
+//   4 column tiles: a wave's k-step is 4 KiB of weights from memory, 8 KiB of fragments from LDS and 32 MFMAs (high and
+//   low part of x), fp32 accumulators [4][4] tiles.  Output columns are stored in natural order (the row permutation of the weight layout is undone:
 //   4 consecutive permuted rows are 4 consecutive features).  accumulate: Y += (the residual connections).
 //   One order of additions per output (k ascending, high before low): results do not depend on R or on the grid.
 constexpr int kBlkKs = 2;                              // k-steps per LDS stage
 constexpr int kBlkStageU4 = kBlkKs * (kBlkRows / 16) * 2 * 64;   // uint4 per stage: 2048 (32 KiB)
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_bf16_block(const uint4* __restrict__ Wsw, int NTILES, int K,
-                                                            const uint4* __restrict__ XF, int RT, int R,
-                                                            float* __restrict__ Y, int ldy, int perm, int p0, int p1,
-                                                            int accumulate) {
-  constexpr int NT = 4, CT = kBlkRows / 16;
+__global__ __launch_bounds__(512) void k_gemm_bf16_block(const uint4* __restrict__ Wsw, int NTILES, int K,
+                                                         const uint4* __restrict__ XF, int RT, int R,
+                                                         float* __restrict__ Y, int ldy, int perm, int p0, int p1,
+                                                         int accumulate) {
+  // 8 waves: wave = (row half rh, feature group fw); a wave owns 4 weight tiles x 4 column tiles (64 x 64 outputs)
+  constexpr int NT = 4, CT = kBlkRows / 32, CTW = kBlkRows / 16;
   extern __shared__ uint4 lds[];                       // [2][kBlkStageU4]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int fw = wave & 3, rh = wave >> 2;
   const int j = lane & 15, g = lane >> 4;
-  const int tile0 = (blockIdx.x * 4 + wave) * NT;
-  const int ct0 = blockIdx.y * CT;
+  const int tile0 = (blockIdx.x * 4 + fw) * NT;
+  const int ct0 = blockIdx.y * CTW;                    // first column tile of the work-group
   const int units_total = K / kUnitK;
   const int nstages = (K >> 5) / kBlkKs;               // K is a multiple of 256: whole stages
   int tile_c[NT];
@@ -2516,20 +2518,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
   };
   // the stage's fragments: per k-step the work-group's 8 column tiles x (high, low) are 1024 consecutive uint4
-  auto load_b = [&](uint4 (&b)[kBlkKs * 4], int stage) {
+  auto load_b = [&](uint4 (&b)[kBlkKs * 2], int stage) {
 #pragma unroll
     for (int ks = 0; ks < kBlkKs; ++ks) {
       const uint4* src = XF + ((size_t)(stage * kBlkKs + ks) * RT + ct0) * 2 * 64 + tid;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) b[ks * 4 + i] = src[i * 256];
+      for (int i = 0; i < 2; ++i) b[ks * 2 + i] = src[i * 512];
     }
   };
-  auto store_b = [&](const uint4 (&b)[kBlkKs * 4], int buf) {
+  auto store_b = [&](const uint4 (&b)[kBlkKs * 2], int buf) {
     uint4* dst = lds + buf * kBlkStageU4 + tid;
 #pragma unroll
     for (int ks = 0; ks < kBlkKs; ++ks)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) dst[ks * 1024 + i * 256] = b[ks * 4 + i];
+      for (int i = 0; i < 2; ++i) dst[ks * 1024 + i * 512] = b[ks * 2 + i];
   };
 
   f32x4 acc[NT][CT];
@@ -2538,19 +2540,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // the fragments of the next column tile are read from LDS before the MFMAs of the current one are issued, so the
-  // wave (alone on its SIMD) does not sit through the LDS latency 8 times per k-step
   auto compute = [&](const uint4 (&a)[kBlkKs][NT], int buf) {
-    const uint4* src = lds + buf * kBlkStageU4 + lane;
-    uint4 bh = src[0], bl = src[64];
+    const uint4* src = lds + buf * kBlkStageU4 + (rh * CT * 2) * 64 + lane;
 #pragma unroll
     for (int ks = 0; ks < kBlkKs; ++ks) {
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct) {
-        const int nxt = ks * CT + ct + 1;                                  // (the last one reads the first again)
-        const int nks = nxt < kBlkKs * CT ? nxt / CT : 0, nct = nxt < kBlkKs * CT ? nxt % CT : 0;
-        const uint4 nh = src[nks * 1024 + (nct * 2) * 64], nl = src[nks * 1024 + (nct * 2 + 1) * 64];
-        const bf16x8 vh = __builtin_bit_cast(bf16x8, bh), vl = __builtin_bit_cast(bf16x8, bl);
+        const bf16x8 vh = __builtin_bit_cast(bf16x8, src[ks * 1024 + (ct * 2) * 64]);
+        const bf16x8 vl = __builtin_bit_cast(bf16x8, src[ks * 1024 + (ct * 2 + 1) * 64]);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
           const bf16x8 av = __builtin_bit_cast(bf16x8, a[ks][t]);
@@ -2561,14 +2558,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           const bf16x8 av = __builtin_bit_cast(bf16x8, a[ks][t]);
           acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, vl, acc[t][ct], 0, 0, 0);
         }
-        bh = nh;
-        bl = nl;
       }
     }
   };
   // two stages per turn so that the weight registers alternate without copies; requests of the next stage go out
-  // before the arithmetic of the current one (unconditionally: past the end the last stage is read again)
-  uint4 a0[kBlkKs][NT], a1[kBlkKs][NT], breg[kBlkKs * 4];
+  // before the arithmetic of the current one (unconditionally: past the end the last stage is read again).  Two waves
+  // per SIMD fill each other's waits for LDS and memory.
+  uint4 a0[kBlkKs][NT], a1[kBlkKs][NT], breg[kBlkKs * 2];
   load_b(breg, 0);
   load_a(a0, 0);
   store_b(breg, 0);
@@ -2595,7 +2591,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       const size_t col = perm_row((tile0 + t) * 16 + 4 * g, perm, p0, p1);
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct) {
-        const int row = (ct0 + ct) * 16 + j;
+        const int row = (ct0 + rh * CT + ct) * 16 + j;
         if (row < R) {
           float4* dst = reinterpret_cast<float4*>(Y + (size_t)row * ldy + col);
           float4 v = make_float4(acc[t][ct][0], acc[t][ct][1], acc[t][ct][2], acc[t][ct][3]);
@@ -2613,7 +2609,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 void launch_gemm_block(const void* W, int N, int K, const uint4* xfrag, int R, float* Y, int ldy, int perm, int p0, int p1,
                        int accumulate, hipStream_t st) {
   const int NTILES = N / 16;
-  dim3 grid((NTILES + 15) / 16, (R + kBlkRows - 1) / kBlkRows), block(256);
+  dim3 grid((NTILES + 15) / 16, (R + kBlkRows - 1) / kBlkRows), block(512);
   hipLaunchKernelGGL(k_gemm_bf16_block, grid, block, 2 * kBlkStageU4 * sizeof(uint4), st, static_cast<const uint4*>(W), NTILES,
                      K, xfrag, pf_col_tiles(R), R, Y, ldy, perm, p0, p1, accumulate);
 }
