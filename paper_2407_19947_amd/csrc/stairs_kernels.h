@@ -8,7 +8,8 @@
 namespace stairs {
 
 constexpr int kMaxRows = 32;        // rows (new tokens) one forward can take
-constexpr int kAttnChunk = 128;     // keys per attention work-group; boundaries are absolute positions
+constexpr int kAttnChunk = 128;     // keys per attention work-group of the fp32-cache kernels and the unit callers count chunks in; boundaries are absolute positions
+constexpr int kAttnChunkH = 256;    // keys per attention work-group of the half-cache kernels (a wave owns 64)
 constexpr int kAttnFusedMaxChunks = 24;   // more chunks per head than this: the chunk merge runs as a second kernel
 constexpr size_t kAttnMergeMaxLds = 150 * 1024;   // most dynamic LDS the chunk merge may take
 constexpr int kSsqGroupF32 = 1024;  // residual columns per sum-of-squares partial, fp32 models

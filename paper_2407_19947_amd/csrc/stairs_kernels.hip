@@ -1701,7 +1701,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
                                            int kv_len, int nchunk_cap, int nch_lds, int rows_per_pass, float* out, int d,
                                            float* s_ml, uint4* frag, int frag_row0) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int nch_max = (kv_len > 0) ? (kv_len - 1) / kAttnChunk + 1 : 0;
+  const int nch_max = (kv_len > 0) ? (kv_len - 1) / kAttnChunkH + 1 : 0;
   float* grp = s_ml + (size_t)M * nch_lds * 2 + kMaxRows;   // (kMaxRows floats after the table stay unused)
   for (int idx = tid; idx < M * nch_max; idx += 256) {
     const int m = idx / nch_max, cc = idx - m * nch_max;
@@ -1712,7 +1712,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
   __syncthreads();
   for (int m = wave; m < M; m += 4) {                 // row maxima (max is exact in any order)
     const int p = pos0 + m * step;
-    const int nch = p >= 0 ? p / kAttnChunk + 1 : 0;
+    const int nch = p >= 0 ? p / kAttnChunkH + 1 : 0;
     float g = -INFINITY;
     for (int cc = lane; cc < nch; cc += 64) g = fmaxf(g, s_ml[((size_t)m * nch_lds + cc) * 2]);
     g = wave_max(g);
@@ -1756,7 +1756,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
       if (p >= 0) {
         float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
         float den = 0.f;
-        group_sum(m, e, 0, p / kAttnChunk + 1, num, den);
+        group_sum(m, e, 0, p / kAttnChunkH + 1, num, den);
         res = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
       }
       *reinterpret_cast<float4*>(out + (size_t)m * d + h * HD + e) = res;
@@ -1773,7 +1773,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
       float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
       float den = 0.f;
       if (p >= 0) {
-        const int nch = p / kAttnChunk + 1;
+        const int nch = p / kAttnChunkH + 1;
         if (g * CB < nch) group_sum(m, e, g * CB, min(nch, (g + 1) * CB), num, den);
       }
       float* o = grp + (size_t)idx * 5;
@@ -1785,7 +1785,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
       const int p = pos0 + m * step;
       float4 res = make_float4(0.f, 0.f, 0.f, 0.f);
       if (p >= 0) {
-        const int ng = (p / kAttnChunk + 1 + CB - 1) / CB;
+        const int ng = (p / kAttnChunkH + 1 + CB - 1) / CB;
         float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
         float den = 0.f;
         for (int g = 0; g < ng; ++g) {
@@ -1832,11 +1832,13 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
   const int step = fixed ? 0 : 1;
   const int kv_len = pos0 + (fixed ? 1 : M);
   const float* brow = am.bias ? am.bias + (size_t)h * am.bias_ld + am.bias_zero : nullptr;
-  const int kb = c * kAttnChunk + wave * 32;          // first key of this wave
+  // a wave owns 64 keys of the chunk as two blocks of 32 (the tiles of the cache layout)
+  const int kb = c * kAttnChunkH + wave * 64;         // first key of this wave
   const bool have_keys = kb < kv_len;
+  const bool have_second = kb + 32 < kv_len;
   // all keys in the first chunk: its work-group writes the result itself (what the merge would give for one chunk:
   // weight exp(0) = 1), the others have nothing to do; no partial results, no ticket
-  const bool single = FUSED && kv_len <= kAttnChunk;
+  const bool single = FUSED && kv_len <= kAttnChunkH;
   if (single && c > 0) return;
 
   // the first query tile's rows are requested before the keys and values: they come from L2 and are
@@ -1853,16 +1855,28 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
     }
   }
 
-  uint4 kreg[2][KK], vreg[ET];
-  if (have_keys) {
-    const uint4* Kh = reinterpret_cast<const uint4*>(Kc + (size_t)h * cap * HD);
-    const uint4* Vh = reinterpret_cast<const uint4*>(Vc + (size_t)h * cap * HD);
+  // the wave's whole share of the chunk is requested at once (keys and values of both blocks: 16 KiB at head_dim 128)
+  uint4 kreg[2][2][KK], vreg[2][ET];
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb) {
+    const bool ok = sb ? have_second : have_keys;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) kreg[t][kk] = Kh[((size_t)((kb >> 4) + t) * KK + kk) * 64 + lane];
+      for (int kk = 0; kk < KK; ++kk) kreg[sb][t][kk] = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-    for (int et = 0; et < ET; ++et) vreg[et] = Vh[((size_t)(kb >> 5) * ET + et) * 64 + lane];
+    for (int et = 0; et < ET; ++et) vreg[sb][et] = make_uint4(0u, 0u, 0u, 0u);   // (a block without keys meets probability 0)
+    if (ok) {
+      const uint4* Kh = reinterpret_cast<const uint4*>(Kc + (size_t)h * cap * HD);
+      const uint4* Vh = reinterpret_cast<const uint4*>(Vc + (size_t)h * cap * HD);
+      const int kbs = kb + 32 * sb;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) kreg[sb][t][kk] = Kh[((size_t)((kbs >> 4) + t) * KK + kk) * 64 + lane];
+#pragma unroll
+      for (int et = 0; et < ET; ++et) vreg[sb][et] = Vh[((size_t)(kbs >> 5) * ET + et) * 64 + lane];
+    }
   }
 
 #pragma unroll
@@ -1890,47 +1904,59 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
                             b.x * scale, b.y * scale, b.z * scale, b.w * scale};
         split_half8(v, qh[kk], ql[kk]);
       }
-      float sc[8];
+      // scores of the wave's 64 keys, their joint maximum, the exponentials, then the two value products
+      float sc[2][8];
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        f32x4 sacc = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int sb = 0; sb < 2; ++sb) {
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          const f16x8 a = __builtin_bit_cast(f16x8, kreg[t][kk]);
-          sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qh[kk], sacc, 0, 0, 0);
-          sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ql[kk], sacc, 0, 0, 0);
-        }
+        for (int t = 0; t < 2; ++t) {
+          f32x4 sacc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int key = kb + t * 16 + g * 4 + v;
-          const bool seen = qi < M && key <= pos0 + qi * step;
-          const float bv = (brow && seen) ? brow[key - (qpos0 + qi)] : 0.f;   // bias by key position - query position
-          sc[t * 4 + v] = seen ? sacc[v] + bv : -INFINITY;
+          for (int kk = 0; kk < KK; ++kk) {
+            const f16x8 a = __builtin_bit_cast(f16x8, kreg[sb][t][kk]);
+            sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qh[kk], sacc, 0, 0, 0);
+            sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ql[kk], sacc, 0, 0, 0);
+          }
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int key = kb + sb * 32 + t * 16 + g * 4 + v;
+            const bool seen = qi < M && key <= pos0 + qi * step;
+            const float bv = (brow && seen) ? brow[key - (qpos0 + qi)] : 0.f;   // bias by key position - query position
+            sc[sb][t * 4 + v] = seen ? sacc[v] + bv : -INFINITY;
+          }
         }
       }
-      float mx = sc[0];
+      float mx = sc[0][0];
 #pragma unroll
-      for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sc[i]);
+      for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sc[0][i]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) mx = fmaxf(mx, sc[1][i]);
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      float pv[8], sum = 0.f;
+      float sum = 0.f;
+      f16x8 ph[2], pl[2];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        pv[i] = (mx == -INFINITY) ? 0.f : expf(sc[i] - mx);
-        sum += pv[i];
+      for (int sb = 0; sb < 2; ++sb) {
+        float pv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          pv[i] = (mx == -INFINITY) ? 0.f : expf(sc[sb][i] - mx);
+          sum += pv[i];
+        }
+        split_half8(pv, ph[sb], pl[sb]);
       }
       sum += __shfl_xor(sum, 16);
       sum += __shfl_xor(sum, 32);
       mw = mx;
       lw = sum;
-      f16x8 ph, pl;
-      split_half8(pv, ph, pl);
 #pragma unroll
-      for (int et = 0; et < ET; ++et) {
-        const f16x8 a = __builtin_bit_cast(f16x8, vreg[et]);
-        oacc[et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ph, oacc[et], 0, 0, 0);
-        oacc[et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pl, oacc[et], 0, 0, 0);
-      }
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int et = 0; et < ET; ++et) {
+          const f16x8 a = __builtin_bit_cast(f16x8, vreg[sb][et]);
+          oacc[et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ph[sb], oacc[et], 0, 0, 0);
+          oacc[et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pl[sb], oacc[et], 0, 0, 0);
+        }
     }
     // merge the four waves (wave order): every wave leaves its maximum, its sum and its output rows as they are; the
     // threads that add the four outputs up scale them by exp(max_w - max) on the way (product rounded, then added)
@@ -2155,6 +2181,8 @@ void launch_attention(const float* q_rot, const void* Kc, const void* Vc, int kv
     const float scale = am.scale > 0.f ? am.scale : 1.0f / sqrtf((float)hd);
     const _Float16* K = static_cast<const _Float16*>(Kc);
     const _Float16* V = static_cast<const _Float16*>(Vc);
+    // the half-cache kernels take 256-key chunks: half as many work-groups as the 128-key units the callers count in
+    nchunk_launch = (nchunk_launch * kAttnChunk + kAttnChunkH - 1) / kAttnChunkH;
     dim3 grid(nchunk_launch, H, nslots), block(256);
     // merge step's LDS: (max, sum) table, row maxima, and for more than kMergeCB chunks the group sums of as many
     // rows per pass as fit in 48 KiB, less when the table is large (the whole stays under kAttnMergeMaxLds)
