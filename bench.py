@@ -30,16 +30,21 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def measured_traffic():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
-    (a line 'traffic_bytes_per_launch: N'), or None."""
+def measured_traffic(kernel_key):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary: lines
+    'kernel: <name>', 'commit: <hash>', 'traffic_bytes_per_launch: N'.  None when the summary is missing or was taken
+    on another kernel than the one this run times (the figure would silently be stale)."""
+    fields = {}
     try:
         for line in open(TRAFFIC_FILE):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+            if ":" in line:
+                key, val = line.split(":", 1)
+                fields.setdefault(key.strip(), val.strip())
     except OSError:
-        pass
-    return None
+        return None, None
+    if kernel_key not in fields.get("kernel", "") or "traffic_bytes_per_launch" not in fields:
+        return None, None
+    return float(fields["traffic_bytes_per_launch"]), fields.get("commit")
 
 
 def cpu_baseline(w, target, draft, prompt, k, sample_P, sample_G):
@@ -208,11 +213,15 @@ def main():
     ms_pair, _ = eng.time_kernel(9, M, ctx_mid, 4)      # what an event pair reads with no kernel inside
     ms_iso, _ = eng.time_kernel(0, M, 0, 4 * target.n_layers)
     achieved = bytes_gu / (ms_situ * 1e-3) / 1e9
-    kname = (f"k_gemm_bf16_rows<{M}, gate/up> (whole X block in LDS, one work-group per weight tile)" if M <= 4
-             else f"k_gemm_bf16<{1 if M <= 16 else 2}, 2, gate/up> (split-K with in-kernel hand-off)")
+    kernel_key = f"k_gemm_bf16_rows<{M}, gate/up" if M <= 4 else f"k_gemm_bf16_wide<{1 if M <= 16 else 2}, 8"
+    kname = (f"k_gemm_bf16_rows<{M}, gate/up> (whole activation block in LDS, one work-group per weight tile)" if M <= 4
+             else f"k_gemm_bf16_wide<{1 if M <= 16 else 2}, 8> (activation fragments from L2, a work-group owns 8 weight tiles over all of k)")
+    traffic, traffic_commit = measured_traffic(kernel_key)
     roofline = {"bound": "hbm", "kernel": kname + ": gate/up projection + SwiGLU at M = k+1 rows",
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                "traffic": measured_traffic(), "bytes_per_launch": bytes_gu, "ms_per_launch": ms_situ,
+                "traffic": traffic, "traffic_source": (f"profiles/{os.path.basename(TRAFFIC_FILE)} at commit {traffic_commit}"
+                                                       if traffic is not None else None),
+                "bytes_per_launch": bytes_gu, "ms_per_launch": ms_situ,
                 "launches_timed": 4 * target.n_layers,
                 "how": "in situ: start/end HIP events of each layer's launch inside whole verification forwards",
                 "event_pair_around_launch_ms": ms_around, "empty_event_pair_ms": ms_pair,
@@ -239,6 +248,10 @@ def main():
             ms, by = eng.time_kernel(6, kk + 1, ctx_mid, 3)
             sweep[str(kk)] = {"ms": ms, "GB/s": by / (ms * 1e-3) / 1e9, "frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
         extras["verify_vs_k"] = sweep
+        extras["verify_vs_k_max_over_k0"] = max(v["ms"] for v in sweep.values()) / sweep["0"]["ms"]
+        # the spec quantities beside the dominant kernel's: the whole verification at the headline's k and one
+        # draft step, algorithmic bytes (all matrices + keys and values of the context) over measured time
+        extras["verify"] = dict(sweep[str(k)], k=k, rows=k + 1, context=ctx_mid)
         ms, by = eng.time_kernel(7, 1, ctx_mid, 8)
         extras["draft_step"] = {"ms": ms, "GB/s": by / (ms * 1e-3) / 1e9, "frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
     # ---- draft length following the acceptance (same output, other iteration count) -----------------------
@@ -305,7 +318,7 @@ def main():
         "ms_per_step": 1e3 * total / len(decode_s), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
         "config": {"workload": args.workload, "prompt_len": P, "generate": G, "k": k, "stair_rows": k + 1,
-                   "target": w["target"], "draft": w["draft"], "timed_region": "decode phase (prefill excluded)"},
+                   "timed_region": "decode phase (prefill excluded)"},
         "tokens_per_s_over_steps": spread,
         "iterations_per_step": stats_last.iterations, "mean_tokens_per_iteration": G / stats_last.iterations,
         "accept_hist": list(stats_last.accept_hist)[:k + 1],
