@@ -69,7 +69,7 @@ struct Model {
 }  // namespace
 
 constexpr int kGemmCounters = 2048;   // >= column groups of the widest GEMM (N / 64)
-constexpr int kAttnCounters = 1024;                    // one per (sequence slot, attention head)
+constexpr int kAttnCounters = 4096;                    // one per (sequence slot, attention head)
 constexpr int kCounters = kGemmCounters + kAttnCounters;
 
 struct stairs_ctx {
@@ -104,6 +104,8 @@ struct stairs_ctx {
   int* tokens = nullptr;       // device copy of the sequence(s): [n_slots][tok_stride], capacity tok_cap each
   int tok_cap = 0, tok_stride = 0;
   int n_slots = 1;             // sequence slots the caches, token arrays and state hold (stairs_reserve_batch)
+  int rows_cap = kMaxRows;     // rows logits, target tokens and attention partial results are sized for
+  int pf_rows = 0;             // rows the block workspaces (pf_*) hold
   int* counters = nullptr;     // [kCounters] split-K / attention hand-off tickets, zero between launches
   int* tgt_tok = nullptr;      // [kMaxRows]
   int* state = nullptr;        // per slot kSlotState ints: [0] = L, [1] = n of last iteration, [2] = constant 0, [3] = active
@@ -444,12 +446,17 @@ size_t max_partial_floats(const stairs_model_cfg* m) {
 // Several sequences: pos.rps > 0 rows per slot, M = rps * (number of slots), slots 0..M/rps-1; otherwise the
 // rows belong to sequence slot `slot`.
 int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows, float* logits_dst);
+int forward_block(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows);
 
 // logits_dst: where the logits rows go (nullptr: c->logits)
 int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows, int slot = 0, float* logits_dst = nullptr) {
   if (m->encdec) {
     if (slot != 0 || pos.rps) return fail(c, STAIRS_EINVAL, "forward: encoder-decoder models take one sequence");
     return forward_ed(c, m, pos, nchunk, M, logits_rows, logits_dst);
+  }
+  if (M > kMaxRows) {                       // many sequences at once: the block kernels
+    if (slot != 0 || logits_dst) return fail(c, STAIRS_EINVAL, "forward: launch shape outside the workspaces");
+    return forward_block(c, m, pos, nchunk, M, logits_rows);
   }
   const stairs_model_cfg& g = m->cfg;
   const int d = g.d_model, f = g.d_ffn, H = g.n_heads, V = g.vocab;
@@ -540,6 +547,52 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
   HIPCHK(c, hipGetLastError());
   return STAIRS_OK;
 #undef SYNCPOINT
+}
+
+// A forward of 33 .. kMaxBlockRows rows of several sequences (pos.rps rows per slot) on the block kernels: the
+// projections run on the MFMA-bound GEMM of the prompt ingestion over all rows at once, attention on the decode
+// kernel (one grid slice per slot, each against its own cache), the rest is element-wise.  Every output has one order
+// of additions whatever the number of rows, so a sequence's results do not depend on which others share the forward
+// (they are not the bits of the decode kernels, whose additions go chunk by chunk).  All rows' logits -> c->logits.
+int forward_block(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_rows) {
+  const stairs_model_cfg& g = m->cfg;
+  const int d = g.d_model, f = g.d_ffn, H = g.n_heads, V = g.vocab;
+  hipStream_t st = c->st;
+  if (!c->block_prefill || !m->bf16 || m->encdec || !pos.rps || M % pos.rps || M > kMaxBlockRows || M > c->pf_rows || M > c->rows_cap ||
+      (logits_rows != 0 && logits_rows != M))
+    return fail(c, STAIRS_EINVAL, "forward: rows outside what the block workspaces hold");
+  const int nslots = M / pos.rps;
+  if (nchunk < 1 || nchunk > c->nchunk_cap || nslots > c->n_slots || nslots * H > kAttnCounters)
+    return fail(c, STAIRS_EINVAL, "forward: launch shape outside the workspaces");
+  const size_t slot_bytes = (size_t)g.n_layers * m->kv_layer_bytes;
+  const size_t slot_stride = slot_bytes / m->esz();
+  // (the gather also leaves sum-of-squares partials nobody needs here: into pf_y, which is scratch until the first GEMM)
+  launch_embed(m->tok_emb, 1, c->tokens, c->tok_stride, c->tok_stride, V, pos, M, d, c->pf_x, c->pf_y, m->hd, g.rope_theta, c->pf_cs, st);
+  const AttnMode amode{0.f, nullptr, 0, 0, 0, nullptr};
+  for (int l = 0; l < g.n_layers; ++l) {
+    const Layer& ly = m->layers[l];
+    char* Kl = m->Kc + l * m->kv_layer_bytes;
+    char* Vl = m->Vc + l * m->kv_layer_bytes;
+    launch_pf_norm_split(c->pf_x, ly.attn_norm, g.rms_eps, M, d, c->pf_frag, st);
+    launch_gemm_block(ly.wqkv, 3 * d, d, c->pf_frag, M, c->pf_y, 3 * d, kPermQKV, d, m->hd, 0, st);
+    launch_pf_rope_kv_rows(c->pf_y, M, d, H, pos, slot_stride, c->pf_cs, c->pf_q, reinterpret_cast<_Float16*>(Kl),
+                           reinterpret_cast<_Float16*>(Vl), m->cap, st);
+    launch_attention(c->pf_q, Kl, Vl, 1, m->cap, d, H, pos.rps, pos, nslots, slot_stride, nchunk, c->nchunk_cap, c->part_o,
+                     c->part_ml, c->counters + kGemmCounters, c->pf_attn, st, amode);
+    launch_pf_norm_split(c->pf_attn, nullptr, 0.f, M, d, c->pf_frag, st);
+    launch_gemm_block(ly.wo, d, d, c->pf_frag, M, c->pf_x, d, kPermNone, 0, 0, 1, st);
+    launch_pf_norm_split(c->pf_x, ly.ffn_norm, g.rms_eps, M, d, c->pf_frag, st);
+    launch_gemm_block(ly.wgu, 2 * f, d, c->pf_frag, M, c->pf_y, 2 * f, kPermGateUp, f, 0, 0, st);
+    launch_pf_swiglu_split(c->pf_y, M, f, c->pf_frag, st);
+    launch_gemm_block(ly.wdown, d, f, c->pf_frag, M, c->pf_x, d, kPermNone, 0, 0, 1, st);
+    if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));
+  }
+  if (logits_rows > 0) {
+    launch_pf_norm_split(c->pf_x, m->final_norm, g.rms_eps, M, d, c->pf_frag, st);
+    launch_gemm_block(m->lm_head, V, d, c->pf_frag, M, c->logits, V, kPermNone, 0, 0, 0, st);
+  }
+  HIPCHK(c, hipGetLastError());
+  return STAIRS_OK;
 }
 
 PosRef abs_pos(const stairs_ctx* c, int p) { return PosRef{c->state + 2, p}; }   // state[2] == 0
@@ -1082,6 +1135,7 @@ static int alloc_workspaces(stairs_ctx* c, const WsDims& w) {
   if (c->block_prefill) {
     // rows per block: what the longest sequence needs, at most kPfRows
     const int rows = std::min(kPfRows, (capmax + kBlkRows - 1) / kBlkRows * kBlkRows);
+    c->pf_rows = rows;
     const size_t wide = std::max<size_t>(3 * (size_t)dmax, 2 * (size_t)fmax), inner = std::max<size_t>(dmax, fmax);
     if ((rc = dev_alloc(c, &c->pf_x, (size_t)rows * dmax)) || (rc = dev_alloc(c, &c->pf_y, (size_t)rows * wide)) ||
         (rc = dev_alloc(c, &c->pf_q, (size_t)rows * dmax)) || (rc = dev_alloc(c, &c->pf_attn, (size_t)rows * dmax)) ||
@@ -1459,7 +1513,9 @@ int stairs_encdec_generate(stairs_ctx* c, const int32_t* src, int32_t S, int32_t
 int stairs_reserve_batch(stairs_ctx* c, int32_t max_batch) {
   if (!c) return STAIRS_EINVAL;
   if (c->encdec) return fail(c, STAIRS_EINVAL, "encoder-decoder contexts take one sequence");
-  if (max_batch < 1 || max_batch > kMaxRows / 2) return fail(c, STAIRS_EINVAL, "max_batch outside [1, STAIRS_MAX_ROWS / 2]");
+  if (max_batch < 1 || max_batch > STAIRS_MAX_BATCH) return fail(c, STAIRS_EINVAL, "max_batch outside [1, STAIRS_MAX_BATCH]");
+  if (max_batch > kMaxRows / 2 && !c->block_prefill)
+    return fail(c, STAIRS_EINVAL, "more than STAIRS_MAX_ROWS / 2 sequences need the block kernels (bf16 models, STAIRS_NO_BLOCK_PREFILL unset)");
   if (!c->T.bf16 || (c->have_draft && !c->D.bf16)) return fail(c, STAIRS_EINVAL, "several sequences need bf16 models");
   if (max_batch * std::max(c->T.cfg.n_heads, c->have_draft ? c->D.cfg.n_heads : 0) > kAttnCounters)
     return fail(c, STAIRS_EINVAL, "max_batch * n_heads exceeds the attention hand-off counters");
@@ -1490,6 +1546,25 @@ int stairs_reserve_batch(stairs_ctx* c, int32_t max_batch) {
     m->Kc = K;
     m->Vc = V;
     m->valid = 0;
+  }
+  // forwards of more than kMaxRows rows: logits, target tokens and attention partial results for kMaxBlockRows rows
+  if (max_batch > kMaxRows / 2 && c->rows_cap < kMaxBlockRows) {
+    const int Hmax = std::max(c->T.cfg.n_heads, c->have_draft ? c->D.cfg.n_heads : 0);
+    float *lg = nullptr, *po = nullptr, *pm = nullptr;
+    int* tt = nullptr;
+    if ((rc = dev_alloc(c, &lg, (size_t)kMaxBlockRows * c->T.cfg.vocab)) ||
+        (rc = dev_alloc(c, &po, (size_t)kMaxBlockRows * Hmax * c->nchunk_cap * 128)) ||
+        (rc = dev_alloc(c, &pm, (size_t)kMaxBlockRows * Hmax * c->nchunk_cap * 2)) || (rc = dev_alloc(c, &tt, (size_t)kMaxBlockRows)))
+      return rc;
+    release(c->logits);
+    release(c->part_o);
+    release(c->part_ml);
+    release(c->tgt_tok);
+    c->logits = lg;
+    c->part_o = po;
+    c->part_ml = pm;
+    c->tgt_tok = tt;
+    c->rows_cap = kMaxBlockRows;
   }
   int *tok = nullptr, *state = nullptr;
   if ((rc = dev_alloc(c, &tok, (size_t)max_batch * c->tok_stride)) || (rc = dev_alloc(c, &state, (size_t)(max_batch + 1) * kSlotState)))
@@ -1522,7 +1597,9 @@ int stairs_generate_batch(stairs_ctx* c, const int32_t* const* prompts, const in
   if (G < 0 || (G > 0 && !tokens_out)) return fail(c, STAIRS_EINVAL, "G < 0 or tokens_out is NULL");
   if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
   if (k > 0 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
-  if (B * (k + 1) > kMaxRows || B * 2 > kMaxRows) return fail(c, STAIRS_EINVAL, "B * (k + 1) exceeds STAIRS_MAX_ROWS");
+  const int rows_max = std::max(B * (k + 1), B * 2);
+  if (rows_max > c->rows_cap || (rows_max > kMaxRows && rows_max > c->pf_rows))
+    return fail(c, STAIRS_EINVAL, "B * (k + 1) exceeds the rows one forward takes (STAIRS_MAX_ROWS, or STAIRS_MAX_BATCH_ROWS after a reservation of more than STAIRS_MAX_ROWS / 2 sequences)");
   if (!c->T.bf16 || (c->have_draft && !c->D.bf16)) return fail(c, STAIRS_EINVAL, "several sequences need bf16 models");
   if (!prompts || !P) return fail(c, STAIRS_EINVAL, "prompts or P is NULL");
   for (int b = 0; b < B; ++b) {

@@ -7,7 +7,8 @@
 
 namespace stairs {
 
-constexpr int kMaxRows = 32;        // rows (new tokens) one forward can take
+constexpr int kMaxRows = 32;        // rows (new tokens) one forward of the decode kernels can take
+constexpr int kMaxBlockRows = 256;  // rows one forward of several sequences can take on the block kernels (beyond kMaxRows)
 constexpr int kAttnChunk = 128;     // keys per attention work-group of the fp32-cache kernels and the unit callers count chunks in; boundaries are absolute positions
 constexpr int kAttnChunkH = 256;    // keys per attention work-group of the half-cache kernels (a wave owns 64)
 constexpr int kAttnFusedMaxChunks = 24;   // more chunks per head than this: the chunk merge runs as a second kernel
@@ -213,6 +214,10 @@ void launch_pf_rope_table(int p0, int R, int hd, float theta, float2* cs, hipStr
 // caches of one layer at positions p0 .. p0+R-1
 void launch_pf_rope_kv(const float* y, int R, int d, int H, int p0, const float2* cs, float* q_rot, _Float16* Kc,
                        _Float16* Vc, int cap, hipStream_t st);
+// the same for R rows positioned by `pos` (several sequences: slot s's caches start s * kv_slot_stride elements in);
+// rows without a position write nothing to the caches
+void launch_pf_rope_kv_rows(const float* y, int R, int d, int H, PosRef pos, size_t kv_slot_stride, const float2* cs,
+                            float* q_rot, _Float16* Kc, _Float16* Vc, int cap, hipStream_t st);
 // attention of a prefill block: R consecutive rows at positions p0.. of ONE sequence against its half caches (keys
 // 0 .. own position), q and out [R, d]; running softmax in registers (no partial results, no merge), a wave per 16 rows
 void launch_attention_flash(const float* q, const void* Kc, const void* Vc, int cap, int d, int H, int R, int p0, float* out,

@@ -2721,6 +2721,37 @@ __global__ __launch_bounds__(256) void k_pf_rope_kv(const float* __restrict__ y,
   store_kv(vd + v_cache_off(p, e, hd), yr[2 * d + e]);
   store_kv(vd + v_cache_off(p, e + half, hd), yr[2 * d + e + half]);
 }
+// The same for rows that sit wherever `pos` puts them (several sequences: row r belongs to slot slot_of(pos, r), whose
+// caches start kv_slot_stride elements after the previous slot's); a row without a position writes nothing.
+__global__ __launch_bounds__(256) void k_pf_rope_kv_rows(const float* __restrict__ y, int d, int H, int hd, PosRef pos,
+                                                         size_t kv_slot_stride, const float2* __restrict__ cs,
+                                                         float* __restrict__ q_rot, _Float16* __restrict__ Kc,
+                                                         _Float16* __restrict__ Vc, int cap) {
+  const int r = blockIdx.y, half = hd >> 1;
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= H * half) return;
+  const int h = idx / half, e = idx - h * half;
+  const int p = pos_of(pos, r);
+  const float* yr = y + (size_t)r * 3 * d + h * hd;
+  const float2 c = cs[r * 64 + e];
+  const float2 q = rope_rotate(yr[e], yr[e + half], c);
+  q_rot[(size_t)r * d + h * hd + e] = q.x;
+  q_rot[(size_t)r * d + h * hd + e + half] = q.y;
+  if (p < 0 || p >= cap) return;
+  const size_t off = (size_t)slot_of(pos, r) * kv_slot_stride + (size_t)h * cap * hd;
+  const float2 k = rope_rotate(yr[d + e], yr[d + e + half], c);
+  store_kv(Kc + off + k_cache_off(p, e, hd), k.x);
+  store_kv(Kc + off + k_cache_off(p, e + half, hd), k.y);
+  store_kv(Vc + off + v_cache_off(p, e, hd), yr[2 * d + e]);
+  store_kv(Vc + off + v_cache_off(p, e + half, hd), yr[2 * d + e + half]);
+}
+void launch_pf_rope_kv_rows(const float* y, int R, int d, int H, PosRef pos, size_t kv_slot_stride, const float2* cs,
+                            float* q_rot, _Float16* Kc, _Float16* Vc, int cap, hipStream_t st) {
+  const int hd = d / H;
+  hipLaunchKernelGGL(k_pf_rope_kv_rows, dim3((H * hd / 2 + 255) / 256, R), dim3(256), 0, st, y, d, H, hd, pos, kv_slot_stride, cs,
+                     q_rot, Kc, Vc, cap);
+}
+
 void launch_pf_rope_kv(const float* y, int R, int d, int H, int p0, const float2* cs, float* q_rot, _Float16* Kc,
                        _Float16* Vc, int cap, hipStream_t st) {
   const int hd = d / H;

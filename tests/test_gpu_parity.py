@@ -317,6 +317,51 @@ def test_batch_against_the_oracle():
     assert st.iterations >= G // (k + 1)
 
 
+def test_wide_batches_on_the_block_kernels():
+    """Forwards of more than 32 rows (many sequences) run on the block kernels of the prompt ingestion.  Every token
+    must be an eps-greedy choice under the oracle's logits for the sequence's own prefix; a sequence's tokens do not
+    depend on which other sequences share the forward (20 sequences x 3 rows against 12 x 3 rows); graph replay equals
+    one-by-one launches; k = 0 (a batch of plain greedy decodes) and the limits."""
+    import os
+    w, target, draft = _batch_pair()
+    lengths = [5, 70, 33, 64, 20, 1, 129, 17, 90, 40, 65, 8, 100, 31, 32, 2, 77, 50, 128, 11]
+    prompts = _prompts(w, lengths)
+    G, k = 20, 2
+    T = so.OracleModel(target, np.float64)
+    with pkg.Stairs(target, draft, k_max=3, max_seq=256) as s:
+        s.reserve_batch(40)
+        toks, st = s.generate_batch(prompts, G, k)                    # 60 rows per verification, 40 / 20 per draft step
+        assert toks.shape == (len(prompts), G) and st.tokens == len(prompts) * G
+        part, _ = s.generate_batch(prompts[:12], G, k)                # 36 rows
+        assert np.array_equal(part, toks[:12])
+        plain, _ = s.generate_batch(prompts + prompts, G, 0)          # 40 sequences, k = 0: 40 rows
+        assert np.array_equal(plain[:20], plain[20:])
+        with pytest.raises(pkg.StairsError) as e:
+            s.generate_batch(prompts + prompts, 4, 7)                 # 40 x 8 rows do not fit
+        assert e.value.code == -1
+        small, _ = s.generate_batch(prompts[:4], G, k)                # 12 rows: the decode kernels, bit-exact path
+        alone, _ = s.generate(prompts[1], G, k)
+        assert np.array_equal(small[1], alone)
+    mism = 0
+    for out in (toks, plain[:20]):
+        for b, p in enumerate(prompts):
+            seq = np.concatenate([p, out[b]])
+            logits = so.forward_full(T, seq[:-1])
+            for j in range(G):
+                row = logits[len(p) - 1 + j]
+                assert row[out[b][j]] >= row.max() - MARGIN_TOL, (b, j)
+                mism += int(np.argmax(row)) != int(out[b][j])
+    _log(f"wide batch: {st.iterations} iterations, {mism} tokens differ from the oracle's argmax (near-ties)")
+    os.environ["STAIRS_NO_GRAPH"] = "1"
+    try:
+        with pkg.Stairs(target, draft, k_max=3, max_seq=256) as s:
+            s.reserve_batch(20)
+            toks2, _ = s.generate_batch(prompts, G, k)
+    finally:
+        del os.environ["STAIRS_NO_GRAPH"]
+    assert np.array_equal(toks2, toks)
+
+
 def test_batch_limits_and_errors():
     w, target, draft = _batch_pair()
     prompts = _prompts(w, [8, 9])
@@ -336,7 +381,7 @@ def test_batch_limits_and_errors():
         empty, st = s.generate_batch(prompts, 0, 3)
         assert empty.shape == (2, 0) and st.iterations == 0
         with pytest.raises(pkg.StairsError):
-            s.reserve_batch(17)
+            s.reserve_batch(129)                              # beyond STAIRS_MAX_BATCH
     fp32 = si.scaled_workload("cfg1_tiny_fp32")
     t32, d32 = si.make_pair(fp32)
     with pkg.Stairs(t32, d32, k_max=2, max_seq=64) as s:
