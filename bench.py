@@ -289,21 +289,31 @@ def main():
     if not args.no_sweep and w["dtype"] == "bf16":
         rngp = np.random.default_rng([w["seed"], 4242])
         V = w["target"]["vocab"]
-        prompts = [prompt] + [rngp.integers(0, V, P).astype(np.int32) for _ in range(7)]
-        eng.reserve_batch(8)
+        n_seq = 64
+        prompts = [prompt] + [rngp.integers(0, V, P).astype(np.int32) for _ in range(n_seq - 1)]
+        eng.reserve_batch(n_seq)
         batched = {}
-        for B, kk in ((2, k), (4, k), (8, k), (8, 3), (16, 1)):
-            if B > 8 or B * (kk + 1) > 32:
+        flop_per_row = 2.0 * 2.0 * target.n_params()          # high and low part of every activation
+        for B, kk in ((2, k), (4, k), (8, k), (8, 3), (16, k), (32, k), (64, k)):
+            rows = B * (kk + 1)
+            if rows > 256:
                 continue
             toks_b, st_b = eng.generate_batch(prompts[:B], G, kk)
-            assert np.array_equal(toks_b[0], toks0), "a sequence of the batch differs from the same sequence alone"
-            batched[f"B{B}_k{kk}"] = {"sequences": B, "k": kk, "rows_per_forward": B * (kk + 1),
+            if rows <= 32:      # the decode kernels: bit for bit the sequence alone
+                assert np.array_equal(toks_b[0], toks0), "a sequence of the batch differs from the same sequence alone"
+            ms_v = st_b.ms_verify / max(1, st_b.iterations)
+            batched[f"B{B}_k{kk}"] = {"sequences": B, "k": kk, "rows_per_forward": rows,
+                                      "kernels": "decode (weight-streaming)" if rows <= 32 else "block (MFMA GEMM)",
                                       "tokens_per_s": B * G / (st_b.ms_decode * 1e-3), "iterations": st_b.iterations,
-                                      "ms_verify_per_iteration": st_b.ms_verify / max(1, st_b.iterations),
+                                      "ms_verify_per_iteration": ms_v,
+                                      "verify_weight_GBps": target.weight_bytes_streamed() / (ms_v * 1e-3) / 1e9,
+                                      "verify_mfma_frac": flop_per_row * rows / (ms_v * 1e-3) / 2.5e15,
                                       "ms_draft_per_iteration": st_b.ms_draft / max(1, st_b.iterations),
-                                      "prefill_ms": st_b.ms_prefill}
-            log(f"[bench] batch B={B} k={kk}: {batched[f'B{B}_k{kk}']['tokens_per_s']:.0f} tok/s aggregate, "
-                f"{st_b.iterations} iterations, verify {batched[f'B{B}_k{kk}']['ms_verify_per_iteration']:.2f} ms/iteration")
+                                      "prefill_ms": st_b.ms_prefill,
+                                      "tokens_equal_sequence_alone": bool(np.array_equal(toks_b[0], toks0))}
+            log(f"[bench] batch B={B} k={kk} ({rows} rows): {batched[f'B{B}_k{kk}']['tokens_per_s']:.0f} tok/s aggregate, "
+                f"{st_b.iterations} iterations, verify {ms_v:.2f} ms/iteration, "
+                f"MFMA {100 * batched[f'B{B}_k{kk}']['verify_mfma_frac']:.1f} %")
         extras["batched_sequences"] = batched
     eng.close()
 

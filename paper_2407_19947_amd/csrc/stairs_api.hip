@@ -89,6 +89,8 @@ struct stairs_ctx {
   bool block_prefill = false;
   float *pf_x = nullptr, *pf_y = nullptr, *pf_q = nullptr, *pf_attn = nullptr;
   uint4* pf_frag = nullptr;    // block fragments of the activation in front of the current projection
+  float* pf_part = nullptr;    // k-split results of block GEMMs with few rows (forwards of many sequences)
+  size_t pf_part_floats = 0;
   float2* pf_cs = nullptr;
   // encoder-decoder contexts: source tokens and the encoder's activations [max_src, .]
   bool encdec = false;
@@ -574,22 +576,22 @@ int forward_block(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int lo
     char* Kl = m->Kc + l * m->kv_layer_bytes;
     char* Vl = m->Vc + l * m->kv_layer_bytes;
     launch_pf_norm_split(c->pf_x, ly.attn_norm, g.rms_eps, M, d, c->pf_frag, st);
-    launch_gemm_block(ly.wqkv, 3 * d, d, c->pf_frag, M, c->pf_y, 3 * d, kPermQKV, d, m->hd, 0, st);
+    launch_gemm_block(ly.wqkv, 3 * d, d, c->pf_frag, M, c->pf_y, 3 * d, kPermQKV, d, m->hd, 0, st, c->pf_part, c->pf_part_floats);
     launch_pf_rope_kv_rows(c->pf_y, M, d, H, pos, slot_stride, c->pf_cs, c->pf_q, reinterpret_cast<_Float16*>(Kl),
                            reinterpret_cast<_Float16*>(Vl), m->cap, st);
     launch_attention(c->pf_q, Kl, Vl, 1, m->cap, d, H, pos.rps, pos, nslots, slot_stride, nchunk, c->nchunk_cap, c->part_o,
                      c->part_ml, c->counters + kGemmCounters, c->pf_attn, st, amode);
     launch_pf_norm_split(c->pf_attn, nullptr, 0.f, M, d, c->pf_frag, st);
-    launch_gemm_block(ly.wo, d, d, c->pf_frag, M, c->pf_x, d, kPermNone, 0, 0, 1, st);
+    launch_gemm_block(ly.wo, d, d, c->pf_frag, M, c->pf_x, d, kPermNone, 0, 0, 1, st, c->pf_part, c->pf_part_floats);
     launch_pf_norm_split(c->pf_x, ly.ffn_norm, g.rms_eps, M, d, c->pf_frag, st);
-    launch_gemm_block(ly.wgu, 2 * f, d, c->pf_frag, M, c->pf_y, 2 * f, kPermGateUp, f, 0, 0, st);
+    launch_gemm_block(ly.wgu, 2 * f, d, c->pf_frag, M, c->pf_y, 2 * f, kPermGateUp, f, 0, 0, st, c->pf_part, c->pf_part_floats);
     launch_pf_swiglu_split(c->pf_y, M, f, c->pf_frag, st);
-    launch_gemm_block(ly.wdown, d, f, c->pf_frag, M, c->pf_x, d, kPermNone, 0, 0, 1, st);
+    launch_gemm_block(ly.wdown, d, f, c->pf_frag, M, c->pf_x, d, kPermNone, 0, 0, 1, st, c->pf_part, c->pf_part_floats);
     if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));
   }
   if (logits_rows > 0) {
     launch_pf_norm_split(c->pf_x, m->final_norm, g.rms_eps, M, d, c->pf_frag, st);
-    launch_gemm_block(m->lm_head, V, d, c->pf_frag, M, c->logits, V, kPermNone, 0, 0, 0, st);
+    launch_gemm_block(m->lm_head, V, d, c->pf_frag, M, c->logits, V, kPermNone, 0, 0, 0, st, c->pf_part, c->pf_part_floats);
   }
   HIPCHK(c, hipGetLastError());
   return STAIRS_OK;
@@ -1552,7 +1554,8 @@ int stairs_reserve_batch(stairs_ctx* c, int32_t max_batch) {
     const int Hmax = std::max(c->T.cfg.n_heads, c->have_draft ? c->D.cfg.n_heads : 0);
     float *lg = nullptr, *po = nullptr, *pm = nullptr;
     int* tt = nullptr;
-    if ((rc = dev_alloc(c, &lg, (size_t)kMaxBlockRows * c->T.cfg.vocab)) ||
+    c->pf_part_floats = (size_t)16 << 20;
+    if ((rc = dev_alloc(c, &c->pf_part, c->pf_part_floats)) || (rc = dev_alloc(c, &lg, (size_t)kMaxBlockRows * c->T.cfg.vocab)) ||
         (rc = dev_alloc(c, &po, (size_t)kMaxBlockRows * Hmax * c->nchunk_cap * 128)) ||
         (rc = dev_alloc(c, &pm, (size_t)kMaxBlockRows * Hmax * c->nchunk_cap * 2)) || (rc = dev_alloc(c, &tt, (size_t)kMaxBlockRows)))
       return rc;

@@ -200,8 +200,10 @@ inline int pf_col_tiles(int R) { return (R + kBlkRows - 1) / kBlkRows * (kBlkRow
 inline size_t pf_frag_bytes(int R, int K) { return (size_t)(K / 32) * pf_col_tiles(R) * 2 * 1024; }
 // Y[R, N] = (accumulate ? Y : 0) + X . W^T; W [N, K] in the operand-tile layout with row permutation (perm, p0, p1)
 // as given to launch_swizzle_bf16 (Y's columns are in natural order), xfrag the fragments of X [R, K]
+// part (optional, part_floats floats): scratch that lets a launch with few rows cut k into pieces for more work-groups
+// (the pieces' results are added in a fixed order by a second kernel)
 void launch_gemm_block(const void* W, int N, int K, const uint4* xfrag, int R, float* Y, int ldy, int perm, int p0, int p1,
-                       int accumulate, hipStream_t st);
+                       int accumulate, hipStream_t st, float* part = nullptr, size_t part_floats = 0);
 // x[r][:] = emb[tokens[p0 + r]][:] as float, r < R (zeros for a position outside [0, tok_cap) or an id outside [0, vocab))
 void launch_pf_embed(const uint16_t* emb, const int* tokens, int p0, int tok_cap, int vocab, int R, int d, float* x,
                      hipStream_t st);

@@ -2519,8 +2519,11 @@ constexpr int kBlkStageU4 = kBlkKs * (kBlkRows / 16) * 2 * 64;   // uint4 per st
 __global__ __launch_bounds__(512) void k_gemm_bf16_block(const uint4* __restrict__ Wsw, int NTILES, int K,
                                                          const uint4* __restrict__ XF, int RT, int R,
                                                          float* __restrict__ Y, int ldy, int perm, int p0, int p1,
-                                                         int accumulate) {
+                                                         int accumulate, int stages_per_split, size_t split_stride) {
   // 8 waves: wave = (row half rh, feature group fw); a wave owns 4 weight tiles x 4 column tiles (64 x 64 outputs)
+  // blockIdx.z = k split: with few rows and few features there are too few (feature, row) blocks to fill the chip, so
+  // the k range is cut into gridDim.z pieces whose results go to Y + z * split_stride and are added up, in split
+  // order, by k_block_reduce
   constexpr int NT = 4, CT = kBlkRows / 32, CTW = kBlkRows / 16;
   extern __shared__ uint4 lds[];                       // [2][kBlkStageU4]
   const int tid = threadIdx.x, lane = tid & 63;
@@ -2530,7 +2533,10 @@ __global__ __launch_bounds__(512) void k_gemm_bf16_block(const uint4* __restrict
   const int tile0 = (blockIdx.x * 4 + fw) * NT;
   const int ct0 = blockIdx.y * CTW;                    // first column tile of the work-group
   const int units_total = K / kUnitK;
-  const int nstages = (K >> 5) / kBlkKs;               // K is a multiple of 256: whole stages
+  const int nstages_all = (K >> 5) / kBlkKs;           // K is a multiple of 256: whole stages
+  const int stage0 = blockIdx.z * stages_per_split;
+  const int nstages = min(nstages_all, stage0 + stages_per_split);     // this split's stages: [stage0, nstages)
+  Y += blockIdx.z * split_stride;
   int tile_c[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) tile_c[t] = min(tile0 + t, NTILES - 1);
@@ -2593,11 +2599,11 @@ __global__ __launch_bounds__(512) void k_gemm_bf16_block(const uint4* __restrict
   // before the arithmetic of the current one (unconditionally: past the end the last stage is read again).  Two waves
   // per SIMD fill each other's waits for LDS and memory.
   uint4 a0[kBlkKs][NT], a1[kBlkKs][NT], breg[kBlkKs * 2];
-  load_b(breg, 0);
-  load_a(a0, 0);
+  load_b(breg, stage0);
+  load_a(a0, stage0);
   store_b(breg, 0);
   __syncthreads();
-  for (int st = 0; st < nstages; st += 2) {
+  for (int st = stage0; st < nstages; st += 2) {
     load_b(breg, min(st + 1, nstages - 1));
     load_a(a1, min(st + 1, nstages - 1));
     __builtin_amdgcn_sched_barrier(0);
@@ -2634,12 +2640,46 @@ __global__ __launch_bounds__(512) void k_gemm_bf16_block(const uint4* __restrict
   }
 }
 
+// Y = (accumulate ? Y : 0) + part[0] + part[1] + ... (in that order): the k splits of a block GEMM with few rows
+__global__ __launch_bounds__(256) void k_block_reduce(const float* __restrict__ part, int nsplit, size_t split_stride, int R, int N,
+                                                      float* __restrict__ Y, int ldy, int accumulate) {
+  const int r = blockIdx.y, c = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (c >= N) return;
+  float4* dst = reinterpret_cast<float4*>(Y + (size_t)r * ldy + c);
+  float4 a = accumulate ? *dst : make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int z = 0; z < nsplit; ++z) {
+    const float4 v = *reinterpret_cast<const float4*>(part + z * split_stride + (size_t)r * N + c);
+    a.x = a.x + v.x; a.y = a.y + v.y; a.z = a.z + v.z; a.w = a.w + v.w;
+  }
+  *dst = a;
+}
+
 void launch_gemm_block(const void* W, int N, int K, const uint4* xfrag, int R, float* Y, int ldy, int perm, int p0, int p1,
-                       int accumulate, hipStream_t st) {
+                       int accumulate, hipStream_t st, float* part, size_t part_floats) {
   const int NTILES = N / 16;
-  dim3 grid((NTILES + 15) / 16, (R + kBlkRows - 1) / kBlkRows), block(512);
-  hipLaunchKernelGGL(k_gemm_bf16_block, grid, block, 2 * kBlkStageU4 * sizeof(uint4), st, static_cast<const uint4*>(W), NTILES,
-                     K, xfrag, pf_col_tiles(R), R, Y, ldy, perm, p0, p1, accumulate);
+  const int FB = (NTILES + 15) / 16, RB = (R + kBlkRows - 1) / kBlkRows;
+  const int nstages = (K / 32) / kBlkKs;
+  // few (feature, row) blocks: cut k into pieces until about every CU has a work-group (each piece at least 8 stages
+  // and an even number of them), as far as the scratch for the pieces' results reaches
+  int nsplit = 1;
+  if (part && FB * RB < 160) {
+    nsplit = std::min({(256 + FB * RB - 1) / (FB * RB), nstages / 8, (int)(part_floats / ((size_t)R * N))});
+    nsplit = std::max(nsplit, 1);
+  }
+  int per = (nstages + nsplit - 1) / nsplit;
+  per += per & 1;
+  nsplit = (nstages + per - 1) / per;
+  dim3 grid(FB, RB, nsplit), block(512);
+  const size_t lds = 2 * kBlkStageU4 * sizeof(uint4);
+  if (nsplit == 1) {
+    hipLaunchKernelGGL(k_gemm_bf16_block, grid, block, lds, st, static_cast<const uint4*>(W), NTILES, K, xfrag, pf_col_tiles(R), R, Y,
+                       ldy, perm, p0, p1, accumulate, per, (size_t)0);
+    return;
+  }
+  const size_t stride = (size_t)R * N;
+  hipLaunchKernelGGL(k_gemm_bf16_block, grid, block, lds, st, static_cast<const uint4*>(W), NTILES, K, xfrag, pf_col_tiles(R), R, part,
+                     N, perm, p0, p1, 0, per, stride);
+  hipLaunchKernelGGL(k_block_reduce, dim3((N / 4 + 255) / 256, R), dim3(256), 0, st, part, nsplit, stride, R, N, Y, ldy, accumulate);
 }
 
 __global__ __launch_bounds__(256) void k_pf_embed(const uint16_t* __restrict__ emb, const int* __restrict__ tokens, int p0,
