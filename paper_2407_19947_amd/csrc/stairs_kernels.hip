@@ -1116,12 +1116,13 @@ static size_t rows_path_lds(int role, int M, int N, int K) {
 
 // Launch shape of k_gemm_bf16_wide: NT weight tiles per wave and NW waves that split the k chunks; nt == 0: the
 // split-K kernel instead.  Measured on 7B-class projections (isolated launches, 8 / 17 rows, microseconds; split-K
-// in brackets): gate/up 1376 tiles 8/4 33 / 46 (37 / 48), unembedding 2000 tiles 8/4 41 / 55 (48 / 63), QKV 768 tiles
-// 4/4 21 / 30 (23 / 33), attention-out 256 tiles 1/8 10.4 / 24 (11.4 / 15.4), down 256 tiles and 22 chunks 1/4 23 /
-// 38 (21 / 34).  More tiles per wave means fewer fragment reads per weight byte (2 CT / NT), which is what the
-// launches with many tiles are bound by beyond the weight stream; with few tiles (N = d_model) there are too few
-// work-groups for that and split-K's extra parallelism wins once the fragments double (more than 16 rows) or k is long.
+// in brackets): gate/up 1376 tiles 8/4 33 / 36 (37 / 48), unembedding 2000 tiles 8/4 41 / 43 (48 / 63), QKV 768 tiles
+// 4/4 21 / 25 (23 / 33), attention-out 256 tiles 1/8 10.4 / 13.4 (11.4 / 15.4), down 256 tiles and 22 chunks 1/4 23 /
+// 32 (21 / 34).  More tiles per wave means fewer fragment reads and fewer, longer-lived waves per weight byte; with
+// few tiles (N = d_model) that leaves too few work-groups, and for a long k at up to 16 rows split-K's extra
+// parallelism still wins.
 struct WideCfg { int nt, nw; };
+constexpr int wide_depth2(int depth1) { return depth1 <= 2 ? 1 : depth1 <= 3 ? 2 : depth1 <= 5 ? 3 : 5; }   // ring depth at two column tiles
 static WideCfg wide_cfg(int role, int M, int NTILES, int K) {
   // STAIRS_WIDE_CFG="nt/nw,nt/nw,nt/nw,nt/nw,nt/nw" (QKV, out, gate-up, down, head; nt = 0: split-K) overrides the
   // choice: tuning aid
@@ -1141,7 +1142,8 @@ static WideCfg wide_cfg(int role, int M, int NTILES, int K) {
   WideCfg c{0, 0};
   if (NTILES >= 1024) c = {8, std::min(4, nchunks)};
   else if (NTILES >= 512) c = {4, std::min(4, nchunks)};
-  else if (NTILES >= 192 && M <= 16 && nchunks <= 8) c = {1, std::min(8, nchunks)};
+  else if (NTILES >= 192 && nchunks <= 8) c = {1, std::min(8, nchunks)};
+  else if (NTILES >= 192 && M > 16) c = {1, 4};          // long k: only with two column tiles does it beat split-K
   if ((int)forced.size() == 5) {
     const WideCfg f = forced[role];
     if ((f.nt == 0 || f.nt == 1 || f.nt == 2 || f.nt == 4 || f.nt == 8) && f.nw >= 1 && f.nw <= 8) c = f;
@@ -1294,9 +1296,10 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
       launch_gemm_kernel(k_gemm_bf16_wide<ct, nt, dp, false>, grid, block, lds, st, Wsw, NTILES, xfrag, M, nrm, K, N,    \
                          role, epi);                                                                                     \
   } while (0)
+  // (two column tiles hold one k-step less in flight: a deeper ring would not fit the 256 registers of a wave)
 #define STAIRS_WIDE_CT(nt, dp)       \
   if (CT == 1) STAIRS_WIDE(1, nt, dp); \
-  else STAIRS_WIDE(2, nt, dp)
+  else STAIRS_WIDE(2, nt, wide_depth2(dp))
     if (wc.nt == 8) { STAIRS_WIDE_CT(8, kWideDepth8); }
     else if (wc.nt == 4) { STAIRS_WIDE_CT(4, kWideDepth4); }
     else if (wc.nt == 2) { STAIRS_WIDE_CT(2, kWideDepth2); }
@@ -2843,7 +2846,10 @@ hipError_t configure_kernels() {
   STAIRS_OPTIN(4);
 #undef STAIRS_OPTIN2
 #undef STAIRS_OPTIN
-#define STAIRS_OPTIN_WIDE(ct, nt, dp)                                            \
+#define STAIRS_OPTIN_WIDE(ct, nt, dp0)                                           \
+  constexpr int dp_##ct##_##nt = (ct) == 1 ? (dp0) : wide_depth2(dp0);          \
+  STAIRS_OPTIN_WIDE_(ct, nt, dp_##ct##_##nt)
+#define STAIRS_OPTIN_WIDE_(ct, nt, dp)                                           \
   optin((const void*)k_gemm_bf16_wide<ct, nt, dp, true>, kWideMaxLds);            \
   optin((const void*)k_gemm_bf16_wide<ct, nt, dp, false>, kWideMaxLds)
   STAIRS_OPTIN_WIDE(1, 8, kWideDepth8); STAIRS_OPTIN_WIDE(2, 8, kWideDepth8);
@@ -2851,6 +2857,7 @@ hipError_t configure_kernels() {
   STAIRS_OPTIN_WIDE(1, 2, kWideDepth2); STAIRS_OPTIN_WIDE(2, 2, kWideDepth2);
   STAIRS_OPTIN_WIDE(1, 1, kWideDepth1); STAIRS_OPTIN_WIDE(2, 1, kWideDepth1);
 #undef STAIRS_OPTIN_WIDE
+#undef STAIRS_OPTIN_WIDE_
   optin((const void*)k_gemm_bf16_block, 2 * kBlkStageU4 * sizeof(uint4));
   // the stand-alone attention merge keeps a table of all chunks in LDS: large for long contexts (the fused
   // merge runs for at most kAttnFusedMaxChunks chunks and stays small)
