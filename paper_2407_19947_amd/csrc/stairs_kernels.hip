@@ -2554,23 +2554,7 @@ __global__ __launch_bounds__(512) void k_gemm_bf16_block(const uint4* __restrict
       for (int t = 0; t < NT; ++t) a[ks][t] = wbase[(size_t)tile_c[t] * ksteps_c * 64];
     }
   };
-  // the stage's fragments: per k-step the work-group's 8 column tiles x (high, low) are 1024 consecutive uint4
-  auto load_b = [&](uint4 (&b)[kBlkKs * 2], int stage) {
-#pragma unroll
-    for (int ks = 0; ks < kBlkKs; ++ks) {
-      const uint4* src = XF + ((size_t)(stage * kBlkKs + ks) * RT + ct0) * 2 * 64 + tid;
-#pragma unroll
-      for (int i = 0; i < 2; ++i) b[ks * 2 + i] = src[i * 512];
-    }
-  };
-  auto store_b = [&](const uint4 (&b)[kBlkKs * 2], int buf) {
-    uint4* dst = lds + buf * kBlkStageU4 + tid;
-#pragma unroll
-    for (int ks = 0; ks < kBlkKs; ++ks)
-#pragma unroll
-      for (int i = 0; i < 2; ++i) dst[ks * 1024 + i * 512] = b[ks * 2 + i];
-  };
-
+  // (the stage's fragments: per k-step the work-group's 8 column tiles x (high, low) are 1024 consecutive uint4)
   f32x4 acc[NT][CT];
 #pragma unroll
   for (int t = 0; t < NT; ++t)
@@ -2601,26 +2585,46 @@ __global__ __launch_bounds__(512) void k_gemm_bf16_block(const uint4* __restrict
   // two stages per turn so that the weight registers alternate without copies; requests of the next stage go out
   // before the arithmetic of the current one (unconditionally: past the end the last stage is read again).  Two waves
   // per SIMD fill each other's waits for LDS and memory.
-  uint4 a0[kBlkKs][NT], a1[kBlkKs][NT], breg[kBlkKs * 2];
-  load_b(breg, stage0);
+  uint4 a0[kBlkKs][NT], a1[kBlkKs][NT];
+  uint4 b0, b1, b2, b3;                                 // the stage's fragments on their way to LDS (2 k-steps x 2)
+#define STAIRS_LOAD_B(stage)                                                                      \
+  do {                                                                                            \
+    const uint4* src_ = XF + ((size_t)((stage) * kBlkKs) * RT + ct0) * 2 * 64 + tid;              \
+    b0 = src_[0];                                                                                 \
+    b1 = src_[512];                                                                               \
+    b2 = src_[(size_t)RT * 2 * 64];                                                               \
+    b3 = src_[(size_t)RT * 2 * 64 + 512];                                                         \
+  } while (0)
+#define STAIRS_STORE_B(buf)                                  \
+  do {                                                       \
+    uint4* dst_ = lds + (buf) * kBlkStageU4 + tid;           \
+    dst_[0] = b0;                                            \
+    dst_[512] = b1;                                          \
+    dst_[1024] = b2;                                         \
+    dst_[1536] = b3;                                         \
+  } while (0)
+  static_assert(kBlkKs == 2, "the fragment staging above is written for two k-steps per stage");
+  STAIRS_LOAD_B(stage0);
   load_a(a0, stage0);
-  store_b(breg, 0);
+  STAIRS_STORE_B(0);
   __syncthreads();
   for (int st = stage0; st < nstages; st += 2) {
-    load_b(breg, min(st + 1, nstages - 1));
+    STAIRS_LOAD_B(min(st + 1, nstages - 1));
     load_a(a1, min(st + 1, nstages - 1));
     __builtin_amdgcn_sched_barrier(0);
     compute(a0, 0);
-    store_b(breg, 1);
+    STAIRS_STORE_B(1);
     __syncthreads();
     if (st + 1 >= nstages) break;
-    load_b(breg, min(st + 2, nstages - 1));
+    STAIRS_LOAD_B(min(st + 2, nstages - 1));
     load_a(a0, min(st + 2, nstages - 1));
     __builtin_amdgcn_sched_barrier(0);
     compute(a1, 1);
-    store_b(breg, 0);
+    STAIRS_STORE_B(0);
     __syncthreads();
   }
+#undef STAIRS_LOAD_B
+#undef STAIRS_STORE_B
 
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
