@@ -1698,6 +1698,10 @@ __device__ __forceinline__ void split_half8(const float* v, f16x8& hi, f16x8& lo
 // More chunks: groups of kMergeCB chunks are summed by different threads in parallel (each as above, from zero) and the
 // group sums added in group order; the grouping depends only on the row's own position.  Dynamic LDS:
 // [M][nch_lds][2] pairs (weight, sum), [kMaxRows] unused, [rows_per_pass][HD/4][groups][5] group sums.
+// e^x for the attention softmax of the half-cache kernels: the hardware's exp2 on x * log2(e) (two instructions, about
+// 1 ulp; the library expf costs ten times that and a wave evaluates 16 per key block).  Arguments are <= 0 here.
+__device__ __forceinline__ float exp_fast(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896340736f); }
+
 constexpr int kMergeCB = 20;
 template <int HD>
 __device__ __forceinline__ void attn_merge(const float* part_o, const float* part_ml, int H, int h, int M, int pos0, int step,
@@ -1723,7 +1727,7 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
     // maximum in the table (the lane that read the slot writes it)
     for (int cc = lane; cc < nch; cc += 64) {
       const float mc = s_ml[((size_t)m * nch_lds + cc) * 2];
-      s_ml[((size_t)m * nch_lds + cc) * 2] = (mc == -INFINITY) ? 0.f : expf(mc - g);
+      s_ml[((size_t)m * nch_lds + cc) * 2] = (mc == -INFINITY) ? 0.f : exp_fast(mc - g);
     }
   }
   __syncthreads();
@@ -1943,7 +1947,7 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
         float pv[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          pv[i] = (mx == -INFINITY) ? 0.f : expf(sc[sb][i] - mx);
+          pv[i] = (mx == -INFINITY) ? 0.f : exp_fast(sc[sb][i] - mx);
           sum += pv[i];
         }
         split_half8(pv, ph[sb], pl[sb]);
@@ -1982,8 +1986,8 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
       if (m < M) {
         const float m0 = s_m[0][jj], m1 = s_m[1][jj], m2 = s_m[2][jj], m3 = s_m[3][jj];
         const float mcc = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
-        const float f0 = (m0 == -INFINITY) ? 0.f : expf(m0 - mcc), f1 = (m1 == -INFINITY) ? 0.f : expf(m1 - mcc);
-        const float f2 = (m2 == -INFINITY) ? 0.f : expf(m2 - mcc), f3 = (m3 == -INFINITY) ? 0.f : expf(m3 - mcc);
+        const float f0 = (m0 == -INFINITY) ? 0.f : exp_fast(m0 - mcc), f1 = (m1 == -INFINITY) ? 0.f : exp_fast(m1 - mcc);
+        const float f2 = (m2 == -INFINITY) ? 0.f : exp_fast(m2 - mcc), f3 = (m3 == -INFINITY) ? 0.f : exp_fast(m3 - mcc);
         const float2 a0 = *reinterpret_cast<const float2*>(&s_o[0][jj][e]), a1 = *reinterpret_cast<const float2*>(&s_o[1][jj][e]);
         const float2 a2 = *reinterpret_cast<const float2*>(&s_o[2][jj][e]), a3 = *reinterpret_cast<const float2*>(&s_o[3][jj][e]);
         const float o0 = __fadd_rn(__fadd_rn(__fadd_rn(__fmul_rn(a0.x, f0), __fmul_rn(a1.x, f1)), __fmul_rn(a2.x, f2)), __fmul_rn(a3.x, f3));
@@ -2104,11 +2108,11 @@ __global__ __launch_bounds__(256, 2) void k_attn_flash(const float* __restrict__
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float m_new = fmaxf(m_run, mx);
-    const float alpha = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);   // m_new >= m_run > -inf there
+    const float alpha = (m_run == -INFINITY) ? 0.f : exp_fast(m_run - m_new);   // m_new >= m_run > -inf there
     float pv[8], sum = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      pv[i] = (m_new == -INFINITY) ? 0.f : expf(sc[i] - m_new);
+      pv[i] = (m_new == -INFINITY) ? 0.f : exp_fast(sc[i] - m_new);
       sum += pv[i];
     }
     sum += __shfl_xor(sum, 16);
