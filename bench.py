@@ -289,14 +289,18 @@ def main():
     if not args.no_sweep and w["dtype"] == "bf16":
         rngp = np.random.default_rng([w["seed"], 4242])
         V = w["target"]["vocab"]
+        # every sequence has K/V caches of its own (both models, half precision): as many slots as fit 128 GB
+        kv_per_seq = sum(2 * 2 * m.n_layers * m.n_heads * m.head_dim for m in (target, draft)) * (P + G + k_max + 8)
         n_seq = 64
+        while n_seq > 8 and n_seq * kv_per_seq > 128e9:
+            n_seq //= 2
         prompts = [prompt] + [rngp.integers(0, V, P).astype(np.int32) for _ in range(n_seq - 1)]
         eng.reserve_batch(n_seq)
         batched = {}
         flop_per_row = 2.0 * 2.0 * target.n_params()          # high and low part of every activation
         for B, kk in ((2, k), (4, k), (8, k), (8, 3), (16, k), (32, k), (64, k)):
             rows = B * (kk + 1)
-            if rows > 256:
+            if rows > 256 or B > n_seq:
                 continue
             toks_b, st_b = eng.generate_batch(prompts[:B], G, kk)
             if rows <= 32:      # the decode kernels: bit for bit the sequence alone

@@ -104,8 +104,9 @@ void stairs_free(stairs_ctx *ctx);
 
 /* Start a new sequence S = prompt[0..P) (the text both models start from, Sec. 3.3 first
  * paragraph): both models ingest prompt[0..P-2] into their KV caches; the last prompt token is
- * the first row of the first stair batch.  Prompts of 64 rows and more are ingested in blocks of up to 512 rows (bf16 models; library
- * GEMMs on row-major copies of the weights), shorter ones with the decode kernels.  Requires 1 <= P and
+ * the first row of the first stair batch.  Prompts of 64 rows and more are ingested in blocks of
+ * up to 2048 rows (bf16 models; the library's own MFMA block GEMM on the same weight tiles the
+ * decode kernels read), shorter ones with the decode kernels.  Requires 1 <= P and
  * P + k_max + 1 <= max_seq of both models.
  * Errors: EINVAL (NULL, P < 1, token id outside [0, vocab)), ECAPACITY. */
 int stairs_prefill(stairs_ctx *ctx, const int32_t *prompt, int32_t P);

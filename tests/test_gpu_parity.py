@@ -391,7 +391,7 @@ def test_batch_limits_and_errors():
 
 
 def test_block_prefill_against_row_prefill_and_oracle(monkeypatch):
-    """Prompts of 64 rows and more are ingested in blocks with library GEMMs; the first stair batch after either
+    """Prompts of 64 rows and more are ingested in blocks on the block GEMM; the first stair batch after either
     kind of prefill must agree with the oracle, and the two kinds with each other far inside the tolerance."""
     w = si.scaled_workload("cfg2_125m", target=dict(n_layers=3, d_model=256, n_heads=4, d_ffn=768, vocab=2048),
                            draft=dict(kind="prefix", n_layers=1), P=600, G=8)
