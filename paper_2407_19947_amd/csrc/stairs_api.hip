@@ -124,7 +124,8 @@ struct stairs_ctx {
   int probe_role = -1;               // role being timed in situ, -1 = none, kProbeEmptyPair = calibration
   bool own_stream = false;
   bool use_graphs = true;      // env STAIRS_NO_GRAPH=1 turns replay off
-  bool sync_launches = false;  // env STAIRS_SYNC_LAUNCHES=1: wait after every kernel (for counter-collecting profilers)
+  bool sync_launches = false;  // env STAIRS_SYNC_LAUNCHES=1 or 2: wait after every kernel (for counter-collecting profilers)
+  bool sync_blocks = false;    // =2: prompts still go through the block kernels (=1: through the decode kernels)
   std::string err;
 };
 
@@ -766,28 +767,45 @@ int ingest_blocks(stairs_ctx* c, Model* m, int from, int to, int slot) {
   hipStream_t st = c->st;
   const size_t slot_bytes = (size_t)g.n_layers * m->kv_layer_bytes;
   const int* tokens = c->tokens + (size_t)slot * c->tok_stride;
+#define PF_SYNC()                                               \
+  do {                                                          \
+    if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));  \
+  } while (0)
   for (int p0 = from; p0 < to; p0 += kPfRows) {
     const int R = std::min(kPfRows, to - p0);
     launch_pf_embed(static_cast<const uint16_t*>(m->tok_emb), tokens, p0, c->tok_stride, g.vocab, R, d, c->pf_x, st);
+    PF_SYNC();
     launch_pf_rope_table(p0, R, m->hd, g.rope_theta, c->pf_cs, st);
+    PF_SYNC();
     for (int l = 0; l < g.n_layers; ++l) {
       const Layer& ly = m->layers[l];
       char* Kl = m->Kc + (size_t)slot * slot_bytes + l * m->kv_layer_bytes;
       char* Vl = m->Vc + (size_t)slot * slot_bytes + l * m->kv_layer_bytes;
       launch_pf_norm_split(c->pf_x, ly.attn_norm, g.rms_eps, R, d, c->pf_frag, st);
+      PF_SYNC();
       launch_gemm_block(ly.wqkv, 3 * d, d, c->pf_frag, R, c->pf_y, 3 * d, kPermQKV, d, m->hd, 0, st);
+      PF_SYNC();
       launch_pf_rope_kv(c->pf_y, R, d, H, p0, c->pf_cs, c->pf_q, reinterpret_cast<_Float16*>(Kl), reinterpret_cast<_Float16*>(Vl),
                         m->cap, st);
+      PF_SYNC();
       launch_attention_flash(c->pf_q, Kl, Vl, m->cap, d, H, R, p0, c->pf_attn, st);
+      PF_SYNC();
       launch_pf_norm_split(c->pf_attn, nullptr, 0.f, R, d, c->pf_frag, st);
+      PF_SYNC();
       launch_gemm_block(ly.wo, d, d, c->pf_frag, R, c->pf_x, d, kPermNone, 0, 0, 1, st);
+      PF_SYNC();
       launch_pf_norm_split(c->pf_x, ly.ffn_norm, g.rms_eps, R, d, c->pf_frag, st);
+      PF_SYNC();
       launch_gemm_block(ly.wgu, 2 * f, d, c->pf_frag, R, c->pf_y, 2 * f, kPermGateUp, f, 0, 0, st);
+      PF_SYNC();
       launch_pf_swiglu_split(c->pf_y, R, f, c->pf_frag, st);
+      PF_SYNC();
       launch_gemm_block(ly.wdown, d, f, c->pf_frag, R, c->pf_x, d, kPermNone, 0, 0, 1, st);
+      PF_SYNC();
     }
     HIPCHK(c, hipGetLastError());
   }
+#undef PF_SYNC
   return STAIRS_OK;
 }
 
@@ -795,8 +813,9 @@ constexpr int kBlockPrefillMin = 64;   // fewer rows than this go through the de
 
 // ingest positions [from, to) of sequence slot `slot` into a model's cache, no logits
 int ingest(stairs_ctx* c, Model* m, int from, int to, int slot = 0) {
-  // (a counter-collecting profiler needs a wait after every launch: then the decode kernels ingest the prompt)
-  if (c->block_prefill && !c->sync_launches && m->bf16 && !m->encdec && to - from >= kBlockPrefillMin) {
+  // (STAIRS_SYNC_LAUNCHES=1, a wait after every launch for a counter-collecting profiler: the decode kernels
+  // ingest the prompt; =2 keeps the block kernels)
+  if (c->block_prefill && (!c->sync_launches || c->sync_blocks) && m->bf16 && !m->encdec && to - from >= kBlockPrefillMin) {
     int rc = ingest_blocks(c, m, from, to, slot);
     if (rc) return rc;
   } else {
@@ -1055,7 +1074,8 @@ static stairs_ctx* new_ctx(void* hip_stream, int k_max, bool have_draft, bool bl
   c->k_max = k_max;
   c->have_draft = have_draft;
   const char* e = getenv("STAIRS_SYNC_LAUNCHES");
-  c->sync_launches = e && e[0] == '1';
+  c->sync_launches = e && (e[0] == '1' || e[0] == '2');
+  c->sync_blocks = e && e[0] == '2';
   e = getenv("STAIRS_NO_GRAPH");
   c->use_graphs = !(e && e[0] == '1') && !c->sync_launches;
   e = getenv("STAIRS_NO_BLOCK_PREFILL");
