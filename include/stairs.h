@@ -76,7 +76,7 @@ typedef struct {
 
 typedef struct {
   int32_t iterations;           /* target iterations (stair batches) run                   */
-  int32_t tokens;               /* tokens produced (= G for stairs_generate)               */
+  int32_t tokens;               /* tokens produced (= G unless an end token stopped it)    */
   int64_t accepted;             /* assistant tokens kept, summed over iterations           */
   float ms_prefill;             /* prompt ingestion, both models                           */
   float ms_decode;              /* everything after prefill until the last token           */
@@ -140,6 +140,15 @@ int stairs_verify_tokens(stairs_ctx *ctx, const int32_t *draft, int32_t k, int32
  * Requires P + G + k + 1 <= max_seq.  k = 0 is plain greedy generation of the target. */
 int stairs_generate(stairs_ctx *ctx, const int32_t *prompt, int32_t P, int32_t G, int32_t k,
                     int32_t *tokens_out, stairs_stats *stats);
+
+/* End token of the generation loops (Sec. 3.2, last sentence: the cycle runs until the answer is complete; for a
+ * real checkpoint that is the main model emitting its end-of-sequence token).  With 0 <= eos_id < vocab every
+ * generation call (stairs_generate, stairs_decode, stairs_decode_adaptive, the sampled and encoder-decoder
+ * variants, and per sequence stairs_generate_batch) stops after the first emitted token equal to eos_id: the
+ * sequence keeps that token and nothing after it, stats->tokens counts what was produced (<= G, summed over the
+ * sequences of a batch), and the entries of tokens_out after the end token are filled with eos_id.  eos_id = -1
+ * (the default) turns this off: exactly G tokens.  Errors: EINVAL (eos_id outside [-1, vocab)). */
+int stairs_set_eos(stairs_ctx *ctx, int32_t eos_id);
 
 /* The loop of stairs_generate without the prefill: continue the current sequence (after
  * stairs_prefill, or after an earlier stairs_decode) by exactly G tokens.  stats->ms_prefill

@@ -216,11 +216,25 @@ def greedy_token(logits_row: np.ndarray) -> int:
 # ----------------------------------------------------------------------------------------
 # the definition: stand-alone greedy generation of the main model (Sec. 3.1)
 # ----------------------------------------------------------------------------------------
-def greedy_bruteforce(model: OracleModel, prompt: Sequence[int], G: int) -> List[int]:
+def greedy_bruteforce(model: OracleModel, prompt: Sequence[int], G: int, eos: Optional[int] = None) -> List[int]:
+    """eos: the main model's end token; the answer is complete once it has been emitted (Sec. 3.2, last sentence:
+    the cycle runs until the prompt is fully answered; reading: for a model with an end token that is the moment it
+    is predicted), at the latest after G tokens."""
     seq = [int(t) for t in prompt]
     for _ in range(G):
         seq.append(greedy_token(forward_full(model, seq)[-1]))
+        if eos is not None and seq[-1] == eos:
+            break
     return seq[len(prompt):]
+
+
+def cut_after_end_token(new_tokens: Sequence[int], eos: Optional[int]) -> Tuple[List[int], bool]:
+    """What an iteration may append when the answer ends at the first end token: the tokens up to and including it
+    (the walk of Sec. 3.3 returned more, but nothing follows the end of the answer), and whether it was there."""
+    out = [int(x) for x in new_tokens]
+    if eos is not None and eos in out:
+        return out[:out.index(eos) + 1], True
+    return out, False
 
 
 # ----------------------------------------------------------------------------------------
@@ -263,7 +277,7 @@ class Iteration:
 
 @dataclass
 class Generation:
-    tokens: List[int]                                  # exactly G generated tokens
+    tokens: List[int]                                  # the generated tokens: G, fewer when an end token closed the answer
     iterations: List[Iteration] = field(default_factory=list)
 
     def mean_tokens_per_iteration(self) -> float:
@@ -271,11 +285,12 @@ class Generation:
 
 
 def stairs_literal(target: OracleModel, draft: OracleModel, prompt: Sequence[int], G: int, k: int,
-                   keep_logits: bool = False) -> Generation:
+                   keep_logits: bool = False, eos: Optional[int] = None) -> Generation:
     seq = [int(t) for t in prompt]
     P = len(seq)
     gen = Generation(tokens=[])
-    while len(seq) - P < G:
+    ended = False
+    while len(seq) - P < G and not ended:
         # assistant model generates k tokens in advance, greedily
         ext = list(seq)
         for _ in range(k):
@@ -291,7 +306,8 @@ def stairs_literal(target: OracleModel, draft: OracleModel, prompt: Sequence[int
         n = len(truth) - len(seq) - 1
         gen.iterations.append(Iteration(len(seq), d, t, n,
                                         np.stack(row_logits) if keep_logits else None))
-        seq = truth
+        new, ended = cut_after_end_token(truth[len(seq):], eos)
+        seq = seq + new
     gen.tokens = seq[P:P + G]
     return gen
 
@@ -367,13 +383,17 @@ class CachedStairs:
         if self.dc is not None:
             self.dc.length = min(self.dc.length, L + n)
 
-    def run(self, G: int, k: int, keep_logits: bool = False) -> Generation:
+    def run(self, G: int, k: int, keep_logits: bool = False, eos: Optional[int] = None) -> Generation:
         gen = Generation(tokens=[])
-        while len(self.seq) - self.P < G:
+        ended = False
+        while len(self.seq) - self.P < G and not ended:
             it = self.verify(self.propose(k))
             if not keep_logits:
                 it.logits = None
             gen.iterations.append(it)
+            new, ended = cut_after_end_token(self.seq[it.L:], eos)
+            if ended:
+                self.adopt(it.L, new)
         gen.tokens = self.seq[self.P:self.P + G]
         return gen
 
@@ -401,17 +421,17 @@ def stairs_adaptive(target: OracleModel, draft: OracleModel, prompt: Sequence[in
 
 
 def stairs_cached(target: OracleModel, draft: Optional[OracleModel], prompt: Sequence[int], G: int,
-                  k: int, keep_logits: bool = False, kv_round=None) -> Generation:
+                  k: int, keep_logits: bool = False, kv_round=None, eos: Optional[int] = None) -> Generation:
     st = CachedStairs(target, draft, prompt, len(prompt) + G + k + 2, kv_round)
-    return st.run(G, k, keep_logits)
+    return st.run(G, k, keep_logits, eos)
 
 
 def stairs_batch(target: OracleModel, draft: Optional[OracleModel], prompts: Sequence[Sequence[int]], G: int,
-                 k: int) -> list:
+                 k: int, eos: Optional[int] = None) -> list:
     """Several prompts at once.  Sec. 3.3 treats one sentence; sequences do not interact (Sec. 3.1: the model maps
     one token sequence to one distribution), so the result for a set of prompts is the result of the method for each
     of them on its own: a list with one Generation per prompt."""
-    return [stairs_cached(target, draft, p, G, k) for p in prompts]
+    return [stairs_cached(target, draft, p, G, k, eos=eos) for p in prompts]
 
 
 def top2_margin(logits_row: np.ndarray) -> float:

@@ -18,7 +18,7 @@ DTYPE_FP32, DTYPE_BF16 = 0, 1
 EXPORTED_SYMBOLS = [
     "stairs_strerror", "stairs_last_error", "stairs_init", "stairs_free", "stairs_prefill",
     "draft_propose", "stairs_verify", "stairs_verify_tokens", "stairs_generate", "stairs_decode", "stairs_decode_adaptive", "stairs_reserve_batch", "stairs_generate_batch",
-    "stairs_get_tokens", "stairs_gemm_host", "stairs_gemm_device", "stairs_time_kernel", "stairs_copy_probe",
+    "stairs_get_tokens", "stairs_set_eos", "stairs_gemm_host", "stairs_gemm_device", "stairs_time_kernel", "stairs_copy_probe",
     "stairs_encdec_init", "stairs_encode", "stairs_encdec_generate",
     "stairs_decode_sampled", "stairs_generate_sampled", "draft_propose_sampled", "stairs_verify_sampled",
     "stairs_rel_bucket",
@@ -115,6 +115,7 @@ def lib() -> C.CDLL:
     L.stairs_generate.argtypes = [vp, i32p, i32, i32, i32, i32p, C.POINTER(StairsStats)]
     L.stairs_decode.argtypes = [vp, i32, i32, i32p, C.POINTER(StairsStats)]
     L.stairs_decode_adaptive.argtypes = [vp, i32, i32, i32p, C.POINTER(StairsStats)]
+    L.stairs_set_eos.argtypes = [vp, i32]
     L.stairs_reserve_batch.argtypes = [vp, i32]
     L.stairs_generate_batch.argtypes = [vp, C.POINTER(i32p), i32p, i32, i32, i32, i32p, C.POINTER(StairsStats)]
     L.stairs_get_tokens.argtypes = [vp, i32p, i32, i32p]
@@ -264,6 +265,10 @@ def stairs_decode_adaptive(ctx, G: int, k_first: int):
     st = StairsStats()
     _check(lib().stairs_decode_adaptive(ctx, G, k_first, _ptr(out, C.c_int32), C.byref(st)), "stairs_decode_adaptive", ctx)
     return out[:G], st
+
+
+def stairs_set_eos(ctx, eos_id: int):
+    _check(lib().stairs_set_eos(ctx, eos_id), "stairs_set_eos", ctx)
 
 
 def stairs_reserve_batch(ctx, max_batch: int):
@@ -474,6 +479,9 @@ class Stairs:
 
     def decode_adaptive(self, G, k_first):
         return stairs_decode_adaptive(self.ctx, G, k_first)
+
+    def set_eos(self, eos_id):
+        stairs_set_eos(self.ctx, eos_id)
 
     def reserve_batch(self, max_batch):
         stairs_reserve_batch(self.ctx, max_batch)

@@ -111,6 +111,7 @@ struct stairs_ctx {
   int* counters = nullptr;     // [kCounters] split-K / attention hand-off tickets, zero between launches
   int* tgt_tok = nullptr;      // [kMaxRows]
   int* state = nullptr;        // per slot kSlotState ints: [0] = L, [1] = n of last iteration, [2] = constant 0, [3] = active
+  int eos_id = -1;             // end token of the generation loops (stairs_set_eos); -1: none
   int* h_pinned = nullptr;     // pinned host: [0..1] state, [2..2+kMaxRows) target tokens; batch: [n_slots][kSlotState] state
   int h_pinned_ints = 0;
   // host mirror
@@ -1172,7 +1173,7 @@ static int alloc_workspaces(stairs_ctx* c, const WsDims& w) {
   if (hipMemsetAsync(c->tokens, 0, ((size_t)c->tok_cap + kMaxRows) * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
   if (hipMemsetAsync(c->state, 0, 2 * kSlotState * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
   if (hipMemsetAsync(c->counters, 0, kCounters * sizeof(int), c->st) != hipSuccess) return bail(STAIRS_EHIP);
-  c->h_pinned_ints = 2 + kMaxRows;
+  c->h_pinned_ints = 2 * kSlotState + kMaxRows;     // single sequence: 2 + rows; a batch of one slot: state + rows
   if (hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), c->h_pinned_ints * sizeof(int), hipHostMallocDefault) != hipSuccess) {
     c->h_pinned = nullptr;
     return bail(STAIRS_ENOMEM);
@@ -1370,6 +1371,7 @@ static int decode_loop(stairs_ctx* c, int32_t G, int32_t k, bool adaptive, int32
   stairs_stats s;
   memset(&s, 0, sizeof(s));
   const int L0 = c->L;
+  int L_end = -1;                  // length of the sequence up to and including the end token, once it was emitted
   int rc;
   HIPCHK(c, hipEventRecord(c->ev[1], c->st));
   while (c->L - L0 < G) {
@@ -1404,22 +1406,41 @@ static int decode_loop(stairs_ctx* c, int32_t G, int32_t k, bool adaptive, int32
     s.accepted += n;
     s.accept_hist[n] += 1;
     if (adaptive) k = (n == k) ? std::min(k + 1, c->k_max) : std::max(1, n + 1);
+    // the end token closes the answer: what the iteration emitted after it is dropped (finish_verify left the
+    // n + 1 emitted tokens in the pinned buffer)
+    if (c->eos_id >= 0) {
+      int j = 0;
+      while (j <= n && c->h_pinned[2 + j] != c->eos_id) ++j;
+      if (j <= n) {
+        L_end = c->L - (n + 1) + j + 1;
+        break;
+      }
+    }
   }
   HIPCHK(c, hipEventRecord(c->ev[0], c->st));
   HIPCHK(c, hipEventSynchronize(c->ev[0]));
   HIPCHK(c, hipEventElapsedTime(&s.ms_decode, c->ev[1], c->ev[0]));
-  s.tokens = G;
-  // the last iteration may have produced more than asked for: the sequence is cut back to
-  // L0 + G (the caches hold a prefix of what they held, which stays valid)
-  if (c->L > L0 + G) {
-    c->L = L0 + G;
+  // the last iteration may have produced more than asked for (or tokens after the end token): the sequence is cut
+  // back (the caches hold a prefix of what they held, which stays valid)
+  const int L_keep = std::min(L0 + G, L_end >= 0 ? L_end : c->L);
+  s.tokens = L_keep - L0;
+  if (c->L > L_keep) {
+    c->L = L_keep;
     c->T.valid = std::min(c->T.valid, c->L - 1);
     if (c->have_draft) c->D.valid = std::min(c->D.valid, c->L - 1);
     HIPCHK(c, hipMemcpyAsync(c->state, &c->L, sizeof(int), hipMemcpyHostToDevice, c->st));
     HIPCHK(c, hipStreamSynchronize(c->st));
   }
-  if (G > 0 && (rc = copy_out(c, tokens_out, c->tokens + L0, (size_t)G * sizeof(int)))) return rc;
+  if (s.tokens > 0 && (rc = copy_out(c, tokens_out, c->tokens + L0, (size_t)s.tokens * sizeof(int)))) return rc;
+  for (int i = s.tokens; i < G; ++i) tokens_out[i] = c->eos_id;
   if (stats) *stats = s;
+  return STAIRS_OK;
+}
+
+int stairs_set_eos(stairs_ctx* c, int32_t eos_id) {
+  if (!c) return STAIRS_EINVAL;
+  if (eos_id < -1 || eos_id >= c->T.cfg.vocab) return fail(c, STAIRS_EINVAL, "end token outside [-1, vocab)");
+  c->eos_id = eos_id;
   return STAIRS_OK;
 }
 
@@ -1599,7 +1620,7 @@ int stairs_reserve_batch(stairs_ctx* c, int32_t max_batch) {
   c->tokens = tok;
   c->state = state;
   int* hp = nullptr;
-  const int ints = std::max(2 + kMaxRows, max_batch * kSlotState);
+  const int ints = std::max(2 + kMaxRows, max_batch * kSlotState + c->rows_cap);
   if (hipHostMalloc(reinterpret_cast<void**>(&hp), ints * sizeof(int), hipHostMallocDefault) != hipSuccess) {
     (void)hipGetLastError();
     return fail(c, STAIRS_ENOMEM, "hipHostMalloc failed");
@@ -1640,7 +1661,7 @@ int stairs_generate_batch(stairs_ctx* c, const int32_t* const* prompts, const in
   HIPCHK(c, hipMemsetAsync(c->counters, 0, kCounters * sizeof(int), c->st));
   HIPCHK(c, hipEventRecord(c->ev[0], c->st));
   std::vector<int> L(B), L0(B), hstate((size_t)B * kSlotState);
-  std::vector<char> active(B, 1);
+  std::vector<char> active(B, 1), ended(B, 0);
   for (int b = 0; b < B; ++b) {
     HIPCHK(c, hipMemcpyAsync(c->tokens + (size_t)b * c->tok_stride, prompts[b], (size_t)P[b] * sizeof(int), hipMemcpyHostToDevice, c->st));
     L[b] = L0[b] = P[b];
@@ -1681,6 +1702,9 @@ int stairs_generate_batch(stairs_ctx* c, const int32_t* const* prompts, const in
     }
     HIPCHK(c, hipEventRecord(c->ev[7], c->st));
     HIPCHK(c, hipMemcpyAsync(c->h_pinned, c->state, (size_t)B * kSlotState * sizeof(int), hipMemcpyDeviceToHost, c->st));
+    int* emitted = c->h_pinned + (size_t)B * kSlotState;       // [B][k + 1] target tokens (with an end token only)
+    if (c->eos_id >= 0)
+      HIPCHK(c, hipMemcpyAsync(emitted, c->tgt_tok, (size_t)B * (k + 1) * sizeof(int), hipMemcpyDeviceToHost, c->st));
     HIPCHK(c, hipStreamSynchronize(c->st));
     bool any_done = false;
     for (int b = 0; b < B; ++b) {
@@ -1690,7 +1714,15 @@ int stairs_generate_batch(stairs_ctx* c, const int32_t* const* prompts, const in
       L[b] += n + 1;
       s.accepted += n;
       s.accept_hist[n] += 1;
-      if (L[b] - L0[b] >= G) {
+      if (c->eos_id >= 0) {                             // the end token closes this sequence's answer
+        int j = 0;
+        while (j <= n && emitted[b * (k + 1) + j] != c->eos_id) ++j;
+        if (j <= n) {
+          L[b] += j - n;
+          ended[b] = 1;
+        }
+      }
+      if (ended[b] || L[b] - L0[b] >= G) {
         active[b] = 0;
         --n_active;
         any_done = true;
@@ -1718,10 +1750,14 @@ int stairs_generate_batch(stairs_ctx* c, const int32_t* const* prompts, const in
   HIPCHK(c, hipEventSynchronize(c->ev[2]));
   HIPCHK(c, hipEventElapsedTime(&s.ms_prefill, c->ev[0], c->ev[1]));
   HIPCHK(c, hipEventElapsedTime(&s.ms_decode, c->ev[1], c->ev[2]));
-  s.tokens = B * G;
-  for (int b = 0; b < B && G > 0; ++b)
-    HIPCHK(c, hipMemcpyAsync(tokens_out + (size_t)b * G, c->tokens + (size_t)b * c->tok_stride + L0[b], (size_t)G * sizeof(int),
+  s.tokens = 0;
+  for (int b = 0; b < B && G > 0; ++b) {
+    const int got = std::min(G, L[b] - L0[b]);
+    s.tokens += got;
+    HIPCHK(c, hipMemcpyAsync(tokens_out + (size_t)b * G, c->tokens + (size_t)b * c->tok_stride + L0[b], (size_t)got * sizeof(int),
                              hipMemcpyDeviceToHost, c->st));
+    for (int i = got; i < G; ++i) tokens_out[(size_t)b * G + i] = c->eos_id;
+  }
   HIPCHK(c, hipStreamSynchronize(c->st));
   if (stats) *stats = s;
   return STAIRS_OK;

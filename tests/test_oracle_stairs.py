@@ -244,3 +244,85 @@ def test_adopting_another_path_keeps_the_caches_consistent():
         it2 = st.verify(d2)
         assert np.allclose(it2.logits, full[len(seq) - 1:], atol=1e-10)
         seq = st.seq
+
+
+# ---- end token (Sec. 3.2, last sentence: the cycle runs until the answer is complete) -------------------------
+def test_cut_after_end_token_hand_cases():
+    assert so.cut_after_end_token([5, 6, 7], None) == ([5, 6, 7], False)
+    assert so.cut_after_end_token([5, 6, 7], 9) == ([5, 6, 7], False)
+    assert so.cut_after_end_token([5, 6, 7], 5) == ([5], True)
+    assert so.cut_after_end_token([5, 6, 7], 6) == ([5, 6], True)
+    assert so.cut_after_end_token([5, 6, 6], 6) == ([5, 6], True)          # the first one ends the answer
+    assert so.cut_after_end_token([7], 7) == ([7], True)
+
+
+def _first_index(tokens, tok):
+    return list(tokens).index(tok)
+
+
+@pytest.mark.parametrize("seed,deep_scale", [(7, 0.05), (8, 1.0)])
+def test_greedy_with_an_end_token_is_the_plain_output_cut_after_it(seed, deep_scale):
+    t, _ = _pair(seed, deep_scale)
+    T = so.OracleModel(t, np.float64)
+    prompt = [3, 1, 4, 1, 5]
+    full = so.greedy_bruteforce(T, prompt, 16)
+    for j in (0, 5, 15):
+        eos = full[j]
+        cut = _first_index(full, eos) + 1                                  # the token may occur earlier than j
+        assert so.greedy_bruteforce(T, prompt, 16, eos=eos) == full[:cut]
+    absent = next(v for v in range(50) if v not in full)
+    assert so.greedy_bruteforce(T, prompt, 16, eos=absent) == full
+
+
+@pytest.mark.parametrize("k", [0, 1, 3, 6])
+@pytest.mark.parametrize("seed,deep_scale", [(7, 0.05), (7, 0.5), (9, 1.0)])
+def test_stairs_with_an_end_token_equals_greedy_with_it(seed, deep_scale, k):
+    """Literal and cached loops stop where stand-alone greedy decoding stops, wherever the end token falls inside an
+    iteration (first emitted token, an accepted assistant token, the last prediction) and when G comes first."""
+    t, d = _pair(seed, deep_scale)
+    T, D = so.OracleModel(t, np.float64), so.OracleModel(d, np.float64)
+    prompt = [2, 7, 1, 8]
+    G = 13
+    full = so.greedy_bruteforce(T, prompt, G)
+    for j in range(0, G, 2):
+        eos = full[j]
+        want = so.greedy_bruteforce(T, prompt, G, eos=eos)
+        assert want[-1] == eos and eos not in want[:-1]
+        lit = so.stairs_literal(T, D, prompt, G, k, eos=eos)
+        assert lit.tokens == want
+        st_ = so.CachedStairs(T, D if k else None, prompt, len(prompt) + G + k + 2)
+        gen = st_.run(G, k, eos=eos)
+        assert gen.tokens == want
+        assert st_.seq == prompt + want                                    # nothing after the end token is kept
+        assert st_.tc.length <= len(st_.seq) - 1                           # and the cache holds no row of it
+        assert len(gen.iterations) == len(lit.iterations)
+    # an end token that comes after G: the length limit wins
+    late = so.greedy_bruteforce(T, prompt, G + 6)
+    cand = [x for x in late[G:] if x not in late[:G]]
+    if cand:
+        assert so.stairs_cached(T, D if k else None, prompt, G, k, eos=cand[0]).tokens == full
+
+
+def test_continuing_after_an_end_token_continues_the_plain_sequence():
+    """The stop only cuts; the state left behind is the sequence up to the end token, from which the loop goes on as
+    plain greedy decoding would (the check the GPU library's rollback is held to)."""
+    t, d = _pair(7, 0.5)
+    T, D = so.OracleModel(t, np.float64), so.OracleModel(d, np.float64)
+    prompt = [3, 1, 4, 1, 5]
+    full = so.greedy_bruteforce(T, prompt, 20)
+    eos = full[6]
+    cut = _first_index(full, eos) + 1
+    st_ = so.CachedStairs(T, D, prompt, 64)
+    assert st_.run(20, 4, eos=eos).tokens == full[:cut]
+    st_.P = len(st_.seq)
+    assert st_.run(20 - cut, 4).tokens == full[cut:]
+
+
+def test_batch_with_an_end_token_is_each_prompt_on_its_own():
+    t, d = _pair(8, 0.5)
+    T, D = so.OracleModel(t, np.float64), so.OracleModel(d, np.float64)
+    prompts = [[3, 1, 4], [1, 5, 9, 2], [6, 5]]
+    eos = so.greedy_bruteforce(T, prompts[0], 10)[4]
+    gens = so.stairs_batch(T, D, prompts, 10, 2, eos=eos)
+    for p, g in zip(prompts, gens):
+        assert g.tokens == so.greedy_bruteforce(T, p, 10, eos=eos)
