@@ -1283,9 +1283,9 @@ int stairs_prefill(stairs_ctx* c, const int32_t* prompt, int32_t P) {
   if (!c) return STAIRS_EINVAL;
   if (c->encdec) return fail(c, STAIRS_EINVAL, "encoder-decoder context: stairs_encode starts a sequence");
   if (!prompt || P < 1) return fail(c, STAIRS_EINVAL, "prompt is NULL or empty");
+  if (!capacity_ok(c, P + c->k_max + 1)) return fail(c, STAIRS_ECAPACITY, "prompt + k_max + 1 exceeds max_seq");
   for (int i = 0; i < P; ++i)
     if (prompt[i] < 0 || prompt[i] >= c->T.cfg.vocab) return fail(c, STAIRS_EINVAL, "prompt token outside the vocabulary");
-  if (!capacity_ok(c, P + c->k_max + 1)) return fail(c, STAIRS_ECAPACITY, "prompt + k_max + 1 exceeds max_seq");
   c->prefilled = false;
   c->pending_k = -1;
   HIPCHK(c, hipMemsetAsync(c->counters, 0, kCounters * sizeof(int), c->st));
@@ -1648,10 +1648,10 @@ int stairs_generate_batch(stairs_ctx* c, const int32_t* const* prompts, const in
   if (!prompts || !P) return fail(c, STAIRS_EINVAL, "prompts or P is NULL");
   for (int b = 0; b < B; ++b) {
     if (!prompts[b] || P[b] < 1) return fail(c, STAIRS_EINVAL, "a prompt is NULL or empty");
-    for (int i = 0; i < P[b]; ++i)
-      if (prompts[b][i] < 0 || prompts[b][i] >= c->T.cfg.vocab) return fail(c, STAIRS_EINVAL, "prompt token outside the vocabulary");
     // a slot that has its G tokens stops, so it never goes past P + G + k
     if (!capacity_ok(c, P[b] + G + k + 1)) return fail(c, STAIRS_ECAPACITY, "P + G + k + 1 exceeds max_seq");
+    for (int i = 0; i < P[b]; ++i)
+      if (prompts[b][i] < 0 || prompts[b][i] >= c->T.cfg.vocab) return fail(c, STAIRS_EINVAL, "prompt token outside the vocabulary");
   }
   stairs_stats s;
   memset(&s, 0, sizeof(s));
