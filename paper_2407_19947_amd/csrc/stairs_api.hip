@@ -605,7 +605,10 @@ int chunks_for(int kv_len) { return (std::max(kv_len, 1) + kAttnChunk - 1) / kAt
 
 // The feed-forward block of an encoder-decoder layer on M rows of x (ssq = their sum-of-squares partials):
 // x += W_out relu(W_in norm(x)); h = workspace [M, f].
-void launch_ed_ffn(stairs_ctx* c, const Model* m, const EdLayer& ly, float* x, float* ssq, int M) {
+// frags: x comes with its activation fragments in c->xf (gain of ffn_norm folded in), the hidden activations leave
+// theirs in c->hf and the result its own in c->xf with next_gain folded in (forwards of more than 4 rows)
+void launch_ed_ffn(stairs_ctx* c, const Model* m, const EdLayer& ly, float* x, float* ssq, int M, bool frags = false,
+                   const float* next_gain = nullptr) {
   const int d = m->cfg.d_model, f = m->cfg.d_ffn, sn = ssq_groups(d, 1);
   const RowNorm none{nullptr, nullptr, 0, 0.f};
   GemmEpi e{};
@@ -614,12 +617,15 @@ void launch_ed_ffn(stairs_ctx* c, const Model* m, const EdLayer& ly, float* x, f
   e.hd = m->hd;
   e.out = c->h;
   e.act = kActRelu;
+  e.frag_out = frags ? c->hf : nullptr;
   RowNorm fn{ly.ffn_norm, ssq, sn, m->cfg.rms_eps};
-  launch_gemm(kRoleHead, 1, ly.w_in, f, d, x, d, M, fn, c->partial, e, c->st);
+  launch_gemm(kRoleHead, 1, ly.w_in, f, d, x, d, M, fn, c->partial, e, c->st, frags ? c->xf : nullptr);
   e.act = kActNone;
   e.out = x;
   e.ssq_out = ssq;
-  launch_gemm(kRoleDown, 1, ly.w_out, d, f, c->h, f, M, none, c->partial, e, c->st);
+  e.frag_out = frags ? c->xf : nullptr;
+  e.frag_gain = next_gain;
+  launch_gemm(kRoleDown, 1, ly.w_out, d, f, c->h, f, M, none, c->partial, e, c->st, frags ? c->hf : nullptr);
 }
 
 // Decoder forward of an encoder-decoder model: M rows of the decoder sequence at pos.. (see forward()).  Per layer:
@@ -637,11 +643,17 @@ int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logit
   do {                                                          \
     if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));  \
   } while (0)
-  launch_embed(m->tok_emb, 1, c->tokens, 0, c->tok_stride, V, pos, M, d, c->x, c->ssq, m->hd, 0.f, c->rope_cs, st);
+  // more than 4 rows: every producer of an activation also leaves its MFMA operand fragments (gain of the norm in
+  // front of the next projection folded in) and the projections take the hand-off-free kernel, as in forward()
+  const bool fr = M > 4;
+  uint4* const xf = fr ? c->xf : nullptr;
+  uint4* const af = fr ? c->af : nullptr;
+  launch_embed(m->tok_emb, 1, c->tokens, 0, c->tok_stride, V, pos, M, d, c->x, c->ssq, m->hd, 0.f, c->rope_cs, st, xf,
+               m->dec[0].attn_norm);
   SYNCPOINT();
   const RowNorm none{nullptr, nullptr, 0, 0.f};
-  const AttnMode self_mode{1.f, m->dec_bias, m->cap, m->cap - 1, 0};
-  const AttnMode cross_mode{1.f, nullptr, 0, 0, c->S};
+  const AttnMode self_mode{1.f, m->dec_bias, m->cap, m->cap - 1, 0, af};
+  const AttnMode cross_mode{1.f, nullptr, 0, 0, c->S, af};
   auto normed = [&](const float* gain) {
     RowNorm n{gain, c->ssq, sn, g.rms_eps};
     return n;
@@ -662,24 +674,30 @@ int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logit
     e.hd = m->hd;
     e.ssq_out = c->ssq;
     e.out = c->q_rot;
-    launch_gemm(kRoleQKV, 1, ly.wqkv, 3 * a, d, c->x, d, M, normed(ly.attn_norm), c->partial, e, st);
+    launch_gemm(kRoleQKV, 1, ly.wqkv, 3 * a, d, c->x, d, M, normed(ly.attn_norm), c->partial, e, st, xf);
     SYNCPOINT();
     launch_attention(c->q_rot, Kl, Vl, 1, m->cap, a, H, M, pos, 1, 0, nchunk, c->nchunk_cap, c->part_o, c->part_ml,
                      c->counters + kGemmCounters, c->attn_out, st, self_mode);
     SYNCPOINT();
     e.out = c->x;
-    launch_gemm(kRoleWo, 1, ly.wo, d, a, c->attn_out, a, M, none, c->partial, e, st);
+    e.frag_out = xf;                               // x after self-attention, for the cross-attention queries
+    e.frag_gain = ly.cross_norm;
+    launch_gemm(kRoleWo, 1, ly.wo, d, a, c->attn_out, a, M, none, c->partial, e, st, af);
     SYNCPOINT();
     e.out = c->q_rot;
-    launch_gemm(kRoleHead, 1, ly.cq, a, d, c->x, d, M, normed(ly.cross_norm), c->partial, e, st);
+    e.frag_out = nullptr;
+    e.frag_gain = nullptr;
+    launch_gemm(kRoleHead, 1, ly.cq, a, d, c->x, d, M, normed(ly.cross_norm), c->partial, e, st, xf);
     SYNCPOINT();
     launch_attention(c->q_rot, m->Kx + l * m->kvx_layer_bytes, m->Vx + l * m->kvx_layer_bytes, 1, m->cap_src, a, H, M, pos, 1, 0,
                      nch_src, c->nchunk_cap, c->part_o, c->part_ml, c->counters + kGemmCounters, c->attn_out, st, cross_mode);
     SYNCPOINT();
     e.out = c->x;
-    launch_gemm(kRoleWo, 1, ly.co, d, a, c->attn_out, a, M, none, c->partial, e, st);
+    e.frag_out = xf;                               // x after cross-attention, for the feed-forward block
+    e.frag_gain = ly.ffn_norm;
+    launch_gemm(kRoleWo, 1, ly.co, d, a, c->attn_out, a, M, none, c->partial, e, st, af);
     SYNCPOINT();
-    launch_ed_ffn(c, m, ly, c->x, c->ssq, M);
+    launch_ed_ffn(c, m, ly, c->x, c->ssq, M, fr, l + 1 < g.n_layers ? m->dec[l + 1].attn_norm : m->final_norm);
     SYNCPOINT();
   }
   if (logits_rows > 0) {
@@ -690,7 +708,7 @@ int forward_ed(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logit
     e.out = logits_dst ? logits_dst : c->logits;
     e.hd = m->hd;
     launch_gemm(kRoleHead, 1, m->lm_head, V, d, c->x + (size_t)r0 * d, d, logits_rows,
-                RowNorm{m->final_norm, c->ssq + r0 * sn, sn, g.rms_eps}, c->partial, e, st);
+                RowNorm{m->final_norm, c->ssq + r0 * sn, sn, g.rms_eps}, c->partial, e, st, r0 == 0 ? xf : nullptr);
     SYNCPOINT();
   }
   HIPCHK(c, hipGetLastError());

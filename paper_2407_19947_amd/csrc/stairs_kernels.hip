@@ -324,6 +324,7 @@ __device__ __forceinline__ void gemm_epilogue(const float* partial, int S, int M
         if (rs) { const float r = rs[m]; a.x *= r; a.y *= r; a.z *= r; a.w *= r; }
         if (epi.act == kActRelu) a = make_float4(fmaxf(a.x, 0.f), fmaxf(a.y, 0.f), fmaxf(a.z, 0.f), fmaxf(a.w, 0.f));
         *reinterpret_cast<float4*>(epi.out + (size_t)m * N + col) = a;
+        if (epi.frag_out) store_frag4(epi.frag_out, m, col, a, epi.frag_gain);
       }
     }
   } else if (ROLE == kRoleWo || ROLE == kRoleDown) {
@@ -913,6 +914,7 @@ __device__ __forceinline__ void gemm_epilogue_lds(const float* csum, int nchunks
         if (rs) { const float r = rs[m]; a.x *= r; a.y *= r; a.z *= r; a.w *= r; }
         if (epi.act == kActRelu) a = make_float4(fmaxf(a.x, 0.f), fmaxf(a.y, 0.f), fmaxf(a.z, 0.f), fmaxf(a.w, 0.f));
         *reinterpret_cast<float4*>(epi.out + (size_t)m * N + col) = a;
+        if (epi.frag_out) store_frag4(epi.frag_out, m, col, a, epi.frag_gain);
       }
     }
   } else if (ROLE == kRoleWo || ROLE == kRoleDown) {
@@ -1139,11 +1141,19 @@ static WideCfg wide_cfg(int role, int M, int NTILES, int K) {
     return v;
   }();
   const int nchunks = gemm_slices(K, 1);
+  // Measured on the 125M, 1B and 7B workloads (5..32 rows): as many tiles per wave (8, 4, 2, 1) as still leave about
+  // 170 work-groups; with one tile per wave up to 8 waves share the k chunks, else 4.  Few tiles with a long k range
+  // (down projections: 128 x 8192 at 1B, 256 x 11008 at 7B) stream better through the split-K kernel, whose grid also
+  // cuts k; from 17 rows on the 7B shape is the exception.  Small matrices are latency-bound either way and the
+  // missing hand-off is what counts (125M at 16 rows: 595 -> 470 us per forward).
   WideCfg c{0, 0};
-  if (NTILES >= 1024) c = {8, std::min(4, nchunks)};
-  else if (NTILES >= 512) c = {4, std::min(4, nchunks)};
-  else if (NTILES >= 192 && nchunks <= 8) c = {1, std::min(8, nchunks)};
-  else if (NTILES >= 192 && M > 16) c = {1, 4};          // long k: only with two column tiles does it beat split-K
+  if (nchunks > 8 && NTILES < 512) {
+    if (NTILES >= 192 && M > 16) c = {1, 4};
+  } else {
+    int nt = 8;
+    while (nt > 1 && NTILES / nt < 170) nt /= 2;
+    c = {nt, std::min(nt == 1 ? 8 : 4, nchunks)};
+  }
   if ((int)forced.size() == 5) {
     const WideCfg f = forced[role];
     if ((f.nt == 0 || f.nt == 1 || f.nt == 2 || f.nt == 4 || f.nt == 8) && f.nw >= 1 && f.nw <= 8) c = f;
