@@ -298,16 +298,16 @@ def main():
         eng.reserve_batch(n_seq)
         batched = {}
         flop_per_row = 2.0 * 2.0 * target.n_params()          # high and low part of every activation
-        for B, kk in ((2, k), (4, k), (8, k), (8, 3), (16, k), (32, k), (64, k)):
+        for B, kk in ((2, k), (4, k), (8, k), (8, 3), (16, k), (16, 3), (32, k), (64, k)):
             rows = B * (kk + 1)
             if rows > 256 or B > n_seq:
                 continue
             toks_b, st_b = eng.generate_batch(prompts[:B], G, kk)
-            if rows <= 32:      # the decode kernels: bit for bit the sequence alone
+            if rows <= 64:      # the weight-streaming kernels: bit for bit the sequence alone
                 assert np.array_equal(toks_b[0], toks0), "a sequence of the batch differs from the same sequence alone"
             ms_v = st_b.ms_verify / max(1, st_b.iterations)
             batched[f"B{B}_k{kk}"] = {"sequences": B, "k": kk, "rows_per_forward": rows,
-                                      "kernels": "decode (weight-streaming)" if rows <= 32 else "block (MFMA GEMM)",
+                                      "kernels": "decode (weight-streaming)" if rows <= 64 else "block (MFMA GEMM)",
                                       "tokens_per_s": B * G / (st_b.ms_decode * 1e-3), "iterations": st_b.iterations,
                                       "ms_verify_per_iteration": ms_v,
                                       "verify_weight_GBps": target.weight_bytes_streamed() / (ms_v * 1e-3) / 1e9,

@@ -44,6 +44,7 @@ extern "C" {
 
 #define STAIRS_MAX_ROWS    32    /* most rows one forward takes: k + 1 <= STAIRS_MAX_ROWS  */
 #define STAIRS_MAX_BATCH        128   /* most sequences stairs_reserve_batch makes room for          */
+#define STAIRS_MAX_STREAM_ROWS  64    /* most rows of several sequences the weight-streaming kernels take */
 #define STAIRS_MAX_BATCH_ROWS   256   /* most rows one forward of several sequences takes            */
 
 /* Shape of one decoder-only pre-RMSNorm transformer (RoPE in the rotate-half pairing
@@ -165,8 +166,9 @@ int stairs_decode_adaptive(stairs_ctx *ctx, int32_t G, int32_t k_first, int32_t 
 
 /* Several independent sequences in one context (a batch of stair batches): the k+1 stair rows of B sequences are
  * scored by ONE forward of B*(k+1) rows, so the weights are streamed once for all of them; every sequence keeps its
- * own key/value caches, length and acceptance (Sec. 3.3 applied per sequence).  Up to STAIRS_MAX_ROWS rows per forward
- * run on the kernels of the single-sequence path and each sequence's output is bit for bit what stairs_generate gives
+ * own key/value caches, length and acceptance (Sec. 3.3 applied per sequence).  Up to STAIRS_MAX_STREAM_ROWS rows per
+ * forward run on the kernels of the single-sequence path (models with d_model, d_ffn <= 16384; else STAIRS_MAX_ROWS)
+ * and each sequence's output is bit for bit what stairs_generate gives
  * for it alone; forwards of more rows (up to STAIRS_MAX_BATCH_ROWS) run on the block kernels of the prompt ingestion
  * (one order of additions per output whatever the batch, so a sequence's output does not depend on which others share
  * the forward; against the sequence alone it is the same greedy choice up to near-ties of the logits).
@@ -177,7 +179,7 @@ int stairs_reserve_batch(stairs_ctx *ctx, int32_t max_batch);
 
 /* prompts: B host pointers, prompts[b] has P[b] tokens (lengths may differ).  Generates exactly G tokens for every
  * sequence with draft length k (a sequence that has its G tokens stops taking part; the loop ends when all have):
- * tokens_out is [B][G] row-major.  Requires B <= reserved batch, max(B * (k+1), B * 2) <= STAIRS_MAX_ROWS (or, with
+ * tokens_out is [B][G] row-major.  Requires B <= reserved batch, max(B * (k+1), B * 2) <= STAIRS_MAX_STREAM_ROWS (or, with
  * more than STAIRS_MAX_ROWS / 2 sequences reserved, <= STAIRS_MAX_BATCH_ROWS), P[b] + G + k + 1 <= max_seq.  stats (optional): iterations = batched iterations, tokens = B * G,
  * accepted / accept_hist summed over sequences.  Afterwards the context holds no current sequence for the
  * single-sequence calls (stairs_prefill starts one).  Errors: EINVAL, ESTATE (k > 0 without a draft), ECAPACITY, EHIP. */

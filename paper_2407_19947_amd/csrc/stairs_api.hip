@@ -107,6 +107,7 @@ struct stairs_ctx {
   int tok_cap = 0, tok_stride = 0;
   int n_slots = 1;             // sequence slots the caches, token arrays and state hold (stairs_reserve_batch)
   int rows_cap = kMaxRows;     // rows logits, target tokens and attention partial results are sized for
+  int fwd_rows = kMaxRows;     // rows one forward of the decode kernels takes (kMaxFwdRows once several sequences are reserved)
   int pf_rows = 0;             // rows the block workspaces (pf_*) hold
   int* counters = nullptr;     // [kCounters] split-K / attention hand-off tickets, zero between launches
   int* tgt_tok = nullptr;      // [kMaxRows]
@@ -458,7 +459,7 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
     if (slot != 0 || pos.rps) return fail(c, STAIRS_EINVAL, "forward: encoder-decoder models take one sequence");
     return forward_ed(c, m, pos, nchunk, M, logits_rows, logits_dst);
   }
-  if (M > kMaxRows) {                       // many sequences at once: the block kernels
+  if (M > c->fwd_rows) {                    // many sequences at once: the block kernels
     if (slot != 0 || logits_dst) return fail(c, STAIRS_EINVAL, "forward: launch shape outside the workspaces");
     return forward_block(c, m, pos, nchunk, M, logits_rows);
   }
@@ -467,7 +468,8 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
   const int b = m->bf16 ? 1 : 0;
   const int sn = ssq_groups(d, b);
   hipStream_t st = c->st;
-  if (nchunk < 1 || nchunk > c->nchunk_cap || M < 1 || M > kMaxRows) return fail(c, STAIRS_EINVAL, "forward: launch shape outside the workspaces");
+  if (nchunk < 1 || nchunk > c->nchunk_cap || M < 1 || M > c->fwd_rows || M > c->rows_cap || (M > kMaxRows && !b))
+    return fail(c, STAIRS_EINVAL, "forward: launch shape outside the workspaces");
 #define SYNCPOINT()                                             \
   do {                                                          \
     if (c->sync_launches) HIPCHK(c, hipStreamSynchronize(st));  \
@@ -1162,15 +1164,18 @@ static int alloc_workspaces(stairs_ctx* c, const WsDims& w) {
        (rc = dev_alloc(c, &c->enc_ssq, (size_t)w.srcmax * ssq_groups(dmax, 1))) ||
        (rc = dev_alloc(c, &c->enc_q, (size_t)w.srcmax * w.amax))))
     return rc;
-  if ((rc = dev_alloc(c, &c->x, (size_t)kMaxRows * dmax)) || (rc = dev_alloc(c, &c->ssq, (size_t)kMaxRows * ssq_groups(dmax, 1))) ||
-      (rc = dev_alloc(c, &c->q_rot, (size_t)kMaxRows * wide)) || (rc = dev_alloc(c, &c->attn_out, (size_t)kMaxRows * wide)) ||
-      (rc = dev_alloc(c, &c->h, (size_t)kMaxRows * fmax)) || (rc = dev_alloc(c, &c->logits, (size_t)kMaxRows * w.vocab)) ||
+  // (activations and their fragments for kMaxFwdRows rows: a few MB; what grows with the context or the vocabulary
+  // is sized for rows_cap rows and enlarged by stairs_reserve_batch)
+  if (frag_bytes(std::max(wide, fmax)) > kFragHalfU4 * 16) return fail(c, STAIRS_EINVAL, "d_model / d_ffn too large for the activation fragment blocks");
+  if ((rc = dev_alloc(c, &c->x, (size_t)kMaxFwdRows * dmax)) || (rc = dev_alloc(c, &c->ssq, (size_t)kMaxFwdRows * ssq_groups(dmax, 1))) ||
+      (rc = dev_alloc(c, &c->q_rot, (size_t)kMaxFwdRows * wide)) || (rc = dev_alloc(c, &c->attn_out, (size_t)kMaxFwdRows * wide)) ||
+      (rc = dev_alloc(c, &c->h, (size_t)kMaxFwdRows * fmax)) || (rc = dev_alloc(c, &c->logits, (size_t)kMaxRows * w.vocab)) ||
       (rc = dev_alloc(c, &c->partial, w.partial_floats)) ||
-      (rc = dev_alloc(c, &c->xf, frag_bytes(dmax) / sizeof(uint4))) || (rc = dev_alloc(c, &c->af, frag_bytes(wide) / sizeof(uint4))) ||
-      (rc = dev_alloc(c, &c->hf, frag_bytes(fmax) / sizeof(uint4))) ||
+      (rc = dev_alloc(c, &c->xf, frag_alloc_bytes(dmax) / sizeof(uint4))) || (rc = dev_alloc(c, &c->af, frag_alloc_bytes(wide) / sizeof(uint4))) ||
+      (rc = dev_alloc(c, &c->hf, frag_alloc_bytes(fmax) / sizeof(uint4))) ||
       (rc = dev_alloc(c, &c->part_o, (size_t)kMaxRows * Hmax * c->nchunk_cap * 128)) ||
       (rc = dev_alloc(c, &c->part_ml, (size_t)kMaxRows * Hmax * c->nchunk_cap * 2)) ||
-      (rc = dev_alloc(c, &c->rope_cs, (size_t)kMaxRows * 64)) || (rc = dev_alloc(c, &c->tokens, (size_t)c->tok_cap + kMaxRows)) ||
+      (rc = dev_alloc(c, &c->rope_cs, (size_t)kMaxFwdRows * 64)) || (rc = dev_alloc(c, &c->tokens, (size_t)c->tok_cap + kMaxRows)) ||
       (rc = dev_alloc(c, &c->tgt_tok, (size_t)kMaxRows)) || (rc = dev_alloc(c, &c->counters, (size_t)kCounters)) || (rc = dev_alloc(c, &c->state, 2 * kSlotState)))
     return bail(rc);
   if (c->block_prefill) {
@@ -1608,15 +1613,21 @@ int stairs_reserve_batch(stairs_ctx* c, int32_t max_batch) {
     m->Vc = V;
     m->valid = 0;
   }
-  // forwards of more than kMaxRows rows: logits, target tokens and attention partial results for kMaxBlockRows rows
-  if (max_batch > kMaxRows / 2 && c->rows_cap < kMaxBlockRows) {
+  // several sequences: the decode kernels take forwards of up to kMaxFwdRows rows (the hand-off-free GEMM holds the
+  // chunk sums of all rows in LDS: k up to 16384), the block kernels up to kMaxBlockRows: logits, target tokens and
+  // attention partial results for that many rows
+  const int want_rows = max_batch > kMaxRows / 2 ? kMaxBlockRows : max_batch >= 2 ? kMaxFwdRows : kMaxRows;
+  if (c->rows_cap < want_rows) {
     const int Hmax = std::max(c->T.cfg.n_heads, c->have_draft ? c->D.cfg.n_heads : 0);
     float *lg = nullptr, *po = nullptr, *pm = nullptr;
     int* tt = nullptr;
-    c->pf_part_floats = (size_t)16 << 20;
-    if ((rc = dev_alloc(c, &c->pf_part, c->pf_part_floats)) || (rc = dev_alloc(c, &lg, (size_t)kMaxBlockRows * c->T.cfg.vocab)) ||
-        (rc = dev_alloc(c, &po, (size_t)kMaxBlockRows * Hmax * c->nchunk_cap * 128)) ||
-        (rc = dev_alloc(c, &pm, (size_t)kMaxBlockRows * Hmax * c->nchunk_cap * 2)) || (rc = dev_alloc(c, &tt, (size_t)kMaxBlockRows)))
+    if (want_rows == kMaxBlockRows && !c->pf_part) {
+      c->pf_part_floats = (size_t)16 << 20;
+      if ((rc = dev_alloc(c, &c->pf_part, c->pf_part_floats))) return rc;
+    }
+    if ((rc = dev_alloc(c, &lg, (size_t)want_rows * c->T.cfg.vocab)) ||
+        (rc = dev_alloc(c, &po, (size_t)want_rows * Hmax * c->nchunk_cap * 128)) ||
+        (rc = dev_alloc(c, &pm, (size_t)want_rows * Hmax * c->nchunk_cap * 2)) || (rc = dev_alloc(c, &tt, (size_t)want_rows)))
       return rc;
     release(c->logits);
     release(c->part_o);
@@ -1626,7 +1637,12 @@ int stairs_reserve_batch(stairs_ctx* c, int32_t max_batch) {
     c->part_o = po;
     c->part_ml = pm;
     c->tgt_tok = tt;
-    c->rows_cap = kMaxBlockRows;
+    c->rows_cap = want_rows;
+  }
+  if (max_batch >= 2) {
+    int kmax = std::max(c->T.cfg.d_model, c->T.cfg.d_ffn);
+    if (c->have_draft) kmax = std::max({kmax, c->D.cfg.d_model, c->D.cfg.d_ffn});
+    if (gemm_takes_rows(kMaxFwdRows, kmax)) c->fwd_rows = kMaxFwdRows;
   }
   int *tok = nullptr, *state = nullptr;
   if ((rc = dev_alloc(c, &tok, (size_t)max_batch * c->tok_stride)) || (rc = dev_alloc(c, &state, (size_t)(max_batch + 1) * kSlotState)))
@@ -1660,8 +1676,8 @@ int stairs_generate_batch(stairs_ctx* c, const int32_t* const* prompts, const in
   if (k < 0 || k > c->k_max) return fail(c, STAIRS_EINVAL, "k outside [0, k_max]");
   if (k > 0 && !c->have_draft) return fail(c, STAIRS_ESTATE, "context has no draft model");
   const int rows_max = std::max(B * (k + 1), B * 2);
-  if (rows_max > c->rows_cap || (rows_max > kMaxRows && rows_max > c->pf_rows))
-    return fail(c, STAIRS_EINVAL, "B * (k + 1) exceeds the rows one forward takes (STAIRS_MAX_ROWS, or STAIRS_MAX_BATCH_ROWS after a reservation of more than STAIRS_MAX_ROWS / 2 sequences)");
+  if (rows_max > c->rows_cap || (rows_max > c->fwd_rows && rows_max > c->pf_rows))
+    return fail(c, STAIRS_EINVAL, "B * (k + 1) exceeds the rows one forward takes (STAIRS_MAX_STREAM_ROWS, or STAIRS_MAX_BATCH_ROWS after a reservation of more than STAIRS_MAX_ROWS / 2 sequences)");
   if (!c->T.bf16 || (c->have_draft && !c->D.bf16)) return fail(c, STAIRS_EINVAL, "several sequences need bf16 models");
   if (!prompts || !P) return fail(c, STAIRS_EINVAL, "prompts or P is NULL");
   for (int b = 0; b < B; ++b) {

@@ -7,7 +7,8 @@
 
 namespace stairs {
 
-constexpr int kMaxRows = 32;        // rows (new tokens) one forward of the decode kernels can take
+constexpr int kMaxRows = 32;        // rows (new tokens) of ONE sequence a forward of the decode kernels can take
+constexpr int kMaxFwdRows = 64;     // rows of all sequences together a forward of the decode kernels can take (bf16)
 constexpr int kMaxBlockRows = 256;  // rows one forward of several sequences can take on the block kernels (beyond kMaxRows)
 constexpr int kAttnChunk = 128;     // keys per attention work-group of the fp32-cache kernels and the unit callers count chunks in; boundaries are absolute positions
 constexpr int kAttnChunkH = 256;    // keys per attention work-group of the half-cache kernels (a wave owns 64)
@@ -120,8 +121,13 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
 // (+ kFragChunkPad uint4 after every 16 k-steps: the k chunks the waves of a work-group read at the same time then do
 // not sit a power of two apart)
 constexpr int kFragChunkPad = 272;
-inline size_t frag_bytes(int K) { return ((size_t)(K / 32) * 256 + (size_t)(K / 512 + 1) * kFragChunkPad) * 16; }
+// rows 32..63 of a forward have a second fragment block of the same layout kFragHalfU4 uint4 after the first
+constexpr size_t kFragHalfU4 = (4u << 20) / 16;
+inline size_t frag_bytes(int K) { return ((size_t)(K / 32) * 256 + (size_t)(K / 512 + 1) * kFragChunkPad) * 16; }   // one block of 32 rows
+inline size_t frag_alloc_bytes(int K) { return kFragHalfU4 * 16 + frag_bytes(K); }                                      // both blocks
 // frag = fragments of x [M, K] (row stride ldx) times gain (nullptr: none)
+// whether launch_gemm takes M > kMaxRows rows of a bf16 projection with k = K (the chunk sums of all rows fit the LDS)
+bool gemm_takes_rows(int M, int K);
 void launch_split_frag(const float* X, int ldx, int M, int K, const float* gain, uint4* frag, hipStream_t st);
 
 // The next bf16 launch_gemm records `start` at the beginning and `stop` at the end of its kernel (the events of the

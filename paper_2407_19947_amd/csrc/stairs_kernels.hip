@@ -50,8 +50,10 @@ __device__ __forceinline__ void bf16_split2(float a, float b, uint32_t& hi, uint
 // [k-step of 32][column tile of 16 rows (2)][high, low][lane] x 16 bytes: lane r + 16 g of k-step kt holds
 // x[16 ct + r][32 kt + 8 g .. + 8] * gain as bf16 (high part) and the bf16 of the remainders (low part), the very
 // values split_bf16x8 gives.  A consumer wave loads a fragment as one coalesced 1 KiB read.
+// Rows 32..63 (forwards of several sequences) have a second block of the same layout kFragHalfU4 uint4 further on.
 __device__ __forceinline__ size_t frag_off(int m, int k) {        // in units of 8 bytes: 4 consecutive k of row m, high part
-  return ((((size_t)(k >> 5) * 2 + (m >> 4)) * 2) * 64 + (size_t)(k >> 9) * kFragChunkPad + (m & 15) + 16 * ((k & 31) >> 3)) * 2 +
+  return (size_t)(m >> 5) * (kFragHalfU4 * 2) +
+         ((((size_t)(k >> 5) * 2 + ((m >> 4) & 1)) * 2) * 64 + (size_t)(k >> 9) * kFragChunkPad + (m & 15) + 16 * ((k & 31) >> 3)) * 2 +
          ((k & 7) >> 2);
 }
 // row m, columns k .. k+3 (k a multiple of 4); g = the gain of those columns or nullptr
@@ -979,7 +981,7 @@ __global__ __launch_bounds__(512) void k_gemm_bf16_wide(const uint4* __restrict_
   constexpr int RING = DEPTH + 1;
   constexpr int W = NT * 16;
   extern __shared__ float csum[];                          // [chunk][M][W]
-  __shared__ float s_rstd[kMaxRows];
+  __shared__ float s_rstd[kMaxFwdRows];
   const int tid = threadIdx.x, lane = tid & 63, NW = blockDim.x >> 6;
   // (the wave index as a scalar: everything derived from it -- chunk, k-step, addresses -- is then scalar arithmetic)
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1011,9 +1013,10 @@ __global__ __launch_bounds__(512) void k_gemm_bf16_wide(const uint4* __restrict_
     }
     const uint4* xb = XF + (size_t)s * 4 * 64 + (size_t)c * kFragChunkPad + lane;
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct) {
-      st.bh[ct] = xb[(ct * 2) * 64];
-      st.bl[ct] = xb[(ct * 2 + 1) * 64];
+    for (int ct = 0; ct < CT; ++ct) {                      // column tiles 2, 3: the second fragment block
+      const uint4* xc = xb + (size_t)(ct >> 1) * kFragHalfU4 + ((ct & 1) * 2) * 64;
+      st.bh[ct] = xc[0];
+      st.bl[ct] = xc[64];
     }
   };
 
@@ -1125,6 +1128,8 @@ static size_t rows_path_lds(int role, int M, int N, int K) {
 // parallelism still wins.
 struct WideCfg { int nt, nw; };
 constexpr int wide_depth2(int depth1) { return depth1 <= 2 ? 1 : depth1 <= 3 ? 2 : depth1 <= 5 ? 3 : 5; }   // ring depth at two column tiles
+constexpr int wide_depth3(int depth1) { return depth1 <= 3 ? 1 : depth1 <= 5 ? 2 : 3; }                      // at three (33..48 rows)
+constexpr int wide_depth4(int depth1) { return depth1 <= 3 ? 1 : 2; }                                        // at four (49..64 rows; 3 spills at one tile)
 static WideCfg wide_cfg(int role, int M, int NTILES, int K) {
   // STAIRS_WIDE_CFG="nt/nw,nt/nw,nt/nw,nt/nw,nt/nw" (QKV, out, gate-up, down, head; nt = 0: split-K) overrides the
   // choice: tuning aid
@@ -1153,6 +1158,10 @@ static WideCfg wide_cfg(int role, int M, int NTILES, int K) {
     int nt = 8;
     while (nt > 1 && NTILES / nt < 170) nt /= 2;
     c = {nt, std::min(nt == 1 ? 8 : 4, nchunks)};
+  }
+  if (M > 2 * 16) {                      // 33..64 rows: this kernel only (split-K stops at two column tiles)
+    if (c.nt == 0) c = {1, 4};
+    if (c.nt == 8) c.nt = 4;
   }
   if ((int)forced.size() == 5) {
     const WideCfg f = forced[role];
@@ -1233,6 +1242,10 @@ static void launch_gemm_kernel(F kernel, dim3 grid, dim3 block, size_t lds, hipS
   }
 }
 
+bool gemm_takes_rows(int M, int K) {
+  return M <= kMaxFwdRows && (size_t)gemm_slices(K, 1) * M * 16 * sizeof(float) <= kWideMaxLds;
+}
+
 void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const float* X, int ldx, int M, RowNorm nrm,
                  float* partial, const GemmEpi& epi, hipStream_t st, const uint4* xfrag) {
   if (!dtype_bf16) {
@@ -1294,7 +1307,7 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
   auto wide_lds = [&](int nt) { return (size_t)nchunks * M * nt * 16 * sizeof(float); };
   while (wc.nt > 1 && wide_lds(wc.nt) > kWideMaxLds) wc.nt /= 2;      // very long k: fewer tiles per work-group
   if (xfrag && wc.nt > 0 && wide_lds(wc.nt) <= kWideMaxLds) {
-    const int CT = (M <= 16) ? 1 : 2;
+    const int CT = (M + 15) / 16;
     dim3 grid((NTILES + wc.nt - 1) / wc.nt), block(64 * wc.nw);
     const size_t lds = wide_lds(wc.nt);
 #define STAIRS_WIDE(ct, nt, dp)                                                                                          \
@@ -1307,14 +1320,20 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
                          role, epi);                                                                                     \
   } while (0)
   // (two column tiles hold one k-step less in flight: a deeper ring would not fit the 256 registers of a wave)
-#define STAIRS_WIDE_CT(nt, dp)       \
+  // (three and four column tiles: one more; 8 tiles per wave do not occur there, their chunk sums exceed the LDS)
+#define STAIRS_WIDE_CT2(nt, dp)        \
   if (CT == 1) STAIRS_WIDE(1, nt, dp); \
   else STAIRS_WIDE(2, nt, wide_depth2(dp))
-    if (wc.nt == 8) { STAIRS_WIDE_CT(8, kWideDepth8); }
+#define STAIRS_WIDE_CT(nt, dp)                          \
+  if (CT <= 2) { STAIRS_WIDE_CT2(nt, dp); }             \
+  else if (CT == 3) STAIRS_WIDE(3, nt, wide_depth3(dp)); \
+  else STAIRS_WIDE(4, nt, wide_depth4(dp))
+    if (wc.nt == 8) { STAIRS_WIDE_CT2(8, kWideDepth8); }
     else if (wc.nt == 4) { STAIRS_WIDE_CT(4, kWideDepth4); }
     else if (wc.nt == 2) { STAIRS_WIDE_CT(2, kWideDepth2); }
     else { STAIRS_WIDE_CT(1, kWideDepth1); }
 #undef STAIRS_WIDE_CT
+#undef STAIRS_WIDE_CT2
 #undef STAIRS_WIDE
     return;
   }
@@ -2864,8 +2883,8 @@ hipError_t configure_kernels() {
   STAIRS_OPTIN(4);
 #undef STAIRS_OPTIN2
 #undef STAIRS_OPTIN
-#define STAIRS_OPTIN_WIDE(ct, nt, dp0)                                           \
-  constexpr int dp_##ct##_##nt = (ct) == 1 ? (dp0) : wide_depth2(dp0);          \
+#define STAIRS_OPTIN_WIDE(ct, nt, dp0)                                                                   \
+  constexpr int dp_##ct##_##nt = (ct) == 1 ? (dp0) : (ct) == 2 ? wide_depth2(dp0) : (ct) == 3 ? wide_depth3(dp0) : wide_depth4(dp0);   \
   STAIRS_OPTIN_WIDE_(ct, nt, dp_##ct##_##nt)
 #define STAIRS_OPTIN_WIDE_(ct, nt, dp)                                           \
   optin((const void*)k_gemm_bf16_wide<ct, nt, dp, true>, kWideMaxLds);            \
@@ -2874,6 +2893,9 @@ hipError_t configure_kernels() {
   STAIRS_OPTIN_WIDE(1, 4, kWideDepth4); STAIRS_OPTIN_WIDE(2, 4, kWideDepth4);
   STAIRS_OPTIN_WIDE(1, 2, kWideDepth2); STAIRS_OPTIN_WIDE(2, 2, kWideDepth2);
   STAIRS_OPTIN_WIDE(1, 1, kWideDepth1); STAIRS_OPTIN_WIDE(2, 1, kWideDepth1);
+  STAIRS_OPTIN_WIDE(3, 4, kWideDepth4); STAIRS_OPTIN_WIDE(4, 4, kWideDepth4);
+  STAIRS_OPTIN_WIDE(3, 2, kWideDepth2); STAIRS_OPTIN_WIDE(4, 2, kWideDepth2);
+  STAIRS_OPTIN_WIDE(3, 1, kWideDepth1); STAIRS_OPTIN_WIDE(4, 1, kWideDepth1);
 #undef STAIRS_OPTIN_WIDE
 #undef STAIRS_OPTIN_WIDE_
   optin((const void*)k_gemm_bf16_block, 2 * kBlkStageU4 * sizeof(uint4));

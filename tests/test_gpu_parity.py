@@ -362,6 +362,56 @@ def test_wide_batches_on_the_block_kernels():
     assert np.array_equal(toks2, toks)
 
 
+@pytest.mark.parametrize("B,k", [(12, 2), (16, 2), (13, 3), (16, 3), (9, 6), (7, 8)])
+def test_batches_of_33_to_64_rows_equal_each_sequence_alone(B, k):
+    """36, 48, 52, 64, 63 and 63 rows per verification (three and four column tiles of the hand-off-free GEMM, the
+    second fragment block, draft steps of 2 B rows): still the weight-streaming kernels with one order of additions
+    per row, so every sequence is bit for bit the sequence generated alone, and so is graph replay vs plain launches."""
+    w, target, draft = _batch_pair()
+    lengths = [40, 1, 129, 128, 5, 77, 64, 33, 2, 100, 17, 90, 31, 65, 8, 127][:B]
+    prompts = _prompts(w, lengths)
+    G = 24
+    with pkg.Stairs(target, draft, k_max=8, max_seq=256) as s:
+        alone = [s.generate(p, G, k)[0].copy() for p in prompts]
+        s.reserve_batch(16)
+        toks, st = s.generate_batch(prompts, G, k)
+        for b in range(B):
+            assert np.array_equal(toks[b], alone[b]), (b, k)
+        assert st.tokens == B * G
+    import os
+    os.environ["STAIRS_NO_GRAPH"] = "1"
+    try:
+        with pkg.Stairs(target, draft, k_max=8, max_seq=256) as s:
+            s.reserve_batch(16)
+            toks2, _ = s.generate_batch(prompts, G, k)
+    finally:
+        del os.environ["STAIRS_NO_GRAPH"]
+    assert np.array_equal(toks2, toks)
+
+
+def test_wide_streaming_batch_against_the_oracle():
+    """48 rows per forward (16 sequences, k = 2) against the oracle: every sequence's tokens are an eps-greedy path of
+    the oracle's logits (the batch holds the same bits as the sequence alone, which the single-sequence tests compare
+    logit by logit; this closes the loop through the batched call itself on a model with several weight tiles per
+    wave: d_model 512, d_ffn 1536)."""
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=3, d_model=512, n_heads=8, d_ffn=1536, vocab=4096),
+                           draft=dict(kind="prefix", n_layers=1), P=40, G=16)
+    target, draft = si.make_pair(w)
+    rng = np.random.default_rng([w["seed"], 78])
+    prompts = [rng.integers(0, 4096, n).astype(np.int32) for n in [40, 3, 129, 70, 9, 33, 64, 1, 100, 17, 90, 31, 65, 8, 127, 50]]
+    T = so.OracleModel(target, np.float64)
+    G, k = 16, 2
+    with pkg.Stairs(target, draft, k_max=2, max_seq=256) as s:
+        s.reserve_batch(16)
+        toks, _ = s.generate_batch(prompts, G, k)
+    for b, p in enumerate(prompts):
+        seq = [int(x) for x in p]
+        for i in range(G):
+            lg = so.forward_full(T, seq)[-1]
+            assert eps_ok(lg, int(toks[b][i])), (b, i)
+            seq.append(int(toks[b][i]))
+
+
 def test_batch_limits_and_errors():
     w, target, draft = _batch_pair()
     prompts = _prompts(w, [8, 9])
@@ -372,8 +422,10 @@ def test_batch_limits_and_errors():
         s.reserve_batch(16)
         toks, _ = s.generate_batch(_prompts(w, [5] * 16), 6, 1)   # 16 sequences x 2 rows = the widest forward
         assert toks.shape == (16, 6)
+        toks, _ = s.generate_batch(_prompts(w, [5] * 16), 6, 3)   # 16 x 4 rows: the widest the streaming kernels take
+        assert toks.shape == (16, 6)
         with pytest.raises(pkg.StairsError) as e:
-            s.generate_batch(_prompts(w, [5] * 16), 6, 2)     # 16 x 3 rows do not fit
+            s.generate_batch(_prompts(w, [5] * 16), 6, 4)     # 16 x 5 rows do not fit
         assert e.value.code == -1
         with pytest.raises(pkg.StairsError) as e:
             s.generate_batch(prompts, 120, 3)                 # capacity
