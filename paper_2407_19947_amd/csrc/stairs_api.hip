@@ -483,6 +483,9 @@ int forward(stairs_ctx* c, Model* m, PosRef pos, int nchunk, int M, int logits_r
   // more than 4 rows (bf16): every producer of an activation also leaves its MFMA operand fragments, with the gain of
   // the norm in front of the next projection folded in, and the projections take the hand-off-free kernel
   const bool fr = b && M > 4;
+  // more than kMaxRows rows exist only on the hand-off-free GEMM: every projection must fit it
+  if (M > kMaxRows && !(fr && gemm_takes_rows(M, std::max(d, f))))
+    return fail(c, STAIRS_EINVAL, "forward: more rows than the weight-streaming kernels take for this model");
   launch_embed(m->tok_emb, b, c->tokens + (pos.rps ? 0 : (size_t)slot * c->tok_stride), pos.rps ? c->tok_stride : 0,
                c->tok_stride, V, pos, M, d, c->x, c->ssq, m->hd, g.rope_theta, c->rope_cs, st, fr ? c->xf : nullptr,
                m->layers[0].attn_norm);
