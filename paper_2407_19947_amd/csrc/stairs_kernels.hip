@@ -645,7 +645,8 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
   extern __shared__ uint4 lds[];
   __shared__ float s_rstd[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int tile = blockIdx.x;
+  // a work-group takes the tiles blockIdx.x, blockIdx.x + gridDim.x, ...: the X block is staged once for all of them
+  int cur_tile = blockIdx.x;
   const int KG = K >> 3;                                   // groups of 8 k per row
   const int units_total = K / kUnitK;
   const int nchunks = (units_total + kSliceUnits - 1) / kSliceUnits;
@@ -657,7 +658,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
   auto unit_ptr = [&](int u) {
     const int c = c_begin + (u >> 1);
     const int units_c = min(kSliceUnits, units_total - c * kSliceUnits);
-    return Wsw + (size_t)c * NTILES * (kSliceUnits * 8) * 64 + ((size_t)tile * units_c + (u & 1)) * 8 * 64 + lane;
+    return Wsw + (size_t)c * NTILES * (kSliceUnits * 8) * 64 + ((size_t)cur_tile * units_c + (u & 1)) * 8 * 64 + lane;
   };
 
   // first pass over the X block: a thread takes all R rows of k group kg (the gain is per k, so it is fetched
@@ -703,12 +704,15 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
   // the wave's first two weight units, again without conditions: a wave with fewer units (short K) loads a valid
   // unit it will not use
   uint4 wb0[8], wb1[8];
-  {
-    const uint4* p0 = (nu > 0) ? unit_ptr(0) : Wsw + (size_t)tile * min(kSliceUnits, units_total) * 8 * 64 + lane;
-    const uint4* p1 = (nu > 1) ? unit_ptr(1) : p0;
-    load_unit<STREAM>(p0, wb0);
-    load_unit<STREAM>(p1, wb1);
-  }
+  // (a macro, not a lambda: register arrays a lambda captures by reference end up in scratch memory)
+#define STAIRS_FIRST_UNITS()                                                                                              \
+  do {                                                                                                                    \
+    const uint4* p0 = (nu > 0) ? unit_ptr(0) : Wsw + (size_t)cur_tile * min(kSliceUnits, units_total) * 8 * 64 + lane;   \
+    const uint4* p1 = (nu > 1) ? unit_ptr(1) : p0;                                                                        \
+    load_unit<STREAM>(p0, wb0);                                                                                           \
+    load_unit<STREAM>(p1, wb1);                                                                                           \
+  } while (0)
+  STAIRS_FIRST_UNITS();
   uint4* xhi = lds;
   uint4* xlo = lds + KG * R;
   float* csum = reinterpret_cast<float*>(lds + 2 * KG * R); // [chunk][R][16]
@@ -778,6 +782,11 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc, 0, 0, 0);
     }
   };
+  // the roles whose epilogue loads nothing from memory request the next tile's first units before it (a load in
+  // the epilogue would have to wait for them)
+  constexpr bool kPrefetchNextTile = ROLE == kRoleGateUp || ROLE == kRoleHead;
+  for (;;) {
+  const int tile = cur_tile;
   for (int u = 0; u < nu; u += 2) {                        // one chunk per pass
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     mfma_unit(wb0, u, acc);
@@ -797,6 +806,11 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
       float* dst = csum + (((c_begin + (u >> 1)) * R + m) << 4) + 4 * (lane >> 4);
       dst[0] = acc[0]; dst[1] = acc[1]; dst[2] = acc[2]; dst[3] = acc[3];
     }
+  }
+  const int next_tile = tile + (int)gridDim.x;
+  if (kPrefetchNextTile && next_tile < NTILES) {
+    cur_tile = next_tile;
+    STAIRS_FIRST_UNITS();
   }
   __syncthreads();
 
@@ -819,10 +833,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
       const float s2 = sumsq4(q[8], q[9], q[10], q[11]), s3 = sumsq4(q[12], q[13], q[14], q[15]);
       epi.ssq_out[tid * (N >> 4) + tile] = (s0 + s1) + (s2 + s3);
     }
-    return;
-  }
-  // a thread takes row m, columns j and j+8 of the tile
-  if (tid < R * 8) {
+  } else if (tid < R * 8) {                                // a thread takes row m, columns j and j+8 of the tile
     const int m = tid >> 3, j = tid & 7;
     float a = lds_chunk_sum(csum + (m << 4) + j, R * 16, nchunks);
     float b = lds_chunk_sum(csum + (m << 4) + j + 8, R * 16, nchunks);
@@ -841,6 +852,14 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
       qkv_pair(a, b, m, col, N / 3, epi);
     }
   }
+  if (next_tile >= NTILES) break;
+  if (!kPrefetchNextTile) {
+    cur_tile = next_tile;
+    STAIRS_FIRST_UNITS();
+  }
+  __syncthreads();                                         // the chunk sums are free for the next tile
+  }
+#undef STAIRS_FIRST_UNITS
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1278,13 +1297,26 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
   const int NTILES = N / 16, KT = K / 32;
   const uint4* Wsw = static_cast<const uint4*>(W);
   if (const size_t rl = rows_path_lds(role, M, N, K)) {
+    // gate/up has several times more tiles than the chip has CUs: one work-group per CU that walks through its
+    // share of the tiles (X block staged once, the next tile's first units requested before the epilogue, all
+    // work-groups resident from the start and done together) streams better than a work-group per tile (7B, 1376
+    // tiles, isolated: 30.1 -> 28.5 us at 3 rows with 230 work-groups of 6 tiles; 459 x 3: 29.1, 344 x 4: 32.5 -- two
+    // work-groups on some CUs and one on others is the worst case; the unembedding's 2000 tiles and, with its
+    // epilogue's loads requested early, QKV's 768 gain nothing)
+    int tpw = 1;
+    if (role == kRoleGateUp && NTILES >= 4 * 256) tpw = (NTILES + 255) / 256;
+    {
+      static const int forced = [] { const char* e = getenv("STAIRS_ROWS_TPW"); return e ? atoi(e) : 0; }();
+      if (forced > 0 && (role == kRoleGateUp || role == kRoleHead)) tpw = forced;    // tuning aid
+    }
+    const dim3 rgrid((NTILES + tpw - 1) / tpw);
 #define STAIRS_ROWS(r, role, nw, gp)                                                                                  \
   do {                                                                                                                 \
   if (epi.stream_weights)                                                                                            \
-    launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp, true>, dim3(NTILES), dim3(64 * nw), rl, st, Wsw, NTILES, X,    \
+    launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp, true>, rgrid, dim3(64 * nw), rl, st, Wsw, NTILES, X,    \
                        ldx, nrm, K, N, epi);                                                                            \
   else                                                                                                                 \
-    launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp, false>, dim3(NTILES), dim3(64 * nw), rl, st, Wsw, NTILES, X,   \
+    launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp, false>, rgrid, dim3(64 * nw), rl, st, Wsw, NTILES, X,   \
                        ldx, nrm, K, N, epi);                                                                            \
   } while (0)
 #define STAIRS_ROWS_ROLE(role, nw, gp)           \
