@@ -285,8 +285,13 @@ __device__ __forceinline__ float2 rope_rotate(float a, float b, float2 cs) {
 }
 // Row m, columns col and col+8 of the permuted QKV output (col & 15 < 8): a rotation pair of q or k, or two
 // plain values of v.  pos0 = position of row 0.
-__device__ __forceinline__ void qkv_pair(float a, float b, int m, int col, int d, const GemmEpi& epi) {
-  const int p = pos_of(epi.pos, m);
+// index of the rotation entry of columns (col, col + 8) of row m (q and k parts; for the v part some valid index)
+__device__ __forceinline__ int qkv_rope_index(int m, int col, int d, int hd) {
+  const int c = col % d, w = c % hd;
+  return m * 64 + (w >> 4) * 8 + (w & 7);
+}
+// p: the row's position (pos_of), cs: its rotation entry (epi.rope_cs[qkv_rope_index]); a caller may have loaded both early
+__device__ __forceinline__ void qkv_pair_at(float a, float b, int m, int col, int d, const GemmEpi& epi, int p, float2 cs) {
   if (p < 0) return;
   const size_t slot_off = (size_t)slot_of(epi.pos, m) * epi.kv_slot_stride;
   const int hd = epi.hd, half = hd >> 1;
@@ -299,7 +304,7 @@ __device__ __forceinline__ void qkv_pair(float a, float b, int m, int col, int d
     return;
   }
   const int e = (w >> 4) * 8 + (w & 7);
-  const float2 r = rope_rotate(a, b, epi.rope_cs[m * 64 + e]);
+  const float2 r = rope_rotate(a, b, cs);
   if (part == 0) {
     epi.out[(size_t)m * d + h * hd + e] = r.x;
     epi.out[(size_t)m * d + h * hd + e + half] = r.y;
@@ -308,6 +313,11 @@ __device__ __forceinline__ void qkv_pair(float a, float b, int m, int col, int d
     store_kv(dst + k_cache_off(p, e, hd), r.x);
     store_kv(dst + k_cache_off(p, e + half, hd), r.y);
   }
+}
+__device__ __forceinline__ void qkv_pair(float a, float b, int m, int col, int d, const GemmEpi& epi) {
+  const int p = pos_of(epi.pos, m);
+  if (p < 0) return;
+  qkv_pair_at(a, b, m, col, d, epi, p, epi.rope_cs[qkv_rope_index(m, col, d, epi.hd)]);
 }
 
 // Epilogue of one column group [c0, c0+W) for all M rows, run by the 256 threads of one work-group.
@@ -643,7 +653,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
   // NW waves; GP = k groups a thread takes in the first staging pass (covers K <= 8 * 64 * NW * GP)
   constexpr int NTH = 64 * NW;
   extern __shared__ uint4 lds[];
-  __shared__ float s_rstd[4];
+  __shared__ float s_rstd[8];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // a work-group takes the tiles blockIdx.x, blockIdx.x + gridDim.x, ...: the X block is staged once for all of them
   int cur_tile = blockIdx.x;
@@ -689,7 +699,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
       gb[j] = gp[1];
     }
   }
-  // row statistics: half a wave per row (R <= 4 rows: waves 0 and 1).  The first 256 partials of the row are
+  // row statistics: half a wave per row (R <= 8 rows: the first (R + 1) / 2 waves).  The first 256 partials of the row are
   // requested here, without conditions (indices clamped, values masked later), and added up after the conversion of
   // the X block, in the order rows_rstd uses: the 1/rms multiplies the finished sums in the epilogue.
   const bool has_stats = nrm.gain && nrm.ssq_part;
@@ -748,7 +758,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
       xlo[kg * R + m] = lo;
     }
   }
-  if (has_stats && wave < 2) {                             // wave-uniform
+  if (has_stats && wave < (R + 1) / 2) {                   // wave-uniform
     float ss = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) ss += (st_pl + 32 * i < nrm.ssq_n) ? sv[i] : 0.f;
@@ -784,7 +794,10 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
   };
   // the roles whose epilogue loads nothing from memory request the next tile's first units before it (a load in
   // the epilogue would have to wait for them)
-  constexpr bool kPrefetchNextTile = ROLE == kRoleGateUp || ROLE == kRoleHead;
+  constexpr bool kPrefetchNextTile = ROLE == kRoleGateUp || ROLE == kRoleHead || ROLE == kRoleQKV;
+  // (QKV: what its epilogue loads -- the row's position, the rotation entry -- is requested before that)
+  int q_pos = 0;
+  if (ROLE == kRoleQKV && tid < R * 8) q_pos = pos_of(epi.pos, tid >> 3);
   for (;;) {
   const int tile = cur_tile;
   for (int u = 0; u < nu; u += 2) {                        // one chunk per pass
@@ -807,6 +820,9 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
       dst[0] = acc[0]; dst[1] = acc[1]; dst[2] = acc[2]; dst[3] = acc[3];
     }
   }
+  float2 q_cs = make_float2(1.f, 0.f);
+  if (ROLE == kRoleQKV && tid < R * 8) q_cs = epi.rope_cs[qkv_rope_index(tid >> 3, tile * 16 + (tid & 7), N / 3, epi.hd)];
+  __builtin_amdgcn_sched_barrier(0);                       // these requests stay in front of the next tile's
   const int next_tile = tile + (int)gridDim.x;
   if (kPrefetchNextTile && next_tile < NTILES) {
     cur_tile = next_tile;
@@ -833,6 +849,12 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
       const float s2 = sumsq4(q[8], q[9], q[10], q[11]), s3 = sumsq4(q[12], q[13], q[14], q[15]);
       epi.ssq_out[tid * (N >> 4) + tile] = (s0 + s1) + (s2 + s3);
     }
+    // more than 4 rows: the next projection may take the kernel that reads activation fragments
+    if (R > 4 && epi.frag_out && tid >= 64 && tid < 64 + R * 4) {
+      const int t = tid - 64, m = t >> 2, q = (t & 3) * 4;
+      const float* v = sq + m * 16 + q;
+      store_frag4(epi.frag_out, m, tile * 16 + q, make_float4(v[0], v[1], v[2], v[3]), epi.frag_gain);
+    }
   } else if (tid < R * 8) {                                // a thread takes row m, columns j and j+8 of the tile
     const int m = tid >> 3, j = tid & 7;
     float a = lds_chunk_sum(csum + (m << 4) + j, R * 16, nchunks);
@@ -842,14 +864,34 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16_rows(const uint4* __restr
       b *= s_rstd[m];
     }
     const int col = tile * 16 + j;
+    // (more than 4 rows: also the result's activation fragments -- the four threads of columns 4q .. 4q+3 sit in
+    // adjacent lanes of wave 0, which holds all R * 8 <= 64 threads of this branch)
+    const int l4 = lane & ~3;
     if (ROLE == kRoleHead) {
       const bool relu = epi.act == kActRelu;
-      epi.out[(size_t)m * N + col] = relu ? fmaxf(a, 0.f) : a;
-      epi.out[(size_t)m * N + col + 8] = relu ? fmaxf(b, 0.f) : b;
+      if (relu) {
+        a = fmaxf(a, 0.f);
+        b = fmaxf(b, 0.f);
+      }
+      epi.out[(size_t)m * N + col] = a;
+      epi.out[(size_t)m * N + col + 8] = b;
+      if (R > 4 && epi.frag_out) {
+        const float4 va = make_float4(__shfl(a, l4), __shfl(a, l4 + 1), __shfl(a, l4 + 2), __shfl(a, l4 + 3));
+        const float4 vb = make_float4(__shfl(b, l4), __shfl(b, l4 + 1), __shfl(b, l4 + 2), __shfl(b, l4 + 3));
+        if ((j & 3) == 0) {
+          store_frag4(epi.frag_out, m, col, va, epi.frag_gain);
+          store_frag4(epi.frag_out, m, col + 8, vb, epi.frag_gain);
+        }
+      }
     } else if (ROLE == kRoleGateUp) {
-      epi.out[(size_t)m * (N >> 1) + tile * 8 + j] = swiglu(a, b);
+      const float o = swiglu(a, b);
+      epi.out[(size_t)m * (N >> 1) + tile * 8 + j] = o;
+      if (R > 4 && epi.frag_out) {
+        const float4 vo = make_float4(__shfl(o, l4), __shfl(o, l4 + 1), __shfl(o, l4 + 2), __shfl(o, l4 + 3));
+        if ((j & 3) == 0) store_frag4(epi.frag_out, m, tile * 8 + j, vo, nullptr);
+      }
     } else {
-      qkv_pair(a, b, m, col, N / 3, epi);
+      qkv_pair_at(a, b, m, col, N / 3, epi, q_pos, q_cs);
     }
   }
   if (next_tile >= NTILES) break;
@@ -1128,8 +1170,11 @@ void launch_split_frag(const float* X, int ldx, int M, int K, const float* gain,
 // have few weight tiles (N = d_model): they run one 8-wave work-group per CU and only when the tiles about
 // cover the chip.
 static size_t rows_path_lds(int role, int M, int N, int K) {
-  if (M > 4) return 0;
+  static const int max_rows = [] { const char* e = getenv("STAIRS_ROWS_MAX"); return e ? atoi(e) : 8; }();   // tuning aid
+  if (M > 8 || M > max_rows) return 0;
   const size_t bytes = (size_t)K * M * 4 + (size_t)(gemm_slices(K, 1) + 1) * M * 16 * 4;
+  // 5..8 rows: the block takes more than half a CU's LDS, so one work-group per CU walks through the tiles
+  if (M > 4) return (role != kRoleDown && bytes <= kRowsPathMaxLdsWide && N / 16 >= 192) ? std::max(bytes, (size_t)81 * 1024) : 0;
   if (role == kRoleWo || role == kRoleDown) {
     // few tiles: only matrices so small that the launch is latency-bound anyway (no partial sums, no hand-off)
     if (N / 16 < 192) return ((size_t)N * K * 2 <= kRowsPathSmallMatrix && bytes <= kRowsPathMaxLdsWide) ? bytes : 0;
@@ -1304,7 +1349,7 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
     // work-groups on some CUs and one on others is the worst case; the unembedding's 2000 tiles and, with its
     // epilogue's loads requested early, QKV's 768 gain nothing)
     int tpw = 1;
-    if (role == kRoleGateUp && NTILES >= 4 * 256) tpw = (NTILES + 255) / 256;
+    if ((role == kRoleGateUp && NTILES >= 4 * 256) || (M > 4 && NTILES > 256)) tpw = (NTILES + 255) / 256;
     {
       static const int forced = [] { const char* e = getenv("STAIRS_ROWS_TPW"); return e ? atoi(e) : 0; }();
       if (forced > 0 && (role == kRoleGateUp || role == kRoleHead)) tpw = forced;    // tuning aid
@@ -1319,17 +1364,24 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
     launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp, false>, rgrid, dim3(64 * nw), rl, st, Wsw, NTILES, X,   \
                        ldx, nrm, K, N, epi);                                                                            \
   } while (0)
-#define STAIRS_ROWS_ROLE(role, nw, gp)           \
+#define STAIRS_ROWS_ROLE4(role, nw, gp)          \
   if (M <= 1) STAIRS_ROWS(1, role, nw, gp);      \
   else if (M == 2) STAIRS_ROWS(2, role, nw, gp); \
   else if (M == 3) STAIRS_ROWS(3, role, nw, gp); \
   else STAIRS_ROWS(4, role, nw, gp)
+#define STAIRS_ROWS_ROLE(role, nw, gp)                \
+  if (M <= 4) { STAIRS_ROWS_ROLE4(role, nw, gp); }    \
+  else if (M == 5) STAIRS_ROWS(5, role, nw, gp);      \
+  else if (M == 6) STAIRS_ROWS(6, role, nw, gp);      \
+  else if (M == 7) STAIRS_ROWS(7, role, nw, gp);      \
+  else STAIRS_ROWS(8, role, nw, gp)
     if (role == kRoleQKV) { STAIRS_ROWS_ROLE(kRoleQKV, 4, 2); }
     else if (role == kRoleGateUp) { STAIRS_ROWS_ROLE(kRoleGateUp, 4, 2); }
     else if (role == kRoleHead) { STAIRS_ROWS_ROLE(kRoleHead, 4, 2); }
     else if (role == kRoleWo) { STAIRS_ROWS_ROLE(kRoleWo, 8, 1); }
-    else { STAIRS_ROWS_ROLE(kRoleDown, 8, 3); }
+    else { STAIRS_ROWS_ROLE4(kRoleDown, 8, 3); }           // (down never takes this path beyond 4 rows: its k is long)
 #undef STAIRS_ROWS_ROLE
+#undef STAIRS_ROWS_ROLE4
 #undef STAIRS_ROWS
     return;
   }
@@ -2913,6 +2965,16 @@ hipError_t configure_kernels() {
   STAIRS_OPTIN(2);
   STAIRS_OPTIN(3);
   STAIRS_OPTIN(4);
+#undef STAIRS_OPTIN2
+#define STAIRS_OPTIN2(r, st)                                                                       \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleQKV, 4, 2, st>, kRowsPathMaxLdsWide);                \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleGateUp, 4, 2, st>, kRowsPathMaxLdsWide);             \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleHead, 4, 2, st>, kRowsPathMaxLdsWide);               \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleWo, 8, 1, st>, kRowsPathMaxLdsWide)
+  STAIRS_OPTIN(5);
+  STAIRS_OPTIN(6);
+  STAIRS_OPTIN(7);
+  STAIRS_OPTIN(8);
 #undef STAIRS_OPTIN2
 #undef STAIRS_OPTIN
 #define STAIRS_OPTIN_WIDE(ct, nt, dp0)                                                                   \
