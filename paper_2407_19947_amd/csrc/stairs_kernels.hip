@@ -1173,8 +1173,10 @@ static size_t rows_path_lds(int role, int M, int N, int K) {
   static const int max_rows = [] { const char* e = getenv("STAIRS_ROWS_MAX"); return e ? atoi(e) : 8; }();   // tuning aid
   if (M > 8 || M > max_rows) return 0;
   const size_t bytes = (size_t)K * M * 4 + (size_t)(gemm_slices(K, 1) + 1) * M * 16 * 4;
-  // 5..8 rows: the block takes more than half a CU's LDS, so one work-group per CU walks through the tiles
-  if (M > 4) return (role != kRoleDown && bytes <= kRowsPathMaxLdsWide && N / 16 >= 192) ? std::max(bytes, (size_t)81 * 1024) : 0;
+  // 5..8 rows: the block takes more than half a CU's LDS, so one work-group per CU walks through the tiles; only
+  // with a k chunk for each of its waves (k >= 2048) does that beat the fragment-reading kernel
+  if (M > 4)
+    return (role != kRoleDown && bytes <= kRowsPathMaxLdsWide && N / 16 >= 192 && K >= 2048) ? std::max(bytes, (size_t)81 * 1024) : 0;
   if (role == kRoleWo || role == kRoleDown) {
     // few tiles: only matrices so small that the launch is latency-bound anyway (no partial sums, no hand-off)
     if (N / 16 < 192) return ((size_t)N * K * 2 <= kRowsPathSmallMatrix && bytes <= kRowsPathMaxLdsWide) ? bytes : 0;
