@@ -551,6 +551,36 @@ def test_longest_context_stair_batches(monkeypatch):
     assert err <= LOGIT_TOL_BF16
 
 
+def test_five_to_eight_rows_on_wide_projections():
+    """Stair batches of 5..8 rows on a model whose projections are wide and long enough for the LDS-resident GEMM in
+    its one-work-group-per-CU form (d_model 2048: k = 2048, QKV 384 tiles, gate/up 256, unembedding 512; the down
+    projection with k = 2048 too): logits against the oracle for every such row count, the rows of a shorter batch
+    bit-identical to the same rows of the longest one, and the tokens of every k equal to plain greedy decoding."""
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=2, d_model=2048, n_heads=16, d_ffn=2048, vocab=8192),
+                           draft=dict(kind="prefix", n_layers=1), P=70, G=12)
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    T = so.OracleModel(target, np.float64)
+    rng = np.random.default_rng([w["seed"], 5])
+    d = [int(x) for x in rng.integers(0, 8192, 8)]
+    want = so.forward_full(T, [int(x) for x in prompt] + d)[len(prompt) - 1:]        # rows of the stair batch
+    with pkg.Stairs(target, draft, k_max=8, max_seq=128) as s:
+        logits = {}
+        for kk in (8, 7, 6, 5, 4, 3, 0):
+            s.prefill(prompt)
+            tgt, n, lg = s.verify_tokens(d[:kk], logits=True)
+            err = float(np.max(np.abs(lg.astype(np.float64) - want[:kk + 1])))
+            _log(f"{kk + 1} rows: max logit error {err:.3g}")
+            assert err <= LOGIT_TOL_BF16
+            logits[kk] = lg.copy()
+        for kk in (7, 6, 5, 4, 3, 0):
+            assert np.array_equal(logits[kk], logits[8][:kk + 1]), kk
+        base, _ = s.generate(prompt, w["G"], 0)
+        for kk in (4, 5, 6, 7, 8):
+            toks, _ = s.generate(prompt, w["G"], kk)
+            assert np.array_equal(toks, base), kk
+
+
 @pytest.mark.parametrize("case", range(14))
 def test_shape_sweep_against_the_oracle(case):
     """Seeded sweep over the documented shape limits: widths with an odd number of 256-wide weight units (768, 1280),
