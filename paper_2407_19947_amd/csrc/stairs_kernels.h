@@ -24,7 +24,7 @@ constexpr int kSpwRows = 9;         // 9..16 rows: a split-K work-group takes tw
 constexpr size_t kRowsPathMaxLds = 68 * 1024;
 constexpr size_t kRowsPathMaxLdsWide = 150 * 1024;
 constexpr size_t kWideMaxLds = 150 * 1024;      // chunk sums of k_gemm_bf16_wide: chunks * rows * 16 NT * 4 bytes
-constexpr int kWideDepth8 = 2, kWideDepth4 = 3, kWideDepth2 = 5, kWideDepth1 = 8;   // k-steps in flight per wave at 4 / 2 / 1 tiles per wave
+constexpr int kWideDepth8 = 2, kWideDepth6 = 2, kWideDepth4 = 3, kWideDepth3 = 4, kWideDepth2 = 5, kWideDepth1 = 8;   // k-steps in flight per wave at 4 / 2 / 1 tiles per wave
 constexpr size_t kRowsPathSmallMatrix = 16u << 20;   // residual-writing projections with fewer tiles than CUs: up to this many bytes
 
 // Where the rows of a forward sit.  One sequence (rps == 0): row r is at position *base + offset + r (base lives

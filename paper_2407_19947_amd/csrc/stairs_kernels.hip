@@ -1212,26 +1212,33 @@ static WideCfg wide_cfg(int role, int M, int NTILES, int K) {
     return v;
   }();
   const int nchunks = gemm_slices(K, 1);
-  // Measured on the 125M, 1B and 7B workloads (5..32 rows): as many tiles per wave (8, 4, 2, 1) as still leave about
-  // 170 work-groups; with one tile per wave up to 8 waves share the k chunks, else 4.  Few tiles with a long k range
-  // (down projections: 128 x 8192 at 1B, 256 x 11008 at 7B) stream better through the split-K kernel, whose grid also
-  // cuts k; from 17 rows on the 7B shape is the exception.  Small matrices are latency-bound either way and the
-  // missing hand-off is what counts (125M at 16 rows: 595 -> 470 us per forward).
+  // Measured on the 125M, 1B and 7B workloads (5..32 rows): about one work-group per CU, i.e. the smallest number of
+  // tiles per wave (1, 2, 3, 4, 6, 8) that covers the matrix with at most 256 work-groups, as long as about 170 remain
+  // (7B: gate/up 1376 tiles -> 6, 230 work-groups: 29.6 us at 9 rows against 32.4 us for 172 work-groups of 8; QKV
+  // 768 -> 3, 256 work-groups: 19.6 against 22.0 us for 192 of 4; unembedding 2000 -> 8); with one tile per wave up
+  // to 8 waves share the k chunks, else 4 (8 and 2 measured slower).  Few tiles with a long k range (down projections:
+  // 128 x 8192 at 1B, 256 x 11008 at 7B) stream better through the split-K kernel, whose grid also cuts k; from 17
+  // rows on the 7B shape is the exception.  Small matrices are latency-bound either way and the missing hand-off is
+  // what counts (125M at 16 rows: 595 -> 470 us per forward).
   WideCfg c{0, 0};
   if (nchunks > 8 && NTILES < 512) {
     if (NTILES >= 192 && M > 16) c = {1, 4};
   } else {
-    int nt = 8;
-    while (nt > 1 && NTILES / nt < 170) nt /= 2;
+    static const int kNts[] = {1, 2, 3, 4, 6, 8};
+    int i = 0;
+    while (i < 5 && kNts[i] * 256 < NTILES) ++i;
+    while (i > 0 && NTILES / kNts[i] < 170) --i;
+    const int nt = kNts[i];
     c = {nt, std::min(nt == 1 ? 8 : 4, nchunks)};
-  }
-  if (M > 2 * 16) {                      // 33..64 rows: this kernel only (split-K stops at two column tiles)
-    if (c.nt == 0) c = {1, 4};
-    if (c.nt == 8) c.nt = 4;
   }
   if ((int)forced.size() == 5) {
     const WideCfg f = forced[role];
-    if ((f.nt == 0 || f.nt == 1 || f.nt == 2 || f.nt == 4 || f.nt == 8) && f.nw >= 1 && f.nw <= 8) c = f;
+    if ((f.nt == 0 || f.nt == 1 || f.nt == 2 || f.nt == 3 || f.nt == 4 || f.nt == 6 || f.nt == 8) && f.nw >= 1 && f.nw <= 8) c = f;
+  }
+  if (M > 2 * 16) {                      // 33..64 rows: this kernel only (split-K stops at two column tiles)
+    if (c.nt == 0) c = {1, 4};
+    if (c.nt > 4) c.nt = 4;                 // (the three- and four-column-tile forms exist for 1, 2 and 4 tiles per wave)
+    if (c.nt == 3) c.nt = 2;
   }
   return c;
 }
@@ -1391,7 +1398,7 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
   WideCfg wc = wide_cfg(role, M, NTILES, K);
   const int nchunks = gemm_slices(K, 1);
   auto wide_lds = [&](int nt) { return (size_t)nchunks * M * nt * 16 * sizeof(float); };
-  while (wc.nt > 1 && wide_lds(wc.nt) > kWideMaxLds) wc.nt /= 2;      // very long k: fewer tiles per work-group
+  while (wc.nt > 1 && wide_lds(wc.nt) > kWideMaxLds) wc.nt = wc.nt == 6 ? 4 : wc.nt == 3 ? 2 : wc.nt / 2;   // very long k: fewer tiles per work-group
   if (xfrag && wc.nt > 0 && wide_lds(wc.nt) <= kWideMaxLds) {
     const int CT = (M + 15) / 16;
     dim3 grid((NTILES + wc.nt - 1) / wc.nt), block(64 * wc.nw);
@@ -1415,6 +1422,8 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
   else if (CT == 3) STAIRS_WIDE(3, nt, wide_depth3(dp)); \
   else STAIRS_WIDE(4, nt, wide_depth4(dp))
     if (wc.nt == 8) { STAIRS_WIDE_CT2(8, kWideDepth8); }
+    else if (wc.nt == 6) { STAIRS_WIDE_CT2(6, kWideDepth6); }
+    else if (wc.nt == 3) { STAIRS_WIDE_CT2(3, kWideDepth3); }
     else if (wc.nt == 4) { STAIRS_WIDE_CT(4, kWideDepth4); }
     else if (wc.nt == 2) { STAIRS_WIDE_CT(2, kWideDepth2); }
     else { STAIRS_WIDE_CT(1, kWideDepth1); }
@@ -2986,6 +2995,8 @@ hipError_t configure_kernels() {
   optin((const void*)k_gemm_bf16_wide<ct, nt, dp, true>, kWideMaxLds);            \
   optin((const void*)k_gemm_bf16_wide<ct, nt, dp, false>, kWideMaxLds)
   STAIRS_OPTIN_WIDE(1, 8, kWideDepth8); STAIRS_OPTIN_WIDE(2, 8, kWideDepth8);
+  STAIRS_OPTIN_WIDE(1, 6, kWideDepth6); STAIRS_OPTIN_WIDE(2, 6, kWideDepth6);
+  STAIRS_OPTIN_WIDE(1, 3, kWideDepth3); STAIRS_OPTIN_WIDE(2, 3, kWideDepth3);
   STAIRS_OPTIN_WIDE(1, 4, kWideDepth4); STAIRS_OPTIN_WIDE(2, 4, kWideDepth4);
   STAIRS_OPTIN_WIDE(1, 2, kWideDepth2); STAIRS_OPTIN_WIDE(2, 2, kWideDepth2);
   STAIRS_OPTIN_WIDE(1, 1, kWideDepth1); STAIRS_OPTIN_WIDE(2, 1, kWideDepth1);
