@@ -1170,10 +1170,10 @@ void launch_split_frag(const float* X, int ldx, int M, int K, const float* gain,
 // have few weight tiles (N = d_model): they run one 8-wave work-group per CU and only when the tiles about
 // cover the chip.
 static size_t rows_path_lds(int role, int M, int N, int K) {
-  static const int max_rows = [] { const char* e = getenv("STAIRS_ROWS_MAX"); return e ? atoi(e) : 8; }();   // tuning aid
-  if (M > 8 || M > max_rows) return 0;
+  static const int max_rows = [] { const char* e = getenv("STAIRS_ROWS_MAX"); return e ? atoi(e) : 7; }();   // tuning aid
+  if (M > 7 || M > max_rows) return 0;
   const size_t bytes = (size_t)K * M * 4 + (size_t)(gemm_slices(K, 1) + 1) * M * 16 * 4;
-  // 5..8 rows: the block takes more than half a CU's LDS, so one work-group per CU walks through the tiles; only
+  // 5..7 rows (at 8 the fragment-reading kernel is as fast): the block takes more than half a CU's LDS, so one work-group per CU walks through the tiles; only
   // with a k chunk for each of its waves (k >= 2048) does that beat the fragment-reading kernel
   if (M > 4)
     return (role != kRoleDown && bytes <= kRowsPathMaxLdsWide && N / 16 >= 192 && K >= 2048) ? std::max(bytes, (size_t)81 * 1024) : 0;
@@ -1382,8 +1382,7 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
   if (M <= 4) { STAIRS_ROWS_ROLE4(role, nw, gp); }    \
   else if (M == 5) STAIRS_ROWS(5, role, nw, gp);      \
   else if (M == 6) STAIRS_ROWS(6, role, nw, gp);      \
-  else if (M == 7) STAIRS_ROWS(7, role, nw, gp);      \
-  else STAIRS_ROWS(8, role, nw, gp)
+  else STAIRS_ROWS(7, role, nw, gp)
     if (role == kRoleQKV) { STAIRS_ROWS_ROLE(kRoleQKV, 4, 2); }
     else if (role == kRoleGateUp) { STAIRS_ROWS_ROLE(kRoleGateUp, 4, 2); }
     else if (role == kRoleHead) { STAIRS_ROWS_ROLE(kRoleHead, 4, 2); }
@@ -2985,7 +2984,6 @@ hipError_t configure_kernels() {
   STAIRS_OPTIN(5);
   STAIRS_OPTIN(6);
   STAIRS_OPTIN(7);
-  STAIRS_OPTIN(8);
 #undef STAIRS_OPTIN2
 #undef STAIRS_OPTIN
 #define STAIRS_OPTIN_WIDE(ct, nt, dp0)                                                                   \
