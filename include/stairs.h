@@ -86,6 +86,13 @@ typedef struct {
   int32_t accept_hist[STAIRS_MAX_ROWS + 1];   /* accept_hist[n] = iterations that kept n   */
 } stairs_stats;
 
+/* Environment variables read by the library (all optional; for measurements and tests, never needed in use):
+ *   STAIRS_NO_GRAPH=1          launch every kernel one by one instead of replaying captured iterations
+ *   STAIRS_NO_BLOCK_PREFILL=1  ingest prompts with the decode kernels, 32 rows per forward (read at stairs_init)
+ *   STAIRS_SYNC_LAUNCHES=1|2   wait after every kernel (counter-collecting profilers); 1 also ingests prompts with
+ *                              the decode kernels, 2 keeps the block kernels
+ *   STAIRS_WIDE_CFG, STAIRS_ROWS_MAX, STAIRS_ROWS_TPW   launch shapes of the GEMM kernels (tuning aids, read once per
+ *                              process; results are bit-identical whatever they say) */
 typedef struct stairs_ctx stairs_ctx;   /* opaque */
 
 const char *stairs_strerror(int code);
