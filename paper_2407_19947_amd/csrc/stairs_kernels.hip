@@ -1238,7 +1238,7 @@ static WideCfg wide_cfg(int role, int M, int NTILES, int K) {
   if (M > 2 * 16) {                      // 33..64 rows: this kernel only (split-K stops at two column tiles)
     if (c.nt == 0) c = {1, 4};
     if (c.nt > 4) c.nt = 4;                 // (the three- and four-column-tile forms exist for 1, 2 and 4 tiles per wave)
-    if (c.nt == 3) c.nt = 2;
+    if (c.nt == 3) c.nt = 4;
   }
   return c;
 }
