@@ -1364,13 +1364,15 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
       if (forced > 0 && (role == kRoleGateUp || role == kRoleHead)) tpw = forced;    // tuning aid
     }
     const dim3 rgrid((NTILES + tpw - 1) / tpw);
+    // (walking work-groups ask for more than half a CU's LDS, so that no CU gets two of them while another has none)
+    const size_t rl_launch = tpw > 1 ? std::max(rl, (size_t)81 * 1024) : rl;
 #define STAIRS_ROWS(r, role, nw, gp)                                                                                  \
   do {                                                                                                                 \
   if (epi.stream_weights)                                                                                            \
-    launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp, true>, rgrid, dim3(64 * nw), rl, st, Wsw, NTILES, X,    \
+    launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp, true>, rgrid, dim3(64 * nw), rl_launch, st, Wsw, NTILES, X,    \
                        ldx, nrm, K, N, epi);                                                                            \
   else                                                                                                                 \
-    launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp, false>, rgrid, dim3(64 * nw), rl, st, Wsw, NTILES, X,   \
+    launch_gemm_kernel(k_gemm_bf16_rows<r, role, nw, gp, false>, rgrid, dim3(64 * nw), rl_launch, st, Wsw, NTILES, X,   \
                        ldx, nrm, K, N, epi);                                                                            \
   } while (0)
 #define STAIRS_ROWS_ROLE4(role, nw, gp)          \
@@ -2964,7 +2966,7 @@ hipError_t configure_kernels() {
   };
 #define STAIRS_OPTIN2(r, st)                                                                       \
   optin((const void*)k_gemm_bf16_rows<r, kRoleQKV, 4, 2, st>, kRowsPathMaxLds);                    \
-  optin((const void*)k_gemm_bf16_rows<r, kRoleGateUp, 4, 2, st>, kRowsPathMaxLds);                 \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleGateUp, 4, 2, st>, kRowsPathMaxLdsWide);             \
   optin((const void*)k_gemm_bf16_rows<r, kRoleHead, 4, 2, st>, kRowsPathMaxLds);                   \
   optin((const void*)k_gemm_bf16_rows<r, kRoleWo, 8, 1, st>, kRowsPathMaxLdsWide);                 \
   optin((const void*)k_gemm_bf16_rows<r, kRoleDown, 8, 3, st>, kRowsPathMaxLdsWide)
