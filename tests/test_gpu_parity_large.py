@@ -67,7 +67,7 @@ def test_cfg4_7b_full_prompt(pair7b):
     """7B target, full 2048-token prompt, side by side with the oracle at the draft lengths the benchmark's sweep
     picks its headline from (k = 1, 2, 3: the kernels for up to 4 rows) and at k = 4 (the kernels for more rows), a
     few iterations each on ONE oracle prefill (the oracle's prompt ingestion is the expensive part; every draft
-    length continues the same teacher-forced sequence); then k = 16 (17 rows) on a shorter prompt."""
+    length continues the same teacher-forced sequence); then k = 16, 6, 8, 11 (17, 7, 9, 12 rows) on a shorter prompt."""
     from oracle import stairs_oracle as so
     from parity_util import compare_generation
     w, target, draft = pair7b
@@ -84,8 +84,19 @@ def test_cfg4_7b_full_prompt(pair7b):
             res = compare_generation(orc, gpu, len(prompt), 10 ** 6, k, LOGIT_TOL_BF16, max_iters=n_it, log=_log)
             _log(f"cfg4 k={k}: err={res['max_logit_err']:.3g} mism={res['token_mismatches']} n={res['n_accepted']} "
                  f"({time.time() - t0:.0f}s)")
-    res = run_side_by_side(target, draft, prompt[:300], 20, 16, np.float32, LOGIT_TOL_BF16, max_iters=2, log=_log)
-    _log(f"cfg4 k=16 (P=300): err={res['max_logit_err']:.3g} n={res['n_accepted']}")
+    # the other row counts' kernels at these dimensions, on a shorter prompt (one oracle prefill again): 17 rows (two
+    # column tiles), 7 rows (the LDS-resident kernel's widest form), 9 and 12 rows (the fragment-reading kernel at one
+    # column tile with 6, 3 and 1 weight tiles per wave)
+    ks2, iters2 = (16, 6, 8, 11), (2, 2, 1, 1)
+    short = prompt[:300]
+    cap2 = len(short) + sum((k + 1) * n for k, n in zip(ks2, iters2)) + max(ks2) + 2
+    orc2 = so.CachedStairs(T, D, short, cap2)
+    with pkg.Stairs(target, draft, k_max=max(ks2), max_seq=cap2) as gpu:
+        gpu.prefill(short)
+        for k, n_it in zip(ks2, iters2):
+            res = compare_generation(orc2, gpu, len(short), 10 ** 6, k, LOGIT_TOL_BF16, max_iters=n_it, log=_log)
+            _log(f"cfg4 k={k} (P=300): err={res['max_logit_err']:.3g} mism={res['token_mismatches']} "
+                 f"n={res['n_accepted']} ({time.time() - t0:.0f}s)")
 
 
 def test_cfg4_7b_stairs_equals_plain_greedy_full_G(pair7b):
