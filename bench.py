@@ -213,10 +213,12 @@ def main():
     ms_pair, _ = eng.time_kernel(9, M, ctx_mid, 4)      # what an event pair reads with no kernel inside
     ms_iso, _ = eng.time_kernel(0, M, 0, 4 * target.n_layers)
     achieved = bytes_gu / (ms_situ * 1e-3) / 1e9
-    kernel_key = f"k_gemm_bf16_rows<{M}, gate/up" if M <= 4 else f"k_gemm_bf16_wide<{1 if M <= 16 else 2}, 8"
-    kname = (f"k_gemm_bf16_rows<{M}, gate/up> (whole activation block in LDS, one work-group per weight tile)" if M <= 4
-             else f"k_gemm_bf16_wide<{1 if M <= 16 else 2}, 8> (activation fragments from L2, a work-group owns 8 weight tiles over all of k)")
-    traffic, traffic_commit = measured_traffic(kernel_key)
+    kernel_key = f"k_gemm_bf16_rows<{M}, gate/up" if M <= 7 else f"k_gemm_bf16_wide<{(M + 15) // 16},"
+    kname = (f"k_gemm_bf16_rows<{M}, gate/up> (whole activation block in LDS, a work-group walks its share of the weight tiles)"
+             if M <= 7 else
+             f"k_gemm_bf16_wide<{(M + 15) // 16}, NT> (activation fragments from L2, a wave owns NT weight tiles over its share of k)")
+    # the committed counter summary is of the default workload's kernel: no figure for another workload or row count
+    traffic, traffic_commit = measured_traffic(kernel_key) if args.workload == "cfg4_7b" else (None, None)
     roofline = {"bound": "hbm", "kernel": kname + ": gate/up projection + SwiGLU at M = k+1 rows",
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                 "traffic": traffic, "traffic_source": (f"profiles/{os.path.basename(TRAFFIC_FILE)} at commit {traffic_commit}"

@@ -807,7 +807,7 @@ int ingest_blocks(stairs_ctx* c, Model* m, int from, int to, int slot) {
       char* Vl = m->Vc + (size_t)slot * slot_bytes + l * m->kv_layer_bytes;
       launch_pf_norm_split(c->pf_x, ly.attn_norm, g.rms_eps, R, d, c->pf_frag, st);
       PF_SYNC();
-      launch_gemm_block(ly.wqkv, 3 * d, d, c->pf_frag, R, c->pf_y, 3 * d, kPermQKV, d, m->hd, 0, st);
+      launch_gemm_block(ly.wqkv, 3 * d, d, c->pf_frag, R, c->pf_y, 3 * d, kPermQKV, d, m->hd, 0, st, c->pf_part, c->pf_part_floats);
       PF_SYNC();
       launch_pf_rope_kv(c->pf_y, R, d, H, p0, c->pf_cs, c->pf_q, reinterpret_cast<_Float16*>(Kl), reinterpret_cast<_Float16*>(Vl),
                         m->cap, st);
@@ -816,15 +816,15 @@ int ingest_blocks(stairs_ctx* c, Model* m, int from, int to, int slot) {
       PF_SYNC();
       launch_pf_norm_split(c->pf_attn, nullptr, 0.f, R, d, c->pf_frag, st);
       PF_SYNC();
-      launch_gemm_block(ly.wo, d, d, c->pf_frag, R, c->pf_x, d, kPermNone, 0, 0, 1, st);
+      launch_gemm_block(ly.wo, d, d, c->pf_frag, R, c->pf_x, d, kPermNone, 0, 0, 1, st, c->pf_part, c->pf_part_floats);
       PF_SYNC();
       launch_pf_norm_split(c->pf_x, ly.ffn_norm, g.rms_eps, R, d, c->pf_frag, st);
       PF_SYNC();
-      launch_gemm_block(ly.wgu, 2 * f, d, c->pf_frag, R, c->pf_y, 2 * f, kPermGateUp, f, 0, 0, st);
+      launch_gemm_block(ly.wgu, 2 * f, d, c->pf_frag, R, c->pf_y, 2 * f, kPermGateUp, f, 0, 0, st, c->pf_part, c->pf_part_floats);
       PF_SYNC();
       launch_pf_swiglu_split(c->pf_y, R, f, c->pf_frag, st);
       PF_SYNC();
-      launch_gemm_block(ly.wdown, d, f, c->pf_frag, R, c->pf_x, d, kPermNone, 0, 0, 1, st);
+      launch_gemm_block(ly.wdown, d, f, c->pf_frag, R, c->pf_x, d, kPermNone, 0, 0, 1, st, c->pf_part, c->pf_part_floats);
       PF_SYNC();
     }
     HIPCHK(c, hipGetLastError());
@@ -1191,6 +1191,9 @@ static int alloc_workspaces(stairs_ctx* c, const WsDims& w) {
         (rc = dev_alloc(c, &c->pf_frag, pf_frag_bytes(rows, (int)inner) / sizeof(uint4))) ||
         (rc = dev_alloc(c, &c->pf_cs, (size_t)rows * 64)))
       return bail(rc);
+    // blocks of few rows have too few (feature, row) tiles for the chip: their GEMMs cut k and need room for the pieces
+    c->pf_part_floats = (size_t)16 << 20;
+    if ((rc = dev_alloc(c, &c->pf_part, c->pf_part_floats))) return bail(rc);
     // rows of a block past its last one are read by the GEMM (and their results dropped): they must hold numbers
     if (hipMemsetAsync(c->pf_frag, 0, pf_frag_bytes(rows, (int)inner), c->st) != hipSuccess) return bail(STAIRS_EHIP);
   }

@@ -69,15 +69,6 @@ __device__ __forceinline__ void store_frag4(uint4* frag, int m, int k, float4 v,
   dst[0] = hi;
   dst[128] = lo;                                               // the low fragment follows 64 lanes x 16 bytes later
 }
-// row m, columns k, k+1 (k even)
-__device__ __forceinline__ void store_frag2(uint4* frag, int m, int k, float a, float b) {
-  uint32_t hi, lo;
-  bf16_split2(a, b, hi, lo);
-  uint32_t* dst = reinterpret_cast<uint32_t*>(reinterpret_cast<uint2*>(frag) + frag_off(m, k & ~3)) + ((k & 3) >> 1);
-  dst[0] = hi;
-  dst[256] = lo;
-}
-
 __device__ __forceinline__ float load_kv(const float* p) { return *p; }
 __device__ __forceinline__ float load_kv(const uint16_t* p) { return bf16_bits_to_float(*p); }
 __device__ __forceinline__ void store_kv(float* p, float v) { *p = v; }
@@ -1179,7 +1170,14 @@ static size_t rows_path_lds(int role, int M, int N, int K) {
     return (role != kRoleDown && bytes <= kRowsPathMaxLdsWide && N / 16 >= 192 && K >= 2048) ? std::max(bytes, (size_t)81 * 1024) : 0;
   if (role == kRoleWo || role == kRoleDown) {
     // few tiles: only matrices so small that the launch is latency-bound anyway (no partial sums, no hand-off)
-    if (N / 16 < 192) return ((size_t)N * K * 2 <= kRowsPathSmallMatrix && bytes <= kRowsPathMaxLdsWide) ? bytes : 0;
+    if (N / 16 < 192) {
+      if ((size_t)N * K * 2 <= kRowsPathSmallMatrix) return bytes <= kRowsPathMaxLdsWide ? bytes : 0;
+      // a larger matrix with few tiles but a long k range (down projection of a 1B-class model: 128 tiles x 16
+      // chunks): 16 waves per work-group, a k chunk each -- half the CUs stream it faster than split-K work-groups
+      // on all of them with their hand-off (measured: 12.4 -> 9.7 us per launch)
+      return (role == kRoleDown && gemm_slices(K, 1) >= 12 && gemm_slices(K, 1) <= 16 && bytes <= kRowsPathMaxLdsWide)
+                 ? std::max(bytes, (size_t)81 * 1024) : 0;
+    }
     return bytes <= kRowsPathMaxLdsWide ? std::max(bytes, (size_t)81 * 1024) : 0;   // > half a CU's LDS: one per CU
   }
   return bytes <= kRowsPathMaxLds ? bytes : 0;
@@ -1389,6 +1387,7 @@ void launch_gemm(int role, int dtype_bf16, const void* W, int N, int K, const fl
     else if (role == kRoleGateUp) { STAIRS_ROWS_ROLE(kRoleGateUp, 4, 2); }
     else if (role == kRoleHead) { STAIRS_ROWS_ROLE(kRoleHead, 4, 2); }
     else if (role == kRoleWo) { STAIRS_ROWS_ROLE(kRoleWo, 8, 1); }
+    else if (NTILES < 192 && (size_t)N * K * 2 > kRowsPathSmallMatrix) { STAIRS_ROWS_ROLE4(kRoleDown, 16, 1); }
     else { STAIRS_ROWS_ROLE4(kRoleDown, 8, 3); }           // (down never takes this path beyond 4 rows: its k is long)
 #undef STAIRS_ROWS_ROLE
 #undef STAIRS_ROWS_ROLE4
@@ -1828,13 +1827,10 @@ __device__ __forceinline__ void split_half8(const float* v, f16x8& hi, f16x8& lo
 __device__ __forceinline__ float exp_fast(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896340736f); }
 
 constexpr int kMergeCB = 20;
-template <int HD>
-__device__ __forceinline__ void attn_merge(const float* part_o, const float* part_ml, int H, int h, int M, int pos0, int step,
-                                           int kv_len, int nchunk_cap, int nch_lds, int rows_per_pass, float* out, int d,
-                                           float* s_ml, uint4* frag, int frag_row0) {
+// Step A of the merge: the (weight, sum) table of all rows and chunks in LDS (see attn_merge)
+__device__ __forceinline__ void attn_merge_table(const float* part_ml, int H, int h, int M, int pos0, int step, int nch_max,
+                                                 int nchunk_cap, int nch_lds, float* s_ml) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int nch_max = (kv_len > 0) ? (kv_len - 1) / kAttnChunkH + 1 : 0;
-  float* grp = s_ml + (size_t)M * nch_lds * 2 + kMaxRows;   // (kMaxRows floats after the table stay unused)
   for (int idx = tid; idx < M * nch_max; idx += 256) {
     const int m = idx / nch_max, cc = idx - m * nch_max;
     const float2 ml = ld_dev2(&part_ml[(((size_t)m * H + h) * nchunk_cap + cc) * 2]);
@@ -1842,6 +1838,21 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
     s_ml[((size_t)m * nch_lds + cc) * 2 + 1] = ml.y;
   }
   __syncthreads();
+  if (nch_max <= 16) {
+    // few chunks: 16 lanes per row, four rows per wave at a time (max is exact in any order)
+    const int cc = lane & 15;
+    for (int m = wave * 4 + (lane >> 4); m < M; m += 16) {
+      const int p = pos0 + m * step;
+      const int nch = p >= 0 ? p / kAttnChunkH + 1 : 0;
+      const float mc = cc < nch ? s_ml[((size_t)m * nch_lds + cc) * 2] : -INFINITY;
+      float g = mc;
+#pragma unroll
+      for (int off = 8; off >= 1; off >>= 1) g = fmaxf(g, __shfl_xor(g, off));
+      if (cc < nch) s_ml[((size_t)m * nch_lds + cc) * 2] = (mc == -INFINITY) ? 0.f : exp_fast(mc - g);
+    }
+    __syncthreads();
+    return;
+  }
   for (int m = wave; m < M; m += 4) {                 // row maxima (max is exact in any order)
     const int p = pos0 + m * step;
     const int nch = p >= 0 ? p / kAttnChunkH + 1 : 0;
@@ -1856,6 +1867,84 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
     }
   }
   __syncthreads();
+}
+
+// The merge for at most CB chunks: a thread takes IPT items (row, 4 adjacent dims) per pass and requests all their
+// chunks' outputs before the table is built -- they do not depend on it, so the merge's two round trips to memory
+// become one -- then adds them up in chunk order, from zero (the order of attn_merge's step B).
+template <int HD, int CB, int IPT>
+__device__ __forceinline__ void attn_merge_direct(const float* part_o, const float* part_ml, int H, int h, int M, int pos0,
+                                                  int step, int nch_max, int nchunk_cap, int nch_lds, float* out, int d,
+                                                  float* s_ml, uint4* frag, int frag_row0) {
+  constexpr int QPR = HD / 4;                         // threads per row
+  const int tid = threadIdx.x, items = M * QPR;
+  float2 va[IPT][CB], vb[IPT][CB];
+  // (a chunk past the row's last re-reads its last: no condition inside an item's requests)
+#define STAIRS_MERGE_LOADS(base)                                                         \
+  _Pragma("unroll") for (int ip = 0; ip < IPT; ++ip) {                                   \
+    const int idx = (base) + ip * 256 + tid;                                             \
+    if (idx < items) {                                                                   \
+      const int m = idx / QPR, e = (idx - m * QPR) * 4;                                  \
+      const int p = pos0 + m * step;                                                     \
+      const int last = p >= 0 ? p / kAttnChunkH : 0;                                     \
+      const float* src = part_o + ((size_t)m * H + h) * nchunk_cap * HD + e;             \
+      _Pragma("unroll") for (int i = 0; i < CB; ++i) {                                   \
+        const float* q = src + (size_t)min(i, last) * HD;                                \
+        va[ip][i] = ld_dev2(q);                                                          \
+        vb[ip][i] = ld_dev2(q + 2);                                                      \
+      }                                                                                  \
+    }                                                                                    \
+  }
+  STAIRS_MERGE_LOADS(0);
+  attn_merge_table(part_ml, H, h, M, pos0, step, nch_max, nchunk_cap, nch_lds, s_ml);
+  for (int base = 0; base < items; base += 256 * IPT) {
+    if (base > 0) { STAIRS_MERGE_LOADS(base); }
+#pragma unroll
+    for (int ip = 0; ip < IPT; ++ip) {
+      const int idx = base + ip * 256 + tid;
+      if (idx < items) {
+        const int m = idx / QPR, e = (idx - m * QPR) * 4;
+        const int p = pos0 + m * step;
+        float4 res = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (p >= 0) {
+          const int nch = p / kAttnChunkH + 1;
+          const float* mlr = s_ml + (size_t)m * nch_lds * 2;
+          float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+          float den = 0.f;
+#pragma unroll
+          for (int i = 0; i < CB; ++i) {
+            if (i < nch) {
+              const float w = mlr[i * 2];
+              num.x = fmaf(w, va[ip][i].x, num.x); num.y = fmaf(w, va[ip][i].y, num.y);
+              num.z = fmaf(w, vb[ip][i].x, num.z); num.w = fmaf(w, vb[ip][i].y, num.w);
+              den = fmaf(w, mlr[i * 2 + 1], den);
+            }
+          }
+          res = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
+        }
+        *reinterpret_cast<float4*>(out + (size_t)m * d + h * HD + e) = res;
+        if (frag) store_frag4(frag, frag_row0 + m, h * HD + e, res, nullptr);
+      }
+    }
+  }
+#undef STAIRS_MERGE_LOADS
+}
+
+template <int HD>
+__device__ __forceinline__ void attn_merge(const float* part_o, const float* part_ml, int H, int h, int M, int pos0, int step,
+                                           int kv_len, int nchunk_cap, int nch_lds, int rows_per_pass, float* out, int d,
+                                           float* s_ml, uint4* frag, int frag_row0) {
+  const int tid = threadIdx.x;
+  const int nch_max = (kv_len > 0) ? (kv_len - 1) / kAttnChunkH + 1 : 0;
+  if (nch_max <= kMergeCB / 2)                        // (no chunk at all: every row gets zeros)
+    return attn_merge_direct<HD, kMergeCB / 2, 2>(part_o, part_ml, H, h, M, pos0, step, nch_max, nchunk_cap, nch_lds, out, d,
+                                                  s_ml, frag, frag_row0);
+  if (nch_max <= kMergeCB)
+    return attn_merge_direct<HD, kMergeCB, 1>(part_o, part_ml, H, h, M, pos0, step, nch_max, nchunk_cap, nch_lds, out, d,
+                                              s_ml, frag, frag_row0);
+  // more chunks: groups of kMergeCB chunks summed in parallel, the group sums added in group order
+  float* grp = s_ml + (size_t)M * nch_lds * 2 + kMaxRows;   // (kMaxRows floats after the table stay unused)
+  attn_merge_table(part_ml, H, h, M, pos0, step, nch_max, nchunk_cap, nch_lds, s_ml);
   constexpr int QPR = HD / 4;                         // threads per row
   constexpr int CB = kMergeCB;
   const int G = (nch_max + CB - 1) / CB;
@@ -1880,22 +1969,6 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
       }
     }
   };
-  if (G <= 1) {
-    for (int idx = tid; idx < M * QPR; idx += 256) {
-      const int m = idx / QPR, e = (idx - m * QPR) * 4;
-      const int p = pos0 + m * step;
-      float4 res = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (p >= 0) {
-        float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
-        float den = 0.f;
-        group_sum(m, e, 0, p / kAttnChunkH + 1, num, den);
-        res = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
-      }
-      *reinterpret_cast<float4*>(out + (size_t)m * d + h * HD + e) = res;
-      if (frag) store_frag4(frag, frag_row0 + m, h * HD + e, res, nullptr);
-    }
-    return;
-  }
   for (int m0 = 0; m0 < M; m0 += rows_per_pass) {
     const int rows = min(rows_per_pass, M - m0);
     for (int idx = tid; idx < rows * QPR * G; idx += 256) {
@@ -1933,15 +2006,16 @@ __device__ __forceinline__ void attn_merge(const float* part_o, const float* par
   }
 }
 
+// (two work-groups per CU: the register budget that keeps both resident)
 template <int HD, int CT, bool FUSED>
-__global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, const _Float16* __restrict__ Kc,
+__global__ __launch_bounds__(256, 2) void k_attn_f16(const float* __restrict__ q, const _Float16* __restrict__ Kc,
                                                   const _Float16* __restrict__ Vc, int cap, int d, int H, int M,
                                                   PosRef pos, size_t kv_slot_stride, float scale, AttnMode am, int nchunk_cap,
                                                   int rows_per_pass, float* part_o, float* part_ml, int* counters,
                                                   float* __restrict__ out) {
   constexpr int KK = HD / 32;   // k-steps of the score MFMA
   constexpr int ET = HD / 16;   // output-dim tiles of the value MFMA
-  __shared__ float s_o[4][16][HD];
+  __shared__ float s_o[4][16][HD + 4];               // (+4: the 16 rows a wave writes at once fall into different banks)
   __shared__ float s_m[4][16], s_l[4][16];
   __shared__ int s_last;
   const int c = blockIdx.x, h = blockIdx.y;
@@ -2022,19 +2096,25 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
       f16x8 qh[KK], ql[KK];
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        float4 a = qa0[kk], b = qb0[kk];
-        if (ct > 0) {
-          a = make_float4(0.f, 0.f, 0.f, 0.f);
-          b = a;
-          if (qi < M) {
-            const float4* qp = reinterpret_cast<const float4*>(q + (size_t)qi * d + h * HD + kk * 32 + g * 8);
-            a = qp[0];
-            b = qp[1];
-          }
-        }
+        const float4 a = qa0[kk], b = qb0[kk];
         const float v[8] = {a.x * scale, a.y * scale, a.z * scale, a.w * scale,
                             b.x * scale, b.y * scale, b.z * scale, b.w * scale};
         split_half8(v, qh[kk], ql[kk]);
+      }
+      // the next query tile's rows are requested now, into the registers just converted: they arrive while this
+      // tile's scores and outputs are computed
+      if (ct + 1 < CT) {
+        const int qn = (ct + 1) * 16 + j;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          qa0[kk] = make_float4(0.f, 0.f, 0.f, 0.f);
+          qb0[kk] = qa0[kk];
+          if (qn < M) {
+            const float4* qp = reinterpret_cast<const float4*>(q + (size_t)qn * d + h * HD + kk * 32 + g * 8);
+            qa0[kk] = qp[0];
+            qb0[kk] = qp[1];
+          }
+        }
       }
       // scores of the wave's 64 keys, their joint maximum, the exponentials, then the two value products
       float sc[2][8];
@@ -2105,18 +2185,21 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
     }
     __syncthreads();
     const int rows_here = min(16, M - ct * 16);      // (<= 0 for a second tile no row falls into)
-    for (int idx = tid; idx < rows_here * (HD / 2); idx += 256) {
-      const int jj = idx / (HD / 2), e = (idx - jj * (HD / 2)) * 2;
+    // (a thread takes 4 adjacent dims of a row: 16 rows are two passes of the 256 threads)
+    for (int idx = tid; idx < rows_here * (HD / 4); idx += 256) {
+      const int jj = idx / (HD / 4), e = (idx - jj * (HD / 4)) * 4;
       const int m = ct * 16 + jj;
       if (m < M) {
         const float m0 = s_m[0][jj], m1 = s_m[1][jj], m2 = s_m[2][jj], m3 = s_m[3][jj];
         const float mcc = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
         const float f0 = (m0 == -INFINITY) ? 0.f : exp_fast(m0 - mcc), f1 = (m1 == -INFINITY) ? 0.f : exp_fast(m1 - mcc);
         const float f2 = (m2 == -INFINITY) ? 0.f : exp_fast(m2 - mcc), f3 = (m3 == -INFINITY) ? 0.f : exp_fast(m3 - mcc);
-        const float2 a0 = *reinterpret_cast<const float2*>(&s_o[0][jj][e]), a1 = *reinterpret_cast<const float2*>(&s_o[1][jj][e]);
-        const float2 a2 = *reinterpret_cast<const float2*>(&s_o[2][jj][e]), a3 = *reinterpret_cast<const float2*>(&s_o[3][jj][e]);
+        const float4 a0 = *reinterpret_cast<const float4*>(&s_o[0][jj][e]), a1 = *reinterpret_cast<const float4*>(&s_o[1][jj][e]);
+        const float4 a2 = *reinterpret_cast<const float4*>(&s_o[2][jj][e]), a3 = *reinterpret_cast<const float4*>(&s_o[3][jj][e]);
         const float o0 = __fadd_rn(__fadd_rn(__fadd_rn(__fmul_rn(a0.x, f0), __fmul_rn(a1.x, f1)), __fmul_rn(a2.x, f2)), __fmul_rn(a3.x, f3));
         const float o1 = __fadd_rn(__fadd_rn(__fadd_rn(__fmul_rn(a0.y, f0), __fmul_rn(a1.y, f1)), __fmul_rn(a2.y, f2)), __fmul_rn(a3.y, f3));
+        const float o2 = __fadd_rn(__fadd_rn(__fadd_rn(__fmul_rn(a0.z, f0), __fmul_rn(a1.z, f1)), __fmul_rn(a2.z, f2)), __fmul_rn(a3.z, f3));
+        const float o3 = __fadd_rn(__fadd_rn(__fadd_rn(__fmul_rn(a0.w, f0), __fmul_rn(a1.w, f1)), __fmul_rn(a2.w, f2)), __fmul_rn(a3.w, f3));
         // the chunk's sum of exponentials (a wave without keys has weight 0 and sum 0: it adds nothing); no branch
         // around the LDS reads
         const float l0 = s_l[0][jj], l1 = s_l[1][jj], l2 = s_l[2][jj], l3 = s_l[3][jj];
@@ -2126,12 +2209,14 @@ __global__ __launch_bounds__(256) void k_attn_f16(const float* __restrict__ q, c
         lc += f2 * l2;
         lc += f3 * l3;
         if (single) {
-          float2 res = make_float2(0.f, 0.f);
-          if (pos0 + m * step >= 0) res = make_float2(o0 / lc, o1 / lc);
-          *reinterpret_cast<float2*>(out + (size_t)m * d + h * HD + e) = res;
-          if (am.frag_out) store_frag2(am.frag_out, row0 + m, h * HD + e, res.x, res.y);
+          float4 res = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (pos0 + m * step >= 0) res = make_float4(o0 / lc, o1 / lc, o2 / lc, o3 / lc);
+          *reinterpret_cast<float4*>(out + (size_t)m * d + h * HD + e) = res;
+          if (am.frag_out) store_frag4(am.frag_out, row0 + m, h * HD + e, res, nullptr);
         } else {
-          st_dev2(&part_o[(((size_t)m * H + h) * nchunk_cap + c) * HD + e], o0, o1);
+          float* po = &part_o[(((size_t)m * H + h) * nchunk_cap + c) * HD + e];
+          st_dev2(po, o0, o1);
+          st_dev2(po + 2, o2, o3);
           // the thread with the row's first dims also leaves the chunk's (max, sum) pair
           if (e == 0) st_dev2(part_ml + (((size_t)m * H + h) * nchunk_cap + c) * 2, mcc, lc);
         }
@@ -2969,7 +3054,8 @@ hipError_t configure_kernels() {
   optin((const void*)k_gemm_bf16_rows<r, kRoleGateUp, 4, 2, st>, kRowsPathMaxLdsWide);             \
   optin((const void*)k_gemm_bf16_rows<r, kRoleHead, 4, 2, st>, kRowsPathMaxLds);                   \
   optin((const void*)k_gemm_bf16_rows<r, kRoleWo, 8, 1, st>, kRowsPathMaxLdsWide);                 \
-  optin((const void*)k_gemm_bf16_rows<r, kRoleDown, 8, 3, st>, kRowsPathMaxLdsWide)
+  optin((const void*)k_gemm_bf16_rows<r, kRoleDown, 8, 3, st>, kRowsPathMaxLdsWide);               \
+  optin((const void*)k_gemm_bf16_rows<r, kRoleDown, 16, 1, st>, kRowsPathMaxLdsWide)
 #define STAIRS_OPTIN(r)    \
   STAIRS_OPTIN2(r, true);  \
   STAIRS_OPTIN2(r, false)
