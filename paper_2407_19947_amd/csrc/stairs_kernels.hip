@@ -2725,15 +2725,15 @@ __device__ __forceinline__ void pf_store_frag4(uint4* frag, int RT, int r, int k
 
 // Y[R, N] (+)= X[R, K] . W[N, K]^T for row blocks of up to thousands of rows: the MFMA-bound regime.
 //   W: the operand-tile layout of the decode kernels (read as the MFMA A operand straight from memory, 1 KiB per load);
-//   X: block fragments (above), staged through LDS two k-steps at a time, double-buffered, shared by the 4 waves.
+//   X: block fragments (above), staged through LDS one k-step at a time, double-buffered, shared by the 8 waves.
 //   Work-group = 256 output features (16 weight tiles) x 128 rows (8 column tiles) on 8 waves, each 4 weight tiles x
 //   4 column tiles: a wave's k-step is 4 KiB of weights from memory, 8 KiB of fragments from LDS and 32 MFMAs (high and
 //   low part of x), fp32 accumulators [4][4] tiles.  Output columns are stored in natural order (the row permutation of the weight layout is undone:
 //   4 consecutive permuted rows are 4 consecutive features).  accumulate: Y += (the residual connections).
 //   One order of additions per output (k ascending, high before low): results do not depend on R or on the grid.
-constexpr int kBlkKs = 2;                              // k-steps per LDS stage
-constexpr int kBlkStageU4 = kBlkKs * (kBlkRows / 16) * 2 * 64;   // uint4 per stage: 2048 (32 KiB)
-__global__ __launch_bounds__(512) void k_gemm_bf16_block(const uint4* __restrict__ Wsw, int NTILES, int K,
+constexpr int kBlkKs = 2;                              // k-steps per stage (the unit the k splits are counted in)
+constexpr int kBlkStageU4 = (kBlkRows / 16) * 2 * 64;  // uint4 per LDS buffer (one k-step): 1024 (16 KiB)
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_bf16_block(const uint4* __restrict__ Wsw, int NTILES, int K,
                                                          const uint4* __restrict__ XF, int RT, int R,
                                                          float* __restrict__ Y, int ldy, int perm, int p0, int p1,
                                                          int accumulate, int stages_per_split, size_t split_stride) {
@@ -2758,85 +2758,86 @@ __global__ __launch_bounds__(512) void k_gemm_bf16_block(const uint4* __restrict
 #pragma unroll
   for (int t = 0; t < NT; ++t) tile_c[t] = min(tile0 + t, NTILES - 1);
 
-  auto load_a = [&](uint4 (&a)[kBlkKs][NT], int stage) {
+  // this split's k-steps: [ks0, ks_end), a multiple of 4 (K is a multiple of 256 and a split an even number of stages)
+  const int ks0 = stage0 * kBlkKs, ks_end = nstages * kBlkKs, ks_last = ks_end - 1;
+  // weights of k-step s (past the split's end the last one is read again): 4 tiles x 1 KiB
+  auto load_a = [&](uint4 (&a)[NT], int s_) {
+    const int s = min(s_, ks_last), c = s >> 4, kk = s & 15;
+    const int ksteps_c = min(kSliceUnits, units_total - c * kSliceUnits) * 8;
+    const uint4* wbase = Wsw + (size_t)c * NTILES * (kSliceUnits * 8) * 64 + (size_t)kk * 64 + lane;
 #pragma unroll
-    for (int ks = 0; ks < kBlkKs; ++ks) {
-      const int s = stage * kBlkKs + ks, c = s >> 4, kk = s & 15;
-      const int ksteps_c = min(kSliceUnits, units_total - c * kSliceUnits) * 8;
-      const uint4* wbase = Wsw + (size_t)c * NTILES * (kSliceUnits * 8) * 64 + (size_t)kk * 64 + lane;
-#pragma unroll
-      for (int t = 0; t < NT; ++t) a[ks][t] = wbase[(size_t)tile_c[t] * ksteps_c * 64];
-    }
+    for (int t = 0; t < NT; ++t) a[t] = wbase[(size_t)tile_c[t] * ksteps_c * 64];
   };
-  // (the stage's fragments: per k-step the work-group's 8 column tiles x (high, low) are 1024 consecutive uint4)
   f32x4 acc[NT][CT];
 #pragma unroll
   for (int t = 0; t < NT; ++t)
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) acc[t][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  auto compute = [&](const uint4 (&a)[kBlkKs][NT], int buf) {
+  // one k-step: the work-group's 8 column tiles x (high, low) are 1024 consecutive uint4 of LDS buffer buf
+  auto compute = [&](const uint4 (&a)[NT], int buf) {
     const uint4* src = lds + buf * kBlkStageU4 + (rh * CT * 2) * 64 + lane;
 #pragma unroll
-    for (int ks = 0; ks < kBlkKs; ++ks) {
+    for (int ct = 0; ct < CT; ++ct) {
+      const bf16x8 vh = __builtin_bit_cast(bf16x8, src[(ct * 2) * 64]);
+      const bf16x8 vl = __builtin_bit_cast(bf16x8, src[(ct * 2 + 1) * 64]);
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct) {
-        const bf16x8 vh = __builtin_bit_cast(bf16x8, src[ks * 1024 + (ct * 2) * 64]);
-        const bf16x8 vl = __builtin_bit_cast(bf16x8, src[ks * 1024 + (ct * 2 + 1) * 64]);
+      for (int t = 0; t < NT; ++t) {
+        const bf16x8 av = __builtin_bit_cast(bf16x8, a[t]);
+        acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, vh, acc[t][ct], 0, 0, 0);
+      }
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const bf16x8 av = __builtin_bit_cast(bf16x8, a[ks][t]);
-          acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, vh, acc[t][ct], 0, 0, 0);
-        }
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const bf16x8 av = __builtin_bit_cast(bf16x8, a[ks][t]);
-          acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, vl, acc[t][ct], 0, 0, 0);
-        }
+      for (int t = 0; t < NT; ++t) {
+        const bf16x8 av = __builtin_bit_cast(bf16x8, a[t]);
+        acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, vl, acc[t][ct], 0, 0, 0);
       }
     }
   };
-  // two stages per turn so that the weight registers alternate without copies; requests of the next stage go out
-  // before the arithmetic of the current one (unconditionally: past the end the last stage is read again).  Two waves
-  // per SIMD fill each other's waits for LDS and memory.
-  uint4 a0[kBlkKs][NT], a1[kBlkKs][NT];
-  uint4 b0, b1, b2, b3;                                 // the stage's fragments on their way to LDS (2 k-steps x 2)
-#define STAIRS_LOAD_B(stage)                                                                      \
+  // Rings of four k-steps in registers, for the weights (4 x 16) and for the fragments on their way to LDS (4 x 8):
+  // before the arithmetic of k-step s, weights and fragments of k-step s + 3 are requested, so a request has three
+  // k-steps' arithmetic to come back in (with one stage of two k-steps the waves spent nearly half their cycles waiting for memory, also at
+  // thousands of rows); after the arithmetic the fragments of k-step s + 1 go to the other LDS buffer.  Four k-steps
+  // per turn of the loop name the rings' registers statically; a split's k-steps are a multiple of four, so no turn
+  // ends early.  All requests are unconditional.  Two waves per SIMD fill each other's waits for LDS and memory.
+  uint4 a0[NT], a1[NT], a2[NT], a3[NT];
+  uint4 b0_0, b0_1, b1_0, b1_1, b2_0, b2_1, b3_0, b3_1;    // (plain variables: small arrays ended up in scratch memory)
+#define STAIRS_LOAD_B(b, s_)                                                                      \
   do {                                                                                            \
-    const uint4* src_ = XF + ((size_t)((stage) * kBlkKs) * RT + ct0) * 2 * 64 + tid;              \
-    b0 = src_[0];                                                                                 \
-    b1 = src_[512];                                                                               \
-    b2 = src_[(size_t)RT * 2 * 64];                                                               \
-    b3 = src_[(size_t)RT * 2 * 64 + 512];                                                         \
+    const uint4* src_ = XF + ((size_t)min((s_), ks_last) * RT + ct0) * 2 * 64 + tid;              \
+    b##_0 = src_[0];                                                                              \
+    b##_1 = src_[512];                                                                            \
   } while (0)
-#define STAIRS_STORE_B(buf)                                  \
+#define STAIRS_STORE_B(buf, b)                               \
   do {                                                       \
     uint4* dst_ = lds + (buf) * kBlkStageU4 + tid;           \
-    dst_[0] = b0;                                            \
-    dst_[512] = b1;                                          \
-    dst_[1024] = b2;                                         \
-    dst_[1536] = b3;                                         \
+    dst_[0] = b##_0;                                         \
+    dst_[512] = b##_1;                                       \
   } while (0)
-  static_assert(kBlkKs == 2, "the fragment staging above is written for two k-steps per stage");
-  STAIRS_LOAD_B(stage0);
-  load_a(a0, stage0);
-  STAIRS_STORE_B(0);
+  // k-step s in LDS buffer buf: ac = its weights, an / bn = the ring slots for k-step s + 3, bs = the fragments of s + 1
+#define STAIRS_BLOCK_STEP(ac, an, bn, bs, s, buf)            \
+  do {                                                       \
+    STAIRS_LOAD_B(bn, (s) + 3);                              \
+    load_a(an, (s) + 3);                                     \
+    __builtin_amdgcn_sched_barrier(0);                       \
+    compute(ac, buf);                                        \
+    STAIRS_STORE_B((buf) ^ 1, bs);                           \
+    __syncthreads();                                         \
+  } while (0)
+  STAIRS_LOAD_B(b0, ks0);
+  load_a(a0, ks0);
+  STAIRS_LOAD_B(b1, ks0 + 1);
+  load_a(a1, ks0 + 1);
+  STAIRS_LOAD_B(b2, ks0 + 2);
+  load_a(a2, ks0 + 2);
+  STAIRS_STORE_B(0, b0);
   __syncthreads();
-  for (int st = stage0; st < nstages; st += 2) {
-    STAIRS_LOAD_B(min(st + 1, nstages - 1));
-    load_a(a1, min(st + 1, nstages - 1));
-    __builtin_amdgcn_sched_barrier(0);
-    compute(a0, 0);
-    STAIRS_STORE_B(1);
-    __syncthreads();
-    if (st + 1 >= nstages) break;
-    STAIRS_LOAD_B(min(st + 2, nstages - 1));
-    load_a(a0, min(st + 2, nstages - 1));
-    __builtin_amdgcn_sched_barrier(0);
-    compute(a1, 1);
-    STAIRS_STORE_B(0);
-    __syncthreads();
+  for (int ks = ks0; ks < ks_end; ks += 4) {
+    STAIRS_BLOCK_STEP(a0, a3, b3, b1, ks, 0);
+    STAIRS_BLOCK_STEP(a1, a0, b0, b2, ks + 1, 1);
+    STAIRS_BLOCK_STEP(a2, a1, b1, b3, ks + 2, 0);
+    STAIRS_BLOCK_STEP(a3, a2, b2, b0, ks + 3, 1);
   }
+#undef STAIRS_BLOCK_STEP
 #undef STAIRS_LOAD_B
 #undef STAIRS_STORE_B
 
