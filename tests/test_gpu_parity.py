@@ -214,6 +214,21 @@ def test_bf16_prompt_lengths_around_chunk_boundaries(P):
     assert res["max_logit_err"] < 2e-3
 
 
+@pytest.mark.parametrize("P,heads,k", [(2700, 2, 5), (5000, 4, 16), (5300, 2, 3), (6300, 4, 8)])
+def test_attention_chunk_counts_of_every_merge_form(P, heads, k):
+    """Contexts of 11, 20, 21 and 25 attention chunks of 256 keys: the chunk merge with all loads in front of its
+    table for up to 10 and up to 20 chunks (the shorter prompts of the other tests cover the first), the grouped merge
+    inside the attention kernel (21..24 chunks) and the merge kernel of its own (from 25 on); head_dim 128 and 64;
+    stair batches of 4 to 17 rows (two query tiles, several passes of the merging work-group)."""
+    w = si.scaled_workload("cfg2_125m", target=dict(n_layers=2, d_model=256, n_heads=heads, d_ffn=256, vocab=512),
+                           draft=dict(kind="prefix", n_layers=1), P=P, G=6)
+    target, draft = si.make_pair(w)
+    prompt = si.make_prompt(w)
+    _log(f"attention merge forms: P={P}, head_dim {256 // heads}, k={k}")
+    res = run_side_by_side(target, draft, prompt, 6, k, np.float64, LOGIT_TOL_BF16)
+    assert res["max_logit_err"] < 5e-3
+
+
 def test_widest_stair_batch_and_exact_capacity():
     """k = k_max = 31 (32 rows, the most one forward takes) with max_seq sized to the last position used."""
     w = si.scaled_workload("cfg2_125m", target=dict(n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=2048),
