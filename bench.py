@@ -340,6 +340,11 @@ def main():
         "accept_hist": list(stats_last.accept_hist)[:k + 1],
         "ms_draft_per_step": stats_last.ms_draft, "ms_verify_per_step": stats_last.ms_verify,
         "prefill_ms": prefill_ms, "k_sweep": k_table,
+        # prompt ingestion (outside the timed region): the layer projections of both models over the P-1 ingested rows,
+        # each activation issued as a high and a low bf16 part, against the dense bf16 MFMA peak
+        "prefill": {"ms": prefill_ms, "rows": P - 1, "tokens_per_s": (P - 1) / (prefill_ms * 1e-3),
+                    "issued_mfma_frac_of_2.5PFLOPs": (2.0 * 2.0 * (P - 1) * sum(m.n_params() - m.vocab * m.d_model for m in (target, draft))
+                                                      / (prefill_ms * 1e-3) / 2.5e15) if w["dtype"] == "bf16" else None},
         "plain_greedy_tokens_per_s": G / plain_s,
         "time_reduction_vs_plain_greedy_pct": 100.0 * (1.0 - (total / len(decode_s)) / plain_s),
         "paper_context": "paper reports 9.58-17.24 % inference-time reduction (T5-3B / T5-large + T5-small, MacBook Pro M2 32 GB)",
