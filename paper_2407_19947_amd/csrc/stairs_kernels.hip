@@ -2077,11 +2077,19 @@ __global__ __launch_bounds__(256, 2) void k_attn_f16(const float* __restrict__ q
       const uint4* Vh = reinterpret_cast<const uint4*>(Vc + (size_t)h * cap * HD);
       const int kbs = kb + 32 * sb;
 #pragma unroll
+      // (the two-kernel form runs at long contexts only, where a layer's keys and values exceed what the memory-side
+      // cache could keep until the next forward: streaming loads there, as for the weights of a large model)
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) kreg[sb][t][kk] = Kh[((size_t)((kbs >> 4) + t) * KK + kk) * 64 + lane];
+        for (int kk = 0; kk < KK; ++kk) {
+          const uint4* p = &Kh[((size_t)((kbs >> 4) + t) * KK + kk) * 64 + lane];
+          kreg[sb][t][kk] = FUSED ? *p : ld_nt(p);
+        }
 #pragma unroll
-      for (int et = 0; et < ET; ++et) vreg[sb][et] = Vh[((size_t)(kbs >> 5) * ET + et) * 64 + lane];
+      for (int et = 0; et < ET; ++et) {
+        const uint4* p = &Vh[((size_t)(kbs >> 5) * ET + et) * 64 + lane];
+        vreg[sb][et] = FUSED ? *p : ld_nt(p);
+      }
     }
   }
 
