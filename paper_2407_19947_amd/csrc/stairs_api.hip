@@ -89,7 +89,7 @@ struct stairs_ctx {
   bool block_prefill = false;
   float *pf_x = nullptr, *pf_y = nullptr, *pf_q = nullptr, *pf_attn = nullptr;
   uint4* pf_frag = nullptr;    // block fragments of the activation in front of the current projection
-  float* pf_part = nullptr;    // k-split results of block GEMMs with few rows (forwards of many sequences)
+  float* pf_part = nullptr;    // k-split results of block GEMMs with few rows (short prompts, forwards of many sequences)
   size_t pf_part_floats = 0;
   float2* pf_cs = nullptr;
   // encoder-decoder contexts: source tokens and the encoder's activations [max_src, .]
